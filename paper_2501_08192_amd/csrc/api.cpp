@@ -1,0 +1,604 @@
+// Context, workspace and step executor of libpreserve_mi355x.
+//
+// Execution model (Section 3, "PRESERVE"): the decode step's operators run in order on the main
+// stream; beside each communication window an event forks the side stream, which runs the
+// prefetch kernels the plan assigned to that window while the main stream sits in the window
+// (here: a spin kernel standing in for the allreduce).  Prefetch kernels only read, so the main
+// stream never has to wait for them; the side stream itself serialises consecutive windows.
+#include <math.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "internal.h"
+
+using namespace psv;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+struct Workspace {
+    size_t total = 0;
+    // offsets
+    size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, q_bf16, part_ml, part_o, attn_f32, attn_bf16, delta,
+        m_f32, m_bf16, inv_freq;
+};
+
+Workspace layout_workspace(const psv_model_desc &d)
+{
+    Workspace w;
+    const size_t B = d.max_batch, Bp = (B + 15) / 16 * 16, H = d.hidden, F = d.ffn;
+    const size_t QR = (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim, QD = (size_t)d.n_q_heads * d.head_dim;
+    const size_t G = d.n_q_heads / d.n_kv_heads;
+    const AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq);
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    w.x = take(B * H * 4);
+    w.y = take(B * H * 4);
+    w.h1_f32 = take(B * H * 4);
+    w.h1_bf16 = take(Bp * H * 2);
+    w.h2_f32 = take(B * H * 4);
+    w.h2_bf16 = take(Bp * H * 2);
+    w.qkv = take(B * QR * 4);
+    w.q_bf16 = take(B * QD * 2);
+    w.part_ml = take(B * d.n_kv_heads * (size_t)sp.n_splits * 16 * 2 * 4);
+    w.part_o = take(B * d.n_kv_heads * (size_t)sp.n_splits * G * 128 * 4);
+    w.attn_f32 = take(B * QD * 4);
+    w.attn_bf16 = take(Bp * QD * 2);
+    w.delta = take(B * H * 4);
+    w.m_f32 = take(B * F * 4);
+    w.m_bf16 = take(Bp * F * 2);
+    w.inv_freq = take(64 * sizeof(double));
+    w.total = off;
+    return w;
+}
+
+struct GraphKey {
+    const float *x_in = nullptr;
+    float *x_out = nullptr;
+    uint32_t batch = 0, lb = 0, le = 0;
+    uint64_t version = 0;
+    bool operator==(const GraphKey &o) const
+    {
+        return x_in == o.x_in && x_out == o.x_out && batch == o.batch && lb == o.lb && le == o.le && version == o.version;
+    }
+};
+
+}  // namespace
+
+struct psv_ctx {
+    psv_model_desc d{};
+    hipStream_t main = nullptr, side = nullptr;
+    int device = 0;
+    uint64_t clock_khz = 100000;
+    Workspace ws{};
+    char *wsp = nullptr;
+    std::vector<psv_layer_weights> weights;
+    std::vector<unsigned char> weights_set;
+    bool kv_set = false;
+    std::vector<void *> k_pools, v_pools;
+    psv_kv_desc kv{};
+    float window_us[2] = {0.f, 0.f};
+    psv_prefetch_policy policy{};
+    uint32_t plan_batch = 0, plan_context = 0;
+    std::vector<psv_plan_entry> plan;
+    std::vector<hipEvent_t> ev_fork, ev_join;   // [layer*2 + window]
+    hipEvent_t ev_end = nullptr;
+    uint64_t version = 1;                        // bumped by every psv_set_*
+    bool use_graph = false;
+    hipGraphExec_t graph_exec = nullptr;
+    GraphKey graph_key{};
+    int32_t profile_op = -1;
+    std::vector<hipEvent_t> prof_events;         // pairs (begin, end)
+    size_t prof_used = 0;
+    uint32_t steps = 0;
+    uint32_t last_prefetch_launches = 0;
+    bool capturing = false;
+
+    template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(wsp + off); }
+};
+
+namespace {
+
+#define HIP_TRY(expr)                        \
+    do {                                     \
+        hipError_t e__ = (expr);             \
+        if (e__ != hipSuccess) return PSV_ERR_HIP; \
+    } while (0)
+
+void drop_graph(psv_ctx *c)
+{
+    if (c->graph_exec) {
+        (void)hipGraphExecDestroy(c->graph_exec);
+        c->graph_exec = nullptr;
+    }
+}
+
+void touch(psv_ctx *c)
+{
+    ++c->version;
+    drop_graph(c);
+}
+
+KvView kv_view(const psv_ctx *c, uint32_t layer)
+{
+    KvView v;
+    v.k_pool = static_cast<uint16_t *>(c->k_pools[layer]);
+    v.v_pool = static_cast<uint16_t *>(c->v_pools[layer]);
+    v.page_table = c->kv.page_table;
+    v.max_blocks = (int)c->kv.max_blocks;
+    v.num_pool_blocks = (int)c->kv.num_pool_blocks;
+    v.seq_lens = c->kv.seq_lens;
+    return v;
+}
+
+uint64_t us_to_ticks(uint64_t clock_khz, float us) { return (uint64_t)llround((double)us * (double)clock_khz / 1000.0); }
+uint32_t spin_cap(float us) { return (uint32_t)(us * 4000.0f) + 100000u; }
+
+psv_status prof_begin(psv_ctx *c, int32_t op)
+{
+    if (c->capturing || c->profile_op != op) return PSV_OK;
+    if (c->prof_used + 2 > c->prof_events.size()) {
+        for (int k = 0; k < 2; ++k) {
+            hipEvent_t e;
+            HIP_TRY(hipEventCreate(&e));
+            c->prof_events.push_back(e);
+        }
+    }
+    HIP_TRY(hipEventRecord(c->prof_events[c->prof_used], c->main));
+    return PSV_OK;
+}
+
+psv_status prof_end(psv_ctx *c, int32_t op)
+{
+    if (c->capturing || c->profile_op != op) return PSV_OK;
+    HIP_TRY(hipEventRecord(c->prof_events[c->prof_used + 1], c->main));
+    c->prof_used += 2;
+    return PSV_OK;
+}
+
+// y[b][:] = W x[b][:] (optionally the SwiGLU pair) with the kernel that suits the batch.
+psv_status projection(psv_ctx *c, const void *W, const void *W2, const float *x_f32, const uint16_t *x_bf16, float *out,
+                      uint16_t *out_bf16, int batch, int N, int K)
+{
+    const uint16_t *w = static_cast<const uint16_t *>(W), *w2 = static_cast<const uint16_t *>(W2);
+    if (gemv_supported(batch, N, K)) {
+        HIP_TRY(launch_gemv(w, w2, x_f32, out, out_bf16, batch, N, K, c->main));
+    } else if (gemm_mfma_supported(batch, N, K)) {
+        HIP_TRY(launch_gemm_mfma(w, w2, x_bf16, out, out_bf16, batch, N, K, c->main));
+    } else {
+        return PSV_ERR_UNSUPPORTED;
+    }
+    return PSV_OK;
+}
+
+const void *weight_ptr(const psv_layer_weights &w, uint32_t op)
+{
+    switch (op) {
+    case PSV_OP_QKV: return w.w_qkv;
+    case PSV_OP_O: return w.w_o;
+    case PSV_OP_GATE: return w.w_gate;
+    case PSV_OP_UP: return w.w_up;
+    case PSV_OP_DOWN: return w.w_down;
+    default: return nullptr;
+    }
+}
+
+psv_status launch_entry(psv_ctx *c, const psv_plan_entry &e, uint32_t batch)
+{
+    const uint32_t wg = c->policy.cu_budget ? c->policy.cu_budget : 64u;
+    if (e.target_op == PSV_OP_ATTN) {
+        const uint32_t ro_tokens = c->plan_context > 0 ? c->plan_context - 1 : 0;
+        const uint32_t blocks_per_seq = (ro_tokens + PSV_BLOCK_TOKENS - 1) / PSV_BLOCK_TOKENS;
+        if (blocks_per_seq == 0) return PSV_OK;
+        const uint64_t bytes_per_block = (uint64_t)c->d.n_kv_heads * PSV_BLOCK_TOKENS * PSV_HEAD_DIM * 2 * 2;
+        uint64_t total = (uint64_t)batch * blocks_per_seq;
+        uint64_t count = (e.bytes + bytes_per_block - 1) / bytes_per_block;
+        if (count > total) count = total;
+        uint64_t per_launch = c->policy.chunk_bytes ? c->policy.chunk_bytes / bytes_per_block : count;
+        if (per_launch == 0) per_launch = 1;
+        const KvView v = kv_view(c, e.target_layer);
+        for (uint64_t first = 0; first < count; first += per_launch) {
+            const uint64_t n = count - first < per_launch ? count - first : per_launch;
+            HIP_TRY(launch_prefetch_kv(v, (int)c->d.n_kv_heads, blocks_per_seq, first, n, wg, c->side));
+            ++c->last_prefetch_launches;
+        }
+        return PSV_OK;
+    }
+    const char *p = static_cast<const char *>(weight_ptr(c->weights[e.target_layer], e.target_op));
+    if (!p) return PSV_ERR_BAD_STATE;
+    const uint64_t bytes = e.bytes & ~(uint64_t)15;
+    uint64_t per_launch = c->policy.chunk_bytes ? (c->policy.chunk_bytes & ~(uint64_t)15) : bytes;
+    if (per_launch == 0) per_launch = 16;
+    for (uint64_t off = 0; off < bytes; off += per_launch) {
+        const uint64_t n = bytes - off < per_launch ? bytes - off : per_launch;
+        HIP_TRY(launch_prefetch(p + off, n, wg, c->side));
+        ++c->last_prefetch_launches;
+    }
+    return PSV_OK;
+}
+
+// The communication window after the attention block (window 0) or the MLP block (window 1).
+psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t batch, uint32_t layer_end, bool *side_used)
+{
+    const float us = c->window_us[window];
+    if (!(us > 0.f)) return PSV_OK;
+    bool forked = false;
+    if (c->policy.mode == 1) {
+        for (const psv_plan_entry &e : c->plan) {
+            if (e.layer != layer || e.window != window || e.target_layer >= layer_end) continue;
+            if (!forked) {
+                hipEvent_t ev = c->ev_fork[layer * 2 + window];
+                HIP_TRY(hipEventRecord(ev, c->main));
+                HIP_TRY(hipStreamWaitEvent(c->side, ev, 0));
+                forked = true;
+            }
+            psv_status st = launch_entry(c, e, batch);
+            if (st != PSV_OK) return st;
+        }
+        if (forked && c->policy.join) HIP_TRY(hipEventRecord(c->ev_join[layer * 2 + window], c->side));
+    }
+    HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), c->main));
+    if (forked && c->policy.join) HIP_TRY(hipStreamWaitEvent(c->main, c->ev_join[layer * 2 + window], 0));
+    if (forked) *side_used = true;
+    return PSV_OK;
+}
+
+psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t batch, uint32_t lb, uint32_t le)
+{
+    const psv_model_desc &d = c->d;
+    const int B = (int)batch, H = (int)d.hidden, F = (int)d.ffn, nq = (int)d.n_q_heads, nkv = (int)d.n_kv_heads;
+    const int QR = (nq + 2 * nkv) * 128, QD = nq * 128;
+    const AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq);
+    float *x = c->at<float>(c->ws.x), *y = c->at<float>(c->ws.y), *delta = c->at<float>(c->ws.delta);
+    float *h1 = c->at<float>(c->ws.h1_f32), *h2 = c->at<float>(c->ws.h2_f32);
+    uint16_t *h1b = c->at<uint16_t>(c->ws.h1_bf16), *h2b = c->at<uint16_t>(c->ws.h2_bf16);
+    float *qkv = c->at<float>(c->ws.qkv), *attn = c->at<float>(c->ws.attn_f32), *m = c->at<float>(c->ws.m_f32);
+    uint16_t *qb = c->at<uint16_t>(c->ws.q_bf16), *attnb = c->at<uint16_t>(c->ws.attn_bf16), *mb = c->at<uint16_t>(c->ws.m_bf16);
+    float *pml = c->at<float>(c->ws.part_ml), *po = c->at<float>(c->ws.part_o);
+    const double *inv_freq = d.rope_theta > 0.f ? c->at<double>(c->ws.inv_freq) : nullptr;
+    hipStream_t s = c->main;
+    bool side_used = false;
+    c->last_prefetch_launches = 0;
+    psv_status st;
+
+    HIP_TRY(launch_add_rmsnorm(x_in, nullptr, static_cast<const uint16_t *>(c->weights[lb].g_attn), d.rms_eps, B, H, x, h1, h1b, s));
+    for (uint32_t l = lb; l < le; ++l) {
+        const psv_layer_weights &w = c->weights[l];
+        const KvView kv = kv_view(c, l);
+
+        if ((st = prof_begin(c, PSV_OP_QKV)) != PSV_OK) return st;
+        if ((st = projection(c, w.w_qkv, nullptr, h1, h1b, qkv, nullptr, B, QR, H)) != PSV_OK) return st;
+        if ((st = prof_end(c, PSV_OP_QKV)) != PSV_OK) return st;
+
+        HIP_TRY(launch_rope_append(qkv, inv_freq, kv, B, nq, nkv, qb, s));
+
+        if ((st = prof_begin(c, PSV_OP_ATTN)) != PSV_OK) return st;
+        HIP_TRY(launch_attn_partial(qb, kv, B, nq, nkv, sp, pml, po, s));
+        HIP_TRY(launch_attn_combine(pml, po, B, nq, nkv, sp, attn, attnb, s));
+        if ((st = prof_end(c, PSV_OP_ATTN)) != PSV_OK) return st;
+
+        if ((st = prof_begin(c, PSV_OP_O)) != PSV_OK) return st;
+        if ((st = projection(c, w.w_o, nullptr, attn, attnb, delta, nullptr, B, H, QD)) != PSV_OK) return st;
+        if ((st = prof_end(c, PSV_OP_O)) != PSV_OK) return st;
+
+        if ((st = comm_window(c, l, 0, batch, le, &side_used)) != PSV_OK) return st;
+
+        HIP_TRY(launch_add_rmsnorm(x, delta, static_cast<const uint16_t *>(w.g_mlp), d.rms_eps, B, H, y, h2, h2b, s));
+
+        if ((st = prof_begin(c, PSV_OP_GATE)) != PSV_OK) return st;
+        if ((st = projection(c, w.w_gate, w.w_up, h2, h2b, m, mb, B, F, H)) != PSV_OK) return st;
+        if ((st = prof_end(c, PSV_OP_GATE)) != PSV_OK) return st;
+
+        if ((st = prof_begin(c, PSV_OP_DOWN)) != PSV_OK) return st;
+        if ((st = projection(c, w.w_down, nullptr, m, mb, delta, nullptr, B, H, F)) != PSV_OK) return st;
+        if ((st = prof_end(c, PSV_OP_DOWN)) != PSV_OK) return st;
+
+        if ((st = comm_window(c, l, 1, batch, le, &side_used)) != PSV_OK) return st;
+
+        if (l + 1 < le)
+            HIP_TRY(launch_add_rmsnorm(y, delta, static_cast<const uint16_t *>(c->weights[l + 1].g_attn), d.rms_eps, B, H, x, h1, h1b, s));
+        else
+            HIP_TRY(launch_add_rmsnorm(y, delta, nullptr, d.rms_eps, B, H, x_out, nullptr, nullptr, s));
+    }
+    if (side_used) {   // the side stream rejoins, so that the next step cannot overtake this one's prefetches
+        HIP_TRY(hipEventRecord(c->ev_end, c->side));
+        HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));
+    }
+    return PSV_OK;
+}
+
+psv_status rebuild_plan(psv_ctx *c)
+{
+    c->plan.clear();
+    if (c->plan_batch == 0) return PSV_OK;
+    size_t n = plan_chain(c->d, c->plan_batch, c->plan_context, c->policy, nullptr, 0);
+    c->plan.resize(n);
+    if (n) plan_chain(c->d, c->plan_batch, c->plan_context, c->policy, c->plan.data(), n);
+    return PSV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t psv_workspace_bytes(const psv_model_desc *desc)
+{
+    if (psv_validate_desc(desc) != PSV_OK) return 0;
+    return layout_workspace(*desc).total;
+}
+
+psv_status psv_create(const psv_model_desc *desc, void *stream_main, void *stream_side, psv_ctx **out)
+{
+    if (!desc || !out) return PSV_ERR_INVALID_ARG;
+    if (psv_validate_desc(desc) != PSV_OK) return PSV_ERR_INVALID_ARG;
+    if (stream_main == stream_side) return PSV_ERR_INVALID_ARG;
+    psv_ctx *c = new (std::nothrow) psv_ctx();
+    if (!c) return PSV_ERR_NOMEM;
+    c->d = *desc;
+    c->main = static_cast<hipStream_t>(stream_main);
+    c->side = static_cast<hipStream_t>(stream_side);
+    auto fail = [&](psv_status st) { psv_destroy(c); return st; };
+    if (hipGetDevice(&c->device) != hipSuccess) return fail(PSV_ERR_HIP);
+    int khz = 0;
+    if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device) == hipSuccess && khz > 0) c->clock_khz = (uint64_t)khz;
+    c->ws = layout_workspace(c->d);
+    if (hipMalloc(reinterpret_cast<void **>(&c->wsp), c->ws.total) != hipSuccess) {
+        c->wsp = nullptr;
+        return fail(PSV_ERR_NOMEM);
+    }
+    if (hipMemset(c->wsp, 0, c->ws.total) != hipSuccess) return fail(PSV_ERR_HIP);
+    if (c->d.rope_theta > 0.f) {
+        double f[64];
+        for (int i = 0; i < 64; ++i) f[i] = pow((double)c->d.rope_theta, -2.0 * (double)i / 128.0);
+        if (hipMemcpy(c->wsp + c->ws.inv_freq, f, sizeof f, hipMemcpyHostToDevice) != hipSuccess) return fail(PSV_ERR_HIP);
+    }
+    c->weights.resize(c->d.n_layers);
+    c->weights_set.assign(c->d.n_layers, 0);
+    c->k_pools.assign(c->d.n_layers, nullptr);
+    c->v_pools.assign(c->d.n_layers, nullptr);
+    c->ev_fork.assign((size_t)c->d.n_layers * 2, nullptr);
+    c->ev_join.assign((size_t)c->d.n_layers * 2, nullptr);
+    for (size_t i = 0; i < c->ev_fork.size(); ++i) {
+        if (hipEventCreateWithFlags(&c->ev_fork[i], hipEventDisableTiming) != hipSuccess) return fail(PSV_ERR_HIP);
+        if (hipEventCreateWithFlags(&c->ev_join[i], hipEventDisableTiming) != hipSuccess) return fail(PSV_ERR_HIP);
+    }
+    if (hipEventCreateWithFlags(&c->ev_end, hipEventDisableTiming) != hipSuccess) return fail(PSV_ERR_HIP);
+    c->policy.mode = 0;
+    c->policy.targets = PSV_TARGET_WEIGHTS | PSV_TARGET_KV;
+    *out = c;
+    return PSV_OK;
+}
+
+psv_status psv_destroy(psv_ctx *c)
+{
+    if (!c) return PSV_ERR_INVALID_ARG;
+    drop_graph(c);
+    for (hipEvent_t e : c->ev_fork) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->ev_join) if (e) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->prof_events) if (e) (void)hipEventDestroy(e);
+    if (c->ev_end) (void)hipEventDestroy(c->ev_end);
+    if (c->wsp) (void)hipFree(c->wsp);
+    delete c;
+    return PSV_OK;
+}
+
+psv_status psv_set_layer_weights(psv_ctx *c, uint32_t layer, const psv_layer_weights *w)
+{
+    if (!c || !w || layer >= c->d.n_layers) return PSV_ERR_INVALID_ARG;
+    if (!w->w_qkv || !w->w_o || !w->w_gate || !w->w_up || !w->w_down || !w->g_attn || !w->g_mlp) return PSV_ERR_INVALID_ARG;
+    const void *ptrs[7] = {w->w_qkv, w->w_o, w->w_gate, w->w_up, w->w_down, w->g_attn, w->g_mlp};
+    for (const void *p : ptrs)
+        if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return PSV_ERR_INVALID_ARG;
+    c->weights[layer] = *w;
+    c->weights_set[layer] = 1;
+    touch(c);
+    return PSV_OK;
+}
+
+psv_status psv_set_kv(psv_ctx *c, const psv_kv_desc *kv)
+{
+    if (!c || !kv || !kv->k_pools || !kv->v_pools || !kv->seq_lens) return PSV_ERR_INVALID_ARG;
+    if (kv->max_blocks == 0 || (uint64_t)kv->max_blocks * PSV_BLOCK_TOKENS < c->d.max_seq) return PSV_ERR_INVALID_ARG;
+    if (kv->num_pool_blocks == 0 || kv->num_pool_blocks > 0x7fffffffu) return PSV_ERR_INVALID_ARG;
+    if ((uint64_t)kv->max_blocks * c->d.max_batch > 0x7fffffffull) return PSV_ERR_INVALID_ARG;
+    if (!kv->page_table && (uint64_t)kv->max_blocks * c->d.max_batch > kv->num_pool_blocks) return PSV_ERR_INVALID_ARG;
+    for (uint32_t l = 0; l < c->d.n_layers; ++l) {
+        if (!kv->k_pools[l] || !kv->v_pools[l]) return PSV_ERR_INVALID_ARG;
+        if (reinterpret_cast<uintptr_t>(kv->k_pools[l]) % 16 || reinterpret_cast<uintptr_t>(kv->v_pools[l]) % 16) return PSV_ERR_INVALID_ARG;
+    }
+    for (uint32_t l = 0; l < c->d.n_layers; ++l) {
+        c->k_pools[l] = kv->k_pools[l];
+        c->v_pools[l] = kv->v_pools[l];
+    }
+    c->kv = *kv;
+    c->kv.k_pools = nullptr;   // the host arrays are copied, not borrowed
+    c->kv.v_pools = nullptr;
+    c->kv_set = true;
+    touch(c);
+    return PSV_OK;
+}
+
+psv_status psv_set_comm_windows(psv_ctx *c, float us_after_attn, float us_after_mlp)
+{
+    if (!c || !(us_after_attn >= 0.f) || !(us_after_mlp >= 0.f) || us_after_attn > 1.0e6f || us_after_mlp > 1.0e6f) return PSV_ERR_INVALID_ARG;
+    c->window_us[0] = us_after_attn;
+    c->window_us[1] = us_after_mlp;
+    touch(c);
+    return PSV_OK;
+}
+
+psv_status psv_set_policy(psv_ctx *c, const psv_prefetch_policy *p, uint32_t batch, uint32_t context)
+{
+    if (!c || !p) return PSV_ERR_INVALID_ARG;
+    if (p->mode > 1 || (p->targets & ~3u) || p->partial > 1 || p->join > 1 || p->cu_budget > 65535) return PSV_ERR_INVALID_ARG;
+    if (batch == 0 || batch > c->d.max_batch || context == 0 || context > c->d.max_seq) return PSV_ERR_INVALID_ARG;
+    c->policy = *p;
+    c->plan_batch = batch;
+    c->plan_context = context;
+    touch(c);
+    return rebuild_plan(c);
+}
+
+psv_status psv_plan(psv_ctx *c, psv_plan_entry *out, size_t cap, size_t *n)
+{
+    if (!c || !n || (cap > 0 && !out)) return PSV_ERR_INVALID_ARG;
+    *n = c->plan.size();
+    for (size_t i = 0; i < c->plan.size() && i < cap; ++i) out[i] = c->plan[i];
+    return PSV_OK;
+}
+
+psv_status psv_set_graph_mode(psv_ctx *c, uint32_t use_graph)
+{
+    if (!c || use_graph > 1) return PSV_ERR_INVALID_ARG;
+    c->use_graph = use_graph == 1;
+    if (!c->use_graph) drop_graph(c);
+    return PSV_OK;
+}
+
+psv_status psv_decode_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t batch, uint32_t lb, uint32_t le)
+{
+    if (!c || !x_in || !x_out) return PSV_ERR_INVALID_ARG;
+    if (batch == 0 || batch > c->d.max_batch || lb >= le || le > c->d.n_layers) return PSV_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(x_in) % 16 || reinterpret_cast<uintptr_t>(x_out) % 16) return PSV_ERR_INVALID_ARG;
+    if (!c->kv_set) return PSV_ERR_BAD_STATE;
+    for (uint32_t l = lb; l < le; ++l)
+        if (!c->weights_set[l]) return PSV_ERR_BAD_STATE;
+    if (c->policy.mode == 1 && c->plan_batch != batch) return PSV_ERR_BAD_STATE;   // the plan was sized for another batch
+    ++c->steps;
+    if (!c->use_graph) return enqueue_step(c, x_in, x_out, batch, lb, le);
+
+    GraphKey key{x_in, x_out, batch, lb, le, c->version};
+    if (!c->graph_exec || !(key == c->graph_key)) {
+        drop_graph(c);
+        hipGraph_t graph = nullptr;
+        HIP_TRY(hipStreamBeginCapture(c->main, hipStreamCaptureModeThreadLocal));
+        c->capturing = true;
+        psv_status st = enqueue_step(c, x_in, x_out, batch, lb, le);
+        c->capturing = false;
+        hipError_t e = hipStreamEndCapture(c->main, &graph);
+        if (st != PSV_OK || e != hipSuccess) {
+            if (graph) (void)hipGraphDestroy(graph);
+            return st != PSV_OK ? st : PSV_ERR_HIP;
+        }
+        e = hipGraphInstantiate(&c->graph_exec, graph, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(graph);
+        if (e != hipSuccess) {
+            c->graph_exec = nullptr;
+            return PSV_ERR_HIP;
+        }
+        c->graph_key = key;
+    }
+    HIP_TRY(hipGraphLaunch(c->graph_exec, c->main));
+    return PSV_OK;
+}
+
+psv_status psv_sync(psv_ctx *c)
+{
+    if (!c) return PSV_ERR_INVALID_ARG;
+    hipError_t a = hipStreamSynchronize(c->main);
+    hipError_t b = hipStreamSynchronize(c->side);
+    hipError_t l = hipGetLastError();
+    return (a == hipSuccess && b == hipSuccess && l == hipSuccess) ? PSV_OK : PSV_ERR_HIP;
+}
+
+psv_status psv_get_stats(psv_ctx *c, psv_stats *out)
+{
+    if (!c || !out) return PSV_ERR_INVALID_ARG;
+    memset(out, 0, sizeof *out);
+    const uint32_t batch = c->plan_batch ? c->plan_batch : c->d.max_batch;
+    const uint32_t context = c->plan_context ? c->plan_context : c->d.max_seq;
+    uint64_t wb = 0;
+    for (uint32_t op = 0; op < PSV_OP_COUNT; ++op)
+        if (op != PSV_OP_ATTN) wb += op_mem_size(c->d, op, batch, context);
+    out->weight_bytes_per_layer = wb;
+    out->kv_bytes_per_layer = (uint64_t)batch * context * c->d.n_kv_heads * c->d.head_dim * 2 * 2;
+    for (const psv_plan_entry &e : c->plan) out->planned_prefetch_bytes += e.bytes;
+    out->workspace_bytes = c->ws.total;
+    out->kernels_per_layer = 9 + (c->window_us[0] > 0.f ? 1 : 0) + (c->window_us[1] > 0.f ? 1 : 0);
+    out->prefetch_launches = c->last_prefetch_launches;
+    out->steps = c->steps;
+    return PSV_OK;
+}
+
+psv_status psv_set_profile_op(psv_ctx *c, int32_t op)
+{
+    if (!c || op < -1 || op >= (int32_t)PSV_OP_COUNT || op == PSV_OP_UP) return PSV_ERR_INVALID_ARG;   // up shares gate's kernel
+    c->profile_op = op;
+    c->prof_used = 0;
+    return PSV_OK;
+}
+
+psv_status psv_get_profile(psv_ctx *c, double *total_ms, uint64_t *launches)
+{
+    if (!c || !total_ms || !launches) return PSV_ERR_INVALID_ARG;
+    psv_status st = psv_sync(c);
+    if (st != PSV_OK) return st;
+    double sum = 0.0;
+    for (size_t i = 0; i + 1 < c->prof_used; i += 2) {
+        float ms = 0.f;
+        HIP_TRY(hipEventElapsedTime(&ms, c->prof_events[i], c->prof_events[i + 1]));
+        sum += ms;
+    }
+    *total_ms = sum;
+    *launches = c->prof_used / 2;
+    c->prof_used = 0;
+    return PSV_OK;
+}
+
+static uint64_t current_clock_khz()
+{
+    int dev = 0, khz = 0;
+    if (hipGetDevice(&dev) == hipSuccess && hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
+        return (uint64_t)khz;
+    return 100000;
+}
+
+psv_status psv_prefetch_region(const void *ptr, uint64_t bytes, uint32_t workgroups, void *stream)
+{
+    if (!ptr || reinterpret_cast<uintptr_t>(ptr) % 16 || workgroups == 0 || workgroups > 65535) return PSV_ERR_INVALID_ARG;
+    HIP_TRY(launch_prefetch(ptr, bytes & ~(uint64_t)15, workgroups, static_cast<hipStream_t>(stream)));
+    return PSV_OK;
+}
+
+psv_status psv_spin(float us, void *stream)
+{
+    if (!(us >= 0.f) || us > 1.0e6f) return PSV_ERR_INVALID_ARG;
+    if (us == 0.f) return PSV_OK;
+    HIP_TRY(launch_spin(us_to_ticks(current_clock_khz(), us), spin_cap(us), static_cast<hipStream_t>(stream)));
+    return PSV_OK;
+}
+
+psv_status psv_copy_bytes(void *dst, const void *src, uint64_t bytes, void *stream)
+{
+    if (!dst || !src || bytes % 16 || reinterpret_cast<uintptr_t>(dst) % 16 || reinterpret_cast<uintptr_t>(src) % 16) return PSV_ERR_INVALID_ARG;
+    HIP_TRY(launch_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
+    return PSV_OK;
+}
+
+psv_status psv_debug_read(psv_ctx *c, uint32_t which, void *host_dst, size_t bytes)
+{
+    if (!c || !host_dst || which >= PSV_DBG_COUNT) return PSV_ERR_INVALID_ARG;
+    psv_status st = psv_sync(c);
+    if (st != PSV_OK) return st;
+    const size_t B = c->d.max_batch, H = c->d.hidden;
+    const size_t QR = (size_t)(c->d.n_q_heads + 2 * c->d.n_kv_heads) * 128, QD = (size_t)c->d.n_q_heads * 128;
+    size_t off = 0, size = 0;
+    switch (which) {
+    case PSV_DBG_H1: off = c->ws.h1_f32; size = B * H * 4; break;
+    case PSV_DBG_QKV: off = c->ws.qkv; size = B * QR * 4; break;
+    case PSV_DBG_ATTN: off = c->ws.attn_f32; size = B * QD * 4; break;
+    case PSV_DBG_Y: off = c->ws.y; size = B * H * 4; break;
+    case PSV_DBG_H2: off = c->ws.h2_f32; size = B * H * 4; break;
+    case PSV_DBG_M: off = c->ws.m_f32; size = B * (size_t)c->d.ffn * 4; break;
+    default: return PSV_ERR_INVALID_ARG;
+    }
+    if (bytes < size) size = bytes;
+    HIP_TRY(hipMemcpy(host_dst, c->wsp + off, size, hipMemcpyDeviceToHost));
+    return PSV_OK;
+}
+
+}  // extern "C"

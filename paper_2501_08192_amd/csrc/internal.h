@@ -1,0 +1,84 @@
+// Internal interface between the host side of libpreserve_mi355x (api.cpp, planner.cpp) and
+// its gfx950 kernels (kernels.hip).  Launch wrappers take plain pointers and sizes, validate
+// nothing (the API layer has already done so) and return the hipError_t of the launch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/preserve.h"
+
+namespace psv {
+
+// ---- attention work split ---------------------------------------------------------------
+// One 64-lane wave consumes the KV-cache in tiles of 32 tokens; a workgroup has 4 waves, so a
+// workgroup's chunk is a multiple of 128 tokens.  Every wave writes its own partial result.
+constexpr int kAttnTileTokens = 32;
+constexpr int kAttnWaves = 4;
+
+struct AttnSplit {
+    int chunk_tokens;   // tokens per workgroup
+    int n_chunks;       // workgroups along the sequence (grid.x)
+    int n_splits;       // partial results per (sequence, kv head) = n_chunks * kAttnWaves
+};
+AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq);
+
+// ---- kernel launchers ---------------------------------------------------------------------
+
+// out_res = res + delta (delta may be null); if gain != null: h = out_res * rsqrt(mean(out_res^2)
+// + eps) * gain, written as fp32 (h_f32) and bf16 (h_bf16, row stride H).  One workgroup per row.
+hipError_t launch_add_rmsnorm(const float *res, const float *delta, const uint16_t *gain, float eps,
+                              int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
+                              hipStream_t s);
+
+// Vector-ALU GEMV for batch <= 4:  out[b][r] = sum_k W[r][k] * x[b][k]   (fp32 x, bf16 W).
+// W2 != null selects the SwiGLU form: out[b][r] = silu(W[r].x[b]) * (W2[r].x[b]); out_bf16
+// (optional, row stride N) receives the rounded result as well.
+hipError_t launch_gemv(const uint16_t *W, const uint16_t *W2, const float *x, float *out,
+                       uint16_t *out_bf16, int batch, int N, int K, hipStream_t s);
+bool gemv_supported(int batch, int N, int K);
+
+// MFMA skinny GEMM for any batch: same contract, x given as bf16 [round_up(batch,16)][K].
+hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_t *x_bf16, float *out,
+                            uint16_t *out_bf16, int batch, int N, int K, hipStream_t s);
+bool gemm_mfma_supported(int batch, int N, int K);
+
+struct KvView {
+    uint16_t *k_pool;
+    uint16_t *v_pool;
+    const int32_t *page_table;   // null => contiguous
+    int max_blocks;
+    int num_pool_blocks;
+    const int32_t *seq_lens;
+};
+
+// Rotary embedding of q and k at position seq_len-1, q -> bf16 [batch][nq][128]; k, v of the new
+// token rounded to bf16 and stored in slot seq_len-1 of the pools.
+hipError_t launch_rope_append(const float *qkv, const double *inv_freq, KvView kv, int batch, int nq,
+                              int nkv, uint16_t *q_bf16, hipStream_t s);
+
+// Split-K decode attention: partial (max, sum, weighted V) per wave, then a fixed-order combine.
+hipError_t launch_attn_partial(const uint16_t *q_bf16, KvView kv, int batch, int nq, int nkv,
+                               AttnSplit split, float *part_ml, float *part_o, hipStream_t s);
+hipError_t launch_attn_combine(const float *part_ml, const float *part_o, int batch, int nq, int nkv,
+                               AttnSplit split, float *out_f32, uint16_t *out_bf16, hipStream_t s);
+
+// Communication stand-in: one workgroup busy-waits `ticks` of the constant-rate wall clock.
+hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, hipStream_t s);
+
+// Prefetch: read [ptr, ptr+bytes) with `workgroups` workgroups, write nothing.
+hipError_t launch_prefetch(const void *ptr, uint64_t bytes, uint32_t workgroups, hipStream_t s);
+// Prefetch logical KV blocks [first, first+count) of the flattened (sequence, block) order, where
+// sequence b owns blocks_per_seq logical blocks; walks the page table.
+hipError_t launch_prefetch_kv(KvView kv, int nkv, uint32_t blocks_per_seq, uint64_t first,
+                              uint64_t count, uint32_t workgroups, hipStream_t s);
+
+hipError_t launch_copy(void *dst, const void *src, uint64_t bytes, hipStream_t s);
+
+// ---- planner (pure host) ---------------------------------------------------------------------
+uint64_t op_mem_size(const psv_model_desc &d, uint32_t op, uint32_t batch, uint32_t context);
+size_t plan_chain(const psv_model_desc &d, uint32_t batch, uint32_t context,
+                  const psv_prefetch_policy &p, psv_plan_entry *out, size_t cap);
+
+}  // namespace psv

@@ -1,0 +1,175 @@
+"""Host-side checks of libpreserve_mi355x.so that need no GPU: the library loads, exports every symbol the
+header declares, validates arguments, and its Algorithm-1 planner agrees with the oracle's."""
+import ctypes as C
+import json
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2501_08192_amd import binding as psv
+from paper_2501_08192_amd import synth
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_symbols():
+    text = open(os.path.join(ROOT, "include", "preserve.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(psv_[a-z_]+)\s*\(", text)))
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    L = psv.lib()
+    names = header_symbols()
+    assert len(names) >= 20
+    for n in names:
+        assert hasattr(L, n), n
+    assert sorted(psv.EXPORTS) == names
+
+
+def test_strerror_is_total():
+    for s in (0, -1, -2, -3, -4, -5, -99, 7):
+        assert isinstance(psv.strerror(s), str) and psv.strerror(s)
+
+
+def _desc(w, **kw):
+    d = dict(n_layers=w.n_layers, hidden=w.hidden, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads, ffn=w.ffn,
+             max_batch=w.batch, max_seq=w.context)
+    d.update(kw)
+    return psv.model_desc(**d)
+
+
+def test_descriptor_validation():
+    for w in synth.WORKLOADS.values():
+        assert psv.psv_validate_desc(_desc(w)) == psv.PSV_OK
+        assert psv.psv_workspace_bytes(_desc(w)) > 0
+    w = synth.WORKLOADS["c2"]
+    bad = [dict(head_dim=64), dict(n_kv_heads=3), dict(hidden=4000), dict(ffn=1000), dict(max_seq=100),
+           dict(max_batch=0), dict(max_batch=65), dict(n_layers=0), dict(n_q_heads=32, n_kv_heads=1),
+           dict(rms_eps=-1.0), dict(rope_theta=-5.0)]
+    for kw in bad:
+        assert psv.psv_validate_desc(_desc(w, **kw)) == psv.PSV_ERR_INVALID_ARG, kw
+        assert psv.psv_workspace_bytes(_desc(w, **kw)) == 0
+    assert psv.lib().psv_validate_desc(None) == psv.PSV_ERR_INVALID_ARG
+
+
+def test_null_and_range_arguments_are_rejected_without_a_gpu():
+    L = psv.lib()
+    d = _desc(synth.WORKLOADS["c1"])
+    n = C.c_size_t(0)
+    pol = psv.prefetch_policy(mode=1, budget_bytes=1 << 30)
+    assert L.psv_plan_chain(None, 1, 256, C.byref(pol), None, 0, C.byref(n)) == psv.PSV_ERR_INVALID_ARG
+    assert L.psv_plan_chain(C.byref(d), 1, 256, None, None, 0, C.byref(n)) == psv.PSV_ERR_INVALID_ARG
+    assert L.psv_plan_chain(C.byref(d), 1, 256, C.byref(pol), None, 0, None) == psv.PSV_ERR_INVALID_ARG
+    assert L.psv_plan_chain(C.byref(d), 1, 256, C.byref(pol), None, 4, C.byref(n)) == psv.PSV_ERR_INVALID_ARG
+    assert L.psv_plan_chain(C.byref(d), 2, 256, C.byref(pol), None, 0, C.byref(n)) == psv.PSV_ERR_INVALID_ARG   # batch > max
+    assert L.psv_plan_chain(C.byref(d), 1, 0, C.byref(pol), None, 0, C.byref(n)) == psv.PSV_ERR_INVALID_ARG
+    bad = psv.prefetch_policy(mode=2)
+    assert L.psv_plan_chain(C.byref(d), 1, 256, C.byref(bad), None, 0, C.byref(n)) == psv.PSV_ERR_INVALID_ARG
+    for fn in (L.psv_destroy, L.psv_sync):
+        assert fn(None) == psv.PSV_ERR_INVALID_ARG
+    assert L.psv_decode_step(None, None, None, 1, 0, 1) == psv.PSV_ERR_INVALID_ARG
+    assert L.psv_create(None, None, None, None) == psv.PSV_ERR_INVALID_ARG
+    out = C.c_void_p()
+    assert L.psv_create(C.byref(d), 5, 5, C.byref(out)) == psv.PSV_ERR_INVALID_ARG     # same stream twice
+    assert L.psv_prefetch_region(None, 64, 1, None) == psv.PSV_ERR_INVALID_ARG
+    assert L.psv_spin(-1.0, None) == psv.PSV_ERR_INVALID_ARG
+    assert L.psv_copy_bytes(None, None, 16, None) == psv.PSV_ERR_INVALID_ARG
+
+
+def test_create_fails_cleanly_without_a_gpu():
+    import torch
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    d = _desc(synth.WORKLOADS["c1"])
+    out = C.c_void_p()
+    st = psv.lib().psv_create(C.byref(d), None, 1, C.byref(out))
+    assert st in (psv.PSV_ERR_HIP, psv.PSV_ERR_NOMEM) and not out.value
+
+
+# ---- Algorithm 1: the library's chain planner against the oracle's general-graph planner -----------------
+
+OPS = ["norm1", "qkv", "rope", "attn", "o", "comm1", "norm2", "gate", "up", "act", "down", "comm2"]
+KIND = {"qkv": oracle.NODE_MATMUL, "attn": oracle.NODE_SELFATTN, "o": oracle.NODE_MATMUL, "gate": oracle.NODE_MATMUL,
+        "up": oracle.NODE_MATMUL, "down": oracle.NODE_MATMUL, "comm1": oracle.NODE_COMM, "comm2": oracle.NODE_COMM}
+OP_ID = {"qkv": psv.PSV_OP_QKV, "attn": psv.PSV_OP_ATTN, "o": psv.PSV_OP_O, "gate": psv.PSV_OP_GATE,
+         "up": psv.PSV_OP_UP, "down": psv.PSV_OP_DOWN}
+
+
+def sizes_of(w, batch, context):
+    """memSize() per operator, restated from the shapes (bf16 = 2 bytes)."""
+    h, f, d = w.hidden, w.ffn, w.head_dim
+    return {"qkv": (w.n_q_heads + 2 * w.n_kv_heads) * d * h * 2, "attn": batch * (context - 1) * w.n_kv_heads * d * 2 * 2,
+            "o": h * w.n_q_heads * d * 2, "gate": f * h * 2, "up": f * h * 2, "down": h * f * 2}
+
+
+def oracle_plan(w, batch, context, C_bytes, targets=3):
+    sz = sizes_of(w, batch, context)
+    names, types, mem = [], [], []
+    for l in range(w.n_layers):
+        for op in OPS:
+            names.append((l, op))
+            k = KIND.get(op, oracle.NODE_OTHER)
+            if k == oracle.NODE_SELFATTN and not targets & 2:
+                k = oracle.NODE_OTHER
+            if k == oracle.NODE_MATMUL and not targets & 1:
+                k = oracle.NODE_OTHER
+            types.append(k)
+            mem.append(sz.get(op, 0))
+    n = len(names)
+    children = [[i + 1] if i + 1 < n else [] for i in range(n)]
+    out = []
+    for comm, tgt in oracle.plan(types, mem, children, C_bytes):
+        (l, cop), (tl, top) = names[comm], names[tgt]
+        out.append(dict(layer=l, window=0 if cop == "comm1" else 1, target_layer=tl, target_op=OP_ID[top],
+                        mem_size=sz[top], bytes=sz[top]))
+    return out
+
+
+@pytest.mark.parametrize("name", ["c1", "c2", "c3", "c4", "c5"])
+def test_chain_planner_matches_oracle_algorithm1(name):
+    w = synth.WORKLOADS[name].scaled(n_layers=3)
+    d = _desc(w)
+    sz = sizes_of(w, w.batch, w.context)
+    budgets = {0, 1, 10 ** 6, 6 * 10 ** 6, 40 * 10 ** 6, 64 * 10 ** 6, 256 * 2 ** 20, 2 ** 40,
+               sz["gate"], sz["gate"] + 1, 3 * sz["gate"], 3 * sz["gate"] + 1, sz["qkv"] + sz["attn"],
+               sz["qkv"] + sz["attn"] + 1, sz["qkv"] + sz["attn"] + sz["o"] + 1}
+    for Cb in sorted(budgets):
+        for targets in (1, 2, 3):
+            pol = psv.prefetch_policy(mode=1, targets=targets, budget_bytes=Cb)
+            got = psv.psv_plan_chain(d, w.batch, w.context, pol)
+            assert got == oracle_plan(w, w.batch, w.context, Cb, targets), (Cb, targets)
+
+
+def test_chain_planner_reproduces_hand_worked_plans():
+    g = json.load(open(os.path.join(ROOT, "tests", "golden", "alg1_plans_8b_shard.json")))
+    w = synth.WORKLOADS["c2"].scaled(n_layers=2)
+    d = _desc(w)
+    inv = {v: k for k, v in OP_ID.items()}
+    for case in g["cases"]:
+        got = psv.psv_plan_chain(d, 1, 2048, psv.prefetch_policy(mode=1, budget_bytes=case["C"]))
+        w1 = [inv[e["target_op"]] for e in got if e["layer"] == 0 and e["window"] == 0]
+        w2 = [inv[e["target_op"]] for e in got if e["layer"] == 0 and e["window"] == 1]
+        assert w1 == case["window1"] and w2 == case["window2"], case
+        assert not [e for e in got if e["layer"] == 1 and e["window"] == 1]          # end of graph
+        for e in got:
+            assert e["bytes"] == e["mem_size"] == g["sizes"][inv[e["target_op"]]]
+
+
+def test_mode_off_plans_nothing_and_partial_extension_fills_the_budget():
+    w = synth.WORKLOADS["c4"].scaled(n_layers=2)
+    d = _desc(w)
+    assert psv.psv_plan_chain(d, w.batch, w.context, psv.prefetch_policy(mode=0, budget_bytes=1 << 40)) == []
+    sz = sizes_of(w, w.batch, w.context)
+    Cb = 64 * 2 ** 20                       # qkv fits, the 256 MiB of KV does not
+    whole = psv.psv_plan_chain(d, w.batch, w.context, psv.prefetch_policy(mode=1, budget_bytes=Cb))
+    part = psv.psv_plan_chain(d, w.batch, w.context, psv.prefetch_policy(mode=1, budget_bytes=Cb, partial=1))
+    w2 = [e for e in whole if e["window"] == 1]
+    p2 = [e for e in part if e["window"] == 1]
+    assert [e["target_op"] for e in w2] == [psv.PSV_OP_QKV]
+    assert [e["target_op"] for e in p2] == [psv.PSV_OP_QKV, psv.PSV_OP_ATTN]
+    assert p2[1]["mem_size"] == sz["attn"] and p2[1]["bytes"] == Cb - 1 - sz["qkv"]
+    assert sum(e["bytes"] for e in p2) < Cb
