@@ -1,0 +1,191 @@
+#!/usr/bin/env python3
+"""Benchmark of the PRESERVE decode step on one MI355X.
+
+A "step" is one pass of the whole hot path (all layers: norms, QKV, RoPE + KV append, decode
+attention, O, comm window #1 || prefetch, gate/up + SwiGLU, down, comm window #2 || prefetch) over one
+batch of synthetic input that is already resident in HBM.  The default workload is c2, one TP=8 shard
+of a Llama-3-8B-shaped model (the configuration the metric is quoted on).  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--budget-mb 64] ...
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--layers", type=int, default=0, help="materialise only the first N layers (0 = all)")
+    ap.add_argument("--budget-mb", type=float, default=64.0, help="Algorithm 1's capacity C")
+    ap.add_argument("--chunk-mb", type=float, default=0.0)
+    ap.add_argument("--cu-budget", type=int, default=64)
+    ap.add_argument("--partial", type=int, default=0)
+    ap.add_argument("--join", type=int, default=0)
+    ap.add_argument("--targets", type=int, default=3)
+    ap.add_argument("--graph", type=int, default=1, help="replay the step as a HIP graph")
+    ap.add_argument("--window-us", type=float, nargs=2, default=None)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = auto)")
+    ap.add_argument("--seed", type=int, default=2501)
+    return ap.parse_args()
+
+
+def time_steps(sess, steps, warmup):
+    """W untimed steps, then exactly K steps between two full synchronisations.  Returns ms per step."""
+    import torch
+    for _ in range(warmup):
+        sess.step()
+    sess.sync()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        sess.step()
+    sess.sync()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / steps
+
+
+def profile_op(sess, op, steps):
+    """Average duration (us) of one operator's kernel, bracketed by HIP events on the main stream."""
+    from paper_2501_08192_amd import binding as psv
+    psv.psv_set_graph_mode(sess.ctx, False)
+    psv.psv_set_profile_op(sess.ctx, op)
+    for _ in range(steps):
+        sess.step()
+    ms, n = psv.psv_get_profile(sess.ctx)
+    psv.psv_set_profile_op(sess.ctx, -1)
+    return ms * 1e3 / max(1, n), n
+
+
+def cpu_baseline(sess, n_layers, target_s=10.0, max_reps=40):
+    """The CPU oracle, as it stands, on the first n_layers of the same workload (host cores of this machine),
+    repeated until about target_s seconds of CPU work have been timed."""
+    import numpy as np
+    import oracle
+    w = sess.w
+    m = oracle.model(w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn, 16, w.rms_eps, w.rope_theta)
+    x0 = sess.x_in.cpu().numpy().astype(np.float64)
+    pt = sess.page_table_host.numpy() if w.paged else None
+    lens = sess.seq_lens_host.numpy()
+    host = [(sess.host_layer(l), *sess.host_pools(l)) for l in sess.layers[:n_layers]]
+    reps, total = 0, 0.0
+    while reps < max_reps and (total < target_s or reps < 1):
+        x = x0
+        t0 = time.perf_counter()
+        for lw, kp, vp in host:
+            x = oracle.decode_layer(m, lw, kp, vp, pt, w.blocks_per_seq, lens, x)
+        total += time.perf_counter() - t0
+        reps += 1
+    return total * 1e6 / (reps * len(host)), len(host), reps, oracle.num_threads()
+
+
+def main():
+    a = parse()
+    if a.gpus != 1:
+        sys.stderr.write("bench.py: this build measures one GPU's shard only (no collectives are part of it); "
+                         "run with --gpus 1\n")
+        sys.exit(2)
+    import torch
+    from paper_2501_08192_amd import binding as psv
+    from paper_2501_08192_amd import synth
+    from paper_2501_08192_amd.harness import Session
+
+    if not torch.cuda.is_available():
+        sys.stderr.write("bench.py: no GPU\n")
+        sys.exit(1)
+    w = synth.WORKLOADS[a.workload]
+    if a.window_us is not None:
+        w = w.scaled(window_us=tuple(a.window_us))
+    layers = list(range(a.layers)) if a.layers else None
+    sess = Session(w, seed=a.seed, layers=layers)
+    L = len(sess.layers)
+    MB = 1 << 20
+    on = psv.prefetch_policy(mode=1, targets=a.targets, budget_bytes=int(a.budget_mb * MB),
+                             chunk_bytes=int(a.chunk_mb * MB), cu_budget=a.cu_budget, partial=a.partial, join=a.join)
+    off = psv.prefetch_policy(mode=0)
+
+    # prefetch off (vanilla execution) and on, same launch configuration otherwise
+    psv.psv_set_graph_mode(sess.ctx, bool(a.graph))
+    sess.set_policy(off)
+    x_off = sess.run().clone()
+    ms_off = time_steps(sess, a.steps, a.warmup)
+    sess.set_policy(on)
+    x_on = sess.run().clone()
+    ms_on = time_steps(sess, a.steps, a.warmup)
+    identical = bool(torch.equal(x_off, x_on))
+    stats = psv.psv_get_stats(sess.ctx)
+
+    us_off, us_on = ms_off * 1e3 / L, ms_on * 1e3 / L
+    win = sum(w.window_us)
+    layer_bytes = stats["weight_bytes_per_layer"] + stats["kv_bytes_per_layer"]
+    eff_off = layer_bytes / max(1e-9, (us_off - win)) / 1e3          # GB/s outside the windows
+    eff_on = layer_bytes / max(1e-9, (us_on - win)) / 1e3
+
+    # roofline of the dominant kernel (gate/up projection + SwiGLU), HBM-bound, prefetch off
+    sess.set_policy(off)
+    gate_us, gate_n = profile_op(sess, psv.PSV_OP_GATE, max(3, min(a.steps, 20)))
+    gate_bytes = 2 * w.ffn * w.hidden * 2
+    sess.set_policy(on)
+    gate_us_on, _ = profile_op(sess, psv.PSV_OP_GATE, max(3, min(a.steps, 20)))
+    achieved = gate_bytes / gate_us / 1e3
+
+    out = {
+        "metric": "decode_step_latency_us_per_layer_prefetch_on",
+        "value": round(us_on, 3),
+        "unit": "us/layer",
+        "n_gpus": 1,
+        "steps": a.steps,
+        "warmup": a.warmup,
+        "ms_per_step": round(ms_on, 5),
+        "higher_is_better": False,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s: %d layers, hidden %d, %d q / %d kv heads x 128, ffn %d, batch %d, context %d, %s KV, "
+                               "windows %g/%g us" % (w.name, L, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch,
+                                                      w.context, "paged" if w.paged else "contiguous", *w.window_us),
+                   "prefetch_budget_mb": a.budget_mb, "cu_budget": a.cu_budget, "chunk_mb": a.chunk_mb,
+                   "partial": a.partial, "join": a.join, "targets": a.targets, "hip_graph": bool(a.graph)},
+        "us_per_layer_prefetch_off": round(us_off, 3),
+        "prefetch_speedup": round(us_off / us_on, 4),
+        "on_off_bit_identical": identical,
+        "layer_bytes": layer_bytes,
+        "planned_prefetch_bytes_per_step": stats["planned_prefetch_bytes"],
+        "effective_hbm_gbps_outside_windows": {"prefetch_off": round(eff_off, 1), "prefetch_on": round(eff_on, 1),
+                                                "peak": HBM_PEAK_GBPS,
+                                                "frac_off": round(eff_off / HBM_PEAK_GBPS, 4),
+                                                "frac_on": round(eff_on / HBM_PEAK_GBPS, 4)},
+        "roofline": {"bound": "hbm", "kernel": "gate/up projection + SwiGLU (prefetch off)",
+                     "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "bytes_per_launch": gate_bytes, "avg_us": round(gate_us, 3), "launches": gate_n,
+                     "avg_us_prefetch_on": round(gate_us_on, 3),
+                     "achieved_prefetch_on": round(gate_bytes / gate_us_on / 1e3, 1)},
+    }
+    if not a.no_cpu_baseline:
+        # whole step when a layer is cheap; otherwise the first layers whose oracle cost is ~10-30 s
+        n_cpu = a.cpu_layers or max(1, min(L, int(6.0e10 / max(1, (stats["weight_bytes_per_layer"] +
+                                                                   8 * stats["kv_bytes_per_layer"]) * w.batch))))
+        cpu_us, n_done, reps, threads = cpu_baseline(sess, n_cpu)
+        out["cpu_baseline"] = {"value": round(cpu_us, 1), "unit": "us/layer", "cores": threads, "kind": "oracle",
+                               "sample": "fp64 C oracle, first %d of %d layers of the same workload, %d repetitions"
+                                         % (n_done, L, reps)}
+    sess.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -23,8 +23,8 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Workspace {
     size_t total = 0;
     // offsets
-    size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, q_bf16, part_ml, part_o, attn_f32, attn_bf16, delta,
-        m_f32, m_bf16, inv_freq;
+    size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, rope, counters, part_ml, part_o, attn_f32, attn_bf16,
+        delta_a, delta_m, m_f32, m_bf16, inv_freq;
 };
 
 Workspace layout_workspace(const psv_model_desc &d)
@@ -43,12 +43,14 @@ Workspace layout_workspace(const psv_model_desc &d)
     w.h2_f32 = take(B * H * 4);
     w.h2_bf16 = take(Bp * H * 2);
     w.qkv = take(B * QR * 4);
-    w.q_bf16 = take(B * QD * 2);
-    w.part_ml = take(B * d.n_kv_heads * (size_t)sp.n_splits * 16 * 2 * 4);
-    w.part_o = take(B * d.n_kv_heads * (size_t)sp.n_splits * G * 128 * 4);
+    w.rope = take(B * 64 * 2 * 4);
+    w.counters = take(B * d.n_kv_heads * 4);
+    w.part_ml = take(B * d.n_kv_heads * (size_t)sp.n_chunks * 16 * 2 * 4);
+    w.part_o = take(B * d.n_kv_heads * (size_t)sp.n_chunks * G * 128 * 4);
     w.attn_f32 = take(B * QD * 4);
     w.attn_bf16 = take(Bp * QD * 2);
-    w.delta = take(B * H * 4);
+    w.delta_a = take(B * H * 4);
+    w.delta_m = take(B * H * 4);
     w.m_f32 = take(B * F * 4);
     w.m_bf16 = take(Bp * F * 2);
     w.inv_freq = take(64 * sizeof(double));
@@ -160,18 +162,13 @@ psv_status prof_end(psv_ctx *c, int32_t op)
     return PSV_OK;
 }
 
-// y[b][:] = W x[b][:] (optionally the SwiGLU pair) with the kernel that suits the batch.
-psv_status projection(psv_ctx *c, const void *W, const void *W2, const float *x_f32, const uint16_t *x_bf16, float *out,
-                      uint16_t *out_bf16, int batch, int N, int K)
+// y[b][:] = W x[b][:] (optionally the SwiGLU pair) on the matrix cores; x as bf16.
+psv_status projection_mfma(psv_ctx *c, const void *W, const void *W2, const uint16_t *x_bf16, float *out,
+                           uint16_t *out_bf16, int batch, int N, int K)
 {
-    const uint16_t *w = static_cast<const uint16_t *>(W), *w2 = static_cast<const uint16_t *>(W2);
-    if (gemv_supported(batch, N, K)) {
-        HIP_TRY(launch_gemv(w, w2, x_f32, out, out_bf16, batch, N, K, c->main));
-    } else if (gemm_mfma_supported(batch, N, K)) {
-        HIP_TRY(launch_gemm_mfma(w, w2, x_bf16, out, out_bf16, batch, N, K, c->main));
-    } else {
-        return PSV_ERR_UNSUPPORTED;
-    }
+    if (!gemm_mfma_supported(batch, N, K)) return PSV_ERR_UNSUPPORTED;
+    HIP_TRY(launch_gemm_mfma(static_cast<const uint16_t *>(W), static_cast<const uint16_t *>(W2), x_bf16, out, out_bf16,
+                             batch, N, K, c->main));
     return PSV_OK;
 }
 
@@ -187,65 +184,120 @@ const void *weight_ptr(const psv_layer_weights &w, uint32_t op)
     }
 }
 
-psv_status launch_entry(psv_ctx *c, const psv_plan_entry &e, uint32_t batch)
+// Packs the plan entries of one window into prefetch launches: one launch per window, or several
+// when the policy caps the bytes per launch (chunk_bytes).
+struct JobBuilder {
+    psv_ctx *c;
+    uint64_t cap;        // bytes per launch (0 = unlimited)
+    uint64_t used = 0;
+    PrefetchJob job{};
+    psv_status st = PSV_OK;
+
+    void flush()
+    {
+        if (st != PSV_OK) return;
+        if (job.n_regions || job.kv_count) {
+            const uint32_t wg = c->policy.cu_budget ? c->policy.cu_budget : 64u;
+            if (launch_prefetch_job(job, wg, c->side) != hipSuccess) st = PSV_ERR_HIP;
+            ++c->last_prefetch_launches;
+        }
+        job = PrefetchJob{};
+        used = 0;
+    }
+    void add_region(const char *p, uint64_t bytes)
+    {
+        bytes &= ~(uint64_t)15;
+        while (bytes && st == PSV_OK) {
+            uint64_t room = cap ? (cap > used ? cap - used : 0) : bytes;
+            room &= ~(uint64_t)15;
+            if (room == 0 || job.n_regions == kPrefetchRegions) { flush(); continue; }
+            const uint64_t n = bytes < room ? bytes : room;
+            job.ptr[job.n_regions] = p;
+            job.n16[job.n_regions] = n / 16;
+            ++job.n_regions;
+            used += n;
+            p += n;
+            bytes -= n;
+        }
+    }
+    void add_kv(const KvView &v, int nkv, uint32_t blocks_per_seq, uint64_t count, uint64_t bytes_per_block)
+    {
+        uint64_t first = 0;
+        while (count && st == PSV_OK) {
+            uint64_t room = cap ? (cap > used ? (cap - used) / bytes_per_block : 0) : count;
+            if (room == 0 && used == 0) room = 1;          // a launch always makes progress
+            if (room == 0 || job.kv_count) { flush(); continue; }
+            const uint64_t n = count < room ? count : room;
+            job.kv = v;
+            job.nkv = nkv;
+            job.blocks_per_seq = blocks_per_seq;
+            job.kv_first = first;
+            job.kv_count = n;
+            used += n * bytes_per_block;
+            first += n;
+            count -= n;
+        }
+    }
+};
+
+psv_status add_entry(psv_ctx *c, JobBuilder &jb, const psv_plan_entry &e, uint32_t batch)
 {
-    const uint32_t wg = c->policy.cu_budget ? c->policy.cu_budget : 64u;
     if (e.target_op == PSV_OP_ATTN) {
         const uint32_t ro_tokens = c->plan_context > 0 ? c->plan_context - 1 : 0;
         const uint32_t blocks_per_seq = (ro_tokens + PSV_BLOCK_TOKENS - 1) / PSV_BLOCK_TOKENS;
         if (blocks_per_seq == 0) return PSV_OK;
         const uint64_t bytes_per_block = (uint64_t)c->d.n_kv_heads * PSV_BLOCK_TOKENS * PSV_HEAD_DIM * 2 * 2;
-        uint64_t total = (uint64_t)batch * blocks_per_seq;
+        const uint64_t total = (uint64_t)batch * blocks_per_seq;
         uint64_t count = (e.bytes + bytes_per_block - 1) / bytes_per_block;
         if (count > total) count = total;
-        uint64_t per_launch = c->policy.chunk_bytes ? c->policy.chunk_bytes / bytes_per_block : count;
-        if (per_launch == 0) per_launch = 1;
-        const KvView v = kv_view(c, e.target_layer);
-        for (uint64_t first = 0; first < count; first += per_launch) {
-            const uint64_t n = count - first < per_launch ? count - first : per_launch;
-            HIP_TRY(launch_prefetch_kv(v, (int)c->d.n_kv_heads, blocks_per_seq, first, n, wg, c->side));
-            ++c->last_prefetch_launches;
-        }
-        return PSV_OK;
+        jb.add_kv(kv_view(c, e.target_layer), (int)c->d.n_kv_heads, blocks_per_seq, count, bytes_per_block);
+        return jb.st;
     }
     const char *p = static_cast<const char *>(weight_ptr(c->weights[e.target_layer], e.target_op));
     if (!p) return PSV_ERR_BAD_STATE;
-    const uint64_t bytes = e.bytes & ~(uint64_t)15;
-    uint64_t per_launch = c->policy.chunk_bytes ? (c->policy.chunk_bytes & ~(uint64_t)15) : bytes;
-    if (per_launch == 0) per_launch = 16;
-    for (uint64_t off = 0; off < bytes; off += per_launch) {
-        const uint64_t n = bytes - off < per_launch ? bytes - off : per_launch;
-        HIP_TRY(launch_prefetch(p + off, n, wg, c->side));
-        ++c->last_prefetch_launches;
-    }
-    return PSV_OK;
+    jb.add_region(p, e.bytes);
+    return jb.st;
 }
 
-// The communication window after the attention block (window 0) or the MLP block (window 1).
+// The communication window after the attention block (window 0) or the MLP block (window 1).  The
+// fork event is recorded before the stand-in for the collective, so the prefetch starts with the
+// window; the stand-in is enqueued first so that the main stream never waits for the host.
 psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t batch, uint32_t layer_end, bool *side_used)
 {
     const float us = c->window_us[window];
     if (!(us > 0.f)) return PSV_OK;
-    bool forked = false;
-    if (c->policy.mode == 1) {
-        for (const psv_plan_entry &e : c->plan) {
-            if (e.layer != layer || e.window != window || e.target_layer >= layer_end) continue;
-            if (!forked) {
-                hipEvent_t ev = c->ev_fork[layer * 2 + window];
-                HIP_TRY(hipEventRecord(ev, c->main));
-                HIP_TRY(hipStreamWaitEvent(c->side, ev, 0));
-                forked = true;
-            }
-            psv_status st = launch_entry(c, e, batch);
-            if (st != PSV_OK) return st;
-        }
-        if (forked && c->policy.join) HIP_TRY(hipEventRecord(c->ev_join[layer * 2 + window], c->side));
-    }
+    bool any = false;
+    if (c->policy.mode == 1)
+        for (const psv_plan_entry &e : c->plan)
+            if (e.layer == layer && e.window == window && e.target_layer < layer_end) { any = true; break; }
+    hipEvent_t ev = c->ev_fork[layer * 2 + window];
+    if (any) HIP_TRY(hipEventRecord(ev, c->main));
     HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), c->main));
-    if (forked && c->policy.join) HIP_TRY(hipStreamWaitEvent(c->main, c->ev_join[layer * 2 + window], 0));
-    if (forked) *side_used = true;
+    if (!any) return PSV_OK;
+    HIP_TRY(hipStreamWaitEvent(c->side, ev, 0));
+    uint64_t cap = c->policy.chunk_bytes & ~(uint64_t)15;
+    if (c->policy.chunk_bytes && cap < 16) cap = 16;
+    JobBuilder jb{c, cap};
+    for (const psv_plan_entry &e : c->plan) {
+        if (e.layer != layer || e.window != window || e.target_layer >= layer_end) continue;
+        psv_status st = add_entry(c, jb, e, batch);
+        if (st != PSV_OK) return st;
+    }
+    jb.flush();
+    if (jb.st != PSV_OK) return jb.st;
+    if (c->policy.join) {
+        HIP_TRY(hipEventRecord(c->ev_join[layer * 2 + window], c->side));
+        HIP_TRY(hipStreamWaitEvent(c->main, c->ev_join[layer * 2 + window], 0));
+    }
+    *side_used = true;
     return PSV_OK;
 }
+
+#define ST_TRY(expr)                      \
+    do {                                  \
+        psv_status st__ = (expr);         \
+        if (st__ != PSV_OK) return st__;  \
+    } while (0)
 
 psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t batch, uint32_t lb, uint32_t le)
 {
@@ -253,57 +305,72 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     const int B = (int)batch, H = (int)d.hidden, F = (int)d.ffn, nq = (int)d.n_q_heads, nkv = (int)d.n_kv_heads;
     const int QR = (nq + 2 * nkv) * 128, QD = nq * 128;
     const AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq);
-    float *x = c->at<float>(c->ws.x), *y = c->at<float>(c->ws.y), *delta = c->at<float>(c->ws.delta);
+    float *x = c->at<float>(c->ws.x), *y = c->at<float>(c->ws.y);
+    float *delta_a = c->at<float>(c->ws.delta_a), *delta_m = c->at<float>(c->ws.delta_m);
     float *h1 = c->at<float>(c->ws.h1_f32), *h2 = c->at<float>(c->ws.h2_f32);
     uint16_t *h1b = c->at<uint16_t>(c->ws.h1_bf16), *h2b = c->at<uint16_t>(c->ws.h2_bf16);
     float *qkv = c->at<float>(c->ws.qkv), *attn = c->at<float>(c->ws.attn_f32), *m = c->at<float>(c->ws.m_f32);
-    uint16_t *qb = c->at<uint16_t>(c->ws.q_bf16), *attnb = c->at<uint16_t>(c->ws.attn_bf16), *mb = c->at<uint16_t>(c->ws.m_bf16);
+    uint16_t *attnb = c->at<uint16_t>(c->ws.attn_bf16), *mb = c->at<uint16_t>(c->ws.m_bf16);
     float *pml = c->at<float>(c->ws.part_ml), *po = c->at<float>(c->ws.part_o);
+    float2 *rope = c->at<float2>(c->ws.rope);
+    unsigned *counters = c->at<unsigned>(c->ws.counters);
     const double *inv_freq = d.rope_theta > 0.f ? c->at<double>(c->ws.inv_freq) : nullptr;
     hipStream_t s = c->main;
     bool side_used = false;
     c->last_prefetch_launches = 0;
-    psv_status st;
+    auto u16 = [](const void *p) { return static_cast<const uint16_t *>(p); };
 
-    HIP_TRY(launch_add_rmsnorm(x_in, nullptr, static_cast<const uint16_t *>(c->weights[lb].g_attn), d.rms_eps, B, H, x, h1, h1b, s));
+    // Small batches run every projection on the vector ALU with the normalisation fused into the
+    // prologue; larger ones use the matrix cores with a separate normalisation kernel.
+    const bool vec = gemv_supported(B, QR, H) && gemv_supported(B, H, QD) && gemv_supported(B, F, H) && gemv_supported(B, H, F);
+
+    HIP_TRY(launch_rope_table(c->kv.seq_lens, inv_freq, (int)c->kv.max_blocks * 16, B, rope, s));
+    const float *res = x_in, *delta = nullptr;   // residual stream entering the layer = res + delta
     for (uint32_t l = lb; l < le; ++l) {
         const psv_layer_weights &w = c->weights[l];
         const KvView kv = kv_view(c, l);
 
-        if ((st = prof_begin(c, PSV_OP_QKV)) != PSV_OK) return st;
-        if ((st = projection(c, w.w_qkv, nullptr, h1, h1b, qkv, nullptr, B, QR, H)) != PSV_OK) return st;
-        if ((st = prof_end(c, PSV_OP_QKV)) != PSV_OK) return st;
-
-        HIP_TRY(launch_rope_append(qkv, inv_freq, kv, B, nq, nkv, qb, s));
-
-        if ((st = prof_begin(c, PSV_OP_ATTN)) != PSV_OK) return st;
-        HIP_TRY(launch_attn_partial(qb, kv, B, nq, nkv, sp, pml, po, s));
-        HIP_TRY(launch_attn_combine(pml, po, B, nq, nkv, sp, attn, attnb, s));
-        if ((st = prof_end(c, PSV_OP_ATTN)) != PSV_OK) return st;
-
-        if ((st = prof_begin(c, PSV_OP_O)) != PSV_OK) return st;
-        if ((st = projection(c, w.w_o, nullptr, attn, attnb, delta, nullptr, B, H, QD)) != PSV_OK) return st;
-        if ((st = prof_end(c, PSV_OP_O)) != PSV_OK) return st;
-
-        if ((st = comm_window(c, l, 0, batch, le, &side_used)) != PSV_OK) return st;
-
-        HIP_TRY(launch_add_rmsnorm(x, delta, static_cast<const uint16_t *>(w.g_mlp), d.rms_eps, B, H, y, h2, h2b, s));
-
-        if ((st = prof_begin(c, PSV_OP_GATE)) != PSV_OK) return st;
-        if ((st = projection(c, w.w_gate, w.w_up, h2, h2b, m, mb, B, F, H)) != PSV_OK) return st;
-        if ((st = prof_end(c, PSV_OP_GATE)) != PSV_OK) return st;
-
-        if ((st = prof_begin(c, PSV_OP_DOWN)) != PSV_OK) return st;
-        if ((st = projection(c, w.w_down, nullptr, m, mb, delta, nullptr, B, H, F)) != PSV_OK) return st;
-        if ((st = prof_end(c, PSV_OP_DOWN)) != PSV_OK) return st;
-
-        if ((st = comm_window(c, l, 1, batch, le, &side_used)) != PSV_OK) return st;
-
-        if (l + 1 < le)
-            HIP_TRY(launch_add_rmsnorm(y, delta, static_cast<const uint16_t *>(c->weights[l + 1].g_attn), d.rms_eps, B, H, x, h1, h1b, s));
+        if (!vec) HIP_TRY(launch_add_rmsnorm(res, delta, u16(w.g_attn), d.rms_eps, B, H, x, h1, h1b, s));
+        ST_TRY(prof_begin(c, PSV_OP_QKV));
+        if (vec)
+            HIP_TRY(launch_gemv_norm(u16(w.w_qkv), nullptr, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H, s));
         else
-            HIP_TRY(launch_add_rmsnorm(y, delta, nullptr, d.rms_eps, B, H, x_out, nullptr, nullptr, s));
+            ST_TRY(projection_mfma(c, w.w_qkv, nullptr, h1b, qkv, nullptr, B, QR, H));
+        ST_TRY(prof_end(c, PSV_OP_QKV));
+
+        ST_TRY(prof_begin(c, PSV_OP_ATTN));
+        HIP_TRY(launch_attn(qkv, rope, kv, B, nq, nkv, sp, pml, po, counters, attn, attnb, s));
+        ST_TRY(prof_end(c, PSV_OP_ATTN));
+
+        ST_TRY(prof_begin(c, PSV_OP_O));
+        if (vec)
+            HIP_TRY(launch_gemv(u16(w.w_o), nullptr, attn, delta_a, B, H, QD, s));
+        else
+            ST_TRY(projection_mfma(c, w.w_o, nullptr, attnb, delta_a, nullptr, B, H, QD));
+        ST_TRY(prof_end(c, PSV_OP_O));
+
+        ST_TRY(comm_window(c, l, 0, batch, le, &side_used));
+
+        if (!vec) HIP_TRY(launch_add_rmsnorm(x, delta_a, u16(w.g_mlp), d.rms_eps, B, H, y, h2, h2b, s));
+        ST_TRY(prof_begin(c, PSV_OP_GATE));
+        if (vec)
+            HIP_TRY(launch_gemv_norm(u16(w.w_gate), u16(w.w_up), x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H, s));
+        else
+            ST_TRY(projection_mfma(c, w.w_gate, w.w_up, h2b, m, mb, B, F, H));
+        ST_TRY(prof_end(c, PSV_OP_GATE));
+
+        ST_TRY(prof_begin(c, PSV_OP_DOWN));
+        if (vec)
+            HIP_TRY(launch_gemv(u16(w.w_down), nullptr, m, delta_m, B, H, F, s));
+        else
+            ST_TRY(projection_mfma(c, w.w_down, nullptr, mb, delta_m, nullptr, B, H, F));
+        ST_TRY(prof_end(c, PSV_OP_DOWN));
+
+        ST_TRY(comm_window(c, l, 1, batch, le, &side_used));
+        res = y;
+        delta = delta_m;
     }
+    HIP_TRY(launch_add_rmsnorm(res, delta, nullptr, d.rms_eps, B, H, x_out, nullptr, nullptr, s));
     if (side_used) {   // the side stream rejoins, so that the next step cannot overtake this one's prefetches
         HIP_TRY(hipEventRecord(c->ev_end, c->side));
         HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));
@@ -518,7 +585,8 @@ psv_status psv_get_stats(psv_ctx *c, psv_stats *out)
     out->kv_bytes_per_layer = (uint64_t)batch * context * c->d.n_kv_heads * c->d.head_dim * 2 * 2;
     for (const psv_plan_entry &e : c->plan) out->planned_prefetch_bytes += e.bytes;
     out->workspace_bytes = c->ws.total;
-    out->kernels_per_layer = 9 + (c->window_us[0] > 0.f ? 1 : 0) + (c->window_us[1] > 0.f ? 1 : 0);
+    const bool vec = batch <= 4 && c->d.hidden <= 8192 && c->d.ffn <= 8192;
+    out->kernels_per_layer = (vec ? 5 : 7) + (c->window_us[0] > 0.f ? 1 : 0) + (c->window_us[1] > 0.f ? 1 : 0);
     out->prefetch_launches = c->last_prefetch_launches;
     out->steps = c->steps;
     return PSV_OK;

@@ -19,30 +19,9 @@ constexpr int kAttnWaves = 4;
 
 struct AttnSplit {
     int chunk_tokens;   // tokens per workgroup
-    int n_chunks;       // workgroups along the sequence (grid.x)
-    int n_splits;       // partial results per (sequence, kv head) = n_chunks * kAttnWaves
+    int n_chunks;       // workgroups along the sequence (grid.x) = partial results per (sequence, kv head)
 };
 AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq);
-
-// ---- kernel launchers ---------------------------------------------------------------------
-
-// out_res = res + delta (delta may be null); if gain != null: h = out_res * rsqrt(mean(out_res^2)
-// + eps) * gain, written as fp32 (h_f32) and bf16 (h_bf16, row stride H).  One workgroup per row.
-hipError_t launch_add_rmsnorm(const float *res, const float *delta, const uint16_t *gain, float eps,
-                              int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
-                              hipStream_t s);
-
-// Vector-ALU GEMV for batch <= 4:  out[b][r] = sum_k W[r][k] * x[b][k]   (fp32 x, bf16 W).
-// W2 != null selects the SwiGLU form: out[b][r] = silu(W[r].x[b]) * (W2[r].x[b]); out_bf16
-// (optional, row stride N) receives the rounded result as well.
-hipError_t launch_gemv(const uint16_t *W, const uint16_t *W2, const float *x, float *out,
-                       uint16_t *out_bf16, int batch, int N, int K, hipStream_t s);
-bool gemv_supported(int batch, int N, int K);
-
-// MFMA skinny GEMM for any batch: same contract, x given as bf16 [round_up(batch,16)][K].
-hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_t *x_bf16, float *out,
-                            uint16_t *out_bf16, int batch, int N, int K, hipStream_t s);
-bool gemm_mfma_supported(int batch, int N, int K);
 
 struct KvView {
     uint16_t *k_pool;
@@ -53,26 +32,56 @@ struct KvView {
     const int32_t *seq_lens;
 };
 
-// Rotary embedding of q and k at position seq_len-1, q -> bf16 [batch][nq][128]; k, v of the new
-// token rounded to bf16 and stored in slot seq_len-1 of the pools.
-hipError_t launch_rope_append(const float *qkv, const double *inv_freq, KvView kv, int batch, int nq,
-                              int nkv, uint16_t *q_bf16, hipStream_t s);
+// ---- kernel launchers ---------------------------------------------------------------------
 
-// Split-K decode attention: partial (max, sum, weighted V) per wave, then a fixed-order combine.
-hipError_t launch_attn_partial(const uint16_t *q_bf16, KvView kv, int batch, int nq, int nkv,
-                               AttnSplit split, float *part_ml, float *part_o, hipStream_t s);
-hipError_t launch_attn_combine(const float *part_ml, const float *part_o, int batch, int nq, int nkv,
-                               AttnSplit split, float *out_f32, uint16_t *out_bf16, hipStream_t s);
+// out_res = res + delta (delta may be null); if gain != null: h = out_res * rsqrt(mean(out_res^2)
+// + eps) * gain, written as fp32 (h_f32) and bf16 (h_bf16, row stride H).  One workgroup per row.
+hipError_t launch_add_rmsnorm(const float *res, const float *delta, const uint16_t *gain, float eps,
+                              int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
+                              hipStream_t s);
+
+// Vector-ALU GEMV for batch <= 4:  out[b][r] = sum_k W[r][k] * x[b][k]   (fp32 x, bf16 W).
+// W2 != null selects the SwiGLU form: out[b][r] = silu(W[r].x[b]) * (W2[r].x[b]).
+hipError_t launch_gemv(const uint16_t *W, const uint16_t *W2, const float *x, float *out, int batch, int N, int K,
+                       hipStream_t s);
+// Same with the activations formed in the prologue: x = rmsnorm(res + delta) * gain.  out_res
+// receives res + delta and out_h (optional) the normalised vector; neither may alias res or delta.
+hipError_t launch_gemv_norm(const uint16_t *W, const uint16_t *W2, const float *res, const float *delta,
+                            const uint16_t *gain, float eps, float *out_res, float *out_h, float *out, int batch,
+                            int N, int K, hipStream_t s);
+bool gemv_supported(int batch, int N, int K);
+
+// MFMA skinny GEMM for any batch: same contract, x given as bf16 [round_up(batch,16)][K].
+hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_t *x_bf16, float *out,
+                            uint16_t *out_bf16, int batch, int N, int K, hipStream_t s);
+bool gemm_mfma_supported(int batch, int N, int K);
+
+// cos/sin of the rotary angles at position seq_len-1: table [batch][64] (inv_freq null => identity).
+hipError_t launch_rope_table(const int32_t *seq_lens, const double *inv_freq, int max_tokens, int batch,
+                             float2 *table, hipStream_t s);
+
+// Decode attention with RoPE, KV append, split-K partials and the final merge in one launch.
+// counters: [batch][nkv] uint32, zero before the first launch (the kernel leaves them zero).
+hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batch, int nq, int nkv, AttnSplit sp,
+                       float *part_ml, float *part_o, unsigned *counters, float *out_f32, uint16_t *out_bf16,
+                       hipStream_t s);
 
 // Communication stand-in: one workgroup busy-waits `ticks` of the constant-rate wall clock.
 hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, hipStream_t s);
 
-// Prefetch: read [ptr, ptr+bytes) with `workgroups` workgroups, write nothing.
+// Prefetch: everything one communication window pulls towards the cache, in one launch.
+constexpr int kPrefetchRegions = 6;
+struct PrefetchJob {
+    const void *ptr[kPrefetchRegions];   // linear regions (projection weights), 16-byte aligned
+    uint64_t n16[kPrefetchRegions];      // their sizes in 16-byte words
+    int n_regions;
+    int nkv;
+    KvView kv;                           // KV range: logical blocks [kv_first, kv_first + kv_count) of the
+    uint32_t blocks_per_seq;             //   flattened (sequence, block) order, blocks_per_seq per sequence
+    uint64_t kv_first, kv_count;
+};
+hipError_t launch_prefetch_job(const PrefetchJob &j, uint32_t workgroups, hipStream_t s);
 hipError_t launch_prefetch(const void *ptr, uint64_t bytes, uint32_t workgroups, hipStream_t s);
-// Prefetch logical KV blocks [first, first+count) of the flattened (sequence, block) order, where
-// sequence b owns blocks_per_seq logical blocks; walks the page table.
-hipError_t launch_prefetch_kv(KvView kv, int nkv, uint32_t blocks_per_seq, uint64_t first,
-                              uint64_t count, uint32_t workgroups, hipStream_t s);
 
 hipError_t launch_copy(void *dst, const void *src, uint64_t bytes, hipStream_t s);
 

@@ -111,122 +111,265 @@ hipError_t launch_add_rmsnorm(const float *res, const float *delta, const uint16
 
 // ------------------------------------------------------------------------------------ GEMV
 
-// Weight-streaming GEMV on the vector ALU (batch NB <= 4).  A wave owns R output rows at a time
-// and walks them along K in 1 KiB steps (64 lanes x 16 bytes, fully coalesced); U steps are
-// issued back to back so that U*R (2*U*R with SwiGLU) 16-byte loads are in flight per lane.  The
-// activations sit in LDS as fp32.  A 64-lane butterfly finishes each row; no atomics, fixed order.
-template <int NB, int R, bool SWIGLU>
-__global__ __launch_bounds__(256) void k_gemv(const uint16_t *__restrict__ W, const uint16_t *__restrict__ W2,
-                                              const float *__restrict__ x, float *__restrict__ out,
-                                              uint16_t *__restrict__ out_bf16, int N, int K)
+// Weight-streaming GEMV on the vector ALU (batch NB <= 4).
+//
+// A workgroup has 512 threads, cut into groups of GS = 64..512 threads such that one 16-byte load
+// per thread covers a whole weight row (K <= 8*GS; ITERS = 2 loads for K up to 8192).  A thread
+// therefore always sees the same k positions, and its slice of the activations lives in registers
+// for the whole kernel: no LDS staging, no re-reads.  Every group owns a contiguous, balanced
+// range of output rows and streams them RB rows at a time, i.e. RB (2*RB with SwiGLU) independent
+// 16-byte loads in flight per thread, issued before anything else the kernel does.  Row sums are
+// finished with a 64-lane butterfly and, for GS > 64, a fixed-order sum over the group's waves
+// through LDS (no atomics; bit-reproducible).
+//
+// FUSE_NORM: the activations are produced in the prologue as rmsnorm(res + delta) * gain, while the
+// first weight loads are in flight; workgroup 0 also stores the new residual (res + delta) and the
+// normalised vector.  This removes the separate normalisation launch from the layer.
+struct GemvArgs {
+    const uint16_t *W, *W2;     // W2 != null: SwiGLU pair (gate, up)
+    const float *x;             // [NB][K] activations (plain mode)
+    const float *res, *delta;   // FUSE_NORM inputs, [NB][K]; delta may be null
+    const uint16_t *gain;       // FUSE_NORM: [K]
+    float eps;
+    float *out_res;             // FUSE_NORM: res + delta, written by workgroup 0 (must not alias res/delta)
+    float *out_h;               // FUSE_NORM: normalised activations, written by workgroup 0 (may be null)
+    float *out;                 // [NB][N]
+    int N, K, gs_log2, passes;
+};
+
+template <int NB, int RB, int ITERS, bool SWIGLU, bool FUSE_NORM>
+__global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
 {
-    constexpr int U = 4;
     constexpr int NW = SWIGLU ? 2 : 1;
-    extern __shared__ float xs[];   // [NB][K]
-    const int tid = threadIdx.x;
-    for (int i = tid * 4; i < NB * K; i += 1024)
-        *reinterpret_cast<float4 *>(xs + i) = *reinterpret_cast<const float4 *>(x + i);
-    __syncthreads();
+    __shared__ float red[8][NW * RB * NB];   // [wave][value]
+    __shared__ float ssq[8][NB];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int GS = 1 << a.gs_log2, groups = 512 >> a.gs_log2, wpg = GS >> 6;
+    const int gid = tid >> a.gs_log2, lg = tid & (GS - 1), gw = wave & (wpg - 1);
+    const int K = a.K, N = a.N;
+    const int slots = gridDim.x * groups, slot = blockIdx.x * groups + gid;
+    const int row_begin = (int)((long long)slot * N / slots), row_end = (int)((long long)(slot + 1) * N / slots);
 
-    const int lane = tid & 63;
-    const int gw = blockIdx.x * 4 + (tid >> 6);
-    const int nw = gridDim.x * 4;
-    for (int row0 = gw * R; row0 < N; row0 += nw * R) {
-        float acc[NW][R][NB];
+    int kk[ITERS];
+    bool kok[ITERS];
 #pragma unroll
-        for (int a = 0; a < NW; ++a)
-#pragma unroll
-            for (int r = 0; r < R; ++r)
-#pragma unroll
-                for (int b = 0; b < NB; ++b) acc[a][r][b] = 0.f;
+    for (int it = 0; it < ITERS; ++it) {
+        kk[it] = (it * GS + lg) * 8;
+        kok[it] = kk[it] < K;
+    }
 
-        for (int k0 = lane * 8; k0 < K; k0 += 512 * U) {
-            uint4 wv[U][NW][R];
+    uint4 wv[ITERS][NW][RB];
+    auto load_rows = [&](int r0) {
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int kk = k0 + u * 512;
-                const bool ok = kk < K;
+        for (int it = 0; it < ITERS; ++it)
 #pragma unroll
-                for (int r = 0; r < R; ++r) {
-                    wv[u][0][r] = ok ? ld16(W + (size_t)(row0 + r) * K + kk) : zero16();
-                    if (SWIGLU) wv[u][NW - 1][r] = ok ? ld16(W2 + (size_t)(row0 + r) * K + kk) : zero16();
-                }
+            for (int r = 0; r < RB; ++r) {
+                const bool ok = kok[it] && (r0 + r < row_end);
+                wv[it][0][r] = ok ? ld16(a.W + (size_t)(r0 + r) * K + kk[it]) : zero16();
+                if (SWIGLU) wv[it][NW - 1][r] = ok ? ld16(a.W2 + (size_t)(r0 + r) * K + kk[it]) : zero16();
             }
+    };
+    int r0 = row_begin;
+    load_rows(r0);   // weights first: everything below overlaps with their flight time
+
+    // ---- activations into registers
+    float xv[ITERS][NB][8];
+    if (FUSE_NORM) {
+        uint4 gv[ITERS];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int kk = k0 + u * 512;
-                if (kk < K) {
+        for (int it = 0; it < ITERS; ++it) gv[it] = kok[it] ? ld16(a.gain + kk[it]) : zero16();
+        float ss[NB];
 #pragma unroll
-                    for (int b = 0; b < NB; ++b) {
-                        float xv[8];
-                        float4 x0 = *reinterpret_cast<const float4 *>(xs + b * K + kk);
-                        float4 x1 = *reinterpret_cast<const float4 *>(xs + b * K + kk + 4);
-                        xv[0] = x0.x; xv[1] = x0.y; xv[2] = x0.z; xv[3] = x0.w;
-                        xv[4] = x1.x; xv[5] = x1.y; xv[6] = x1.z; xv[7] = x1.w;
+        for (int b = 0; b < NB; ++b) {
+            ss[b] = 0.f;
 #pragma unroll
-                        for (int a = 0; a < NW; ++a)
+            for (int it = 0; it < ITERS; ++it) {
+                float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+                if (kok[it]) {
+                    v0 = *reinterpret_cast<const float4 *>(a.res + (size_t)b * K + kk[it]);
+                    v1 = *reinterpret_cast<const float4 *>(a.res + (size_t)b * K + kk[it] + 4);
+                    if (a.delta) {
+                        float4 d0 = *reinterpret_cast<const float4 *>(a.delta + (size_t)b * K + kk[it]);
+                        float4 d1 = *reinterpret_cast<const float4 *>(a.delta + (size_t)b * K + kk[it] + 4);
+                        v0.x += d0.x; v0.y += d0.y; v0.z += d0.z; v0.w += d0.w;
+                        v1.x += d1.x; v1.y += d1.y; v1.z += d1.z; v1.w += d1.w;
+                    }
+                    if (blockIdx.x == 0 && gid == 0) {
+                        *reinterpret_cast<float4 *>(a.out_res + (size_t)b * K + kk[it]) = v0;
+                        *reinterpret_cast<float4 *>(a.out_res + (size_t)b * K + kk[it] + 4) = v1;
+                    }
+                }
+                float *x = xv[it][b];
+                x[0] = v0.x; x[1] = v0.y; x[2] = v0.z; x[3] = v0.w;
+                x[4] = v1.x; x[5] = v1.y; x[6] = v1.z; x[7] = v1.w;
 #pragma unroll
-                            for (int r = 0; r < R; ++r) acc[a][r][b] = dot8(wv[u][a][r], xv, acc[a][r][b]);
+                for (int e = 0; e < 8; ++e) ss[b] += x[e] * x[e];
+            }
+            ss[b] = wave_sum(ss[b]);
+        }
+        if (lane == 0)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) ssq[wave][b] = ss[b];
+        __syncthreads();
+#pragma unroll
+        for (int b = 0; b < NB; ++b) {
+            float tot = 0.f;
+            for (int w2 = 0; w2 < wpg; ++w2) tot += ssq[gid * wpg + w2][b];   // fixed order
+            const float inv = 1.0f / sqrtf(tot / (float)K + a.eps);
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                float *x = xv[it][b];
+                if (kok[it]) {
+                    const uint4 g = gv[it];
+                    x[0] *= inv * bf16_lo(g.x); x[1] *= inv * bf16_hi(g.x);
+                    x[2] *= inv * bf16_lo(g.y); x[3] *= inv * bf16_hi(g.y);
+                    x[4] *= inv * bf16_lo(g.z); x[5] *= inv * bf16_hi(g.z);
+                    x[6] *= inv * bf16_lo(g.w); x[7] *= inv * bf16_hi(g.w);
+                    if (a.out_h && blockIdx.x == 0 && gid == 0) {
+                        *reinterpret_cast<float4 *>(a.out_h + (size_t)b * K + kk[it]) = make_float4(x[0], x[1], x[2], x[3]);
+                        *reinterpret_cast<float4 *>(a.out_h + (size_t)b * K + kk[it] + 4) = make_float4(x[4], x[5], x[6], x[7]);
                     }
                 }
             }
         }
+    } else {
 #pragma unroll
-        for (int r = 0; r < R; ++r)
+        for (int b = 0; b < NB; ++b)
 #pragma unroll
-            for (int b = 0; b < NB; ++b) {
-                float v = wave_sum(acc[0][r][b]);
-                if (SWIGLU) {
-                    float u = wave_sum(acc[NW - 1][r][b]);
-                    v = silu_mul(v, u);
+            for (int it = 0; it < ITERS; ++it) {
+                float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
+                if (kok[it]) {
+                    v0 = *reinterpret_cast<const float4 *>(a.x + (size_t)b * K + kk[it]);
+                    v1 = *reinterpret_cast<const float4 *>(a.x + (size_t)b * K + kk[it] + 4);
                 }
-                if (lane == 0) {
-                    out[(size_t)b * N + row0 + r] = v;
-                    if (out_bf16) out_bf16[(size_t)b * N + row0 + r] = (uint16_t)f32_to_bf16(v);
-                }
+                float *x = xv[it][b];
+                x[0] = v0.x; x[1] = v0.y; x[2] = v0.z; x[3] = v0.w;
+                x[4] = v1.x; x[5] = v1.y; x[6] = v1.z; x[7] = v1.w;
             }
     }
+
+    // ---- stream the rows.  `passes` is the same for every group of the launch, so the barriers match.
+    for (int pass = 0; pass < a.passes; ++pass) {
+        float acc[NW][RB][NB];
+#pragma unroll
+        for (int q = 0; q < NW; ++q)
+#pragma unroll
+            for (int r = 0; r < RB; ++r)
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    float s = 0.f;
+#pragma unroll
+                    for (int it = 0; it < ITERS; ++it) s = dot8(wv[it][q][r], xv[it][b], s);
+                    acc[q][r][b] = wave_sum(s);
+                }
+        const int rows_here = r0;
+        r0 += RB;
+        if (pass + 1 < a.passes) load_rows(r0);   // next pass's loads fly during the reduction below
+
+        if (wpg == 1) {
+            if (lane == 0)
+#pragma unroll
+                for (int r = 0; r < RB; ++r)
+                    if (rows_here + r < row_end)
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) {
+                            float v = acc[0][r][b];
+                            if (SWIGLU) v = silu_mul(v, acc[NW - 1][r][b]);
+                            a.out[(size_t)b * N + rows_here + r] = v;
+                        }
+        } else {
+            if (lane == 0)
+#pragma unroll
+                for (int q = 0; q < NW; ++q)
+#pragma unroll
+                    for (int r = 0; r < RB; ++r)
+#pragma unroll
+                        for (int b = 0; b < NB; ++b) red[wave][(q * RB + r) * NB + b] = acc[q][r][b];
+            __syncthreads();
+            if (lg < RB * NB) {
+                const int r = lg / NB, b = lg % NB;
+                if (rows_here + r < row_end) {
+                    float v = 0.f, u = 0.f;
+                    for (int w2 = 0; w2 < wpg; ++w2) {   // fixed order
+                        v += red[gid * wpg + w2][r * NB + b];
+                        if (SWIGLU) u += red[gid * wpg + w2][(RB + r) * NB + b];
+                    }
+                    if (SWIGLU) v = silu_mul(v, u);
+                    a.out[(size_t)b * N + rows_here + r] = v;
+                }
+            }
+            __syncthreads();
+        }
+    }
+    (void)gw;
 }
 
 bool gemv_supported(int batch, int N, int K)
 {
-    return batch >= 1 && batch <= 4 && K % 256 == 0 && N % 2 == 0 && (size_t)batch * K * 4 <= 64 * 1024;
+    return batch >= 1 && batch <= 4 && K % 8 == 0 && K >= 64 && K <= 8192 && N >= 1;
 }
 
-template <int NB, int R, bool SW>
-static hipError_t gemv_go(const uint16_t *W, const uint16_t *W2, const float *x, float *out,
-                          uint16_t *out_bf16, int N, int K, int blocks, hipStream_t s)
+template <int NB, int ITERS, bool SW, bool FN>
+static hipError_t gemv_go(GemvArgs a, hipStream_t s)
 {
-    hipLaunchKernelGGL((k_gemv<NB, R, SW>), dim3(blocks), dim3(256), (size_t)NB * K * sizeof(float), s, W, W2,
-                       x, out, out_bf16, N, K);
+    constexpr int RB = SW ? 4 : 8;
+    int gs_log2 = 6;
+    while ((8 << gs_log2) * ITERS < a.K && gs_log2 < 9) ++gs_log2;
+    const int groups = 512 >> gs_log2;
+    // enough workgroups that a group gets at most RB rows per pass and the grid is a multiple of the
+    // 256 CUs (2 workgroups fit on a CU); rows are dealt to the groups in balanced contiguous ranges.
+    long long want = ((long long)a.N + (long long)RB * groups - 1) / ((long long)RB * groups);
+    long long blocks = (want + 255) / 256 * 256;
+    if (blocks < 256) blocks = 256;
+    if (blocks > 1024) blocks = 1024;
+    const long long slots = blocks * groups;
+    const long long max_rows = (a.N + slots - 1) / slots;
+    a.gs_log2 = gs_log2;
+    a.passes = (int)((max_rows + RB - 1) / RB);
+    if (a.passes < 1) a.passes = 1;
+    hipLaunchKernelGGL((k_gemv<NB, RB, ITERS, SW, FN>), dim3((unsigned)blocks), dim3(512), 0, s, a);
     return hipGetLastError();
 }
 
 template <int NB>
-static hipError_t gemv_pick(const uint16_t *W, const uint16_t *W2, const float *x, float *out,
-                            uint16_t *out_bf16, int N, int K, hipStream_t s)
+static hipError_t gemv_pick(const GemvArgs &a, hipStream_t s)
 {
-    // Two rows per wave once there are enough rows to give every one of 2048 waves work.
-    const bool sw = W2 != nullptr;
-    const int R = (!sw && N >= 4096) ? 2 : 1;
-    int waves = N / R;
-    int blocks = (waves + 3) / 4;
-    if (blocks > 1024) blocks = 1024;
-    if (sw) return gemv_go<NB, 1, true>(W, W2, x, out, out_bf16, N, K, blocks, s);
-    if (R == 2) return gemv_go<NB, 2, false>(W, W2, x, out, out_bf16, N, K, blocks, s);
-    return gemv_go<NB, 1, false>(W, W2, x, out, out_bf16, N, K, blocks, s);
+    const bool sw = a.W2 != nullptr, fn = a.res != nullptr, two = a.K > 4096;
+    if (two) {
+        if (sw) return fn ? gemv_go<NB, 2, true, true>(a, s) : gemv_go<NB, 2, true, false>(a, s);
+        return fn ? gemv_go<NB, 2, false, true>(a, s) : gemv_go<NB, 2, false, false>(a, s);
+    }
+    if (sw) return fn ? gemv_go<NB, 1, true, true>(a, s) : gemv_go<NB, 1, true, false>(a, s);
+    return fn ? gemv_go<NB, 1, false, true>(a, s) : gemv_go<NB, 1, false, false>(a, s);
 }
 
-hipError_t launch_gemv(const uint16_t *W, const uint16_t *W2, const float *x, float *out,
-                       uint16_t *out_bf16, int batch, int N, int K, hipStream_t s)
+static hipError_t gemv_dispatch(const GemvArgs &a, int batch, hipStream_t s)
 {
     switch (batch) {
-    case 1: return gemv_pick<1>(W, W2, x, out, out_bf16, N, K, s);
-    case 2: return gemv_pick<2>(W, W2, x, out, out_bf16, N, K, s);
-    case 3: return gemv_pick<3>(W, W2, x, out, out_bf16, N, K, s);
-    case 4: return gemv_pick<4>(W, W2, x, out, out_bf16, N, K, s);
+    case 1: return gemv_pick<1>(a, s);
+    case 2: return gemv_pick<2>(a, s);
+    case 3: return gemv_pick<3>(a, s);
+    case 4: return gemv_pick<4>(a, s);
     default: return hipErrorInvalidValue;
     }
+}
+
+hipError_t launch_gemv(const uint16_t *W, const uint16_t *W2, const float *x, float *out, int batch, int N, int K,
+                       hipStream_t s)
+{
+    GemvArgs a{};
+    a.W = W; a.W2 = W2; a.x = x; a.out = out; a.N = N; a.K = K;
+    return gemv_dispatch(a, batch, s);
+}
+
+hipError_t launch_gemv_norm(const uint16_t *W, const uint16_t *W2, const float *res, const float *delta,
+                            const uint16_t *gain, float eps, float *out_res, float *out_h, float *out, int batch,
+                            int N, int K, hipStream_t s)
+{
+    GemvArgs a{};
+    a.W = W; a.W2 = W2; a.res = res; a.delta = delta; a.gain = gain; a.eps = eps; a.out_res = out_res; a.out_h = out_h;
+    a.out = out; a.N = N; a.K = K;
+    return gemv_dispatch(a, batch, s);
 }
 
 // ------------------------------------------------------------------------------------ MFMA skinny GEMM
@@ -355,53 +498,30 @@ __device__ __forceinline__ int kv_phys_block(const int32_t *page_table, int max_
     return (blk >= 0 && blk < num_pool_blocks) ? blk : -1;   // a corrupt entry is skipped, never followed
 }
 
-// ------------------------------------------------------------------------------------ RoPE + append
+// ------------------------------------------------------------------------------------ RoPE table
 
-// grid (nq + nkv, batch), 64 threads: thread i rotates the pair (i, i+64) of one head.  Angles are
-// formed in double (position * theta^(-2i/128)) so that long contexts lose nothing to fp32 range
-// reduction.  q heads go to a bf16 staging buffer; k heads (rotated) and the matching v heads are
-// rounded to bf16 and stored in slot seq_len-1 of the pools.
-__global__ __launch_bounds__(64) void k_rope_append(const float *__restrict__ qkv, const double *__restrict__ inv_freq,
-                                                    KvView kv, int nq, int nkv, uint16_t *__restrict__ q_bf16)
+// cos/sin of the rotary angles at position seq_len-1, one row of 64 pairs per sequence.  The angle
+// is formed and reduced in double (position * theta^(-2i/128)), so long contexts lose nothing to
+// fp32 range reduction.  The position is the same for every layer, so this runs once per step.
+__global__ __launch_bounds__(64) void k_rope_table(const int32_t *__restrict__ seq_lens, const double *__restrict__ inv_freq,
+                                                   int max_tokens, float2 *__restrict__ table)
 {
-    const int hh = blockIdx.x, b = blockIdx.y, i = threadIdx.x;
-    const int qkv_rows = (nq + 2 * nkv) * 128;
-    int T = kv.seq_lens[b];
-    if (T < 1 || T > kv.max_blocks * 16) return;
-    const int pos = T - 1;
-    float c = 1.f, sn = 0.f;
+    const int b = blockIdx.x, i = threadIdx.x;
+    int T = seq_lens[b];
+    if (T < 1 || T > max_tokens) T = 1;
+    float2 cs = make_float2(1.f, 0.f);
     if (inv_freq) {
         double sd, cd;
-        sincos((double)pos * inv_freq[i], &sd, &cd);
-        c = (float)cd;
-        sn = (float)sd;
+        sincos((double)(T - 1) * inv_freq[i], &sd, &cd);
+        cs = make_float2((float)cd, (float)sd);
     }
-    const float *row = qkv + (size_t)b * qkv_rows + (size_t)hh * 128;
-    const float a = row[i], bb = row[i + 64];
-    const float ra = a * c - bb * sn, rb = bb * c + a * sn;
-    if (hh < nq) {
-        uint16_t *q = q_bf16 + ((size_t)b * nq + hh) * 128;
-        q[i] = (uint16_t)f32_to_bf16(ra);
-        q[i + 64] = (uint16_t)f32_to_bf16(rb);
-        return;
-    }
-    const int kvh = hh - nq;
-    const int blk = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, pos >> 4);
-    if (blk < 0) return;
-    const int r = pos & 15;
-    uint16_t *kdst = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + r) * 128;
-    kdst[i] = (uint16_t)f32_to_bf16(ra);
-    kdst[i + 64] = (uint16_t)f32_to_bf16(rb);
-    const float *vrow = qkv + (size_t)b * qkv_rows + (size_t)(nq + nkv + kvh) * 128;
-    uint16_t *vdst = kv.v_pool + ((size_t)blk * nkv + kvh) * 128 * 16 + r;
-    vdst[(size_t)i * 16] = (uint16_t)f32_to_bf16(vrow[i]);
-    vdst[(size_t)(i + 64) * 16] = (uint16_t)f32_to_bf16(vrow[i + 64]);
+    table[b * 64 + i] = cs;
 }
 
-hipError_t launch_rope_append(const float *qkv, const double *inv_freq, KvView kv, int batch, int nq,
-                              int nkv, uint16_t *q_bf16, hipStream_t s)
+hipError_t launch_rope_table(const int32_t *seq_lens, const double *inv_freq, int max_tokens, int batch, float2 *table,
+                             hipStream_t s)
 {
-    hipLaunchKernelGGL(k_rope_append, dim3(nq + nkv, batch), dim3(64), 0, s, qkv, inv_freq, kv, nq, nkv, q_bf16);
+    hipLaunchKernelGGL(k_rope_table, dim3(batch), dim3(64), 0, s, seq_lens, inv_freq, max_tokens, table);
     return hipGetLastError();
 }
 
@@ -417,39 +537,106 @@ AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq)
     sp.chunk_tokens = (int)(per_wave * kAttnTileTokens * kAttnWaves);
     sp.n_chunks = (int)((max_seq + sp.chunk_tokens - 1) / sp.chunk_tokens);
     if (sp.n_chunks < 1) sp.n_chunks = 1;
-    sp.n_splits = sp.n_chunks * kAttnWaves;
     return sp;
 }
 
-// Split-K decode attention, grouped-query aware.  grid (chunks, kv heads, batch), 4 waves; wave w
-// of chunk c takes the 32-token tiles c*chunk + (w + 4*it)*32.  All G <= 16 query heads that share
-// the kv head ride in the N side of the MFMAs, so K and V are read from HBM exactly once.
+struct AttnArgs {
+    const float *qkv;          // [batch][(nq+2nkv)*128] projection output, not yet rotated
+    const float2 *rope;        // [batch][64] (cos, sin)
+    KvView kv;
+    int nq, nkv, chunk_tokens, n_chunks;
+    float *part_ml;            // [batch][nkv][n_chunks][16][2]
+    float *part_o;             // [batch][nkv][n_chunks][G][128]
+    unsigned *counters;        // [batch][nkv], zero between launches
+    float *out_f32;            // [batch][nq*128]
+    uint16_t *out_bf16;        // same, rounded (operand of the MFMA O projection)
+};
+
+// Split-K decode attention with everything around it fused in.  grid (chunks, kv heads, batch),
+// 4 waves; wave w of chunk c takes the 32-token tiles c*chunk + (w + 4*it)*32.
 //
-//   S^T[token][g]  = K[token][:] . Q[g][:]      A = K rows (token-major in the pool)
-//   O^T[chan][g]  += V^T[chan][token] P[g][token]   A = V^T rows (channel-major in the pool)
-//
-// Tile 1 of a 32-token group covers tokens {8q+0..3}, tile 2 tokens {8q+4..7} (q = 0..3), so that
-// after the two S^T MFMAs lane (g, q) holds the scores of the 8 consecutive tokens 8q..8q+7 of its
-// query head: exactly the B-fragment the O^T MFMA needs.  Probabilities never leave registers.
-__global__ __launch_bounds__(256) void k_attn_partial(const uint16_t *__restrict__ q_bf16, KvView kv, int nq, int nkv,
-                                                      int chunk_tokens, int n_splits,
-                                                      float *__restrict__ part_ml, float *__restrict__ part_o)
+//  * prologue: the G <= 16 query heads sharing the kv head are rotated (RoPE) straight into MFMA
+//    B-fragments; the workgroup whose chunk holds token T-1 also rotates the new key, rounds key and
+//    value to bf16 and appends them to the cache before it reads its tiles.
+//  * main loop: all G heads ride in the N side of the MFMAs, so K and V are read from HBM once.
+//        S^T[token][g]  = K[token][:] . Q[g][:]          A = K rows (token-major in the pool)
+//        O^T[chan][g]  += V^T[chan][token] P[g][token]   A = V^T rows (channel-major in the pool)
+//    Tile 1 of a 32-token group covers tokens {8q+0..3}, tile 2 tokens {8q+4..7} (q = 0..3), so after
+//    the two S^T MFMAs lane (g, q) holds the scores of the 8 consecutive tokens 8q..8q+7 of its head:
+//    exactly the B-fragment the O^T MFMA needs.  Probabilities never leave registers.
+//  * epilogue: the 4 waves merge through LDS, the workgroup stores one partial (max, sum, O), and
+//    the last workgroup of a (sequence, kv head) to finish -- found with a ticket counter -- merges
+//    all partials in chunk order.  The order of every sum is fixed, so results are reproducible.
+__global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 {
+    __shared__ float ms[kAttnWaves][16], ls[kAttnWaves][16];
+    __shared__ f32x4 accs[kAttnWaves][8][64];
+    __shared__ unsigned ticket;
+
     const int b = blockIdx.z, kvh = blockIdx.y, c = blockIdx.x;
-    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63, i = lane & 15, q4 = lane >> 4;
-    const int G = nq / nkv;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, q4 = lane >> 4;
+    const int nq = a.nq, nkv = a.nkv, G = nq / nkv;
+    const KvView &kv = a.kv;
+    const int qkv_rows = (nq + 2 * nkv) * 128;
     int T = kv.seq_lens[b];
     if (T < 0 || T > kv.max_blocks * 16) T = 0;
-    const int t_begin = c * chunk_tokens;
-    const int t_end = min(T, t_begin + chunk_tokens);
+    const int t_begin = c * a.chunk_tokens;
+    const int t_end = min(T, t_begin + a.chunk_tokens);
     const int n_valid_blocks = (T + 15) >> 4;
+    const float *qkv_b = a.qkv + (size_t)b * qkv_rows;
+    const float2 *rope_b = a.rope + b * 64;
 
+    // ---- append the new token's K and V (one workgroup per kv head does it)
+    if (T >= 1 && c == (T - 1) / a.chunk_tokens) {
+        if (tid < 64) {
+            const int pos = T - 1;
+            const int blk = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, pos >> 4);
+            if (blk >= 0) {
+                const float2 cs = rope_b[tid];
+                const float *krow = qkv_b + (size_t)(nq + kvh) * 128;
+                const float *vrow = qkv_b + (size_t)(nq + nkv + kvh) * 128;
+                const float lo = krow[tid], hi = krow[tid + 64];
+                const int r = pos & 15;
+                uint16_t *kdst = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + r) * 128;
+                kdst[tid] = (uint16_t)f32_to_bf16(lo * cs.x - hi * cs.y);
+                kdst[tid + 64] = (uint16_t)f32_to_bf16(hi * cs.x + lo * cs.y);
+                uint16_t *vdst = kv.v_pool + ((size_t)blk * nkv + kvh) * 128 * 16 + r;
+                vdst[(size_t)tid * 16] = (uint16_t)f32_to_bf16(vrow[tid]);
+                vdst[(size_t)(tid + 64) * 16] = (uint16_t)f32_to_bf16(vrow[tid + 64]);
+            }
+            __threadfence();
+        }
+        __syncthreads();   // uniform: the condition depends on the workgroup only
+    }
+
+    // ---- Q fragments, rotated: lane (g = i, q4) holds channels ks*32 + q4*8 + e; channel f < 64
+    //      pairs with f + 64, i.e. fragment ks with fragment ks + 2 of the same lane.
     bf16x8 qf[4];
+    {
+        uint4 z = zero16();
+        qf[0] = qf[1] = qf[2] = qf[3] = __builtin_bit_cast(bf16x8, z);
+        if (i < G) {
+            const float *qrow = qkv_b + (size_t)(kvh * G + i) * 128;
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) {
-        uint4 v = zero16();
-        if (i < G) v = ld16(q_bf16 + ((size_t)b * nq + kvh * G + i) * 128 + ks * 32 + q4 * 8);
-        qf[ks] = __builtin_bit_cast(bf16x8, v);
+            for (int ks = 0; ks < 2; ++ks) {
+                const int f0 = ks * 32 + q4 * 8;
+                float lo[8], hi[8], rl[8], rh[8];
+                *reinterpret_cast<float4 *>(lo) = *reinterpret_cast<const float4 *>(qrow + f0);
+                *reinterpret_cast<float4 *>(lo + 4) = *reinterpret_cast<const float4 *>(qrow + f0 + 4);
+                *reinterpret_cast<float4 *>(hi) = *reinterpret_cast<const float4 *>(qrow + f0 + 64);
+                *reinterpret_cast<float4 *>(hi + 4) = *reinterpret_cast<const float4 *>(qrow + f0 + 68);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float2 cs = rope_b[f0 + e];
+                    rl[e] = lo[e] * cs.x - hi[e] * cs.y;
+                    rh[e] = hi[e] * cs.x + lo[e] * cs.y;
+                }
+                uint4 pl = make_uint4(pack_bf16(rl[0], rl[1]), pack_bf16(rl[2], rl[3]), pack_bf16(rl[4], rl[5]), pack_bf16(rl[6], rl[7]));
+                uint4 ph = make_uint4(pack_bf16(rh[0], rh[1]), pack_bf16(rh[2], rh[3]), pack_bf16(rh[4], rh[5]), pack_bf16(rh[6], rh[7]));
+                qf[ks] = __builtin_bit_cast(bf16x8, pl);
+                qf[ks + 2] = __builtin_bit_cast(bf16x8, ph);
+            }
+        }
     }
 
     const float kScale = 0.08838834764831845f * 1.4426950408889634f;   // 1/sqrt(128) * log2(e)
@@ -548,62 +735,70 @@ __global__ __launch_bounds__(256) void k_attn_partial(const uint16_t *__restrict
             acc[dg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dg]), pfrag, acc[dg], 0, 0, 0);
     }
 
+    // ---- merge the 4 waves (wave order)
     l_part += __shfl_xor(l_part, 16, 64);
     l_part += __shfl_xor(l_part, 32, 64);
-
-    if (i < G) {
-        const int sp = c * kAttnWaves + w;
-        const size_t slot = ((size_t)b * nkv + kvh) * n_splits + sp;
-        if (q4 == 0) {
-            part_ml[(slot * 16 + i) * 2 + 0] = m_run;
-            part_ml[(slot * 16 + i) * 2 + 1] = l_part;
-        }
-        float *o = part_o + (slot * G + i) * 128 + 4 * q4;
+    if (q4 == 0) ms[w][i] = m_run;
+    __syncthreads();
+    const float M = fmaxf(fmaxf(ms[0][i], ms[1][i]), fmaxf(ms[2][i], ms[3][i]));
+    const float sc = exp2f(m_run - M);
+    if (q4 == 0) ls[w][i] = l_part * sc;
 #pragma unroll
-        for (int dg = 0; dg < 8; ++dg)
-            *reinterpret_cast<float4 *>(o + dg * 16) = make_float4(acc[dg][0], acc[dg][1], acc[dg][2], acc[dg][3]);
-    }
-}
-
-hipError_t launch_attn_partial(const uint16_t *q_bf16, KvView kv, int batch, int nq, int nkv, AttnSplit sp,
-                               float *part_ml, float *part_o, hipStream_t s)
-{
-    hipLaunchKernelGGL(k_attn_partial, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, q_bf16, kv, nq, nkv,
-                       sp.chunk_tokens, sp.n_splits, part_ml, part_o);
-    return hipGetLastError();
-}
-
-// Fixed-order combine of the per-wave partials: grid (nq, batch), 128 threads = 128 channels.
-__global__ __launch_bounds__(128) void k_attn_combine(const float *__restrict__ part_ml, const float *__restrict__ part_o,
-                                                      int nq, int nkv, int n_splits, float *__restrict__ out_f32,
-                                                      uint16_t *__restrict__ out_bf16)
-{
-    const int h = blockIdx.x, b = blockIdx.y, ch = threadIdx.x;
-    const int G = nq / nkv, kvh = h / G, g = h % G;
-    const size_t slot0 = ((size_t)b * nkv + kvh) * n_splits;
-    float M = -1.0e30f;
-    for (int sp = 0; sp < n_splits; ++sp) M = fmaxf(M, part_ml[((slot0 + sp) * 16 + g) * 2]);
-    float den = 0.f, num = 0.f;
-    for (int sp = 0; sp < n_splits; ++sp) {
-        const float m = part_ml[((slot0 + sp) * 16 + g) * 2];
-        const float l = part_ml[((slot0 + sp) * 16 + g) * 2 + 1];
-        if (l > 0.f) {
-            const float wgt = exp2f(m - M);
-            den += wgt * l;
-            num += wgt * part_o[((slot0 + sp) * G + g) * 128 + ch];
+    for (int dg = 0; dg < 8; ++dg) accs[w][dg][lane] = acc[dg] * sc;
+    __syncthreads();
+    const size_t slot0 = ((size_t)b * nkv + kvh) * a.n_chunks;
+    if (i < G) {
+        const size_t slot = slot0 + c;
+        if (w == 0 && q4 == 0) {
+            a.part_ml[(slot * 16 + i) * 2 + 0] = M;
+            a.part_ml[(slot * 16 + i) * 2 + 1] = ls[0][i] + ls[1][i] + ls[2][i] + ls[3][i];
+        }
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            const int dg = 2 * w + d;
+            f32x4 v = accs[0][dg][lane];
+            v += accs[1][dg][lane];
+            v += accs[2][dg][lane];
+            v += accs[3][dg][lane];
+            *reinterpret_cast<float4 *>(a.part_o + (slot * G + i) * 128 + dg * 16 + 4 * q4) = make_float4(v[0], v[1], v[2], v[3]);
         }
     }
-    const float o = den > 0.f ? num / den : 0.f;
-    const size_t idx = ((size_t)b * nq + h) * 128 + ch;
-    out_f32[idx] = o;
-    out_bf16[idx] = (uint16_t)f32_to_bf16(o);
+
+    // ---- the last workgroup of this (sequence, kv head) merges all chunks, in chunk order
+    __threadfence();
+    __syncthreads();
+    if (tid == 0) ticket = atomicAdd(&a.counters[b * nkv + kvh], 1u);
+    __syncthreads();
+    if (ticket != (unsigned)(a.n_chunks - 1)) return;
+    if (tid == 0) a.counters[b * nkv + kvh] = 0u;   // ready for the next launch
+    __threadfence();
+    const int ch = tid & 127;
+    for (int g = tid >> 7; g < G; g += 2) {
+        float Mx = -1.0e30f;
+        for (int sp = 0; sp < a.n_chunks; ++sp) Mx = fmaxf(Mx, a.part_ml[((slot0 + sp) * 16 + g) * 2]);
+        float den = 0.f, num = 0.f;
+#pragma unroll 4
+        for (int sp = 0; sp < a.n_chunks; ++sp) {
+            const float m = a.part_ml[((slot0 + sp) * 16 + g) * 2];
+            const float l = a.part_ml[((slot0 + sp) * 16 + g) * 2 + 1];
+            const float o = a.part_o[((slot0 + sp) * G + g) * 128 + ch];
+            const float wgt = l > 0.f ? exp2f(m - Mx) : 0.f;
+            den += wgt * l;
+            num += wgt * o;
+        }
+        const float o = den > 0.f ? num / den : 0.f;
+        const size_t idx = ((size_t)b * nq + kvh * G + g) * 128 + ch;
+        a.out_f32[idx] = o;
+        a.out_bf16[idx] = (uint16_t)f32_to_bf16(o);
+    }
 }
 
-hipError_t launch_attn_combine(const float *part_ml, const float *part_o, int batch, int nq, int nkv, AttnSplit sp,
-                               float *out_f32, uint16_t *out_bf16, hipStream_t s)
+hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batch, int nq, int nkv, AttnSplit sp,
+                       float *part_ml, float *part_o, unsigned *counters, float *out_f32, uint16_t *out_bf16,
+                       hipStream_t s)
 {
-    hipLaunchKernelGGL(k_attn_combine, dim3(nq, batch), dim3(128), 0, s, part_ml, part_o, nq, nkv, sp.n_splits,
-                       out_f32, out_bf16);
+    AttnArgs a{qkv, rope, kv, nq, nkv, sp.chunk_tokens, sp.n_chunks, part_ml, part_o, counters, out_f32, out_bf16};
+    hipLaunchKernelGGL(k_attn, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -629,72 +824,70 @@ hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, hipStream_t s)
 
 // ------------------------------------------------------------------------------------ prefetch
 
-// Reads a region with 16-byte loads and throws the data away: the loads allocate the lines in the
-// memory-side cache (and in the L2 of the XCD that ran the workgroup).  Nothing is written.
-__global__ __launch_bounds__(256) void k_prefetch(const uint4 *__restrict__ p, uint64_t n16)
+// Reads memory with 16-byte loads and throws the data away: the loads allocate the lines in the
+// memory-side cache (Infinity Cache).  Nothing is written.  One launch serves a whole communication
+// window: up to kPrefetchRegions linear regions (projection weights) plus a range of KV blocks that
+// is walked through the page table.  The grid size is the CU budget of the policy.
+__device__ __forceinline__ uint32_t fold(uint4 v) { return v.x ^ v.y ^ v.z ^ v.w; }
+
+__global__ __launch_bounds__(256) void k_prefetch(PrefetchJob j)
 {
     constexpr int U = 8;
     const uint64_t stride = (uint64_t)gridDim.x * 256;
+    const uint64_t me = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     uint32_t sink = 0;
-    uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    for (; i + (U - 1) * stride < n16; i += U * stride) {
-        uint4 v[U];
+    for (int r = 0; r < j.n_regions; ++r) {
+        const uint4 *p = reinterpret_cast<const uint4 *>(j.ptr[r]);
+        const uint64_t n16 = j.n16[r];
+        uint64_t i = me;
+        for (; i + (U - 1) * stride < n16; i += U * stride) {
+            uint4 v[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) v[u] = p[i + u * stride];
+            for (int u = 0; u < U; ++u) v[u] = p[i + u * stride];
 #pragma unroll
-        for (int u = 0; u < U; ++u) sink ^= v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+            for (int u = 0; u < U; ++u) sink ^= fold(v[u]);
+        }
+        for (; i < n16; i += stride) sink ^= fold(p[i]);
     }
-    for (; i < n16; i += stride) {
-        uint4 v = p[i];
-        sink ^= v.x ^ v.y ^ v.z ^ v.w;
+    if (j.kv_count) {
+        // one wave per logical block: K part and V part of every kv head (4 KiB each per head)
+        const int lane = threadIdx.x & 63;
+        const uint64_t gw = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+        const uint64_t nw = (uint64_t)gridDim.x * 4;
+        const uint32_t per_block16 = (uint32_t)j.nkv * 256;   // 16-byte words per pool block
+        for (uint64_t q = gw; q < j.kv_count; q += nw) {
+            const uint64_t lin = j.kv_first + q;
+            const int b = (int)(lin / j.blocks_per_seq), lb = (int)(lin % j.blocks_per_seq);
+            if (lb >= j.kv.max_blocks) continue;
+            const int blk = kv_phys_block(j.kv.page_table, j.kv.max_blocks, j.kv.num_pool_blocks, b, lb);
+            if (blk < 0) continue;
+            const uint4 *kp = reinterpret_cast<const uint4 *>(j.kv.k_pool) + (size_t)blk * per_block16;
+            const uint4 *vp = reinterpret_cast<const uint4 *>(j.kv.v_pool) + (size_t)blk * per_block16;
+            for (uint32_t o = lane; o < per_block16; o += 256) {   // per_block16 is a multiple of 256
+                uint4 a0 = kp[o], a1 = kp[o + 64], a2 = kp[o + 128], a3 = kp[o + 192];
+                uint4 b0 = vp[o], b1 = vp[o + 64], b2 = vp[o + 128], b3 = vp[o + 192];
+                sink ^= fold(a0) ^ fold(a1) ^ fold(a2) ^ fold(a3) ^ fold(b0) ^ fold(b1) ^ fold(b2) ^ fold(b3);
+            }
+        }
     }
     asm volatile("" ::"v"(sink));   // keeps the loads alive without a store
 }
 
+hipError_t launch_prefetch_job(const PrefetchJob &j, uint32_t workgroups, hipStream_t s)
+{
+    if (workgroups == 0 || (j.n_regions == 0 && j.kv_count == 0)) return hipSuccess;
+    hipLaunchKernelGGL(k_prefetch, dim3(workgroups), dim3(256), 0, s, j);
+    return hipGetLastError();
+}
+
 hipError_t launch_prefetch(const void *ptr, uint64_t bytes, uint32_t workgroups, hipStream_t s)
 {
-    if (bytes < 16 || workgroups == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_prefetch, dim3(workgroups), dim3(256), 0, s, reinterpret_cast<const uint4 *>(ptr), bytes / 16);
-    return hipGetLastError();
-}
-
-// KV prefetch: one wave per logical block (K part and V part of every kv head, 4 KiB each per head).
-__global__ __launch_bounds__(256) void k_prefetch_kv(KvView kv, int nkv, uint32_t blocks_per_seq, uint64_t first,
-                                                     uint64_t count)
-{
-    const int lane = threadIdx.x & 63;
-    const uint64_t gw = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    const uint64_t nw = (uint64_t)gridDim.x * 4;
-    const uint32_t per_block16 = (uint32_t)nkv * 16 * 128 * 2 / 16;   // 16-byte words per pool block
-    uint32_t sink = 0;
-    for (uint64_t j = gw; j < count; j += nw) {
-        const uint64_t lin = first + j;
-        const int b = (int)(lin / blocks_per_seq), lb = (int)(lin % blocks_per_seq);
-        if (lb >= kv.max_blocks) continue;
-        const int blk = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb);
-        if (blk < 0) continue;
-        const uint4 *kp = reinterpret_cast<const uint4 *>(kv.k_pool) + (size_t)blk * per_block16;
-        const uint4 *vp = reinterpret_cast<const uint4 *>(kv.v_pool) + (size_t)blk * per_block16;
-        for (uint32_t o = lane; o < per_block16; o += 256) {
-            uint4 a0 = kp[o], a1 = (o + 64 < per_block16) ? kp[o + 64] : zero16();
-            uint4 a2 = (o + 128 < per_block16) ? kp[o + 128] : zero16(), a3 = (o + 192 < per_block16) ? kp[o + 192] : zero16();
-            uint4 b0 = vp[o], b1 = (o + 64 < per_block16) ? vp[o + 64] : zero16();
-            uint4 b2 = (o + 128 < per_block16) ? vp[o + 128] : zero16(), b3 = (o + 192 < per_block16) ? vp[o + 192] : zero16();
-            sink ^= a0.x ^ a1.x ^ a2.x ^ a3.x ^ b0.x ^ b1.x ^ b2.x ^ b3.x;
-            sink ^= a0.y ^ a1.y ^ a2.y ^ a3.y ^ b0.y ^ b1.y ^ b2.y ^ b3.y;
-            sink ^= a0.z ^ a1.z ^ a2.z ^ a3.z ^ b0.z ^ b1.z ^ b2.z ^ b3.z;
-            sink ^= a0.w ^ a1.w ^ a2.w ^ a3.w ^ b0.w ^ b1.w ^ b2.w ^ b3.w;
-        }
-    }
-    asm volatile("" ::"v"(sink));
-}
-
-hipError_t launch_prefetch_kv(KvView kv, int nkv, uint32_t blocks_per_seq, uint64_t first, uint64_t count,
-                              uint32_t workgroups, hipStream_t s)
-{
-    if (count == 0 || workgroups == 0) return hipSuccess;
-    hipLaunchKernelGGL(k_prefetch_kv, dim3(workgroups), dim3(256), 0, s, kv, nkv, blocks_per_seq, first, count);
-    return hipGetLastError();
+    if (bytes < 16) return hipSuccess;
+    PrefetchJob j{};
+    j.n_regions = 1;
+    j.ptr[0] = ptr;
+    j.n16[0] = bytes / 16;
+    return launch_prefetch_job(j, workgroups, s);
 }
 
 // ------------------------------------------------------------------------------------ copy (counter calibration)
