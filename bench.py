@@ -30,11 +30,11 @@ def parse():
     ap.add_argument("--layers", type=int, default=0, help="materialise only the first N layers (0 = all)")
     ap.add_argument("--budget-mb", type=float, default=64.0, help="Algorithm 1's capacity C")
     ap.add_argument("--chunk-mb", type=float, default=0.0)
-    ap.add_argument("--cu-budget", type=int, default=64)
+    ap.add_argument("--cu-budget", type=int, default=256)
     ap.add_argument("--partial", type=int, default=0)
     ap.add_argument("--join", type=int, default=0)
     ap.add_argument("--targets", type=int, default=3)
-    ap.add_argument("--graph", type=int, default=1, help="replay the step as a HIP graph")
+    ap.add_argument("--graph", type=int, default=0, help="1 = replay the step as a HIP graph")
     ap.add_argument("--window-us", type=float, nargs=2, default=None)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = auto)")

@@ -24,7 +24,7 @@ struct Workspace {
     size_t total = 0;
     // offsets
     size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, rope, counters, part_ml, part_o, attn_f32, attn_bf16,
-        delta_a, delta_m, m_f32, m_bf16, inv_freq;
+        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag;
 };
 
 Workspace layout_workspace(const psv_model_desc &d)
@@ -39,21 +39,22 @@ Workspace layout_workspace(const psv_model_desc &d)
     w.x = take(B * H * 4);
     w.y = take(B * H * 4);
     w.h1_f32 = take(B * H * 4);
-    w.h1_bf16 = take(Bp * H * 2);
+    w.h1_bf16 = take(2 * Bp * H * 2);
     w.h2_f32 = take(B * H * 4);
-    w.h2_bf16 = take(Bp * H * 2);
+    w.h2_bf16 = take(2 * Bp * H * 2);
     w.qkv = take(B * QR * 4);
     w.rope = take(B * 64 * 2 * 4);
     w.counters = take(B * d.n_kv_heads * 4);
     w.part_ml = take(B * d.n_kv_heads * (size_t)sp.n_chunks * 16 * 2 * 4);
     w.part_o = take(B * d.n_kv_heads * (size_t)sp.n_chunks * G * 128 * 4);
     w.attn_f32 = take(B * QD * 4);
-    w.attn_bf16 = take(Bp * QD * 2);
+    w.attn_bf16 = take(2 * Bp * QD * 2);
     w.delta_a = take(B * H * 4);
     w.delta_m = take(B * H * 4);
     w.m_f32 = take(B * F * 4);
-    w.m_bf16 = take(Bp * F * 2);
+    w.m_bf16 = take(2 * Bp * F * 2);
     w.inv_freq = take(64 * sizeof(double));
+    w.flag = take(256);
     w.total = off;
     return w;
 }
@@ -98,6 +99,7 @@ struct psv_ctx {
     size_t prof_used = 0;
     uint32_t steps = 0;
     uint32_t last_prefetch_launches = 0;
+    unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
     bool capturing = false;
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(wsp + off); }
@@ -189,6 +191,8 @@ const void *weight_ptr(const psv_layer_weights &w, uint32_t op)
 struct JobBuilder {
     psv_ctx *c;
     uint64_t cap;        // bytes per launch (0 = unlimited)
+    const unsigned *flag;   // device-side fork (null: the caller orders the side stream with an event)
+    unsigned seq;
     uint64_t used = 0;
     PrefetchJob job{};
     psv_status st = PSV_OK;
@@ -198,6 +202,10 @@ struct JobBuilder {
         if (st != PSV_OK) return;
         if (job.n_regions || job.kv_count) {
             const uint32_t wg = c->policy.cu_budget ? c->policy.cu_budget : 64u;
+            job.flag = flag;
+            job.seq = seq;
+            job.wait_iters = 1u << 20;
+            job.wait_ticks = c->clock_khz * 20;    // 20 ms
             if (launch_prefetch_job(job, wg, c->side) != hipSuccess) st = PSV_ERR_HIP;
             ++c->last_prefetch_launches;
         }
@@ -260,8 +268,8 @@ psv_status add_entry(psv_ctx *c, JobBuilder &jb, const psv_plan_entry &e, uint32
 }
 
 // The communication window after the attention block (window 0) or the MLP block (window 1).  The
-// fork event is recorded before the stand-in for the collective, so the prefetch starts with the
-// window; the stand-in is enqueued first so that the main stream never waits for the host.
+// stand-in for the collective is enqueued first, so that the main stream never waits for the host;
+// the window's prefetch job goes to the side stream and starts when the window starts.
 psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t batch, uint32_t layer_end, bool *side_used)
 {
     const float us = c->window_us[window];
@@ -270,14 +278,18 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
     if (c->policy.mode == 1)
         for (const psv_plan_entry &e : c->plan)
             if (e.layer == layer && e.window == window && e.target_layer < layer_end) { any = true; break; }
+    // Eager launches fork on the device: the window kernel publishes a sequence number that the prefetch
+    // job, already queued on the side stream, waits for.  Under graph capture the fork is an event edge.
+    unsigned *flag = c->capturing ? nullptr : c->at<unsigned>(c->ws.flag);
+    const unsigned seq = ++c->window_seq;
     hipEvent_t ev = c->ev_fork[layer * 2 + window];
-    if (any) HIP_TRY(hipEventRecord(ev, c->main));
-    HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), c->main));
+    if (any && !flag) HIP_TRY(hipEventRecord(ev, c->main));
+    HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), flag, seq, c->main));
     if (!any) return PSV_OK;
-    HIP_TRY(hipStreamWaitEvent(c->side, ev, 0));
+    if (!flag) HIP_TRY(hipStreamWaitEvent(c->side, ev, 0));
     uint64_t cap = c->policy.chunk_bytes & ~(uint64_t)15;
     if (c->policy.chunk_bytes && cap < 16) cap = 16;
-    JobBuilder jb{c, cap};
+    JobBuilder jb{c, cap, flag, seq};
     for (const psv_plan_entry &e : c->plan) {
         if (e.layer != layer || e.window != window || e.target_layer >= layer_end) continue;
         psv_status st = add_entry(c, jb, e, batch);
@@ -319,6 +331,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     bool side_used = false;
     c->last_prefetch_launches = 0;
     auto u16 = [](const void *p) { return static_cast<const uint16_t *>(p); };
+    const size_t plane_h = (size_t)((B + 15) / 16 * 16) * H;   // hi -> lo plane distance of the bf16 activations
 
     // Small batches run every projection on the vector ALU with the normalisation fused into the
     // prologue; larger ones use the matrix cores with a separate normalisation kernel.
@@ -330,7 +343,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         const psv_layer_weights &w = c->weights[l];
         const KvView kv = kv_view(c, l);
 
-        if (!vec) HIP_TRY(launch_add_rmsnorm(res, delta, u16(w.g_attn), d.rms_eps, B, H, x, h1, h1b, s));
+        if (!vec) HIP_TRY(launch_add_rmsnorm(res, delta, u16(w.g_attn), d.rms_eps, B, H, x, h1, h1b, plane_h, s));
         ST_TRY(prof_begin(c, PSV_OP_QKV));
         if (vec)
             HIP_TRY(launch_gemv_norm(u16(w.w_qkv), nullptr, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H, s));
@@ -351,7 +364,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
 
         ST_TRY(comm_window(c, l, 0, batch, le, &side_used));
 
-        if (!vec) HIP_TRY(launch_add_rmsnorm(x, delta_a, u16(w.g_mlp), d.rms_eps, B, H, y, h2, h2b, s));
+        if (!vec) HIP_TRY(launch_add_rmsnorm(x, delta_a, u16(w.g_mlp), d.rms_eps, B, H, y, h2, h2b, plane_h, s));
         ST_TRY(prof_begin(c, PSV_OP_GATE));
         if (vec)
             HIP_TRY(launch_gemv_norm(u16(w.w_gate), u16(w.w_up), x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H, s));
@@ -370,8 +383,8 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         res = y;
         delta = delta_m;
     }
-    HIP_TRY(launch_add_rmsnorm(res, delta, nullptr, d.rms_eps, B, H, x_out, nullptr, nullptr, s));
-    if (side_used) {   // the side stream rejoins, so that the next step cannot overtake this one's prefetches
+    HIP_TRY(launch_add_rmsnorm(res, delta, nullptr, d.rms_eps, B, H, x_out, nullptr, nullptr, 0, s));
+    if (side_used && c->capturing) {   // a captured side branch has to rejoin the origin stream
         HIP_TRY(hipEventRecord(c->ev_end, c->side));
         HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));
     }
@@ -636,7 +649,7 @@ psv_status psv_spin(float us, void *stream)
 {
     if (!(us >= 0.f) || us > 1.0e6f) return PSV_ERR_INVALID_ARG;
     if (us == 0.f) return PSV_OK;
-    HIP_TRY(launch_spin(us_to_ticks(current_clock_khz(), us), spin_cap(us), static_cast<hipStream_t>(stream)));
+    HIP_TRY(launch_spin(us_to_ticks(current_clock_khz(), us), spin_cap(us), nullptr, 0, static_cast<hipStream_t>(stream)));
     return PSV_OK;
 }
 

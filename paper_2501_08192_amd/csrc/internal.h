@@ -16,6 +16,7 @@ namespace psv {
 // workgroup's chunk is a multiple of 128 tokens.  Every wave writes its own partial result.
 constexpr int kAttnTileTokens = 32;
 constexpr int kAttnWaves = 4;
+constexpr int kAttnMaxChunks = 256;
 
 struct AttnSplit {
     int chunk_tokens;   // tokens per workgroup
@@ -35,10 +36,11 @@ struct KvView {
 // ---- kernel launchers ---------------------------------------------------------------------
 
 // out_res = res + delta (delta may be null); if gain != null: h = out_res * rsqrt(mean(out_res^2)
-// + eps) * gain, written as fp32 (h_f32) and bf16 (h_bf16, row stride H).  One workgroup per row.
+// + eps) * gain, written as fp32 (h_f32) and as hi/lo bf16 planes (h_bf16, row stride H, lo plane
+// plane_stride elements after the hi plane).  One workgroup per row.
 hipError_t launch_add_rmsnorm(const float *res, const float *delta, const uint16_t *gain, float eps,
                               int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
-                              hipStream_t s);
+                              size_t plane_stride, hipStream_t s);
 
 // Vector-ALU GEMV for batch <= 4:  out[b][r] = sum_k W[r][k] * x[b][k]   (fp32 x, bf16 W).
 // W2 != null selects the SwiGLU form: out[b][r] = silu(W[r].x[b]) * (W2[r].x[b]).
@@ -51,7 +53,8 @@ hipError_t launch_gemv_norm(const uint16_t *W, const uint16_t *W2, const float *
                             int N, int K, hipStream_t s);
 bool gemv_supported(int batch, int N, int K);
 
-// MFMA skinny GEMM for any batch: same contract, x given as bf16 [round_up(batch,16)][K].
+// MFMA skinny GEMM for any batch: same contract, x given as two bf16 planes (x = hi + lo), each
+// [round_up(batch,16)][K], lo directly after hi; out_bf16 (optional) is written in the same form.
 hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_t *x_bf16, float *out,
                             uint16_t *out_bf16, int batch, int N, int K, hipStream_t s);
 bool gemm_mfma_supported(int batch, int N, int K);
@@ -67,7 +70,8 @@ hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batc
                        hipStream_t s);
 
 // Communication stand-in: one workgroup busy-waits `ticks` of the constant-rate wall clock.
-hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, hipStream_t s);
+// `flag` (optional): the kernel stores `seq` there on entry, which releases the prefetch job of this window.
+hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned seq, hipStream_t s);
 
 // Prefetch: everything one communication window pulls towards the cache, in one launch.
 constexpr int kPrefetchRegions = 6;
@@ -79,6 +83,10 @@ struct PrefetchJob {
     KvView kv;                           // KV range: logical blocks [kv_first, kv_first + kv_count) of the
     uint32_t blocks_per_seq;             //   flattened (sequence, block) order, blocks_per_seq per sequence
     uint64_t kv_first, kv_count;
+    const unsigned *flag;                // optional device-side fork: start once *flag has reached seq
+    unsigned seq;
+    uint32_t wait_iters;                 // bounds of the wait (polls, wall-clock ticks)
+    uint64_t wait_ticks;
 };
 hipError_t launch_prefetch_job(const PrefetchJob &j, uint32_t workgroups, hipStream_t s);
 hipError_t launch_prefetch(const void *ptr, uint64_t bytes, uint32_t workgroups, hipStream_t s);

@@ -29,6 +29,15 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return f32_to_bf16(lo) | (f32_to_bf16(hi) << 16);
 }
 
+// Activations that feed the matrix cores are carried as two bf16 planes, x = hi + lo (+ a remainder below
+// 2^-17 |x|): one MFMA per plane restores fp32-grade accuracy at negligible cost, since the matrix cores
+// idle most of the time in a bandwidth-bound GEMM.  lo plane = hi plane + plane_stride elements.
+__device__ __forceinline__ void split_bf16(float v, uint32_t &hi, uint32_t &lo)
+{
+    hi = f32_to_bf16(v);
+    lo = f32_to_bf16(v - __uint_as_float(hi << 16));
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
@@ -57,14 +66,14 @@ __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f +
 
 // ------------------------------------------------------------------------------------ norm
 
-// out_res = res + delta; h = out_res * rsqrt(mean(out_res^2) + eps) * gain.  One workgroup per
-// batch row; the row is re-read from out_res for the second pass (each thread re-reads only what
+// out_res = res + delta; h = out_res * rsqrt(mean(out_res^2) + eps) * gain, stored as fp32 and as
+// the hi/lo bf16 planes the matrix-core GEMM reads.  One workgroup per batch row; the row is re-read from out_res for the second pass (each thread re-reads only what
 // it wrote itself).
 __global__ __launch_bounds__(256) void k_add_rmsnorm(const float *__restrict__ res,
                                                      const float *__restrict__ delta,
                                                      const uint16_t *__restrict__ gain, float eps, int H,
                                                      float *out_res, float *__restrict__ h_f32,
-                                                     uint16_t *__restrict__ h_bf16)
+                                                     uint16_t *__restrict__ h_bf16, size_t plane_stride)
 {
     __shared__ float red[4];
     const int b = blockIdx.x, tid = threadIdx.x;
@@ -95,17 +104,19 @@ __global__ __launch_bounds__(256) void k_add_rmsnorm(const float *__restrict__ r
         v.z = v.z * inv * bf16_lo(g.y);
         v.w = v.w * inv * bf16_hi(g.y);
         *reinterpret_cast<float4 *>(h_f32 + (size_t)b * H + i) = v;
-        uint2 pk = make_uint2(pack_bf16(v.x, v.y), pack_bf16(v.z, v.w));
-        *reinterpret_cast<uint2 *>(h_bf16 + (size_t)b * H + i) = pk;
+        uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+        split_bf16(v.x, h0, l0); split_bf16(v.y, h1, l1); split_bf16(v.z, h2, l2); split_bf16(v.w, h3, l3);
+        *reinterpret_cast<uint2 *>(h_bf16 + (size_t)b * H + i) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+        *reinterpret_cast<uint2 *>(h_bf16 + plane_stride + (size_t)b * H + i) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
     }
 }
 
 hipError_t launch_add_rmsnorm(const float *res, const float *delta, const uint16_t *gain, float eps,
                               int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
-                              hipStream_t s)
+                              size_t plane_stride, hipStream_t s)
 {
     hipLaunchKernelGGL(k_add_rmsnorm, dim3(batch), dim3(256), 0, s, res, delta, gain, eps, H, out_res,
-                       h_f32, h_bf16);
+                       h_f32, h_bf16, plane_stride);
     return hipGetLastError();
 }
 
@@ -385,7 +396,8 @@ __global__ __launch_bounds__(NWAVES * 64) void k_gemm_mfma(const uint16_t *__res
                                                             const uint16_t *__restrict__ W2,
                                                             const uint16_t *__restrict__ xb,
                                                             float *__restrict__ out,
-                                                            uint16_t *__restrict__ out_bf16, int batch, int N, int K)
+                                                            uint16_t *__restrict__ out_bf16, int batch, int N, int K,
+                                                            size_t x_plane, size_t out_plane)
 {
     constexpr int NW = SWIGLU ? 2 : 1;
     __shared__ f32x4 red[NWAVES][NW][NB][64];
@@ -404,7 +416,7 @@ __global__ __launch_bounds__(NWAVES * 64) void k_gemm_mfma(const uint16_t *__res
     const uint16_t *xrow = xb + (size_t)i * K + g * 16;
 
     for (int kb = w * 64; kb < K; kb += NWAVES * 64) {
-        uint4 a0[NW], a1[NW], b0[NB], b1[NB];
+        uint4 a0[NW], a1[NW], b0[NB], b1[NB], c0[NB], c1[NB];
         a0[0] = ld16(wrow + kb);
         a1[0] = ld16(wrow + kb + 8);
         if (SWIGLU) {
@@ -415,6 +427,8 @@ __global__ __launch_bounds__(NWAVES * 64) void k_gemm_mfma(const uint16_t *__res
         for (int n = 0; n < NB; ++n) {
             b0[n] = ld16(xrow + (size_t)n * 16 * K + kb);
             b1[n] = ld16(xrow + (size_t)n * 16 * K + kb + 8);
+            c0[n] = ld16(xrow + x_plane + (size_t)n * 16 * K + kb);       // lo plane
+            c1[n] = ld16(xrow + x_plane + (size_t)n * 16 * K + kb + 8);
         }
 #pragma unroll
         for (int a = 0; a < NW; ++a)
@@ -424,6 +438,10 @@ __global__ __launch_bounds__(NWAVES * 64) void k_gemm_mfma(const uint16_t *__res
                                                                     __builtin_bit_cast(bf16x8, b0[n]), acc[a][n], 0, 0, 0);
                 acc[a][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1[a]),
                                                                     __builtin_bit_cast(bf16x8, b1[n]), acc[a][n], 0, 0, 0);
+                acc[a][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0[a]),
+                                                                    __builtin_bit_cast(bf16x8, c0[n]), acc[a][n], 0, 0, 0);
+                acc[a][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1[a]),
+                                                                    __builtin_bit_cast(bf16x8, c1[n]), acc[a][n], 0, 0, 0);
             }
     }
 #pragma unroll
@@ -448,8 +466,12 @@ __global__ __launch_bounds__(NWAVES * 64) void k_gemm_mfma(const uint16_t *__res
         if (b < batch) {
             const size_t o = (size_t)b * N + row0 + 4 * g;
             *reinterpret_cast<float4 *>(out + o) = make_float4(v[0], v[1], v[2], v[3]);
-            if (out_bf16)
-                *reinterpret_cast<uint2 *>(out_bf16 + o) = make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+            if (out_bf16) {
+                uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+                split_bf16(v[0], h0, l0); split_bf16(v[1], h1, l1); split_bf16(v[2], h2, l2); split_bf16(v[3], h3, l3);
+                *reinterpret_cast<uint2 *>(out_bf16 + o) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+                *reinterpret_cast<uint2 *>(out_bf16 + out_plane + o) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+            }
         }
     }
 }
@@ -463,15 +485,17 @@ template <int NB, int NWAVES>
 static hipError_t gemm_go(const uint16_t *W, const uint16_t *W2, const uint16_t *xb, float *out,
                           uint16_t *out_bf16, int batch, int N, int K, hipStream_t s)
 {
+    const size_t x_plane = (size_t)NB * 16 * K, out_plane = (size_t)NB * 16 * N;
     if (W2)
         hipLaunchKernelGGL((k_gemm_mfma<NB, NWAVES, true>), dim3(N / 16), dim3(NWAVES * 64), 0, s, W, W2, xb, out,
-                           out_bf16, batch, N, K);
+                           out_bf16, batch, N, K, x_plane, out_plane);
     else
         hipLaunchKernelGGL((k_gemm_mfma<NB, NWAVES, false>), dim3(N / 16), dim3(NWAVES * 64), 0, s, W, W2, xb, out,
-                           out_bf16, batch, N, K);
+                           out_bf16, batch, N, K, x_plane, out_plane);
     return hipGetLastError();
 }
 
+// x_bf16 / out_bf16: hi plane [round_up(batch,16)][K or N] followed by the lo plane of the same shape.
 hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_t *xb, float *out,
                             uint16_t *out_bf16, int batch, int N, int K, hipStream_t s)
 {
@@ -534,7 +558,11 @@ AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq)
     uint64_t per_wave = (tiles + 4095) / 4096;
     if (per_wave < 1) per_wave = 1;
     AttnSplit sp;
-    sp.chunk_tokens = (int)(per_wave * kAttnTileTokens * kAttnWaves);
+    const int unit = kAttnTileTokens * kAttnWaves;
+    sp.chunk_tokens = (int)(per_wave * unit);
+    // at most kAttnMaxChunks partials per (sequence, kv head): the final merge keeps their weights in LDS
+    const int floor_chunk = (int)(((max_seq + kAttnMaxChunks - 1) / kAttnMaxChunks + unit - 1) / unit * unit);
+    if (sp.chunk_tokens < floor_chunk) sp.chunk_tokens = floor_chunk;
     sp.n_chunks = (int)((max_seq + sp.chunk_tokens - 1) / sp.chunk_tokens);
     if (sp.n_chunks < 1) sp.n_chunks = 1;
     return sp;
@@ -549,7 +577,8 @@ struct AttnArgs {
     float *part_o;             // [batch][nkv][n_chunks][G][128]
     unsigned *counters;        // [batch][nkv], zero between launches
     float *out_f32;            // [batch][nq*128]
-    uint16_t *out_bf16;        // same, rounded (operand of the MFMA O projection)
+    uint16_t *out_bf16;        // same as hi/lo bf16 planes (operand of the MFMA O projection)
+    size_t out_plane;          // distance between the planes, elements
 };
 
 // Split-K decode attention with everything around it fused in.  grid (chunks, kv heads, batch),
@@ -772,24 +801,48 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     if (ticket != (unsigned)(a.n_chunks - 1)) return;
     if (tid == 0) a.counters[b * nkv + kvh] = 0u;   // ready for the next launch
     __threadfence();
+    // weights of the chunks: every thread derives them from the (max, sum) pairs with independent loads
+    float *wl = reinterpret_cast<float *>(&accs[0][0][0]);   // LDS reuse: [G][n_chunks] weights, then [G] 1/den
+    const int nc = a.n_chunks;
+    for (int g = w; g < G; g += kAttnWaves) {
+        float Mx = -1.0e30f;
+        for (int sp = lane; sp < nc; sp += 64) Mx = fmaxf(Mx, a.part_ml[((slot0 + sp) * 16 + g) * 2]);
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) Mx = fmaxf(Mx, __shfl_xor(Mx, off, 64));
+        float den = 0.f;
+        for (int sp0 = 0; sp0 < nc; sp0 += 64) {       // chunk order: lanes ascending, then blocks of 64
+            const int sp = sp0 + lane;
+            float wgt = 0.f, l = 0.f;
+            if (sp < nc) {
+                const float m = a.part_ml[((slot0 + sp) * 16 + g) * 2];
+                l = a.part_ml[((slot0 + sp) * 16 + g) * 2 + 1];
+                wgt = l > 0.f ? exp2f(m - Mx) : 0.f;
+                wl[g * nc + sp] = wgt;
+            }
+            den += wave_sum(wgt * l);
+        }
+        if (lane == 0) wl[G * nc + g] = den > 0.f ? 1.0f / den : 0.f;
+    }
+    __syncthreads();
     const int ch = tid & 127;
     for (int g = tid >> 7; g < G; g += 2) {
-        float Mx = -1.0e30f;
-        for (int sp = 0; sp < a.n_chunks; ++sp) Mx = fmaxf(Mx, a.part_ml[((slot0 + sp) * 16 + g) * 2]);
-        float den = 0.f, num = 0.f;
-#pragma unroll 4
-        for (int sp = 0; sp < a.n_chunks; ++sp) {
-            const float m = a.part_ml[((slot0 + sp) * 16 + g) * 2];
-            const float l = a.part_ml[((slot0 + sp) * 16 + g) * 2 + 1];
-            const float o = a.part_o[((slot0 + sp) * G + g) * 128 + ch];
-            const float wgt = l > 0.f ? exp2f(m - Mx) : 0.f;
-            den += wgt * l;
-            num += wgt * o;
+        float num = 0.f;
+        int sp = 0;
+        for (; sp + 8 <= nc; sp += 8) {
+            float o[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) o[u] = a.part_o[((slot0 + sp + u) * G + g) * 128 + ch];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) num = fmaf(wl[g * nc + sp + u], o[u], num);
         }
-        const float o = den > 0.f ? num / den : 0.f;
+        for (; sp < nc; ++sp) num = fmaf(wl[g * nc + sp], a.part_o[((slot0 + sp) * G + g) * 128 + ch], num);
+        const float o = num * wl[G * nc + g];
         const size_t idx = ((size_t)b * nq + kvh * G + g) * 128 + ch;
         a.out_f32[idx] = o;
-        a.out_bf16[idx] = (uint16_t)f32_to_bf16(o);
+        uint32_t hi, lo;
+        split_bf16(o, hi, lo);
+        a.out_bf16[idx] = (uint16_t)hi;
+        a.out_bf16[a.out_plane + idx] = (uint16_t)lo;
     }
 }
 
@@ -797,7 +850,8 @@ hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batc
                        float *part_ml, float *part_o, unsigned *counters, float *out_f32, uint16_t *out_bf16,
                        hipStream_t s)
 {
-    AttnArgs a{qkv, rope, kv, nq, nkv, sp.chunk_tokens, sp.n_chunks, part_ml, part_o, counters, out_f32, out_bf16};
+    const size_t out_plane = (size_t)((batch + 15) / 16 * 16) * nq * 128;
+    AttnArgs a{qkv, rope, kv, nq, nkv, sp.chunk_tokens, sp.n_chunks, part_ml, part_o, counters, out_f32, out_bf16, out_plane};
     hipLaunchKernelGGL(k_attn, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
     return hipGetLastError();
 }
@@ -805,10 +859,13 @@ hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batc
 // ------------------------------------------------------------------------------------ spin window
 
 // One workgroup of one wave busy-waits on the constant-rate wall clock; the iteration cap makes
-// sure the wave exits even if the clock misbehaves.
-__global__ __launch_bounds__(64) void k_spin(uint64_t ticks, uint32_t max_iters)
+// sure the wave exits even if the clock misbehaves.  On entry it publishes the window's sequence
+// number: the prefetch kernel that belongs to this window is already resident on the side stream
+// and starts the moment it sees the number (a device-side fork, no host event in between).
+__global__ __launch_bounds__(64) void k_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned seq)
 {
     const uint64_t t0 = wall_clock64();
+    if (flag && threadIdx.x == 0) __hip_atomic_store(flag, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     uint32_t it = 0;
     while (wall_clock64() - t0 < ticks && it < max_iters) {
         __builtin_amdgcn_s_sleep(2);
@@ -816,9 +873,9 @@ __global__ __launch_bounds__(64) void k_spin(uint64_t ticks, uint32_t max_iters)
     }
 }
 
-hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, hipStream_t s)
+hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned seq, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_spin, dim3(1), dim3(64), 0, s, ticks, max_iters);
+    hipLaunchKernelGGL(k_spin, dim3(1), dim3(64), 0, s, ticks, max_iters, flag, seq);
     return hipGetLastError();
 }
 
@@ -833,6 +890,26 @@ __device__ __forceinline__ uint32_t fold(uint4 v) { return v.x ^ v.y ^ v.z ^ v.w
 __global__ __launch_bounds__(256) void k_prefetch(PrefetchJob j)
 {
     constexpr int U = 8;
+    if (j.flag) {
+        // Wait (bounded) until the main stream has entered the window this job belongs to.  Being early
+        // or late can never change a result -- the kernel only reads -- so the bound is just an exit
+        // guarantee.  If a later window has already begun, the data would arrive after its consumers
+        // ran: skip it.
+        __shared__ int go;
+        if (threadIdx.x == 0) {
+            const uint64_t t0 = wall_clock64();
+            unsigned v = __hip_atomic_load(j.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            uint32_t it = 0;
+            while ((int)(v - j.seq) < 0 && it < j.wait_iters && wall_clock64() - t0 < j.wait_ticks) {
+                __builtin_amdgcn_s_sleep(4);
+                v = __hip_atomic_load(j.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ++it;
+            }
+            go = (int)(v - j.seq) <= 0;
+        }
+        __syncthreads();
+        if (!go) return;
+    }
     const uint64_t stride = (uint64_t)gridDim.x * 256;
     const uint64_t me = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     uint32_t sink = 0;

@@ -1,0 +1,90 @@
+"""GPU parity at the full sizes of the five benchmark workloads, in the launch configuration bench.py times
+(eager launches, prefetch on with a 64 MiB budget and 256 workgroups).  c1 and c2 are checked over the whole
+step; c3-c5 hold 18-60 GB of weights and cache, so for them single layers are materialised at their real
+shape, run through the same entry point with a layer range, and compared output by output with the oracle.
+Tolerance: |gpu - ref| <= 2e-2 + 1e-2*|ref|; prefetch on/off must agree bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2501_08192_amd import binding as psv
+from paper_2501_08192_amd import synth
+from paper_2501_08192_amd.harness import Session
+
+pytestmark = pytest.mark.gpu
+
+ATOL, RTOL = 2e-2, 1e-2
+
+
+def bench_policy(w):
+    return psv.prefetch_policy(mode=1, budget_bytes=64 << 20, cu_budget=256, partial=1 if w.paged else 0)
+
+
+def check_layers(w, layers, seed=2501):
+    m = oracle.model(w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn, 16, w.rms_eps, w.rope_theta)
+    with Session(w, seed=seed, layers=layers) as s:
+        lens = s.seq_lens_host.numpy()
+        pt = s.page_table_host.numpy() if w.paged else None
+        x = s.x_in.cpu().numpy().astype(np.float64)
+        kv_ref = {}
+        for l in layers:
+            kp, vp = s.host_pools(l)
+            x = oracle.decode_layer(m, s.host_layer(l), kp, vp, pt, w.blocks_per_seq, lens, x)
+            kv_ref[l] = (kp, vp)
+        lb, le = layers[0], layers[-1] + 1
+        assert layers == list(range(lb, le))
+        off = s.run(layer_begin=lb, layer_end=le).clone()
+        k_off = [s.k_pools[l].clone() for l in layers]
+        s.set_policy(bench_policy(w))
+        plan = psv.psv_plan(s.ctx)
+        on = s.run(layer_begin=lb, layer_end=le).clone()
+        assert torch.equal(on, off), "prefetch on/off differ"
+        for l, k0 in zip(layers, k_off):
+            assert torch.equal(s.k_pools[l], k0)
+        got = on.cpu().numpy().astype(np.float64)
+        err = np.abs(got - x)
+        bound = ATOL + RTOL * np.abs(x)
+        assert np.isfinite(got).all()
+        assert (err <= bound).all(), "%s layers %s: max|err| %.4g, worst excess %.4g, max|ref| %.3g" % (
+            w.name, layers, err.max(), (err - bound).max(), np.abs(x).max())
+        # appended cache entries of the last layer, as values
+        l = layers[-1]
+        for got_pool, ref_pool in ((synth.bits(s.k_pools[l]), kv_ref[l][0]), (synth.bits(s.v_pools[l]), kv_ref[l][1])):
+            diff = got_pool != ref_pool
+            if diff.any():
+                g = torch.from_numpy(got_pool[diff].view(np.int16)).view(torch.bfloat16).double().numpy()
+                r = torch.from_numpy(ref_pool[diff].view(np.int16)).view(torch.bfloat16).double().numpy()
+                assert (np.abs(g - r) <= ATOL + RTOL * np.abs(r)).all()
+            assert diff.sum() <= w.batch * w.n_kv_heads * w.head_dim        # at most the new slots differ
+        return err.max(), plan
+
+
+def test_c1_whole_step():
+    w = synth.WORKLOADS["c1"]
+    check_layers(w, list(range(w.n_layers)))
+
+
+def test_c2_whole_step_32_layers():
+    w = synth.WORKLOADS["c2"]
+    err, plan = check_layers(w, list(range(w.n_layers)))
+    assert len(plan) == 6 * w.n_layers - 3          # every window prefetches its three operators; last window none
+
+
+def test_c3_first_two_layers_and_last_layer():
+    w = synth.WORKLOADS["c3"]
+    check_layers(w, [0, 1])
+    check_layers(w, [w.n_layers - 1])
+
+
+def test_c4_one_layer_paged_batch64():
+    w = synth.WORKLOADS["c4"]
+    err, plan = check_layers(w, [0, 1])
+    kv = [e for e in plan if e["target_op"] == psv.PSV_OP_ATTN]
+    assert kv and all(e["bytes"] < e["mem_size"] for e in kv)       # 256 MiB of KV: only a prefix fits the budget
+
+
+def test_c5_one_layer_paged_context_32k():
+    w = synth.WORKLOADS["c5"]
+    check_layers(w, [0])
+    check_layers(w, [w.n_layers - 1])
