@@ -593,14 +593,12 @@ struct AttnArgs {
 //    Tile 1 of a 32-token group covers tokens {8q+0..3}, tile 2 tokens {8q+4..7} (q = 0..3), so after
 //    the two S^T MFMAs lane (g, q) holds the scores of the 8 consecutive tokens 8q..8q+7 of its head:
 //    exactly the B-fragment the O^T MFMA needs.  Probabilities never leave registers.
-//  * epilogue: the 4 waves merge through LDS, the workgroup stores one partial (max, sum, O), and
-//    the last workgroup of a (sequence, kv head) to finish -- found with a ticket counter -- merges
-//    all partials in chunk order.  The order of every sum is fixed, so results are reproducible.
+//  * epilogue: the 4 waves merge through LDS and the workgroup stores one partial (max, sum, O);
+//    k_attn_merge then combines the partials of a (sequence, kv head) in chunk order.
 __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 {
     __shared__ float ms[kAttnWaves][16], ls[kAttnWaves][16];
     __shared__ f32x4 accs[kAttnWaves][8][64];
-    __shared__ unsigned ticket;
 
     const int b = blockIdx.z, kvh = blockIdx.y, c = blockIdx.x;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, q4 = lane >> 4;
@@ -793,24 +791,26 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         }
     }
 
-    // ---- the last workgroup of this (sequence, kv head) merges all chunks, in chunk order
-    __threadfence();
-    __syncthreads();
-    if (tid == 0) ticket = atomicAdd(&a.counters[b * nkv + kvh], 1u);
-    __syncthreads();
-    if (ticket != (unsigned)(a.n_chunks - 1)) return;
-    if (tid == 0) a.counters[b * nkv + kvh] = 0u;   // ready for the next launch
-    __threadfence();
-    // weights of the chunks: every thread derives them from the (max, sum) pairs with independent loads
-    float *wl = reinterpret_cast<float *>(&accs[0][0][0]);   // LDS reuse: [G][n_chunks] weights, then [G] 1/den
-    const int nc = a.n_chunks;
-    for (int g = w; g < G; g += kAttnWaves) {
+}
+
+// Merge of the chunk partials of one (sequence, kv head): grid (kv heads, batch), 1024 threads.
+// Softmax weights of the chunks are formed once (LDS), then every output channel sums its chunks
+// in chunk order; when G*128 < 1024 the chunks are dealt to several thread groups whose partial
+// sums are added in group order.  All orders are fixed, so the result is reproducible.
+__global__ __launch_bounds__(1024) void k_attn_merge(AttnArgs a)
+{
+    __shared__ float wl[16 * kAttnMaxChunks + 16];   // [G][n_chunks] weights, then [G] 1/denominator
+    __shared__ float psum[1024];
+    const int kvh = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int nq = a.nq, nkv = a.nkv, G = nq / nkv, nc = a.n_chunks;
+    const size_t slot0 = ((size_t)b * nkv + kvh) * nc;
+    for (int g = w; g < G; g += 16) {
         float Mx = -1.0e30f;
         for (int sp = lane; sp < nc; sp += 64) Mx = fmaxf(Mx, a.part_ml[((slot0 + sp) * 16 + g) * 2]);
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) Mx = fmaxf(Mx, __shfl_xor(Mx, off, 64));
         float den = 0.f;
-        for (int sp0 = 0; sp0 < nc; sp0 += 64) {       // chunk order: lanes ascending, then blocks of 64
+        for (int sp0 = 0; sp0 < nc; sp0 += 64) {
             const int sp = sp0 + lane;
             float wgt = 0.f, l = 0.f;
             if (sp < nc) {
@@ -824,25 +824,43 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         if (lane == 0) wl[G * nc + g] = den > 0.f ? 1.0f / den : 0.f;
     }
     __syncthreads();
-    const int ch = tid & 127;
-    for (int g = tid >> 7; g < G; g += 2) {
+    const int outs = G * 128;                              // 128 .. 2048
+    const int S = outs >= 1024 ? 1 : 1024 / outs;          // thread groups sharing the chunks
+    const int per = (nc + S - 1) / S;
+    for (int o0 = 0; o0 < outs; o0 += 1024) {
+        const int o = o0 + (S == 1 ? tid : tid % outs), sg = S == 1 ? 0 : tid / outs;
+        const int g = o >> 7, ch = o & 127;
         float num = 0.f;
-        int sp = 0;
-        for (; sp + 8 <= nc; sp += 8) {
-            float o[8];
+        if (o < outs) {
+            const int sp_end = min(nc, (sg + 1) * per);
+            int sp = sg * per;
+            for (; sp + 8 <= sp_end; sp += 8) {
+                float v[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) o[u] = a.part_o[((slot0 + sp + u) * G + g) * 128 + ch];
+                for (int u = 0; u < 8; ++u) v[u] = a.part_o[((slot0 + sp + u) * G + g) * 128 + ch];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) num = fmaf(wl[g * nc + sp + u], o[u], num);
+                for (int u = 0; u < 8; ++u) num = fmaf(wl[g * nc + sp + u], v[u], num);
+            }
+            for (; sp < sp_end; ++sp) num = fmaf(wl[g * nc + sp], a.part_o[((slot0 + sp) * G + g) * 128 + ch], num);
         }
-        for (; sp < nc; ++sp) num = fmaf(wl[g * nc + sp], a.part_o[((slot0 + sp) * G + g) * 128 + ch], num);
-        const float o = num * wl[G * nc + g];
-        const size_t idx = ((size_t)b * nq + kvh * G + g) * 128 + ch;
-        a.out_f32[idx] = o;
-        uint32_t hi, lo;
-        split_bf16(o, hi, lo);
-        a.out_bf16[idx] = (uint16_t)hi;
-        a.out_bf16[a.out_plane + idx] = (uint16_t)lo;
+        if (S > 1) {
+            psum[tid] = num;
+            __syncthreads();
+            if (sg == 0) {
+                num = 0.f;
+                for (int k = 0; k < S; ++k) num += psum[k * outs + o];   // group order
+            }
+            __syncthreads();
+        }
+        if (sg == 0 && o < outs) {
+            const float r = num * wl[G * nc + g];
+            const size_t idx = ((size_t)b * nq + kvh * G + g) * 128 + ch;
+            a.out_f32[idx] = r;
+            uint32_t hi, lo;
+            split_bf16(r, hi, lo);
+            a.out_bf16[idx] = (uint16_t)hi;
+            a.out_bf16[a.out_plane + idx] = (uint16_t)lo;
+        }
     }
 }
 
@@ -853,6 +871,9 @@ hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batc
     const size_t out_plane = (size_t)((batch + 15) / 16 * 16) * nq * 128;
     AttnArgs a{qkv, rope, kv, nq, nkv, sp.chunk_tokens, sp.n_chunks, part_ml, part_o, counters, out_f32, out_bf16, out_plane};
     hipLaunchKernelGGL(k_attn, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(k_attn_merge, dim3(nkv, batch), dim3(1024), 0, s, a);
     return hipGetLastError();
 }
 
