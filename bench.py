@@ -133,12 +133,26 @@ def main():
     eff_off = layer_bytes / max(1e-9, (us_off - win)) / 1e3          # GB/s outside the windows
     eff_on = layer_bytes / max(1e-9, (us_on - win)) / 1e3
 
-    # roofline of the dominant kernel (gate/up projection + SwiGLU), HBM-bound, prefetch off
-    sess.set_policy(off)
-    gate_us, gate_n = profile_op(sess, psv.PSV_OP_GATE, max(3, min(a.steps, 20)))
-    gate_bytes = 2 * w.ffn * w.hidden * 2
-    sess.set_policy(on)
-    gate_us_on, _ = profile_op(sess, psv.PSV_OP_GATE, max(3, min(a.steps, 20)))
+    # per-operator kernel durations (events attached to the kernel dispatches), prefetch off and on; the
+    # dominant kernel -- gate/up projection + SwiGLU, HBM-bound -- carries the roofline entry
+    qkv_rows = (w.n_q_heads + 2 * w.n_kv_heads) * w.head_dim
+    op_bytes = {"qkv": 2 * qkv_rows * w.hidden, "attn": stats["kv_bytes_per_layer"],
+                "o": 2 * w.hidden * w.n_q_heads * w.head_dim, "gate_up": 2 * 2 * w.ffn * w.hidden,
+                "down": 2 * w.hidden * w.ffn}
+    op_ids = {"qkv": psv.PSV_OP_QKV, "attn": psv.PSV_OP_ATTN, "o": psv.PSV_OP_O, "gate_up": psv.PSV_OP_GATE,
+              "down": psv.PSV_OP_DOWN}
+    n_prof = max(3, min(a.steps, 10))
+    kernels = {}
+    for mode_name, pol in (("off", off), ("on", on)):
+        sess.set_policy(pol)
+        for name, op in op_ids.items():
+            us, n = profile_op(sess, op, n_prof)
+            kernels.setdefault(name, {"bytes": op_bytes[name]})
+            kernels[name]["us_" + mode_name] = round(us, 3)
+            kernels[name]["gbps_" + mode_name] = round(op_bytes[name] / us / 1e3, 1)
+            kernels[name]["launches"] = n
+    gate_us, gate_us_on, gate_n = kernels["gate_up"]["us_off"], kernels["gate_up"]["us_on"], kernels["gate_up"]["launches"]
+    gate_bytes = op_bytes["gate_up"]
     achieved = gate_bytes / gate_us / 1e3
 
     out = {
@@ -175,6 +189,7 @@ def main():
                      "avg_us_prefetch_on": round(gate_us_on, 3),
                      "achieved_prefetch_on": round(gate_bytes / gate_us_on / 1e3, 1)},
     }
+    out["kernels"] = kernels
     if not a.no_cpu_baseline:
         # whole step when a layer is cheap; otherwise the first layers whose oracle cost is ~10-30 s
         n_cpu = a.cpu_layers or max(1, min(L, int(6.0e10 / max(1, (stats["weight_bytes_per_layer"] +

@@ -204,8 +204,11 @@ psv_status psv_get_stats(psv_ctx *ctx, psv_stats *out);
 
 /* ---- measurement and test aids ---------------------------------------------------------- */
 
-/* When op is a PSV_OP_* id, every later eager-mode decode step brackets each launch of that
- * operator's kernel with HIP events on stream_main; op = -1 switches it off. */
+/* When op is a PSV_OP_* id (not PSV_OP_UP: gate and up share one kernel), every later eager-mode
+ * decode step binds a HIP event to the dispatch of each main-stream kernel; the duration reported
+ * for the operator is the time from the end of the kernel launched just before it on stream_main
+ * to the end of the operator's kernel (for PSV_OP_ATTN: the split-K kernel, not the small merge
+ * that follows).  op = -1 switches it off.  Synchronises. */
 psv_status psv_set_profile_op(psv_ctx *ctx, int32_t op);
 /* After psv_sync: total milliseconds and number of bracketed launches since the last call of
  * psv_set_profile_op; resets the accumulation. */

@@ -6,9 +6,11 @@
 // (here: a spin kernel standing in for the allreduce).  Prefetch kernels only read, so the main
 // stream never has to wait for them; the side stream itself serialises consecutive windows.
 #include <math.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <new>
+#include <utility>
 #include <vector>
 
 #include "internal.h"
@@ -23,7 +25,7 @@ inline size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 struct Workspace {
     size_t total = 0;
     // offsets
-    size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, rope, counters, part_ml, part_o, attn_f32, attn_bf16,
+    size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, rope, part_ml, part_o, attn_f32, attn_bf16,
         delta_a, delta_m, m_f32, m_bf16, inv_freq, flag;
 };
 
@@ -44,7 +46,6 @@ Workspace layout_workspace(const psv_model_desc &d)
     w.h2_bf16 = take(2 * Bp * H * 2);
     w.qkv = take(B * QR * 4);
     w.rope = take(B * 64 * 2 * 4);
-    w.counters = take(B * d.n_kv_heads * 4);
     w.part_ml = take(B * d.n_kv_heads * (size_t)sp.n_chunks * 16 * 2 * 4);
     w.part_o = take(B * d.n_kv_heads * (size_t)sp.n_chunks * G * 128 * 4);
     w.attn_f32 = take(B * QD * 4);
@@ -95,8 +96,10 @@ struct psv_ctx {
     hipGraphExec_t graph_exec = nullptr;
     GraphKey graph_key{};
     int32_t profile_op = -1;
-    std::vector<hipEvent_t> prof_events;         // pairs (begin, end)
-    size_t prof_used = 0;
+    std::vector<hipEvent_t> prof_events;         // pool, one per profiled launch
+    size_t prof_next = 0;
+    hipEvent_t prof_last = nullptr;              // event of the previous main-stream kernel
+    std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_pairs;
     uint32_t steps = 0;
     uint32_t last_prefetch_launches = 0;
     unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
@@ -111,6 +114,12 @@ namespace {
     do {                                     \
         hipError_t e__ = (expr);             \
         if (e__ != hipSuccess) return PSV_ERR_HIP; \
+    } while (0)
+
+#define ST_TRY(expr)                      \
+    do {                                  \
+        psv_status st__ = (expr);         \
+        if (st__ != PSV_OK) return st__;  \
     } while (0)
 
 void drop_graph(psv_ctx *c)
@@ -142,25 +151,22 @@ KvView kv_view(const psv_ctx *c, uint32_t layer)
 uint64_t us_to_ticks(uint64_t clock_khz, float us) { return (uint64_t)llround((double)us * (double)clock_khz / 1000.0); }
 uint32_t spin_cap(float us) { return (uint32_t)(us * 4000.0f) + 100000u; }
 
-psv_status prof_begin(psv_ctx *c, int32_t op)
+// Per-operator timing.  While profiling is on, every main-stream kernel carries an event bound to its own
+// dispatch (its end timestamp).  The duration of an operator's kernel is the distance between its event and
+// the event of the kernel launched just before it on the same stream, i.e. the kernel's execution time plus
+// the true dispatch gap -- no marker packets in between, which would add ~2 us each.
+psv_status prof_tag(psv_ctx *c, int32_t op)
 {
-    if (c->capturing || c->profile_op != op) return PSV_OK;
-    if (c->prof_used + 2 > c->prof_events.size()) {
-        for (int k = 0; k < 2; ++k) {
-            hipEvent_t e;
-            HIP_TRY(hipEventCreate(&e));
-            c->prof_events.push_back(e);
-        }
+    if (c->capturing || c->profile_op < 0) return PSV_OK;
+    if (c->prof_next == c->prof_events.size()) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreate(&e));
+        c->prof_events.push_back(e);
     }
-    HIP_TRY(hipEventRecord(c->prof_events[c->prof_used], c->main));
-    return PSV_OK;
-}
-
-psv_status prof_end(psv_ctx *c, int32_t op)
-{
-    if (c->capturing || c->profile_op != op) return PSV_OK;
-    HIP_TRY(hipEventRecord(c->prof_events[c->prof_used + 1], c->main));
-    c->prof_used += 2;
+    hipEvent_t ev = c->prof_events[c->prof_next++];
+    set_launch_events(nullptr, ev);
+    if (op == c->profile_op && c->prof_last) c->prof_pairs.push_back({c->prof_last, ev});
+    c->prof_last = ev;
     return PSV_OK;
 }
 
@@ -191,8 +197,7 @@ const void *weight_ptr(const psv_layer_weights &w, uint32_t op)
 struct JobBuilder {
     psv_ctx *c;
     uint64_t cap;        // bytes per launch (0 = unlimited)
-    const unsigned *flag;   // device-side fork (null: the caller orders the side stream with an event)
-    unsigned seq;
+    const unsigned *skip;   // word written by the gate kernel of this window (null under graph capture)
     uint64_t used = 0;
     PrefetchJob job{};
     psv_status st = PSV_OK;
@@ -202,10 +207,7 @@ struct JobBuilder {
         if (st != PSV_OK) return;
         if (job.n_regions || job.kv_count) {
             const uint32_t wg = c->policy.cu_budget ? c->policy.cu_budget : 64u;
-            job.flag = flag;
-            job.seq = seq;
-            job.wait_iters = 1u << 20;
-            job.wait_ticks = c->clock_khz * 20;    // 20 ms
+            job.skip = skip;
             if (launch_prefetch_job(job, wg, c->side) != hipSuccess) st = PSV_ERR_HIP;
             ++c->last_prefetch_launches;
         }
@@ -278,18 +280,24 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
     if (c->policy.mode == 1)
         for (const psv_plan_entry &e : c->plan)
             if (e.layer == layer && e.window == window && e.target_layer < layer_end) { any = true; break; }
-    // Eager launches fork on the device: the window kernel publishes a sequence number that the prefetch
-    // job, already queued on the side stream, waits for.  Under graph capture the fork is an event edge.
+    // Eager launches fork on the device: the window kernel publishes a sequence number that a one-wave gate
+    // kernel, queued on the side stream ahead of the prefetch launches, waits for.  Under graph capture the
+    // fork is an event edge.
     unsigned *flag = c->capturing ? nullptr : c->at<unsigned>(c->ws.flag);
     const unsigned seq = ++c->window_seq;
     hipEvent_t ev = c->ev_fork[layer * 2 + window];
     if (any && !flag) HIP_TRY(hipEventRecord(ev, c->main));
+    ST_TRY(prof_tag(c, -2));
     HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), flag, seq, c->main));
     if (!any) return PSV_OK;
-    if (!flag) HIP_TRY(hipStreamWaitEvent(c->side, ev, 0));
+    unsigned *skip = flag ? flag + 16 : nullptr;
+    if (flag)
+        HIP_TRY(launch_gate(flag, seq, 1u << 20, c->clock_khz * 20 /* 20 ms */, skip, c->side));
+    else
+        HIP_TRY(hipStreamWaitEvent(c->side, ev, 0));
     uint64_t cap = c->policy.chunk_bytes & ~(uint64_t)15;
     if (c->policy.chunk_bytes && cap < 16) cap = 16;
-    JobBuilder jb{c, cap, flag, seq};
+    JobBuilder jb{c, cap, skip};
     for (const psv_plan_entry &e : c->plan) {
         if (e.layer != layer || e.window != window || e.target_layer >= layer_end) continue;
         psv_status st = add_entry(c, jb, e, batch);
@@ -305,12 +313,6 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
     return PSV_OK;
 }
 
-#define ST_TRY(expr)                      \
-    do {                                  \
-        psv_status st__ = (expr);         \
-        if (st__ != PSV_OK) return st__;  \
-    } while (0)
-
 psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t batch, uint32_t lb, uint32_t le)
 {
     const psv_model_desc &d = c->d;
@@ -325,7 +327,6 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     uint16_t *attnb = c->at<uint16_t>(c->ws.attn_bf16), *mb = c->at<uint16_t>(c->ws.m_bf16);
     float *pml = c->at<float>(c->ws.part_ml), *po = c->at<float>(c->ws.part_o);
     float2 *rope = c->at<float2>(c->ws.rope);
-    unsigned *counters = c->at<unsigned>(c->ws.counters);
     const double *inv_freq = d.rope_theta > 0.f ? c->at<double>(c->ws.inv_freq) : nullptr;
     hipStream_t s = c->main;
     bool side_used = false;
@@ -337,52 +338,58 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     // prologue; larger ones use the matrix cores with a separate normalisation kernel.
     const bool vec = gemv_supported(B, QR, H) && gemv_supported(B, H, QD) && gemv_supported(B, F, H) && gemv_supported(B, H, F);
 
+    ST_TRY(prof_tag(c, -2));
     HIP_TRY(launch_rope_table(c->kv.seq_lens, inv_freq, (int)c->kv.max_blocks * 16, B, rope, s));
     const float *res = x_in, *delta = nullptr;   // residual stream entering the layer = res + delta
     for (uint32_t l = lb; l < le; ++l) {
         const psv_layer_weights &w = c->weights[l];
         const KvView kv = kv_view(c, l);
 
+        if (!vec) ST_TRY(prof_tag(c, -2));
         if (!vec) HIP_TRY(launch_add_rmsnorm(res, delta, u16(w.g_attn), d.rms_eps, B, H, x, h1, h1b, plane_h, s));
-        ST_TRY(prof_begin(c, PSV_OP_QKV));
+        ST_TRY(prof_tag(c, PSV_OP_QKV));
         if (vec)
             HIP_TRY(launch_gemv_norm(u16(w.w_qkv), nullptr, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H, s));
         else
             ST_TRY(projection_mfma(c, w.w_qkv, nullptr, h1b, qkv, nullptr, B, QR, H));
-        ST_TRY(prof_end(c, PSV_OP_QKV));
 
-        ST_TRY(prof_begin(c, PSV_OP_ATTN));
-        HIP_TRY(launch_attn(qkv, rope, kv, B, nq, nkv, sp, pml, po, counters, attn, attnb, s));
-        ST_TRY(prof_end(c, PSV_OP_ATTN));
+        ST_TRY(prof_tag(c, PSV_OP_ATTN));
+        HIP_TRY(launch_attn(qkv, rope, kv, B, nq, nkv, sp, pml, po, s));
+        const bool fuse_merge = vec && gemv_merge_supported(B, nq, sp.n_chunks);
+        if (!fuse_merge) {
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_attn_merge(pml, po, B, nq, nkv, sp, attn, attnb, s));
+        }
 
-        ST_TRY(prof_begin(c, PSV_OP_O));
-        if (vec)
+        ST_TRY(prof_tag(c, PSV_OP_O));
+        if (fuse_merge)
+            HIP_TRY(launch_gemv_merge(u16(w.w_o), pml, po, nq, nkv, sp.n_chunks, attn, delta_a, B, H, s));
+        else if (vec)
             HIP_TRY(launch_gemv(u16(w.w_o), nullptr, attn, delta_a, B, H, QD, s));
         else
             ST_TRY(projection_mfma(c, w.w_o, nullptr, attnb, delta_a, nullptr, B, H, QD));
-        ST_TRY(prof_end(c, PSV_OP_O));
 
         ST_TRY(comm_window(c, l, 0, batch, le, &side_used));
 
+        if (!vec) ST_TRY(prof_tag(c, -2));
         if (!vec) HIP_TRY(launch_add_rmsnorm(x, delta_a, u16(w.g_mlp), d.rms_eps, B, H, y, h2, h2b, plane_h, s));
-        ST_TRY(prof_begin(c, PSV_OP_GATE));
+        ST_TRY(prof_tag(c, PSV_OP_GATE));
         if (vec)
             HIP_TRY(launch_gemv_norm(u16(w.w_gate), u16(w.w_up), x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H, s));
         else
             ST_TRY(projection_mfma(c, w.w_gate, w.w_up, h2b, m, mb, B, F, H));
-        ST_TRY(prof_end(c, PSV_OP_GATE));
 
-        ST_TRY(prof_begin(c, PSV_OP_DOWN));
+        ST_TRY(prof_tag(c, PSV_OP_DOWN));
         if (vec)
             HIP_TRY(launch_gemv(u16(w.w_down), nullptr, m, delta_m, B, H, F, s));
         else
             ST_TRY(projection_mfma(c, w.w_down, nullptr, mb, delta_m, nullptr, B, H, F));
-        ST_TRY(prof_end(c, PSV_OP_DOWN));
 
         ST_TRY(comm_window(c, l, 1, batch, le, &side_used));
         res = y;
         delta = delta_m;
     }
+    ST_TRY(prof_tag(c, -2));
     HIP_TRY(launch_add_rmsnorm(res, delta, nullptr, d.rms_eps, B, H, x_out, nullptr, nullptr, 0, s));
     if (side_used && c->capturing) {   // a captured side branch has to rejoin the origin stream
         HIP_TRY(hipEventRecord(c->ev_end, c->side));
@@ -608,8 +615,12 @@ psv_status psv_get_stats(psv_ctx *c, psv_stats *out)
 psv_status psv_set_profile_op(psv_ctx *c, int32_t op)
 {
     if (!c || op < -1 || op >= (int32_t)PSV_OP_COUNT || op == PSV_OP_UP) return PSV_ERR_INVALID_ARG;   // up shares gate's kernel
+    psv_status st = psv_sync(c);
+    if (st != PSV_OK) return st;
     c->profile_op = op;
-    c->prof_used = 0;
+    c->prof_next = 0;
+    c->prof_last = nullptr;
+    c->prof_pairs.clear();
     return PSV_OK;
 }
 
@@ -619,14 +630,16 @@ psv_status psv_get_profile(psv_ctx *c, double *total_ms, uint64_t *launches)
     psv_status st = psv_sync(c);
     if (st != PSV_OK) return st;
     double sum = 0.0;
-    for (size_t i = 0; i + 1 < c->prof_used; i += 2) {
+    for (const auto &pr : c->prof_pairs) {
         float ms = 0.f;
-        HIP_TRY(hipEventElapsedTime(&ms, c->prof_events[i], c->prof_events[i + 1]));
+        HIP_TRY(hipEventElapsedTime(&ms, pr.first, pr.second));
         sum += ms;
     }
     *total_ms = sum;
-    *launches = c->prof_used / 2;
-    c->prof_used = 0;
+    *launches = c->prof_pairs.size();
+    c->prof_next = 0;
+    c->prof_last = nullptr;
+    c->prof_pairs.clear();
     return PSV_OK;
 }
 

@@ -35,6 +35,9 @@ struct KvView {
 
 // ---- kernel launchers ---------------------------------------------------------------------
 
+// The next kernel launched from this thread records `start` / `stop` around its own execution.
+void set_launch_events(hipEvent_t start, hipEvent_t stop);
+
 // out_res = res + delta (delta may be null); if gain != null: h = out_res * rsqrt(mean(out_res^2)
 // + eps) * gain, written as fp32 (h_f32) and as hi/lo bf16 planes (h_bf16, row stride H, lo plane
 // plane_stride elements after the hi plane).  One workgroup per row.
@@ -52,6 +55,12 @@ hipError_t launch_gemv_norm(const uint16_t *W, const uint16_t *W2, const float *
                             const uint16_t *gain, float eps, float *out_res, float *out_h, float *out, int batch,
                             int N, int K, hipStream_t s);
 bool gemv_supported(int batch, int N, int K);
+// O projection with the attention merge in its prologue: x = merged split-K partials (K = nq*128).
+// out_attn (optional) receives the merged attention output.  Usable for few chunks only.
+constexpr int kGemvMergeMaxChunks = 32;
+bool gemv_merge_supported(int batch, int nq, int n_chunks);
+hipError_t launch_gemv_merge(const uint16_t *W, const float *part_ml, const float *part_o, int nq, int nkv,
+                             int n_chunks, float *out_attn, float *out, int batch, int N, hipStream_t s);
 
 // MFMA skinny GEMM for any batch: same contract, x given as two bf16 planes (x = hi + lo), each
 // [round_up(batch,16)][K], lo directly after hi; out_bf16 (optional) is written in the same form.
@@ -63,14 +72,15 @@ bool gemm_mfma_supported(int batch, int N, int K);
 hipError_t launch_rope_table(const int32_t *seq_lens, const double *inv_freq, int max_tokens, int batch,
                              float2 *table, hipStream_t s);
 
-// Decode attention with RoPE, KV append, split-K partials and the final merge in one launch.
-// counters: [batch][nkv] uint32, zero before the first launch (the kernel leaves them zero).
+// Decode attention: RoPE of q, KV append and split-K partials (max, sum, weighted V) per workgroup ...
 hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batch, int nq, int nkv, AttnSplit sp,
-                       float *part_ml, float *part_o, unsigned *counters, float *out_f32, uint16_t *out_bf16,
-                       hipStream_t s);
+                       float *part_ml, float *part_o, hipStream_t s);
+// ... and the fixed-order merge of the partials into out_f32 and the hi/lo bf16 planes out_bf16.
+hipError_t launch_attn_merge(const float *part_ml, const float *part_o, int batch, int nq, int nkv, AttnSplit sp,
+                             float *out_f32, uint16_t *out_bf16, hipStream_t s);
 
 // Communication stand-in: one workgroup busy-waits `ticks` of the constant-rate wall clock.
-// `flag` (optional): the kernel stores `seq` there on entry, which releases the prefetch job of this window.
+// `flag` (optional): the kernel stores `seq` there on entry, which releases the gate of this window.
 hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned seq, hipStream_t s);
 
 // Prefetch: everything one communication window pulls towards the cache, in one launch.
@@ -83,11 +93,12 @@ struct PrefetchJob {
     KvView kv;                           // KV range: logical blocks [kv_first, kv_first + kv_count) of the
     uint32_t blocks_per_seq;             //   flattened (sequence, block) order, blocks_per_seq per sequence
     uint64_t kv_first, kv_count;
-    const unsigned *flag;                // optional device-side fork: start once *flag has reached seq
-    unsigned seq;
-    uint32_t wait_iters;                 // bounds of the wait (polls, wall-clock ticks)
-    uint64_t wait_ticks;
+    const unsigned *skip;                // optional: word written by the gate kernel; non-zero => do nothing
 };
+// One-wave gate on the side stream: returns when *flag has reached seq (or the bounds expire) and
+// writes *skip = 1 if *flag is already beyond seq.
+hipError_t launch_gate(const unsigned *flag, unsigned seq, uint32_t wait_iters, uint64_t wait_ticks, unsigned *skip,
+                       hipStream_t s);
 hipError_t launch_prefetch_job(const PrefetchJob &j, uint32_t workgroups, hipStream_t s);
 hipError_t launch_prefetch(const void *ptr, uint64_t bytes, uint32_t workgroups, hipStream_t s);
 

@@ -5,9 +5,31 @@
 // around 16-byte-per-lane coalesced loads with many loads in flight per 64-lane wave; matrix
 // cores (16x16x32 bf16 MFMA) are used where a vector-ALU formulation would bind on arithmetic
 // (batch > 4 projections, grouped-query attention).
+#include <hip/hip_ext.h>
+
 #include "internal.h"
 
 namespace psv {
+
+// Optional events that the next kernel launch attaches to its own dispatch: `stop` is bound to the kernel
+// command and carries its end timestamp; `start` is a marker ahead of it.  Used by the per-operator
+// profiling of the API layer.
+static thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+void set_launch_events(hipEvent_t start, hipEvent_t stop)
+{
+    g_ev_start = start;
+    g_ev_stop = stop;
+}
+
+#define PSV_LAUNCH(kernel, grid, block, shmem, stream, ...)                                                      \
+    do {                                                                                                         \
+        if (g_ev_start || g_ev_stop) {                                                                           \
+            hipExtLaunchKernelGGL(kernel, grid, block, shmem, stream, g_ev_start, g_ev_stop, 0, __VA_ARGS__);    \
+            g_ev_start = g_ev_stop = nullptr;                                                                    \
+        } else {                                                                                                 \
+            hipLaunchKernelGGL(kernel, grid, block, shmem, stream, __VA_ARGS__);                                 \
+        }                                                                                                        \
+    } while (0)
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
@@ -115,7 +137,7 @@ hipError_t launch_add_rmsnorm(const float *res, const float *delta, const uint16
                               int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
                               size_t plane_stride, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_add_rmsnorm, dim3(batch), dim3(256), 0, s, res, delta, gain, eps, H, out_res,
+    PSV_LAUNCH(k_add_rmsnorm, dim3(batch), dim3(256), 0, s, res, delta, gain, eps, H, out_res,
                        h_f32, h_bf16, plane_stride);
     return hipGetLastError();
 }
@@ -133,9 +155,12 @@ hipError_t launch_add_rmsnorm(const float *res, const float *delta, const uint16
 // finished with a 64-lane butterfly and, for GS > 64, a fixed-order sum over the group's waves
 // through LDS (no atomics; bit-reproducible).
 //
-// FUSE_NORM: the activations are produced in the prologue as rmsnorm(res + delta) * gain, while the
-// first weight loads are in flight; workgroup 0 also stores the new residual (res + delta) and the
-// normalised vector.  This removes the separate normalisation launch from the layer.
+// MODE selects where the activations come from, always while the first weight loads are in flight:
+//   GEMV_PLAIN  a vector in memory;
+//   GEMV_NORM   rmsnorm(res + delta) * gain formed in the prologue; workgroup 0 also stores the new
+//               residual (res + delta) and the normalised vector -- no separate normalisation launch;
+//   GEMV_MERGE  the attention output, merged in the prologue from the split-K partials of the attention
+//               kernel (chunk order, fixed) -- no separate merge launch; workgroup 0 stores it as well.
 struct GemvArgs {
     const uint16_t *W, *W2;     // W2 != null: SwiGLU pair (gate, up)
     const float *x;             // [NB][K] activations (plain mode)
@@ -146,9 +171,14 @@ struct GemvArgs {
     float *out_h;               // FUSE_NORM: normalised activations, written by workgroup 0 (may be null)
     float *out;                 // [NB][N]
     int N, K, gs_log2, passes;
+    // MODE_MERGE: the activations are the attention output, merged here from the split-K partials
+    const float *part_ml, *part_o;
+    int nkv, G, nc;             // kv heads, query heads per kv head, chunks per (sequence, kv head)
 };
 
-template <int NB, int RB, int ITERS, bool SWIGLU, bool FUSE_NORM>
+enum { GEMV_PLAIN = 0, GEMV_NORM = 1, GEMV_MERGE = 2 };
+
+template <int NB, int RB, int ITERS, bool SWIGLU, int MODE>
 __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
 {
     constexpr int NW = SWIGLU ? 2 : 1;
@@ -185,7 +215,7 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
 
     // ---- activations into registers
     float xv[ITERS][NB][8];
-    if (FUSE_NORM) {
+    if (MODE == GEMV_NORM) {
         uint4 gv[ITERS];
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) gv[it] = kok[it] ? ld16(a.gain + kk[it]) : zero16();
@@ -243,6 +273,60 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
                 }
             }
         }
+    } else if (MODE == GEMV_MERGE) {
+#pragma unroll
+        for (int b = 0; b < NB; ++b)
+#pragma unroll
+            for (int it = 0; it < ITERS; ++it) {
+                float *x = xv[it][b];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) x[e] = 0.f;
+                if (kok[it]) {
+                    const int h = kk[it] >> 7, ch0 = kk[it] & 127, kvh = h / a.G, g = h % a.G;
+                    const size_t slot0 = ((size_t)b * a.nkv + kvh) * a.nc;
+                    // One pass with a running maximum; loads are issued MB chunks at a time so that their
+                    // latencies overlap.  Chunk order is fixed, so the result is reproducible.
+                    constexpr int MB = 8;
+                    const float2 *ml = reinterpret_cast<const float2 *>(a.part_ml) + slot0 * 16 + g;
+                    float Mx = -1.0e30f, den = 0.f;
+                    for (int sp0 = 0; sp0 < a.nc; sp0 += MB) {
+                        float2 t[MB];
+                        float4 o0[MB], o1[MB];
+#pragma unroll
+                        for (int u = 0; u < MB; ++u) {
+                            const bool ok = sp0 + u < a.nc;
+                            const float *o = a.part_o + ((slot0 + sp0 + u) * a.G + g) * 128 + ch0;
+                            t[u] = ok ? ml[(size_t)(sp0 + u) * 16] : make_float2(-1.0e30f, 0.f);
+                            o0[u] = ok ? *reinterpret_cast<const float4 *>(o) : make_float4(0.f, 0.f, 0.f, 0.f);
+                            o1[u] = ok ? *reinterpret_cast<const float4 *>(o + 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+                        }
+                        float bm = Mx;
+#pragma unroll
+                        for (int u = 0; u < MB; ++u) bm = fmaxf(bm, t[u].x);
+                        const float rs = exp2f(Mx - bm);
+                        Mx = bm;
+                        den *= rs;
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) x[e] *= rs;
+#pragma unroll
+                        for (int u = 0; u < MB; ++u) {
+                            const float wgt = t[u].y > 0.f ? exp2f(t[u].x - Mx) : 0.f;
+                            den += wgt * t[u].y;
+                            x[0] = fmaf(wgt, o0[u].x, x[0]); x[1] = fmaf(wgt, o0[u].y, x[1]);
+                            x[2] = fmaf(wgt, o0[u].z, x[2]); x[3] = fmaf(wgt, o0[u].w, x[3]);
+                            x[4] = fmaf(wgt, o1[u].x, x[4]); x[5] = fmaf(wgt, o1[u].y, x[5]);
+                            x[6] = fmaf(wgt, o1[u].z, x[6]); x[7] = fmaf(wgt, o1[u].w, x[7]);
+                        }
+                    }
+                    const float inv = den > 0.f ? 1.0f / den : 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) x[e] *= inv;
+                    if (a.out_h && blockIdx.x == 0 && gid == 0) {
+                        *reinterpret_cast<float4 *>(a.out_h + (size_t)b * K + kk[it]) = make_float4(x[0], x[1], x[2], x[3]);
+                        *reinterpret_cast<float4 *>(a.out_h + (size_t)b * K + kk[it] + 4) = make_float4(x[4], x[5], x[6], x[7]);
+                    }
+                }
+            }
     } else {
 #pragma unroll
         for (int b = 0; b < NB; ++b)
@@ -320,7 +404,7 @@ bool gemv_supported(int batch, int N, int K)
     return batch >= 1 && batch <= 4 && K % 8 == 0 && K >= 64 && K <= 8192 && N >= 1;
 }
 
-template <int NB, int ITERS, bool SW, bool FN>
+template <int NB, int ITERS, bool SW, int MODE>
 static hipError_t gemv_go(GemvArgs a, hipStream_t s)
 {
     constexpr int RB = SW ? 4 : 8;
@@ -338,29 +422,26 @@ static hipError_t gemv_go(GemvArgs a, hipStream_t s)
     a.gs_log2 = gs_log2;
     a.passes = (int)((max_rows + RB - 1) / RB);
     if (a.passes < 1) a.passes = 1;
-    hipLaunchKernelGGL((k_gemv<NB, RB, ITERS, SW, FN>), dim3((unsigned)blocks), dim3(512), 0, s, a);
+    PSV_LAUNCH((k_gemv<NB, RB, ITERS, SW, MODE>), dim3((unsigned)blocks), dim3(512), 0, s, a);
     return hipGetLastError();
 }
 
-template <int NB>
+template <int NB, int MODE>
 static hipError_t gemv_pick(const GemvArgs &a, hipStream_t s)
 {
-    const bool sw = a.W2 != nullptr, fn = a.res != nullptr, two = a.K > 4096;
-    if (two) {
-        if (sw) return fn ? gemv_go<NB, 2, true, true>(a, s) : gemv_go<NB, 2, true, false>(a, s);
-        return fn ? gemv_go<NB, 2, false, true>(a, s) : gemv_go<NB, 2, false, false>(a, s);
-    }
-    if (sw) return fn ? gemv_go<NB, 1, true, true>(a, s) : gemv_go<NB, 1, true, false>(a, s);
-    return fn ? gemv_go<NB, 1, false, true>(a, s) : gemv_go<NB, 1, false, false>(a, s);
+    const bool sw = a.W2 != nullptr, two = a.K > 4096;
+    if (two) return sw ? gemv_go<NB, 2, true, MODE>(a, s) : gemv_go<NB, 2, false, MODE>(a, s);
+    return sw ? gemv_go<NB, 1, true, MODE>(a, s) : gemv_go<NB, 1, false, MODE>(a, s);
 }
 
+template <int MODE>
 static hipError_t gemv_dispatch(const GemvArgs &a, int batch, hipStream_t s)
 {
     switch (batch) {
-    case 1: return gemv_pick<1>(a, s);
-    case 2: return gemv_pick<2>(a, s);
-    case 3: return gemv_pick<3>(a, s);
-    case 4: return gemv_pick<4>(a, s);
+    case 1: return gemv_pick<1, MODE>(a, s);
+    case 2: return gemv_pick<2, MODE>(a, s);
+    case 3: return gemv_pick<3, MODE>(a, s);
+    case 4: return gemv_pick<4, MODE>(a, s);
     default: return hipErrorInvalidValue;
     }
 }
@@ -370,7 +451,7 @@ hipError_t launch_gemv(const uint16_t *W, const uint16_t *W2, const float *x, fl
 {
     GemvArgs a{};
     a.W = W; a.W2 = W2; a.x = x; a.out = out; a.N = N; a.K = K;
-    return gemv_dispatch(a, batch, s);
+    return gemv_dispatch<GEMV_PLAIN>(a, batch, s);
 }
 
 hipError_t launch_gemv_norm(const uint16_t *W, const uint16_t *W2, const float *res, const float *delta,
@@ -380,7 +461,21 @@ hipError_t launch_gemv_norm(const uint16_t *W, const uint16_t *W2, const float *
     GemvArgs a{};
     a.W = W; a.W2 = W2; a.res = res; a.delta = delta; a.gain = gain; a.eps = eps; a.out_res = out_res; a.out_h = out_h;
     a.out = out; a.N = N; a.K = K;
-    return gemv_dispatch(a, batch, s);
+    return gemv_dispatch<GEMV_NORM>(a, batch, s);
+}
+
+bool gemv_merge_supported(int batch, int nq, int n_chunks)
+{
+    return batch >= 1 && batch <= 4 && nq * 128 <= 4096 && n_chunks <= kGemvMergeMaxChunks;
+}
+
+hipError_t launch_gemv_merge(const uint16_t *W, const float *part_ml, const float *part_o, int nq, int nkv,
+                             int n_chunks, float *out_attn, float *out, int batch, int N, hipStream_t s)
+{
+    GemvArgs a{};
+    a.W = W; a.part_ml = part_ml; a.part_o = part_o; a.nkv = nkv; a.G = nq / nkv; a.nc = n_chunks; a.out_h = out_attn;
+    a.out = out; a.N = N; a.K = nq * 128;
+    return gemv_dispatch<GEMV_MERGE>(a, batch, s);
 }
 
 // ------------------------------------------------------------------------------------ MFMA skinny GEMM
@@ -487,10 +582,10 @@ static hipError_t gemm_go(const uint16_t *W, const uint16_t *W2, const uint16_t 
 {
     const size_t x_plane = (size_t)NB * 16 * K, out_plane = (size_t)NB * 16 * N;
     if (W2)
-        hipLaunchKernelGGL((k_gemm_mfma<NB, NWAVES, true>), dim3(N / 16), dim3(NWAVES * 64), 0, s, W, W2, xb, out,
+        PSV_LAUNCH((k_gemm_mfma<NB, NWAVES, true>), dim3(N / 16), dim3(NWAVES * 64), 0, s, W, W2, xb, out,
                            out_bf16, batch, N, K, x_plane, out_plane);
     else
-        hipLaunchKernelGGL((k_gemm_mfma<NB, NWAVES, false>), dim3(N / 16), dim3(NWAVES * 64), 0, s, W, W2, xb, out,
+        PSV_LAUNCH((k_gemm_mfma<NB, NWAVES, false>), dim3(N / 16), dim3(NWAVES * 64), 0, s, W, W2, xb, out,
                            out_bf16, batch, N, K, x_plane, out_plane);
     return hipGetLastError();
 }
@@ -545,7 +640,7 @@ __global__ __launch_bounds__(64) void k_rope_table(const int32_t *__restrict__ s
 hipError_t launch_rope_table(const int32_t *seq_lens, const double *inv_freq, int max_tokens, int batch, float2 *table,
                              hipStream_t s)
 {
-    hipLaunchKernelGGL(k_rope_table, dim3(batch), dim3(64), 0, s, seq_lens, inv_freq, max_tokens, table);
+    PSV_LAUNCH(k_rope_table, dim3(batch), dim3(64), 0, s, seq_lens, inv_freq, max_tokens, table);
     return hipGetLastError();
 }
 
@@ -575,7 +670,6 @@ struct AttnArgs {
     int nq, nkv, chunk_tokens, n_chunks;
     float *part_ml;            // [batch][nkv][n_chunks][16][2]
     float *part_o;             // [batch][nkv][n_chunks][G][128]
-    unsigned *counters;        // [batch][nkv], zero between launches
     float *out_f32;            // [batch][nq*128]
     uint16_t *out_bf16;        // same as hi/lo bf16 planes (operand of the MFMA O projection)
     size_t out_plane;          // distance between the planes, elements
@@ -613,29 +707,6 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     const float *qkv_b = a.qkv + (size_t)b * qkv_rows;
     const float2 *rope_b = a.rope + b * 64;
 
-    // ---- append the new token's K and V (one workgroup per kv head does it)
-    if (T >= 1 && c == (T - 1) / a.chunk_tokens) {
-        if (tid < 64) {
-            const int pos = T - 1;
-            const int blk = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, pos >> 4);
-            if (blk >= 0) {
-                const float2 cs = rope_b[tid];
-                const float *krow = qkv_b + (size_t)(nq + kvh) * 128;
-                const float *vrow = qkv_b + (size_t)(nq + nkv + kvh) * 128;
-                const float lo = krow[tid], hi = krow[tid + 64];
-                const int r = pos & 15;
-                uint16_t *kdst = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + r) * 128;
-                kdst[tid] = (uint16_t)f32_to_bf16(lo * cs.x - hi * cs.y);
-                kdst[tid + 64] = (uint16_t)f32_to_bf16(hi * cs.x + lo * cs.y);
-                uint16_t *vdst = kv.v_pool + ((size_t)blk * nkv + kvh) * 128 * 16 + r;
-                vdst[(size_t)tid * 16] = (uint16_t)f32_to_bf16(vrow[tid]);
-                vdst[(size_t)(tid + 64) * 16] = (uint16_t)f32_to_bf16(vrow[tid + 64]);
-            }
-            __threadfence();
-        }
-        __syncthreads();   // uniform: the condition depends on the workgroup only
-    }
-
     // ---- Q fragments, rotated: lane (g = i, q4) holds channels ks*32 + q4*8 + e; channel f < 64
     //      pairs with f + 64, i.e. fragment ks with fragment ks + 2 of the same lane.
     bf16x8 qf[4];
@@ -664,6 +735,29 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                 qf[ks + 2] = __builtin_bit_cast(bf16x8, ph);
             }
         }
+    }
+
+    // ---- append the new token's K and V (one workgroup per kv head does it)
+    if (T >= 1 && c == (T - 1) / a.chunk_tokens) {
+        if (tid < 64) {
+            const int pos = T - 1;
+            const int blk = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, pos >> 4);
+            if (blk >= 0) {
+                const float2 cs = rope_b[tid];
+                const float *krow = qkv_b + (size_t)(nq + kvh) * 128;
+                const float *vrow = qkv_b + (size_t)(nq + nkv + kvh) * 128;
+                const float lo = krow[tid], hi = krow[tid + 64];
+                const int r = pos & 15;
+                uint16_t *kdst = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + r) * 128;
+                kdst[tid] = (uint16_t)f32_to_bf16(lo * cs.x - hi * cs.y);
+                kdst[tid + 64] = (uint16_t)f32_to_bf16(hi * cs.x + lo * cs.y);
+                uint16_t *vdst = kv.v_pool + ((size_t)blk * nkv + kvh) * 128 * 16 + r;
+                vdst[(size_t)tid * 16] = (uint16_t)f32_to_bf16(vrow[tid]);
+                vdst[(size_t)(tid + 64) * 16] = (uint16_t)f32_to_bf16(vrow[tid + 64]);
+            }
+            __threadfence();
+        }
+        __syncthreads();   // uniform: the condition depends on the workgroup only
     }
 
     const float kScale = 0.08838834764831845f * 1.4426950408889634f;   // 1/sqrt(128) * log2(e)
@@ -864,16 +958,27 @@ __global__ __launch_bounds__(1024) void k_attn_merge(AttnArgs a)
     }
 }
 
-hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batch, int nq, int nkv, AttnSplit sp,
-                       float *part_ml, float *part_o, unsigned *counters, float *out_f32, uint16_t *out_bf16,
-                       hipStream_t s)
+static AttnArgs attn_args(const float *qkv, const float2 *rope, KvView kv, int batch, int nq, int nkv, AttnSplit sp,
+                          float *part_ml, float *part_o, float *out_f32, uint16_t *out_bf16)
 {
     const size_t out_plane = (size_t)((batch + 15) / 16 * 16) * nq * 128;
-    AttnArgs a{qkv, rope, kv, nq, nkv, sp.chunk_tokens, sp.n_chunks, part_ml, part_o, counters, out_f32, out_bf16, out_plane};
-    hipLaunchKernelGGL(k_attn, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(k_attn_merge, dim3(nkv, batch), dim3(1024), 0, s, a);
+    return AttnArgs{qkv, rope, kv, nq, nkv, sp.chunk_tokens, sp.n_chunks, part_ml, part_o, out_f32, out_bf16, out_plane};
+}
+
+hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batch, int nq, int nkv, AttnSplit sp,
+                       float *part_ml, float *part_o, hipStream_t s)
+{
+    AttnArgs a = attn_args(qkv, rope, kv, batch, nq, nkv, sp, part_ml, part_o, nullptr, nullptr);
+    PSV_LAUNCH(k_attn, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_attn_merge(const float *part_ml, const float *part_o, int batch, int nq, int nkv, AttnSplit sp,
+                             float *out_f32, uint16_t *out_bf16, hipStream_t s)
+{
+    AttnArgs a = attn_args(nullptr, nullptr, KvView{}, batch, nq, nkv, sp, const_cast<float *>(part_ml),
+                           const_cast<float *>(part_o), out_f32, out_bf16);
+    PSV_LAUNCH(k_attn_merge, dim3(nkv, batch), dim3(1024), 0, s, a);
     return hipGetLastError();
 }
 
@@ -881,8 +986,8 @@ hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batc
 
 // One workgroup of one wave busy-waits on the constant-rate wall clock; the iteration cap makes
 // sure the wave exits even if the clock misbehaves.  On entry it publishes the window's sequence
-// number: the prefetch kernel that belongs to this window is already resident on the side stream
-// and starts the moment it sees the number (a device-side fork, no host event in between).
+// number: a gate kernel (k_gate) is already waiting for it on the side stream, ahead of the window's
+// prefetch launches (a device-side fork, no host event in between).
 __global__ __launch_bounds__(64) void k_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned seq)
 {
     const uint64_t t0 = wall_clock64();
@@ -896,7 +1001,7 @@ __global__ __launch_bounds__(64) void k_spin(uint64_t ticks, uint32_t max_iters,
 
 hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned seq, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_spin, dim3(1), dim3(64), 0, s, ticks, max_iters, flag, seq);
+    PSV_LAUNCH(k_spin, dim3(1), dim3(64), 0, s, ticks, max_iters, flag, seq);
     return hipGetLastError();
 }
 
@@ -911,26 +1016,7 @@ __device__ __forceinline__ uint32_t fold(uint4 v) { return v.x ^ v.y ^ v.z ^ v.w
 __global__ __launch_bounds__(256) void k_prefetch(PrefetchJob j)
 {
     constexpr int U = 8;
-    if (j.flag) {
-        // Wait (bounded) until the main stream has entered the window this job belongs to.  Being early
-        // or late can never change a result -- the kernel only reads -- so the bound is just an exit
-        // guarantee.  If a later window has already begun, the data would arrive after its consumers
-        // ran: skip it.
-        __shared__ int go;
-        if (threadIdx.x == 0) {
-            const uint64_t t0 = wall_clock64();
-            unsigned v = __hip_atomic_load(j.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            uint32_t it = 0;
-            while ((int)(v - j.seq) < 0 && it < j.wait_iters && wall_clock64() - t0 < j.wait_ticks) {
-                __builtin_amdgcn_s_sleep(4);
-                v = __hip_atomic_load(j.flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                ++it;
-            }
-            go = (int)(v - j.seq) <= 0;
-        }
-        __syncthreads();
-        if (!go) return;
-    }
+    if (j.skip && *j.skip) return;   // the gate kernel ahead of this launch found the window already over
     const uint64_t stride = (uint64_t)gridDim.x * 256;
     const uint64_t me = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     uint32_t sink = 0;
@@ -971,10 +1057,38 @@ __global__ __launch_bounds__(256) void k_prefetch(PrefetchJob j)
     asm volatile("" ::"v"(sink));   // keeps the loads alive without a store
 }
 
+// Device-side fork.  One wave waits (bounded) until the main stream has entered the window whose
+// sequence number is `seq` (published by k_spin), then ends, which releases the prefetch launches queued
+// behind it on the side stream.  A single wave cannot keep any main-stream kernel off the CUs, whatever
+// that kernel's register or LDS footprint.  If a later window has already begun, the data would arrive
+// after its consumers ran: *skip = 1 tells the prefetch launches to do nothing.  Being early or late can
+// never change a result (prefetch only reads), so the bounds are just an exit guarantee.
+__global__ __launch_bounds__(64) void k_gate(const unsigned *flag, unsigned seq, uint32_t wait_iters, uint64_t wait_ticks,
+                                             unsigned *skip)
+{
+    if (threadIdx.x != 0) return;
+    const uint64_t t0 = wall_clock64();
+    unsigned v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t it = 0;
+    while ((int)(v - seq) < 0 && it < wait_iters && wall_clock64() - t0 < wait_ticks) {
+        __builtin_amdgcn_s_sleep(2);
+        v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ++it;
+    }
+    *skip = (int)(v - seq) > 0 ? 1u : 0u;
+}
+
+hipError_t launch_gate(const unsigned *flag, unsigned seq, uint32_t wait_iters, uint64_t wait_ticks, unsigned *skip,
+                       hipStream_t s)
+{
+    PSV_LAUNCH(k_gate, dim3(1), dim3(64), 0, s, flag, seq, wait_iters, wait_ticks, skip);
+    return hipGetLastError();
+}
+
 hipError_t launch_prefetch_job(const PrefetchJob &j, uint32_t workgroups, hipStream_t s)
 {
     if (workgroups == 0 || (j.n_regions == 0 && j.kv_count == 0)) return hipSuccess;
-    hipLaunchKernelGGL(k_prefetch, dim3(workgroups), dim3(256), 0, s, j);
+    PSV_LAUNCH(k_prefetch, dim3(workgroups), dim3(256), 0, s, j);
     return hipGetLastError();
 }
 
@@ -1002,7 +1116,7 @@ hipError_t launch_copy(void *dst, const void *src, uint64_t bytes, hipStream_t s
     uint64_t n16 = bytes / 16;
     uint64_t blocks = (n16 + 255) / 256;
     if (blocks > 4096) blocks = 4096;
-    hipLaunchKernelGGL(k_copy, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<uint4 *>(dst),
+    PSV_LAUNCH(k_copy, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<uint4 *>(dst),
                        reinterpret_cast<const uint4 *>(src), n16);
     return hipGetLastError();
 }
