@@ -39,6 +39,9 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = auto)")
     ap.add_argument("--seed", type=int, default=2501)
+    ap.add_argument("--calibrate-copy-mb", type=int, default=0,
+                    help="also launch one plain copy kernel of this size (known bytes, to scale hardware counters)")
+    ap.add_argument("--skip-kernel-table", action="store_true", help="omit the per-operator event timing passes")
     return ap.parse_args()
 
 
@@ -89,6 +92,17 @@ def cpu_baseline(sess, n_layers, target_s=10.0, max_reps=40):
         total += time.perf_counter() - t0
         reps += 1
     return total * 1e6 / (reps * len(host)), len(host), reps, oracle.num_threads()
+
+
+def stored_traffic(workload, kernel):
+    """HBM bytes per launch of a kernel from the committed rocprofv3 PMC summary (None if there is none)."""
+    import re
+    path = os.path.join(ROOT, "profiles", "%s_pmc_hbm_traffic.md" % workload)
+    try:
+        m = re.search(r"traffic_bytes_per_launch\[%s,%s\]\s*=\s*(\d+)" % (workload, kernel), open(path).read())
+        return int(m.group(1)) if m else None
+    except OSError:
+        return None
 
 
 def main():
@@ -143,7 +157,16 @@ def main():
               "down": psv.PSV_OP_DOWN}
     n_prof = max(3, min(a.steps, 10))
     kernels = {}
+    if a.calibrate_copy_mb > 0:
+        nb = a.calibrate_copy_mb << 20
+        src = torch.empty(nb, dtype=torch.uint8, device="cuda").random_()
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        psv.psv_copy_bytes(dst, src, nb, sess.main)
+        sess.sync()
     for mode_name, pol in (("off", off), ("on", on)):
+        if a.skip_kernel_table and mode_name == "on":
+            break
         sess.set_policy(pol)
         for name, op in op_ids.items():
             us, n = profile_op(sess, op, n_prof)
@@ -151,7 +174,8 @@ def main():
             kernels[name]["us_" + mode_name] = round(us, 3)
             kernels[name]["gbps_" + mode_name] = round(op_bytes[name] / us / 1e3, 1)
             kernels[name]["launches"] = n
-    gate_us, gate_us_on, gate_n = kernels["gate_up"]["us_off"], kernels["gate_up"]["us_on"], kernels["gate_up"]["launches"]
+    gate_us, gate_n = kernels["gate_up"]["us_off"], kernels["gate_up"]["launches"]
+    gate_us_on = kernels["gate_up"].get("us_on", float("nan"))
     gate_bytes = op_bytes["gate_up"]
     achieved = gate_bytes / gate_us / 1e3
 
@@ -184,7 +208,7 @@ def main():
                                                 "frac_on": round(eff_on / HBM_PEAK_GBPS, 4)},
         "roofline": {"bound": "hbm", "kernel": "gate/up projection + SwiGLU (prefetch off)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": None,
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": stored_traffic(w.name, "gate_up"),
                      "bytes_per_launch": gate_bytes, "avg_us": round(gate_us, 3), "launches": gate_n,
                      "avg_us_prefetch_on": round(gate_us_on, 3),
                      "achieved_prefetch_on": round(gate_bytes / gate_us_on / 1e3, 1)},
