@@ -26,7 +26,7 @@ struct Workspace {
     size_t total = 0;
     // offsets
     size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, rope, part_ml, part_o, attn_f32, attn_bf16,
-        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag;
+        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag, part;
 };
 
 Workspace layout_workspace(const psv_model_desc &d)
@@ -56,6 +56,11 @@ Workspace layout_workspace(const psv_model_desc &d)
     w.m_bf16 = take(2 * Bp * F * 2);
     w.inv_freq = take(64 * sizeof(double));
     w.flag = take(256);
+    {   // split-K partials of the widest projection
+        size_t widest = QR > H ? QR : H;
+        if (2 * F > widest) widest = 2 * F;
+        w.part = take((size_t)kSkMaxSplits * B * widest * 4);
+    }
     w.total = off;
     return w;
 }
@@ -104,6 +109,7 @@ struct psv_ctx {
     uint32_t last_prefetch_launches = 0;
     unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
     bool capturing = false;
+    bool old_mfma = false;                       // A/B switch: K-split-in-workgroup GEMM instead of the split-K one
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(wsp + off); }
 };
@@ -335,23 +341,34 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     const size_t plane_h = (size_t)((B + 15) / 16 * 16) * H;   // hi -> lo plane distance of the bf16 activations
 
     // Small batches run every projection on the vector ALU with the normalisation fused into the
-    // prologue; larger ones use the matrix cores with a separate normalisation kernel.
+    // prologue; larger ones use the matrix cores (split-K GEMM + reductions) with a separate normalisation.
     const bool vec = gemv_supported(B, QR, H) && gemv_supported(B, H, QD) && gemv_supported(B, F, H) && gemv_supported(B, H, F);
+    const bool sk = !vec && !c->old_mfma;
+    float *part = c->at<float>(c->ws.part);
 
     ST_TRY(prof_tag(c, -2));
     HIP_TRY(launch_rope_table(c->kv.seq_lens, inv_freq, (int)c->kv.max_blocks * 16, B, rope, s));
     const float *res = x_in, *delta = nullptr;   // residual stream entering the layer = res + delta
+    int delta_splits = 1;                        // delta may be a stack of split-K partials
     for (uint32_t l = lb; l < le; ++l) {
         const psv_layer_weights &w = c->weights[l];
         const KvView kv = kv_view(c, l);
 
-        if (!vec) ST_TRY(prof_tag(c, -2));
-        if (!vec) HIP_TRY(launch_add_rmsnorm(res, delta, u16(w.g_attn), d.rms_eps, B, H, x, h1, h1b, plane_h, s));
+        if (!vec) {
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_add_rmsnorm(res, delta, delta_splits, u16(w.g_attn), d.rms_eps, B, H, x, h1, h1b, plane_h, s));
+        }
         ST_TRY(prof_tag(c, PSV_OP_QKV));
-        if (vec)
+        if (vec) {
             HIP_TRY(launch_gemv_norm(u16(w.w_qkv), nullptr, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H, s));
-        else
+        } else if (sk) {
+            if (!gemm_sk_supported(B, QR, H)) return PSV_ERR_UNSUPPORTED;
+            HIP_TRY(launch_gemm_sk(u16(w.w_qkv), nullptr, 0, h1b, part, B, QR, H, s));
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H), B, QR, false, qkv, nullptr, s));
+        } else {
             ST_TRY(projection_mfma(c, w.w_qkv, nullptr, h1b, qkv, nullptr, B, QR, H));
+        }
 
         ST_TRY(prof_tag(c, PSV_OP_ATTN));
         HIP_TRY(launch_attn(qkv, rope, kv, B, nq, nkv, sp, pml, po, s));
@@ -362,35 +379,58 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         }
 
         ST_TRY(prof_tag(c, PSV_OP_O));
-        if (fuse_merge)
+        const float *attn_delta = delta_a;
+        int attn_splits = 1;
+        if (fuse_merge) {
             HIP_TRY(launch_gemv_merge(u16(w.w_o), pml, po, nq, nkv, sp.n_chunks, attn, delta_a, B, H, s));
-        else if (vec)
+        } else if (vec) {
             HIP_TRY(launch_gemv(u16(w.w_o), nullptr, attn, delta_a, B, H, QD, s));
-        else
+        } else if (sk) {
+            if (!gemm_sk_supported(B, H, QD)) return PSV_ERR_UNSUPPORTED;
+            HIP_TRY(launch_gemm_sk(u16(w.w_o), nullptr, 0, attnb, part, B, H, QD, s));
+            attn_delta = part;
+            attn_splits = gemm_sk_splits(B, H, QD);
+        } else {
             ST_TRY(projection_mfma(c, w.w_o, nullptr, attnb, delta_a, nullptr, B, H, QD));
+        }
 
         ST_TRY(comm_window(c, l, 0, batch, le, &side_used));
 
-        if (!vec) ST_TRY(prof_tag(c, -2));
-        if (!vec) HIP_TRY(launch_add_rmsnorm(x, delta_a, u16(w.g_mlp), d.rms_eps, B, H, y, h2, h2b, plane_h, s));
+        if (!vec) {
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_add_rmsnorm(x, attn_delta, attn_splits, u16(w.g_mlp), d.rms_eps, B, H, y, h2, h2b, plane_h, s));
+        }
         ST_TRY(prof_tag(c, PSV_OP_GATE));
-        if (vec)
+        if (vec) {
             HIP_TRY(launch_gemv_norm(u16(w.w_gate), u16(w.w_up), x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H, s));
-        else
+        } else if (sk) {
+            if (!gemm_sk_supported(B, 2 * F, H)) return PSV_ERR_UNSUPPORTED;
+            HIP_TRY(launch_gemm_sk(u16(w.w_gate), u16(w.w_up), F, h2b, part, B, 2 * F, H, s));
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H), B, 2 * F, true, m, mb, s));
+        } else {
             ST_TRY(projection_mfma(c, w.w_gate, w.w_up, h2b, m, mb, B, F, H));
+        }
 
         ST_TRY(prof_tag(c, PSV_OP_DOWN));
-        if (vec)
+        delta = delta_m;
+        delta_splits = 1;
+        if (vec) {
             HIP_TRY(launch_gemv(u16(w.w_down), nullptr, m, delta_m, B, H, F, s));
-        else
+        } else if (sk) {
+            if (!gemm_sk_supported(B, H, F)) return PSV_ERR_UNSUPPORTED;
+            HIP_TRY(launch_gemm_sk(u16(w.w_down), nullptr, 0, mb, part, B, H, F, s));
+            delta = part;
+            delta_splits = gemm_sk_splits(B, H, F);
+        } else {
             ST_TRY(projection_mfma(c, w.w_down, nullptr, mb, delta_m, nullptr, B, H, F));
+        }
 
         ST_TRY(comm_window(c, l, 1, batch, le, &side_used));
         res = y;
-        delta = delta_m;
     }
     ST_TRY(prof_tag(c, -2));
-    HIP_TRY(launch_add_rmsnorm(res, delta, nullptr, d.rms_eps, B, H, x_out, nullptr, nullptr, 0, s));
+    HIP_TRY(launch_add_rmsnorm(res, delta, delta_splits, nullptr, d.rms_eps, B, H, x_out, nullptr, nullptr, 0, s));
     if (side_used && c->capturing) {   // a captured side branch has to rejoin the origin stream
         HIP_TRY(hipEventRecord(c->ev_end, c->side));
         HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));
@@ -433,6 +473,7 @@ psv_status psv_create(const psv_model_desc *desc, void *stream_main, void *strea
     int khz = 0;
     if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device) == hipSuccess && khz > 0) c->clock_khz = (uint64_t)khz;
     c->ws = layout_workspace(c->d);
+    c->old_mfma = getenv("PSV_MFMA_OLD") != nullptr;
     if (hipMalloc(reinterpret_cast<void **>(&c->wsp), c->ws.total) != hipSuccess) {
         c->wsp = nullptr;
         return fail(PSV_ERR_NOMEM);

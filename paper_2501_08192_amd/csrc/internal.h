@@ -38,11 +38,12 @@ struct KvView {
 // The next kernel launched from this thread records `start` / `stop` around its own execution.
 void set_launch_events(hipEvent_t start, hipEvent_t stop);
 
-// out_res = res + delta (delta may be null); if gain != null: h = out_res * rsqrt(mean(out_res^2)
-// + eps) * gain, written as fp32 (h_f32) and as hi/lo bf16 planes (h_bf16, row stride H, lo plane
-// plane_stride elements after the hi plane).  One workgroup per row.
-hipError_t launch_add_rmsnorm(const float *res, const float *delta, const uint16_t *gain, float eps,
-                              int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
+// out_res = res + delta (delta may be null, or `delta_splits` > 1 split-K partials [split][batch][H] that
+// are summed in split order); if gain != null: h = out_res * rsqrt(mean(out_res^2) + eps) * gain, written
+// as fp32 (h_f32) and as hi/lo bf16 planes (h_bf16, row stride H, lo plane plane_stride elements after the
+// hi plane).  One workgroup per row.
+hipError_t launch_add_rmsnorm(const float *res, const float *delta, int delta_splits, const uint16_t *gain,
+                              float eps, int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
                               size_t plane_stride, hipStream_t s);
 
 // Vector-ALU GEMV for batch <= 4:  out[b][r] = sum_k W[r][k] * x[b][k]   (fp32 x, bf16 W).
@@ -67,6 +68,19 @@ hipError_t launch_gemv_merge(const uint16_t *W, const float *part_ml, const floa
 hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_t *x_bf16, float *out,
                             uint16_t *out_bf16, int batch, int N, int K, hipStream_t s);
 bool gemm_mfma_supported(int batch, int N, int K);
+
+// Split-K skinny GEMM on the matrix cores with the activation slab shared through LDS:
+// part[split][b][r] = partial sums of W[r].x[b] (rows >= split_row come from W2), to be summed in split
+// order by launch_sk_reduce or launch_add_rmsnorm.  x_bf16 as for launch_gemm_mfma.
+constexpr int kSkMaxSplits = 16;
+int gemm_sk_splits(int batch, int N, int K);
+bool gemm_sk_supported(int batch, int N, int K);
+hipError_t launch_gemm_sk(const uint16_t *W, const uint16_t *W2, int split_row, const uint16_t *x_bf16, float *part,
+                          int batch, int N, int K, hipStream_t s);
+// out = sum of the splits; swiglu: N = gate | up columns, out = silu(gate) * up of width N/2.  out_bf16
+// (optional) receives hi/lo planes.
+hipError_t launch_sk_reduce(const float *part, int splits, int batch, int N, bool swiglu, float *out,
+                            uint16_t *out_bf16, hipStream_t s);
 
 // cos/sin of the rotary angles at position seq_len-1: table [batch][64] (inv_freq null => identity).
 hipError_t launch_rope_table(const int32_t *seq_lens, const double *inv_freq, int max_tokens, int batch,

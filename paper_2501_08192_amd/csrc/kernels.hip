@@ -89,56 +89,77 @@ __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f +
 // ------------------------------------------------------------------------------------ norm
 
 // out_res = res + delta; h = out_res * rsqrt(mean(out_res^2) + eps) * gain, stored as fp32 and as
-// the hi/lo bf16 planes the matrix-core GEMM reads.  One workgroup per batch row; the row is re-read from out_res for the second pass (each thread re-reads only what
-// it wrote itself).
-__global__ __launch_bounds__(256) void k_add_rmsnorm(const float *__restrict__ res,
-                                                     const float *__restrict__ delta,
-                                                     const uint16_t *__restrict__ gain, float eps, int H,
-                                                     float *out_res, float *__restrict__ h_f32,
-                                                     uint16_t *__restrict__ h_bf16, size_t plane_stride)
+// the hi/lo bf16 planes the matrix-core GEMM reads.  delta may be given as `delta_splits` split-K partials
+// [split][batch][H], which are summed in split order first.  One workgroup of 1024 threads per batch
+// row; the row stays in registers between the two phases.
+__global__ __launch_bounds__(1024) void k_add_rmsnorm(const float *__restrict__ res,
+                                                      const float *__restrict__ delta, int delta_splits,
+                                                      size_t delta_stride,
+                                                      const uint16_t *__restrict__ gain, float eps, int H,
+                                                      float *out_res, float *__restrict__ h_f32,
+                                                      uint16_t *__restrict__ h_bf16, size_t plane_stride)
 {
-    __shared__ float red[4];
+    constexpr int MAXV = 4;   // float4 per thread: H <= 16384
+    __shared__ float red[16];
     const int b = blockIdx.x, tid = threadIdx.x;
     const float *r = res + (size_t)b * H;
     const float *d = delta ? delta + (size_t)b * H : nullptr;
     float *o = out_res + (size_t)b * H;
+    float4 v[MAXV];
+    uint2 gv[MAXV];
     float ss = 0.f;
-    for (int i = tid * 4; i < H; i += 1024) {
-        float4 v = *reinterpret_cast<const float4 *>(r + i);
-        if (d) {
-            float4 e = *reinterpret_cast<const float4 *>(d + i);
-            v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w;
+#pragma unroll
+    for (int q = 0; q < MAXV; ++q) {
+        const int i = (q * 1024 + tid) * 4;
+        v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
+        gv[q] = make_uint2(0u, 0u);
+        if (i < H) {
+            v[q] = *reinterpret_cast<const float4 *>(r + i);
+            if (gain) gv[q] = *reinterpret_cast<const uint2 *>(gain + i);
+            if (d) {
+                float4 e = *reinterpret_cast<const float4 *>(d + i);
+                for (int ks = 1; ks < delta_splits; ++ks) {     // split-K partials of the projection, split order
+                    const float4 t = *reinterpret_cast<const float4 *>(d + ks * delta_stride + i);
+                    e.x += t.x; e.y += t.y; e.z += t.z; e.w += t.w;
+                }
+                v[q].x += e.x; v[q].y += e.y; v[q].z += e.z; v[q].w += e.w;
+            }
+            *reinterpret_cast<float4 *>(o + i) = v[q];
+            ss += v[q].x * v[q].x + v[q].y * v[q].y + v[q].z * v[q].z + v[q].w * v[q].w;
         }
-        *reinterpret_cast<float4 *>(o + i) = v;
-        ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
     }
     if (!gain) return;
     ss = wave_sum(ss);
     if ((tid & 63) == 0) red[tid >> 6] = ss;
     __syncthreads();
-    ss = red[0] + red[1] + red[2] + red[3];
+    ss = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) ss += red[k];
     const float inv = 1.0f / sqrtf(ss / (float)H + eps);
-    for (int i = tid * 4; i < H; i += 1024) {
-        float4 v = *reinterpret_cast<const float4 *>(o + i);
-        uint2 g = *reinterpret_cast<const uint2 *>(gain + i);
-        v.x = v.x * inv * bf16_lo(g.x);
-        v.y = v.y * inv * bf16_hi(g.x);
-        v.z = v.z * inv * bf16_lo(g.y);
-        v.w = v.w * inv * bf16_hi(g.y);
-        *reinterpret_cast<float4 *>(h_f32 + (size_t)b * H + i) = v;
-        uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
-        split_bf16(v.x, h0, l0); split_bf16(v.y, h1, l1); split_bf16(v.z, h2, l2); split_bf16(v.w, h3, l3);
-        *reinterpret_cast<uint2 *>(h_bf16 + (size_t)b * H + i) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-        *reinterpret_cast<uint2 *>(h_bf16 + plane_stride + (size_t)b * H + i) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+#pragma unroll
+    for (int q = 0; q < MAXV; ++q) {
+        const int i = (q * 1024 + tid) * 4;
+        if (i < H) {
+            float4 t = v[q];
+            t.x = t.x * inv * bf16_lo(gv[q].x);
+            t.y = t.y * inv * bf16_hi(gv[q].x);
+            t.z = t.z * inv * bf16_lo(gv[q].y);
+            t.w = t.w * inv * bf16_hi(gv[q].y);
+            *reinterpret_cast<float4 *>(h_f32 + (size_t)b * H + i) = t;
+            uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+            split_bf16(t.x, h0, l0); split_bf16(t.y, h1, l1); split_bf16(t.z, h2, l2); split_bf16(t.w, h3, l3);
+            *reinterpret_cast<uint2 *>(h_bf16 + (size_t)b * H + i) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+            *reinterpret_cast<uint2 *>(h_bf16 + plane_stride + (size_t)b * H + i) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+        }
     }
 }
 
-hipError_t launch_add_rmsnorm(const float *res, const float *delta, const uint16_t *gain, float eps,
-                              int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
+hipError_t launch_add_rmsnorm(const float *res, const float *delta, int delta_splits, const uint16_t *gain,
+                              float eps, int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
                               size_t plane_stride, hipStream_t s)
 {
-    PSV_LAUNCH(k_add_rmsnorm, dim3(batch), dim3(256), 0, s, res, delta, gain, eps, H, out_res,
-                       h_f32, h_bf16, plane_stride);
+    PSV_LAUNCH(k_add_rmsnorm, dim3(batch), dim3(1024), 0, s, res, delta, delta_splits, (size_t)batch * H, gain, eps, H,
+               out_res, h_f32, h_bf16, plane_stride);
     return hipGetLastError();
 }
 
@@ -607,6 +628,232 @@ hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_
     }
 }
 
+// ------------------------------------------------------------------------------------ split-K skinny GEMM
+
+// part[ks][b][r] = sum over the K-range of split ks of W[r][k] x[b][k], for batches of 17..64 (and any
+// smaller batch).  A workgroup of 4 waves owns 128 weight rows (2 MFMA row tiles per wave) and a range of
+// 64-element K slabs.  Per slab the activations of all batch entries (hi and lo bf16 planes) are brought
+// into LDS once, in MFMA fragment order, and every wave reads its B-fragments from there, so the 16-byte
+// global loads of a wave are spent on weights only: 32 contiguous bytes per lane per row tile, i.e. whole
+// 128-byte lines of 16 rows.  Weight fragments are prefetched PF slabs ahead through a register ring and
+// the activation slab two slabs ahead, which keeps 16 KiB per wave in flight even when only a few
+// workgroups exist (small matrices at batch 64 cannot use many: every extra K split costs a partial
+// result of batch x rows floats).  Splits are summed later in split order by the consumer (k_sk_reduce or
+// k_add_rmsnorm): deterministic, no atomics.
+struct GemmSkArgs {
+    const uint16_t *W, *W2;   // rows >= split_row are taken from W2 (row - split_row): gate | up in one launch
+    int split_row;
+    const uint16_t *xb;       // hi plane [round_up(batch,16)][K], lo plane x_plane elements further
+    size_t x_plane;
+    float *part;              // [splits][batch][N]
+    int batch, N, K, n_slabs, slabs_per_block;
+};
+
+template <int NB>
+__global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
+{
+    constexpr int PF = 4;
+    __shared__ uint4 xs[2][NB * 4][64];   // [buffer][(batch tile*2 + plane)*2 + k half][lane]
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
+    const int row_base = blockIdx.x * 128 + w * 32;
+    const int s0 = blockIdx.y * a.slabs_per_block, s1 = min(s0 + a.slabs_per_block, a.n_slabs);
+    const int K = a.K;
+
+    const uint16_t *wp[2];
+    bool wok[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const int r = row_base + mt * 16 + i;
+        wok[mt] = r < a.N;
+        const int rr = wok[mt] ? r : 0;
+        wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 16;
+    }
+    struct WFrag { uint4 a0[2], a1[2]; };
+    auto load_w = [&](int s, WFrag &f) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            f.a0[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64) : zero16();
+            f.a1[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64 + 8) : zero16();
+        }
+    };
+    // activation slab: NB*256 16-byte units, unit u = ((tile*2 + plane)*16 + row)*8 + segment
+    auto load_slab = [&](int s, uint4 (&r)[NB]) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int u = tid + j * 256, n = u >> 8, p = (u >> 7) & 1, row = (u >> 3) & 15, seg = u & 7;
+            r[j] = ld16(a.xb + (size_t)p * a.x_plane + (size_t)(n * 16 + row) * K + (size_t)s * 64 + seg * 8);
+        }
+    };
+    auto store_slab = [&](int buf, const uint4 (&r)[NB]) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int u = tid + j * 256, n = u >> 8, p = (u >> 7) & 1, row = (u >> 3) & 15, seg = u & 7;
+            xs[buf][(n * 2 + p) * 2 + (seg & 1)][(seg >> 1) * 16 + row] = r[j];   // fragment order: k = g*16 + half*8 + e
+        }
+    };
+
+    f32x4 acc[2][NB];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int n = 0; n < NB; ++n) acc[mt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    WFrag wq[PF];
+#pragma unroll
+    for (int q = 0; q < PF; ++q)
+        if (s0 + q < s1) load_w(s0 + q, wq[q]);
+    uint4 xr[2][NB];
+    if (s0 < s1) {
+        load_slab(s0, xr[0]);
+        if (s0 + 1 < s1) load_slab(s0 + 1, xr[1]);
+        store_slab(0, xr[0]);
+    }
+    __syncthreads();
+
+    for (int sb = s0; sb < s1; sb += PF) {
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            const int s = sb + q;
+            if (s < s1) {                       // uniform over the workgroup
+                const int buf = q & 1;          // (s - s0) & 1, because PF is even
+                if (s + 2 < s1) load_slab(s + 2, xr[q & 1]);
+#pragma unroll
+                for (int n = 0; n < NB; ++n) {
+                    const bf16x8 bh0 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 0) * 2 + 0][lane]);
+                    const bf16x8 bh1 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 0) * 2 + 1][lane]);
+                    const bf16x8 bl0 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 1) * 2 + 0][lane]);
+                    const bf16x8 bl1 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 1) * 2 + 1][lane]);
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt) {
+                        const bf16x8 a0 = __builtin_bit_cast(bf16x8, wq[q].a0[mt]);
+                        const bf16x8 a1 = __builtin_bit_cast(bf16x8, wq[q].a1[mt]);
+                        acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bh0, acc[mt][n], 0, 0, 0);
+                        acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bh1, acc[mt][n], 0, 0, 0);
+                        acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bl0, acc[mt][n], 0, 0, 0);
+                        acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bl1, acc[mt][n], 0, 0, 0);
+                    }
+                }
+                if (s + PF < s1) load_w(s + PF, wq[q]);
+                if (s + 1 < s1) store_slab(buf ^ 1, xr[(q + 1) & 1]);
+                __syncthreads();
+            }
+        }
+    }
+
+    // D fragment: lane holds rows 4g..4g+3 of batch column i
+    float *part = a.part + (size_t)blockIdx.y * a.batch * a.N;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const int r = row_base + mt * 16 + 4 * g;
+        if (r < a.N)
+#pragma unroll
+            for (int n = 0; n < NB; ++n) {
+                const int b = n * 16 + i;
+                if (b < a.batch)
+                    *reinterpret_cast<float4 *>(part + (size_t)b * a.N + r) =
+                        make_float4(acc[mt][n][0], acc[mt][n][1], acc[mt][n][2], acc[mt][n][3]);
+            }
+    }
+}
+
+// Number of K splits, from a small cost model of the kernel: a workgroup needs ~0.6 us per slab it walks
+// (latency of one pipelined slab step), 512 workgroups are resident at a time, and weights plus partial
+// results (written once, read back once) stream at ~4 TB/s.  More splits shorten the walk and cost partial
+// traffic of batch * N * 8 bytes each; small matrices at batch 64 end up with 4-16 splits, wide ones at
+// small batch with as many as keep every CU busy.
+int gemm_sk_splits(int batch, int N, int K)
+{
+    const int n_slabs = K / 64;
+    const double row_groups = (double)((N + 127) / 128);
+    const double w_bytes = 2.0 * N * K, part_bytes = 8.0 * batch * N;
+    int best = 1;
+    double best_cost = 1e30;
+    for (int ks = 1; ks <= kSkMaxSplits && ks * 2 <= n_slabs; ++ks) {
+        const int spb = (n_slabs + ks - 1) / ks;
+        const int real = (n_slabs + spb - 1) / spb;
+        if (real != ks) continue;
+        const double rounds = (double)(long long)((row_groups * ks + 511) / 512);
+        const double cost = rounds * spb * 0.6 + (w_bytes + ks * part_bytes) / 4.0e6;
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = ks; }
+    }
+    return best;
+}
+
+bool gemm_sk_supported(int batch, int N, int K)
+{
+    return batch >= 1 && batch <= 64 && N % 16 == 0 && K % 64 == 0;
+}
+
+hipError_t launch_gemm_sk(const uint16_t *W, const uint16_t *W2, int split_row, const uint16_t *xb, float *part,
+                          int batch, int N, int K, hipStream_t s)
+{
+    const int nb = (batch + 15) / 16;
+    GemmSkArgs a{};
+    a.W = W; a.W2 = W2 ? W2 : W; a.split_row = W2 ? split_row : N; a.xb = xb; a.x_plane = (size_t)nb * 16 * K;
+    a.part = part; a.batch = batch; a.N = N; a.K = K; a.n_slabs = K / 64;
+    const int splits = gemm_sk_splits(batch, N, K);
+    a.slabs_per_block = (a.n_slabs + splits - 1) / splits;
+    const dim3 grid((N + 127) / 128, splits);
+    switch (nb) {
+    case 1: PSV_LAUNCH(k_gemm_sk<1>, grid, dim3(256), 0, s, a); break;
+    case 2: PSV_LAUNCH(k_gemm_sk<2>, grid, dim3(256), 0, s, a); break;
+    case 3: PSV_LAUNCH(k_gemm_sk<3>, grid, dim3(256), 0, s, a); break;
+    case 4: PSV_LAUNCH(k_gemm_sk<4>, grid, dim3(256), 0, s, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// out[b][n] = sum over splits (split order) of part[ks][b][n]; with SwiGLU the N columns are gate | up
+// halves and the result is silu(gate) * up, [batch][N/2], stored as fp32 and as hi/lo bf16 planes.
+template <bool SWIGLU>
+__global__ __launch_bounds__(256) void k_sk_reduce(const float *__restrict__ part, int splits, int batch, int N,
+                                                   float *__restrict__ out, uint16_t *__restrict__ out_bf16, size_t out_plane)
+{
+    const int NO = SWIGLU ? N / 2 : N;                 // output columns
+    const size_t total4 = (size_t)batch * NO / 4;
+    const size_t split_stride = (size_t)batch * N;
+    for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < total4; q += (size_t)gridDim.x * 256) {
+        const size_t e = q * 4, b = e / NO, c = e % NO;
+        const float *p = part + b * N + c;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f), u = v;
+        for (int ks = 0; ks < splits; ++ks) {
+            const float4 t = *reinterpret_cast<const float4 *>(p + ks * split_stride);
+            v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
+            if (SWIGLU) {
+                const float4 t2 = *reinterpret_cast<const float4 *>(p + ks * split_stride + NO);
+                u.x += t2.x; u.y += t2.y; u.z += t2.z; u.w += t2.w;
+            }
+        }
+        if (SWIGLU) {
+            v.x = silu_mul(v.x, u.x); v.y = silu_mul(v.y, u.y); v.z = silu_mul(v.z, u.z); v.w = silu_mul(v.w, u.w);
+        }
+        *reinterpret_cast<float4 *>(out + b * NO + c) = v;
+        if (out_bf16) {
+            uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+            split_bf16(v.x, h0, l0); split_bf16(v.y, h1, l1); split_bf16(v.z, h2, l2); split_bf16(v.w, h3, l3);
+            *reinterpret_cast<uint2 *>(out_bf16 + b * NO + c) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+            *reinterpret_cast<uint2 *>(out_bf16 + out_plane + b * NO + c) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+        }
+    }
+}
+
+hipError_t launch_sk_reduce(const float *part, int splits, int batch, int N, bool swiglu, float *out,
+                            uint16_t *out_bf16, hipStream_t s)
+{
+    const int NO = swiglu ? N / 2 : N;
+    const size_t total4 = (size_t)batch * NO / 4;
+    unsigned blocks = (unsigned)((total4 + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
+    const size_t out_plane = (size_t)((batch + 15) / 16 * 16) * NO;
+    if (swiglu)
+        PSV_LAUNCH(k_sk_reduce<true>, dim3(blocks), dim3(256), 0, s, part, splits, batch, N, out, out_bf16, out_plane);
+    else
+        PSV_LAUNCH(k_sk_reduce<false>, dim3(blocks), dim3(256), 0, s, part, splits, batch, N, out, out_bf16, out_plane);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------ KV addressing
 
 __device__ __forceinline__ int kv_phys_block(const int32_t *page_table, int max_blocks, int num_pool_blocks,
@@ -648,17 +895,20 @@ hipError_t launch_rope_table(const int32_t *seq_lens, const double *inv_freq, in
 
 AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq)
 {
-    // Aim at ~4096 waves over the whole launch, at least one 32-token tile per wave.
-    uint64_t tiles = (uint64_t)batch * n_kv_heads * ((max_seq + kAttnTileTokens - 1) / kAttnTileTokens);
-    uint64_t per_wave = (tiles + 4095) / 4096;
-    if (per_wave < 1) per_wave = 1;
-    AttnSplit sp;
+    // The attention kernel keeps 3 workgroups resident per CU (register bound): aim at no more than 768
+    // workgroups, i.e. one resident round without a tail, with whole 4-tile (128-token) steps per chunk
+    // and at most kAttnMaxChunks chunks per (sequence, kv head).
     const int unit = kAttnTileTokens * kAttnWaves;
-    sp.chunk_tokens = (int)(per_wave * unit);
-    // at most kAttnMaxChunks partials per (sequence, kv head): the final merge keeps their weights in LDS
-    const int floor_chunk = (int)(((max_seq + kAttnMaxChunks - 1) / kAttnMaxChunks + unit - 1) / unit * unit);
-    if (sp.chunk_tokens < floor_chunk) sp.chunk_tokens = floor_chunk;
-    sp.n_chunks = (int)((max_seq + sp.chunk_tokens - 1) / sp.chunk_tokens);
+    const uint64_t seqs = (uint64_t)batch * n_kv_heads;
+    uint64_t max_chunks = 768 / (seqs ? seqs : 1);
+    if (max_chunks < 1) max_chunks = 1;
+    if (max_chunks > (uint64_t)kAttnMaxChunks) max_chunks = kAttnMaxChunks;
+    uint64_t chunk = ((uint64_t)max_seq + max_chunks - 1) / max_chunks;
+    chunk = (chunk + unit - 1) / unit * unit;
+    if (chunk < (uint64_t)unit) chunk = unit;
+    AttnSplit sp;
+    sp.chunk_tokens = (int)chunk;
+    sp.n_chunks = (int)((max_seq + chunk - 1) / chunk);
     if (sp.n_chunks < 1) sp.n_chunks = 1;
     return sp;
 }
