@@ -28,10 +28,12 @@ def parse():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2")
     ap.add_argument("--layers", type=int, default=0, help="materialise only the first N layers (0 = all)")
-    ap.add_argument("--budget-mb", type=float, default=64.0, help="Algorithm 1's capacity C")
+    ap.add_argument("--budget-mb", type=float, default=0.0,
+                    help="Algorithm 1's capacity C; 0 = what the prefetch kernel can pull inside one window "
+                         "(window us x 4.5 MB/us), capped at 192 MB of the 256 MB Infinity Cache")
     ap.add_argument("--chunk-mb", type=float, default=0.0)
     ap.add_argument("--cu-budget", type=int, default=256)
-    ap.add_argument("--partial", type=int, default=0)
+    ap.add_argument("--partial", type=int, default=-1, help="-1 = on for paged workloads (KV per layer exceeds any budget)")
     ap.add_argument("--join", type=int, default=0)
     ap.add_argument("--targets", type=int, default=3)
     ap.add_argument("--graph", type=int, default=0, help="1 = replay the step as a HIP graph")
@@ -39,6 +41,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = auto)")
     ap.add_argument("--seed", type=int, default=2501)
+    ap.add_argument("--contiguous", action="store_true", help="force a contiguous (unpaged) KV cache")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="also launch one plain copy kernel of this size (known bytes, to scale hardware counters)")
     ap.add_argument("--skip-kernel-table", action="store_true", help="omit the per-operator event timing passes")
@@ -122,10 +125,16 @@ def main():
     w = synth.WORKLOADS[a.workload]
     if a.window_us is not None:
         w = w.scaled(window_us=tuple(a.window_us))
+    if a.contiguous:
+        w = w.scaled(paged=False)
     layers = list(range(a.layers)) if a.layers else None
     sess = Session(w, seed=a.seed, layers=layers)
     L = len(sess.layers)
     MB = 1 << 20
+    if a.budget_mb <= 0:
+        a.budget_mb = min(192.0, max(w.window_us) * 4.5)
+    if a.partial < 0:
+        a.partial = 1 if w.paged else 0
     on = psv.prefetch_policy(mode=1, targets=a.targets, budget_bytes=int(a.budget_mb * MB),
                              chunk_bytes=int(a.chunk_mb * MB), cu_budget=a.cu_budget, partial=a.partial, join=a.join)
     off = psv.prefetch_policy(mode=0)

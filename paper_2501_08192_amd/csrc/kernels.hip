@@ -6,6 +6,7 @@
 // cores (16x16x32 bf16 MFMA) are used where a vector-ALU formulation would bind on arithmetic
 // (batch > 4 projections, grouped-query attention).
 #include <hip/hip_ext.h>
+#include <stdlib.h>
 
 #include "internal.h"
 
@@ -906,6 +907,7 @@ AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq)
     uint64_t chunk = ((uint64_t)max_seq + max_chunks - 1) / max_chunks;
     chunk = (chunk + unit - 1) / unit * unit;
     if (chunk < (uint64_t)unit) chunk = unit;
+    if (const char *e = getenv("PSV_ATTN_CHUNK")) chunk = (uint64_t)atoi(e);
     AttnSplit sp;
     sp.chunk_tokens = (int)chunk;
     sp.n_chunks = (int)((max_seq + chunk - 1) / chunk);
