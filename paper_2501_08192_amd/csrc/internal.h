@@ -17,6 +17,7 @@ namespace psv {
 constexpr int kAttnTileTokens = 32;
 constexpr int kAttnWaves = 4;
 constexpr int kAttnMaxChunks = 256;
+constexpr int kAttnResident = 768;    // workgroups of the attention kernel resident on the chip at a time (3 per CU)
 
 struct AttnSplit {
     int chunk_tokens;   // tokens per workgroup

@@ -901,13 +901,12 @@ AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq)
     // and at most kAttnMaxChunks chunks per (sequence, kv head).
     const int unit = kAttnTileTokens * kAttnWaves;
     const uint64_t seqs = (uint64_t)batch * n_kv_heads;
-    uint64_t max_chunks = 768 / (seqs ? seqs : 1);
+    uint64_t max_chunks = kAttnResident / (seqs ? seqs : 1);
     if (max_chunks < 1) max_chunks = 1;
     if (max_chunks > (uint64_t)kAttnMaxChunks) max_chunks = kAttnMaxChunks;
     uint64_t chunk = ((uint64_t)max_seq + max_chunks - 1) / max_chunks;
     chunk = (chunk + unit - 1) / unit * unit;
     if (chunk < (uint64_t)unit) chunk = unit;
-    if (const char *e = getenv("PSV_ATTN_CHUNK")) chunk = (uint64_t)atoi(e);
     AttnSplit sp;
     sp.chunk_tokens = (int)chunk;
     sp.n_chunks = (int)((max_seq + chunk - 1) / chunk);
@@ -1262,12 +1261,12 @@ hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsig
 // Reads memory with 16-byte loads and throws the data away: the loads allocate the lines in the
 // memory-side cache (Infinity Cache).  Nothing is written.  One launch serves a whole communication
 // window: up to kPrefetchRegions linear regions (projection weights) plus a range of KV blocks that
-// is walked through the page table.  The grid size is the CU budget of the policy.
+// is walked through the page table.  The grid size is the CU budget of the policy; 16 x 16-byte loads are in flight per thread.
 __device__ __forceinline__ uint32_t fold(uint4 v) { return v.x ^ v.y ^ v.z ^ v.w; }
 
 __global__ __launch_bounds__(256) void k_prefetch(PrefetchJob j)
 {
-    constexpr int U = 8;
+    constexpr int U = 16;
     if (j.skip && *j.skip) return;   // the gate kernel ahead of this launch found the window already over
     const uint64_t stride = (uint64_t)gridDim.x * 256;
     const uint64_t me = (uint64_t)blockIdx.x * 256 + threadIdx.x;
@@ -1275,15 +1274,18 @@ __global__ __launch_bounds__(256) void k_prefetch(PrefetchJob j)
     for (int r = 0; r < j.n_regions; ++r) {
         const uint4 *p = reinterpret_cast<const uint4 *>(j.ptr[r]);
         const uint64_t n16 = j.n16[r];
-        uint64_t i = me;
-        for (; i + (U - 1) * stride < n16; i += U * stride) {
+        // batches of U independent loads per thread; the ragged end of a region is predicated rather than
+        // peeled into a one-load-at-a-time loop, so a region costs one round trip per batch, tail included
+        for (uint64_t base = me; base < n16; base += U * stride) {
             uint4 v[U];
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[u] = p[i + u * stride];
+            for (int u = 0; u < U; ++u) {
+                const uint64_t idx = base + u * stride;
+                v[u] = idx < n16 ? p[idx] : zero16();
+            }
 #pragma unroll
             for (int u = 0; u < U; ++u) sink ^= fold(v[u]);
         }
-        for (; i < n16; i += stride) sink ^= fold(p[i]);
     }
     if (j.kv_count) {
         // one wave per logical block: K part and V part of every kv head (4 KiB each per head)
