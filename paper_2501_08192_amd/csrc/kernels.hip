@@ -61,11 +61,28 @@ __device__ __forceinline__ void split_bf16(float v, uint32_t &hi, uint32_t &lo)
     lo = f32_to_bf16(v - __uint_as_float(hi << 16));
 }
 
+// Sum over the 64 lanes of a wave, returned in every lane.  Four DPP steps (quad swaps, half-row and row
+// mirrors: VALU only, no LDS crossbar traffic) leave the sum of each 16-lane row in all of its lanes; the
+// four row sums are then read through scalar registers.  Must be called with all lanes active.  A
+// ds_bpermute butterfly does the same in six LDS-pipe round trips per value, which cost ~2 us per GEMV.
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float v)
+{
+    const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
+    return v + __int_as_float(t);
+}
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
-    return v;
+    v = dpp_add<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_add<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_add<0x141>(v);   // row_half_mirror
+    v = dpp_add<0x140>(v);   // row_mirror
+    const int iv = __float_as_int(v);
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(iv, 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(iv, 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(iv, 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(iv, 48));
+    return (r0 + r1) + (r2 + r3);
 }
 
 __device__ __forceinline__ uint4 ld16(const uint16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
@@ -653,7 +670,7 @@ struct GemmSkArgs {
 template <int NB>
 __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
 {
-    constexpr int PF = 4;
+    constexpr int PF = 4;   // slabs of weight fragments in flight per wave (8 measured no faster)
     __shared__ uint4 xs[2][NB * 4][64];   // [buffer][(batch tile*2 + plane)*2 + k half][lane]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
     const int row_base = blockIdx.x * 128 + w * 32;
