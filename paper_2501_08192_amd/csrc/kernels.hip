@@ -971,9 +971,50 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     if (T < 0 || T > kv.max_blocks * 16) T = 0;
     const int t_begin = c * a.chunk_tokens;
     const int t_end = min(T, t_begin + a.chunk_tokens);
-    const int n_valid_blocks = (T + 15) >> 4;
     const float *qkv_b = a.qkv + (size_t)b * qkv_rows;
     const float2 *rope_b = a.rope + b * 64;
+
+    // ---- K/V tile loader.  The addresses depend on the page table only, not on the sequence length (tokens
+    //      past the span are masked later, and every logical block below max_blocks maps into the pool), so
+    //      each wave issues the loads of its first tile right away, ahead of everything else in the kernel.
+    const int tau1 = 8 * (i >> 2) + (i & 3);          // token (within the 32-token group) of K row i, tile 1
+    uint4 ka[4], kb[4], vf[8];
+    auto load_tile = [&](int t0) {
+        const int lb = t0 >> 4;
+        const int blkA = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb);
+        const int blkB = (lb + 1 < kv.max_blocks)
+                             ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb + 1) : -1;
+        // K fragments: tile 1 row i = token tau1, tile 2 row i = token tau1 + 4
+        {
+            const int blk = (i < 8) ? blkA : blkB;
+            if (blk >= 0) {
+                const uint16_t *base = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + (tau1 & 15)) * 128 + q4 * 8;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) {
+                    ka[ks] = ld16(base + ks * 32);
+                    kb[ks] = ld16(base + 4 * 128 + ks * 32);
+                }
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) { ka[ks] = zero16(); kb[ks] = zero16(); }
+            }
+        }
+        // V^T fragments: row = channel dg*16 + i, k-slots of lane group q4 = tokens 8*q4 .. 8*q4+7
+        {
+            const int blk = (q4 < 2) ? blkA : blkB;
+            if (blk >= 0) {
+                const uint16_t *base = kv.v_pool + (((size_t)blk * nkv + kvh) * 128 + i) * 16 + (q4 & 1) * 8;
+#pragma unroll
+                for (int dg = 0; dg < 8; ++dg) vf[dg] = ld16(base + dg * 16 * 16);
+            } else {
+#pragma unroll
+                for (int dg = 0; dg < 8; ++dg) vf[dg] = zero16();
+            }
+        }
+    };
+    const int t_first = t_begin + w * kAttnTileTokens;
+    const bool early = t_first < kv.max_blocks * 16;
+    if (early) load_tile(t_first);
 
     // ---- Q fragments, rotated: lane (g = i, q4) holds channels ks*32 + q4*8 + e; channel f < 64
     //      pairs with f + 64, i.e. fragment ks with fragment ks + 2 of the same lane.
@@ -1026,6 +1067,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
             __threadfence();
         }
         __syncthreads();   // uniform: the condition depends on the workgroup only
+        if (early && T - 1 >= t_first && T - 1 < t_first + kAttnTileTokens) load_tile(t_first);   // now with the new entry
     }
 
     const float kScale = 0.08838834764831845f * 1.4426950408889634f;   // 1/sqrt(128) * log2(e)
@@ -1034,41 +1076,8 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 #pragma unroll
     for (int dg = 0; dg < 8; ++dg) acc[dg] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const int tau1 = 8 * (i >> 2) + (i & 3);          // token (within the 32-token group) of K row i, tile 1
-    for (int t0 = t_begin + w * kAttnTileTokens; t0 < t_end; t0 += kAttnWaves * kAttnTileTokens) {
-        const int lb = t0 >> 4;
-        const int blkA = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb);
-        const int blkB = (lb + 1 < n_valid_blocks)
-                             ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb + 1) : -1;
-        // K fragments: tile 1 row i = token tau1, tile 2 row i = token tau1 + 4
-        uint4 ka[4], kb[4];
-        {
-            const int blk = (i < 8) ? blkA : blkB;
-            if (blk >= 0) {
-                const uint16_t *base = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + (tau1 & 15)) * 128 + q4 * 8;
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) {
-                    ka[ks] = ld16(base + ks * 32);
-                    kb[ks] = ld16(base + 4 * 128 + ks * 32);
-                }
-            } else {
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks) { ka[ks] = zero16(); kb[ks] = zero16(); }
-            }
-        }
-        // V^T fragments: row = channel dg*16 + i, k-slots of lane group q4 = tokens 8*q4 .. 8*q4+7
-        uint4 vf[8];
-        {
-            const int blk = (q4 < 2) ? blkA : blkB;
-            if (blk >= 0) {
-                const uint16_t *base = kv.v_pool + (((size_t)blk * nkv + kvh) * 128 + i) * 16 + (q4 & 1) * 8;
-#pragma unroll
-                for (int dg = 0; dg < 8; ++dg) vf[dg] = ld16(base + dg * 16 * 16);
-            } else {
-#pragma unroll
-                for (int dg = 0; dg < 8; ++dg) vf[dg] = zero16();
-            }
-        }
+    for (int t0 = t_first; t0 < t_end; t0 += kAttnWaves * kAttnTileTokens) {
+        if (t0 != t_first || !early) load_tile(t0);
 
         f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
