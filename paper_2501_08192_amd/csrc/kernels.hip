@@ -135,11 +135,16 @@ __global__ __launch_bounds__(1024) void k_add_rmsnorm(const float *__restrict__ 
             v[q] = *reinterpret_cast<const float4 *>(r + i);
             if (gain) gv[q] = *reinterpret_cast<const uint2 *>(gain + i);
             if (d) {
-                float4 e = *reinterpret_cast<const float4 *>(d + i);
-                for (int ks = 1; ks < delta_splits; ++ks) {     // split-K partials of the projection, split order
-                    const float4 t = *reinterpret_cast<const float4 *>(d + ks * delta_stride + i);
-                    e.x += t.x; e.y += t.y; e.z += t.z; e.w += t.w;
-                }
+                // split-K partials of the projection: all loads first (their latencies overlap), then the
+                // sum in split order
+                float4 t[kSkMaxSplits];
+#pragma unroll
+                for (int ks = 0; ks < kSkMaxSplits; ++ks)
+                    t[ks] = ks < delta_splits ? *reinterpret_cast<const float4 *>(d + ks * delta_stride + i)
+                                              : make_float4(0.f, 0.f, 0.f, 0.f);
+                float4 e = t[0];
+#pragma unroll
+                for (int ks = 1; ks < kSkMaxSplits; ++ks) { e.x += t[ks].x; e.y += t[ks].y; e.z += t[ks].z; e.w += t[ks].w; }
                 v[q].x += e.x; v[q].y += e.y; v[q].z += e.z; v[q].w += e.w;
             }
             *reinterpret_cast<float4 *>(o + i) = v[q];
@@ -840,14 +845,21 @@ __global__ __launch_bounds__(256) void k_sk_reduce(const float *__restrict__ par
     for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < total4; q += (size_t)gridDim.x * 256) {
         const size_t e = q * 4, b = e / NO, c = e % NO;
         const float *p = part + b * N + c;
-        float4 v = make_float4(0.f, 0.f, 0.f, 0.f), u = v;
-        for (int ks = 0; ks < splits; ++ks) {
-            const float4 t = *reinterpret_cast<const float4 *>(p + ks * split_stride);
-            v.x += t.x; v.y += t.y; v.z += t.z; v.w += t.w;
-            if (SWIGLU) {
-                const float4 t2 = *reinterpret_cast<const float4 *>(p + ks * split_stride + NO);
-                u.x += t2.x; u.y += t2.y; u.z += t2.z; u.w += t2.w;
-            }
+        // all split loads first (their latencies overlap), then the sums in split order
+        float4 t[kSkMaxSplits], t2[SWIGLU ? kSkMaxSplits : 1];
+#pragma unroll
+        for (int ks = 0; ks < kSkMaxSplits; ++ks) {
+            t[ks] = ks < splits ? *reinterpret_cast<const float4 *>(p + ks * split_stride) : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (SWIGLU)
+                t2[ks] = ks < splits ? *reinterpret_cast<const float4 *>(p + ks * split_stride + NO)
+                                     : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        float4 v = t[0], u = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (SWIGLU) u = t2[0];
+#pragma unroll
+        for (int ks = 1; ks < kSkMaxSplits; ++ks) {
+            v.x += t[ks].x; v.y += t[ks].y; v.z += t[ks].z; v.w += t[ks].w;
+            if (SWIGLU) { u.x += t2[ks].x; u.y += t2[ks].y; u.z += t2[ks].z; u.w += t2[ks].w; }
         }
         if (SWIGLU) {
             v.x = silu_mul(v.x, u.x); v.y = silu_mul(v.y, u.y); v.z = silu_mul(v.z, u.z); v.w = silu_mul(v.w, u.w);
