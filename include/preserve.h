@@ -202,6 +202,15 @@ psv_status psv_sync(psv_ctx *ctx);
 
 psv_status psv_get_stats(psv_ctx *ctx, psv_stats *out);
 
+/* Checks that work on stream_side really runs beside work on stream_main.  HIP multiplexes streams
+ * onto a few hardware queues; two streams that land on the same queue execute one after the other,
+ * and a prefetch can then never overlap its window.  The check runs a 1 ms window kernel on
+ * stream_main and a gate on stream_side that waits for the window's start flag, and times on the
+ * host how long stream_side takes to drain: *concurrent = 1 if the gate got through in under half
+ * the window, 0 if it had to wait for the window's end (then create the context again with another
+ * side stream).  Synchronises both streams. */
+psv_status psv_check_overlap(psv_ctx *ctx, int32_t *concurrent);
+
 /* ---- measurement and test aids ---------------------------------------------------------- */
 
 /* When op is a PSV_OP_* id (not PSV_OP_UP: gate and up share one kernel), every later eager-mode

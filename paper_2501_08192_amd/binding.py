@@ -19,7 +19,7 @@ PSV_DBG_H1, PSV_DBG_QKV, PSV_DBG_ATTN, PSV_DBG_Y, PSV_DBG_H2, PSV_DBG_M = range(
 EXPORTS = [
     "psv_strerror", "psv_validate_desc", "psv_workspace_bytes", "psv_plan_chain", "psv_create", "psv_destroy",
     "psv_set_layer_weights", "psv_set_kv", "psv_set_comm_windows", "psv_set_policy", "psv_plan",
-    "psv_set_graph_mode", "psv_decode_step", "psv_sync", "psv_get_stats", "psv_set_profile_op",
+    "psv_set_graph_mode", "psv_decode_step", "psv_sync", "psv_get_stats", "psv_check_overlap", "psv_set_profile_op",
     "psv_get_profile", "psv_prefetch_region", "psv_spin", "psv_copy_bytes", "psv_debug_read",
 ]
 
@@ -94,6 +94,7 @@ def lib():
             "psv_decode_step": (C.c_int32, [vp, vp, vp, u32, u32, u32]),
             "psv_sync": (C.c_int32, [vp]),
             "psv_get_stats": (C.c_int32, [vp, C.POINTER(psv_stats)]),
+            "psv_check_overlap": (C.c_int32, [vp, C.POINTER(C.c_int32)]),
             "psv_set_profile_op": (C.c_int32, [vp, C.c_int32]),
             "psv_get_profile": (C.c_int32, [vp, C.POINTER(C.c_double), C.POINTER(u64)]),
             "psv_prefetch_region": (C.c_int32, [vp, u64, u32, vp]),
@@ -220,6 +221,12 @@ def psv_get_stats(ctx):
     s = psv_stats()
     _check(lib().psv_get_stats(ctx, C.byref(s)), "psv_get_stats")
     return {n: getattr(s, n) for n, _ in psv_stats._fields_ if n != "reserved"}
+
+
+def psv_check_overlap(ctx):
+    out = C.c_int32(0)
+    _check(lib().psv_check_overlap(ctx, C.byref(out)), "psv_check_overlap")
+    return bool(out.value)
 
 
 def psv_set_profile_op(ctx, op):

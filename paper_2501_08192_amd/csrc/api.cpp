@@ -11,6 +11,7 @@
 
 #include <new>
 #include <utility>
+#include <chrono>
 #include <vector>
 
 #include "internal.h"
@@ -342,7 +343,10 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
 
     // Small batches run every projection on the vector ALU with the normalisation fused into the
     // prologue; larger ones use the matrix cores (split-K GEMM + reductions) with a separate normalisation.
-    const bool vec = gemv_supported(B, QR, H) && gemv_supported(B, H, QD) && gemv_supported(B, F, H) && gemv_supported(B, H, F);
+    // (Measured crossover: the vector path loses ~10 us per layer and extra batch row to register pressure;
+    // batch 1 always wins there, batch 2 only on the 8B-sized matrices.)
+    const bool vec = (B == 1 || (B == 2 && H <= 4096)) && gemv_supported(B, QR, H) && gemv_supported(B, H, QD) &&
+                     gemv_supported(B, F, H) && gemv_supported(B, H, F);
     const bool sk = !vec && !c->old_mfma;
     float *part = c->at<float>(c->ws.part);
 
@@ -646,11 +650,30 @@ psv_status psv_get_stats(psv_ctx *c, psv_stats *out)
     out->kv_bytes_per_layer = (uint64_t)batch * context * c->d.n_kv_heads * c->d.head_dim * 2 * 2;
     for (const psv_plan_entry &e : c->plan) out->planned_prefetch_bytes += e.bytes;
     out->workspace_bytes = c->ws.total;
-    const bool vec = batch <= 4 && c->d.hidden <= 8192 && c->d.ffn <= 8192;
+    const bool vec = (batch == 1 || (batch == 2 && c->d.hidden <= 4096)) && c->d.hidden <= 8192 && c->d.ffn <= 8192;
     out->kernels_per_layer = (vec ? 5 : 7) + (c->window_us[0] > 0.f ? 1 : 0) + (c->window_us[1] > 0.f ? 1 : 0);
     out->prefetch_launches = c->last_prefetch_launches;
     out->steps = c->steps;
     return PSV_OK;
+}
+
+psv_status psv_check_overlap(psv_ctx *c, int32_t *concurrent)
+{
+    if (!c || !concurrent) return PSV_ERR_INVALID_ARG;
+    psv_status st = psv_sync(c);
+    if (st != PSV_OK) return st;
+    unsigned *flag = c->at<unsigned>(c->ws.flag);
+    const unsigned seq = ++c->window_seq;
+    // A gate that shares a hardware queue with the spin starts only once the spin has ended: time, on the host,
+    // how long the side stream takes to drain while a 1 ms window runs on the main stream.
+    const float us = 1000.f;
+    const auto t0 = std::chrono::steady_clock::now();
+    HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), flag, seq, c->main));
+    HIP_TRY(launch_gate(flag, seq, 1u << 20, c->clock_khz * 4 /* 4 ms */, flag + 16, c->side));
+    HIP_TRY(hipStreamSynchronize(c->side));
+    const double waited_us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
+    *concurrent = waited_us < 0.5 * us ? 1 : 0;
+    return psv_sync(c);
 }
 
 psv_status psv_set_profile_op(psv_ctx *c, int32_t op)

@@ -47,7 +47,7 @@ hipError_t launch_add_rmsnorm(const float *res, const float *delta, int delta_sp
                               float eps, int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
                               size_t plane_stride, hipStream_t s);
 
-// Vector-ALU GEMV for batch <= 4:  out[b][r] = sum_k W[r][k] * x[b][k]   (fp32 x, bf16 W).
+// Vector-ALU GEMV for batch <= 2:  out[b][r] = sum_k W[r][k] * x[b][k]   (fp32 x, bf16 W).
 // W2 != null selects the SwiGLU form: out[b][r] = silu(W[r].x[b]) * (W2[r].x[b]).
 hipError_t launch_gemv(const uint16_t *W, const uint16_t *W2, const float *x, float *out, int batch, int N, int K,
                        hipStream_t s);
@@ -59,7 +59,7 @@ hipError_t launch_gemv_norm(const uint16_t *W, const uint16_t *W2, const float *
 bool gemv_supported(int batch, int N, int K);
 // O projection with the attention merge in its prologue: x = merged split-K partials (K = nq*128).
 // out_attn (optional) receives the merged attention output.  Usable for few chunks only.
-constexpr int kGemvMergeMaxChunks = 32;
+constexpr int kGemvMergeMaxChunks = 16;
 bool gemv_merge_supported(int batch, int nq, int n_chunks);
 hipError_t launch_gemv_merge(const uint16_t *W, const float *part_ml, const float *part_o, int nq, int nkv,
                              int n_chunks, float *out_attn, float *out, int batch, int N, hipStream_t s);

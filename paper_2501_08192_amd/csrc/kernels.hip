@@ -188,7 +188,7 @@ hipError_t launch_add_rmsnorm(const float *res, const float *delta, int delta_sp
 
 // ------------------------------------------------------------------------------------ GEMV
 
-// Weight-streaming GEMV on the vector ALU (batch NB <= 4).
+// Weight-streaming GEMV on the vector ALU (batch NB <= 2).
 //
 // A workgroup has 512 (merge mode: 256) threads, cut into groups of GS = 64..512 threads such that one 16-byte load
 // per thread covers a whole weight row (K <= 8*GS; ITERS = 2 loads for K up to 8192).  A thread
@@ -445,7 +445,7 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
 
 bool gemv_supported(int batch, int N, int K)
 {
-    return batch >= 1 && batch <= 4 && K % 8 == 0 && K >= 64 && K <= 8192 && N >= 1;
+    return batch >= 1 && batch <= 2 && K % 8 == 0 && K >= 64 && K <= 8192 && N >= 1;
 }
 
 // Workgroup size: 512 threads, except for the merge mode, whose prologue is repeated by every group of
@@ -490,9 +490,7 @@ static hipError_t gemv_dispatch(const GemvArgs &a, int batch, hipStream_t s)
     switch (batch) {
     case 1: return gemv_pick<1, MODE>(a, s);
     case 2: return gemv_pick<2, MODE>(a, s);
-    case 3: return gemv_pick<3, MODE>(a, s);
-    case 4: return gemv_pick<4, MODE>(a, s);
-    default: return hipErrorInvalidValue;
+    default: return hipErrorInvalidValue;   // larger batches run on the matrix cores
     }
 }
 
@@ -516,7 +514,7 @@ hipError_t launch_gemv_norm(const uint16_t *W, const uint16_t *W2, const float *
 
 bool gemv_merge_supported(int batch, int nq, int n_chunks)
 {
-    return batch >= 1 && batch <= 4 && nq * 128 <= 4096 && n_chunks <= kGemvMergeMaxChunks;
+    return batch >= 1 && batch <= 2 && nq * 128 <= 4096 && n_chunks <= kGemvMergeMaxChunks;
 }
 
 hipError_t launch_gemv_merge(const uint16_t *W, const float *part_ml, const float *part_o, int nq, int nkv,

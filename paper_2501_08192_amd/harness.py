@@ -21,11 +21,22 @@ class Session:
         torch.cuda.set_device(self.device)
         self.layers = list(range(w.n_layers)) if layers is None else list(layers)
         self.max_seq = (w.context + 15) // 16 * 16
-        self.main = torch.cuda.Stream(device=self.device)
-        self.side = torch.cuda.Stream(device=self.device)
         self.desc = psv.model_desc(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch, self.max_seq,
                                    head_dim=w.head_dim, rms_eps=w.rms_eps, rope_theta=w.rope_theta)
-        self.ctx = psv.psv_create(self.desc, self.main, self.side)
+        # HIP maps streams onto a few hardware queues; take a side stream that really runs beside the main one
+        self.main = torch.cuda.Stream(device=self.device)
+        self.overlap = False
+        self._spare_streams = []
+        for _ in range(8):
+            self.side = torch.cuda.Stream(device=self.device)
+            self.ctx = psv.psv_create(self.desc, self.main, self.side)
+            self.overlap = psv.psv_check_overlap(self.ctx)
+            if self.overlap:
+                break
+            psv.psv_destroy(self.ctx)
+            self._spare_streams.append(self.side)
+        else:
+            self.ctx = psv.psv_create(self.desc, self.main, self.side)
         self.pool_blocks = w.pool_blocks + int(pool_slack_blocks)
         self.weights, self.k_pools, self.v_pools = {}, {}, {}
         for l in self.layers:

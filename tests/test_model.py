@@ -1,0 +1,50 @@
+"""The analytic latency model (paper Section 5, re-parameterised): consistency with the library's planner and
+the qualitative behaviour the paper and the measurements show.  CPU only."""
+import pytest
+
+from paper_2501_08192_amd import binding as psv
+from paper_2501_08192_amd import model, synth
+
+
+def _bytes(w):
+    return model.op_bytes(w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch, w.context)
+
+
+@pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
+@pytest.mark.parametrize("budget_mb", [8, 64, 192])
+def test_model_plan_matches_library_planner(name, budget_mb):
+    w = synth.WORKLOADS[name].scaled(n_layers=2)
+    b = _bytes(w)
+    # the library counts the read-only span (context - 1); feed the model the same number
+    b["attn"] = w.batch * (w.context - 1) * w.n_kv_heads * w.head_dim * 4
+    budget = budget_mb << 20
+    d = psv.model_desc(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch, w.context)
+    plan = psv.psv_plan_chain(d, w.batch, w.context, psv.prefetch_policy(mode=1, budget_bytes=budget, partial=1))
+    lib = {psv.OP_NAMES[e["target_op"]]: e["bytes"] for e in plan if e["layer"] == 0}
+    mod = {k: v for k, v in model.plan_windows(b, budget).items() if v > 0}
+    assert lib == {k: int(v) for k, v in mod.items()}
+
+
+def test_prefetch_off_is_the_plain_sum():
+    w = synth.WORKLOADS["c2"]
+    b, m = _bytes(w), model.Machine()
+    want = 5 * m.t_fixed + sum(b.values()) / m.bw_hbm + sum(w.window_us)
+    assert model.layer_time(b, w.window_us, m, 0.0) == pytest.approx(want)
+
+
+def test_speedup_has_a_knee_at_window_capacity_and_at_cache_capacity():
+    w = synth.WORKLOADS["c5"]
+    b, m = _bytes(w), model.Machine()
+    short = [model.speedup(b, (5.0, 5.0), m, c * 1e6) for c in (16, 64, 192)]
+    assert short[0] > short[2]                       # a short window is overrun by a large prefetch
+    long_ = [model.speedup(b, (50.0, 50.0), m, c * 1e6) for c in (16, 64, 192, 600)]
+    assert long_[0] < long_[1] < long_[2]            # a long window rewards a larger budget ...
+    assert long_[3] <= long_[2]                      # ... up to the cache capacity
+    assert model.speedup(b, (0.0, 0.0), m, 192e6) <= 1.0 + 1e-12    # nothing to hide behind
+
+
+def test_best_budget_grows_with_the_window():
+    w = synth.WORKLOADS["c5"]
+    b, m = _bytes(w), model.Machine()
+    picks = [model.best_budget(b, (x, x), m) for x in (5.0, 20.0, 50.0)]
+    assert picks[0] <= picks[1] <= picks[2] and picks[0] < picks[2]
