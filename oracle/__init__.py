@@ -1,4 +1,4 @@
-"""ctypes front-end of the C oracle (oracle/preserve_oracle.c).
+"""ctypes front-end of the C oracle (oracle/preserve_oracle.c, oracle/preserve_oracle_q8.c).
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the CPU-baseline leg of
 bench.py; never by the GPU package.  bf16 tensors are numpy uint16 arrays holding the raw bits;
@@ -32,6 +32,17 @@ class _KV(C.Structure):
                 ("max_blocks", C.c_int32), ("seq_lens", C.c_void_p)]
 
 
+class _LayerWeightsX(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in
+                ("w_qkv", "w_o", "w_gate", "w_up", "w_down", "s_qkv", "s_o", "s_gate", "s_up", "s_down",
+                 "g_attn", "g_mlp")]
+
+
+class _KVX(C.Structure):
+    _fields_ = [("k_pool", C.c_void_p), ("v_pool", C.c_void_p), ("kv_int8", C.c_int32),
+                ("page_table", C.c_void_p), ("max_blocks", C.c_int32), ("seq_lens", C.c_void_p)]
+
+
 def lib():
     global _lib
     if _lib is None:
@@ -57,6 +68,16 @@ def lib():
         L.orc_decode_layer.restype = C.c_int
         L.orc_decode_layer.argtypes = [C.POINTER(_Model), C.POINTER(_LayerWeights), C.POINTER(_KV),
                                        C.c_int, C.c_void_p]
+        L.orc_linear_q8.restype = None
+        L.orc_linear_q8.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        L.orc_quantize_row.restype = None
+        L.orc_quantize_row.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.orc_attention_head_q8.restype = None
+        L.orc_attention_head_q8.argtypes = [C.POINTER(_Model), C.POINTER(_KVX), C.c_int, C.c_int,
+                                            C.c_void_p, C.c_void_p]
+        L.orc_decode_layer_x.restype = C.c_int
+        L.orc_decode_layer_x.argtypes = [C.POINTER(_Model), C.POINTER(_LayerWeightsX), C.POINTER(_KVX),
+                                         C.c_int, C.c_void_p]
         L.orc_plan.restype = C.c_int64
         L.orc_plan.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_uint64,
                                C.c_void_p, C.c_void_p, C.c_int64]
@@ -189,6 +210,119 @@ def decode_step(m, layers, k_pools, v_pools, page_table, max_blocks, seq_lens, x
     xx = _f64(x).copy()
     for lw, kp, vp in zip(layers, k_pools, v_pools):
         xx = decode_layer(m, lw, kp, vp, page_table, max_blocks, seq_lens, xx)
+    return xx
+
+
+# ---- int8 variant ------------------------------------------------------------------------
+
+def kv_unit_bytes(m) -> int:
+    """Bytes of one (block, kv head) unit of an int8 pool: codes, then one fp32 scale per token."""
+    return m.block_tokens * m.head_dim + 4 * m.block_tokens
+
+
+def linear_q8(codes, scale, vec):
+    w = np.ascontiguousarray(codes)
+    if w.dtype != np.int8:
+        raise TypeError("int8 weights expected, got %s" % w.dtype)
+    sc = np.ascontiguousarray(scale, dtype=np.float32)
+    v = _f64(vec)
+    rows, cols = w.shape
+    assert v.shape == (cols,) and sc.shape == (rows,)
+    out = np.empty(rows, dtype=np.float64)
+    lib().orc_linear_q8(_ptr(w), _ptr(sc), _ptr(v), rows, cols, _ptr(out))
+    return out
+
+
+def quantize_row(vec):
+    """Returns (int8 codes, fp32 scale) of the append rule."""
+    v = _f64(vec)
+    codes = np.zeros(v.size, dtype=np.int8)
+    scale = np.zeros(1, dtype=np.float32)
+    lib().orc_quantize_row(_ptr(v), v.size, 1, _ptr(codes), _ptr(scale))
+    return codes, np.float32(scale[0])
+
+
+def _pool_bytes(a, what):
+    if a.dtype == np.uint16 or a.dtype == np.uint8:
+        if not a.flags["C_CONTIGUOUS"]:
+            raise ValueError("%s must be contiguous (it is written in place)" % what)
+        return a
+    raise TypeError("%s: uint16 (bf16 bits) or uint8 (int8 layout) expected, got %s" % (what, a.dtype))
+
+
+def _kvx_struct(k_pool, v_pool, page_table, max_blocks, seq_lens):
+    kp, vp = _pool_bytes(k_pool, "k_pool"), _pool_bytes(v_pool, "v_pool")
+    if kp.dtype != vp.dtype:
+        raise TypeError("k_pool and v_pool must have the same format")
+    keep = [kp, vp, np.ascontiguousarray(seq_lens, dtype=np.int32)]
+    pt = None
+    if page_table is not None:
+        pt = np.ascontiguousarray(page_table, dtype=np.int32)
+        keep.append(pt)
+    kv = _KVX(_ptr(kp), _ptr(vp), 1 if kp.dtype == np.uint8 else 0, _ptr(pt) if pt is not None else None,
+              int(max_blocks), _ptr(keep[2]))
+    return kv, keep
+
+
+def attention_head_q8(m, k_pool, v_pool, page_table, max_blocks, seq_lens, b, q_head, q):
+    if k_pool.dtype != np.uint8:
+        raise TypeError("int8 pools are passed as uint8 byte arrays")
+    kv, keep = _kvx_struct(k_pool, v_pool, page_table, max_blocks, seq_lens)
+    qv = _f64(q)
+    out = np.empty(m.head_dim, dtype=np.float64)
+    lib().orc_attention_head_q8(C.byref(m), C.byref(kv), int(b), int(q_head), _ptr(qv), _ptr(out))
+    del keep
+    return out
+
+
+_SCALE_OF = {"w_qkv": "s_qkv", "w_o": "s_o", "w_gate": "s_gate", "w_up": "s_up", "w_down": "s_down"}
+
+
+def decode_layer_x(m, weights, k_pool, v_pool, page_table, max_blocks, seq_lens, x):
+    """One decoder layer with bf16 weights (uint16 arrays) or int8 weights (int8 arrays plus fp32 per-row
+    scales under s_qkv, s_o, s_gate, s_up, s_down), over a bf16 cache (uint16 pools) or an int8 cache (uint8
+    pools with embedded scales).  Pools are updated in place."""
+    int8_w = weights["w_qkv"].dtype == np.int8
+    keep = []
+    ptrs = {}
+    for n in ("w_qkv", "w_o", "w_gate", "w_up", "w_down"):
+        a = np.ascontiguousarray(weights[n])
+        if a.dtype != (np.int8 if int8_w else np.uint16):
+            raise TypeError("%s: mixed weight formats" % n)
+        keep.append(a)
+        ptrs[n] = _ptr(a)
+        if int8_w:
+            sc = np.ascontiguousarray(weights[_SCALE_OF[n]], dtype=np.float32)
+            assert sc.shape == (a.shape[0],)
+            keep.append(sc)
+            ptrs[_SCALE_OF[n]] = _ptr(sc)
+        else:
+            ptrs[_SCALE_OF[n]] = None
+    for n in ("g_attn", "g_mlp"):
+        a = _u16(weights[n])
+        keep.append(a)
+        ptrs[n] = _ptr(a)
+    qkv_rows = (m.n_q_heads + 2 * m.n_kv_heads) * m.head_dim
+    assert weights["w_qkv"].shape == (qkv_rows, m.hidden)
+    assert weights["w_o"].shape == (m.hidden, m.n_q_heads * m.head_dim)
+    assert weights["w_gate"].shape == (m.ffn, m.hidden) and weights["w_up"].shape == (m.ffn, m.hidden)
+    assert weights["w_down"].shape == (m.hidden, m.ffn)
+    lw = _LayerWeightsX(*[ptrs[n] for n, _ in _LayerWeightsX._fields_])
+    kv, keep2 = _kvx_struct(k_pool, v_pool, page_table, max_blocks, seq_lens)
+    xx = _f64(x).copy()
+    batch = xx.shape[0]
+    assert xx.shape == (batch, m.hidden)
+    rc = lib().orc_decode_layer_x(C.byref(m), C.byref(lw), C.byref(kv), batch, _ptr(xx))
+    del keep, keep2
+    if rc != 0:
+        raise ValueError("orc_decode_layer_x rejected its arguments (rc=%d)" % rc)
+    return xx
+
+
+def decode_step_x(m, layers, k_pools, v_pools, page_table, max_blocks, seq_lens, x):
+    xx = _f64(x).copy()
+    for lw, kp, vp in zip(layers, k_pools, v_pools):
+        xx = decode_layer_x(m, lw, kp, vp, page_table, max_blocks, seq_lens, xx)
     return xx
 
 

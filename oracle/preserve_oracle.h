@@ -84,6 +84,49 @@ int orc_decode_step(const orc_model *m, int n_layers, const orc_layer_weights *w
                     const int32_t *page_table, int32_t max_blocks, const int32_t *seq_lens,
                     int batch, double *x);
 
+/* ---- int8 variant -------------------------------------------------------------------------
+ *
+ * The paper's measurements store weights and KV-cache in int8 (Section 4, experimental set-up and
+ * the captions of its result tables) but give no quantisation scheme; this is the one assumed here.
+ *
+ * Weights: int8 codes [rows][cols] row-major and one fp32 scale per output row;
+ *          W[r][c] = scale[r] * code[r][c].
+ * KV-cache: one fp32 scale per (token, kv head).  A block of one kv head is bt*d code bytes followed
+ *          by bt fp32 scales (2048 + 64 bytes for bt = 16, d = 128); a pool block is n_kv_heads of
+ *          those.  K codes are [token][channel], V codes [channel][token], as in the bf16 layout.
+ *          K[t][c] = k_scale[t] * code[t][c]; likewise V.
+ * Append rule (orc_quantize_row), taken in single precision because it decides integers:
+ *          vf = (float)v;  amax = max|vf|;  scale = amax > 0 ? amax / 127 : 1;
+ *          code = clamp(rintf(vf / scale), -127, 127)     (ties to even).
+ * Activations stay in floating point (the paper also quantises them; only the bytes streamed from
+ * memory matter to the method, and those are weights and KV).
+ */
+void orc_linear_q8(const int8_t *codes, const float *scale, const double *in, int rows, int cols,
+                   double *out);
+void orc_quantize_row(const double *v, int n, int stride, int8_t *codes, float *scale);
+
+typedef struct {
+    const void *w_qkv, *w_o, *w_gate, *w_up, *w_down;        /* bf16 or int8 codes, shapes as above */
+    const float *s_qkv, *s_o, *s_gate, *s_up, *s_down;        /* per-row scales; NULL => bf16 weights */
+    const uint16_t *g_attn, *g_mlp;                           /* bf16 [H] */
+} orc_layer_weights_x;
+
+typedef struct {
+    void *k_pool, *v_pool;       /* bf16 pools, or int8 pools with embedded scales */
+    int32_t kv_int8;             /* 0 => bf16 layout, 1 => int8 layout */
+    const int32_t *page_table;
+    int32_t max_blocks;
+    const int32_t *seq_lens;
+} orc_kv_x;
+
+/* One (sequence, query head) of decode attention over an int8 cache. */
+void orc_attention_head_q8(const orc_model *m, const orc_kv_x *kv, int b, int q_head,
+                           const double *q, double *out);
+
+/* One decoder layer with either weight format and either cache format. */
+int orc_decode_layer_x(const orc_model *m, const orc_layer_weights_x *w, const orc_kv_x *kv,
+                       int batch, double *x);
+
 /* ---- Algorithm 1 (prefetch operator insertion) on a general graph ---- */
 enum { ORC_NODE_OTHER = 0, ORC_NODE_COMM = 1, ORC_NODE_MATMUL = 2, ORC_NODE_SELFATTN = 3 };
 
