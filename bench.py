@@ -42,6 +42,9 @@ def parse():
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = auto)")
     ap.add_argument("--seed", type=int, default=2501)
     ap.add_argument("--contiguous", action="store_true", help="force a contiguous (unpaged) KV cache")
+    ap.add_argument("--format", default="bf16", choices=["bf16", "int8", "w8", "kv8"],
+                    help="storage format of weights and KV-cache: bf16 (the benchmark's), int8 (both, the paper's "
+                         "measurement precision), w8 / kv8 (only the weights / only the cache in int8)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="also launch one plain copy kernel of this size (known bytes, to scale hardware counters)")
     ap.add_argument("--skip-kernel-table", action="store_true", help="omit the per-operator event timing passes")
@@ -91,7 +94,7 @@ def cpu_baseline(sess, n_layers, target_s=10.0, max_reps=40):
         x = x0
         t0 = time.perf_counter()
         for lw, kp, vp in host:
-            x = oracle.decode_layer(m, lw, kp, vp, pt, w.blocks_per_seq, lens, x)
+            x = oracle.decode_layer_x(m, lw, kp, vp, pt, w.blocks_per_seq, lens, x)
         total += time.perf_counter() - t0
         reps += 1
     return total * 1e6 / (reps * len(host)), len(host), reps, oracle.num_threads()
@@ -127,6 +130,9 @@ def main():
         w = w.scaled(window_us=tuple(a.window_us))
     if a.contiguous:
         w = w.scaled(paged=False)
+    if a.format != "bf16":
+        w = w.scaled(weight_format="int8" if a.format in ("int8", "w8") else "bf16",
+                     kv_format="int8" if a.format in ("int8", "kv8") else "bf16")
     layers = list(range(a.layers)) if a.layers else None
     sess = Session(w, seed=a.seed, layers=layers)
     L = len(sess.layers)
@@ -159,9 +165,10 @@ def main():
     # per-operator kernel durations (events attached to the kernel dispatches), prefetch off and on; the
     # dominant kernel -- gate/up projection + SwiGLU, HBM-bound -- carries the roofline entry
     qkv_rows = (w.n_q_heads + 2 * w.n_kv_heads) * w.head_dim
-    op_bytes = {"qkv": 2 * qkv_rows * w.hidden, "attn": stats["kv_bytes_per_layer"],
-                "o": 2 * w.hidden * w.n_q_heads * w.head_dim, "gate_up": 2 * 2 * w.ffn * w.hidden,
-                "down": 2 * w.hidden * w.ffn}
+    wb = 1 if w.weight_format == "int8" else 2          # bytes per weight
+    op_bytes = {"qkv": wb * qkv_rows * w.hidden, "attn": stats["kv_bytes_per_layer"],
+                "o": wb * w.hidden * w.n_q_heads * w.head_dim, "gate_up": wb * 2 * w.ffn * w.hidden,
+                "down": wb * w.hidden * w.ffn}
     op_ids = {"qkv": psv.PSV_OP_QKV, "attn": psv.PSV_OP_ATTN, "o": psv.PSV_OP_O, "gate_up": psv.PSV_OP_GATE,
               "down": psv.PSV_OP_DOWN}
     n_prof = max(3, min(a.steps, 10))
@@ -199,7 +206,8 @@ def main():
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16",
+        "dtype": "bf16" if a.format == "bf16" else "%s (storage: %s weights, %s KV; fp32 accumulation)" % (
+            a.format, w.weight_format, w.kv_format),
         "data": "synthetic",
         "config": {"workload": "%s: %d layers, hidden %d, %d q / %d kv heads x 128, ffn %d, batch %d, context %d, %s KV, "
                                "windows %g/%g us" % (w.name, L, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch,
@@ -217,7 +225,7 @@ def main():
                                                 "frac_on": round(eff_on / HBM_PEAK_GBPS, 4)},
         "roofline": {"bound": "hbm", "kernel": "gate/up projection + SwiGLU (prefetch off)",
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": stored_traffic(w.name, "gate_up"),
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": stored_traffic(w.name, "gate_up") if a.format == "bf16" else None,
                      "bytes_per_launch": gate_bytes, "avg_us": round(gate_us, 3), "launches": gate_n,
                      "avg_us_prefetch_on": round(gate_us_on, 3),
                      "achieved_prefetch_on": round(gate_bytes / gate_us_on / 1e3, 1)},

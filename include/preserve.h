@@ -22,6 +22,15 @@
  *    [block][kv head][16 tokens][128 channels] and one V pool [block][kv head][128 channels]
  *    [16 tokens].  Token t of sequence b lives in block page_table[b*max_blocks + t/16], or in
  *    block b*max_blocks + t/16 when the page table is NULL ("contiguous" cache).
+ *  - int8 formats (the precision the paper measures in, Section 4; it gives no quantisation scheme, this
+ *    one is symmetric and per row).  Weights (weight_format = PSV_FMT_INT8): int8 codes row-major
+ *    [out, in] plus one fp32 scale per output row, W[r][c] = scale[r] * code[r][c]; RMSNorm gains stay
+ *    bf16.  KV-cache (kv_format = PSV_FMT_INT8): one fp32 scale per (token, kv head); the unit of one
+ *    (block, kv head) is 2048 code bytes (K: [16 tokens][128 channels], V: [128 channels][16 tokens])
+ *    followed by the 16 fp32 scales of its tokens = PSV_KV_UNIT_BYTES_INT8 bytes, and a pool block is
+ *    n_kv_heads units.  The step quantises the key and value rows it appends in single precision:
+ *    scale = max|v| / 127 (1 if the row is zero), code = clamp(rint(v / scale), -127, 127), ties to
+ *    even.  Activations stay in floating point.
  *  - seq_lens[b] is the attention span INCLUDING the token decoded by the step: the step
  *    writes slot seq_lens[b]-1 of every layer's cache and attends over [0, seq_lens[b]).
  *    It never changes seq_lens or the page table, so repeating a call is idempotent.
@@ -42,6 +51,10 @@ extern "C" {
 
 #define PSV_BLOCK_TOKENS 16u
 #define PSV_HEAD_DIM 128u
+#define PSV_KV_UNIT_BYTES_BF16 4096u   /* one (block, kv head) of a bf16 K or V pool */
+#define PSV_KV_UNIT_BYTES_INT8 2112u   /* 2048 int8 codes + 16 fp32 scales */
+
+enum { PSV_FMT_BF16 = 0u, PSV_FMT_INT8 = 1u };
 
 typedef int32_t psv_status;
 enum {
@@ -55,7 +68,7 @@ enum {
 
 typedef struct psv_ctx psv_ctx;   /* opaque */
 
-/* Shape of one shard.  hidden % 512 == 0, ffn % 256 == 0, head_dim == 128,
+/* Shape and storage formats of one shard.  hidden % 512 == 0, ffn % 256 == 0, head_dim == 128,
  * n_q_heads % n_kv_heads == 0, n_q_heads / n_kv_heads <= 16, max_seq % 16 == 0. */
 typedef struct {
     uint32_t n_layers;
@@ -68,9 +81,11 @@ typedef struct {
     float    rope_theta;    /* 0 => rotary embedding disabled */
     uint32_t max_batch;
     uint32_t max_seq;       /* largest seq_lens[b] that will be used */
+    uint32_t weight_format; /* PSV_FMT_BF16 or PSV_FMT_INT8: format of the five projection matrices */
+    uint32_t kv_format;     /* PSV_FMT_BF16 or PSV_FMT_INT8: format of the K and V pools */
 } psv_model_desc;
 
-/* dev pointers, bf16 */
+/* dev pointers; projection matrices in the descriptor's weight_format, gains bf16 */
 typedef struct {
     const void *w_qkv;      /* [(nq+2nkv)*128, H]  rows: q heads, then k heads, then v heads */
     const void *w_o;        /* [H, nq*128] */
@@ -79,6 +94,9 @@ typedef struct {
     const void *w_down;     /* [H, F] */
     const void *g_attn;     /* [H]  RMSNorm gain before the attention block */
     const void *g_mlp;      /* [H]  RMSNorm gain before the MLP block */
+    /* fp32 per-output-row scales of the int8 format, same row order as the matrices; ignored
+     * (may be NULL) for bf16 weights */
+    const float *s_qkv, *s_o, *s_gate, *s_up, *s_down;
 } psv_layer_weights;
 
 typedef struct {
@@ -149,7 +167,8 @@ size_t psv_workspace_bytes(const psv_model_desc *desc);
  * per layer  norm, QKV, rope, attention, O, COMM, norm, gate, up, act, down, COMM.
  * For every communication op the operators that follow it, up to the next communication op or
  * the end of the graph, are visited in program order; a MatMul contributes its weight bytes,
- * the attention its read-only K+V bytes (batch * (context-1) tokens); an operator receives a
+ * the attention its read-only K+V bytes (batch * (context-1) tokens; int8 caches include their
+ * scales), both in the descriptor's formats; an operator receives a
  * prefetch while the running sum stays strictly below policy->budget_bytes; the first one that
  * does not fit ends that window.  Operators whose class is not in policy->targets are visited
  * but neither counted nor prefetched.  mode == 0 yields an empty plan.

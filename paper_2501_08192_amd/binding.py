@@ -14,6 +14,9 @@ PSV_OK, PSV_ERR_INVALID_ARG, PSV_ERR_BAD_STATE, PSV_ERR_UNSUPPORTED, PSV_ERR_HIP
 PSV_TARGET_WEIGHTS, PSV_TARGET_KV = 1, 2
 PSV_OP_QKV, PSV_OP_ATTN, PSV_OP_O, PSV_OP_GATE, PSV_OP_UP, PSV_OP_DOWN = range(6)
 OP_NAMES = ["qkv", "attn", "o", "gate", "up", "down"]
+PSV_FMT_BF16, PSV_FMT_INT8 = 0, 1
+FORMATS = {"bf16": PSV_FMT_BF16, "int8": PSV_FMT_INT8}
+PSV_KV_UNIT_BYTES_BF16, PSV_KV_UNIT_BYTES_INT8 = 4096, 2112
 PSV_DBG_H1, PSV_DBG_QKV, PSV_DBG_ATTN, PSV_DBG_Y, PSV_DBG_H2, PSV_DBG_M = range(6)
 
 EXPORTS = [
@@ -28,11 +31,12 @@ class psv_model_desc(C.Structure):
     _fields_ = [("n_layers", C.c_uint32), ("hidden", C.c_uint32), ("n_q_heads", C.c_uint32),
                 ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32), ("ffn", C.c_uint32),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("max_batch", C.c_uint32),
-                ("max_seq", C.c_uint32)]
+                ("max_seq", C.c_uint32), ("weight_format", C.c_uint32), ("kv_format", C.c_uint32)]
 
 
 class psv_layer_weights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("w_qkv", "w_o", "w_gate", "w_up", "w_down", "g_attn", "g_mlp")]
+    _fields_ = [(n, C.c_void_p) for n in ("w_qkv", "w_o", "w_gate", "w_up", "w_down", "g_attn", "g_mlp",
+                                          "s_qkv", "s_o", "s_gate", "s_up", "s_down")]
 
 
 class psv_kv_desc(C.Structure):
@@ -134,9 +138,9 @@ def strerror(status):
 
 
 def model_desc(n_layers, hidden, n_q_heads, n_kv_heads, ffn, max_batch, max_seq, head_dim=128, rms_eps=1e-5,
-               rope_theta=500000.0):
+               rope_theta=500000.0, weight_format="bf16", kv_format="bf16"):
     return psv_model_desc(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, rms_eps, rope_theta, max_batch,
-                          max_seq)
+                          max_seq, FORMATS[weight_format], FORMATS[kv_format])
 
 
 def prefetch_policy(mode=0, targets=PSV_TARGET_WEIGHTS | PSV_TARGET_KV, budget_bytes=0, chunk_bytes=0, cu_budget=0,
@@ -176,8 +180,9 @@ def psv_destroy(ctx):
 
 
 def psv_set_layer_weights(ctx, layer, weights):
-    """weights: dict name -> bf16 device tensor (w_qkv, w_o, w_gate, w_up, w_down, g_attn, g_mlp)."""
-    w = psv_layer_weights(*[_dev_ptr(weights[n]) for n, _ in psv_layer_weights._fields_])
+    """weights: dict name -> device tensor: w_qkv, w_o, w_gate, w_up, w_down (bf16, or int8 codes), g_attn, g_mlp
+    (bf16) and, for int8 weights, the fp32 per-row scales s_qkv, s_o, s_gate, s_up, s_down."""
+    w = psv_layer_weights(*[_dev_ptr(weights.get(n)) for n, _ in psv_layer_weights._fields_])
     _check(lib().psv_set_layer_weights(ctx, layer, C.byref(w)), "psv_set_layer_weights")
 
 

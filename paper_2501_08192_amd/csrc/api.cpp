@@ -148,6 +148,7 @@ KvView kv_view(const psv_ctx *c, uint32_t layer)
     KvView v;
     v.k_pool = static_cast<uint16_t *>(c->k_pools[layer]);
     v.v_pool = static_cast<uint16_t *>(c->v_pools[layer]);
+    v.int8 = c->d.kv_format == PSV_FMT_INT8 ? 1 : 0;
     v.page_table = c->kv.page_table;
     v.max_blocks = (int)c->kv.max_blocks;
     v.num_pool_blocks = (int)c->kv.num_pool_blocks;
@@ -185,6 +186,22 @@ psv_status projection_mfma(psv_ctx *c, const void *W, const void *W2, const uint
     HIP_TRY(launch_gemm_mfma(static_cast<const uint16_t *>(W), static_cast<const uint16_t *>(W2), x_bf16, out, out_bf16,
                              batch, N, K, c->main));
     return PSV_OK;
+}
+
+// Projection matrix `op` of a layer in the context's weight format.
+Mat mat_of(const psv_ctx *c, const psv_layer_weights &w, uint32_t op)
+{
+    const bool q8 = c->d.weight_format == PSV_FMT_INT8;
+    Mat m;
+    switch (op) {
+    case PSV_OP_QKV: m.w = w.w_qkv; m.scale = q8 ? w.s_qkv : nullptr; break;
+    case PSV_OP_O: m.w = w.w_o; m.scale = q8 ? w.s_o : nullptr; break;
+    case PSV_OP_GATE: m.w = w.w_gate; m.scale = q8 ? w.s_gate : nullptr; break;
+    case PSV_OP_UP: m.w = w.w_up; m.scale = q8 ? w.s_up : nullptr; break;
+    case PSV_OP_DOWN: m.w = w.w_down; m.scale = q8 ? w.s_down : nullptr; break;
+    default: break;
+    }
+    return m;
 }
 
 const void *weight_ptr(const psv_layer_weights &w, uint32_t op)
@@ -263,7 +280,8 @@ psv_status add_entry(psv_ctx *c, JobBuilder &jb, const psv_plan_entry &e, uint32
         const uint32_t ro_tokens = c->plan_context > 0 ? c->plan_context - 1 : 0;
         const uint32_t blocks_per_seq = (ro_tokens + PSV_BLOCK_TOKENS - 1) / PSV_BLOCK_TOKENS;
         if (blocks_per_seq == 0) return PSV_OK;
-        const uint64_t bytes_per_block = (uint64_t)c->d.n_kv_heads * PSV_BLOCK_TOKENS * PSV_HEAD_DIM * 2 * 2;
+        const uint64_t unit = c->d.kv_format == PSV_FMT_INT8 ? PSV_KV_UNIT_BYTES_INT8 : PSV_KV_UNIT_BYTES_BF16;
+        const uint64_t bytes_per_block = (uint64_t)c->d.n_kv_heads * unit * 2;   // K and V
         const uint64_t total = (uint64_t)batch * blocks_per_seq;
         uint64_t count = (e.bytes + bytes_per_block - 1) / bytes_per_block;
         if (count > total) count = total;
@@ -339,6 +357,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     bool side_used = false;
     c->last_prefetch_launches = 0;
     auto u16 = [](const void *p) { return static_cast<const uint16_t *>(p); };
+    const bool w8 = d.weight_format == PSV_FMT_INT8;
     const size_t plane_h = (size_t)((B + 15) / 16 * 16) * H;   // hi -> lo plane distance of the bf16 activations
 
     // Small batches run every projection on the vector ALU with the normalisation fused into the
@@ -348,6 +367,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     const bool vec = (B == 1 || (B == 2 && H <= 4096)) && gemv_supported(B, QR, H) && gemv_supported(B, H, QD) &&
                      gemv_supported(B, F, H) && gemv_supported(B, H, F);
     const bool sk = !vec && !c->old_mfma;
+    if (!vec && !sk && w8) return PSV_ERR_UNSUPPORTED;   // the older matrix-core kernel reads bf16 weights only
     float *part = c->at<float>(c->ws.part);
 
     ST_TRY(prof_tag(c, -2));
@@ -357,6 +377,8 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     for (uint32_t l = lb; l < le; ++l) {
         const psv_layer_weights &w = c->weights[l];
         const KvView kv = kv_view(c, l);
+        const Mat Wqkv = mat_of(c, w, PSV_OP_QKV), Wo = mat_of(c, w, PSV_OP_O), Wg = mat_of(c, w, PSV_OP_GATE),
+                  Wu = mat_of(c, w, PSV_OP_UP), Wd = mat_of(c, w, PSV_OP_DOWN);
 
         if (!vec) {
             ST_TRY(prof_tag(c, -2));
@@ -364,12 +386,12 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         }
         ST_TRY(prof_tag(c, PSV_OP_QKV));
         if (vec) {
-            HIP_TRY(launch_gemv_norm(u16(w.w_qkv), nullptr, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H, s));
+            HIP_TRY(launch_gemv_norm(Wqkv, Mat{}, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H, s));
         } else if (sk) {
             if (!gemm_sk_supported(B, QR, H)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(u16(w.w_qkv), nullptr, 0, h1b, part, B, QR, H, s));
+            HIP_TRY(launch_gemm_sk(Wqkv, Mat{}, 0, h1b, part, B, QR, H, s));
             ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H), B, QR, false, qkv, nullptr, s));
+            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H, w8), B, QR, false, qkv, nullptr, s));
         } else {
             ST_TRY(projection_mfma(c, w.w_qkv, nullptr, h1b, qkv, nullptr, B, QR, H));
         }
@@ -386,14 +408,14 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         const float *attn_delta = delta_a;
         int attn_splits = 1;
         if (fuse_merge) {
-            HIP_TRY(launch_gemv_merge(u16(w.w_o), pml, po, nq, nkv, sp.n_chunks, attn, delta_a, B, H, s));
+            HIP_TRY(launch_gemv_merge(Wo, pml, po, nq, nkv, sp.n_chunks, attn, delta_a, B, H, s));
         } else if (vec) {
-            HIP_TRY(launch_gemv(u16(w.w_o), nullptr, attn, delta_a, B, H, QD, s));
+            HIP_TRY(launch_gemv(Wo, Mat{}, attn, delta_a, B, H, QD, s));
         } else if (sk) {
             if (!gemm_sk_supported(B, H, QD)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(u16(w.w_o), nullptr, 0, attnb, part, B, H, QD, s));
+            HIP_TRY(launch_gemm_sk(Wo, Mat{}, 0, attnb, part, B, H, QD, s));
             attn_delta = part;
-            attn_splits = gemm_sk_splits(B, H, QD);
+            attn_splits = gemm_sk_splits(B, H, QD, w8);
         } else {
             ST_TRY(projection_mfma(c, w.w_o, nullptr, attnb, delta_a, nullptr, B, H, QD));
         }
@@ -406,12 +428,12 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         }
         ST_TRY(prof_tag(c, PSV_OP_GATE));
         if (vec) {
-            HIP_TRY(launch_gemv_norm(u16(w.w_gate), u16(w.w_up), x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H, s));
+            HIP_TRY(launch_gemv_norm(Wg, Wu, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H, s));
         } else if (sk) {
             if (!gemm_sk_supported(B, 2 * F, H)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(u16(w.w_gate), u16(w.w_up), F, h2b, part, B, 2 * F, H, s));
+            HIP_TRY(launch_gemm_sk(Wg, Wu, F, h2b, part, B, 2 * F, H, s));
             ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H), B, 2 * F, true, m, mb, s));
+            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H, w8), B, 2 * F, true, m, mb, s));
         } else {
             ST_TRY(projection_mfma(c, w.w_gate, w.w_up, h2b, m, mb, B, F, H));
         }
@@ -420,12 +442,12 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         delta = delta_m;
         delta_splits = 1;
         if (vec) {
-            HIP_TRY(launch_gemv(u16(w.w_down), nullptr, m, delta_m, B, H, F, s));
+            HIP_TRY(launch_gemv(Wd, Mat{}, m, delta_m, B, H, F, s));
         } else if (sk) {
             if (!gemm_sk_supported(B, H, F)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(u16(w.w_down), nullptr, 0, mb, part, B, H, F, s));
+            HIP_TRY(launch_gemm_sk(Wd, Mat{}, 0, mb, part, B, H, F, s));
             delta = part;
-            delta_splits = gemm_sk_splits(B, H, F);
+            delta_splits = gemm_sk_splits(B, H, F, w8);
         } else {
             ST_TRY(projection_mfma(c, w.w_down, nullptr, mb, delta_m, nullptr, B, H, F));
         }
@@ -525,6 +547,11 @@ psv_status psv_set_layer_weights(psv_ctx *c, uint32_t layer, const psv_layer_wei
     const void *ptrs[7] = {w->w_qkv, w->w_o, w->w_gate, w->w_up, w->w_down, w->g_attn, w->g_mlp};
     for (const void *p : ptrs)
         if (reinterpret_cast<uintptr_t>(p) % 16 != 0) return PSV_ERR_INVALID_ARG;
+    if (c->d.weight_format == PSV_FMT_INT8) {
+        const float *scales[5] = {w->s_qkv, w->s_o, w->s_gate, w->s_up, w->s_down};
+        for (const float *p : scales)
+            if (!p || reinterpret_cast<uintptr_t>(p) % 16 != 0) return PSV_ERR_INVALID_ARG;
+    }
     c->weights[layer] = *w;
     c->weights_set[layer] = 1;
     touch(c);
@@ -647,7 +674,7 @@ psv_status psv_get_stats(psv_ctx *c, psv_stats *out)
     for (uint32_t op = 0; op < PSV_OP_COUNT; ++op)
         if (op != PSV_OP_ATTN) wb += op_mem_size(c->d, op, batch, context);
     out->weight_bytes_per_layer = wb;
-    out->kv_bytes_per_layer = (uint64_t)batch * context * c->d.n_kv_heads * c->d.head_dim * 2 * 2;
+    out->kv_bytes_per_layer = op_mem_size(c->d, PSV_OP_ATTN, batch, context + 1);   // the whole span, new token included
     for (const psv_plan_entry &e : c->plan) out->planned_prefetch_bytes += e.bytes;
     out->workspace_bytes = c->ws.total;
     const bool vec = (batch == 1 || (batch == 2 && c->d.hidden <= 4096)) && c->d.hidden <= 8192 && c->d.ffn <= 8192;

@@ -26,12 +26,20 @@ struct AttnSplit {
 AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq);
 
 struct KvView {
-    uint16_t *k_pool;
+    uint16_t *k_pool;            // bf16 pool, or (int8 != 0) byte pool of PSV_KV_UNIT_BYTES_INT8 units
     uint16_t *v_pool;
+    int int8;
     const int32_t *page_table;   // null => contiguous
     int max_blocks;
     int num_pool_blocks;
     const int32_t *seq_lens;
+};
+
+// A projection matrix in either storage format: bf16 [rows][cols] (scale == nullptr), or int8 codes
+// [rows][cols] with one fp32 scale per row.
+struct Mat {
+    const void *w = nullptr;
+    const float *scale = nullptr;
 };
 
 // ---- kernel launchers ---------------------------------------------------------------------
@@ -47,13 +55,12 @@ hipError_t launch_add_rmsnorm(const float *res, const float *delta, int delta_sp
                               float eps, int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
                               size_t plane_stride, hipStream_t s);
 
-// Vector-ALU GEMV for batch <= 2:  out[b][r] = sum_k W[r][k] * x[b][k]   (fp32 x, bf16 W).
-// W2 != null selects the SwiGLU form: out[b][r] = silu(W[r].x[b]) * (W2[r].x[b]).
-hipError_t launch_gemv(const uint16_t *W, const uint16_t *W2, const float *x, float *out, int batch, int N, int K,
-                       hipStream_t s);
+// Vector-ALU GEMV for batch <= 2:  out[b][r] = sum_k W[r][k] * x[b][k]   (fp32 x; W bf16 or int8 + row scale).
+// W2.w != null selects the SwiGLU form: out[b][r] = silu(W[r].x[b]) * (W2[r].x[b]); same format as W.
+hipError_t launch_gemv(Mat W, Mat W2, const float *x, float *out, int batch, int N, int K, hipStream_t s);
 // Same with the activations formed in the prologue: x = rmsnorm(res + delta) * gain.  out_res
 // receives res + delta and out_h (optional) the normalised vector; neither may alias res or delta.
-hipError_t launch_gemv_norm(const uint16_t *W, const uint16_t *W2, const float *res, const float *delta,
+hipError_t launch_gemv_norm(Mat W, Mat W2, const float *res, const float *delta,
                             const uint16_t *gain, float eps, float *out_res, float *out_h, float *out, int batch,
                             int N, int K, hipStream_t s);
 bool gemv_supported(int batch, int N, int K);
@@ -61,7 +68,7 @@ bool gemv_supported(int batch, int N, int K);
 // out_attn (optional) receives the merged attention output.  Usable for few chunks only.
 constexpr int kGemvMergeMaxChunks = 16;
 bool gemv_merge_supported(int batch, int nq, int n_chunks);
-hipError_t launch_gemv_merge(const uint16_t *W, const float *part_ml, const float *part_o, int nq, int nkv,
+hipError_t launch_gemv_merge(Mat W, const float *part_ml, const float *part_o, int nq, int nkv,
                              int n_chunks, float *out_attn, float *out, int batch, int N, hipStream_t s);
 
 // MFMA skinny GEMM for any batch: same contract, x given as two bf16 planes (x = hi + lo), each
@@ -74,9 +81,9 @@ bool gemm_mfma_supported(int batch, int N, int K);
 // part[split][b][r] = partial sums of W[r].x[b] (rows >= split_row come from W2), to be summed in split
 // order by launch_sk_reduce or launch_add_rmsnorm.  x_bf16 as for launch_gemm_mfma.
 constexpr int kSkMaxSplits = 16;
-int gemm_sk_splits(int batch, int N, int K);
+int gemm_sk_splits(int batch, int N, int K, bool w8);
 bool gemm_sk_supported(int batch, int N, int K);
-hipError_t launch_gemm_sk(const uint16_t *W, const uint16_t *W2, int split_row, const uint16_t *x_bf16, float *part,
+hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *x_bf16, float *part,
                           int batch, int N, int K, hipStream_t s);
 // out = sum of the splits; swiglu: N = gate | up columns, out = silu(gate) * up of width N/2.  out_bf16
 // (optional) receives hi/lo planes.

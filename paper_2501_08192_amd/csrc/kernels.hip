@@ -8,6 +8,8 @@
 #include <hip/hip_ext.h>
 #include <stdlib.h>
 
+#include <type_traits>
+
 #include "internal.h"
 
 namespace psv {
@@ -85,8 +87,55 @@ __device__ __forceinline__ float wave_sum(float v)
     return (r0 + r1) + (r2 + r3);
 }
 
+// Maximum over the 64 lanes of a wave, returned in every lane (all lanes must be active).
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    return v;
+}
+
+// int8 code of v under `scale`: round to nearest (ties to even), clamp to [-127, 127]
+__device__ __forceinline__ uint8_t quant_i8(float v, float scale)
+{
+    float q = rintf(v / scale);
+    q = fminf(fmaxf(q, -127.0f), 127.0f);
+    return (uint8_t)(int8_t)(int)q;
+}
+
 __device__ __forceinline__ uint4 ld16(const uint16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
 __device__ __forceinline__ uint4 zero16() { return make_uint4(0u, 0u, 0u, 0u); }
+
+__device__ __forceinline__ uint2 ld8(const void *p) { return *reinterpret_cast<const uint2 *>(p); }
+
+// int8 code j (0..3) of a 32-bit word as a float
+template <int J>
+__device__ __forceinline__ float i8f(uint32_t w) { return (float)((int32_t)(w << (24 - 8 * J)) >> 24); }
+
+// dot of 8 int8 weights (one 8-byte word) with 8 fp32 activations
+__device__ __forceinline__ float dot8(uint2 w, const float (&x)[8], float acc)
+{
+    acc = fmaf(i8f<0>(w.x), x[0], acc);
+    acc = fmaf(i8f<1>(w.x), x[1], acc);
+    acc = fmaf(i8f<2>(w.x), x[2], acc);
+    acc = fmaf(i8f<3>(w.x), x[3], acc);
+    acc = fmaf(i8f<0>(w.y), x[4], acc);
+    acc = fmaf(i8f<1>(w.y), x[5], acc);
+    acc = fmaf(i8f<2>(w.y), x[6], acc);
+    acc = fmaf(i8f<3>(w.y), x[7], acc);
+    return acc;
+}
+
+// 8 int8 codes -> 8 bf16 (exact: a code has 7 significant bits) in MFMA fragment order
+__device__ __forceinline__ uint4 i8x8_to_bf16(uint32_t w0, uint32_t w1)
+{
+    // perm selector: high halves of two floats -> one packed bf16 pair
+    const uint32_t p0 = __builtin_amdgcn_perm(__float_as_uint(i8f<1>(w0)), __float_as_uint(i8f<0>(w0)), 0x07060302u);
+    const uint32_t p1 = __builtin_amdgcn_perm(__float_as_uint(i8f<3>(w0)), __float_as_uint(i8f<2>(w0)), 0x07060302u);
+    const uint32_t p2 = __builtin_amdgcn_perm(__float_as_uint(i8f<1>(w1)), __float_as_uint(i8f<0>(w1)), 0x07060302u);
+    const uint32_t p3 = __builtin_amdgcn_perm(__float_as_uint(i8f<3>(w1)), __float_as_uint(i8f<2>(w1)), 0x07060302u);
+    return make_uint4(p0, p1, p2, p3);
+}
 
 // dot of 8 bf16 weights (one 16-byte word) with 8 fp32 activations
 __device__ __forceinline__ float dot8(uint4 w, const float (&x)[8], float acc)
@@ -206,7 +255,8 @@ hipError_t launch_add_rmsnorm(const float *res, const float *delta, int delta_sp
 //   GEMV_MERGE  the attention output, merged in the prologue from the split-K partials of the attention
 //               kernel (chunk order, fixed) -- no separate merge launch; workgroup 0 stores it as well.
 struct GemvArgs {
-    const uint16_t *W, *W2;     // W2 != null: SwiGLU pair (gate, up)
+    const void *W, *W2;         // W2 != null: SwiGLU pair (gate, up); bf16, or int8 codes (template W8)
+    const float *scale, *scale2;   // int8 only: per-row scales of W and W2
     const float *x;             // [NB][K] activations (plain mode)
     const float *res, *delta;   // FUSE_NORM inputs, [NB][K]; delta may be null
     const uint16_t *gain;       // FUSE_NORM: [K]
@@ -222,10 +272,12 @@ struct GemvArgs {
 
 enum { GEMV_PLAIN = 0, GEMV_NORM = 1, GEMV_MERGE = 2 };
 
-template <int NB, int RB, int ITERS, bool SWIGLU, int MODE>
+template <int NB, int RB, int ITERS, bool SWIGLU, int MODE, bool W8>
 __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
 {
     constexpr int NW = SWIGLU ? 2 : 1;
+    constexpr int WB = W8 ? 1 : 2;                       // bytes per weight
+    using WV = typename std::conditional<W8, uint2, uint4>::type;   // 8 weights
     __shared__ float red[8][NW * RB * NB];   // [wave][value]
     __shared__ float ssq[8][NB];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -243,19 +295,36 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
         kok[it] = kk[it] < K;
     }
 
-    uint4 wv[ITERS][NW][RB];
+    WV wv[ITERS][NW][RB];
+    const char *Wb = static_cast<const char *>(a.W), *W2b = static_cast<const char *>(a.W2);
+    auto ldw = [](const char *p) {
+        if constexpr (W8) return ld8(p);
+        else return *reinterpret_cast<const uint4 *>(p);
+    };
+    // int8: the thread that will store output (row r, batch entry b) of a pass fetches that row's scale
+    // together with the pass's weights
+    const int my_r = lg / NB;
+    float sc[NW] = {};
     auto load_rows = [&](int r0) {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it)
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
                 const bool ok = kok[it] && (r0 + r < row_end);
-                wv[it][0][r] = ok ? ld16(a.W + (size_t)(r0 + r) * K + kk[it]) : zero16();
-                if (SWIGLU) wv[it][NW - 1][r] = ok ? ld16(a.W2 + (size_t)(r0 + r) * K + kk[it]) : zero16();
+                const size_t off = ((size_t)(r0 + r) * K + kk[it]) * WB;
+                wv[it][0][r] = ok ? ldw(Wb + off) : WV{};
+                if (SWIGLU) wv[it][NW - 1][r] = ok ? ldw(W2b + off) : WV{};
             }
+    };
+    auto load_scales = [&](int r0) {
+        if (W8 && lg < RB * NB && r0 + my_r < row_end) {
+            sc[0] = a.scale[r0 + my_r];
+            if (SWIGLU) sc[NW - 1] = a.scale2[r0 + my_r];
+        }
     };
     int r0 = row_begin;
     load_rows(r0);   // weights first: everything below overlaps with their flight time
+    load_scales(r0);
 
     // ---- activations into registers
     float xv[ITERS][NB][8];
@@ -403,7 +472,13 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
                 }
         const int rows_here = r0;
         r0 += RB;
-        if (pass + 1 < a.passes) load_rows(r0);   // next pass's loads fly during the reduction below
+        float sc_now[NW];
+#pragma unroll
+        for (int q = 0; q < NW; ++q) sc_now[q] = sc[q];
+        if (pass + 1 < a.passes) {   // next pass's loads fly during the reduction below
+            load_rows(r0);
+            load_scales(r0);
+        }
 
         if (wpg == 1) {
             if (lane == 0)
@@ -412,8 +487,12 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
                     if (rows_here + r < row_end)
 #pragma unroll
                         for (int b = 0; b < NB; ++b) {
-                            float v = acc[0][r][b];
-                            if (SWIGLU) v = silu_mul(v, acc[NW - 1][r][b]);
+                            float v = acc[0][r][b], u = SWIGLU ? acc[NW - 1][r][b] : 0.f;
+                            if (W8) {   // one wave per row group: a rare shape, the scale is fetched late
+                                v *= a.scale[rows_here + r];
+                                if (SWIGLU) u *= a.scale2[rows_here + r];
+                            }
+                            if (SWIGLU) v = silu_mul(v, u);
                             a.out[(size_t)b * N + rows_here + r] = v;
                         }
         } else {
@@ -432,6 +511,10 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
                     for (int w2 = 0; w2 < wpg; ++w2) {   // fixed order
                         v += red[gid * wpg + w2][r * NB + b];
                         if (SWIGLU) u += red[gid * wpg + w2][(RB + r) * NB + b];
+                    }
+                    if (W8) {
+                        v *= sc_now[0];
+                        if (SWIGLU) u *= sc_now[NW - 1];
                     }
                     if (SWIGLU) v = silu_mul(v, u);
                     a.out[(size_t)b * N + rows_here + r] = v;
@@ -452,10 +535,11 @@ bool gemv_supported(int batch, int N, int K)
 // threads that covers a row: 256 threads measured 1 us faster there.
 static constexpr int gemv_threads(int mode) { return mode == GEMV_MERGE ? 256 : 512; }
 
-template <int NB, int ITERS, bool SW, int MODE>
+template <int NB, int ITERS, bool SW, int MODE, bool W8>
 static hipError_t gemv_go(GemvArgs a, hipStream_t s)
 {
-    constexpr int RB = SW ? 4 : 8;
+    // rows per pass: as many as keep 128 bytes (x ITERS) of weight loads in flight per thread
+    constexpr int RB = (SW ? 4 : 8) * (W8 ? 2 : 1);
     const int threads = gemv_threads(MODE);
     int gs_log2 = 6;
     while ((8 << gs_log2) * ITERS < a.K && (1 << gs_log2) < threads) ++gs_log2;
@@ -471,7 +555,7 @@ static hipError_t gemv_go(GemvArgs a, hipStream_t s)
     a.gs_log2 = gs_log2;
     a.passes = (int)((max_rows + RB - 1) / RB);
     if (a.passes < 1) a.passes = 1;
-    PSV_LAUNCH((k_gemv<NB, RB, ITERS, SW, MODE>), dim3((unsigned)blocks), dim3(threads), 0, s, a);
+    PSV_LAUNCH((k_gemv<NB, RB, ITERS, SW, MODE, W8>), dim3((unsigned)blocks), dim3(threads), 0, s, a);
     return hipGetLastError();
 }
 
@@ -480,8 +564,12 @@ static hipError_t gemv_pick(const GemvArgs &a, hipStream_t s)
 {
     const int threads = gemv_threads(MODE);
     const bool sw = a.W2 != nullptr, two = a.K > 8 * threads;
-    if (two) return sw ? gemv_go<NB, 2, true, MODE>(a, s) : gemv_go<NB, 2, false, MODE>(a, s);
-    return sw ? gemv_go<NB, 1, true, MODE>(a, s) : gemv_go<NB, 1, false, MODE>(a, s);
+    if (a.scale) {
+        if (two) return sw ? gemv_go<NB, 2, true, MODE, true>(a, s) : gemv_go<NB, 2, false, MODE, true>(a, s);
+        return sw ? gemv_go<NB, 1, true, MODE, true>(a, s) : gemv_go<NB, 1, false, MODE, true>(a, s);
+    }
+    if (two) return sw ? gemv_go<NB, 2, true, MODE, false>(a, s) : gemv_go<NB, 2, false, MODE, false>(a, s);
+    return sw ? gemv_go<NB, 1, true, MODE, false>(a, s) : gemv_go<NB, 1, false, MODE, false>(a, s);
 }
 
 template <int MODE>
@@ -494,20 +582,19 @@ static hipError_t gemv_dispatch(const GemvArgs &a, int batch, hipStream_t s)
     }
 }
 
-hipError_t launch_gemv(const uint16_t *W, const uint16_t *W2, const float *x, float *out, int batch, int N, int K,
-                       hipStream_t s)
+hipError_t launch_gemv(Mat W, Mat W2, const float *x, float *out, int batch, int N, int K, hipStream_t s)
 {
     GemvArgs a{};
-    a.W = W; a.W2 = W2; a.x = x; a.out = out; a.N = N; a.K = K;
+    a.W = W.w; a.W2 = W2.w; a.scale = W.scale; a.scale2 = W2.scale; a.x = x; a.out = out; a.N = N; a.K = K;
     return gemv_dispatch<GEMV_PLAIN>(a, batch, s);
 }
 
-hipError_t launch_gemv_norm(const uint16_t *W, const uint16_t *W2, const float *res, const float *delta,
+hipError_t launch_gemv_norm(Mat W, Mat W2, const float *res, const float *delta,
                             const uint16_t *gain, float eps, float *out_res, float *out_h, float *out, int batch,
                             int N, int K, hipStream_t s)
 {
     GemvArgs a{};
-    a.W = W; a.W2 = W2; a.res = res; a.delta = delta; a.gain = gain; a.eps = eps; a.out_res = out_res; a.out_h = out_h;
+    a.W = W.w; a.W2 = W2.w; a.scale = W.scale; a.scale2 = W2.scale; a.res = res; a.delta = delta; a.gain = gain; a.eps = eps; a.out_res = out_res; a.out_h = out_h;
     a.out = out; a.N = N; a.K = K;
     return gemv_dispatch<GEMV_NORM>(a, batch, s);
 }
@@ -517,11 +604,11 @@ bool gemv_merge_supported(int batch, int nq, int n_chunks)
     return batch >= 1 && batch <= 2 && nq * 128 <= 4096 && n_chunks <= kGemvMergeMaxChunks;
 }
 
-hipError_t launch_gemv_merge(const uint16_t *W, const float *part_ml, const float *part_o, int nq, int nkv,
+hipError_t launch_gemv_merge(Mat W, const float *part_ml, const float *part_o, int nq, int nkv,
                              int n_chunks, float *out_attn, float *out, int batch, int N, hipStream_t s)
 {
     GemvArgs a{};
-    a.W = W; a.part_ml = part_ml; a.part_o = part_o; a.nkv = nkv; a.G = nq / nkv; a.nc = n_chunks; a.out_h = out_attn;
+    a.W = W.w; a.scale = W.scale; a.part_ml = part_ml; a.part_o = part_o; a.nkv = nkv; a.G = nq / nkv; a.nc = n_chunks; a.out_h = out_attn;
     a.out = out; a.N = N; a.K = nq * 128;
     return gemv_dispatch<GEMV_MERGE>(a, batch, s);
 }
@@ -668,7 +755,8 @@ hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_
 // result of batch x rows floats).  Splits are summed later in split order by the consumer (k_sk_reduce or
 // k_add_rmsnorm): deterministic, no atomics.
 struct GemmSkArgs {
-    const uint16_t *W, *W2;   // rows >= split_row are taken from W2 (row - split_row): gate | up in one launch
+    const void *W, *W2;       // rows >= split_row are taken from W2 (row - split_row): gate | up in one launch;
+    const float *scale, *scale2;   // bf16, or (template W8) int8 codes with per-row scales
     int split_row;
     const uint16_t *xb;       // hi plane [round_up(batch,16)][K], lo plane x_plane elements further
     size_t x_plane;
@@ -676,31 +764,37 @@ struct GemmSkArgs {
     int batch, N, K, n_slabs, slabs_per_block;
 };
 
-template <int NB>
+template <int NB, bool W8>
 __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
 {
-    constexpr int PF = 4;   // slabs of weight fragments in flight per wave (8 measured no faster)
+    constexpr int PF = W8 ? 8 : 4;   // slabs of weight fragments in flight per wave: 16 KiB either way
+    constexpr int WB = W8 ? 1 : 2;   // bytes per weight
     __shared__ uint4 xs[2][NB * 4][64];   // [buffer][(batch tile*2 + plane)*2 + k half][lane]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
     const int row_base = blockIdx.x * 128 + w * 32;
     const int s0 = blockIdx.y * a.slabs_per_block, s1 = min(s0 + a.slabs_per_block, a.n_slabs);
     const int K = a.K;
 
-    const uint16_t *wp[2];
+    // Lane (i, g) owns elements g*16 .. g*16+15 of row i of every 64-element slab: 32 contiguous bytes of
+    // bf16 (two fragments), or 16 bytes of int8 codes that are widened to the same two fragments on use.
+    const char *wp[2];
     bool wok[2];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
         const int r = row_base + mt * 16 + i;
         wok[mt] = r < a.N;
         const int rr = wok[mt] ? r : 0;
-        wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 16;
+        const char *base = rr < a.split_row ? static_cast<const char *>(a.W) + (size_t)rr * K * WB
+                                            : static_cast<const char *>(a.W2) + (size_t)(rr - a.split_row) * K * WB;
+        wp[mt] = base + g * 16 * WB;
     }
-    struct WFrag { uint4 a0[2], a1[2]; };
+    struct WFrag { uint4 a0[2], a1[W8 ? 1 : 2]; };   // int8: a0 holds all 16 codes
     auto load_w = [&](int s, WFrag &f) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
-            f.a0[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64) : zero16();
-            f.a1[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64 + 8) : zero16();
+            const char *p = wp[mt] + (size_t)s * 64 * WB;
+            f.a0[mt] = wok[mt] ? *reinterpret_cast<const uint4 *>(p) : zero16();
+            if constexpr (!W8) f.a1[mt] = wok[mt] ? *reinterpret_cast<const uint4 *>(p + 16) : zero16();
         }
     };
     // activation slab: NB*256 16-byte units, unit u = ((tile*2 + plane)*16 + row)*8 + segment
@@ -752,8 +846,15 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
                     const bf16x8 bl1 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 1) * 2 + 1][lane]);
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt) {
-                        const bf16x8 a0 = __builtin_bit_cast(bf16x8, wq[q].a0[mt]);
-                        const bf16x8 a1 = __builtin_bit_cast(bf16x8, wq[q].a1[mt]);
+                        bf16x8 a0, a1;
+                        if constexpr (W8) {
+                            const uint4 c = wq[q].a0[mt];
+                            a0 = __builtin_bit_cast(bf16x8, i8x8_to_bf16(c.x, c.y));
+                            a1 = __builtin_bit_cast(bf16x8, i8x8_to_bf16(c.z, c.w));
+                        } else {
+                            a0 = __builtin_bit_cast(bf16x8, wq[q].a0[mt]);
+                            a1 = __builtin_bit_cast(bf16x8, wq[q].a1[mt]);
+                        }
                         acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bh0, acc[mt][n], 0, 0, 0);
                         acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bh1, acc[mt][n], 0, 0, 0);
                         acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bl0, acc[mt][n], 0, 0, 0);
@@ -772,14 +873,19 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
         const int r = row_base + mt * 16 + 4 * g;
-        if (r < a.N)
+        if (r < a.N) {
+            float4 sc = make_float4(1.f, 1.f, 1.f, 1.f);
+            if (W8)   // split_row is a multiple of 4, so the four rows share a matrix
+                sc = r < a.split_row ? *reinterpret_cast<const float4 *>(a.scale + r)
+                                     : *reinterpret_cast<const float4 *>(a.scale2 + (r - a.split_row));
 #pragma unroll
             for (int n = 0; n < NB; ++n) {
                 const int b = n * 16 + i;
                 if (b < a.batch)
                     *reinterpret_cast<float4 *>(part + (size_t)b * a.N + r) =
-                        make_float4(acc[mt][n][0], acc[mt][n][1], acc[mt][n][2], acc[mt][n][3]);
+                        make_float4(acc[mt][n][0] * sc.x, acc[mt][n][1] * sc.y, acc[mt][n][2] * sc.z, acc[mt][n][3] * sc.w);
             }
+        }
     }
 }
 
@@ -788,11 +894,11 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
 // results (written once, read back once) stream at ~4 TB/s.  More splits shorten the walk and cost partial
 // traffic of batch * N * 8 bytes each; small matrices at batch 64 end up with 4-16 splits, wide ones at
 // small batch with as many as keep every CU busy.
-int gemm_sk_splits(int batch, int N, int K)
+int gemm_sk_splits(int batch, int N, int K, bool w8)
 {
     const int n_slabs = K / 64;
     const double row_groups = (double)((N + 127) / 128);
-    const double w_bytes = 2.0 * N * K, part_bytes = 8.0 * batch * N;
+    const double w_bytes = (w8 ? 1.0 : 2.0) * N * K, part_bytes = 8.0 * batch * N;
     int best = 1;
     double best_cost = 1e30;
     for (int ks = 1; ks <= kSkMaxSplits && ks * 2 <= n_slabs; ++ks) {
@@ -811,22 +917,33 @@ bool gemm_sk_supported(int batch, int N, int K)
     return batch >= 1 && batch <= 64 && N % 16 == 0 && K % 64 == 0;
 }
 
-hipError_t launch_gemm_sk(const uint16_t *W, const uint16_t *W2, int split_row, const uint16_t *xb, float *part,
+hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, float *part,
                           int batch, int N, int K, hipStream_t s)
 {
     const int nb = (batch + 15) / 16;
     GemmSkArgs a{};
-    a.W = W; a.W2 = W2 ? W2 : W; a.split_row = W2 ? split_row : N; a.xb = xb; a.x_plane = (size_t)nb * 16 * K;
+    a.W = W.w; a.W2 = W2.w ? W2.w : W.w; a.scale = W.scale; a.scale2 = W2.w ? W2.scale : W.scale;
+    a.split_row = W2.w ? split_row : N; a.xb = xb; a.x_plane = (size_t)nb * 16 * K;
     a.part = part; a.batch = batch; a.N = N; a.K = K; a.n_slabs = K / 64;
-    const int splits = gemm_sk_splits(batch, N, K);
+    const int splits = gemm_sk_splits(batch, N, K, W.scale != nullptr);
     a.slabs_per_block = (a.n_slabs + splits - 1) / splits;
     const dim3 grid((N + 127) / 128, splits);
-    switch (nb) {
-    case 1: PSV_LAUNCH(k_gemm_sk<1>, grid, dim3(256), 0, s, a); break;
-    case 2: PSV_LAUNCH(k_gemm_sk<2>, grid, dim3(256), 0, s, a); break;
-    case 3: PSV_LAUNCH(k_gemm_sk<3>, grid, dim3(256), 0, s, a); break;
-    case 4: PSV_LAUNCH(k_gemm_sk<4>, grid, dim3(256), 0, s, a); break;
-    default: return hipErrorInvalidValue;
+    if (W.scale) {
+        switch (nb) {
+        case 1: PSV_LAUNCH((k_gemm_sk<1, true>), grid, dim3(256), 0, s, a); break;
+        case 2: PSV_LAUNCH((k_gemm_sk<2, true>), grid, dim3(256), 0, s, a); break;
+        case 3: PSV_LAUNCH((k_gemm_sk<3, true>), grid, dim3(256), 0, s, a); break;
+        case 4: PSV_LAUNCH((k_gemm_sk<4, true>), grid, dim3(256), 0, s, a); break;
+        default: return hipErrorInvalidValue;
+        }
+    } else {
+        switch (nb) {
+        case 1: PSV_LAUNCH((k_gemm_sk<1, false>), grid, dim3(256), 0, s, a); break;
+        case 2: PSV_LAUNCH((k_gemm_sk<2, false>), grid, dim3(256), 0, s, a); break;
+        case 3: PSV_LAUNCH((k_gemm_sk<3, false>), grid, dim3(256), 0, s, a); break;
+        case 4: PSV_LAUNCH((k_gemm_sk<4, false>), grid, dim3(256), 0, s, a); break;
+        default: return hipErrorInvalidValue;
+        }
     }
     return hipGetLastError();
 }
@@ -973,6 +1090,14 @@ struct AttnArgs {
 //    exactly the B-fragment the O^T MFMA needs.  Probabilities never leave registers.
 //  * epilogue: the 4 waves merge through LDS and the workgroup stores one partial (max, sum, O);
 //    k_attn_merge then combines the partials of a (sequence, kv head) in chunk order.
+//
+// KV8 = int8 cache: a (block, kv head) unit is 2048 code bytes + 16 fp32 token scales.  A lane's K loads
+// are two 16-byte words per row (channels q4*16 .. +15 and 64 + q4*16 .. +15; the query fragments use the
+// same channel order), its V loads one 8-byte word per channel row; codes are widened to bf16 (exactly)
+// just before the MFMAs; scores are multiplied by the key scale of their token and probabilities by the
+// value scale before they become the B operand of the second contraction.  The appended rows are
+// quantised per row in single precision: scale = max|v| / 127, code = rint(v / scale).
+template <bool KV8>
 __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 {
     __shared__ float ms[kAttnWaves][16], ls[kAttnWaves][16];
@@ -994,12 +1119,48 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     //      past the span are masked later, and every logical block below max_blocks maps into the pool), so
     //      each wave issues the loads of its first tile right away, ahead of everything else in the kernel.
     const int tau1 = 8 * (i >> 2) + (i & 3);          // token (within the 32-token group) of K row i, tile 1
-    uint4 ka[4], kb[4], vf[8];
+    uint4 ka[KV8 ? 2 : 4], kb[KV8 ? 2 : 4], vf[KV8 ? 1 : 8];
+    uint2 vq[KV8 ? 8 : 1];                 // int8: V codes, 8 tokens of one channel row
+    float4 ksc[KV8 ? 2 : 1], vsc[KV8 ? 2 : 1];   // int8: key / value scales of tokens 8*q4 .. 8*q4+7
+    const uint8_t *k8 = reinterpret_cast<const uint8_t *>(kv.k_pool), *v8 = reinterpret_cast<const uint8_t *>(kv.v_pool);
     auto load_tile = [&](int t0) {
         const int lb = t0 >> 4;
         const int blkA = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb);
         const int blkB = (lb + 1 < kv.max_blocks)
                              ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb + 1) : -1;
+        if constexpr (KV8) {
+            {   // K codes: tile 1 row i = token tau1, tile 2 row i = token tau1 + 4
+                const int blk = (i < 8) ? blkA : blkB;
+                if (blk >= 0) {
+                    const uint8_t *base = k8 + ((size_t)blk * nkv + kvh) * PSV_KV_UNIT_BYTES_INT8 + (tau1 & 15) * 128 + q4 * 16;
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) {
+                        ka[j] = *reinterpret_cast<const uint4 *>(base + j * 64);
+                        kb[j] = *reinterpret_cast<const uint4 *>(base + 4 * 128 + j * 64);
+                    }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 2; ++j) { ka[j] = zero16(); kb[j] = zero16(); }
+                }
+            }
+            {   // V codes and both scale vectors: tokens 8*q4 .. 8*q4+7 of the tile
+                const int blk = (q4 < 2) ? blkA : blkB;
+                if (blk >= 0) {
+                    const size_t unit = ((size_t)blk * nkv + kvh) * PSV_KV_UNIT_BYTES_INT8;
+                    const uint8_t *base = v8 + unit + i * 16 + (q4 & 1) * 8;
+#pragma unroll
+                    for (int dg = 0; dg < 8; ++dg) vq[dg] = ld8(base + dg * 16 * 16);
+                    const float4 *ks4 = reinterpret_cast<const float4 *>(k8 + unit + 2048 + (q4 & 1) * 32);
+                    const float4 *vs4 = reinterpret_cast<const float4 *>(v8 + unit + 2048 + (q4 & 1) * 32);
+                    ksc[0] = ks4[0]; ksc[1] = ks4[1];
+                    vsc[0] = vs4[0]; vsc[1] = vs4[1];
+                } else {
+#pragma unroll
+                    for (int dg = 0; dg < 8; ++dg) vq[dg] = make_uint2(0u, 0u);
+                    ksc[0] = ksc[1] = vsc[0] = vsc[1] = make_float4(0.f, 0.f, 0.f, 0.f);
+                }
+            }
+        } else {
         // K fragments: tile 1 row i = token tau1, tile 2 row i = token tau1 + 4
         {
             const int blk = (i < 8) ? blkA : blkB;
@@ -1027,6 +1188,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                 for (int dg = 0; dg < 8; ++dg) vf[dg] = zero16();
             }
         }
+        }
     };
     const int t_first = t_begin + w * kAttnTileTokens;
     const bool early = t_first < kv.max_blocks * 16;
@@ -1042,7 +1204,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
             const float *qrow = qkv_b + (size_t)(kvh * G + i) * 128;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
-                const int f0 = ks * 32 + q4 * 8;
+                const int f0 = KV8 ? q4 * 16 + ks * 8 : ks * 32 + q4 * 8;   // same channel order as the K fragments
                 float lo[8], hi[8], rl[8], rh[8];
                 *reinterpret_cast<float4 *>(lo) = *reinterpret_cast<const float4 *>(qrow + f0);
                 *reinterpret_cast<float4 *>(lo + 4) = *reinterpret_cast<const float4 *>(qrow + f0 + 4);
@@ -1073,12 +1235,33 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                 const float *vrow = qkv_b + (size_t)(nq + nkv + kvh) * 128;
                 const float lo = krow[tid], hi = krow[tid + 64];
                 const int r = pos & 15;
-                uint16_t *kdst = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + r) * 128;
-                kdst[tid] = (uint16_t)f32_to_bf16(lo * cs.x - hi * cs.y);
-                kdst[tid + 64] = (uint16_t)f32_to_bf16(hi * cs.x + lo * cs.y);
-                uint16_t *vdst = kv.v_pool + ((size_t)blk * nkv + kvh) * 128 * 16 + r;
-                vdst[(size_t)tid * 16] = (uint16_t)f32_to_bf16(vrow[tid]);
-                vdst[(size_t)(tid + 64) * 16] = (uint16_t)f32_to_bf16(vrow[tid + 64]);
+                const float k0 = lo * cs.x - hi * cs.y, k1 = hi * cs.x + lo * cs.y;
+                const float v0 = vrow[tid], v1 = vrow[tid + 64];
+                if constexpr (KV8) {
+                    // per-row symmetric quantisation; the whole wave is here (blk is uniform)
+                    const float ka_max = wave_max(fmaxf(fabsf(k0), fabsf(k1)));
+                    const float va_max = wave_max(fmaxf(fabsf(v0), fabsf(v1)));
+                    const float ksc1 = ka_max > 0.f ? ka_max / 127.0f : 1.0f;
+                    const float vsc1 = va_max > 0.f ? va_max / 127.0f : 1.0f;
+                    const size_t unit = ((size_t)blk * nkv + kvh) * PSV_KV_UNIT_BYTES_INT8;
+                    uint8_t *kdst = reinterpret_cast<uint8_t *>(kv.k_pool) + unit;
+                    uint8_t *vdst = reinterpret_cast<uint8_t *>(kv.v_pool) + unit;
+                    kdst[r * 128 + tid] = quant_i8(k0, ksc1);
+                    kdst[r * 128 + tid + 64] = quant_i8(k1, ksc1);
+                    vdst[tid * 16 + r] = quant_i8(v0, vsc1);
+                    vdst[(tid + 64) * 16 + r] = quant_i8(v1, vsc1);
+                    if (tid == 0) {
+                        reinterpret_cast<float *>(kdst + 2048)[r] = ksc1;
+                        reinterpret_cast<float *>(vdst + 2048)[r] = vsc1;
+                    }
+                } else {
+                    uint16_t *kdst = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + r) * 128;
+                    kdst[tid] = (uint16_t)f32_to_bf16(k0);
+                    kdst[tid + 64] = (uint16_t)f32_to_bf16(k1);
+                    uint16_t *vdst = kv.v_pool + ((size_t)blk * nkv + kvh) * 128 * 16 + r;
+                    vdst[(size_t)tid * 16] = (uint16_t)f32_to_bf16(v0);
+                    vdst[(size_t)(tid + 64) * 16] = (uint16_t)f32_to_bf16(v1);
+                }
             }
             __threadfence();
         }
@@ -1098,12 +1281,25 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[ks]), qf[ks], s1, 0, 0, 0);
-            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[ks]), qf[ks], s2, 0, 0, 0);
+            bf16x8 fa, fb;
+            if constexpr (KV8) {
+                const uint4 ca = ka[ks >> 1], cb = kb[ks >> 1];
+                fa = __builtin_bit_cast(bf16x8, (ks & 1) ? i8x8_to_bf16(ca.z, ca.w) : i8x8_to_bf16(ca.x, ca.y));
+                fb = __builtin_bit_cast(bf16x8, (ks & 1) ? i8x8_to_bf16(cb.z, cb.w) : i8x8_to_bf16(cb.x, cb.y));
+            } else {
+                fa = __builtin_bit_cast(bf16x8, ka[ks]);
+                fb = __builtin_bit_cast(bf16x8, kb[ks]);
+            }
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, qf[ks], s1, 0, 0, 0);
+            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb, qf[ks], s2, 0, 0, 0);
         }
         // lane (g = i, q4) now holds tokens t0 + 8*q4 + e, e = 0..7
         float sv[8];
         const int tl = t0 + 8 * q4;
+        if constexpr (KV8) {   // dequantise the scores: one key scale per token
+            s1[0] *= ksc[0].x; s1[1] *= ksc[0].y; s1[2] *= ksc[0].z; s1[3] *= ksc[0].w;
+            s2[0] *= ksc[1].x; s2[1] *= ksc[1].y; s2[2] *= ksc[1].z; s2[3] *= ksc[1].w;
+        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             sv[e] = (tl + e < t_end) ? s1[e] * kScale : -INFINITY;
@@ -1127,8 +1323,15 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 #pragma unroll
         for (int dg = 0; dg < 8; ++dg) acc[dg] *= alpha;
 
+        if constexpr (KV8) {
+            // value scales ride on the probabilities; slots past the span may hold any scale, and their
+            // probability is an exact zero only while it is not multiplied by a NaN or an infinity
+            const float vs[8] = {vsc[0].x, vsc[0].y, vsc[0].z, vsc[0].w, vsc[1].x, vsc[1].y, vsc[1].z, vsc[1].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) p[e] = (tl + e < t_end) ? p[e] * vs[e] : 0.f;
+        }
         uint4 pk = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
-        if (t0 + kAttnTileTokens > t_end) {
+        if constexpr (!KV8) if (t0 + kAttnTileTokens > t_end) {
             // ragged tail: cache slots past the span may hold anything (even NaN); blank them so
             // that 0 * garbage cannot reach the accumulators.
             uint32_t mlo[4];
@@ -1145,8 +1348,12 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         }
         const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pk);
 #pragma unroll
-        for (int dg = 0; dg < 8; ++dg)
-            acc[dg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dg]), pfrag, acc[dg], 0, 0, 0);
+        for (int dg = 0; dg < 8; ++dg) {
+            bf16x8 fv;
+            if constexpr (KV8) fv = __builtin_bit_cast(bf16x8, i8x8_to_bf16(vq[dg].x, vq[dg].y));
+            else fv = __builtin_bit_cast(bf16x8, vf[dg]);
+            acc[dg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fv, pfrag, acc[dg], 0, 0, 0);
+        }
     }
 
     // ---- merge the 4 waves (wave order)
@@ -1262,7 +1469,10 @@ hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batc
                        float *part_ml, float *part_o, hipStream_t s)
 {
     AttnArgs a = attn_args(qkv, rope, kv, batch, nq, nkv, sp, part_ml, part_o, nullptr, nullptr);
-    PSV_LAUNCH(k_attn, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
+    if (kv.int8)
+        PSV_LAUNCH(k_attn<true>, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
+    else
+        PSV_LAUNCH(k_attn<false>, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -1334,7 +1544,8 @@ __global__ __launch_bounds__(256) void k_prefetch(PrefetchJob j)
         const int lane = threadIdx.x & 63;
         const uint64_t gw = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
         const uint64_t nw = (uint64_t)gridDim.x * 4;
-        const uint32_t per_block16 = (uint32_t)j.nkv * 256;   // 16-byte words per pool block
+        // 16-byte words per pool block (K or V): bf16 256 per kv head, int8 132 (codes + token scales)
+        const uint32_t per_block16 = (uint32_t)j.nkv * (j.kv.int8 ? PSV_KV_UNIT_BYTES_INT8 / 16 : 256);
         for (uint64_t q = gw; q < j.kv_count; q += nw) {
             const uint64_t lin = j.kv_first + q;
             const int b = (int)(lin / j.blocks_per_seq), lb = (int)(lin % j.blocks_per_seq);
@@ -1343,9 +1554,10 @@ __global__ __launch_bounds__(256) void k_prefetch(PrefetchJob j)
             if (blk < 0) continue;
             const uint4 *kp = reinterpret_cast<const uint4 *>(j.kv.k_pool) + (size_t)blk * per_block16;
             const uint4 *vp = reinterpret_cast<const uint4 *>(j.kv.v_pool) + (size_t)blk * per_block16;
-            for (uint32_t o = lane; o < per_block16; o += 256) {   // per_block16 is a multiple of 256
-                uint4 a0 = kp[o], a1 = kp[o + 64], a2 = kp[o + 128], a3 = kp[o + 192];
-                uint4 b0 = vp[o], b1 = vp[o + 64], b2 = vp[o + 128], b3 = vp[o + 192];
+            for (uint32_t o = lane; o < per_block16; o += 256) {
+                const bool p1 = o + 64 < per_block16, p2 = o + 128 < per_block16, p3 = o + 192 < per_block16;
+                uint4 a0 = kp[o], a1 = p1 ? kp[o + 64] : zero16(), a2 = p2 ? kp[o + 128] : zero16(), a3 = p3 ? kp[o + 192] : zero16();
+                uint4 b0 = vp[o], b1 = p1 ? vp[o + 64] : zero16(), b2 = p2 ? vp[o + 128] : zero16(), b3 = p3 ? vp[o + 192] : zero16();
                 sink ^= fold(a0) ^ fold(a1) ^ fold(a2) ^ fold(a3) ^ fold(b0) ^ fold(b1) ^ fold(b2) ^ fold(b3);
             }
         }

@@ -16,6 +16,7 @@ static bool desc_ok(const psv_model_desc &d)
     if (!(d.rms_eps >= 0.f) || !(d.rope_theta >= 0.f)) return false;
     if (d.max_batch == 0 || d.max_batch > 64) return false;
     if (d.max_seq == 0 || d.max_seq % PSV_BLOCK_TOKENS != 0 || d.max_seq > (1u << 20)) return false;
+    if (d.weight_format > PSV_FMT_INT8 || d.kv_format > PSV_FMT_INT8) return false;
     return true;
 }
 
@@ -24,13 +25,16 @@ static bool desc_ok(const psv_model_desc &d)
 uint64_t op_mem_size(const psv_model_desc &d, uint32_t op, uint32_t batch, uint32_t context)
 {
     const uint64_t H = d.hidden, F = d.ffn, hd = d.head_dim;
+    const uint64_t wb = d.weight_format == PSV_FMT_INT8 ? 1 : 2;                 // bytes per weight
+    // K and V bytes of one token of one kv head; the int8 cache carries a 4-byte scale per row
+    const uint64_t kvb = d.kv_format == PSV_FMT_INT8 ? 2 * (hd + 4) : 2 * hd * 2;
     switch (op) {
-    case PSV_OP_QKV: return (uint64_t)(d.n_q_heads + 2 * d.n_kv_heads) * hd * H * 2;
-    case PSV_OP_ATTN: return (uint64_t)batch * (context > 0 ? context - 1 : 0) * d.n_kv_heads * hd * 2 * 2;
-    case PSV_OP_O: return H * d.n_q_heads * hd * 2;
-    case PSV_OP_GATE: return F * H * 2;
-    case PSV_OP_UP: return F * H * 2;
-    case PSV_OP_DOWN: return H * F * 2;
+    case PSV_OP_QKV: return (uint64_t)(d.n_q_heads + 2 * d.n_kv_heads) * hd * H * wb;
+    case PSV_OP_ATTN: return (uint64_t)batch * (context > 0 ? context - 1 : 0) * d.n_kv_heads * kvb;
+    case PSV_OP_O: return H * d.n_q_heads * hd * wb;
+    case PSV_OP_GATE: return F * H * wb;
+    case PSV_OP_UP: return F * H * wb;
+    case PSV_OP_DOWN: return H * F * wb;
     default: return 0;
     }
 }

@@ -22,7 +22,8 @@ class Session:
         self.layers = list(range(w.n_layers)) if layers is None else list(layers)
         self.max_seq = (w.context + 15) // 16 * 16
         self.desc = psv.model_desc(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch, self.max_seq,
-                                   head_dim=w.head_dim, rms_eps=w.rms_eps, rope_theta=w.rope_theta)
+                                   head_dim=w.head_dim, rms_eps=w.rms_eps, rope_theta=w.rope_theta,
+                                   weight_format=w.weight_format, kv_format=w.kv_format)
         # HIP maps streams onto a few hardware queues; take a side stream that really runs beside the main one
         self.main = torch.cuda.Stream(device=self.device)
         self.overlap = False

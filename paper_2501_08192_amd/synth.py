@@ -11,6 +11,10 @@ KV-cache layout (bt = 16 tokens per block):
     K pool [n_blocks, n_kv_heads, bt, head_dim]   (token-major inside a block)
     V pool [n_blocks, n_kv_heads, head_dim, bt]   (channel-major inside a block)
 A "contiguous" cache is the same pool with the implicit page table block(b, j) = b*max_blocks + j.
+
+int8 formats (the precision of the paper's measurements): weights are int8 codes plus one fp32 scale per
+output row; a KV pool is a byte tensor [n_blocks, n_kv_heads, 2112]: 2048 codes (K token-major, V
+channel-major) followed by the 16 fp32 scales of the block's tokens.
 """
 from dataclasses import dataclass, replace
 
@@ -34,6 +38,8 @@ class Workload:
     window_us: tuple        # (after attention block, after MLP block)
     rms_eps: float = 1e-5
     rope_theta: float = 500000.0
+    weight_format: str = "bf16"   # or "int8"
+    kv_format: str = "bf16"       # or "int8"
 
     @property
     def qkv_rows(self):
@@ -50,11 +56,13 @@ class Workload:
     @property
     def weight_bytes_per_layer(self):
         h, f = self.hidden, self.ffn
-        return 2 * (self.qkv_rows * h + h * self.n_q_heads * self.head_dim + 3 * f * h)
+        per = 1 if self.weight_format == "int8" else 2
+        return per * (self.qkv_rows * h + h * self.n_q_heads * self.head_dim + 3 * f * h)
 
     @property
     def kv_bytes_per_layer(self):
-        return 2 * 2 * self.batch * self.context * self.n_kv_heads * self.head_dim
+        per_token = 2 * (self.head_dim + 4) if self.kv_format == "int8" else 2 * 2 * self.head_dim   # K and V
+        return per_token * self.batch * self.context * self.n_kv_heads
 
     @property
     def layer_bytes(self):
@@ -94,9 +102,39 @@ def _normal(shape, std, mean, seed, name, layer, device):
     return t.to(torch.bfloat16)
 
 
+CODE_STD = 42.0   # int8 codes are drawn as round(N(0, 42^2)) clamped to +-127 (3 sigma)
+KV_UNIT_INT8 = BLOCK_TOKENS * 128 + 4 * BLOCK_TOKENS
+
+_SCALE_IDS = {"w_qkv": 21, "w_o": 22, "w_gate": 23, "w_up": 24, "w_down": 25, "k_pool": 28, "v_pool": 29}
+
+
+def _codes(shape, seed, name, layer, device):
+    g = _gen(seed, name, layer, device)
+    t = torch.randn(shape, generator=g, device=device, dtype=torch.float32)
+    return t.mul_(CODE_STD).round_().clamp_(-127, 127).to(torch.int8)
+
+
+def _scales(shape, typical, seed, name, layer, device):
+    """fp32 scales spread +-25 % around typical / CODE_STD, so that code * scale ~ N(0, typical^2)."""
+    g = torch.Generator(device=device)
+    g.manual_seed((int(seed) * 1000003 + _SCALE_IDS[name] * 10007 + int(layer)) & 0x7FFFFFFFFFFFFFFF)
+    u = torch.rand(shape, generator=g, device=device, dtype=torch.float32)
+    return u.mul_(0.5).add_(0.75).mul_(typical / CODE_STD)
+
+
 def layer_weights(w: Workload, layer: int, seed: int = 2501, device="cpu"):
-    """bf16 weights of one layer: projections N(0, 0.02^2), norm gains 1 + N(0, 0.02^2)."""
+    """Weights of one layer: projections N(0, 0.02^2) (bf16, or int8 codes with fp32 row scales under s_*),
+    norm gains 1 + N(0, 0.02^2) in bf16."""
     h, f, nqd = w.hidden, w.ffn, w.n_q_heads * w.head_dim
+    if w.weight_format == "int8":
+        shapes = {"w_qkv": (w.qkv_rows, h), "w_o": (h, nqd), "w_gate": (f, h), "w_up": (f, h), "w_down": (h, f)}
+        out = {}
+        for n, shp in shapes.items():
+            out[n] = _codes(shp, seed, n, layer, device)
+            out["s_" + n[2:]] = _scales((shp[0],), 0.02, seed, n, layer, device)
+        out["g_attn"] = _normal((h,), 0.02, 1.0, seed, "g_attn", layer, device)
+        out["g_mlp"] = _normal((h,), 0.02, 1.0, seed, "g_mlp", layer, device)
+        return out
     return {
         "w_qkv": _normal((w.qkv_rows, h), 0.02, 0.0, seed, "w_qkv", layer, device),
         "w_o": _normal((h, nqd), 0.02, 0.0, seed, "w_o", layer, device),
@@ -109,8 +147,19 @@ def layer_weights(w: Workload, layer: int, seed: int = 2501, device="cpu"):
 
 
 def kv_pools(w: Workload, layer: int, seed: int = 2501, device="cpu", n_blocks=None):
-    """bf16 K and V pools of one layer, every slot N(0,1)."""
+    """K and V pools of one layer, every slot ~ N(0,1): bf16, or the int8 byte layout."""
     nb = w.pool_blocks if n_blocks is None else int(n_blocks)
+    if w.kv_format == "int8":
+        assert w.head_dim == 128
+        pools = []
+        for name in ("k_pool", "v_pool"):
+            pool = torch.empty((nb, w.n_kv_heads, KV_UNIT_INT8), dtype=torch.uint8, device=device)
+            codes = _codes((nb, w.n_kv_heads, BLOCK_TOKENS * 128), seed, name, layer, device)
+            pool[:, :, :BLOCK_TOKENS * 128] = codes.view(torch.uint8)
+            sc = _scales((nb, w.n_kv_heads, BLOCK_TOKENS), 1.0, seed, name, layer, device)
+            pool[:, :, BLOCK_TOKENS * 128:] = sc.view(torch.uint8)
+            pools.append(pool)
+        return pools[0], pools[1]
     k = _normal((nb, w.n_kv_heads, BLOCK_TOKENS, w.head_dim), 1.0, 0.0, seed, "k_pool", layer, device)
     v = _normal((nb, w.n_kv_heads, w.head_dim, BLOCK_TOKENS), 1.0, 0.0, seed, "v_pool", layer, device)
     return k, v
@@ -137,6 +186,9 @@ def x_in(w: Workload, seed: int = 2501, device="cpu"):
 
 
 def bits(t: torch.Tensor):
-    """Raw bf16 bit patterns of a tensor as a numpy uint16 array (host copy)."""
-    assert t.dtype == torch.bfloat16
-    return t.detach().cpu().contiguous().view(torch.int16).numpy().view("uint16")
+    """Host copy as numpy: raw bf16 bit patterns (uint16) for bf16 tensors, the values themselves for int8 codes,
+    uint8 pools and fp32 scales."""
+    if t.dtype == torch.bfloat16:
+        return t.detach().cpu().contiguous().view(torch.int16).numpy().view("uint16")
+    assert t.dtype in (torch.int8, torch.uint8, torch.float32)
+    return t.detach().cpu().contiguous().numpy()
