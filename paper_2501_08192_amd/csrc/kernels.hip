@@ -535,28 +535,54 @@ bool gemv_supported(int batch, int N, int K)
 // threads that covers a row: 256 threads measured 1 us faster there.
 static constexpr int gemv_threads(int mode) { return mode == GEMV_MERGE ? 256 : 512; }
 
-template <int NB, int ITERS, bool SW, int MODE, bool W8>
+// Launch geometry shared by every instantiation: group size (threads that cover one row), workgroups, and
+// the most rows any group owns.
+struct GemvGeom {
+    int gs_log2, groups, max_rows;
+    long long blocks;
+};
+static GemvGeom gemv_geom(int N, int K, int iters, int threads, int rb)
+{
+    GemvGeom g;
+    g.gs_log2 = 6;
+    while ((8 << g.gs_log2) * iters < K && (1 << g.gs_log2) < threads) ++g.gs_log2;
+    g.groups = threads >> g.gs_log2;
+    // enough workgroups that a group gets at most rb rows per pass and the grid is a multiple of the
+    // 256 CUs (2 workgroups fit on a CU); rows are dealt to the groups in balanced contiguous ranges.
+    const long long want = ((long long)N + (long long)rb * g.groups - 1) / ((long long)rb * g.groups);
+    g.blocks = (want + 255) / 256 * 256;
+    if (g.blocks < 256) g.blocks = 256;
+    if (g.blocks > 1024) g.blocks = 1024;
+    const long long slots = g.blocks * g.groups;
+    g.max_rows = (int)((N + slots - 1) / slots);
+    return g;
+}
+
+template <int NB, int RB, int ITERS, bool SW, int MODE, bool W8>
 static hipError_t gemv_go(GemvArgs a, hipStream_t s)
 {
-    // rows per pass: as many as keep 128 bytes (x ITERS) of weight loads in flight per thread
-    constexpr int RB = (SW ? 4 : 8) * (W8 ? 2 : 1);
     const int threads = gemv_threads(MODE);
-    int gs_log2 = 6;
-    while ((8 << gs_log2) * ITERS < a.K && (1 << gs_log2) < threads) ++gs_log2;
-    const int groups = threads >> gs_log2;
-    // enough workgroups that a group gets at most RB rows per pass and the grid is a multiple of the
-    // 256 CUs (2 workgroups fit on a CU); rows are dealt to the groups in balanced contiguous ranges.
-    long long want = ((long long)a.N + (long long)RB * groups - 1) / ((long long)RB * groups);
-    long long blocks = (want + 255) / 256 * 256;
-    if (blocks < 256) blocks = 256;
-    if (blocks > 1024) blocks = 1024;
-    const long long slots = blocks * groups;
-    const long long max_rows = (a.N + slots - 1) / slots;
-    a.gs_log2 = gs_log2;
-    a.passes = (int)((max_rows + RB - 1) / RB);
+    const GemvGeom g = gemv_geom(a.N, a.K, ITERS, threads, RB);
+    a.gs_log2 = g.gs_log2;
+    a.passes = (g.max_rows + RB - 1) / RB;
     if (a.passes < 1) a.passes = 1;
-    PSV_LAUNCH((k_gemv<NB, RB, ITERS, SW, MODE, W8>), dim3((unsigned)blocks), dim3(threads), 0, s, a);
+    PSV_LAUNCH((k_gemv<NB, RB, ITERS, SW, MODE, W8>), dim3((unsigned)g.blocks), dim3(threads), 0, s, a);
     return hipGetLastError();
+}
+
+// Rows per pass: as many as keep 128 bytes (x ITERS) of weight loads in flight per thread (8 rows of bf16, 16
+// of int8; half of that for a SwiGLU pair) -- but no more than a group owns when the matrix is small and the
+// minimum grid of 256 workgroups already leaves only a few rows per group, since padded rows cost ALU work.
+template <int NB, int ITERS, bool SW, int MODE, bool W8>
+static hipError_t gemv_rows(const GemvArgs &a, hipStream_t s)
+{
+    constexpr int RBMAX = (SW ? 4 : 8) * (W8 ? 2 : 1);
+    const int threads = gemv_threads(MODE);
+    int rb = RBMAX;
+    while (rb > 4 && gemv_geom(a.N, a.K, ITERS, threads, rb).max_rows <= rb / 2) rb /= 2;
+    if constexpr (RBMAX >= 16) if (rb == 16) return gemv_go<NB, 16, ITERS, SW, MODE, W8>(a, s);
+    if constexpr (RBMAX >= 8) if (rb == 8) return gemv_go<NB, 8, ITERS, SW, MODE, W8>(a, s);
+    return gemv_go<NB, 4, ITERS, SW, MODE, W8>(a, s);
 }
 
 template <int NB, int MODE>
@@ -564,12 +590,13 @@ static hipError_t gemv_pick(const GemvArgs &a, hipStream_t s)
 {
     const int threads = gemv_threads(MODE);
     const bool sw = a.W2 != nullptr, two = a.K > 8 * threads;
+    if (MODE == GEMV_MERGE && sw) return hipErrorInvalidValue;   // the merge prologue feeds the O projection only
     if (a.scale) {
-        if (two) return sw ? gemv_go<NB, 2, true, MODE, true>(a, s) : gemv_go<NB, 2, false, MODE, true>(a, s);
-        return sw ? gemv_go<NB, 1, true, MODE, true>(a, s) : gemv_go<NB, 1, false, MODE, true>(a, s);
+        if (two) return sw ? gemv_rows<NB, 2, MODE != GEMV_MERGE, MODE, true>(a, s) : gemv_rows<NB, 2, false, MODE, true>(a, s);
+        return sw ? gemv_rows<NB, 1, MODE != GEMV_MERGE, MODE, true>(a, s) : gemv_rows<NB, 1, false, MODE, true>(a, s);
     }
-    if (two) return sw ? gemv_go<NB, 2, true, MODE, false>(a, s) : gemv_go<NB, 2, false, MODE, false>(a, s);
-    return sw ? gemv_go<NB, 1, true, MODE, false>(a, s) : gemv_go<NB, 1, false, MODE, false>(a, s);
+    if (two) return sw ? gemv_rows<NB, 2, MODE != GEMV_MERGE, MODE, false>(a, s) : gemv_rows<NB, 2, false, MODE, false>(a, s);
+    return sw ? gemv_rows<NB, 1, MODE != GEMV_MERGE, MODE, false>(a, s) : gemv_rows<NB, 1, false, MODE, false>(a, s);
 }
 
 template <int MODE>
