@@ -36,7 +36,7 @@ Workspace layout_workspace(const psv_model_desc &d)
     const size_t B = d.max_batch, Bp = (B + 15) / 16 * 16, H = d.hidden, F = d.ffn;
     const size_t QR = (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim, QD = (size_t)d.n_q_heads * d.head_dim;
     const size_t G = d.n_q_heads / d.n_kv_heads;
-    const AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq);
+    const AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq, d.kv_format == PSV_FMT_INT8);
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
     w.x = take(B * H * 4);
@@ -343,7 +343,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     const psv_model_desc &d = c->d;
     const int B = (int)batch, H = (int)d.hidden, F = (int)d.ffn, nq = (int)d.n_q_heads, nkv = (int)d.n_kv_heads;
     const int QR = (nq + 2 * nkv) * 128, QD = nq * 128;
-    const AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq);
+    const AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq, d.kv_format == PSV_FMT_INT8);
     float *x = c->at<float>(c->ws.x), *y = c->at<float>(c->ws.y);
     float *delta_a = c->at<float>(c->ws.delta_a), *delta_m = c->at<float>(c->ws.delta_m);
     float *h1 = c->at<float>(c->ws.h1_f32), *h2 = c->at<float>(c->ws.h2_f32);

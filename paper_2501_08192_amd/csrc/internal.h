@@ -14,7 +14,8 @@ namespace psv {
 // ---- attention work split ---------------------------------------------------------------
 // One 64-lane wave consumes the KV-cache in tiles of 32 tokens; a workgroup has 4 waves, so a
 // workgroup's chunk is a multiple of 128 tokens.  Every wave writes its own partial result.
-constexpr int kAttnTileTokens = 32;
+constexpr int kAttnTileTokens = 32;       // tokens per wave and loop step, bf16 cache
+constexpr int kAttnTileTokensInt8 = 64;   // int8 cache
 constexpr int kAttnWaves = 4;
 constexpr int kAttnMaxChunks = 256;
 constexpr int kAttnResident = 768;    // workgroups of the attention kernel resident on the chip at a time (3 per CU)
@@ -23,7 +24,7 @@ struct AttnSplit {
     int chunk_tokens;   // tokens per workgroup
     int n_chunks;       // workgroups along the sequence (grid.x) = partial results per (sequence, kv head)
 };
-AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq);
+AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq, bool kv_int8);
 
 struct KvView {
     uint16_t *k_pool;            // bf16 pool, or (int8 != 0) byte pool of PSV_KV_UNIT_BYTES_INT8 units

@@ -1071,12 +1071,12 @@ hipError_t launch_rope_table(const int32_t *seq_lens, const double *inv_freq, in
 
 // ------------------------------------------------------------------------------------ decode attention
 
-AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq)
+AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq, bool kv_int8)
 {
     // The attention kernel keeps 3 workgroups resident per CU (register bound): aim at no more than 768
     // workgroups, i.e. one resident round without a tail, with whole 4-tile (128-token) steps per chunk
     // and at most kAttnMaxChunks chunks per (sequence, kv head).
-    const int unit = kAttnTileTokens * kAttnWaves;
+    const int unit = (kv_int8 ? kAttnTileTokensInt8 : kAttnTileTokens) * kAttnWaves;
     const uint64_t seqs = (uint64_t)batch * n_kv_heads;
     uint64_t max_chunks = kAttnResident / (seqs ? seqs : 1);
     if (max_chunks < 1) max_chunks = 1;
@@ -1117,14 +1117,6 @@ struct AttnArgs {
 //    exactly the B-fragment the O^T MFMA needs.  Probabilities never leave registers.
 //  * epilogue: the 4 waves merge through LDS and the workgroup stores one partial (max, sum, O);
 //    k_attn_merge then combines the partials of a (sequence, kv head) in chunk order.
-//
-// KV8 = int8 cache: a (block, kv head) unit is 2048 code bytes + 16 fp32 token scales.  A lane's K loads
-// are two 16-byte words per row (channels q4*16 .. +15 and 64 + q4*16 .. +15; the query fragments use the
-// same channel order), its V loads one 8-byte word per channel row; codes are widened to bf16 (exactly)
-// just before the MFMAs; scores are multiplied by the key scale of their token and probabilities by the
-// value scale before they become the B operand of the second contraction.  The appended rows are
-// quantised per row in single precision: scale = max|v| / 127, code = rint(v / scale).
-template <bool KV8>
 __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 {
     __shared__ float ms[kAttnWaves][16], ls[kAttnWaves][16];
@@ -1146,48 +1138,12 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     //      past the span are masked later, and every logical block below max_blocks maps into the pool), so
     //      each wave issues the loads of its first tile right away, ahead of everything else in the kernel.
     const int tau1 = 8 * (i >> 2) + (i & 3);          // token (within the 32-token group) of K row i, tile 1
-    uint4 ka[KV8 ? 2 : 4], kb[KV8 ? 2 : 4], vf[KV8 ? 1 : 8];
-    uint2 vq[KV8 ? 8 : 1];                 // int8: V codes, 8 tokens of one channel row
-    float4 ksc[KV8 ? 2 : 1], vsc[KV8 ? 2 : 1];   // int8: key / value scales of tokens 8*q4 .. 8*q4+7
-    const uint8_t *k8 = reinterpret_cast<const uint8_t *>(kv.k_pool), *v8 = reinterpret_cast<const uint8_t *>(kv.v_pool);
+    uint4 ka[4], kb[4], vf[8];
     auto load_tile = [&](int t0) {
         const int lb = t0 >> 4;
         const int blkA = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb);
         const int blkB = (lb + 1 < kv.max_blocks)
                              ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb + 1) : -1;
-        if constexpr (KV8) {
-            {   // K codes: tile 1 row i = token tau1, tile 2 row i = token tau1 + 4
-                const int blk = (i < 8) ? blkA : blkB;
-                if (blk >= 0) {
-                    const uint8_t *base = k8 + ((size_t)blk * nkv + kvh) * PSV_KV_UNIT_BYTES_INT8 + (tau1 & 15) * 128 + q4 * 16;
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) {
-                        ka[j] = *reinterpret_cast<const uint4 *>(base + j * 64);
-                        kb[j] = *reinterpret_cast<const uint4 *>(base + 4 * 128 + j * 64);
-                    }
-                } else {
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) { ka[j] = zero16(); kb[j] = zero16(); }
-                }
-            }
-            {   // V codes and both scale vectors: tokens 8*q4 .. 8*q4+7 of the tile
-                const int blk = (q4 < 2) ? blkA : blkB;
-                if (blk >= 0) {
-                    const size_t unit = ((size_t)blk * nkv + kvh) * PSV_KV_UNIT_BYTES_INT8;
-                    const uint8_t *base = v8 + unit + i * 16 + (q4 & 1) * 8;
-#pragma unroll
-                    for (int dg = 0; dg < 8; ++dg) vq[dg] = ld8(base + dg * 16 * 16);
-                    const float4 *ks4 = reinterpret_cast<const float4 *>(k8 + unit + 2048 + (q4 & 1) * 32);
-                    const float4 *vs4 = reinterpret_cast<const float4 *>(v8 + unit + 2048 + (q4 & 1) * 32);
-                    ksc[0] = ks4[0]; ksc[1] = ks4[1];
-                    vsc[0] = vs4[0]; vsc[1] = vs4[1];
-                } else {
-#pragma unroll
-                    for (int dg = 0; dg < 8; ++dg) vq[dg] = make_uint2(0u, 0u);
-                    ksc[0] = ksc[1] = vsc[0] = vsc[1] = make_float4(0.f, 0.f, 0.f, 0.f);
-                }
-            }
-        } else {
         // K fragments: tile 1 row i = token tau1, tile 2 row i = token tau1 + 4
         {
             const int blk = (i < 8) ? blkA : blkB;
@@ -1215,7 +1171,6 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                 for (int dg = 0; dg < 8; ++dg) vf[dg] = zero16();
             }
         }
-        }
     };
     const int t_first = t_begin + w * kAttnTileTokens;
     const bool early = t_first < kv.max_blocks * 16;
@@ -1231,7 +1186,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
             const float *qrow = qkv_b + (size_t)(kvh * G + i) * 128;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
-                const int f0 = KV8 ? q4 * 16 + ks * 8 : ks * 32 + q4 * 8;   // same channel order as the K fragments
+                const int f0 = ks * 32 + q4 * 8;
                 float lo[8], hi[8], rl[8], rh[8];
                 *reinterpret_cast<float4 *>(lo) = *reinterpret_cast<const float4 *>(qrow + f0);
                 *reinterpret_cast<float4 *>(lo + 4) = *reinterpret_cast<const float4 *>(qrow + f0 + 4);
@@ -1262,33 +1217,12 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                 const float *vrow = qkv_b + (size_t)(nq + nkv + kvh) * 128;
                 const float lo = krow[tid], hi = krow[tid + 64];
                 const int r = pos & 15;
-                const float k0 = lo * cs.x - hi * cs.y, k1 = hi * cs.x + lo * cs.y;
-                const float v0 = vrow[tid], v1 = vrow[tid + 64];
-                if constexpr (KV8) {
-                    // per-row symmetric quantisation; the whole wave is here (blk is uniform)
-                    const float ka_max = wave_max(fmaxf(fabsf(k0), fabsf(k1)));
-                    const float va_max = wave_max(fmaxf(fabsf(v0), fabsf(v1)));
-                    const float ksc1 = ka_max > 0.f ? ka_max / 127.0f : 1.0f;
-                    const float vsc1 = va_max > 0.f ? va_max / 127.0f : 1.0f;
-                    const size_t unit = ((size_t)blk * nkv + kvh) * PSV_KV_UNIT_BYTES_INT8;
-                    uint8_t *kdst = reinterpret_cast<uint8_t *>(kv.k_pool) + unit;
-                    uint8_t *vdst = reinterpret_cast<uint8_t *>(kv.v_pool) + unit;
-                    kdst[r * 128 + tid] = quant_i8(k0, ksc1);
-                    kdst[r * 128 + tid + 64] = quant_i8(k1, ksc1);
-                    vdst[tid * 16 + r] = quant_i8(v0, vsc1);
-                    vdst[(tid + 64) * 16 + r] = quant_i8(v1, vsc1);
-                    if (tid == 0) {
-                        reinterpret_cast<float *>(kdst + 2048)[r] = ksc1;
-                        reinterpret_cast<float *>(vdst + 2048)[r] = vsc1;
-                    }
-                } else {
-                    uint16_t *kdst = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + r) * 128;
-                    kdst[tid] = (uint16_t)f32_to_bf16(k0);
-                    kdst[tid + 64] = (uint16_t)f32_to_bf16(k1);
-                    uint16_t *vdst = kv.v_pool + ((size_t)blk * nkv + kvh) * 128 * 16 + r;
-                    vdst[(size_t)tid * 16] = (uint16_t)f32_to_bf16(v0);
-                    vdst[(size_t)(tid + 64) * 16] = (uint16_t)f32_to_bf16(v1);
-                }
+                uint16_t *kdst = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + r) * 128;
+                kdst[tid] = (uint16_t)f32_to_bf16(lo * cs.x - hi * cs.y);
+                kdst[tid + 64] = (uint16_t)f32_to_bf16(hi * cs.x + lo * cs.y);
+                uint16_t *vdst = kv.v_pool + ((size_t)blk * nkv + kvh) * 128 * 16 + r;
+                vdst[(size_t)tid * 16] = (uint16_t)f32_to_bf16(vrow[tid]);
+                vdst[(size_t)(tid + 64) * 16] = (uint16_t)f32_to_bf16(vrow[tid + 64]);
             }
             __threadfence();
         }
@@ -1308,25 +1242,12 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            bf16x8 fa, fb;
-            if constexpr (KV8) {
-                const uint4 ca = ka[ks >> 1], cb = kb[ks >> 1];
-                fa = __builtin_bit_cast(bf16x8, (ks & 1) ? i8x8_to_bf16(ca.z, ca.w) : i8x8_to_bf16(ca.x, ca.y));
-                fb = __builtin_bit_cast(bf16x8, (ks & 1) ? i8x8_to_bf16(cb.z, cb.w) : i8x8_to_bf16(cb.x, cb.y));
-            } else {
-                fa = __builtin_bit_cast(bf16x8, ka[ks]);
-                fb = __builtin_bit_cast(bf16x8, kb[ks]);
-            }
-            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fa, qf[ks], s1, 0, 0, 0);
-            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb, qf[ks], s2, 0, 0, 0);
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[ks]), qf[ks], s1, 0, 0, 0);
+            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[ks]), qf[ks], s2, 0, 0, 0);
         }
         // lane (g = i, q4) now holds tokens t0 + 8*q4 + e, e = 0..7
         float sv[8];
         const int tl = t0 + 8 * q4;
-        if constexpr (KV8) {   // dequantise the scores: one key scale per token
-            s1[0] *= ksc[0].x; s1[1] *= ksc[0].y; s1[2] *= ksc[0].z; s1[3] *= ksc[0].w;
-            s2[0] *= ksc[1].x; s2[1] *= ksc[1].y; s2[2] *= ksc[1].z; s2[3] *= ksc[1].w;
-        }
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             sv[e] = (tl + e < t_end) ? s1[e] * kScale : -INFINITY;
@@ -1350,15 +1271,8 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 #pragma unroll
         for (int dg = 0; dg < 8; ++dg) acc[dg] *= alpha;
 
-        if constexpr (KV8) {
-            // value scales ride on the probabilities; slots past the span may hold any scale, and their
-            // probability is an exact zero only while it is not multiplied by a NaN or an infinity
-            const float vs[8] = {vsc[0].x, vsc[0].y, vsc[0].z, vsc[0].w, vsc[1].x, vsc[1].y, vsc[1].z, vsc[1].w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) p[e] = (tl + e < t_end) ? p[e] * vs[e] : 0.f;
-        }
         uint4 pk = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
-        if constexpr (!KV8) if (t0 + kAttnTileTokens > t_end) {
+        if (t0 + kAttnTileTokens > t_end) {
             // ragged tail: cache slots past the span may hold anything (even NaN); blank them so
             // that 0 * garbage cannot reach the accumulators.
             uint32_t mlo[4];
@@ -1375,12 +1289,8 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         }
         const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pk);
 #pragma unroll
-        for (int dg = 0; dg < 8; ++dg) {
-            bf16x8 fv;
-            if constexpr (KV8) fv = __builtin_bit_cast(bf16x8, i8x8_to_bf16(vq[dg].x, vq[dg].y));
-            else fv = __builtin_bit_cast(bf16x8, vf[dg]);
-            acc[dg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fv, pfrag, acc[dg], 0, 0, 0);
-        }
+        for (int dg = 0; dg < 8; ++dg)
+            acc[dg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dg]), pfrag, acc[dg], 0, 0, 0);
     }
 
     // ---- merge the 4 waves (wave order)
@@ -1412,6 +1322,295 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         }
     }
 
+}
+
+// ---- int8 cache: decode attention on the int8 matrix cores -------------------------------------------------
+//
+// Same split-K scheme and the same partials as k_attn, but the cache codes go into v_mfma_i32_16x16x64_i8 as
+// they are (no widening): the floating-point operand of each contraction is cut into two int8 "digits" with
+// a per-column scale, x ~ s * (d1 + d2 / 254), |d| <= 127, which keeps 15-16 bits of the column's largest
+// element, and the two exact i32 results are recombined as 254 * D1 + D2 before one conversion to fp32.
+//   S^T[token][g] = K[token][:] . Q[g][:]      A = K codes, 16 bytes = 16 channels per lane and k step
+//                                              B = digits of the rotated query (scale per head)
+//   O^T[chan][g] += V^T[chan][token] P'[g][token]   A = V codes, 16 bytes = the 16 tokens of one block
+//                                              B = digits of P' = softmax numerator x value scale (scale per
+//                                                  head and tile)
+// A wave tile is 64 tokens = 4 cache blocks.  Row i of score tile m (m = 0..3) is token 16*(i/4) + 4m + i%4,
+// so that lane (g, q4) ends up with the scores of tokens 16*q4 .. 16*q4+15 -- block q4, in byte order -- which
+// is exactly the B operand of the second contraction.  Key scales multiply the scores, value scales the
+// probabilities.  The appended rows are quantised per row in single precision (scale = max|v| / 127,
+// code = rint(v / scale)), stored, and re-read by the wave whose tile holds them.
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+
+// low bytes of four floats that hold small integers in "magic number" form (x + 1.5 * 2^23)
+__device__ __forceinline__ uint32_t pack_magic_bytes(float a0, float a1, float a2, float a3)
+{
+    const uint32_t lo = __builtin_amdgcn_perm(__float_as_uint(a1), __float_as_uint(a0), 0x0c0c0400u);   // a0.b0 | a1.b0 << 8
+    const uint32_t hi = __builtin_amdgcn_perm(__float_as_uint(a3), __float_as_uint(a2), 0x04000c0cu);   // a2.b0 << 16 | a3.b0 << 24
+    return lo | hi;
+}
+
+// Two int8 digits of t (|t| <= 127.5): d1 = rint(t), d2 = rint(254 * (t - d1)); both returned in magic form.
+__device__ __forceinline__ void two_digits(float t, float &m1, float &m2)
+{
+    const float kMagic = 12582912.0f;   // 1.5 * 2^23: adding it rounds to an integer (ties to even)
+    m1 = t + kMagic;
+    const float r = t - (m1 - kMagic);
+    m2 = fmaf(r, 254.0f, kMagic);
+}
+
+__global__ __launch_bounds__(256) void k_attn_q8(AttnArgs a)
+{
+    constexpr int TT = kAttnTileTokensInt8;
+    __shared__ float ms[kAttnWaves][16], ls[kAttnWaves][16];
+    __shared__ f32x4 accs[kAttnWaves][8][64];
+
+    const int b = blockIdx.z, kvh = blockIdx.y, c = blockIdx.x;
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, q4 = lane >> 4;
+    const int nq = a.nq, nkv = a.nkv, G = nq / nkv;
+    const KvView &kv = a.kv;
+    const int qkv_rows = (nq + 2 * nkv) * 128;
+    int T = kv.seq_lens[b];
+    if (T < 0 || T > kv.max_blocks * 16) T = 0;
+    const int t_begin = c * a.chunk_tokens;
+    const int t_end = min(T, t_begin + a.chunk_tokens);
+    const float *qkv_b = a.qkv + (size_t)b * qkv_rows;
+    const float2 *rope_b = a.rope + b * 64;
+    uint8_t *k8 = reinterpret_cast<uint8_t *>(kv.k_pool), *v8 = reinterpret_cast<uint8_t *>(kv.v_pool);
+
+    // ---- tile loader (addresses depend on the page table only, so the first tile is requested right away)
+    uint4 kc[4][2], vc[8];
+    float4 ksc[4], vsc[4];
+    auto load_tile = [&](int t0) {
+        const int lb = t0 >> 4;
+        const int lbk = lb + (i >> 2), lbv = lb + q4;        // block of this lane's K rows / of its V tokens
+        const int blkK = lbk < kv.max_blocks ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lbk) : -1;
+        const int blkV = lbv < kv.max_blocks ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lbv) : -1;
+        // A block outside the table (or a corrupt entry) reads block 0 and is blanked with selects: whole-array
+        // assignments in two branches would push the fragments out of registers.
+        const bool okK = blkK >= 0, okV = blkV >= 0;
+        {
+            const uint8_t *base = k8 + ((size_t)(okK ? blkK : 0) * nkv + kvh) * PSV_KV_UNIT_BYTES_INT8 + (i & 3) * 128 + q4 * 16;
+#pragma unroll
+            for (int m = 0; m < 4; ++m)
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const uint4 v = *reinterpret_cast<const uint4 *>(base + m * 4 * 128 + j * 64);
+                    kc[m][j] = make_uint4(okK ? v.x : 0u, okK ? v.y : 0u, okK ? v.z : 0u, okK ? v.w : 0u);
+                }
+        }
+        {
+            const size_t unit = ((size_t)(okV ? blkV : 0) * nkv + kvh) * PSV_KV_UNIT_BYTES_INT8;
+#pragma unroll
+            for (int dg = 0; dg < 8; ++dg) {
+                const uint4 v = *reinterpret_cast<const uint4 *>(v8 + unit + (dg * 16 + i) * 16);
+                vc[dg] = make_uint4(okV ? v.x : 0u, okV ? v.y : 0u, okV ? v.z : 0u, okV ? v.w : 0u);
+            }
+            const float4 *ks4 = reinterpret_cast<const float4 *>(k8 + unit + 2048);
+            const float4 *vs4 = reinterpret_cast<const float4 *>(v8 + unit + 2048);
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const float4 kq = ks4[m], vq4 = vs4[m];
+                ksc[m] = make_float4(okV ? kq.x : 0.f, okV ? kq.y : 0.f, okV ? kq.z : 0.f, okV ? kq.w : 0.f);
+                vsc[m] = make_float4(okV ? vq4.x : 0.f, okV ? vq4.y : 0.f, okV ? vq4.z : 0.f, okV ? vq4.w : 0.f);
+            }
+        }
+    };
+    const int t_first = t_begin + w * TT;
+    const bool early = t_first < kv.max_blocks * 16;
+    if (early) load_tile(t_first);
+
+    // ---- query digits: lane (g = i, q4) holds channels j*64 + q4*16 + e (j = 0, 1; e = 0..15), the byte order of
+    //      its K codes; channel f < 64 pairs with f + 64 for the rotation, i.e. j = 0 with j = 1 of the same lane
+    uint4 qd1[2], qd2[2];
+    float q_back = 0.f;                       // head scale / 254 * softmax scale, applied to 254*S1 + S2
+    const float kScale = 0.08838834764831845f * 1.4426950408889634f;   // 1/sqrt(128) * log2(e)
+    {
+        float ql[16], qh[16];
+        const bool have_q = i < G;
+        const float *qrow = qkv_b + (size_t)(kvh * G + (have_q ? i : 0)) * 128 + q4 * 16;
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            const float4 lo = *reinterpret_cast<const float4 *>(qrow + e4 * 4);
+            const float4 hi = *reinterpret_cast<const float4 *>(qrow + 64 + e4 * 4);
+            const float2 c0 = rope_b[q4 * 16 + e4 * 4 + 0], c1 = rope_b[q4 * 16 + e4 * 4 + 1];
+            const float2 c2 = rope_b[q4 * 16 + e4 * 4 + 2], c3 = rope_b[q4 * 16 + e4 * 4 + 3];
+            ql[e4 * 4 + 0] = have_q ? lo.x * c0.x - hi.x * c0.y : 0.f;
+            qh[e4 * 4 + 0] = have_q ? hi.x * c0.x + lo.x * c0.y : 0.f;
+            ql[e4 * 4 + 1] = have_q ? lo.y * c1.x - hi.y * c1.y : 0.f;
+            qh[e4 * 4 + 1] = have_q ? hi.y * c1.x + lo.y * c1.y : 0.f;
+            ql[e4 * 4 + 2] = have_q ? lo.z * c2.x - hi.z * c2.y : 0.f;
+            qh[e4 * 4 + 2] = have_q ? hi.z * c2.x + lo.z * c2.y : 0.f;
+            ql[e4 * 4 + 3] = have_q ? lo.w * c3.x - hi.w * c3.y : 0.f;
+            qh[e4 * 4 + 3] = have_q ? hi.w * c3.x + lo.w * c3.y : 0.f;
+        }
+        float amax = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) amax = fmaxf(amax, fmaxf(fabsf(ql[e]), fabsf(qh[e])));
+        amax = fmaxf(amax, __shfl_xor(amax, 16, 64));
+        amax = fmaxf(amax, __shfl_xor(amax, 32, 64));
+        const float inv = amax > 0.f ? 127.0f / amax : 0.f;
+        q_back = amax / 127.0f / 254.0f * kScale;
+        uint32_t w1[2][4], w2[2][4];
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            float a1[4], a2[4], b1[4], b2[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                two_digits(ql[e4 * 4 + u] * inv, a1[u], a2[u]);
+                two_digits(qh[e4 * 4 + u] * inv, b1[u], b2[u]);
+            }
+            w1[0][e4] = pack_magic_bytes(a1[0], a1[1], a1[2], a1[3]);
+            w2[0][e4] = pack_magic_bytes(a2[0], a2[1], a2[2], a2[3]);
+            w1[1][e4] = pack_magic_bytes(b1[0], b1[1], b1[2], b1[3]);
+            w2[1][e4] = pack_magic_bytes(b2[0], b2[1], b2[2], b2[3]);
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            qd1[j] = make_uint4(w1[j][0], w1[j][1], w1[j][2], w1[j][3]);
+            qd2[j] = make_uint4(w2[j][0], w2[j][1], w2[j][2], w2[j][3]);
+        }
+    }
+
+    // ---- append the new token's K and V (one workgroup per kv head does it)
+    if (T >= 1 && c == (T - 1) / a.chunk_tokens) {
+        if (tid < 64) {
+            const int pos = T - 1;
+            const int blk = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, pos >> 4);
+            if (blk >= 0) {    // uniform over the wave
+                const float2 cs = rope_b[tid];
+                const float *krow = qkv_b + (size_t)(nq + kvh) * 128;
+                const float *vrow = qkv_b + (size_t)(nq + nkv + kvh) * 128;
+                const float lo = krow[tid], hi = krow[tid + 64];
+                const int r = pos & 15;
+                const float k0 = lo * cs.x - hi * cs.y, k1 = hi * cs.x + lo * cs.y;
+                const float v0 = vrow[tid], v1 = vrow[tid + 64];
+                const float ka_max = wave_max(fmaxf(fabsf(k0), fabsf(k1)));
+                const float va_max = wave_max(fmaxf(fabsf(v0), fabsf(v1)));
+                const float ksc1 = ka_max > 0.f ? ka_max / 127.0f : 1.0f;
+                const float vsc1 = va_max > 0.f ? va_max / 127.0f : 1.0f;
+                const size_t unit = ((size_t)blk * nkv + kvh) * PSV_KV_UNIT_BYTES_INT8;
+                uint8_t *kdst = k8 + unit, *vdst = v8 + unit;
+                kdst[r * 128 + tid] = quant_i8(k0, ksc1);
+                kdst[r * 128 + tid + 64] = quant_i8(k1, ksc1);
+                vdst[tid * 16 + r] = quant_i8(v0, vsc1);
+                vdst[(tid + 64) * 16 + r] = quant_i8(v1, vsc1);
+                if (tid == 0) {
+                    reinterpret_cast<float *>(kdst + 2048)[r] = ksc1;
+                    reinterpret_cast<float *>(vdst + 2048)[r] = vsc1;
+                }
+            }
+            __threadfence();
+        }
+        __syncthreads();   // uniform: the condition depends on the workgroup only
+        if (early && T - 1 >= t_first && T - 1 < t_first + TT) load_tile(t_first);   // now with the new entry
+    }
+
+    float m_run = -1.0e30f, l_part = 0.f;
+    f32x4 acc[8];
+#pragma unroll
+    for (int dg = 0; dg < 8; ++dg) acc[dg] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int t0 = t_first; t0 < t_end; t0 += kAttnWaves * TT) {
+        if (t0 != t_first || !early) load_tile(t0);
+
+        // scores of tokens t0 + 16*q4 + e, e = 4m + j
+        float sv[16];
+        const int tl = t0 + 16 * q4;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            i32x4 s1 = {0, 0, 0, 0}, s2 = {0, 0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const i32x4 ak = __builtin_bit_cast(i32x4, kc[m][j]);
+                s1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(ak, __builtin_bit_cast(i32x4, qd1[j]), s1, 0, 0, 0);
+                s2 = __builtin_amdgcn_mfma_i32_16x16x64_i8(ak, __builtin_bit_cast(i32x4, qd2[j]), s2, 0, 0, 0);
+            }
+            const float kk4[4] = {ksc[m].x, ksc[m].y, ksc[m].z, ksc[m].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float raw = (float)(s1[j] * 254 + s2[j]);
+                sv[4 * m + j] = (tl + 4 * m + j < t_end) ? raw * q_back * kk4[j] : -INFINITY;
+            }
+        }
+        float tmax = sv[0];
+#pragma unroll
+        for (int e = 1; e < 16; ++e) tmax = fmaxf(tmax, sv[e]);
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 16, 64));
+        tmax = fmaxf(tmax, __shfl_xor(tmax, 32, 64));
+        const float m_new = fmaxf(m_run, tmax);
+        const float alpha = exp2f(m_run - m_new);
+        float pv[16], psum = 0.f, pmax = 0.f;
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            const float vv4[4] = {vsc[m].x, vsc[m].y, vsc[m].z, vsc[m].w};
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int e = 4 * m + j;
+                const float p = exp2f(sv[e] - m_new);
+                psum += p;
+                // slots past the span may hold any scale: their probability is an exact zero only while it is
+                // not multiplied by a NaN or an infinity
+                pv[e] = (tl + e < t_end) ? p * vv4[j] : 0.f;
+                pmax = fmaxf(pmax, fabsf(pv[e]));
+            }
+        }
+        l_part = l_part * alpha + psum;
+        m_run = m_new;
+        pmax = fmaxf(pmax, __shfl_xor(pmax, 16, 64));
+        pmax = fmaxf(pmax, __shfl_xor(pmax, 32, 64));
+        const float p_inv = pmax > 0.f ? 127.0f / pmax : 0.f;
+        const float p_back = pmax / 127.0f / 254.0f;
+        uint32_t pw1[4], pw2[4];
+#pragma unroll
+        for (int m = 0; m < 4; ++m) {
+            float a1[4], a2[4];
+#pragma unroll
+            for (int j = 0; j < 4; ++j) two_digits(pv[4 * m + j] * p_inv, a1[j], a2[j]);
+            pw1[m] = pack_magic_bytes(a1[0], a1[1], a1[2], a1[3]);
+            pw2[m] = pack_magic_bytes(a2[0], a2[1], a2[2], a2[3]);
+        }
+        const i32x4 pd1 = {(int)pw1[0], (int)pw1[1], (int)pw1[2], (int)pw1[3]};
+        const i32x4 pd2 = {(int)pw2[0], (int)pw2[1], (int)pw2[2], (int)pw2[3]};
+#pragma unroll
+        for (int dg = 0; dg < 8; ++dg) {
+            const i32x4 av = __builtin_bit_cast(i32x4, vc[dg]);
+            const i32x4 z = {0, 0, 0, 0};
+            const i32x4 o1 = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, pd1, z, 0, 0, 0);
+            const i32x4 o2 = __builtin_amdgcn_mfma_i32_16x16x64_i8(av, pd2, z, 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[dg][j] = fmaf(acc[dg][j], alpha, p_back * (float)(o1[j] * 254 + o2[j]));
+        }
+    }
+
+    // ---- merge the 4 waves (wave order); same partials as k_attn
+    l_part += __shfl_xor(l_part, 16, 64);
+    l_part += __shfl_xor(l_part, 32, 64);
+    if (q4 == 0) ms[w][i] = m_run;
+    __syncthreads();
+    const float M = fmaxf(fmaxf(ms[0][i], ms[1][i]), fmaxf(ms[2][i], ms[3][i]));
+    const float sc = exp2f(m_run - M);
+    if (q4 == 0) ls[w][i] = l_part * sc;
+#pragma unroll
+    for (int dg = 0; dg < 8; ++dg) accs[w][dg][lane] = acc[dg] * sc;
+    __syncthreads();
+    const size_t slot0 = ((size_t)b * nkv + kvh) * a.n_chunks;
+    if (i < G) {
+        const size_t slot = slot0 + c;
+        if (w == 0 && q4 == 0) {
+            a.part_ml[(slot * 16 + i) * 2 + 0] = M;
+            a.part_ml[(slot * 16 + i) * 2 + 1] = ls[0][i] + ls[1][i] + ls[2][i] + ls[3][i];
+        }
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            const int dg = 2 * w + d;
+            f32x4 v = accs[0][dg][lane];
+            v += accs[1][dg][lane];
+            v += accs[2][dg][lane];
+            v += accs[3][dg][lane];
+            *reinterpret_cast<float4 *>(a.part_o + (slot * G + i) * 128 + dg * 16 + 4 * q4) = make_float4(v[0], v[1], v[2], v[3]);
+        }
+    }
 }
 
 // Merge of the chunk partials of one (sequence, kv head): grid (kv heads, batch), 1024 threads.
@@ -1497,9 +1696,9 @@ hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batc
 {
     AttnArgs a = attn_args(qkv, rope, kv, batch, nq, nkv, sp, part_ml, part_o, nullptr, nullptr);
     if (kv.int8)
-        PSV_LAUNCH(k_attn<true>, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
+        PSV_LAUNCH(k_attn_q8, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
     else
-        PSV_LAUNCH(k_attn<false>, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
+        PSV_LAUNCH(k_attn, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 
@@ -1567,25 +1766,46 @@ __global__ __launch_bounds__(256) void k_prefetch(PrefetchJob j)
         }
     }
     if (j.kv_count) {
-        // one wave per logical block: K part and V part of every kv head (4 KiB each per head)
+        // A wave takes NBW logical blocks per step and requests the K part and the V part of every kv head of all
+        // of them before it looks at any result (bf16: 4 KiB each per head; int8: 2112 bytes, codes + scales).
+        constexpr int NBW = 4;
         const int lane = threadIdx.x & 63;
         const uint64_t gw = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
         const uint64_t nw = (uint64_t)gridDim.x * 4;
-        // 16-byte words per pool block (K or V): bf16 256 per kv head, int8 132 (codes + token scales)
-        const uint32_t per_block16 = (uint32_t)j.nkv * (j.kv.int8 ? PSV_KV_UNIT_BYTES_INT8 / 16 : 256);
-        for (uint64_t q = gw; q < j.kv_count; q += nw) {
-            const uint64_t lin = j.kv_first + q;
-            const int b = (int)(lin / j.blocks_per_seq), lb = (int)(lin % j.blocks_per_seq);
-            if (lb >= j.kv.max_blocks) continue;
-            const int blk = kv_phys_block(j.kv.page_table, j.kv.max_blocks, j.kv.num_pool_blocks, b, lb);
-            if (blk < 0) continue;
-            const uint4 *kp = reinterpret_cast<const uint4 *>(j.kv.k_pool) + (size_t)blk * per_block16;
-            const uint4 *vp = reinterpret_cast<const uint4 *>(j.kv.v_pool) + (size_t)blk * per_block16;
-            for (uint32_t o = lane; o < per_block16; o += 256) {
-                const bool p1 = o + 64 < per_block16, p2 = o + 128 < per_block16, p3 = o + 192 < per_block16;
-                uint4 a0 = kp[o], a1 = p1 ? kp[o + 64] : zero16(), a2 = p2 ? kp[o + 128] : zero16(), a3 = p3 ? kp[o + 192] : zero16();
-                uint4 b0 = vp[o], b1 = p1 ? vp[o + 64] : zero16(), b2 = p2 ? vp[o + 128] : zero16(), b3 = p3 ? vp[o + 192] : zero16();
-                sink ^= fold(a0) ^ fold(a1) ^ fold(a2) ^ fold(a3) ^ fold(b0) ^ fold(b1) ^ fold(b2) ^ fold(b3);
+        const uint32_t per_block16 = (uint32_t)j.nkv * (j.kv.int8 ? PSV_KV_UNIT_BYTES_INT8 / 16 : 256);   // 16-byte words
+        for (uint64_t q0 = gw * NBW; q0 < j.kv_count; q0 += nw * NBW) {
+            const uint4 *kp[NBW], *vp[NBW];
+#pragma unroll
+            for (int u = 0; u < NBW; ++u) {
+                kp[u] = vp[u] = nullptr;
+                const uint64_t q = q0 + u;
+                if (q < j.kv_count) {
+                    const uint64_t lin = j.kv_first + q;
+                    const int b = (int)(lin / j.blocks_per_seq), lb = (int)(lin % j.blocks_per_seq);
+                    const int blk = lb < j.kv.max_blocks
+                                        ? kv_phys_block(j.kv.page_table, j.kv.max_blocks, j.kv.num_pool_blocks, b, lb) : -1;
+                    if (blk >= 0) {
+                        kp[u] = reinterpret_cast<const uint4 *>(j.kv.k_pool) + (size_t)blk * per_block16;
+                        vp[u] = reinterpret_cast<const uint4 *>(j.kv.v_pool) + (size_t)blk * per_block16;
+                    }
+                }
+            }
+            for (uint32_t o = lane; o < per_block16; o += 192) {   // 3 words per pool: one step covers an int8 unit
+                const bool p1 = o + 64 < per_block16, p2 = o + 128 < per_block16;
+                uint4 v[NBW][6];
+#pragma unroll
+                for (int u = 0; u < NBW; ++u) {
+                    const bool ok = kp[u] != nullptr;
+                    v[u][0] = ok ? kp[u][o] : zero16();
+                    v[u][1] = ok && p1 ? kp[u][o + 64] : zero16();
+                    v[u][2] = ok && p2 ? kp[u][o + 128] : zero16();
+                    v[u][3] = ok ? vp[u][o] : zero16();
+                    v[u][4] = ok && p1 ? vp[u][o + 64] : zero16();
+                    v[u][5] = ok && p2 ? vp[u][o + 128] : zero16();
+                }
+#pragma unroll
+                for (int u = 0; u < NBW; ++u)
+                    sink ^= fold(v[u][0]) ^ fold(v[u][1]) ^ fold(v[u][2]) ^ fold(v[u][3]) ^ fold(v[u][4]) ^ fold(v[u][5]);
             }
         }
     }
