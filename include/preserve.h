@@ -251,7 +251,10 @@ psv_status psv_spin(float us, void *stream);
  * byte counters against a known size. */
 psv_status psv_copy_bytes(void *dst, const void *src, uint64_t bytes, void *stream);
 
-/* Intermediate buffers of the most recent layer executed, for debugging parity failures. */
+/* Intermediate buffers of the most recent layer executed, for debugging parity failures.  PSV_DBG_H1 and
+ * PSV_DBG_H2 exist only when the step ran on the vector path (batch 1, or batch 2 with H <= 4096): the
+ * matrix-core path never forms the normalised activations (it scales the projection's result instead), and
+ * psv_debug_read returns PSV_ERR_BAD_STATE for them. */
 enum {
     PSV_DBG_H1 = 0,     /* fp32 [batch, H]            normalised input of QKV */
     PSV_DBG_QKV = 1,    /* fp32 [batch, (nq+2nkv)*128] projection output before rotation */

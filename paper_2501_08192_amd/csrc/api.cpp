@@ -27,7 +27,7 @@ struct Workspace {
     size_t total = 0;
     // offsets
     size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, rope, part_ml, part_o, attn_f32, attn_bf16,
-        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag, part;
+        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag, part, ssq;
 };
 
 Workspace layout_workspace(const psv_model_desc &d)
@@ -57,6 +57,7 @@ Workspace layout_workspace(const psv_model_desc &d)
     w.m_bf16 = take(2 * Bp * F * 2);
     w.inv_freq = take(64 * sizeof(double));
     w.flag = take(256);
+    w.ssq = take(B * (H / 512) * 4);
     {   // split-K partials of the widest projection
         size_t widest = QR > H ? QR : H;
         if (2 * F > widest) widest = 2 * F;
@@ -110,6 +111,7 @@ struct psv_ctx {
     uint32_t last_prefetch_launches = 0;
     unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
     bool capturing = false;
+    bool last_step_vec = false;                  // the last step formed h1 / h2 (vector path)
     bool old_mfma = false;                       // A/B switch: K-split-in-workgroup GEMM instead of the split-K one
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(wsp + off); }
@@ -367,8 +369,9 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     const bool vec = (B == 1 || (B == 2 && H <= 4096)) && gemv_supported(B, QR, H) && gemv_supported(B, H, QD) &&
                      gemv_supported(B, F, H) && gemv_supported(B, H, F);
     const bool sk = !vec && !c->old_mfma;
+    c->last_step_vec = !sk;
     if (!vec && !sk && w8) return PSV_ERR_UNSUPPORTED;   // the older matrix-core kernel reads bf16 weights only
-    float *part = c->at<float>(c->ws.part);
+    float *part = c->at<float>(c->ws.part), *ssq = c->at<float>(c->ws.ssq);
 
     ST_TRY(prof_tag(c, -2));
     HIP_TRY(launch_rope_table(c->kv.seq_lens, inv_freq, (int)c->kv.max_blocks * 16, B, rope, s));
@@ -380,7 +383,10 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         const Mat Wqkv = mat_of(c, w, PSV_OP_QKV), Wo = mat_of(c, w, PSV_OP_O), Wg = mat_of(c, w, PSV_OP_GATE),
                   Wu = mat_of(c, w, PSV_OP_UP), Wd = mat_of(c, w, PSV_OP_DOWN);
 
-        if (!vec) {
+        if (sk) {
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x, u16(w.g_attn), h1b, plane_h, ssq, s));
+        } else if (!vec) {
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_add_rmsnorm(res, delta, delta_splits, u16(w.g_attn), d.rms_eps, B, H, x, h1, h1b, plane_h, s));
         }
@@ -389,7 +395,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_gemv_norm(Wqkv, Mat{}, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H, s));
         } else if (sk) {
             if (!gemm_sk_supported(B, QR, H)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(Wqkv, Mat{}, 0, h1b, part, B, QR, H, s));
+            HIP_TRY(launch_gemm_sk(Wqkv, Mat{}, 0, h1b, ssq, d.rms_eps, part, B, QR, H, s));
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H, w8), B, QR, false, qkv, nullptr, s));
         } else {
@@ -413,7 +419,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_gemv(Wo, Mat{}, attn, delta_a, B, H, QD, s));
         } else if (sk) {
             if (!gemm_sk_supported(B, H, QD)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(Wo, Mat{}, 0, attnb, part, B, H, QD, s));
+            HIP_TRY(launch_gemm_sk(Wo, Mat{}, 0, attnb, nullptr, 0.f, part, B, H, QD, s));
             attn_delta = part;
             attn_splits = gemm_sk_splits(B, H, QD, w8);
         } else {
@@ -422,7 +428,10 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
 
         ST_TRY(comm_window(c, l, 0, batch, le, &side_used));
 
-        if (!vec) {
+        if (sk) {
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_resid_sum(x, attn_delta, attn_splits, B, H, y, u16(w.g_mlp), h2b, plane_h, ssq, s));
+        } else if (!vec) {
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_add_rmsnorm(x, attn_delta, attn_splits, u16(w.g_mlp), d.rms_eps, B, H, y, h2, h2b, plane_h, s));
         }
@@ -431,7 +440,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_gemv_norm(Wg, Wu, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H, s));
         } else if (sk) {
             if (!gemm_sk_supported(B, 2 * F, H)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(Wg, Wu, F, h2b, part, B, 2 * F, H, s));
+            HIP_TRY(launch_gemm_sk(Wg, Wu, F, h2b, ssq, d.rms_eps, part, B, 2 * F, H, s));
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H, w8), B, 2 * F, true, m, mb, s));
         } else {
@@ -445,7 +454,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_gemv(Wd, Mat{}, m, delta_m, B, H, F, s));
         } else if (sk) {
             if (!gemm_sk_supported(B, H, F)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(Wd, Mat{}, 0, mb, part, B, H, F, s));
+            HIP_TRY(launch_gemm_sk(Wd, Mat{}, 0, mb, nullptr, 0.f, part, B, H, F, s));
             delta = part;
             delta_splits = gemm_sk_splits(B, H, F, w8);
         } else {
@@ -456,7 +465,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         res = y;
     }
     ST_TRY(prof_tag(c, -2));
-    HIP_TRY(launch_add_rmsnorm(res, delta, delta_splits, nullptr, d.rms_eps, B, H, x_out, nullptr, nullptr, 0, s));
+    HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x_out, nullptr, nullptr, 0, nullptr, s));
     if (side_used && c->capturing) {   // a captured side branch has to rejoin the origin stream
         HIP_TRY(hipEventRecord(c->ev_end, c->side));
         HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));
@@ -771,6 +780,7 @@ psv_status psv_debug_read(psv_ctx *c, uint32_t which, void *host_dst, size_t byt
     if (st != PSV_OK) return st;
     const size_t B = c->d.max_batch, H = c->d.hidden;
     const size_t QR = (size_t)(c->d.n_q_heads + 2 * c->d.n_kv_heads) * 128, QD = (size_t)c->d.n_q_heads * 128;
+    if ((which == PSV_DBG_H1 || which == PSV_DBG_H2) && !c->last_step_vec) return PSV_ERR_BAD_STATE;
     size_t off = 0, size = 0;
     switch (which) {
     case PSV_DBG_H1: off = c->ws.h1_f32; size = B * H * 4; break;

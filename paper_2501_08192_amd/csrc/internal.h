@@ -84,8 +84,15 @@ bool gemm_mfma_supported(int batch, int N, int K);
 constexpr int kSkMaxSplits = 16;
 int gemm_sk_splits(int batch, int N, int K, bool w8);
 bool gemm_sk_supported(int batch, int N, int K);
-hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *x_bf16, float *part,
-                          int batch, int N, int K, hipStream_t s);
+// ssq != null (K % 512 == 0): x_bf16 holds x * gain without the 1/rms factor of its RMSNorm and ssq the partial
+// sums of squares [batch][K / 512] written by launch_resid_sum; the result is multiplied by 1/rms of its batch row.
+hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *x_bf16, const float *ssq, float eps,
+                          float *part, int batch, int N, int K, hipStream_t s);
+// out_res = res + delta (delta: null, or `delta_splits` split-K partials summed in split order), one float4 per
+// thread over grid (H / 512, batch).  gain != null: also out_res * gain as hi/lo bf16 planes (xg_bf16, lo plane
+// plane_stride elements after the hi plane) and the sums of squares per workgroup, ssq[batch][H / 512].
+hipError_t launch_resid_sum(const float *res, const float *delta, int delta_splits, int batch, int H, float *out_res,
+                            const uint16_t *gain, uint16_t *xg_bf16, size_t plane_stride, float *ssq, hipStream_t s);
 // out = sum of the splits; swiglu: N = gate | up columns, out = silu(gate) * up of width N/2.  out_bf16
 // (optional) receives hi/lo planes.
 hipError_t launch_sk_reduce(const float *part, int splits, int batch, int N, bool swiglu, float *out,

@@ -235,6 +235,58 @@ hipError_t launch_add_rmsnorm(const float *res, const float *delta, int delta_sp
     return hipGetLastError();
 }
 
+// Residual add for the matrix-core path, spread over many workgroups: grid (H / 512, batch), one float4 per
+// thread.  out_res = res + delta, where delta may be `delta_splits` split-K partials [split][batch][H] that are
+// summed in split order.  With a gain, the kernel also prepares the next projection's operand without ever seeing
+// a whole row: it stores out_res * gain as hi/lo bf16 planes and the sum of squares of its 512 outputs in
+// ssq[batch][H / 512].  RMSNorm is linear in its 1/rms factor, so that projection runs on the unnormalised planes
+// and multiplies its result by 1/rms of the batch row, which it forms from ssq (k_gemm_sk).
+__global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res, const float *__restrict__ delta,
+                                                   int delta_splits, size_t delta_stride, int H,
+                                                   float *__restrict__ out_res, const uint16_t *__restrict__ gain,
+                                                   uint16_t *__restrict__ xg_bf16, size_t plane_stride,
+                                                   float *__restrict__ ssq)
+{
+    __shared__ float red[2];
+    const int b = blockIdx.y, tid = threadIdx.x;
+    const int i = (blockIdx.x * 128 + tid) * 4;       // H is a multiple of 512: always inside the row
+    const size_t at = (size_t)b * H + i;
+    float4 v = *reinterpret_cast<const float4 *>(res + at);
+    uint2 g = make_uint2(0u, 0u);
+    if (gain) g = *reinterpret_cast<const uint2 *>(gain + i);
+    if (delta) {
+        const float *d = delta + at;
+        float4 t[kSkMaxSplits];   // all loads first (their latencies overlap), then the sum in split order
+#pragma unroll
+        for (int ks = 0; ks < kSkMaxSplits; ++ks)
+            t[ks] = ks < delta_splits ? *reinterpret_cast<const float4 *>(d + ks * delta_stride)
+                                      : make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 e = t[0];
+#pragma unroll
+        for (int ks = 1; ks < kSkMaxSplits; ++ks) { e.x += t[ks].x; e.y += t[ks].y; e.z += t[ks].z; e.w += t[ks].w; }
+        v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w;
+    }
+    *reinterpret_cast<float4 *>(out_res + at) = v;
+    if (!gain) return;
+    uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+    split_bf16(v.x * bf16_lo(g.x), h0, l0); split_bf16(v.y * bf16_hi(g.x), h1, l1);
+    split_bf16(v.z * bf16_lo(g.y), h2, l2); split_bf16(v.w * bf16_hi(g.y), h3, l3);
+    *reinterpret_cast<uint2 *>(xg_bf16 + at) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+    *reinterpret_cast<uint2 *>(xg_bf16 + plane_stride + at) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+    const float ss = wave_sum(v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    if (tid == 0) ssq[(size_t)b * gridDim.x + blockIdx.x] = red[0] + red[1];
+}
+
+hipError_t launch_resid_sum(const float *res, const float *delta, int delta_splits, int batch, int H, float *out_res,
+                            const uint16_t *gain, uint16_t *xg_bf16, size_t plane_stride, float *ssq, hipStream_t s)
+{
+    PSV_LAUNCH(k_resid_sum, dim3(H / 512, batch), dim3(128), 0, s, res, delta, delta_splits, (size_t)batch * H, H,
+               out_res, gain, xg_bf16, plane_stride, ssq);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------ GEMV
 
 // Weight-streaming GEMV on the vector ALU (batch NB <= 2).
@@ -789,6 +841,10 @@ struct GemmSkArgs {
     size_t x_plane;
     float *part;              // [splits][batch][N]
     int batch, N, K, n_slabs, slabs_per_block;
+    // ssq != null: the activations are x * gain without the 1/rms factor of their RMSNorm; ssq[batch][K / 512]
+    // holds partial sums of squares of x (k_resid_sum) and the epilogue multiplies column b by 1/rms(b)
+    const float *ssq;
+    float eps;
 };
 
 template <int NB, bool W8>
@@ -845,6 +901,7 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
     for (int mt = 0; mt < 2; ++mt)
 #pragma unroll
         for (int n = 0; n < NB; ++n) acc[mt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    __shared__ float inv_s[NB * 16];
 
     WFrag wq[PF];
 #pragma unroll
@@ -855,6 +912,30 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
         load_slab(s0, xr[0]);
         if (s0 + 1 < s1) load_slab(s0 + 1, xr[1]);
         store_slab(0, xr[0]);
+    }
+    // 1/rms of every batch row from the partial sums of squares (block order); read in the epilogue only, the
+    // barriers of the main loop make it visible
+    if (tid < NB * 16) {
+        float inv = 1.0f;
+        if (a.ssq) {
+            float tot = 0.f;
+            const int nblk = K / 512;                       // <= 32
+            if (tid < a.batch) {
+                const float *p = a.ssq + (size_t)tid * nblk;
+                if ((nblk & 3) == 0) {                      // all loads at once, then the sum in block order
+                    float4 t[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        t[q] = 4 * q < nblk ? *reinterpret_cast<const float4 *>(p + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) tot = (((tot + t[q].x) + t[q].y) + t[q].z) + t[q].w;
+                } else {
+                    for (int q = 0; q < nblk; ++q) tot += p[q];
+                }
+            }
+            inv = 1.0f / sqrtf(tot / (float)K + a.eps);
+        }
+        inv_s[tid] = inv;
     }
     __syncthreads();
 
@@ -908,9 +989,11 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
 #pragma unroll
             for (int n = 0; n < NB; ++n) {
                 const int b = n * 16 + i;
+                const float inv = inv_s[b];
                 if (b < a.batch)
                     *reinterpret_cast<float4 *>(part + (size_t)b * a.N + r) =
-                        make_float4(acc[mt][n][0] * sc.x, acc[mt][n][1] * sc.y, acc[mt][n][2] * sc.z, acc[mt][n][3] * sc.w);
+                        make_float4(acc[mt][n][0] * sc.x * inv, acc[mt][n][1] * sc.y * inv, acc[mt][n][2] * sc.z * inv,
+                                    acc[mt][n][3] * sc.w * inv);
             }
         }
     }
@@ -944,11 +1027,12 @@ bool gemm_sk_supported(int batch, int N, int K)
     return batch >= 1 && batch <= 64 && N % 16 == 0 && K % 64 == 0;
 }
 
-hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, float *part,
+hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, const float *ssq, float eps, float *part,
                           int batch, int N, int K, hipStream_t s)
 {
     const int nb = (batch + 15) / 16;
     GemmSkArgs a{};
+    a.ssq = ssq; a.eps = eps;
     a.W = W.w; a.W2 = W2.w ? W2.w : W.w; a.scale = W.scale; a.scale2 = W2.w ? W2.scale : W.scale;
     a.split_row = W2.w ? split_row : N; a.xb = xb; a.x_plane = (size_t)nb * 16 * K;
     a.part = part; a.batch = batch; a.N = N; a.K = K; a.n_slabs = K / 64;
