@@ -1697,74 +1697,76 @@ __global__ __launch_bounds__(256) void k_attn_q8(AttnArgs a)
     }
 }
 
-// Merge of the chunk partials of one (sequence, kv head): grid (kv heads, batch), 1024 threads.
-// Softmax weights of the chunks are formed once (LDS), then every output channel sums its chunks
-// in chunk order; when G*128 < 1024 the chunks are dealt to several thread groups whose partial
-// sums are added in group order.  All orders are fixed, so the result is reproducible.
+// Merge of the chunk partials of one (sequence, query head): grid (query heads, batch), 1024 threads = 128
+// channels x 8 groups that share the chunks.  Wave 0 forms the softmax weights of the chunks once (LDS); every
+// thread sums its group's chunks of its channel in chunk order, and the 8 partial sums are added in group order.
+// All orders are fixed, so the result is reproducible.
 __global__ __launch_bounds__(1024) void k_attn_merge(AttnArgs a)
 {
-    __shared__ float wl[16 * kAttnMaxChunks + 16];   // [G][n_chunks] weights, then [G] 1/denominator
+    __shared__ float wl[kAttnMaxChunks + 8];   // weights of the chunks (+ slack for the predicated last batch)
+    __shared__ float inv_den;
     __shared__ float psum[1024];
-    const int kvh = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int j = blockIdx.x, b = blockIdx.y, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int nq = a.nq, nkv = a.nkv, G = nq / nkv, nc = a.n_chunks;
+    const int kvh = j / G, g = j % G;
     const size_t slot0 = ((size_t)b * nkv + kvh) * nc;
-    for (int g = w; g < G; g += 16) {
+    if (w == 0) {
+        constexpr int MU = kAttnMaxChunks / 64;
+        float2 ml[MU];
         float Mx = -1.0e30f;
-        for (int sp = lane; sp < nc; sp += 64) Mx = fmaxf(Mx, a.part_ml[((slot0 + sp) * 16 + g) * 2]);
 #pragma unroll
-        for (int off = 32; off > 0; off >>= 1) Mx = fmaxf(Mx, __shfl_xor(Mx, off, 64));
-        float den = 0.f;
-        for (int sp0 = 0; sp0 < nc; sp0 += 64) {
-            const int sp = sp0 + lane;
-            float wgt = 0.f, l = 0.f;
-            if (sp < nc) {
-                const float m = a.part_ml[((slot0 + sp) * 16 + g) * 2];
-                l = a.part_ml[((slot0 + sp) * 16 + g) * 2 + 1];
-                wgt = l > 0.f ? exp2f(m - Mx) : 0.f;
-                wl[g * nc + sp] = wgt;
-            }
-            den += wave_sum(wgt * l);
+        for (int u = 0; u < MU; ++u) {
+            const int sp = lane + 64 * u;
+            ml[u] = sp < nc ? *reinterpret_cast<const float2 *>(a.part_ml + ((slot0 + sp) * 16 + g) * 2)
+                            : make_float2(-1.0e30f, 0.f);
+            Mx = fmaxf(Mx, ml[u].x);
         }
-        if (lane == 0) wl[G * nc + g] = den > 0.f ? 1.0f / den : 0.f;
+        Mx = wave_max(Mx);
+        float den = 0.f;
+#pragma unroll
+        for (int u = 0; u < MU; ++u) {
+            const int sp = lane + 64 * u;
+            const float wgt = ml[u].y > 0.f ? exp2f(ml[u].x - Mx) : 0.f;
+            if (sp < nc) wl[sp] = wgt;
+            den += wave_sum(wgt * ml[u].y);
+        }
+        if (lane == 0) inv_den = den > 0.f ? 1.0f / den : 0.f;
     }
     __syncthreads();
-    const int outs = G * 128;                              // 128 .. 2048
-    const int S = outs >= 1024 ? 1 : 1024 / outs;          // thread groups sharing the chunks
-    const int per = (nc + S - 1) / S;
-    for (int o0 = 0; o0 < outs; o0 += 1024) {
-        const int o = o0 + (S == 1 ? tid : tid % outs), sg = S == 1 ? 0 : tid / outs;
-        const int g = o >> 7, ch = o & 127;
-        float num = 0.f;
-        if (o < outs) {
-            const int sp_end = min(nc, (sg + 1) * per);
-            int sp = sg * per;
-            for (; sp + 8 <= sp_end; sp += 8) {
-                float v[8];
+    const int ch = tid & 127, sg = tid >> 7;               // 8 groups
+    const int per = (nc + 7) / 8;
+    const int sp_end = min(nc, (sg + 1) * per);
+    const float *po = a.part_o + (slot0 * G + g) * 128 + ch;
+    const size_t stride = (size_t)G * 128;                 // chunk to chunk
+    float num = 0.f;
+    int sp = sg * per;
+    for (; sp + 8 <= sp_end; sp += 8) {
+        float v[8];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) v[u] = a.part_o[((slot0 + sp + u) * G + g) * 128 + ch];
+        for (int u = 0; u < 8; ++u) v[u] = po[(size_t)(sp + u) * stride];
 #pragma unroll
-                for (int u = 0; u < 8; ++u) num = fmaf(wl[g * nc + sp + u], v[u], num);
-            }
-            for (; sp < sp_end; ++sp) num = fmaf(wl[g * nc + sp], a.part_o[((slot0 + sp) * G + g) * 128 + ch], num);
-        }
-        if (S > 1) {
-            psum[tid] = num;
-            __syncthreads();
-            if (sg == 0) {
-                num = 0.f;
-                for (int k = 0; k < S; ++k) num += psum[k * outs + o];   // group order
-            }
-            __syncthreads();
-        }
-        if (sg == 0 && o < outs) {
-            const float r = num * wl[G * nc + g];
-            const size_t idx = ((size_t)b * nq + kvh * G + g) * 128 + ch;
-            a.out_f32[idx] = r;
-            uint32_t hi, lo;
-            split_bf16(r, hi, lo);
-            a.out_bf16[idx] = (uint16_t)hi;
-            a.out_bf16[a.out_plane + idx] = (uint16_t)lo;
-        }
+        for (int u = 0; u < 8; ++u) num = fmaf(wl[sp + u], v[u], num);
+    }
+    {   // ragged end of the group's range, still one batch of loads
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = sp + u < sp_end ? po[(size_t)(sp + u) * stride] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) num = fmaf(sp + u < sp_end ? wl[sp + u] : 0.f, v[u], num);
+    }
+    psum[tid] = num;
+    __syncthreads();
+    if (sg == 0) {
+        num = 0.f;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) num += psum[k * 128 + ch];   // group order
+        const float r = num * inv_den;
+        const size_t idx = ((size_t)b * nq + j) * 128 + ch;
+        a.out_f32[idx] = r;
+        uint32_t hi, lo;
+        split_bf16(r, hi, lo);
+        a.out_bf16[idx] = (uint16_t)hi;
+        a.out_bf16[a.out_plane + idx] = (uint16_t)lo;
     }
 }
 
@@ -1791,7 +1793,7 @@ hipError_t launch_attn_merge(const float *part_ml, const float *part_o, int batc
 {
     AttnArgs a = attn_args(nullptr, nullptr, KvView{}, batch, nq, nkv, sp, const_cast<float *>(part_ml),
                            const_cast<float *>(part_o), out_f32, out_bf16);
-    PSV_LAUNCH(k_attn_merge, dim3(nkv, batch), dim3(1024), 0, s, a);
+    PSV_LAUNCH(k_attn_merge, dim3(nq, batch), dim3(1024), 0, s, a);
     return hipGetLastError();
 }
 
