@@ -385,7 +385,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
 
         if (sk) {
             ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x, u16(w.g_attn), h1b, plane_h, ssq, s));
+            HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x, u16(w.g_attn), h1b, plane_h, w8, ssq, s));
         } else if (!vec) {
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_add_rmsnorm(res, delta, delta_splits, u16(w.g_attn), d.rms_eps, B, H, x, h1, h1b, plane_h, s));
@@ -397,7 +397,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             if (!gemm_sk_supported(B, QR, H)) return PSV_ERR_UNSUPPORTED;
             HIP_TRY(launch_gemm_sk(Wqkv, Mat{}, 0, h1b, ssq, d.rms_eps, part, B, QR, H, s));
             ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H, w8), B, QR, false, qkv, nullptr, s));
+            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H, w8), B, QR, false, qkv, nullptr, false, s));
         } else {
             ST_TRY(projection_mfma(c, w.w_qkv, nullptr, h1b, qkv, nullptr, B, QR, H));
         }
@@ -407,7 +407,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         const bool fuse_merge = vec && gemv_merge_supported(B, nq, sp.n_chunks);
         if (!fuse_merge) {
             ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_attn_merge(pml, po, B, nq, nkv, sp, attn, attnb, s));
+            HIP_TRY(launch_attn_merge(pml, po, B, nq, nkv, sp, attn, attnb, sk && w8, s));
         }
 
         ST_TRY(prof_tag(c, PSV_OP_O));
@@ -430,7 +430,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
 
         if (sk) {
             ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_resid_sum(x, attn_delta, attn_splits, B, H, y, u16(w.g_mlp), h2b, plane_h, ssq, s));
+            HIP_TRY(launch_resid_sum(x, attn_delta, attn_splits, B, H, y, u16(w.g_mlp), h2b, plane_h, w8, ssq, s));
         } else if (!vec) {
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_add_rmsnorm(x, attn_delta, attn_splits, u16(w.g_mlp), d.rms_eps, B, H, y, h2, h2b, plane_h, s));
@@ -442,7 +442,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             if (!gemm_sk_supported(B, 2 * F, H)) return PSV_ERR_UNSUPPORTED;
             HIP_TRY(launch_gemm_sk(Wg, Wu, F, h2b, ssq, d.rms_eps, part, B, 2 * F, H, s));
             ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H, w8), B, 2 * F, true, m, mb, s));
+            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H, w8), B, 2 * F, true, m, mb, w8, s));
         } else {
             ST_TRY(projection_mfma(c, w.w_gate, w.w_up, h2b, m, mb, B, F, H));
         }
@@ -465,7 +465,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         res = y;
     }
     ST_TRY(prof_tag(c, -2));
-    HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x_out, nullptr, nullptr, 0, nullptr, s));
+    HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x_out, nullptr, nullptr, 0, false, nullptr, s));
     if (side_used && c->capturing) {   // a captured side branch has to rejoin the origin stream
         HIP_TRY(hipEventRecord(c->ev_end, c->side));
         HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));

@@ -36,6 +36,11 @@ struct KvView {
     const int32_t *seq_lens;
 };
 
+// Operand of a matrix-core projection as its producer stores it (the `x_bf16` / `out_bf16` arguments below):
+// two bf16 planes (hi, lo; x = hi + lo) of [round_up(batch,16)][K] elements for bf16 weights, or -- `digits` --
+// for int8 weights two int8 digit planes of the same shape followed by one fp32 scale per 128 elements of a row.
+// Both fit the same buffer of 4 * round_up(batch,16) * K bytes.
+
 // A projection matrix in either storage format: bf16 [rows][cols] (scale == nullptr), or int8 codes
 // [rows][cols] with one fp32 scale per row.
 struct Mat {
@@ -92,11 +97,12 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *x_bf16, 
 // thread over grid (H / 512, batch).  gain != null: also out_res * gain as hi/lo bf16 planes (xg_bf16, lo plane
 // plane_stride elements after the hi plane) and the sums of squares per workgroup, ssq[batch][H / 512].
 hipError_t launch_resid_sum(const float *res, const float *delta, int delta_splits, int batch, int H, float *out_res,
-                            const uint16_t *gain, uint16_t *xg_bf16, size_t plane_stride, float *ssq, hipStream_t s);
+                            const uint16_t *gain, uint16_t *xg_bf16, size_t plane_stride, bool digits, float *ssq,
+                            hipStream_t s);
 // out = sum of the splits; swiglu: N = gate | up columns, out = silu(gate) * up of width N/2.  out_bf16
 // (optional) receives hi/lo planes.
 hipError_t launch_sk_reduce(const float *part, int splits, int batch, int N, bool swiglu, float *out,
-                            uint16_t *out_bf16, hipStream_t s);
+                            uint16_t *out_bf16, bool digits, hipStream_t s);
 
 // cos/sin of the rotary angles at position seq_len-1: table [batch][64] (inv_freq null => identity).
 hipError_t launch_rope_table(const int32_t *seq_lens, const double *inv_freq, int max_tokens, int batch,
@@ -107,7 +113,7 @@ hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batc
                        float *part_ml, float *part_o, hipStream_t s);
 // ... and the fixed-order merge of the partials into out_f32 and the hi/lo bf16 planes out_bf16.
 hipError_t launch_attn_merge(const float *part_ml, const float *part_o, int batch, int nq, int nkv, AttnSplit sp,
-                             float *out_f32, uint16_t *out_bf16, hipStream_t s);
+                             float *out_f32, uint16_t *out_bf16, bool digits, hipStream_t s);
 
 // Communication stand-in: one workgroup busy-waits `ticks` of the constant-rate wall clock.
 // `flag` (optional): the kernel stores `seq` there on entry, which releases the gate of this window.

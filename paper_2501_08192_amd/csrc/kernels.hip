@@ -36,6 +36,7 @@ void set_launch_events(hipEvent_t start, hipEvent_t stop)
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 // ------------------------------------------------------------------------------------ helpers
 
@@ -87,6 +88,60 @@ __device__ __forceinline__ float wave_sum(float v)
     return (r0 + r1) + (r2 + r3);
 }
 
+// low bytes of four floats that hold small integers in "magic number" form (x + 1.5 * 2^23)
+__device__ __forceinline__ uint32_t pack_magic_bytes(float a0, float a1, float a2, float a3)
+{
+    const uint32_t lo = __builtin_amdgcn_perm(__float_as_uint(a1), __float_as_uint(a0), 0x0c0c0400u);   // a0.b0 | a1.b0 << 8
+    const uint32_t hi = __builtin_amdgcn_perm(__float_as_uint(a3), __float_as_uint(a2), 0x04000c0cu);   // a2.b0 << 16 | a3.b0 << 24
+    return lo | hi;
+}
+
+// Two int8 digits of t (|t| <= 127.5): d1 = rint(t), d2 = rint(254 * (t - d1)); both returned in magic form.
+__device__ __forceinline__ void two_digits(float t, float &m1, float &m2)
+{
+    const float kMagic = 12582912.0f;   // 1.5 * 2^23: adding it rounds to an integer (ties to even)
+    m1 = t + kMagic;
+    const float r = t - (m1 - kMagic);
+    m2 = fmaf(r, 254.0f, kMagic);
+}
+
+// Maximum over aligned groups of 32 lanes, returned in every lane of the group (all lanes must be active).
+template <int CTRL>
+__device__ __forceinline__ float dpp_max(float v)
+{
+    const int t = __builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true);
+    return fmaxf(v, __int_as_float(t));
+}
+__device__ __forceinline__ float max32(float v)
+{
+    v = dpp_max<0xB1>(v);    // quad_perm [1,0,3,2]
+    v = dpp_max<0x4E>(v);    // quad_perm [2,3,0,1]
+    v = dpp_max<0x141>(v);   // row_half_mirror
+    v = dpp_max<0x140>(v);   // row_mirror: every lane holds the maximum of its row of 16
+    return fmaxf(v, __shfl_xor(v, 16, 64));
+}
+
+// Operand format of the int8 matrix-core projections ("digit planes"): an activation row is cut into blocks of
+// 128 consecutive elements; every element is stored as two int8 digits, x ~ s * (d1 + d2 / 254) with s = (largest
+// magnitude of the block) / 127, which keeps 15-16 bits of the block's largest element.  Plane d1 is [rows][K]
+// bytes at `base`, plane d2 follows `plane` bytes later, the block scales [rows][K / 128] fp32 after both.
+// Called by the 32 consecutive lanes that hold one block, four elements each (k0 = first of the lane's four).
+__device__ __forceinline__ void store_digits4(uint8_t *base, size_t plane, int K, size_t row, int k0, float4 v)
+{
+    const float amax = max32(fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+    const float inv = amax > 0.f ? 127.0f / amax : 0.f;
+    float a1[4], a2[4];
+    two_digits(v.x * inv, a1[0], a2[0]);
+    two_digits(v.y * inv, a1[1], a2[1]);
+    two_digits(v.z * inv, a1[2], a2[2]);
+    two_digits(v.w * inv, a1[3], a2[3]);
+    uint8_t *p = base + row * K + k0;
+    *reinterpret_cast<uint32_t *>(p) = pack_magic_bytes(a1[0], a1[1], a1[2], a1[3]);
+    *reinterpret_cast<uint32_t *>(p + plane) = pack_magic_bytes(a2[0], a2[1], a2[2], a2[3]);
+    if ((threadIdx.x & 31) == 0)
+        reinterpret_cast<float *>(base + 2 * plane)[row * (K / 128) + k0 / 128] = amax / 127.0f;
+}
+
 // Maximum over the 64 lanes of a wave, returned in every lane (all lanes must be active).
 __device__ __forceinline__ float wave_max(float v)
 {
@@ -124,17 +179,6 @@ __device__ __forceinline__ float dot8(uint2 w, const float (&x)[8], float acc)
     acc = fmaf(i8f<2>(w.y), x[6], acc);
     acc = fmaf(i8f<3>(w.y), x[7], acc);
     return acc;
-}
-
-// 8 int8 codes -> 8 bf16 (exact: a code has 7 significant bits) in MFMA fragment order
-__device__ __forceinline__ uint4 i8x8_to_bf16(uint32_t w0, uint32_t w1)
-{
-    // perm selector: high halves of two floats -> one packed bf16 pair
-    const uint32_t p0 = __builtin_amdgcn_perm(__float_as_uint(i8f<1>(w0)), __float_as_uint(i8f<0>(w0)), 0x07060302u);
-    const uint32_t p1 = __builtin_amdgcn_perm(__float_as_uint(i8f<3>(w0)), __float_as_uint(i8f<2>(w0)), 0x07060302u);
-    const uint32_t p2 = __builtin_amdgcn_perm(__float_as_uint(i8f<1>(w1)), __float_as_uint(i8f<0>(w1)), 0x07060302u);
-    const uint32_t p3 = __builtin_amdgcn_perm(__float_as_uint(i8f<3>(w1)), __float_as_uint(i8f<2>(w1)), 0x07060302u);
-    return make_uint4(p0, p1, p2, p3);
 }
 
 // dot of 8 bf16 weights (one 16-byte word) with 8 fp32 activations
@@ -245,7 +289,7 @@ __global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res
                                                    int delta_splits, size_t delta_stride, int H,
                                                    float *__restrict__ out_res, const uint16_t *__restrict__ gain,
                                                    uint16_t *__restrict__ xg_bf16, size_t plane_stride,
-                                                   float *__restrict__ ssq)
+                                                   int digits, float *__restrict__ ssq)
 {
     __shared__ float red[2];
     const int b = blockIdx.y, tid = threadIdx.x;
@@ -268,11 +312,15 @@ __global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res
     }
     *reinterpret_cast<float4 *>(out_res + at) = v;
     if (!gain) return;
-    uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
-    split_bf16(v.x * bf16_lo(g.x), h0, l0); split_bf16(v.y * bf16_hi(g.x), h1, l1);
-    split_bf16(v.z * bf16_lo(g.y), h2, l2); split_bf16(v.w * bf16_hi(g.y), h3, l3);
-    *reinterpret_cast<uint2 *>(xg_bf16 + at) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-    *reinterpret_cast<uint2 *>(xg_bf16 + plane_stride + at) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+    const float4 xg = make_float4(v.x * bf16_lo(g.x), v.y * bf16_hi(g.x), v.z * bf16_lo(g.y), v.w * bf16_hi(g.y));
+    if (digits) {   // operand of an int8 projection
+        store_digits4(reinterpret_cast<uint8_t *>(xg_bf16), plane_stride, H, (size_t)b, i, xg);
+    } else {
+        uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+        split_bf16(xg.x, h0, l0); split_bf16(xg.y, h1, l1); split_bf16(xg.z, h2, l2); split_bf16(xg.w, h3, l3);
+        *reinterpret_cast<uint2 *>(xg_bf16 + at) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+        *reinterpret_cast<uint2 *>(xg_bf16 + plane_stride + at) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+    }
     const float ss = wave_sum(v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w);
     if ((tid & 63) == 0) red[tid >> 6] = ss;
     __syncthreads();
@@ -280,10 +328,11 @@ __global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res
 }
 
 hipError_t launch_resid_sum(const float *res, const float *delta, int delta_splits, int batch, int H, float *out_res,
-                            const uint16_t *gain, uint16_t *xg_bf16, size_t plane_stride, float *ssq, hipStream_t s)
+                            const uint16_t *gain, uint16_t *xg_bf16, size_t plane_stride, bool digits, float *ssq,
+                            hipStream_t s)
 {
     PSV_LAUNCH(k_resid_sum, dim3(H / 512, batch), dim3(128), 0, s, res, delta, delta_splits, (size_t)batch * H, H,
-               out_res, gain, xg_bf16, plane_stride, ssq);
+               out_res, gain, xg_bf16, plane_stride, digits ? 1 : 0, ssq);
     return hipGetLastError();
 }
 
@@ -834,8 +883,7 @@ hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_
 // result of batch x rows floats).  Splits are summed later in split order by the consumer (k_sk_reduce or
 // k_add_rmsnorm): deterministic, no atomics.
 struct GemmSkArgs {
-    const void *W, *W2;       // rows >= split_row are taken from W2 (row - split_row): gate | up in one launch;
-    const float *scale, *scale2;   // bf16, or (template W8) int8 codes with per-row scales
+    const uint16_t *W, *W2;   // rows >= split_row are taken from W2 (row - split_row): gate | up in one launch
     int split_row;
     const uint16_t *xb;       // hi plane [round_up(batch,16)][K], lo plane x_plane elements further
     size_t x_plane;
@@ -847,37 +895,32 @@ struct GemmSkArgs {
     float eps;
 };
 
-template <int NB, bool W8>
+template <int NB>
 __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
 {
-    constexpr int PF = W8 ? 8 : 4;   // slabs of weight fragments in flight per wave: 16 KiB either way
-    constexpr int WB = W8 ? 1 : 2;   // bytes per weight
+    constexpr int PF = 4;   // slabs of weight fragments in flight per wave (8 measured no faster)
     __shared__ uint4 xs[2][NB * 4][64];   // [buffer][(batch tile*2 + plane)*2 + k half][lane]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
     const int row_base = blockIdx.x * 128 + w * 32;
     const int s0 = blockIdx.y * a.slabs_per_block, s1 = min(s0 + a.slabs_per_block, a.n_slabs);
     const int K = a.K;
 
-    // Lane (i, g) owns elements g*16 .. g*16+15 of row i of every 64-element slab: 32 contiguous bytes of
-    // bf16 (two fragments), or 16 bytes of int8 codes that are widened to the same two fragments on use.
-    const char *wp[2];
+    // Lane (i, g) owns elements g*16 .. g*16+15 of row i of every 64-element slab: 32 contiguous bytes = two fragments.
+    const uint16_t *wp[2];
     bool wok[2];
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
         const int r = row_base + mt * 16 + i;
         wok[mt] = r < a.N;
         const int rr = wok[mt] ? r : 0;
-        const char *base = rr < a.split_row ? static_cast<const char *>(a.W) + (size_t)rr * K * WB
-                                            : static_cast<const char *>(a.W2) + (size_t)(rr - a.split_row) * K * WB;
-        wp[mt] = base + g * 16 * WB;
+        wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 16;
     }
-    struct WFrag { uint4 a0[2], a1[W8 ? 1 : 2]; };   // int8: a0 holds all 16 codes
+    struct WFrag { uint4 a0[2], a1[2]; };
     auto load_w = [&](int s, WFrag &f) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
-            const char *p = wp[mt] + (size_t)s * 64 * WB;
-            f.a0[mt] = wok[mt] ? *reinterpret_cast<const uint4 *>(p) : zero16();
-            if constexpr (!W8) f.a1[mt] = wok[mt] ? *reinterpret_cast<const uint4 *>(p + 16) : zero16();
+            f.a0[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64) : zero16();
+            f.a1[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64 + 8) : zero16();
         }
     };
     // activation slab: NB*256 16-byte units, unit u = ((tile*2 + plane)*16 + row)*8 + segment
@@ -954,15 +997,8 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
                     const bf16x8 bl1 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 1) * 2 + 1][lane]);
 #pragma unroll
                     for (int mt = 0; mt < 2; ++mt) {
-                        bf16x8 a0, a1;
-                        if constexpr (W8) {
-                            const uint4 c = wq[q].a0[mt];
-                            a0 = __builtin_bit_cast(bf16x8, i8x8_to_bf16(c.x, c.y));
-                            a1 = __builtin_bit_cast(bf16x8, i8x8_to_bf16(c.z, c.w));
-                        } else {
-                            a0 = __builtin_bit_cast(bf16x8, wq[q].a0[mt]);
-                            a1 = __builtin_bit_cast(bf16x8, wq[q].a1[mt]);
-                        }
+                        const bf16x8 a0 = __builtin_bit_cast(bf16x8, wq[q].a0[mt]);
+                        const bf16x8 a1 = __builtin_bit_cast(bf16x8, wq[q].a1[mt]);
                         acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bh0, acc[mt][n], 0, 0, 0);
                         acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bh1, acc[mt][n], 0, 0, 0);
                         acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bl0, acc[mt][n], 0, 0, 0);
@@ -982,10 +1018,178 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
     for (int mt = 0; mt < 2; ++mt) {
         const int r = row_base + mt * 16 + 4 * g;
         if (r < a.N) {
-            float4 sc = make_float4(1.f, 1.f, 1.f, 1.f);
-            if (W8)   // split_row is a multiple of 4, so the four rows share a matrix
-                sc = r < a.split_row ? *reinterpret_cast<const float4 *>(a.scale + r)
-                                     : *reinterpret_cast<const float4 *>(a.scale2 + (r - a.split_row));
+#pragma unroll
+            for (int n = 0; n < NB; ++n) {
+                const int b = n * 16 + i;
+                const float inv = inv_s[b];
+                if (b < a.batch)
+                    *reinterpret_cast<float4 *>(part + (size_t)b * a.N + r) =
+                        make_float4(acc[mt][n][0] * inv, acc[mt][n][1] * inv, acc[mt][n][2] * inv, acc[mt][n][3] * inv);
+            }
+        }
+    }
+}
+
+// The same split-K projection for int8 weights, entirely on the int8 matrix cores: the weight codes are the A
+// operand as they are (16 bytes = 16 consecutive k of one row per lane and 64-element slab), the activations
+// arrive as two int8 digit planes with one scale per 128-element block (store_digits4) and are the B operand.
+// Each digit has its own exact i32 accumulator; at the end of every 128-element block (two slabs) the pair is
+// folded into the fp32 accumulator as scale/254 * (254*D1 + D2).  No per-element conversion of weights anywhere.
+// (128-element slabs, i.e. whole 128-byte lines per row and step, measured slower: 19.6 -> 25 us on the 70B-shaped
+// gate/up matrix at batch 8.)
+struct GemmI8Args {
+    const int8_t *W, *W2;          // rows >= split_row come from W2
+    const float *scale, *scale2;   // per-row weight scales
+    int split_row;
+    const uint8_t *xd;             // digit plane d1 [round_up(batch,16)][K]; d2 x_plane bytes later; then the block scales
+    size_t x_plane;
+    float *part;                   // [splits][batch][N]
+    int batch, N, K, n_slabs, slabs_per_block;
+    const float *ssq;              // see GemmSkArgs
+    float eps;
+};
+
+template <int NB>
+__global__ __launch_bounds__(256) void k_gemm_sk_i8(GemmI8Args a)
+{
+    constexpr int PF = 8;                          // slabs of weight codes in flight per wave (2 x 16 bytes each)
+    __shared__ uint4 xs[2][NB * 2][64];            // [buffer][batch tile * 2 + digit][lane]
+    __shared__ float bs[2][NB * 16];               // block scale of each batch row for the buffered slab
+    __shared__ float inv_s[NB * 16];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
+    const int row_base = blockIdx.x * 128 + w * 32;
+    const int s0 = blockIdx.y * a.slabs_per_block, s1 = min(s0 + a.slabs_per_block, a.n_slabs);
+    const int K = a.K;
+    const float *bscale = reinterpret_cast<const float *>(a.xd + 2 * a.x_plane);
+    const int nblk128 = K / 128;
+
+    const int8_t *wp[2];
+    bool wok[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const int r = row_base + mt * 16 + i;
+        wok[mt] = r < a.N;
+        const int rr = wok[mt] ? r : 0;
+        wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 16;
+    }
+    // Lane (i, g) owns bytes g*16 .. g*16+15 of row i of every 64-element slab: the A operand of one MFMA.
+    struct WFrag { uint4 c[2]; };
+    auto load_w = [&](int s, WFrag &f) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+            f.c[mt] = wok[mt] ? *reinterpret_cast<const uint4 *>(wp[mt] + (size_t)s * 64) : zero16();
+    };
+    // activation slab: NB*128 16-byte units, unit u = ((tile*2 + digit)*16 + row)*4 + segment
+    constexpr int NU = (NB + 1) / 2;
+    struct SlabRegs { uint4 r[NU]; float sc; };
+    auto load_slab = [&](int s, SlabRegs &sr) {
+#pragma unroll
+        for (int j = 0; j < NU; ++j) {
+            const int u = tid + j * 256, n = u >> 7, dgt = (u >> 6) & 1, row = (u >> 2) & 15, seg = u & 3;
+            sr.r[j] = u < NB * 128 ? *reinterpret_cast<const uint4 *>(a.xd + (size_t)dgt * a.x_plane +
+                                                                       (size_t)(n * 16 + row) * K + (size_t)s * 64 + seg * 16)
+                                   : zero16();
+        }
+        sr.sc = tid < NB * 16 ? bscale[(size_t)tid * nblk128 + (s >> 1)] : 0.f;
+    };
+    auto store_slab = [&](int buf, const SlabRegs &sr) {
+#pragma unroll
+        for (int j = 0; j < NU; ++j) {
+            const int u = tid + j * 256, n = u >> 7, dgt = (u >> 6) & 1, row = (u >> 2) & 15, seg = u & 3;
+            if (u < NB * 128) xs[buf][n * 2 + dgt][seg * 16 + row] = sr.r[j];   // B operand: lane (row, segment)
+        }
+        if (tid < NB * 16) bs[buf][tid] = sr.sc;
+    };
+    f32x4 acc[2][NB];
+    i32x4 d1[2][NB], d2[2][NB];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+            acc[mt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+            d1[mt][n] = i32x4{0, 0, 0, 0};
+            d2[mt][n] = i32x4{0, 0, 0, 0};
+        }
+
+    WFrag wq[PF];
+#pragma unroll
+    for (int q = 0; q < PF; ++q)
+        if (s0 + q < s1) load_w(s0 + q, wq[q]);
+    SlabRegs xr[2];
+    if (s0 < s1) {
+        load_slab(s0, xr[0]);
+        if (s0 + 1 < s1) load_slab(s0 + 1, xr[1]);
+        store_slab(0, xr[0]);
+    }
+    if (tid < NB * 16) {   // 1/rms of every batch row (see k_gemm_sk)
+        float inv = 1.0f;
+        if (a.ssq) {
+            float tot = 0.f;
+            const int nblk = K / 512;
+            if (tid < a.batch) {
+                const float *p = a.ssq + (size_t)tid * nblk;
+                if ((nblk & 3) == 0) {
+                    float4 t[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        t[q] = 4 * q < nblk ? *reinterpret_cast<const float4 *>(p + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) tot = (((tot + t[q].x) + t[q].y) + t[q].z) + t[q].w;
+                } else {
+                    for (int q = 0; q < nblk; ++q) tot += p[q];
+                }
+            }
+            inv = 1.0f / sqrtf(tot / (float)K + a.eps);
+        }
+        inv_s[tid] = inv;
+    }
+    __syncthreads();
+
+    for (int sb = s0; sb < s1; sb += PF) {
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            const int s = sb + q;
+            if (s < s1) {                       // uniform over the workgroup
+                const int buf = q & 1;          // (s - s0) & 1, because PF is even
+                if (s + 2 < s1) load_slab(s + 2, xr[q & 1]);
+                const bool fold = (s & 1) || s + 1 == s1;   // end of a 128-element block, or of this workgroup's range
+#pragma unroll
+                for (int n = 0; n < NB; ++n) {
+                    const i32x4 x1 = __builtin_bit_cast(i32x4, xs[buf][n * 2 + 0][lane]);
+                    const i32x4 x2 = __builtin_bit_cast(i32x4, xs[buf][n * 2 + 1][lane]);
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt) {
+                        const i32x4 wc = __builtin_bit_cast(i32x4, wq[q].c[mt]);
+                        d1[mt][n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wc, x1, d1[mt][n], 0, 0, 0);
+                        d2[mt][n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wc, x2, d2[mt][n], 0, 0, 0);
+                    }
+                    if (fold) {
+                        const float sc = bs[buf][n * 16 + i] * (1.0f / 254.0f);
+#pragma unroll
+                        for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                acc[mt][n][j] = fmaf(sc, (float)(d1[mt][n][j] * 254 + d2[mt][n][j]), acc[mt][n][j]);
+                            d1[mt][n] = i32x4{0, 0, 0, 0};
+                            d2[mt][n] = i32x4{0, 0, 0, 0};
+                        }
+                    }
+                }
+                if (s + PF < s1) load_w(s + PF, wq[q]);
+                if (s + 1 < s1) store_slab(buf ^ 1, xr[(q + 1) & 1]);
+                __syncthreads();
+            }
+        }
+    }
+
+    // D fragment: lane holds rows 4g..4g+3 of batch column i
+    float *part = a.part + (size_t)blockIdx.y * a.batch * a.N;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const int r = row_base + mt * 16 + 4 * g;
+        if (r < a.N) {
+            const float4 sc = r < a.split_row ? *reinterpret_cast<const float4 *>(a.scale + r)
+                                              : *reinterpret_cast<const float4 *>(a.scale2 + (r - a.split_row));
 #pragma unroll
             for (int n = 0; n < NB; ++n) {
                 const int b = n * 16 + i;
@@ -1031,30 +1235,38 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
                           int batch, int N, int K, hipStream_t s)
 {
     const int nb = (batch + 15) / 16;
+    if (W.scale) {   // int8 weights: xb holds digit planes (bytes), see k_gemm_sk_i8
+        GemmI8Args q{};
+        q.W = static_cast<const int8_t *>(W.w); q.W2 = static_cast<const int8_t *>(W2.w ? W2.w : W.w);
+        q.scale = W.scale; q.scale2 = W2.w ? W2.scale : W.scale; q.split_row = W2.w ? split_row : N;
+        q.xd = reinterpret_cast<const uint8_t *>(xb); q.x_plane = (size_t)nb * 16 * K;
+        q.part = part; q.batch = batch; q.N = N; q.K = K; q.n_slabs = K / 64; q.ssq = ssq; q.eps = eps;
+        const int splits = gemm_sk_splits(batch, N, K, true);
+        q.slabs_per_block = (q.n_slabs + splits - 1) / splits;
+        const dim3 grid((N + 127) / 128, splits);
+        switch (nb) {
+        case 1: PSV_LAUNCH(k_gemm_sk_i8<1>, grid, dim3(256), 0, s, q); break;
+        case 2: PSV_LAUNCH(k_gemm_sk_i8<2>, grid, dim3(256), 0, s, q); break;
+        case 3: PSV_LAUNCH(k_gemm_sk_i8<3>, grid, dim3(256), 0, s, q); break;
+        case 4: PSV_LAUNCH(k_gemm_sk_i8<4>, grid, dim3(256), 0, s, q); break;
+        default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
     GemmSkArgs a{};
     a.ssq = ssq; a.eps = eps;
-    a.W = W.w; a.W2 = W2.w ? W2.w : W.w; a.scale = W.scale; a.scale2 = W2.w ? W2.scale : W.scale;
+    a.W = static_cast<const uint16_t *>(W.w); a.W2 = static_cast<const uint16_t *>(W2.w ? W2.w : W.w);
     a.split_row = W2.w ? split_row : N; a.xb = xb; a.x_plane = (size_t)nb * 16 * K;
     a.part = part; a.batch = batch; a.N = N; a.K = K; a.n_slabs = K / 64;
-    const int splits = gemm_sk_splits(batch, N, K, W.scale != nullptr);
+    const int splits = gemm_sk_splits(batch, N, K, false);
     a.slabs_per_block = (a.n_slabs + splits - 1) / splits;
     const dim3 grid((N + 127) / 128, splits);
-    if (W.scale) {
-        switch (nb) {
-        case 1: PSV_LAUNCH((k_gemm_sk<1, true>), grid, dim3(256), 0, s, a); break;
-        case 2: PSV_LAUNCH((k_gemm_sk<2, true>), grid, dim3(256), 0, s, a); break;
-        case 3: PSV_LAUNCH((k_gemm_sk<3, true>), grid, dim3(256), 0, s, a); break;
-        case 4: PSV_LAUNCH((k_gemm_sk<4, true>), grid, dim3(256), 0, s, a); break;
-        default: return hipErrorInvalidValue;
-        }
-    } else {
-        switch (nb) {
-        case 1: PSV_LAUNCH((k_gemm_sk<1, false>), grid, dim3(256), 0, s, a); break;
-        case 2: PSV_LAUNCH((k_gemm_sk<2, false>), grid, dim3(256), 0, s, a); break;
-        case 3: PSV_LAUNCH((k_gemm_sk<3, false>), grid, dim3(256), 0, s, a); break;
-        case 4: PSV_LAUNCH((k_gemm_sk<4, false>), grid, dim3(256), 0, s, a); break;
-        default: return hipErrorInvalidValue;
-        }
+    switch (nb) {
+    case 1: PSV_LAUNCH(k_gemm_sk<1>, grid, dim3(256), 0, s, a); break;
+    case 2: PSV_LAUNCH(k_gemm_sk<2>, grid, dim3(256), 0, s, a); break;
+    case 3: PSV_LAUNCH(k_gemm_sk<3>, grid, dim3(256), 0, s, a); break;
+    case 4: PSV_LAUNCH(k_gemm_sk<4>, grid, dim3(256), 0, s, a); break;
+    default: return hipErrorInvalidValue;
     }
     return hipGetLastError();
 }
@@ -1063,7 +1275,8 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
 // halves and the result is silu(gate) * up, [batch][N/2], stored as fp32 and as hi/lo bf16 planes.
 template <bool SWIGLU>
 __global__ __launch_bounds__(256) void k_sk_reduce(const float *__restrict__ part, int splits, int batch, int N,
-                                                   float *__restrict__ out, uint16_t *__restrict__ out_bf16, size_t out_plane)
+                                                   float *__restrict__ out, uint16_t *__restrict__ out_bf16, size_t out_plane,
+                                                   int digits)
 {
     const int NO = SWIGLU ? N / 2 : N;                 // output columns
     const size_t total4 = (size_t)batch * NO / 4;
@@ -1091,7 +1304,9 @@ __global__ __launch_bounds__(256) void k_sk_reduce(const float *__restrict__ par
             v.x = silu_mul(v.x, u.x); v.y = silu_mul(v.y, u.y); v.z = silu_mul(v.z, u.z); v.w = silu_mul(v.w, u.w);
         }
         *reinterpret_cast<float4 *>(out + b * NO + c) = v;
-        if (out_bf16) {
+        if (out_bf16 && digits) {   // whole waves take this branch together (NO is a multiple of 256)
+            store_digits4(reinterpret_cast<uint8_t *>(out_bf16), out_plane, NO, b, (int)c, v);
+        } else if (out_bf16) {
             uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
             split_bf16(v.x, h0, l0); split_bf16(v.y, h1, l1); split_bf16(v.z, h2, l2); split_bf16(v.w, h3, l3);
             *reinterpret_cast<uint2 *>(out_bf16 + b * NO + c) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
@@ -1101,7 +1316,7 @@ __global__ __launch_bounds__(256) void k_sk_reduce(const float *__restrict__ par
 }
 
 hipError_t launch_sk_reduce(const float *part, int splits, int batch, int N, bool swiglu, float *out,
-                            uint16_t *out_bf16, hipStream_t s)
+                            uint16_t *out_bf16, bool digits, hipStream_t s)
 {
     const int NO = swiglu ? N / 2 : N;
     const size_t total4 = (size_t)batch * NO / 4;
@@ -1110,9 +1325,9 @@ hipError_t launch_sk_reduce(const float *part, int splits, int batch, int N, boo
     if (blocks < 1) blocks = 1;
     const size_t out_plane = (size_t)((batch + 15) / 16 * 16) * NO;
     if (swiglu)
-        PSV_LAUNCH(k_sk_reduce<true>, dim3(blocks), dim3(256), 0, s, part, splits, batch, N, out, out_bf16, out_plane);
+        PSV_LAUNCH(k_sk_reduce<true>, dim3(blocks), dim3(256), 0, s, part, splits, batch, N, out, out_bf16, out_plane, digits ? 1 : 0);
     else
-        PSV_LAUNCH(k_sk_reduce<false>, dim3(blocks), dim3(256), 0, s, part, splits, batch, N, out, out_bf16, out_plane);
+        PSV_LAUNCH(k_sk_reduce<false>, dim3(blocks), dim3(256), 0, s, part, splits, batch, N, out, out_bf16, out_plane, digits ? 1 : 0);
     return hipGetLastError();
 }
 
@@ -1185,6 +1400,7 @@ struct AttnArgs {
     float *out_f32;            // [batch][nq*128]
     uint16_t *out_bf16;        // same as hi/lo bf16 planes (operand of the MFMA O projection)
     size_t out_plane;          // distance between the planes, elements
+    int out_digits;            // out_bf16 receives int8 digit planes (operand of an int8 projection) instead
 };
 
 // Split-K decode attention with everything around it fused in.  grid (chunks, kv heads, batch),
@@ -1424,24 +1640,6 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 // is exactly the B operand of the second contraction.  Key scales multiply the scores, value scales the
 // probabilities.  The appended rows are quantised per row in single precision (scale = max|v| / 127,
 // code = rint(v / scale)), stored, and re-read by the wave whose tile holds them.
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-
-// low bytes of four floats that hold small integers in "magic number" form (x + 1.5 * 2^23)
-__device__ __forceinline__ uint32_t pack_magic_bytes(float a0, float a1, float a2, float a3)
-{
-    const uint32_t lo = __builtin_amdgcn_perm(__float_as_uint(a1), __float_as_uint(a0), 0x0c0c0400u);   // a0.b0 | a1.b0 << 8
-    const uint32_t hi = __builtin_amdgcn_perm(__float_as_uint(a3), __float_as_uint(a2), 0x04000c0cu);   // a2.b0 << 16 | a3.b0 << 24
-    return lo | hi;
-}
-
-// Two int8 digits of t (|t| <= 127.5): d1 = rint(t), d2 = rint(254 * (t - d1)); both returned in magic form.
-__device__ __forceinline__ void two_digits(float t, float &m1, float &m2)
-{
-    const float kMagic = 12582912.0f;   // 1.5 * 2^23: adding it rounds to an integer (ties to even)
-    m1 = t + kMagic;
-    const float r = t - (m1 - kMagic);
-    m2 = fmaf(r, 254.0f, kMagic);
-}
 
 __global__ __launch_bounds__(256) void k_attn_q8(AttnArgs a)
 {
@@ -1763,10 +1961,21 @@ __global__ __launch_bounds__(1024) void k_attn_merge(AttnArgs a)
         const float r = num * inv_den;
         const size_t idx = ((size_t)b * nq + j) * 128 + ch;
         a.out_f32[idx] = r;
-        uint32_t hi, lo;
-        split_bf16(r, hi, lo);
-        a.out_bf16[idx] = (uint16_t)hi;
-        a.out_bf16[a.out_plane + idx] = (uint16_t)lo;
+        if (!a.out_digits) {
+            uint32_t hi, lo;
+            split_bf16(r, hi, lo);
+            a.out_bf16[idx] = (uint16_t)hi;
+            a.out_bf16[a.out_plane + idx] = (uint16_t)lo;
+        }
+        psum[ch] = r;      // the writers of psum[0..127] are these same threads
+    }
+    if (!a.out_digits) return;
+    __syncthreads();
+    if (tid < 32) {        // one head = one 128-element block of the digit planes: 32 lanes x 4 channels
+        const float4 v = make_float4(psum[4 * tid], psum[4 * tid + 1], psum[4 * tid + 2], psum[4 * tid + 3]);
+        // only half of the wave is here, so the block maximum comes from LDS-free DPP steps within rows of 16 and
+        // one exchange between the two rows, all inside lanes 0..31
+        store_digits4(reinterpret_cast<uint8_t *>(a.out_bf16), a.out_plane, nq * 128, (size_t)b, j * 128 + 4 * tid, v);
     }
 }
 
@@ -1774,7 +1983,7 @@ static AttnArgs attn_args(const float *qkv, const float2 *rope, KvView kv, int b
                           float *part_ml, float *part_o, float *out_f32, uint16_t *out_bf16)
 {
     const size_t out_plane = (size_t)((batch + 15) / 16 * 16) * nq * 128;
-    return AttnArgs{qkv, rope, kv, nq, nkv, sp.chunk_tokens, sp.n_chunks, part_ml, part_o, out_f32, out_bf16, out_plane};
+    return AttnArgs{qkv, rope, kv, nq, nkv, sp.chunk_tokens, sp.n_chunks, part_ml, part_o, out_f32, out_bf16, out_plane, 0};
 }
 
 hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batch, int nq, int nkv, AttnSplit sp,
@@ -1789,10 +1998,11 @@ hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batc
 }
 
 hipError_t launch_attn_merge(const float *part_ml, const float *part_o, int batch, int nq, int nkv, AttnSplit sp,
-                             float *out_f32, uint16_t *out_bf16, hipStream_t s)
+                             float *out_f32, uint16_t *out_bf16, bool digits, hipStream_t s)
 {
     AttnArgs a = attn_args(nullptr, nullptr, KvView{}, batch, nq, nkv, sp, const_cast<float *>(part_ml),
                            const_cast<float *>(part_o), out_f32, out_bf16);
+    a.out_digits = digits ? 1 : 0;
     PSV_LAUNCH(k_attn_merge, dim3(nq, batch), dim3(1024), 0, s, a);
     return hipGetLastError();
 }
