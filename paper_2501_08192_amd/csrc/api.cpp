@@ -112,7 +112,6 @@ struct psv_ctx {
     unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
     bool capturing = false;
     bool last_step_vec = false;                  // the last step formed h1 / h2 (vector path)
-    bool old_mfma = false;                       // A/B switch: K-split-in-workgroup GEMM instead of the split-K one
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(wsp + off); }
 };
@@ -177,16 +176,6 @@ psv_status prof_tag(psv_ctx *c, int32_t op)
     set_launch_events(nullptr, ev);
     if (op == c->profile_op && c->prof_last) c->prof_pairs.push_back({c->prof_last, ev});
     c->prof_last = ev;
-    return PSV_OK;
-}
-
-// y[b][:] = W x[b][:] (optionally the SwiGLU pair) on the matrix cores; x as bf16.
-psv_status projection_mfma(psv_ctx *c, const void *W, const void *W2, const uint16_t *x_bf16, float *out,
-                           uint16_t *out_bf16, int batch, int N, int K)
-{
-    if (!gemm_mfma_supported(batch, N, K)) return PSV_ERR_UNSUPPORTED;
-    HIP_TRY(launch_gemm_mfma(static_cast<const uint16_t *>(W), static_cast<const uint16_t *>(W2), x_bf16, out, out_bf16,
-                             batch, N, K, c->main));
     return PSV_OK;
 }
 
@@ -362,15 +351,15 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     const bool w8 = d.weight_format == PSV_FMT_INT8;
     const size_t plane_h = (size_t)((B + 15) / 16 * 16) * H;   // hi -> lo plane distance of the bf16 activations
 
-    // Small batches run every projection on the vector ALU with the normalisation fused into the
-    // prologue; larger ones use the matrix cores (split-K GEMM + reductions) with a separate normalisation.
-    // (Measured crossover: the vector path loses ~10 us per layer and extra batch row to register pressure;
-    // batch 1 always wins there, batch 2 only on the 8B-sized matrices.)
+    // Batch 1 (and batch 2 on 8B-sized matrices) runs every projection on the vector ALU with the normalisation
+    // fused into the prologue; larger batches use the matrix cores: split-K GEMMs whose partials are summed by the
+    // residual kernel (O, down) or a small reduction kernel (QKV; gate/up with SwiGLU), the RMSNorm factor being
+    // applied in the epilogue of the GEMM that follows the residual kernel.
+    // (Measured crossover: the vector path loses ~10 us per layer and extra batch row to register pressure.)
     const bool vec = (B == 1 || (B == 2 && H <= 4096)) && gemv_supported(B, QR, H) && gemv_supported(B, H, QD) &&
                      gemv_supported(B, F, H) && gemv_supported(B, H, F);
-    const bool sk = !vec && !c->old_mfma;
-    c->last_step_vec = !sk;
-    if (!vec && !sk && w8) return PSV_ERR_UNSUPPORTED;   // the older matrix-core kernel reads bf16 weights only
+    const bool sk = !vec;
+    c->last_step_vec = vec;
     float *part = c->at<float>(c->ws.part), *ssq = c->at<float>(c->ws.ssq);
 
     ST_TRY(prof_tag(c, -2));
@@ -386,20 +375,15 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         if (sk) {
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x, u16(w.g_attn), h1b, plane_h, w8, ssq, s));
-        } else if (!vec) {
-            ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_add_rmsnorm(res, delta, delta_splits, u16(w.g_attn), d.rms_eps, B, H, x, h1, h1b, plane_h, s));
         }
         ST_TRY(prof_tag(c, PSV_OP_QKV));
         if (vec) {
             HIP_TRY(launch_gemv_norm(Wqkv, Mat{}, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H, s));
-        } else if (sk) {
+        } else {
             if (!gemm_sk_supported(B, QR, H)) return PSV_ERR_UNSUPPORTED;
             HIP_TRY(launch_gemm_sk(Wqkv, Mat{}, 0, h1b, ssq, d.rms_eps, part, B, QR, H, s));
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H, w8), B, QR, false, qkv, nullptr, false, s));
-        } else {
-            ST_TRY(projection_mfma(c, w.w_qkv, nullptr, h1b, qkv, nullptr, B, QR, H));
         }
 
         ST_TRY(prof_tag(c, PSV_OP_ATTN));
@@ -417,13 +401,11 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_gemv_merge(Wo, pml, po, nq, nkv, sp.n_chunks, attn, delta_a, B, H, s));
         } else if (vec) {
             HIP_TRY(launch_gemv(Wo, Mat{}, attn, delta_a, B, H, QD, s));
-        } else if (sk) {
+        } else {
             if (!gemm_sk_supported(B, H, QD)) return PSV_ERR_UNSUPPORTED;
             HIP_TRY(launch_gemm_sk(Wo, Mat{}, 0, attnb, nullptr, 0.f, part, B, H, QD, s));
             attn_delta = part;
             attn_splits = gemm_sk_splits(B, H, QD, w8);
-        } else {
-            ST_TRY(projection_mfma(c, w.w_o, nullptr, attnb, delta_a, nullptr, B, H, QD));
         }
 
         ST_TRY(comm_window(c, l, 0, batch, le, &side_used));
@@ -431,20 +413,15 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         if (sk) {
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_resid_sum(x, attn_delta, attn_splits, B, H, y, u16(w.g_mlp), h2b, plane_h, w8, ssq, s));
-        } else if (!vec) {
-            ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_add_rmsnorm(x, attn_delta, attn_splits, u16(w.g_mlp), d.rms_eps, B, H, y, h2, h2b, plane_h, s));
         }
         ST_TRY(prof_tag(c, PSV_OP_GATE));
         if (vec) {
             HIP_TRY(launch_gemv_norm(Wg, Wu, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H, s));
-        } else if (sk) {
+        } else {
             if (!gemm_sk_supported(B, 2 * F, H)) return PSV_ERR_UNSUPPORTED;
             HIP_TRY(launch_gemm_sk(Wg, Wu, F, h2b, ssq, d.rms_eps, part, B, 2 * F, H, s));
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H, w8), B, 2 * F, true, m, mb, w8, s));
-        } else {
-            ST_TRY(projection_mfma(c, w.w_gate, w.w_up, h2b, m, mb, B, F, H));
         }
 
         ST_TRY(prof_tag(c, PSV_OP_DOWN));
@@ -452,13 +429,11 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         delta_splits = 1;
         if (vec) {
             HIP_TRY(launch_gemv(Wd, Mat{}, m, delta_m, B, H, F, s));
-        } else if (sk) {
+        } else {
             if (!gemm_sk_supported(B, H, F)) return PSV_ERR_UNSUPPORTED;
             HIP_TRY(launch_gemm_sk(Wd, Mat{}, 0, mb, nullptr, 0.f, part, B, H, F, s));
             delta = part;
             delta_splits = gemm_sk_splits(B, H, F, w8);
-        } else {
-            ST_TRY(projection_mfma(c, w.w_down, nullptr, mb, delta_m, nullptr, B, H, F));
         }
 
         ST_TRY(comm_window(c, l, 1, batch, le, &side_used));
@@ -508,7 +483,6 @@ psv_status psv_create(const psv_model_desc *desc, void *stream_main, void *strea
     int khz = 0;
     if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device) == hipSuccess && khz > 0) c->clock_khz = (uint64_t)khz;
     c->ws = layout_workspace(c->d);
-    c->old_mfma = getenv("PSV_MFMA_OLD") != nullptr;
     if (hipMalloc(reinterpret_cast<void **>(&c->wsp), c->ws.total) != hipSuccess) {
         c->wsp = nullptr;
         return fail(PSV_ERR_NOMEM);

@@ -53,14 +53,6 @@ struct Mat {
 // The next kernel launched from this thread records `start` / `stop` around its own execution.
 void set_launch_events(hipEvent_t start, hipEvent_t stop);
 
-// out_res = res + delta (delta may be null, or `delta_splits` > 1 split-K partials [split][batch][H] that
-// are summed in split order); if gain != null: h = out_res * rsqrt(mean(out_res^2) + eps) * gain, written
-// as fp32 (h_f32) and as hi/lo bf16 planes (h_bf16, row stride H, lo plane plane_stride elements after the
-// hi plane).  One workgroup per row.
-hipError_t launch_add_rmsnorm(const float *res, const float *delta, int delta_splits, const uint16_t *gain,
-                              float eps, int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
-                              size_t plane_stride, hipStream_t s);
-
 // Vector-ALU GEMV for batch <= 2:  out[b][r] = sum_k W[r][k] * x[b][k]   (fp32 x; W bf16 or int8 + row scale).
 // W2.w != null selects the SwiGLU form: out[b][r] = silu(W[r].x[b]) * (W2[r].x[b]); same format as W.
 hipError_t launch_gemv(Mat W, Mat W2, const float *x, float *out, int batch, int N, int K, hipStream_t s);
@@ -77,15 +69,9 @@ bool gemv_merge_supported(int batch, int nq, int n_chunks);
 hipError_t launch_gemv_merge(Mat W, const float *part_ml, const float *part_o, int nq, int nkv,
                              int n_chunks, float *out_attn, float *out, int batch, int N, hipStream_t s);
 
-// MFMA skinny GEMM for any batch: same contract, x given as two bf16 planes (x = hi + lo), each
-// [round_up(batch,16)][K], lo directly after hi; out_bf16 (optional) is written in the same form.
-hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_t *x_bf16, float *out,
-                            uint16_t *out_bf16, int batch, int N, int K, hipStream_t s);
-bool gemm_mfma_supported(int batch, int N, int K);
-
 // Split-K skinny GEMM on the matrix cores with the activation slab shared through LDS:
 // part[split][b][r] = partial sums of W[r].x[b] (rows >= split_row come from W2), to be summed in split
-// order by launch_sk_reduce or launch_add_rmsnorm.  x_bf16 as for launch_gemm_mfma.
+// order by launch_sk_reduce or launch_resid_sum.  x_bf16: see the operand formats above.
 constexpr int kSkMaxSplits = 16;
 int gemm_sk_splits(int batch, int N, int K, bool w8);
 bool gemm_sk_supported(int batch, int N, int K);

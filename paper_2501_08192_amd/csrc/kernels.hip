@@ -199,86 +199,6 @@ __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f +
 
 // ------------------------------------------------------------------------------------ norm
 
-// out_res = res + delta; h = out_res * rsqrt(mean(out_res^2) + eps) * gain, stored as fp32 and as
-// the hi/lo bf16 planes the matrix-core GEMM reads.  delta may be given as `delta_splits` split-K partials
-// [split][batch][H], which are summed in split order first.  One workgroup of 1024 threads per batch
-// row; the row stays in registers between the two phases.
-__global__ __launch_bounds__(1024) void k_add_rmsnorm(const float *__restrict__ res,
-                                                      const float *__restrict__ delta, int delta_splits,
-                                                      size_t delta_stride,
-                                                      const uint16_t *__restrict__ gain, float eps, int H,
-                                                      float *out_res, float *__restrict__ h_f32,
-                                                      uint16_t *__restrict__ h_bf16, size_t plane_stride)
-{
-    constexpr int MAXV = 4;   // float4 per thread: H <= 16384
-    __shared__ float red[16];
-    const int b = blockIdx.x, tid = threadIdx.x;
-    const float *r = res + (size_t)b * H;
-    const float *d = delta ? delta + (size_t)b * H : nullptr;
-    float *o = out_res + (size_t)b * H;
-    float4 v[MAXV];
-    uint2 gv[MAXV];
-    float ss = 0.f;
-#pragma unroll
-    for (int q = 0; q < MAXV; ++q) {
-        const int i = (q * 1024 + tid) * 4;
-        v[q] = make_float4(0.f, 0.f, 0.f, 0.f);
-        gv[q] = make_uint2(0u, 0u);
-        if (i < H) {
-            v[q] = *reinterpret_cast<const float4 *>(r + i);
-            if (gain) gv[q] = *reinterpret_cast<const uint2 *>(gain + i);
-            if (d) {
-                // split-K partials of the projection: all loads first (their latencies overlap), then the
-                // sum in split order
-                float4 t[kSkMaxSplits];
-#pragma unroll
-                for (int ks = 0; ks < kSkMaxSplits; ++ks)
-                    t[ks] = ks < delta_splits ? *reinterpret_cast<const float4 *>(d + ks * delta_stride + i)
-                                              : make_float4(0.f, 0.f, 0.f, 0.f);
-                float4 e = t[0];
-#pragma unroll
-                for (int ks = 1; ks < kSkMaxSplits; ++ks) { e.x += t[ks].x; e.y += t[ks].y; e.z += t[ks].z; e.w += t[ks].w; }
-                v[q].x += e.x; v[q].y += e.y; v[q].z += e.z; v[q].w += e.w;
-            }
-            *reinterpret_cast<float4 *>(o + i) = v[q];
-            ss += v[q].x * v[q].x + v[q].y * v[q].y + v[q].z * v[q].z + v[q].w * v[q].w;
-        }
-    }
-    if (!gain) return;
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) red[tid >> 6] = ss;
-    __syncthreads();
-    ss = 0.f;
-#pragma unroll
-    for (int k = 0; k < 16; ++k) ss += red[k];
-    const float inv = 1.0f / sqrtf(ss / (float)H + eps);
-#pragma unroll
-    for (int q = 0; q < MAXV; ++q) {
-        const int i = (q * 1024 + tid) * 4;
-        if (i < H) {
-            float4 t = v[q];
-            t.x = t.x * inv * bf16_lo(gv[q].x);
-            t.y = t.y * inv * bf16_hi(gv[q].x);
-            t.z = t.z * inv * bf16_lo(gv[q].y);
-            t.w = t.w * inv * bf16_hi(gv[q].y);
-            *reinterpret_cast<float4 *>(h_f32 + (size_t)b * H + i) = t;
-            uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
-            split_bf16(t.x, h0, l0); split_bf16(t.y, h1, l1); split_bf16(t.z, h2, l2); split_bf16(t.w, h3, l3);
-            *reinterpret_cast<uint2 *>(h_bf16 + (size_t)b * H + i) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-            *reinterpret_cast<uint2 *>(h_bf16 + plane_stride + (size_t)b * H + i) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
-        }
-    }
-}
-
-hipError_t launch_add_rmsnorm(const float *res, const float *delta, int delta_splits, const uint16_t *gain,
-                              float eps, int batch, int H, float *out_res, float *h_f32, uint16_t *h_bf16,
-                              size_t plane_stride, hipStream_t s)
-{
-    PSV_LAUNCH(k_add_rmsnorm, dim3(batch), dim3(1024), 0, s, res, delta, delta_splits, (size_t)batch * H, gain, eps, H,
-               out_res, h_f32, h_bf16, plane_stride);
-    return hipGetLastError();
-}
-
 // Residual add for the matrix-core path, spread over many workgroups: grid (H / 512, batch), one float4 per
 // thread.  out_res = res + delta, where delta may be `delta_splits` split-K partials [split][batch][H] that are
 // summed in split order.  With a gain, the kernel also prepares the next projection's operand without ever seeing
@@ -741,135 +661,6 @@ hipError_t launch_gemv_merge(Mat W, const float *part_ml, const float *part_o, i
     return gemv_dispatch<GEMV_MERGE>(a, batch, s);
 }
 
-// ------------------------------------------------------------------------------------ MFMA skinny GEMM
-
-// out[b][r] = sum_k W[r][k] x[b][k] with v_mfma_f32_16x16x32_bf16: the 16 rows of a weight tile
-// are the M side, 16 batch entries the N side.  The waves of a workgroup split K between them in
-// interleaved 64-element slices; every lane loads 32 contiguous bytes per row and slice (so a wave
-// touches whole 128-byte lines of 16 rows) and feeds them to two MFMAs.  Because A and B fragments
-// use the same (lane group, element) -> k mapping, the order of k inside a slice does not matter.
-// Partial tiles are summed through LDS in wave order (deterministic).
-template <int NB, int NWAVES, bool SWIGLU>
-__global__ __launch_bounds__(NWAVES * 64) void k_gemm_mfma(const uint16_t *__restrict__ W,
-                                                            const uint16_t *__restrict__ W2,
-                                                            const uint16_t *__restrict__ xb,
-                                                            float *__restrict__ out,
-                                                            uint16_t *__restrict__ out_bf16, int batch, int N, int K,
-                                                            size_t x_plane, size_t out_plane)
-{
-    constexpr int NW = SWIGLU ? 2 : 1;
-    __shared__ f32x4 red[NWAVES][NW][NB][64];
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int i = lane & 15, g = lane >> 4;
-    const int row0 = blockIdx.x * 16;
-
-    f32x4 acc[NW][NB];
-#pragma unroll
-    for (int a = 0; a < NW; ++a)
-#pragma unroll
-        for (int n = 0; n < NB; ++n) acc[a][n] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    const uint16_t *wrow = W + (size_t)(row0 + i) * K + g * 16;
-    const uint16_t *w2row = SWIGLU ? W2 + (size_t)(row0 + i) * K + g * 16 : nullptr;
-    const uint16_t *xrow = xb + (size_t)i * K + g * 16;
-
-    for (int kb = w * 64; kb < K; kb += NWAVES * 64) {
-        uint4 a0[NW], a1[NW], b0[NB], b1[NB], c0[NB], c1[NB];
-        a0[0] = ld16(wrow + kb);
-        a1[0] = ld16(wrow + kb + 8);
-        if (SWIGLU) {
-            a0[NW - 1] = ld16(w2row + kb);
-            a1[NW - 1] = ld16(w2row + kb + 8);
-        }
-#pragma unroll
-        for (int n = 0; n < NB; ++n) {
-            b0[n] = ld16(xrow + (size_t)n * 16 * K + kb);
-            b1[n] = ld16(xrow + (size_t)n * 16 * K + kb + 8);
-            c0[n] = ld16(xrow + x_plane + (size_t)n * 16 * K + kb);       // lo plane
-            c1[n] = ld16(xrow + x_plane + (size_t)n * 16 * K + kb + 8);
-        }
-#pragma unroll
-        for (int a = 0; a < NW; ++a)
-#pragma unroll
-            for (int n = 0; n < NB; ++n) {
-                acc[a][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0[a]),
-                                                                    __builtin_bit_cast(bf16x8, b0[n]), acc[a][n], 0, 0, 0);
-                acc[a][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1[a]),
-                                                                    __builtin_bit_cast(bf16x8, b1[n]), acc[a][n], 0, 0, 0);
-                acc[a][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a0[a]),
-                                                                    __builtin_bit_cast(bf16x8, c0[n]), acc[a][n], 0, 0, 0);
-                acc[a][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a1[a]),
-                                                                    __builtin_bit_cast(bf16x8, c1[n]), acc[a][n], 0, 0, 0);
-            }
-    }
-#pragma unroll
-    for (int a = 0; a < NW; ++a)
-#pragma unroll
-        for (int n = 0; n < NB; ++n) red[w][a][n][lane] = acc[a][n];
-    __syncthreads();
-
-    // D fragment: lane holds rows 4g..4g+3 of column i  ->  out[batch n*16+i][row0 + 4g + j]
-    for (int n = w; n < NB; n += NWAVES) {
-        f32x4 v = red[0][0][n][lane];
-#pragma unroll
-        for (int ww = 1; ww < NWAVES; ++ww) v += red[ww][0][n][lane];
-        if (SWIGLU) {
-            f32x4 u = red[0][NW - 1][n][lane];
-#pragma unroll
-            for (int ww = 1; ww < NWAVES; ++ww) u += red[ww][NW - 1][n][lane];
-#pragma unroll
-            for (int j = 0; j < 4; ++j) v[j] = silu_mul(v[j], u[j]);
-        }
-        const int b = n * 16 + i;
-        if (b < batch) {
-            const size_t o = (size_t)b * N + row0 + 4 * g;
-            *reinterpret_cast<float4 *>(out + o) = make_float4(v[0], v[1], v[2], v[3]);
-            if (out_bf16) {
-                uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
-                split_bf16(v[0], h0, l0); split_bf16(v[1], h1, l1); split_bf16(v[2], h2, l2); split_bf16(v[3], h3, l3);
-                *reinterpret_cast<uint2 *>(out_bf16 + o) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-                *reinterpret_cast<uint2 *>(out_bf16 + out_plane + o) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
-            }
-        }
-    }
-}
-
-bool gemm_mfma_supported(int batch, int N, int K)
-{
-    return batch >= 1 && batch <= 64 && N % 16 == 0 && K % 64 == 0;
-}
-
-template <int NB, int NWAVES>
-static hipError_t gemm_go(const uint16_t *W, const uint16_t *W2, const uint16_t *xb, float *out,
-                          uint16_t *out_bf16, int batch, int N, int K, hipStream_t s)
-{
-    const size_t x_plane = (size_t)NB * 16 * K, out_plane = (size_t)NB * 16 * N;
-    if (W2)
-        PSV_LAUNCH((k_gemm_mfma<NB, NWAVES, true>), dim3(N / 16), dim3(NWAVES * 64), 0, s, W, W2, xb, out,
-                           out_bf16, batch, N, K, x_plane, out_plane);
-    else
-        PSV_LAUNCH((k_gemm_mfma<NB, NWAVES, false>), dim3(N / 16), dim3(NWAVES * 64), 0, s, W, W2, xb, out,
-                           out_bf16, batch, N, K, x_plane, out_plane);
-    return hipGetLastError();
-}
-
-// x_bf16 / out_bf16: hi plane [round_up(batch,16)][K or N] followed by the lo plane of the same shape.
-hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_t *xb, float *out,
-                            uint16_t *out_bf16, int batch, int N, int K, hipStream_t s)
-{
-    const int nb = (batch + 15) / 16;
-    // Few row tiles (a narrow projection): 8 waves per workgroup split K further so that the
-    // launch still puts >= 2 waves on every SIMD of the chip.
-    const bool wide = (N / 16) < 1024;
-    switch (nb) {
-    case 1: return wide ? gemm_go<1, 8>(W, W2, xb, out, out_bf16, batch, N, K, s) : gemm_go<1, 4>(W, W2, xb, out, out_bf16, batch, N, K, s);
-    case 2: return wide ? gemm_go<2, 8>(W, W2, xb, out, out_bf16, batch, N, K, s) : gemm_go<2, 4>(W, W2, xb, out, out_bf16, batch, N, K, s);
-    case 3: return wide ? gemm_go<3, 8>(W, W2, xb, out, out_bf16, batch, N, K, s) : gemm_go<3, 4>(W, W2, xb, out, out_bf16, batch, N, K, s);
-    case 4: return wide ? gemm_go<4, 8>(W, W2, xb, out, out_bf16, batch, N, K, s) : gemm_go<4, 4>(W, W2, xb, out, out_bf16, batch, N, K, s);
-    default: return hipErrorInvalidValue;
-    }
-}
-
 // ------------------------------------------------------------------------------------ split-K skinny GEMM
 
 // part[ks][b][r] = sum over the K-range of split ks of W[r][k] x[b][k], for batches of 17..64 (and any
@@ -881,7 +672,7 @@ hipError_t launch_gemm_mfma(const uint16_t *W, const uint16_t *W2, const uint16_
 // the activation slab two slabs ahead, which keeps 16 KiB per wave in flight even when only a few
 // workgroups exist (small matrices at batch 64 cannot use many: every extra K split costs a partial
 // result of batch x rows floats).  Splits are summed later in split order by the consumer (k_sk_reduce or
-// k_add_rmsnorm): deterministic, no atomics.
+// k_resid_sum): deterministic, no atomics.
 struct GemmSkArgs {
     const uint16_t *W, *W2;   // rows >= split_row are taken from W2 (row - split_row): gate | up in one launch
     int split_row;
