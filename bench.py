@@ -38,6 +38,9 @@ def parse():
     ap.add_argument("--targets", type=int, default=3)
     ap.add_argument("--graph", type=int, default=0, help="1 = replay the step as a HIP graph")
     ap.add_argument("--window-us", type=float, nargs=2, default=None)
+    ap.add_argument("--tune", type=int, default=0,
+                    help="1 = let the library time its candidate attention splits on layer 0 first (psv_tune_attention); "
+                         "the default split is within ~1 %% of the tuned one on the five workloads")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = auto)")
     ap.add_argument("--seed", type=int, default=2501)
@@ -145,6 +148,8 @@ def main():
                              chunk_bytes=int(a.chunk_mb * MB), cu_budget=a.cu_budget, partial=a.partial, join=a.join)
     off = psv.prefetch_policy(mode=0)
 
+    attn_chunk = sess.tune_attention() if a.tune else 0
+
     # prefetch off (vanilla execution) and on, same launch configuration otherwise
     psv.psv_set_graph_mode(sess.ctx, bool(a.graph))
     sess.set_policy(off)
@@ -213,7 +218,8 @@ def main():
                                "windows %g/%g us" % (w.name, L, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch,
                                                       w.context, "paged" if w.paged else "contiguous", *w.window_us),
                    "prefetch_budget_mb": a.budget_mb, "cu_budget": a.cu_budget, "chunk_mb": a.chunk_mb,
-                   "partial": a.partial, "join": a.join, "targets": a.targets, "hip_graph": bool(a.graph)},
+                   "partial": a.partial, "join": a.join, "targets": a.targets, "hip_graph": bool(a.graph),
+                   "attn_tokens_per_workgroup": attn_chunk if a.tune else "default"},
         "us_per_layer_prefetch_off": round(us_off, 3),
         "prefetch_speedup": round(us_off / us_on, 4),
         "on_off_bit_identical": identical,

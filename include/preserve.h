@@ -221,6 +221,19 @@ psv_status psv_sync(psv_ctx *ctx);
 
 psv_status psv_get_stats(psv_ctx *ctx, psv_stats *out);
 
+/* Chooses how many tokens of a sequence one attention workgroup covers (the split of the span over
+ * workgroups).  The default comes from a heuristic on (max_batch, kv heads, max_seq); which split is fastest
+ * depends on the shape in ways a heuristic captures only roughly (measured spread over the candidates: 10 %;
+ * the default lands within 1-2 % of the best on the shapes it was centred on), so this call times
+ * psv_decode_step(ctx, x_in, x_out, batch, 0, 1) -- layer 0 only, prefetching off, no windows -- for a list of
+ * candidate splits and keeps the fastest for all later steps of this context.  It has the side effects of that
+ * decode step (x_out, slot seq_lens[b]-1 of layer 0's cache) and needs weights of layer 0 and the KV-cache set.
+ * The split changes the summation order of the attention partials, i.e. results before and after tuning agree
+ * to rounding, not bit for bit; within one split they stay bit-identical for every policy.  *chunk_tokens
+ * (optional) receives the choice.  Synchronises both streams. */
+psv_status psv_tune_attention(psv_ctx *ctx, const float *x_in, float *x_out, uint32_t batch,
+                              uint32_t *chunk_tokens);
+
 /* Checks that work on stream_side really runs beside work on stream_main.  HIP multiplexes streams
  * onto a few hardware queues; two streams that land on the same queue execute one after the other,
  * and a prefetch can then never overlap its window.  The check runs a 1 ms window kernel on

@@ -22,7 +22,8 @@ PSV_DBG_H1, PSV_DBG_QKV, PSV_DBG_ATTN, PSV_DBG_Y, PSV_DBG_H2, PSV_DBG_M = range(
 EXPORTS = [
     "psv_strerror", "psv_validate_desc", "psv_workspace_bytes", "psv_plan_chain", "psv_create", "psv_destroy",
     "psv_set_layer_weights", "psv_set_kv", "psv_set_comm_windows", "psv_set_policy", "psv_plan",
-    "psv_set_graph_mode", "psv_decode_step", "psv_sync", "psv_get_stats", "psv_check_overlap", "psv_set_profile_op",
+    "psv_set_graph_mode", "psv_decode_step", "psv_sync", "psv_get_stats", "psv_tune_attention", "psv_check_overlap",
+    "psv_set_profile_op",
     "psv_get_profile", "psv_prefetch_region", "psv_spin", "psv_copy_bytes", "psv_debug_read",
 ]
 
@@ -98,6 +99,7 @@ def lib():
             "psv_decode_step": (C.c_int32, [vp, vp, vp, u32, u32, u32]),
             "psv_sync": (C.c_int32, [vp]),
             "psv_get_stats": (C.c_int32, [vp, C.POINTER(psv_stats)]),
+            "psv_tune_attention": (C.c_int32, [vp, vp, vp, u32, C.POINTER(u32)]),
             "psv_check_overlap": (C.c_int32, [vp, C.POINTER(C.c_int32)]),
             "psv_set_profile_op": (C.c_int32, [vp, C.c_int32]),
             "psv_get_profile": (C.c_int32, [vp, C.POINTER(C.c_double), C.POINTER(u64)]),
@@ -226,6 +228,12 @@ def psv_get_stats(ctx):
     s = psv_stats()
     _check(lib().psv_get_stats(ctx, C.byref(s)), "psv_get_stats")
     return {n: getattr(s, n) for n, _ in psv_stats._fields_ if n != "reserved"}
+
+
+def psv_tune_attention(ctx, x_in, x_out, batch):
+    out = C.c_uint32(0)
+    _check(lib().psv_tune_attention(ctx, _dev_ptr(x_in), _dev_ptr(x_out), batch, C.byref(out)), "psv_tune_attention")
+    return int(out.value)
 
 
 def psv_check_overlap(ctx):

@@ -36,7 +36,14 @@ Workspace layout_workspace(const psv_model_desc &d)
     const size_t B = d.max_batch, Bp = (B + 15) / 16 * 16, H = d.hidden, F = d.ffn;
     const size_t QR = (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim, QD = (size_t)d.n_q_heads * d.head_dim;
     const size_t G = d.n_q_heads / d.n_kv_heads;
-    const AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq, d.kv_format == PSV_FMT_INT8);
+    // room for the finest attention split psv_tune_attention may choose, not only the default one
+    const size_t tile_unit = (size_t)(d.kv_format == PSV_FMT_INT8 ? kAttnTileTokensInt8 : kAttnTileTokens) * kAttnWaves;
+    AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq, d.kv_format == PSV_FMT_INT8);
+    {
+        size_t finest = (d.max_seq + tile_unit - 1) / tile_unit;
+        if (finest > (size_t)kAttnMaxChunks) finest = kAttnMaxChunks;
+        if ((size_t)sp.n_chunks < finest) sp.n_chunks = (int)finest;
+    }
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
     w.x = take(B * H * 4);
@@ -111,6 +118,7 @@ struct psv_ctx {
     uint32_t last_prefetch_launches = 0;
     unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
     bool capturing = false;
+    uint32_t attn_chunk_tokens = 0;               // 0 = default split; else tokens per attention workgroup (psv_tune_attention)
     bool last_step_vec = false;                  // the last step formed h1 / h2 (vector path)
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(wsp + off); }
@@ -155,6 +163,18 @@ KvView kv_view(const psv_ctx *c, uint32_t layer)
     v.num_pool_blocks = (int)c->kv.num_pool_blocks;
     v.seq_lens = c->kv.seq_lens;
     return v;
+}
+
+// Attention split of this context: the default heuristic, or the chunk size chosen by psv_tune_attention.
+AttnSplit ctx_split(const psv_ctx *c)
+{
+    const psv_model_desc &d = c->d;
+    AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq, d.kv_format == PSV_FMT_INT8);
+    if (c->attn_chunk_tokens) {
+        sp.chunk_tokens = (int)c->attn_chunk_tokens;
+        sp.n_chunks = (int)((d.max_seq + c->attn_chunk_tokens - 1) / c->attn_chunk_tokens);
+    }
+    return sp;
 }
 
 uint64_t us_to_ticks(uint64_t clock_khz, float us) { return (uint64_t)llround((double)us * (double)clock_khz / 1000.0); }
@@ -334,7 +354,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     const psv_model_desc &d = c->d;
     const int B = (int)batch, H = (int)d.hidden, F = (int)d.ffn, nq = (int)d.n_q_heads, nkv = (int)d.n_kv_heads;
     const int QR = (nq + 2 * nkv) * 128, QD = nq * 128;
-    const AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq, d.kv_format == PSV_FMT_INT8);
+    const AttnSplit sp = ctx_split(c);
     float *x = c->at<float>(c->ws.x), *y = c->at<float>(c->ws.y);
     float *delta_a = c->at<float>(c->ws.delta_a), *delta_m = c->at<float>(c->ws.delta_m);
     float *h1 = c->at<float>(c->ws.h1_f32), *h2 = c->at<float>(c->ws.h2_f32);
@@ -684,6 +704,58 @@ psv_status psv_check_overlap(psv_ctx *c, int32_t *concurrent)
     const double waited_us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
     *concurrent = waited_us < 0.5 * us ? 1 : 0;
     return psv_sync(c);
+}
+
+psv_status psv_tune_attention(psv_ctx *c, const float *x_in, float *x_out, uint32_t batch, uint32_t *chunk_tokens)
+{
+    if (!c || !x_in || !x_out || batch == 0 || batch > c->d.max_batch) return PSV_ERR_INVALID_ARG;
+    if (!c->kv_set || !c->weights_set[0]) return PSV_ERR_BAD_STATE;
+    psv_status st = psv_sync(c);
+    if (st != PSV_OK) return st;
+    const psv_model_desc &d = c->d;
+    const uint32_t unit = (d.kv_format == PSV_FMT_INT8 ? kAttnTileTokensInt8 : kAttnTileTokens) * kAttnWaves;
+    // measured with prefetching off, eager launches and no windows; everything is restored afterwards
+    const psv_prefetch_policy saved_policy = c->policy;
+    const float saved_win[2] = {c->window_us[0], c->window_us[1]};
+    const bool saved_graph = c->use_graph;
+    c->policy.mode = 0;
+    c->window_us[0] = c->window_us[1] = 0.f;
+    c->use_graph = false;
+    drop_graph(c);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) st = PSV_ERR_HIP;
+    uint32_t best = 0;
+    float best_ms = 0.f;
+    const AttnSplit def = attn_split(d.max_batch, d.n_kv_heads, d.max_seq, d.kv_format == PSV_FMT_INT8);
+    static const uint32_t mult[] = {1, 2, 3, 4, 5, 6, 7, 8, 10, 11, 12, 14, 16, 20, 24, 28, 32, 40, 48, 64};
+    for (int k = -1; k < (int)(sizeof mult / sizeof mult[0]) && st == PSV_OK; ++k) {
+        const uint32_t chunk = k < 0 ? (uint32_t)def.chunk_tokens : mult[k] * unit;
+        const uint64_t n_chunks = ((uint64_t)d.max_seq + chunk - 1) / chunk;
+        if (n_chunks > (uint64_t)kAttnMaxChunks || (k >= 0 && chunk == (uint32_t)def.chunk_tokens)) continue;
+        const uint64_t wgs = n_chunks * d.n_kv_heads * batch;
+        if (k >= 0 && (wgs > 8192 || (wgs < 128 && chunk > unit))) continue;   // far from filling the chip, or a long tail of rounds
+        c->attn_chunk_tokens = chunk;
+        float ms = 0.f;
+        for (int rep = 0; rep < 2 + 8 && st == PSV_OK; ++rep) {
+            if (rep == 2 && hipEventRecord(e0, c->main) != hipSuccess) st = PSV_ERR_HIP;
+            if (st == PSV_OK) st = enqueue_step(c, x_in, x_out, batch, 0, 1);
+        }
+        if (st == PSV_OK && (hipEventRecord(e1, c->main) != hipSuccess || hipEventSynchronize(e1) != hipSuccess ||
+                             hipEventElapsedTime(&ms, e0, e1) != hipSuccess))
+            st = PSV_ERR_HIP;
+        if (st == PSV_OK && (best == 0 || ms < best_ms)) { best = chunk; best_ms = ms; }
+    }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    c->policy = saved_policy;
+    c->window_us[0] = saved_win[0];
+    c->window_us[1] = saved_win[1];
+    c->use_graph = saved_graph;
+    c->attn_chunk_tokens = (st == PSV_OK && best != (uint32_t)def.chunk_tokens) ? best : 0;
+    touch(c);
+    if (st == PSV_OK && chunk_tokens) *chunk_tokens = best;
+    const psv_status st2 = psv_sync(c);
+    return st != PSV_OK ? st : st2;
 }
 
 psv_status psv_set_profile_op(psv_ctx *c, int32_t op)

@@ -18,7 +18,7 @@ constexpr int kAttnTileTokens = 32;       // tokens per wave and loop step, bf16
 constexpr int kAttnTileTokensInt8 = 64;   // int8 cache
 constexpr int kAttnWaves = 4;
 constexpr int kAttnMaxChunks = 256;
-constexpr int kAttnResident = 768;    // workgroups of the attention kernel resident on the chip at a time (3 per CU)
+constexpr int kAttnResident = 448;      // workgroups the default split aims at: one round that leaves every CU a little slack
 
 struct AttnSplit {
     int chunk_tokens;   // tokens per workgroup

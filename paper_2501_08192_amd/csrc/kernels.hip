@@ -1163,9 +1163,11 @@ hipError_t launch_rope_table(const int32_t *seq_lens, const double *inv_freq, in
 
 AttnSplit attn_split(uint32_t batch, uint32_t n_kv_heads, uint32_t max_seq, bool kv_int8)
 {
-    // The attention kernel keeps 3 workgroups resident per CU (register bound): aim at no more than 768
-    // workgroups, i.e. one resident round without a tail, with whole 4-tile (128-token) steps per chunk
-    // and at most kAttnMaxChunks chunks per (sequence, kv head).
+    // Two workgroups of the attention kernel fit on a CU (register bound), 512 on the chip.  Measured on the
+    // large shapes, one round of somewhat fewer workgroups (400-450) is fastest: a second, partial round costs a
+    // whole chunk time, and a completely full chip is slower than a nearly full one.  So: at most kAttnResident
+    // workgroups, chunks of whole steps (4 waves x one tile) and at most kAttnMaxChunks chunks per
+    // (sequence, kv head).  psv_tune_attention replaces this guess by a measurement.
     const int unit = (kv_int8 ? kAttnTileTokensInt8 : kAttnTileTokens) * kAttnWaves;
     const uint64_t seqs = (uint64_t)batch * n_kv_heads;
     uint64_t max_chunks = kAttnResident / (seqs ? seqs : 1);

@@ -66,6 +66,11 @@ class Session:
     def set_windows(self, us0, us1):
         psv.psv_set_comm_windows(self.ctx, float(us0), float(us1))
 
+    def tune_attention(self):
+        """Times the candidate attention splits on layer 0 and keeps the fastest; returns tokens per workgroup."""
+        assert 0 in self.layers
+        return psv.psv_tune_attention(self.ctx, self.x_in, self.x_out, self.w.batch)
+
     def step(self, x_in=None, x_out=None, layer_begin=None, layer_end=None):
         lb = self.layers[0] if layer_begin is None else layer_begin
         le = self.layers[-1] + 1 if layer_end is None else layer_end

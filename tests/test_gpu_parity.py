@@ -238,6 +238,26 @@ def test_prefetch_policies_and_graph_mode_are_bit_identical(wl):
         assert psv.psv_get_stats(s.ctx)["steps"] > 10
 
 
+@pytest.mark.parametrize("wl", [W("tune1", 2, 1024, 8, 2, 768, 2, 3000), W("tune2", 2, 512, 4, 1, 512, 24, 700, paged=True)])
+def test_tuned_attention_split_matches_oracle_and_policies_stay_bit_identical(wl):
+    with Session(wl, seed=31) as s:
+        before = s.run().clone()
+        chunk = s.tune_attention()
+        assert chunk >= 128 and chunk % 128 == 0
+        ref, _, _ = run_oracle(s, s.layers)
+        base = s.run().clone()
+        assert_close(base.cpu().numpy(), ref, wl.name)
+        assert_close(before.cpu().numpy(), ref, wl.name + " (default split)")
+        for pol in _policies(wl)[:3]:
+            for graph in (False, True):
+                s.set_policy(pol)
+                psv.psv_set_graph_mode(s.ctx, graph)
+                for rep in range(2):
+                    assert torch.equal(s.run(), base)
+        assert s.tune_attention() % 128 == 0        # callable again; the context keeps working
+        assert_close(s.run().cpu().numpy(), ref, wl.name + " (second tuning)")
+
+
 def test_layer_ranges_chain_like_the_whole_step():
     w = W("range", 3, 512, 4, 2, 256, 2, 90)
     with Session(w, seed=22) as s:
