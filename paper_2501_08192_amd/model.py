@@ -21,11 +21,14 @@ class Machine:
     small_kernels: float = 0.0   # extra us per layer for merge / reduce / norm launches (matrix-core path)
 
 
-def op_bytes(hidden, n_q, n_kv, ffn, batch, context, head_dim=128):
-    """Algorithmic bytes of the operators of one layer (bf16)."""
-    qkv = (n_q + 2 * n_kv) * head_dim * hidden * 2
-    return {"qkv": qkv, "attn": batch * context * n_kv * head_dim * 2 * 2, "o": hidden * n_q * head_dim * 2,
-            "gate": ffn * hidden * 2, "up": ffn * hidden * 2, "down": hidden * ffn * 2}
+def op_bytes(hidden, n_q, n_kv, ffn, batch, context, head_dim=128, weight_format="bf16", kv_format="bf16"):
+    """Algorithmic bytes of the operators of one layer: bf16, or the int8 formats (1 byte per weight; per cached
+    token and kv head 128 code bytes + a 4-byte scale, for K and for V)."""
+    wb = 1 if weight_format == "int8" else 2
+    kv_token = 2 * (head_dim + 4) if kv_format == "int8" else 2 * 2 * head_dim
+    qkv = (n_q + 2 * n_kv) * head_dim * hidden * wb
+    return {"qkv": qkv, "attn": batch * context * n_kv * kv_token, "o": hidden * n_q * head_dim * wb,
+            "gate": ffn * hidden * wb, "up": ffn * hidden * wb, "down": hidden * ffn * wb}
 
 
 def plan_windows(b, budget):

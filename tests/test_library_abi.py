@@ -173,3 +173,43 @@ def test_mode_off_plans_nothing_and_partial_extension_fills_the_budget():
     assert [e["target_op"] for e in p2] == [psv.PSV_OP_QKV, psv.PSV_OP_ATTN]
     assert p2[1]["mem_size"] == sz["attn"] and p2[1]["bytes"] == Cb - 1 - sz["qkv"]
     assert sum(e["bytes"] for e in p2) < Cb
+
+
+def test_storage_formats_in_the_descriptor_and_the_planner():
+    w = synth.WORKLOADS["c2"]
+    for wf in ("bf16", "int8"):
+        for kf in ("bf16", "int8"):
+            assert psv.psv_validate_desc(_desc(w, weight_format=wf, kv_format=kf)) == psv.PSV_OK
+    d = _desc(w)
+    d.weight_format = 2
+    assert psv.psv_validate_desc(d) == psv.PSV_ERR_INVALID_ARG
+    d = _desc(w)
+    d.kv_format = 7
+    assert psv.psv_validate_desc(d) == psv.PSV_ERR_INVALID_ARG
+    # memSize() follows the formats: 1 byte per int8 weight; 128 codes + a 4-byte scale per cached row, K and V
+    pol = psv.prefetch_policy(mode=1, budget_bytes=1 << 40)
+    plan16 = psv.psv_plan_chain(_desc(w), w.batch, w.context, pol)
+    plan8 = psv.psv_plan_chain(_desc(w, weight_format="int8", kv_format="int8"), w.batch, w.context, pol)
+    assert len(plan16) == len(plan8)
+    for a, b in zip(plan16, plan8):
+        assert (a["layer"], a["window"], a["target_op"]) == (b["layer"], b["window"], b["target_op"])
+        if a["target_op"] == psv.PSV_OP_ATTN:
+            rows = w.batch * (w.context - 1) * w.n_kv_heads
+            assert a["mem_size"] == rows * 2 * 128 * 2 and b["mem_size"] == rows * 2 * (128 + 4)
+        else:
+            assert a["mem_size"] == 2 * b["mem_size"]
+    # a budget that holds gate + up in bf16 but not down holds all three in int8 (strict comparison)
+    fh = w.ffn * w.hidden
+    pol = psv.prefetch_policy(mode=1, targets=psv.PSV_TARGET_WEIGHTS, budget_bytes=4 * fh + 1)
+    ops16 = [e["target_op"] for e in psv.psv_plan_chain(_desc(w), 1, 64, pol) if e["layer"] == 0 and e["window"] == 0]
+    ops8 = [e["target_op"] for e in psv.psv_plan_chain(_desc(w, weight_format="int8"), 1, 64, pol)
+            if e["layer"] == 0 and e["window"] == 0]
+    assert ops16 == [psv.PSV_OP_GATE, psv.PSV_OP_UP] and ops8 == [psv.PSV_OP_GATE, psv.PSV_OP_UP, psv.PSV_OP_DOWN]
+
+
+def test_binding_structs_match_the_header_layout():
+    # field order and sizes restated from include/preserve.h
+    assert C.sizeof(psv.psv_model_desc) == 12 * 4
+    assert C.sizeof(psv.psv_layer_weights) == 12 * C.sizeof(C.c_void_p)
+    assert C.sizeof(psv.psv_prefetch_policy) == 40
+    assert C.sizeof(psv.psv_plan_entry) == 32

@@ -48,3 +48,13 @@ def test_best_budget_grows_with_the_window():
     b, m = _bytes(w), model.Machine()
     picks = [model.best_budget(b, (x, x), m) for x in (5.0, 20.0, 50.0)]
     assert picks[0] <= picks[1] <= picks[2] and picks[0] < picks[2]
+
+
+def test_int8_formats_halve_the_weight_bytes_and_shrink_the_cache_rows():
+    b16 = model.op_bytes(8192, 8, 1, 3584, 32, 32768)
+    b8 = model.op_bytes(8192, 8, 1, 3584, 32, 32768, weight_format="int8", kv_format="int8")
+    for op in ("qkv", "o", "gate", "up", "down"):
+        assert b16[op] == 2 * b8[op]
+    assert b8["attn"] * 512 == b16["attn"] * 264          # (128 + 4) * 2 bytes per row against 128 * 2 * 2
+    m = model.Machine()
+    assert model.layer_time(b8, (20.0, 20.0), m) < model.layer_time(b16, (20.0, 20.0), m)
