@@ -35,6 +35,9 @@ def parse():
     ap.add_argument("--cu-budget", type=int, default=256)
     ap.add_argument("--partial", type=int, default=-1, help="-1 = on for paged workloads (KV per layer exceeds any budget)")
     ap.add_argument("--join", type=int, default=0)
+    ap.add_argument("--prelaunch", type=int, default=1,
+                    help="1 = the first operator after a window is launched at the window's start and holds its weights in "
+                         "registers until the window ends (policy extension; batch 1-2 only)")
     ap.add_argument("--targets", type=int, default=3)
     ap.add_argument("--graph", type=int, default=0, help="1 = replay the step as a HIP graph")
     ap.add_argument("--window-us", type=float, nargs=2, default=None)
@@ -145,7 +148,8 @@ def main():
     if a.partial < 0:
         a.partial = 1 if w.paged else 0
     on = psv.prefetch_policy(mode=1, targets=a.targets, budget_bytes=int(a.budget_mb * MB),
-                             chunk_bytes=int(a.chunk_mb * MB), cu_budget=a.cu_budget, partial=a.partial, join=a.join)
+                             chunk_bytes=int(a.chunk_mb * MB), cu_budget=a.cu_budget, partial=a.partial, join=a.join,
+                             prelaunch=a.prelaunch)
     off = psv.prefetch_policy(mode=0)
 
     attn_chunk = sess.tune_attention() if a.tune else 0
@@ -218,7 +222,7 @@ def main():
                                "windows %g/%g us" % (w.name, L, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch,
                                                       w.context, "paged" if w.paged else "contiguous", *w.window_us),
                    "prefetch_budget_mb": a.budget_mb, "cu_budget": a.cu_budget, "chunk_mb": a.chunk_mb,
-                   "partial": a.partial, "join": a.join, "targets": a.targets, "hip_graph": bool(a.graph),
+                   "partial": a.partial, "join": a.join, "prelaunch": a.prelaunch, "targets": a.targets, "hip_graph": bool(a.graph),
                    "attn_tokens_per_workgroup": attn_chunk if a.tune else "default"},
         "us_per_layer_prefetch_off": round(us_off, 3),
         "prefetch_speedup": round(us_off / us_on, 4),

@@ -121,7 +121,16 @@ typedef struct {
                                 reads it */
     uint32_t join;           /* 0 = the op after a window starts when the window ends;
                                 1 = it also waits for that window's prefetch to finish */
-    uint32_t reserved;
+    uint32_t prelaunch;      /* 0 = every prefetch goes to the memory-side cache (the paper's scheme);
+                                1 = extension for this hardware, whose large on-chip memory is the register
+                                file (128 MB) rather than a shared cache: when Algorithm 1 hands the first
+                                operator after a window (gate/up, or the next layer's QKV) to that window,
+                                that operator's kernel is itself launched at the start of the window on the
+                                other stream, loads its first weights into registers while the window runs,
+                                waits for the window's end on a device flag and finishes from registers; the
+                                operator chain continues on that stream, so the two streams swap roles at
+                                every window.  Takes effect for eager launches at batch 1 (and batch 2 up
+                                to H = 4096); otherwise ignored.  Results are bit-identical either way. */
 } psv_prefetch_policy;
 
 enum { PSV_TARGET_WEIGHTS = 1u, PSV_TARGET_KV = 2u };
@@ -216,7 +225,8 @@ psv_status psv_set_graph_mode(psv_ctx *ctx, uint32_t use_graph);
 psv_status psv_decode_step(psv_ctx *ctx, const float *x_in, float *x_out, uint32_t batch,
                            uint32_t layer_begin, uint32_t layer_end);
 
-/* Waits for both streams; returns PSV_ERR_HIP if any enqueued work failed. */
+/* Waits for both streams; returns PSV_ERR_HIP if any enqueued work failed (including a pre-launched kernel
+ * whose bounded wait for its window expired). */
 psv_status psv_sync(psv_ctx *ctx);
 
 psv_status psv_get_stats(psv_ctx *ctx, psv_stats *out);
@@ -263,6 +273,11 @@ psv_status psv_spin(float us, void *stream);
 /* A plain device-to-device copy kernel of `bytes` (multiple of 16) used to calibrate hardware
  * byte counters against a known size. */
 psv_status psv_copy_bytes(void *dst, const void *src, uint64_t bytes, void *stream);
+
+/* Test aid for the prelaunch policy: while on, a kernel launched ahead of its window's end gives up its
+ * (always bounded) wait at once.  The kernel then still completes, sets an error word, and the next psv_sync
+ * returns PSV_ERR_HIP once; the context stays usable. */
+psv_status psv_debug_force_wait_timeout(psv_ctx *ctx, uint32_t on);
 
 /* Intermediate buffers of the most recent layer executed, for debugging parity failures.  PSV_DBG_H1 and
  * PSV_DBG_H2 exist only when the step ran on the vector path (batch 1, or batch 2 with H <= 4096): the

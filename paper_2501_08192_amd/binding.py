@@ -25,6 +25,7 @@ EXPORTS = [
     "psv_set_graph_mode", "psv_decode_step", "psv_sync", "psv_get_stats", "psv_tune_attention", "psv_check_overlap",
     "psv_set_profile_op",
     "psv_get_profile", "psv_prefetch_region", "psv_spin", "psv_copy_bytes", "psv_debug_read",
+    "psv_debug_force_wait_timeout",
 ]
 
 
@@ -49,7 +50,7 @@ class psv_kv_desc(C.Structure):
 class psv_prefetch_policy(C.Structure):
     _fields_ = [("mode", C.c_uint32), ("targets", C.c_uint32), ("budget_bytes", C.c_uint64),
                 ("chunk_bytes", C.c_uint64), ("cu_budget", C.c_uint32), ("partial", C.c_uint32),
-                ("join", C.c_uint32), ("reserved", C.c_uint32)]
+                ("join", C.c_uint32), ("prelaunch", C.c_uint32)]
 
 
 class psv_plan_entry(C.Structure):
@@ -107,6 +108,7 @@ def lib():
             "psv_spin": (C.c_int32, [C.c_float, vp]),
             "psv_copy_bytes": (C.c_int32, [vp, vp, u64, vp]),
             "psv_debug_read": (C.c_int32, [vp, u32, vp, sz]),
+            "psv_debug_force_wait_timeout": (C.c_int32, [vp, u32]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -146,8 +148,8 @@ def model_desc(n_layers, hidden, n_q_heads, n_kv_heads, ffn, max_batch, max_seq,
 
 
 def prefetch_policy(mode=0, targets=PSV_TARGET_WEIGHTS | PSV_TARGET_KV, budget_bytes=0, chunk_bytes=0, cu_budget=0,
-                    partial=0, join=0):
-    return psv_prefetch_policy(mode, targets, budget_bytes, chunk_bytes, cu_budget, partial, join, 0)
+                    partial=0, join=0, prelaunch=0):
+    return psv_prefetch_policy(mode, targets, budget_bytes, chunk_bytes, cu_budget, partial, join, prelaunch)
 
 
 def psv_validate_desc(desc):
@@ -268,3 +270,7 @@ def psv_debug_read(ctx, which, host_array):
     """host_array: a contiguous numpy array that receives the buffer."""
     _check(lib().psv_debug_read(ctx, which, host_array.ctypes.data_as(C.c_void_p), host_array.nbytes), "psv_debug_read")
     return host_array
+
+
+def psv_debug_force_wait_timeout(ctx, on):
+    _check(lib().psv_debug_force_wait_timeout(ctx, 1 if on else 0), "psv_debug_force_wait_timeout")

@@ -119,6 +119,8 @@ struct psv_ctx {
     unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
     bool capturing = false;
     uint32_t attn_chunk_tokens = 0;               // 0 = default split; else tokens per attention workgroup (psv_tune_attention)
+    bool prelaunch_used = false;                 // some consumer was launched ahead of its window's end: check the error word at sync
+    bool force_wait_timeout = false;             // test aid: such consumers give up waiting at once (and report it)
     bool last_step_vec = false;                  // the last step formed h1 / h2 (vector path)
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(wsp + off); }
@@ -233,6 +235,7 @@ struct JobBuilder {
     psv_ctx *c;
     uint64_t cap;        // bytes per launch (0 = unlimited)
     const unsigned *skip;   // word written by the gate kernel of this window (null under graph capture)
+    hipStream_t stream;     // where the prefetch launches go
     uint64_t used = 0;
     PrefetchJob job{};
     psv_status st = PSV_OK;
@@ -243,7 +246,7 @@ struct JobBuilder {
         if (job.n_regions || job.kv_count) {
             const uint32_t wg = c->policy.cu_budget ? c->policy.cu_budget : 64u;
             job.skip = skip;
-            if (launch_prefetch_job(job, wg, c->side) != hipSuccess) st = PSV_ERR_HIP;
+            if (launch_prefetch_job(job, wg, stream) != hipSuccess) st = PSV_ERR_HIP;
             ++c->last_prefetch_launches;
         }
         job = PrefetchJob{};
@@ -305,11 +308,40 @@ psv_status add_entry(psv_ctx *c, JobBuilder &jb, const psv_plan_entry &e, uint32
     return jb.st;
 }
 
+// The two streams of a step.  Normally `cur` is the caller's main stream for the whole step; with the
+// `prelaunch` policy the operator chain hops to the other stream at every communication window.
+struct Lanes {
+    hipStream_t cur, other;
+};
+
 // The communication window after the attention block (window 0) or the MLP block (window 1).  The
-// stand-in for the collective is enqueued first, so that the main stream never waits for the host;
-// the window's prefetch job goes to the side stream and starts when the window starts.
-psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t batch, uint32_t layer_end, bool *side_used)
+// stand-in for the collective is enqueued first, so that the stream never waits for the host; the window's
+// prefetch job goes to the other stream and starts when the window starts.
+//
+// prelaunch (policy extension, eager launches, vector path): the first consumer after the window -- gate/up
+// after window 0, the next layer's QKV after window 1 -- is the one operator whose weights are needed the moment
+// the window ends.  If Algorithm 1 planned a prefetch for it, that prefetch is done by the consumer itself: the
+// caller launches it on the other stream right behind the window's gate and its (remaining) prefetch job, with a
+// GemvWait on the window's end.  It pulls its first weights into registers while the window runs and finishes a
+// few microseconds after the window does.  The rest of the chain follows it on that stream, so the two streams
+// swap roles at every window and no host-side event is needed: every cross-stream dependency is one of the two
+// flags the window kernel publishes (start, end).  *wait_set tells the caller to launch the consumer that way.
+// Does the plan hand the whole weight matrix of the first consumer after (layer, window) to that window, so that
+// the consumer can be launched ahead of time (policy.prelaunch, eager launches, vector path)?
+bool can_prelaunch(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t layer_end, bool vec)
 {
+    if (c->capturing || !vec || c->policy.mode != 1 || !c->policy.prelaunch || !(c->window_us[window] > 0.f)) return false;
+    if (window == 1 && layer + 1 >= layer_end) return false;       // end of the graph: no consumer
+    const uint32_t first_op = window == 0 ? PSV_OP_GATE : PSV_OP_QKV;
+    for (const psv_plan_entry &e : c->plan)
+        if (e.layer == layer && e.window == window && e.target_op == first_op && e.bytes == e.mem_size) return true;
+    return false;
+}
+
+psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t batch, uint32_t layer_end, bool pre,
+                       Lanes *ln, GemvWait *wait, bool *wait_set, bool *side_used)
+{
+    *wait_set = false;
     const float us = c->window_us[window];
     if (!(us > 0.f)) return PSV_OK;
     bool any = false;
@@ -317,35 +349,50 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
         for (const psv_plan_entry &e : c->plan)
             if (e.layer == layer && e.window == window && e.target_layer < layer_end) { any = true; break; }
     // Eager launches fork on the device: the window kernel publishes a sequence number that a one-wave gate
-    // kernel, queued on the side stream ahead of the prefetch launches, waits for.  Under graph capture the
+    // kernel, queued on the other stream ahead of the prefetch launches, waits for.  Under graph capture the
     // fork is an event edge.
     unsigned *flag = c->capturing ? nullptr : c->at<unsigned>(c->ws.flag);
+    unsigned *done = flag ? flag + 32 : nullptr, *err = flag ? flag + 48 : nullptr;
     const unsigned seq = ++c->window_seq;
+    const uint32_t first_op = window == 0 ? PSV_OP_GATE : PSV_OP_QKV;
     hipEvent_t ev = c->ev_fork[layer * 2 + window];
-    if (any && !flag) HIP_TRY(hipEventRecord(ev, c->main));
+    if (any && !flag) HIP_TRY(hipEventRecord(ev, ln->cur));
     ST_TRY(prof_tag(c, -2));
-    HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), flag, seq, c->main));
+    HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), flag, done, seq, ln->cur));
     if (!any) return PSV_OK;
     unsigned *skip = flag ? flag + 16 : nullptr;
     if (flag)
-        HIP_TRY(launch_gate(flag, seq, 1u << 20, c->clock_khz * 20 /* 20 ms */, skip, c->side));
+        HIP_TRY(launch_gate(flag, seq, 1u << 20, c->clock_khz * 20 /* 20 ms */, skip, ln->other));
     else
-        HIP_TRY(hipStreamWaitEvent(c->side, ev, 0));
+        HIP_TRY(hipStreamWaitEvent(ln->other, ev, 0));
     uint64_t cap = c->policy.chunk_bytes & ~(uint64_t)15;
     if (c->policy.chunk_bytes && cap < 16) cap = 16;
-    JobBuilder jb{c, cap, skip};
+    JobBuilder jb{c, cap, skip, ln->other};
     for (const psv_plan_entry &e : c->plan) {
         if (e.layer != layer || e.window != window || e.target_layer >= layer_end) continue;
+        // what the pre-launched consumer reads itself needs no second copy in the memory-side cache
+        if (pre && (e.target_op == first_op || (window == 0 && e.target_op == PSV_OP_UP))) continue;
         psv_status st = add_entry(c, jb, e, batch);
         if (st != PSV_OK) return st;
     }
     jb.flush();
     if (jb.st != PSV_OK) return jb.st;
-    if (c->policy.join) {
-        HIP_TRY(hipEventRecord(c->ev_join[layer * 2 + window], c->side));
-        HIP_TRY(hipStreamWaitEvent(c->main, c->ev_join[layer * 2 + window], 0));
-    }
     *side_used = true;
+    if (pre) {
+        wait->done = done;
+        wait->seq = seq;
+        wait->iters = c->force_wait_timeout ? 0u : (1u << 22);
+        wait->ticks = c->force_wait_timeout ? 0ull : us_to_ticks(c->clock_khz, us) * 2 + c->clock_khz * 20 /* + 20 ms */;
+        wait->err = err;
+        *wait_set = true;
+        c->prelaunch_used = true;
+        std::swap(ln->cur, ln->other);     // the chain continues behind the consumer
+        return PSV_OK;
+    }
+    if (c->policy.join) {
+        HIP_TRY(hipEventRecord(c->ev_join[layer * 2 + window], ln->other));
+        HIP_TRY(hipStreamWaitEvent(ln->cur, c->ev_join[layer * 2 + window], 0));
+    }
     return PSV_OK;
 }
 
@@ -364,7 +411,10 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     float *pml = c->at<float>(c->ws.part_ml), *po = c->at<float>(c->ws.part_o);
     float2 *rope = c->at<float2>(c->ws.rope);
     const double *inv_freq = d.rope_theta > 0.f ? c->at<double>(c->ws.inv_freq) : nullptr;
-    hipStream_t s = c->main;
+    Lanes ln{c->main, c->side};
+    hipStream_t &s = ln.cur;          // the stream the operator chain is on (changes at a pre-launching window)
+    GemvWait wait{};
+    bool wait_qkv = false, wait_gate = false;
     bool side_used = false;
     c->last_prefetch_launches = 0;
     auto u16 = [](const void *p) { return static_cast<const uint16_t *>(p); };
@@ -382,6 +432,18 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     c->last_step_vec = vec;
     float *part = c->at<float>(c->ws.part), *ssq = c->at<float>(c->ws.ssq);
 
+    // The chain hops to the other stream at every pre-launching window and has to be back on the main stream when
+    // the step ends (the caller's own work on that stream follows it): with an odd number of such windows the last
+    // one runs without pre-launch.
+    int pre_left = 0;
+    for (uint32_t l = lb; l < le; ++l)
+        for (uint32_t wdw = 0; wdw < 2; ++wdw) pre_left += can_prelaunch(c, l, wdw, le, vec) ? 1 : 0;
+    if (pre_left & 1) --pre_left;
+    auto take_pre = [&](uint32_t l, uint32_t wdw) {
+        if (pre_left > 0 && can_prelaunch(c, l, wdw, le, vec)) { --pre_left; return true; }
+        return false;
+    };
+
     ST_TRY(prof_tag(c, -2));
     HIP_TRY(launch_rope_table(c->kv.seq_lens, inv_freq, (int)c->kv.max_blocks * 16, B, rope, s));
     const float *res = x_in, *delta = nullptr;   // residual stream entering the layer = res + delta
@@ -398,7 +460,9 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         }
         ST_TRY(prof_tag(c, PSV_OP_QKV));
         if (vec) {
-            HIP_TRY(launch_gemv_norm(Wqkv, Mat{}, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H, s));
+            HIP_TRY(launch_gemv_norm(Wqkv, Mat{}, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H,
+                                     wait_qkv ? &wait : nullptr, s));
+            wait_qkv = false;
         } else {
             if (!gemm_sk_supported(B, QR, H)) return PSV_ERR_UNSUPPORTED;
             HIP_TRY(launch_gemm_sk(Wqkv, Mat{}, 0, h1b, ssq, d.rms_eps, part, B, QR, H, s));
@@ -428,7 +492,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             attn_splits = gemm_sk_splits(B, H, QD, w8);
         }
 
-        ST_TRY(comm_window(c, l, 0, batch, le, &side_used));
+        ST_TRY(comm_window(c, l, 0, batch, le, take_pre(l, 0), &ln, &wait, &wait_gate, &side_used));
 
         if (sk) {
             ST_TRY(prof_tag(c, -2));
@@ -436,7 +500,9 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         }
         ST_TRY(prof_tag(c, PSV_OP_GATE));
         if (vec) {
-            HIP_TRY(launch_gemv_norm(Wg, Wu, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H, s));
+            HIP_TRY(launch_gemv_norm(Wg, Wu, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H,
+                                     wait_gate ? &wait : nullptr, s));
+            wait_gate = false;
         } else {
             if (!gemm_sk_supported(B, 2 * F, H)) return PSV_ERR_UNSUPPORTED;
             HIP_TRY(launch_gemm_sk(Wg, Wu, F, h2b, ssq, d.rms_eps, part, B, 2 * F, H, s));
@@ -456,11 +522,15 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             delta_splits = gemm_sk_splits(B, H, F, w8);
         }
 
-        ST_TRY(comm_window(c, l, 1, batch, le, &side_used));
+        ST_TRY(comm_window(c, l, 1, batch, le, take_pre(l, 1), &ln, &wait, &wait_qkv, &side_used));
         res = y;
     }
     ST_TRY(prof_tag(c, -2));
     HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x_out, nullptr, nullptr, 0, false, nullptr, s));
+    if (ln.cur != c->main) {           // cannot happen with the pairing above; kept as a safety net
+        HIP_TRY(hipEventRecord(c->ev_end, ln.cur));
+        HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));
+    }
     if (side_used && c->capturing) {   // a captured side branch has to rejoin the origin stream
         HIP_TRY(hipEventRecord(c->ev_end, c->side));
         HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));
@@ -596,7 +666,8 @@ psv_status psv_set_comm_windows(psv_ctx *c, float us_after_attn, float us_after_
 psv_status psv_set_policy(psv_ctx *c, const psv_prefetch_policy *p, uint32_t batch, uint32_t context)
 {
     if (!c || !p) return PSV_ERR_INVALID_ARG;
-    if (p->mode > 1 || (p->targets & ~3u) || p->partial > 1 || p->join > 1 || p->cu_budget > 65535) return PSV_ERR_INVALID_ARG;
+    if (p->mode > 1 || (p->targets & ~3u) || p->partial > 1 || p->join > 1 || p->prelaunch > 1 || p->cu_budget > 65535)
+        return PSV_ERR_INVALID_ARG;
     if (batch == 0 || batch > c->d.max_batch || context == 0 || context > c->d.max_seq) return PSV_ERR_INVALID_ARG;
     c->policy = *p;
     c->plan_batch = batch;
@@ -664,7 +735,26 @@ psv_status psv_sync(psv_ctx *c)
     hipError_t a = hipStreamSynchronize(c->main);
     hipError_t b = hipStreamSynchronize(c->side);
     hipError_t l = hipGetLastError();
-    return (a == hipSuccess && b == hipSuccess && l == hipSuccess) ? PSV_OK : PSV_ERR_HIP;
+    if (!(a == hipSuccess && b == hipSuccess && l == hipSuccess)) return PSV_ERR_HIP;
+    if (c->prelaunch_used) {   // did a consumer launched ahead of time give up waiting for its window's end?
+        unsigned *err = c->at<unsigned>(c->ws.flag) + 48;
+        unsigned v = 0;
+        if (hipMemcpy(&v, err, sizeof v, hipMemcpyDeviceToHost) != hipSuccess) return PSV_ERR_HIP;
+        c->prelaunch_used = false;
+        if (v) {
+            (void)hipMemset(err, 0, sizeof v);
+            return PSV_ERR_HIP;
+        }
+    }
+    return PSV_OK;
+}
+
+psv_status psv_debug_force_wait_timeout(psv_ctx *c, uint32_t on)
+{
+    if (!c || on > 1) return PSV_ERR_INVALID_ARG;
+    c->force_wait_timeout = on == 1;
+    touch(c);
+    return PSV_OK;
 }
 
 psv_status psv_get_stats(psv_ctx *c, psv_stats *out)
@@ -698,7 +788,7 @@ psv_status psv_check_overlap(psv_ctx *c, int32_t *concurrent)
     // how long the side stream takes to drain while a 1 ms window runs on the main stream.
     const float us = 1000.f;
     const auto t0 = std::chrono::steady_clock::now();
-    HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), flag, seq, c->main));
+    HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), flag, nullptr, seq, c->main));
     HIP_TRY(launch_gate(flag, seq, 1u << 20, c->clock_khz * 4 /* 4 ms */, flag + 16, c->side));
     HIP_TRY(hipStreamSynchronize(c->side));
     const double waited_us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
@@ -808,7 +898,7 @@ psv_status psv_spin(float us, void *stream)
 {
     if (!(us >= 0.f) || us > 1.0e6f) return PSV_ERR_INVALID_ARG;
     if (us == 0.f) return PSV_OK;
-    HIP_TRY(launch_spin(us_to_ticks(current_clock_khz(), us), spin_cap(us), nullptr, 0, static_cast<hipStream_t>(stream)));
+    HIP_TRY(launch_spin(us_to_ticks(current_clock_khz(), us), spin_cap(us), nullptr, nullptr, 0, static_cast<hipStream_t>(stream)));
     return PSV_OK;
 }
 

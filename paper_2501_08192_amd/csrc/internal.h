@@ -58,9 +58,19 @@ void set_launch_events(hipEvent_t start, hipEvent_t stop);
 hipError_t launch_gemv(Mat W, Mat W2, const float *x, float *out, int batch, int N, int K, hipStream_t s);
 // Same with the activations formed in the prologue: x = rmsnorm(res + delta) * gain.  out_res
 // receives res + delta and out_h (optional) the normalised vector; neither may alias res or delta.
+// wait != null: the kernel is launched before its inputs exist.  It requests its first weights, then waits
+// (bounded) until *done has reached seq -- published by the window kernel when the window ends -- and only
+// then reads res / delta.  A wait that hits its bounds sets *err and the kernel continues.
+struct GemvWait {
+    const unsigned *done;
+    unsigned seq;
+    uint32_t iters;
+    uint64_t ticks;
+    unsigned *err;
+};
 hipError_t launch_gemv_norm(Mat W, Mat W2, const float *res, const float *delta,
                             const uint16_t *gain, float eps, float *out_res, float *out_h, float *out, int batch,
-                            int N, int K, hipStream_t s);
+                            int N, int K, const GemvWait *wait, hipStream_t s);
 bool gemv_supported(int batch, int N, int K);
 // O projection with the attention merge in its prologue: x = merged split-K partials (K = nq*128).
 // out_attn (optional) receives the merged attention output.  Usable for few chunks only.
@@ -102,8 +112,9 @@ hipError_t launch_attn_merge(const float *part_ml, const float *part_o, int batc
                              float *out_f32, uint16_t *out_bf16, bool digits, hipStream_t s);
 
 // Communication stand-in: one workgroup busy-waits `ticks` of the constant-rate wall clock.
-// `flag` (optional): the kernel stores `seq` there on entry, which releases the gate of this window.
-hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned seq, hipStream_t s);
+// `flag` (optional): the kernel stores `seq` there on entry, which releases the gate of this window; `done`
+// (optional): it stores `seq` there when the window ends, which releases a consumer launched ahead of time.
+hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned *done, unsigned seq, hipStream_t s);
 
 // Prefetch: everything one communication window pulls towards the cache, in one launch.
 constexpr int kPrefetchRegions = 6;

@@ -195,6 +195,19 @@ __device__ __forceinline__ float dot8(uint4 w, const float (&x)[8], float acc)
     return acc;
 }
 
+// Device-coherent 16-byte loads (sc0 sc1: served by the memory side, past the caches that are not kept coherent
+// while a kernel runs), for data that another kernel may have written after this one started.  The compiler does
+// not count the loads of an asm statement, so ldc_issue only requests and ldc_wait -- which names the destination
+// registers as operands, so that no use can be scheduled above it -- waits for everything outstanding.
+__device__ __forceinline__ void ldc_issue(f32x4 &v, const float *p)
+{
+    asm volatile("global_load_dwordx4 %0, %1, off sc0 sc1" : "=v"(v) : "v"(p) : "memory");
+}
+__device__ __forceinline__ void ldc_wait(f32x4 &a, f32x4 &b, f32x4 &c, f32x4 &d)
+{
+    asm volatile("s_waitcnt vmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d) : : "memory");
+}
+
 __device__ __forceinline__ float silu_mul(float g, float u) { return g / (1.0f + expf(-g)) * u; }
 
 // ------------------------------------------------------------------------------------ norm
@@ -289,6 +302,13 @@ struct GemvArgs {
     // MODE_MERGE: the activations are the attention output, merged here from the split-K partials
     const float *part_ml, *part_o;
     int nkv, G, nc;             // kv heads, query heads per kv head, chunks per (sequence, kv head)
+    // Launched ahead of time (GemvWait): after requesting its first weights, every workgroup waits until
+    // *wait_done has reached wait_seq -- the end of the communication window -- before it touches activations
+    const unsigned *wait_done;
+    unsigned wait_seq;
+    uint32_t wait_iters;        // bounds of the wait: iterations of the poll loop and wall-clock ticks; a wait that
+    uint64_t wait_ticks;        //   runs into them sets *wait_err and the kernel goes on (it always ends)
+    unsigned *wait_err;
 };
 
 enum { GEMV_PLAIN = 0, GEMV_NORM = 1, GEMV_MERGE = 2 };
@@ -347,6 +367,32 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
     load_rows(r0);   // weights first: everything below overlaps with their flight time
     load_scales(r0);
 
+    // ---- launched ahead of its inputs: the weights above travel (and then sit in registers) while the
+    //      communication window is still running; one wave of the workgroup polls for the window's end
+    if (a.wait_done) {
+        __shared__ unsigned wait_ok;
+        if (wave == 0) {
+            const uint64_t t0 = wall_clock64();
+            // relaxed polls (an acquire per poll would invalidate caches every time); one acquire fence follows
+            unsigned v = __hip_atomic_load(a.wait_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            uint32_t it = 0;
+            while ((int)(v - a.wait_seq) < 0 && it < a.wait_iters && wall_clock64() - t0 < a.wait_ticks) {
+                __builtin_amdgcn_s_sleep(8);
+                v = __hip_atomic_load(a.wait_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ++it;
+            }
+            if (lane == 0) {
+                wait_ok = (int)(v - a.wait_seq) >= 0 ? 1u : 0u;
+                if (!wait_ok) atomicOr(a.wait_err, 1u);
+            }
+        }
+        __syncthreads();
+        // The activations read below may have been written while this kernel was already running (by the
+        // collective of the window), so they are fetched with device-coherent loads (ldc_issue); a fence that
+        // invalidates the caches instead costs ~30 us when 4096 waves issue it.
+    }
+    const bool late_inputs = a.wait_done != nullptr;
+
     // ---- activations into registers
     float xv[ITERS][NB][8];
     if (MODE == GEMV_NORM) {
@@ -361,11 +407,28 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
             for (int it = 0; it < ITERS; ++it) {
                 float4 v0 = make_float4(0.f, 0.f, 0.f, 0.f), v1 = v0;
                 if (kok[it]) {
-                    v0 = *reinterpret_cast<const float4 *>(a.res + (size_t)b * K + kk[it]);
-                    v1 = *reinterpret_cast<const float4 *>(a.res + (size_t)b * K + kk[it] + 4);
+                    float4 d0 = make_float4(0.f, 0.f, 0.f, 0.f), d1 = d0;
+                    if (late_inputs) {
+                        const float *dp = a.delta ? a.delta : a.res;   // (a pre-launched kernel always has a delta)
+                        f32x4 q0, q1, q2, q3;
+                        ldc_issue(q0, a.res + (size_t)b * K + kk[it]);
+                        ldc_issue(q1, a.res + (size_t)b * K + kk[it] + 4);
+                        ldc_issue(q2, dp + (size_t)b * K + kk[it]);
+                        ldc_issue(q3, dp + (size_t)b * K + kk[it] + 4);
+                        ldc_wait(q0, q1, q2, q3);
+                        v0 = make_float4(q0[0], q0[1], q0[2], q0[3]);
+                        v1 = make_float4(q1[0], q1[1], q1[2], q1[3]);
+                        d0 = make_float4(q2[0], q2[1], q2[2], q2[3]);
+                        d1 = make_float4(q3[0], q3[1], q3[2], q3[3]);
+                    } else {
+                        v0 = *reinterpret_cast<const float4 *>(a.res + (size_t)b * K + kk[it]);
+                        v1 = *reinterpret_cast<const float4 *>(a.res + (size_t)b * K + kk[it] + 4);
+                        if (a.delta) {
+                            d0 = *reinterpret_cast<const float4 *>(a.delta + (size_t)b * K + kk[it]);
+                            d1 = *reinterpret_cast<const float4 *>(a.delta + (size_t)b * K + kk[it] + 4);
+                        }
+                    }
                     if (a.delta) {
-                        float4 d0 = *reinterpret_cast<const float4 *>(a.delta + (size_t)b * K + kk[it]);
-                        float4 d1 = *reinterpret_cast<const float4 *>(a.delta + (size_t)b * K + kk[it] + 4);
                         v0.x += d0.x; v0.y += d0.y; v0.z += d0.z; v0.w += d0.w;
                         v1.x += d1.x; v1.y += d1.y; v1.z += d1.z; v1.w += d1.w;
                     }
@@ -639,9 +702,13 @@ hipError_t launch_gemv(Mat W, Mat W2, const float *x, float *out, int batch, int
 
 hipError_t launch_gemv_norm(Mat W, Mat W2, const float *res, const float *delta,
                             const uint16_t *gain, float eps, float *out_res, float *out_h, float *out, int batch,
-                            int N, int K, hipStream_t s)
+                            int N, int K, const GemvWait *wait, hipStream_t s)
 {
     GemvArgs a{};
+    if (wait) {
+        a.wait_done = wait->done; a.wait_seq = wait->seq; a.wait_iters = wait->iters; a.wait_ticks = wait->ticks;
+        a.wait_err = wait->err;
+    }
     a.W = W.w; a.W2 = W2.w; a.scale = W.scale; a.scale2 = W2.scale; a.res = res; a.delta = delta; a.gain = gain; a.eps = eps; a.out_res = out_res; a.out_h = out_h;
     a.out = out; a.N = N; a.K = K;
     return gemv_dispatch<GEMV_NORM>(a, batch, s);
@@ -1806,7 +1873,9 @@ hipError_t launch_attn_merge(const float *part_ml, const float *part_o, int batc
 // sure the wave exits even if the clock misbehaves.  On entry it publishes the window's sequence
 // number: a gate kernel (k_gate) is already waiting for it on the side stream, ahead of the window's
 // prefetch launches (a device-side fork, no host event in between).
-__global__ __launch_bounds__(64) void k_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned seq)
+// On exit it publishes the same number in *done (release order): a consumer kernel that was launched ahead of
+// time on the other stream and has already pulled its weights into registers waits for exactly that (k_gemv).
+__global__ __launch_bounds__(64) void k_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned *done, unsigned seq)
 {
     const uint64_t t0 = wall_clock64();
     if (flag && threadIdx.x == 0) __hip_atomic_store(flag, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -1815,11 +1884,12 @@ __global__ __launch_bounds__(64) void k_spin(uint64_t ticks, uint32_t max_iters,
         __builtin_amdgcn_s_sleep(2);
         ++it;
     }
+    if (done && threadIdx.x == 0) __hip_atomic_store(done, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned seq, hipStream_t s)
+hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned *done, unsigned seq, hipStream_t s)
 {
-    PSV_LAUNCH(k_spin, dim3(1), dim3(64), 0, s, ticks, max_iters, flag, seq);
+    PSV_LAUNCH(k_spin, dim3(1), dim3(64), 0, s, ticks, max_iters, flag, done, seq);
     return hipGetLastError();
 }
 
@@ -1855,32 +1925,37 @@ __global__ __launch_bounds__(256) void k_prefetch(PrefetchJob j)
         }
     }
     if (j.kv_count) {
-        // A wave takes NBW logical blocks per step and requests the K part and the V part of every kv head of all
-        // of them before it looks at any result (bf16: 4 KiB each per head; int8: 2112 bytes, codes + scales).
+        // Work item = one (logical block, kv head): a K unit and a V unit (bf16: 4 KiB each; int8: 2112 bytes, codes
+        // + scales).  A wave takes up to NBW items per step and requests all of them before it looks at any
+        // result; with few items every wave takes one, so that a small cache is spread over many waves.
         constexpr int NBW = 4;
         const int lane = threadIdx.x & 63;
         const uint64_t gw = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
         const uint64_t nw = (uint64_t)gridDim.x * 4;
-        const uint32_t per_block16 = (uint32_t)j.nkv * (j.kv.int8 ? PSV_KV_UNIT_BYTES_INT8 / 16 : 256);   // 16-byte words
-        for (uint64_t q0 = gw * NBW; q0 < j.kv_count; q0 += nw * NBW) {
+        const uint32_t unit16 = j.kv.int8 ? PSV_KV_UNIT_BYTES_INT8 / 16 : 256;   // 16-byte words per unit
+        const uint64_t items = j.kv_count * (uint64_t)j.nkv;
+        const int nbw = items >= nw * NBW ? NBW : 1;
+        for (uint64_t q0 = gw * nbw; q0 < items; q0 += nw * nbw) {
             const uint4 *kp[NBW], *vp[NBW];
 #pragma unroll
             for (int u = 0; u < NBW; ++u) {
                 kp[u] = vp[u] = nullptr;
                 const uint64_t q = q0 + u;
-                if (q < j.kv_count) {
-                    const uint64_t lin = j.kv_first + q;
+                if (u < nbw && q < items) {
+                    const uint64_t lin = j.kv_first + q / j.nkv;
+                    const int kvh = (int)(q % j.nkv);
                     const int b = (int)(lin / j.blocks_per_seq), lb = (int)(lin % j.blocks_per_seq);
                     const int blk = lb < j.kv.max_blocks
                                         ? kv_phys_block(j.kv.page_table, j.kv.max_blocks, j.kv.num_pool_blocks, b, lb) : -1;
                     if (blk >= 0) {
-                        kp[u] = reinterpret_cast<const uint4 *>(j.kv.k_pool) + (size_t)blk * per_block16;
-                        vp[u] = reinterpret_cast<const uint4 *>(j.kv.v_pool) + (size_t)blk * per_block16;
+                        const size_t at = ((size_t)blk * j.nkv + kvh) * unit16;
+                        kp[u] = reinterpret_cast<const uint4 *>(j.kv.k_pool) + at;
+                        vp[u] = reinterpret_cast<const uint4 *>(j.kv.v_pool) + at;
                     }
                 }
             }
-            for (uint32_t o = lane; o < per_block16; o += 192) {   // 3 words per pool: one step covers an int8 unit
-                const bool p1 = o + 64 < per_block16, p2 = o + 128 < per_block16;
+            for (uint32_t o = lane; o < unit16; o += 192) {   // 3 words per pool: one step covers an int8 unit
+                const bool p1 = o + 64 < unit16, p2 = o + 128 < unit16;
                 uint4 v[NBW][6];
 #pragma unroll
                 for (int u = 0; u < NBW; ++u) {

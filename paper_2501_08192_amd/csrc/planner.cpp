@@ -117,7 +117,8 @@ psv_status psv_plan_chain(const psv_model_desc *desc, uint32_t batch, uint32_t c
     if (!desc || !policy || !n || (cap > 0 && !out)) return PSV_ERR_INVALID_ARG;
     if (!desc_ok(*desc) || batch == 0 || batch > desc->max_batch || context == 0 || context > desc->max_seq)
         return PSV_ERR_INVALID_ARG;
-    if (policy->mode > 1 || (policy->targets & ~3u) || policy->partial > 1 || policy->join > 1) return PSV_ERR_INVALID_ARG;
+    if (policy->mode > 1 || (policy->targets & ~3u) || policy->partial > 1 || policy->join > 1 || policy->prelaunch > 1)
+        return PSV_ERR_INVALID_ARG;
     *n = plan_chain(*desc, batch, context, *policy, out, cap);
     return PSV_OK;
 }

@@ -207,6 +207,9 @@ def _policies(w):
         psv.prefetch_policy(mode=1, budget_bytes=1 << 20, partial=1, chunk_bytes=4096),
         psv.prefetch_policy(mode=1, targets=psv.PSV_TARGET_KV, budget_bytes=big, chunk_bytes=64 << 10),
         psv.prefetch_policy(mode=1, targets=psv.PSV_TARGET_WEIGHTS, budget_bytes=big),
+        psv.prefetch_policy(mode=1, budget_bytes=big, prelaunch=1),
+        psv.prefetch_policy(mode=1, budget_bytes=big, prelaunch=1, chunk_bytes=1 << 20, cu_budget=8, join=1),
+        psv.prefetch_policy(mode=1, targets=psv.PSV_TARGET_KV, budget_bytes=big, prelaunch=1),
     ]
 
 
@@ -233,8 +236,9 @@ def test_prefetch_policies_and_graph_mode_are_bit_identical(wl):
                         assert torch.equal(got[0], base[0]), (pol.mode, pol.join, graph, win)
                         for a, b in zip(got[1] + got[2], base[1] + base[2]):
                             assert torch.equal(a, b)
+        s.set_policy(_policies(wl)[6])
         plan = psv.psv_plan(s.ctx)
-        assert all(e["target_op"] != psv.PSV_OP_ATTN for e in plan)       # last policy: weights only
+        assert all(e["target_op"] != psv.PSV_OP_ATTN for e in plan)       # that policy: weights only
         assert psv.psv_get_stats(s.ctx)["steps"] > 10
 
 
@@ -256,6 +260,39 @@ def test_tuned_attention_split_matches_oracle_and_policies_stay_bit_identical(wl
                     assert torch.equal(s.run(), base)
         assert s.tune_attention() % 128 == 0        # callable again; the context keeps working
         assert_close(s.run().cpu().numpy(), ref, wl.name + " (second tuning)")
+
+
+def test_prelaunched_consumers_whole_steps_odd_layer_counts_and_windows():
+    """Pre-launch hops streams at every window: odd hop counts, a zero window in between and back-to-back steps."""
+    for L, win in ((1, (5.0, 5.0)), (2, (5.0, 0.0)), (3, (0.0, 8.0)), (3, (6.0, 6.0))):
+        w = W("pre%d" % L, L, 1024, 8, 2, 768, 1, 200, win=win)
+        with Session(w, seed=41) as s:
+            base = s.run().clone()
+            ref, _, _ = run_oracle(s, s.layers)
+            assert_close(base.cpu().numpy(), ref, w.name)
+            s.set_policy(psv.prefetch_policy(mode=1, budget_bytes=1 << 40, prelaunch=1))
+            for rep in range(3):
+                s.step()                                  # no host synchronisation between steps
+            s.sync()
+            assert torch.equal(s.x_out, base), (L, win)
+            assert torch.equal(s.run(layer_begin=0, layer_end=1), s.run(layer_begin=0, layer_end=1))
+
+
+def test_prelaunched_consumer_that_gives_up_waiting_is_reported_and_the_context_survives():
+    w = W("prefail", 2, 1024, 8, 2, 768, 1, 120, win=(300.0, 300.0))     # long windows: the consumers surely start inside them
+    with Session(w, seed=42) as s:
+        base = s.run().clone()
+        s.set_policy(psv.prefetch_policy(mode=1, budget_bytes=1 << 40, prelaunch=1))
+        psv.psv_debug_force_wait_timeout(s.ctx, True)
+        s.step()
+        with pytest.raises(psv.PsvError) as e:
+            s.sync()
+        assert e.value.status == psv.PSV_ERR_HIP
+        psv.psv_debug_force_wait_timeout(s.ctx, False)
+        assert torch.equal(s.run(), base)                 # reported once; the next step is clean
+        s.set_policy(psv.prefetch_policy(mode=1, budget_bytes=1 << 40, prelaunch=0))
+        psv.psv_debug_force_wait_timeout(s.ctx, True)     # nothing is pre-launched: nothing to time out
+        assert torch.equal(s.run(), base)
 
 
 def test_layer_ranges_chain_like_the_whole_step():
