@@ -223,6 +223,7 @@ def main():
                                                       w.context, "paged" if w.paged else "contiguous", *w.window_us),
                    "prefetch_budget_mb": a.budget_mb, "cu_budget": a.cu_budget, "chunk_mb": a.chunk_mb,
                    "partial": a.partial, "join": a.join, "prelaunch": a.prelaunch, "targets": a.targets, "hip_graph": bool(a.graph),
+                   "streams_overlap": bool(sess.overlap),
                    "attn_tokens_per_workgroup": attn_chunk if a.tune else "default"},
         "us_per_layer_prefetch_off": round(us_off, 3),
         "prefetch_speedup": round(us_off / us_on, 4),

@@ -130,7 +130,12 @@ typedef struct {
                                 waits for the window's end on a device flag and finishes from registers; the
                                 operator chain continues on that stream, so the two streams swap roles at
                                 every window.  Takes effect for eager launches at batch 1 (and batch 2 up
-                                to H = 4096); otherwise ignored.  Results are bit-identical either way. */
+                                to H = 4096), and only on a context whose two streams run concurrently
+                                (psv_check_overlap; psv_set_policy runs that check itself if it has not
+                                been run): a kernel that waits on a flag must never sit in front of the
+                                kernel that sets it -- under a profiler that serialises kernels, or on two
+                                streams that share a hardware queue, it would wait until its time limit.
+                                Otherwise ignored.  Results are bit-identical either way. */
 } psv_prefetch_policy;
 
 enum { PSV_TARGET_WEIGHTS = 1u, PSV_TARGET_KV = 2u };
@@ -250,7 +255,8 @@ psv_status psv_tune_attention(psv_ctx *ctx, const float *x_in, float *x_out, uin
  * stream_main and a gate on stream_side that waits for the window's start flag, and times on the
  * host how long stream_side takes to drain: *concurrent = 1 if the gate got through in under half
  * the window, 0 if it had to wait for the window's end (then create the context again with another
- * side stream).  Synchronises both streams. */
+ * side stream).  The context remembers the answer: policy.prelaunch stays without effect unless it is 1.
+ * Synchronises both streams. */
 psv_status psv_check_overlap(psv_ctx *ctx, int32_t *concurrent);
 
 /* ---- measurement and test aids ---------------------------------------------------------- */

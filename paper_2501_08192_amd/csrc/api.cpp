@@ -119,6 +119,7 @@ struct psv_ctx {
     unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
     bool capturing = false;
     uint32_t attn_chunk_tokens = 0;               // 0 = default split; else tokens per attention workgroup (psv_tune_attention)
+    int overlap = -1;                            // psv_check_overlap's last answer (-1 = not run yet)
     bool prelaunch_used = false;                 // some consumer was launched ahead of its window's end: check the error word at sync
     bool force_wait_timeout = false;             // test aid: such consumers give up waiting at once (and report it)
     bool last_step_vec = false;                  // the last step formed h1 / h2 (vector path)
@@ -331,6 +332,7 @@ struct Lanes {
 bool can_prelaunch(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t layer_end, bool vec)
 {
     if (c->capturing || !vec || c->policy.mode != 1 || !c->policy.prelaunch || !(c->window_us[window] > 0.f)) return false;
+    if (c->overlap != 1) return false;      // a waiting kernel may only be queued where it cannot block the window kernel
     if (window == 1 && layer + 1 >= layer_end) return false;       // end of the graph: no consumer
     const uint32_t first_op = window == 0 ? PSV_OP_GATE : PSV_OP_QKV;
     for (const psv_plan_entry &e : c->plan)
@@ -669,6 +671,11 @@ psv_status psv_set_policy(psv_ctx *c, const psv_prefetch_policy *p, uint32_t bat
     if (p->mode > 1 || (p->targets & ~3u) || p->partial > 1 || p->join > 1 || p->prelaunch > 1 || p->cu_budget > 65535)
         return PSV_ERR_INVALID_ARG;
     if (batch == 0 || batch > c->d.max_batch || context == 0 || context > c->d.max_seq) return PSV_ERR_INVALID_ARG;
+    if (p->mode == 1 && p->prelaunch && c->overlap < 0) {   // pre-launched kernels need streams that really overlap
+        int32_t concurrent = 0;
+        psv_status st = psv_check_overlap(c, &concurrent);
+        if (st != PSV_OK) return st;
+    }
     c->policy = *p;
     c->plan_batch = batch;
     c->plan_context = context;
@@ -793,6 +800,8 @@ psv_status psv_check_overlap(psv_ctx *c, int32_t *concurrent)
     HIP_TRY(hipStreamSynchronize(c->side));
     const double waited_us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
     *concurrent = waited_us < 0.5 * us ? 1 : 0;
+    c->overlap = *concurrent;
+    touch(c);
     return psv_sync(c);
 }
 
