@@ -126,7 +126,7 @@ def main():
     import torch
     from paper_2501_08192_amd import binding as psv
     from paper_2501_08192_amd import synth
-    from paper_2501_08192_amd.harness import Session
+    from paper_2501_08192_amd.harness import Session, default_policy
 
     if not torch.cuda.is_available():
         sys.stderr.write("bench.py: no GPU\n")
@@ -147,9 +147,10 @@ def main():
         a.budget_mb = min(192.0, max(w.window_us) * 4.5)
     if a.partial < 0:
         a.partial = 1 if w.paged else 0
-    on = psv.prefetch_policy(mode=1, targets=a.targets, budget_bytes=int(a.budget_mb * MB),
-                             chunk_bytes=int(a.chunk_mb * MB), cu_budget=a.cu_budget, partial=a.partial, join=a.join,
-                             prelaunch=a.prelaunch)
+    # with no flags this is harness.default_policy(w), the configuration the full-size parity tests run
+    on = default_policy(w, targets=a.targets, budget_bytes=int(a.budget_mb * MB),
+                        chunk_bytes=int(a.chunk_mb * MB), cu_budget=a.cu_budget, partial=a.partial, join=a.join,
+                        prelaunch=a.prelaunch)
     off = psv.prefetch_policy(mode=0)
 
     attn_chunk = sess.tune_attention() if a.tune else 0

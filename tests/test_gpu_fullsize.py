@@ -1,5 +1,5 @@
 """GPU parity at the full sizes of the five benchmark workloads, in the launch configuration bench.py times
-(eager launches, prefetch on with a 64 MiB budget and 256 workgroups).  c1 and c2 are checked over the whole
+(eager launches, bench.py's default prefetch policy from harness.default_policy).  c1 and c2 are checked over the whole
 step; c3-c5 hold 18-60 GB of weights and cache, so for them single layers are materialised at their real
 shape, run through the same entry point with a layer range, and compared output by output with the oracle.
 Tolerance: |gpu - ref| <= 2e-2 + 1e-2*|ref|; prefetch on/off must agree bit for bit."""
@@ -10,7 +10,7 @@ import torch
 import oracle
 from paper_2501_08192_amd import binding as psv
 from paper_2501_08192_amd import synth
-from paper_2501_08192_amd.harness import Session
+from paper_2501_08192_amd.harness import Session, default_policy
 
 pytestmark = pytest.mark.gpu
 
@@ -18,7 +18,7 @@ ATOL, RTOL = 2e-2, 1e-2
 
 
 def bench_policy(w):
-    return psv.prefetch_policy(mode=1, budget_bytes=64 << 20, cu_budget=256, partial=1 if w.paged else 0)
+    return default_policy(w)
 
 
 def check_layers(w, layers, seed=2501):
