@@ -150,8 +150,9 @@ def test_rope_disabled():
     check_step(W("norope", 1, 512, 4, 4, 256, 2, 40, theta=0.0), seed=3)
 
 
-def test_multi_head_groups_and_batches_on_the_vector_path():
-    check_step(W("g1", 2, 1024, 8, 8, 512, 4, 90), seed=4)          # G = 1, batch 4
+def test_query_head_groupings_one_and_sixteen_heads_per_kv_head():
+    check_step(W("g1", 2, 1024, 8, 8, 512, 4, 90), seed=4)          # G = 1, batch 4 (matrix-core projections)
+    check_step(W("g1b2", 2, 1024, 8, 8, 512, 2, 90), seed=4)        # G = 1, batch 2 (vector projections)
     check_step(W("g16", 1, 512, 16, 1, 256, 2, 65), seed=5)         # G = 16
 
 
