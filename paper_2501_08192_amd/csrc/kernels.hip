@@ -1313,11 +1313,12 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     //      each wave issues the loads of its first tile right away, ahead of everything else in the kernel.
     const int tau1 = 8 * (i >> 2) + (i & 3);          // token (within the 32-token group) of K row i, tile 1
     uint4 ka[4], kb[4], vf[8];
-    auto load_tile = [&](int t0) {
+    auto lookup = [&](int t0, int &blkA, int &blkB) {
         const int lb = t0 >> 4;
-        const int blkA = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb);
-        const int blkB = (lb + 1 < kv.max_blocks)
-                             ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb + 1) : -1;
+        blkA = kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb);
+        blkB = (lb + 1 < kv.max_blocks) ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lb + 1) : -1;
+    };
+    auto load_blocks = [&](int blkA, int blkB) {
         // K fragments: tile 1 row i = token tau1, tile 2 row i = token tau1 + 4
         {
             const int blk = (i < 8) ? blkA : blkB;
@@ -1346,9 +1347,34 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
             }
         }
     };
+    auto load_tile = [&](int t0) {
+        int blkA, blkB;
+        lookup(t0, blkA, blkB);
+        load_blocks(blkA, blkB);
+    };
+    // Order of the first requests: page-table entries of the first tile, then the query rows and the rotary
+    // table, then the tile itself.  Loads return in order, so the query can be rotated while the tile -- the one
+    // request that goes all the way to HBM -- is still on its way.
     const int t_first = t_begin + w * kAttnTileTokens;
     const bool early = t_first < kv.max_blocks * 16;
-    if (early) load_tile(t_first);
+    int blkA0 = -1, blkB0 = -1;
+    if (early) lookup(t_first, blkA0, blkB0);
+    float qlo[2][8], qhi[2][8];
+    float2 qcs[2][8];
+    if (i < G) {
+        const float *qrow = qkv_b + (size_t)(kvh * G + i) * 128;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            const int f0 = ks * 32 + q4 * 8;
+            *reinterpret_cast<float4 *>(qlo[ks]) = *reinterpret_cast<const float4 *>(qrow + f0);
+            *reinterpret_cast<float4 *>(qlo[ks] + 4) = *reinterpret_cast<const float4 *>(qrow + f0 + 4);
+            *reinterpret_cast<float4 *>(qhi[ks]) = *reinterpret_cast<const float4 *>(qrow + f0 + 64);
+            *reinterpret_cast<float4 *>(qhi[ks] + 4) = *reinterpret_cast<const float4 *>(qrow + f0 + 68);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qcs[ks][e] = rope_b[f0 + e];
+        }
+    }
+    if (early) load_blocks(blkA0, blkB0);
 
     // ---- Q fragments, rotated: lane (g = i, q4) holds channels ks*32 + q4*8 + e; channel f < 64
     //      pairs with f + 64, i.e. fragment ks with fragment ks + 2 of the same lane.
@@ -1357,18 +1383,13 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         uint4 z = zero16();
         qf[0] = qf[1] = qf[2] = qf[3] = __builtin_bit_cast(bf16x8, z);
         if (i < G) {
-            const float *qrow = qkv_b + (size_t)(kvh * G + i) * 128;
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
-                const int f0 = ks * 32 + q4 * 8;
-                float lo[8], hi[8], rl[8], rh[8];
-                *reinterpret_cast<float4 *>(lo) = *reinterpret_cast<const float4 *>(qrow + f0);
-                *reinterpret_cast<float4 *>(lo + 4) = *reinterpret_cast<const float4 *>(qrow + f0 + 4);
-                *reinterpret_cast<float4 *>(hi) = *reinterpret_cast<const float4 *>(qrow + f0 + 64);
-                *reinterpret_cast<float4 *>(hi + 4) = *reinterpret_cast<const float4 *>(qrow + f0 + 68);
+                const float *lo = qlo[ks], *hi = qhi[ks];
+                float rl[8], rh[8];
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    const float2 cs = rope_b[f0 + e];
+                    const float2 cs = qcs[ks][e];
                     rl[e] = lo[e] * cs.x - hi[e] * cs.y;
                     rh[e] = hi[e] * cs.x + lo[e] * cs.y;
                 }
@@ -1537,11 +1558,13 @@ __global__ __launch_bounds__(256) void k_attn_q8(AttnArgs a)
     // ---- tile loader (addresses depend on the page table only, so the first tile is requested right away)
     uint4 kc[4][2], vc[8];
     float4 ksc[4], vsc[4];
-    auto load_tile = [&](int t0) {
+    auto lookup = [&](int t0, int &blkK, int &blkV) {
         const int lb = t0 >> 4;
         const int lbk = lb + (i >> 2), lbv = lb + q4;        // block of this lane's K rows / of its V tokens
-        const int blkK = lbk < kv.max_blocks ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lbk) : -1;
-        const int blkV = lbv < kv.max_blocks ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lbv) : -1;
+        blkK = lbk < kv.max_blocks ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lbk) : -1;
+        blkV = lbv < kv.max_blocks ? kv_phys_block(kv.page_table, kv.max_blocks, kv.num_pool_blocks, b, lbv) : -1;
+    };
+    auto load_blocks = [&](int blkK, int blkV) {
         // A block outside the table (or a corrupt entry) reads block 0 and is blanked with selects: whole-array
         // assignments in two branches would push the fragments out of registers.
         const bool okK = blkK >= 0, okV = blkV >= 0;
@@ -1572,9 +1595,31 @@ __global__ __launch_bounds__(256) void k_attn_q8(AttnArgs a)
             }
         }
     };
+    auto load_tile = [&](int t0) {
+        int blkK, blkV;
+        lookup(t0, blkK, blkV);
+        load_blocks(blkK, blkV);
+    };
+    // Order of the first requests: page-table entries of the first tile, then the query row and the rotary table,
+    // then the tile itself; loads return in order, so the query digits are formed while the tile is on its way.
     const int t_first = t_begin + w * TT;
     const bool early = t_first < kv.max_blocks * 16;
-    if (early) load_tile(t_first);
+    int blkK0 = -1, blkV0 = -1;
+    if (early) lookup(t_first, blkK0, blkV0);
+    const bool have_q = i < G;
+    float4 q_lo[4], q_hi[4];
+    float2 q_cs[16];
+    {
+        const float *qrow = qkv_b + (size_t)(kvh * G + (have_q ? i : 0)) * 128 + q4 * 16;
+#pragma unroll
+        for (int e4 = 0; e4 < 4; ++e4) {
+            q_lo[e4] = *reinterpret_cast<const float4 *>(qrow + e4 * 4);
+            q_hi[e4] = *reinterpret_cast<const float4 *>(qrow + 64 + e4 * 4);
+#pragma unroll
+            for (int u = 0; u < 4; ++u) q_cs[e4 * 4 + u] = rope_b[q4 * 16 + e4 * 4 + u];
+        }
+    }
+    if (early) load_blocks(blkK0, blkV0);
 
     // ---- query digits: lane (g = i, q4) holds channels j*64 + q4*16 + e (j = 0, 1; e = 0..15), the byte order of
     //      its K codes; channel f < 64 pairs with f + 64 for the rotation, i.e. j = 0 with j = 1 of the same lane
@@ -1583,14 +1628,10 @@ __global__ __launch_bounds__(256) void k_attn_q8(AttnArgs a)
     const float kScale = 0.08838834764831845f * 1.4426950408889634f;   // 1/sqrt(128) * log2(e)
     {
         float ql[16], qh[16];
-        const bool have_q = i < G;
-        const float *qrow = qkv_b + (size_t)(kvh * G + (have_q ? i : 0)) * 128 + q4 * 16;
 #pragma unroll
         for (int e4 = 0; e4 < 4; ++e4) {
-            const float4 lo = *reinterpret_cast<const float4 *>(qrow + e4 * 4);
-            const float4 hi = *reinterpret_cast<const float4 *>(qrow + 64 + e4 * 4);
-            const float2 c0 = rope_b[q4 * 16 + e4 * 4 + 0], c1 = rope_b[q4 * 16 + e4 * 4 + 1];
-            const float2 c2 = rope_b[q4 * 16 + e4 * 4 + 2], c3 = rope_b[q4 * 16 + e4 * 4 + 3];
+            const float4 lo = q_lo[e4], hi = q_hi[e4];
+            const float2 c0 = q_cs[e4 * 4 + 0], c1 = q_cs[e4 * 4 + 1], c2 = q_cs[e4 * 4 + 2], c3 = q_cs[e4 * 4 + 3];
             ql[e4 * 4 + 0] = have_q ? lo.x * c0.x - hi.x * c0.y : 0.f;
             qh[e4 * 4 + 0] = have_q ? hi.x * c0.x + lo.x * c0.y : 0.f;
             ql[e4 * 4 + 1] = have_q ? lo.y * c1.x - hi.y * c1.y : 0.f;
