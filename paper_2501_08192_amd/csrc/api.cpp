@@ -364,7 +364,11 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
     if (!any) return PSV_OK;
     unsigned *skip = flag ? flag + 16 : nullptr;
     if (flag)
-        HIP_TRY(launch_gate(flag, seq, 1u << 20, c->clock_khz * 20 /* 20 ms */, skip, ln->other));
+        // A gate that gives up only costs its window's prefetch -- unless a consumer is queued behind it: that
+        // one must not start (and then run out of patience itself) while the stream of the window is merely
+        // held up by earlier work of the caller, so its gate and its own wait are bounded by a second, not 20 ms.
+        HIP_TRY(launch_gate(flag, seq, pre ? 1u << 22 : 1u << 20, c->clock_khz * (pre ? 1000 : 20) /* 1 s : 20 ms */, skip,
+                            ln->other));
     else
         HIP_TRY(hipStreamWaitEvent(ln->other, ev, 0));
     uint64_t cap = c->policy.chunk_bytes & ~(uint64_t)15;
@@ -384,7 +388,7 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
         wait->done = done;
         wait->seq = seq;
         wait->iters = c->force_wait_timeout ? 0u : (1u << 22);
-        wait->ticks = c->force_wait_timeout ? 0ull : us_to_ticks(c->clock_khz, us) * 2 + c->clock_khz * 20 /* + 20 ms */;
+        wait->ticks = c->force_wait_timeout ? 0ull : us_to_ticks(c->clock_khz, us) * 2 + c->clock_khz * 1000 /* + 1 s */;
         wait->err = err;
         *wait_set = true;
         c->prelaunch_used = true;

@@ -296,6 +296,19 @@ def test_prelaunched_consumer_that_gives_up_waiting_is_reported_and_the_context_
         assert torch.equal(s.run(), base)
 
 
+def test_prelaunched_consumers_outwait_earlier_work_on_the_main_stream():
+    """60 ms of unrelated work queued on the main stream ahead of the step: the gates and the consumers launched ahead on
+    the other stream have to sit it out (their waits are bounded by a second), not give up and compute on stale data."""
+    w = W("prebusy", 2, 1024, 8, 2, 768, 1, 120, win=(8.0, 8.0))
+    with Session(w, seed=43) as s:
+        base = s.run().clone()
+        s.set_policy(psv.prefetch_policy(mode=1, budget_bytes=1 << 40, prelaunch=1))
+        psv.psv_spin(60000.0, s.main)
+        s.step()
+        s.sync()                                          # would raise if a consumer had given up
+        assert torch.equal(s.x_out, base)
+
+
 def test_layer_ranges_chain_like_the_whole_step():
     w = W("range", 3, 512, 4, 2, 256, 2, 90)
     with Session(w, seed=22) as s:
