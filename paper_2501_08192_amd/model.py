@@ -19,6 +19,9 @@ class Machine:
     t_fork: float = 2.5          # us from window start to the first prefetch load (gate kernel + dispatch)
     cache_bytes: float = 192e6   # usable part of the 256 MB Infinity Cache
     small_kernels: float = 0.0   # extra us per layer for merge / reduce / norm launches (matrix-core path)
+    reg_bytes: float = 32e6      # weights the first pass of a GEMV launched into a window holds in registers
+    t_post: float = 3.0          # us such a kernel still needs after the window (poll, activations, reduce, drain)
+    bw_reg: float = 24e6         # bytes/us at which it works through the weights it holds (c2: QKV 3.3 us, gate/up 4.3 us)
 
 
 def op_bytes(hidden, n_q, n_kv, ffn, batch, context, head_dim=128, weight_format="bf16", kv_format="bf16"):
@@ -46,11 +49,27 @@ def plan_windows(b, budget):
     return out
 
 
-def layer_time(b, windows, m: Machine, budget=0.0):
+def prelaunched(b, windows, budget):
+    """Which first consumers the `prelaunch` policy launches into their window: gate/up after window 1, the next
+    layer's QKV after window 2, each only if the plan hands that window the whole operator (the gate matrix for
+    the pair).  Batch 1-2 only: the matrix-core path has no such launch."""
+    planned = plan_windows(b, budget) if budget > 0 else {}
+    return {"gate_up": windows[0] > 0 and planned.get("gate", 0.0) >= b["gate"],
+            "qkv": windows[1] > 0 and planned.get("qkv", 0.0) >= b["qkv"]}
+
+
+def layer_time(b, windows, m: Machine, budget=0.0, prelaunch=False):
     """us per layer.  budget = 0: prefetch off.  A window of 0 us launches no prefetch; a window's plan larger
-    than the cache keeps only cache_bytes / planned of itself resident."""
+    than the cache keeps only cache_bytes / planned of itself resident.  prelaunch: the first consumer of a window
+    that the plan covers whole is launched into the window; it is not prefetched a second time, holds up to
+    reg_bytes of its weights in registers when the window ends and streams the rest."""
     groups = (("gate", "up", "down"), ("qkv", "attn", "o"))
     planned = plan_windows(b, budget) if budget > 0 else {}
+    pre = prelaunched(b, windows, budget) if prelaunch else {"gate_up": False, "qkv": False}
+    if pre["gate_up"]:
+        planned["gate"] = planned["up"] = 0.0
+    if pre["qkv"]:
+        planned["qkv"] = 0.0
     hit = {}
     for w, ops in zip(windows, groups):
         tot = sum(planned.get(op, 0.0) for op in ops)
@@ -60,8 +79,11 @@ def layer_time(b, windows, m: Machine, budget=0.0):
     kernels = [("qkv", b["qkv"], hit["qkv"]), ("attn", b["attn"], hit["attn"]), ("o", b["o"], hit["o"]),
                ("gate_up", b["gate"] + b["up"], hit["gate"] + hit["up"]), ("down", b["down"], hit["down"])]
     t = m.small_kernels
-    for _, nbytes, h in kernels:
-        t += m.t_fixed + h / m.bw_cache + (nbytes - h) / m.bw_hbm
+    for name, nbytes, h in kernels:
+        if pre.get(name):
+            t += m.t_post + min(nbytes, m.reg_bytes) / m.bw_reg + max(0.0, nbytes - m.reg_bytes) / m.bw_hbm
+        else:
+            t += m.t_fixed + h / m.bw_cache + (nbytes - h) / m.bw_hbm
     for w, ops in zip(windows, groups):
         if w <= 0:
             continue
@@ -77,5 +99,5 @@ def best_budget(b, windows, m: Machine, candidates=(8e6, 16e6, 32e6, 64e6, 96e6,
     return min(candidates, key=lambda c: layer_time(b, windows, m, c))
 
 
-def speedup(b, windows, m: Machine, budget):
-    return layer_time(b, windows, m, 0.0) / layer_time(b, windows, m, budget)
+def speedup(b, windows, m: Machine, budget, prelaunch=False):
+    return layer_time(b, windows, m, 0.0) / layer_time(b, windows, m, budget, prelaunch)
