@@ -39,7 +39,8 @@ def parse():
                     help="1 = the first operator after a window is launched at the window's start and holds its weights in "
                          "registers until the window ends (policy extension; batch 1-2 only)")
     ap.add_argument("--targets", type=int, default=3)
-    ap.add_argument("--graph", type=int, default=0, help="1 = replay the step as a HIP graph")
+    ap.add_argument("--graph", type=int, default=0,
+                    help="1 = replay the step as a HIP graph (the library refuses unless PSV_ENABLE_HIP_GRAPHS=1 is set)")
     ap.add_argument("--window-us", type=float, nargs=2, default=None)
     ap.add_argument("--tune", type=int, default=0,
                     help="1 = let the library time its candidate attention splits on layer 0 first (psv_tune_attention); "

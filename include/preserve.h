@@ -217,7 +217,11 @@ psv_status psv_set_policy(psv_ctx *ctx, const psv_prefetch_policy *policy, uint3
 psv_status psv_plan(psv_ctx *ctx, psv_plan_entry *out, size_t cap, size_t *n);
 
 /* 0 = launch kernels one by one on the two streams; 1 = capture the step into a HIP graph on
- * first use (keyed by the argument tuple of psv_decode_step) and replay it afterwards. */
+ * first use (keyed by the argument tuple of psv_decode_step) and replay it afterwards.
+ * Graph mode is switched off by default: 1 is answered with PSV_ERR_UNSUPPORTED unless the environment
+ * variable PSV_ENABLE_HIP_GRAPHS is "1".  Test runs that went through many capture / replay / destroy
+ * cycles ended, rarely, in an abort inside the HIP runtime; until that is understood the eager path (which
+ * is also the faster one on this runtime) is the only one enabled. */
 psv_status psv_set_graph_mode(psv_ctx *ctx, uint32_t use_graph);
 
 /*

@@ -5,6 +5,7 @@
 // prefetch kernels the plan assigned to that window while the main stream sits in the window
 // (here: a spin kernel standing in for the allreduce).  Prefetch kernels only read, so the main
 // stream never has to wait for them; the side stream itself serialises consecutive windows.
+#include <cstdlib>
 #include <math.h>
 #include <stdlib.h>
 #include <string.h>
@@ -698,6 +699,12 @@ psv_status psv_plan(psv_ctx *c, psv_plan_entry *out, size_t cap, size_t *n)
 psv_status psv_set_graph_mode(psv_ctx *c, uint32_t use_graph)
 {
     if (!c || use_graph > 1) return PSV_ERR_INVALID_ARG;
+    if (use_graph == 1) {
+        // Off unless asked for twice: runs that captured, replayed and destroyed step graphs ended twice (in ~20 runs
+        // of ~75 captures each) in an abort inside the HIP runtime, with no message and no cause found.
+        const char *on = std::getenv("PSV_ENABLE_HIP_GRAPHS");
+        if (!on || on[0] != '1' || on[1] != '\0') return PSV_ERR_UNSUPPORTED;
+    }
     c->use_graph = use_graph == 1;
     if (!c->use_graph) drop_graph(c);
     return PSV_OK;
