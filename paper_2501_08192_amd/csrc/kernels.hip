@@ -349,16 +349,41 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
     // together with the pass's weights
     const int my_r = lg / NB;
     float sc[NW] = {};
+    // Where the activations are requested ahead of the weights (the ordinary kernel with the fused normalisation),
+    // every load of a pass is issued unconditionally, in straight-line code: a row past the group's range re-reads
+    // the group's last row (a cache hit; its result is never stored) and a thread past the end of a short row reads
+    // column 0 and blanks what it got.  Predicated loads would sit in blocks of their own, and the compiler's wait
+    // counters are conservative across such blocks: it would wait for the weights before any arithmetic on the
+    // activations that were requested ahead of them.
+    constexpr bool ahead = MODE == GEMV_NORM && !WAIT;     // activations are requested ahead of the weights
     auto load_rows = [&](int r0) {
+        if constexpr (!ahead) {
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it)
+            for (int it = 0; it < ITERS; ++it)
+#pragma unroll
+                for (int r = 0; r < RB; ++r) {
+                    const bool ok = kok[it] && (r0 + r < row_end);
+                    const size_t off = ((size_t)(r0 + r) * K + kk[it]) * WB;
+                    wv[it][0][r] = ok ? ldw(Wb + off) : WV{};
+                    if (SWIGLU) wv[it][NW - 1][r] = ok ? ldw(W2b + off) : WV{};
+                }
+            return;
+        }
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            const int col = kok[it] ? kk[it] : 0;
 #pragma unroll
             for (int r = 0; r < RB; ++r) {
-                const bool ok = kok[it] && (r0 + r < row_end);
-                const size_t off = ((size_t)(r0 + r) * K + kk[it]) * WB;
-                wv[it][0][r] = ok ? ldw(Wb + off) : WV{};
-                if (SWIGLU) wv[it][NW - 1][r] = ok ? ldw(W2b + off) : WV{};
+                const int row = max(min(r0 + r, row_end - 1), 0);          // row_end <= N, N >= 1: always inside the matrix
+                const size_t off = ((size_t)row * K + col) * WB;
+                const WV w1 = ldw(Wb + off);
+                wv[it][0][r] = kok[it] ? w1 : WV{};
+                if (SWIGLU) {
+                    const WV w2 = ldw(W2b + off);
+                    wv[it][NW - 1][r] = kok[it] ? w2 : WV{};
+                }
             }
+        }
     };
     auto load_scales = [&](int r0) {
         if (W8 && lg < RB * NB && r0 + my_r < row_end) {
@@ -366,8 +391,54 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
             if (SWIGLU) sc[NW - 1] = a.scale2[r0 + my_r];
         }
     };
+    // ---- order of the first requests.  Loads return in order, and the activations come from the caches (or the
+    //      memory-side cache) while the weights come from HBM: requested first, the activations are back while
+    //      the weights are still on their way, and the prologue (normalisation, attention merge) runs in that
+    //      time instead of after it (c2 gate/up: 9.4 -> 8.9 us).  A kernel launched ahead of its inputs (WAIT)
+    //      cannot do that: its activations do not exist yet; it requests the weights, waits, and only then
+    //      reads them.  The other modes keep the weights first: measured no faster the other way round.
+    constexpr bool late_inputs = WAIT;
+    constexpr int MB = 8;                        // MERGE: chunks merged per round
+    float4 xr[ITERS][NB][2], xd[ITERS][NB][2];   // NORM: residual and delta slices
+    uint4 gv[ITERS];                             // NORM: gains
+    float2 mt[MB];                               // MERGE: (max, sum) and two 16-byte pieces of the partial of MB chunks
+    float4 mo0[MB], mo1[MB];
+    if (ahead) {
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) {
+            gv[it] = kok[it] ? ld16(a.gain + kk[it]) : zero16();
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+                xr[it][b][0] = xr[it][b][1] = xd[it][b][0] = xd[it][b][1] = z;
+                if (kok[it]) {
+                    const float *src = a.res;
+                    xr[it][b][0] = *reinterpret_cast<const float4 *>(src + (size_t)b * K + kk[it]);
+                    xr[it][b][1] = *reinterpret_cast<const float4 *>(src + (size_t)b * K + kk[it] + 4);
+                    if (a.delta) {
+                        xd[it][b][0] = *reinterpret_cast<const float4 *>(a.delta + (size_t)b * K + kk[it]);
+                        xd[it][b][1] = *reinterpret_cast<const float4 *>(a.delta + (size_t)b * K + kk[it] + 4);
+                    }
+                }
+            }
+        }
+    }
+    auto merge_loads = [&](int b, int it, int sp0) {   // partials of chunks sp0 .. sp0+MB-1 for this thread's slice
+        const int h = kk[it] >> 7, ch0 = kk[it] & 127, kvh = h / a.G, g = h % a.G;
+        const size_t slot0 = ((size_t)b * a.nkv + kvh) * a.nc;
+        const float2 *ml = reinterpret_cast<const float2 *>(a.part_ml) + slot0 * 16 + g;
+#pragma unroll
+        for (int u = 0; u < MB; ++u) {
+            const bool ok = sp0 + u < a.nc;
+            const float *o = a.part_o + ((slot0 + sp0 + u) * a.G + g) * 128 + ch0;
+            mt[u] = ok ? ml[(size_t)(sp0 + u) * 16] : make_float2(-1.0e30f, 0.f);
+            mo0[u] = ok ? *reinterpret_cast<const float4 *>(o) : make_float4(0.f, 0.f, 0.f, 0.f);
+            mo1[u] = ok ? *reinterpret_cast<const float4 *>(o + 4) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    };
+
     int r0 = row_begin;
-    load_rows(r0);   // weights first: everything below overlaps with their flight time
+    load_rows(r0);
     load_scales(r0);
 
     // ---- launched ahead of its inputs: the weights above travel (and then sit in registers) while the
@@ -394,14 +465,13 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
         // collective of the window), so they are fetched with device-coherent loads (ldc_issue); a fence that
         // invalidates the caches instead costs ~30 us when 4096 waves issue it.
     }
-    constexpr bool late_inputs = WAIT;
 
     // ---- activations into registers
     float xv[ITERS][NB][8];
     if (MODE == GEMV_NORM) {
-        uint4 gv[ITERS];
+        if (WAIT)
 #pragma unroll
-        for (int it = 0; it < ITERS; ++it) gv[it] = kok[it] ? ld16(a.gain + kk[it]) : zero16();
+            for (int it = 0; it < ITERS; ++it) gv[it] = kok[it] ? ld16(a.gain + kk[it]) : zero16();
         float ss[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
@@ -424,12 +494,8 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
                         d0 = make_float4(q2[0], q2[1], q2[2], q2[3]);
                         d1 = make_float4(q3[0], q3[1], q3[2], q3[3]);
                     } else {
-                        v0 = *reinterpret_cast<const float4 *>(a.res + (size_t)b * K + kk[it]);
-                        v1 = *reinterpret_cast<const float4 *>(a.res + (size_t)b * K + kk[it] + 4);
-                        if (a.delta) {
-                            d0 = *reinterpret_cast<const float4 *>(a.delta + (size_t)b * K + kk[it]);
-                            d1 = *reinterpret_cast<const float4 *>(a.delta + (size_t)b * K + kk[it] + 4);
-                        }
+                        v0 = xr[it][b][0]; v1 = xr[it][b][1];
+                        d0 = xd[it][b][0]; d1 = xd[it][b][1];
                     }
                     if (a.delta) {
                         v0.x += d0.x; v0.y += d0.y; v0.z += d0.z; v0.w += d0.w;
@@ -482,27 +548,15 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) x[e] = 0.f;
                 if (kok[it]) {
-                    const int h = kk[it] >> 7, ch0 = kk[it] & 127, kvh = h / a.G, g = h % a.G;
-                    const size_t slot0 = ((size_t)b * a.nkv + kvh) * a.nc;
                     // One pass with a running maximum; loads are issued MB chunks at a time so that their
-                    // latencies overlap.  Chunk order is fixed, so the result is reproducible.
-                    constexpr int MB = 8;
-                    const float2 *ml = reinterpret_cast<const float2 *>(a.part_ml) + slot0 * 16 + g;
+                    // latencies overlap.  Chunk order is fixed, so the result is reproducible.  (Requesting the
+                    // first round ahead of the weights, 16 chunks at a time, was slower for short chunk lists.)
                     float Mx = -1.0e30f, den = 0.f;
                     for (int sp0 = 0; sp0 < a.nc; sp0 += MB) {
-                        float2 t[MB];
-                        float4 o0[MB], o1[MB];
-#pragma unroll
-                        for (int u = 0; u < MB; ++u) {
-                            const bool ok = sp0 + u < a.nc;
-                            const float *o = a.part_o + ((slot0 + sp0 + u) * a.G + g) * 128 + ch0;
-                            t[u] = ok ? ml[(size_t)(sp0 + u) * 16] : make_float2(-1.0e30f, 0.f);
-                            o0[u] = ok ? *reinterpret_cast<const float4 *>(o) : make_float4(0.f, 0.f, 0.f, 0.f);
-                            o1[u] = ok ? *reinterpret_cast<const float4 *>(o + 4) : make_float4(0.f, 0.f, 0.f, 0.f);
-                        }
+                        merge_loads(b, it, sp0);
                         float bm = Mx;
 #pragma unroll
-                        for (int u = 0; u < MB; ++u) bm = fmaxf(bm, t[u].x);
+                        for (int u = 0; u < MB; ++u) bm = fmaxf(bm, mt[u].x);
                         const float rs = exp2f(Mx - bm);
                         Mx = bm;
                         den *= rs;
@@ -510,12 +564,12 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
                         for (int e = 0; e < 8; ++e) x[e] *= rs;
 #pragma unroll
                         for (int u = 0; u < MB; ++u) {
-                            const float wgt = t[u].y > 0.f ? exp2f(t[u].x - Mx) : 0.f;
-                            den += wgt * t[u].y;
-                            x[0] = fmaf(wgt, o0[u].x, x[0]); x[1] = fmaf(wgt, o0[u].y, x[1]);
-                            x[2] = fmaf(wgt, o0[u].z, x[2]); x[3] = fmaf(wgt, o0[u].w, x[3]);
-                            x[4] = fmaf(wgt, o1[u].x, x[4]); x[5] = fmaf(wgt, o1[u].y, x[5]);
-                            x[6] = fmaf(wgt, o1[u].z, x[6]); x[7] = fmaf(wgt, o1[u].w, x[7]);
+                            const float wgt = mt[u].y > 0.f ? exp2f(mt[u].x - Mx) : 0.f;
+                            den += wgt * mt[u].y;
+                            x[0] = fmaf(wgt, mo0[u].x, x[0]); x[1] = fmaf(wgt, mo0[u].y, x[1]);
+                            x[2] = fmaf(wgt, mo0[u].z, x[2]); x[3] = fmaf(wgt, mo0[u].w, x[3]);
+                            x[4] = fmaf(wgt, mo1[u].x, x[4]); x[5] = fmaf(wgt, mo1[u].y, x[5]);
+                            x[6] = fmaf(wgt, mo1[u].z, x[6]); x[7] = fmaf(wgt, mo1[u].w, x[7]);
                         }
                     }
                     const float inv = den > 0.f ? 1.0f / den : 0.f;
