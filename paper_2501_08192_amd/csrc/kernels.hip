@@ -849,6 +849,13 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
             f.a1[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64 + 8) : zero16();
         }
     };
+    auto load_w_all = [&](int s, WFrag &f) {   // unpredicated: a row past N reads row 0 (wp) and is never stored
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            f.a0[mt] = ld16(wp[mt] + (size_t)s * 64);
+            f.a1[mt] = ld16(wp[mt] + (size_t)s * 64 + 8);
+        }
+    };
     // activation slab: NB*256 16-byte units, unit u = ((tile*2 + plane)*16 + row)*8 + segment
     auto load_slab = [&](int s, uint4 (&r)[NB]) {
 #pragma unroll
@@ -908,29 +915,48 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
     }
     __syncthreads();
 
-    for (int sb = s0; sb < s1; sb += PF) {
+    auto mfma_slab = [&](int buf, const WFrag &f) {
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+            const bf16x8 bh0 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 0) * 2 + 0][lane]);
+            const bf16x8 bh1 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 0) * 2 + 1][lane]);
+            const bf16x8 bl0 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 1) * 2 + 0][lane]);
+            const bf16x8 bl1 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 1) * 2 + 1][lane]);
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                const bf16x8 a0 = __builtin_bit_cast(bf16x8, f.a0[mt]);
+                const bf16x8 a1 = __builtin_bit_cast(bf16x8, f.a1[mt]);
+                acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bh0, acc[mt][n], 0, 0, 0);
+                acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bh1, acc[mt][n], 0, 0, 0);
+                acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bl0, acc[mt][n], 0, 0, 0);
+                acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bl1, acc[mt][n], 0, 0, 0);
+            }
+        }
+    };
+    // Steady state: as long as every slab this round touches exists (s + PF < s1 for all four steps), the round is
+    // straight-line code -- no predicate on any load.  Only then can the compiler count the loads issued after the
+    // one it needs and wait with the exact vmcnt; behind predicated loads it waits for everything outstanding at the
+    // top of every round, which exposes a full memory latency per PF slabs.
+    int sb = s0;
+    for (; sb + 2 * PF <= s1; sb += PF) {
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            const int s = sb + q, buf = q & 1;      // (s - s0) & 1, because PF is even
+            load_slab(s + 2, xr[q & 1]);
+            mfma_slab(buf, wq[q]);
+            load_w_all(s + PF, wq[q]);
+            store_slab(buf ^ 1, xr[(q + 1) & 1]);
+            __syncthreads();
+        }
+    }
+    for (; sb < s1; sb += PF) {                     // the last rounds: every step checks what is left
 #pragma unroll
         for (int q = 0; q < PF; ++q) {
             const int s = sb + q;
             if (s < s1) {                       // uniform over the workgroup
-                const int buf = q & 1;          // (s - s0) & 1, because PF is even
+                const int buf = q & 1;
                 if (s + 2 < s1) load_slab(s + 2, xr[q & 1]);
-#pragma unroll
-                for (int n = 0; n < NB; ++n) {
-                    const bf16x8 bh0 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 0) * 2 + 0][lane]);
-                    const bf16x8 bh1 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 0) * 2 + 1][lane]);
-                    const bf16x8 bl0 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 1) * 2 + 0][lane]);
-                    const bf16x8 bl1 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 1) * 2 + 1][lane]);
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt) {
-                        const bf16x8 a0 = __builtin_bit_cast(bf16x8, wq[q].a0[mt]);
-                        const bf16x8 a1 = __builtin_bit_cast(bf16x8, wq[q].a1[mt]);
-                        acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bh0, acc[mt][n], 0, 0, 0);
-                        acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bh1, acc[mt][n], 0, 0, 0);
-                        acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bl0, acc[mt][n], 0, 0, 0);
-                        acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bl1, acc[mt][n], 0, 0, 0);
-                    }
-                }
+                mfma_slab(buf, wq[q]);
                 if (s + PF < s1) load_w(s + PF, wq[q]);
                 if (s + 1 < s1) store_slab(buf ^ 1, xr[(q + 1) & 1]);
                 __syncthreads();
