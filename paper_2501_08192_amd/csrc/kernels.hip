@@ -824,7 +824,7 @@ struct GemmSkArgs {
 template <int NB>
 __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
 {
-    constexpr int PF = 4;   // slabs of weight fragments in flight per wave (8 measured no faster)
+    constexpr int PF = 4;   // slabs of weight fragments in flight per wave (8 measured slower: fewer straight-line rounds, more registers)
     __shared__ uint4 xs[2][NB * 4][64];   // [buffer][(batch tile*2 + plane)*2 + k half][lane]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
     const int row_base = blockIdx.x * 128 + w * 32;
