@@ -2,12 +2,13 @@
 import os
 import subprocess
 import sys
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpreserve_mi355x.so")
-SOURCES = ["kernels.hip", "api.cpp", "planner.cpp"]
-HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(HERE, "..", "include", "preserve.h")]
+SOURCES = ["gemv.hip", "gemm_sk.hip", "attention.hip", "window.hip", "api.cpp", "planner.cpp"]
+HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "device.h"), os.path.join(HERE, "..", "include", "preserve.h")]
 
 # Packed-FP32 VALU instructions are switched off for all device code.
 HIP_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-result",
@@ -26,13 +27,18 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not is_stale():
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    objs = []
-    for s in SOURCES:
+    def compile_one(s):
         obj = os.path.join(CSRC, os.path.splitext(s)[0] + ".o")
         cmd = [hipcc] + HIP_FLAGS + ["-c", os.path.join(CSRC, s), "-o", obj]
         if s.endswith(".cpp"):
             cmd = [hipcc, "-O2", "-std=c++17", "-fPIC", "-Wall", "-c", os.path.join(CSRC, s), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
+        return s, obj, r
+
+    objs = []
+    with ThreadPoolExecutor(max_workers=min(len(SOURCES), 8)) as pool:      # the files are independent
+        results = list(pool.map(compile_one, SOURCES))
+    for s, obj, r in results:
         if verbose or r.returncode != 0:
             sys.stderr.write(r.stdout + "\n".join(
                 l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l) + "\n")

@@ -1,0 +1,557 @@
+// gfx950 (MI355X, CDNA4) kernels of the PRESERVE decode step: the split-K projections on the matrix cores and the small kernels around them.
+//
+// Weights and the KV-cache are bf16 (or int8 codes with fp32 scales) in HBM; every accumulation is fp32.  The step
+// is bound by HBM bandwidth (Section 2, "LLM decoding is memory BW-limited"), so the kernels are built around
+// 16-byte-per-lane coalesced loads with many loads in flight per 64-lane wave; the matrix cores are used where a
+// vector-ALU formulation would bind on arithmetic (batch > 2 projections, grouped-query attention).
+#include "device.h"
+
+namespace psv {
+
+// ------------------------------------------------------------------------------------ norm
+
+// Residual add for the matrix-core path, spread over many workgroups: grid (H / 512, batch), one float4 per
+// thread.  out_res = res + delta, where delta may be `delta_splits` split-K partials [split][batch][H] that are
+// summed in split order.  With a gain, the kernel also prepares the next projection's operand without ever seeing
+// a whole row: it stores out_res * gain as hi/lo bf16 planes and the sum of squares of its 512 outputs in
+// ssq[batch][H / 512].  RMSNorm is linear in its 1/rms factor, so that projection runs on the unnormalised planes
+// and multiplies its result by 1/rms of the batch row, which it forms from ssq (k_gemm_sk).
+__global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res, const float *__restrict__ delta,
+                                                   int delta_splits, size_t delta_stride, int H,
+                                                   float *__restrict__ out_res, const uint16_t *__restrict__ gain,
+                                                   uint16_t *__restrict__ xg_bf16, size_t plane_stride,
+                                                   int digits, float *__restrict__ ssq)
+{
+    __shared__ float red[2];
+    const int b = blockIdx.y, tid = threadIdx.x;
+    const int i = (blockIdx.x * 128 + tid) * 4;       // H is a multiple of 512: always inside the row
+    const size_t at = (size_t)b * H + i;
+    float4 v = *reinterpret_cast<const float4 *>(res + at);
+    uint2 g = make_uint2(0u, 0u);
+    if (gain) g = *reinterpret_cast<const uint2 *>(gain + i);
+    if (delta) {
+        const float *d = delta + at;
+        float4 t[kSkMaxSplits];   // all loads first (their latencies overlap), then the sum in split order
+#pragma unroll
+        for (int ks = 0; ks < kSkMaxSplits; ++ks)
+            t[ks] = ks < delta_splits ? *reinterpret_cast<const float4 *>(d + ks * delta_stride)
+                                      : make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 e = t[0];
+#pragma unroll
+        for (int ks = 1; ks < kSkMaxSplits; ++ks) { e.x += t[ks].x; e.y += t[ks].y; e.z += t[ks].z; e.w += t[ks].w; }
+        v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w;
+    }
+    *reinterpret_cast<float4 *>(out_res + at) = v;
+    if (!gain) return;
+    const float4 xg = make_float4(v.x * bf16_lo(g.x), v.y * bf16_hi(g.x), v.z * bf16_lo(g.y), v.w * bf16_hi(g.y));
+    if (digits) {   // operand of an int8 projection
+        store_digits4(reinterpret_cast<uint8_t *>(xg_bf16), plane_stride, H, (size_t)b, i, xg);
+    } else {
+        uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+        split_bf16(xg.x, h0, l0); split_bf16(xg.y, h1, l1); split_bf16(xg.z, h2, l2); split_bf16(xg.w, h3, l3);
+        *reinterpret_cast<uint2 *>(xg_bf16 + at) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+        *reinterpret_cast<uint2 *>(xg_bf16 + plane_stride + at) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+    }
+    const float ss = wave_sum(v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w);
+    if ((tid & 63) == 0) red[tid >> 6] = ss;
+    __syncthreads();
+    if (tid == 0) ssq[(size_t)b * gridDim.x + blockIdx.x] = red[0] + red[1];
+}
+
+hipError_t launch_resid_sum(const float *res, const float *delta, int delta_splits, int batch, int H, float *out_res,
+                            const uint16_t *gain, uint16_t *xg_bf16, size_t plane_stride, bool digits, float *ssq,
+                            hipStream_t s)
+{
+    PSV_LAUNCH(k_resid_sum, dim3(H / 512, batch), dim3(128), 0, s, res, delta, delta_splits, (size_t)batch * H, H,
+               out_res, gain, xg_bf16, plane_stride, digits ? 1 : 0, ssq);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------ split-K skinny GEMM
+
+// part[ks][b][r] = sum over the K-range of split ks of W[r][k] x[b][k], for batches of 17..64 (and any
+// smaller batch).  A workgroup of 4 waves owns 128 weight rows (2 MFMA row tiles per wave) and a range of
+// 64-element K slabs.  Per slab the activations of all batch entries (hi and lo bf16 planes) are brought
+// into LDS once, in MFMA fragment order, and every wave reads its B-fragments from there, so the 16-byte
+// global loads of a wave are spent on weights only: 32 contiguous bytes per lane per row tile, i.e. whole
+// 128-byte lines of 16 rows.  Weight fragments are prefetched PF slabs ahead through a register ring and
+// the activation slab two slabs ahead, which keeps 16 KiB per wave in flight even when only a few
+// workgroups exist (small matrices at batch 64 cannot use many: every extra K split costs a partial
+// result of batch x rows floats).  Splits are summed later in split order by the consumer (k_sk_reduce or
+// k_resid_sum): deterministic, no atomics.
+struct GemmSkArgs {
+    const uint16_t *W, *W2;   // rows >= split_row are taken from W2 (row - split_row): gate | up in one launch
+    int split_row;
+    const uint16_t *xb;       // hi plane [round_up(batch,16)][K], lo plane x_plane elements further
+    size_t x_plane;
+    float *part;              // [splits][batch][N]
+    int batch, N, K, n_slabs, slabs_per_block;
+    // ssq != null: the activations are x * gain without the 1/rms factor of their RMSNorm; ssq[batch][K / 512]
+    // holds partial sums of squares of x (k_resid_sum) and the epilogue multiplies column b by 1/rms(b)
+    const float *ssq;
+    float eps;
+};
+
+template <int NB>
+__global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
+{
+    constexpr int PF = 4;   // slabs of weight fragments in flight per wave (8 measured slower: fewer straight-line rounds, more registers)
+    __shared__ uint4 xs[2][NB * 4][64];   // [buffer][(batch tile*2 + plane)*2 + k half][lane]
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
+    const int row_base = blockIdx.x * 128 + w * 32;
+    const int s0 = blockIdx.y * a.slabs_per_block, s1 = min(s0 + a.slabs_per_block, a.n_slabs);
+    const int K = a.K;
+
+    // Lane (i, g) owns elements g*16 .. g*16+15 of row i of every 64-element slab: 32 contiguous bytes = two fragments.
+    const uint16_t *wp[2];
+    bool wok[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const int r = row_base + mt * 16 + i;
+        wok[mt] = r < a.N;
+        const int rr = wok[mt] ? r : 0;
+        wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 16;
+    }
+    struct WFrag { uint4 a0[2], a1[2]; };
+    auto load_w = [&](int s, WFrag &f) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            f.a0[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64) : zero16();
+            f.a1[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64 + 8) : zero16();
+        }
+    };
+    auto load_w_all = [&](int s, WFrag &f) {   // unpredicated: a row past N reads row 0 (wp) and is never stored
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt) {
+            f.a0[mt] = ld16(wp[mt] + (size_t)s * 64);
+            f.a1[mt] = ld16(wp[mt] + (size_t)s * 64 + 8);
+        }
+    };
+    // activation slab: NB*256 16-byte units, unit u = ((tile*2 + plane)*16 + row)*8 + segment
+    auto load_slab = [&](int s, uint4 (&r)[NB]) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int u = tid + j * 256, n = u >> 8, p = (u >> 7) & 1, row = (u >> 3) & 15, seg = u & 7;
+            r[j] = ld16(a.xb + (size_t)p * a.x_plane + (size_t)(n * 16 + row) * K + (size_t)s * 64 + seg * 8);
+        }
+    };
+    auto store_slab = [&](int buf, const uint4 (&r)[NB]) {
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int u = tid + j * 256, n = u >> 8, p = (u >> 7) & 1, row = (u >> 3) & 15, seg = u & 7;
+            xs[buf][(n * 2 + p) * 2 + (seg & 1)][(seg >> 1) * 16 + row] = r[j];   // fragment order: k = g*16 + half*8 + e
+        }
+    };
+
+    f32x4 acc[2][NB];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int n = 0; n < NB; ++n) acc[mt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    __shared__ float inv_s[NB * 16];
+
+    WFrag wq[PF];
+#pragma unroll
+    for (int q = 0; q < PF; ++q)
+        if (s0 + q < s1) load_w(s0 + q, wq[q]);
+    uint4 xr[2][NB];
+    if (s0 < s1) {
+        load_slab(s0, xr[0]);
+        if (s0 + 1 < s1) load_slab(s0 + 1, xr[1]);
+        store_slab(0, xr[0]);
+    }
+    // 1/rms of every batch row from the partial sums of squares (block order); read in the epilogue only, the
+    // barriers of the main loop make it visible
+    if (tid < NB * 16) {
+        float inv = 1.0f;
+        if (a.ssq) {
+            float tot = 0.f;
+            const int nblk = K / 512;                       // <= 32
+            if (tid < a.batch) {
+                const float *p = a.ssq + (size_t)tid * nblk;
+                if ((nblk & 3) == 0) {                      // all loads at once, then the sum in block order
+                    float4 t[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        t[q] = 4 * q < nblk ? *reinterpret_cast<const float4 *>(p + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) tot = (((tot + t[q].x) + t[q].y) + t[q].z) + t[q].w;
+                } else {
+                    for (int q = 0; q < nblk; ++q) tot += p[q];
+                }
+            }
+            inv = 1.0f / sqrtf(tot / (float)K + a.eps);
+        }
+        inv_s[tid] = inv;
+    }
+    __syncthreads();
+
+    auto mfma_slab = [&](int buf, const WFrag &f) {
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+            const bf16x8 bh0 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 0) * 2 + 0][lane]);
+            const bf16x8 bh1 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 0) * 2 + 1][lane]);
+            const bf16x8 bl0 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 1) * 2 + 0][lane]);
+            const bf16x8 bl1 = __builtin_bit_cast(bf16x8, xs[buf][(n * 2 + 1) * 2 + 1][lane]);
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                const bf16x8 a0 = __builtin_bit_cast(bf16x8, f.a0[mt]);
+                const bf16x8 a1 = __builtin_bit_cast(bf16x8, f.a1[mt]);
+                acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bh0, acc[mt][n], 0, 0, 0);
+                acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bh1, acc[mt][n], 0, 0, 0);
+                acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bl0, acc[mt][n], 0, 0, 0);
+                acc[mt][n] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bl1, acc[mt][n], 0, 0, 0);
+            }
+        }
+    };
+    // Steady state: as long as every slab this round touches exists (s + PF < s1 for all four steps), the round is
+    // straight-line code -- no predicate on any load.  Only then can the compiler count the loads issued after the
+    // one it needs and wait with the exact vmcnt; behind predicated loads it waits for everything outstanding at the
+    // top of every round, which exposes a full memory latency per PF slabs.
+    int sb = s0;
+    for (; sb + 2 * PF <= s1; sb += PF) {
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            const int s = sb + q, buf = q & 1;      // (s - s0) & 1, because PF is even
+            load_slab(s + 2, xr[q & 1]);
+            mfma_slab(buf, wq[q]);
+            load_w_all(s + PF, wq[q]);
+            store_slab(buf ^ 1, xr[(q + 1) & 1]);
+            __syncthreads();
+        }
+    }
+    for (; sb < s1; sb += PF) {                     // the last rounds: every step checks what is left
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            const int s = sb + q;
+            if (s < s1) {                       // uniform over the workgroup
+                const int buf = q & 1;
+                if (s + 2 < s1) load_slab(s + 2, xr[q & 1]);
+                mfma_slab(buf, wq[q]);
+                if (s + PF < s1) load_w(s + PF, wq[q]);
+                if (s + 1 < s1) store_slab(buf ^ 1, xr[(q + 1) & 1]);
+                __syncthreads();
+            }
+        }
+    }
+
+    // D fragment: lane holds rows 4g..4g+3 of batch column i
+    float *part = a.part + (size_t)blockIdx.y * a.batch * a.N;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const int r = row_base + mt * 16 + 4 * g;
+        if (r < a.N) {
+#pragma unroll
+            for (int n = 0; n < NB; ++n) {
+                const int b = n * 16 + i;
+                const float inv = inv_s[b];
+                if (b < a.batch)
+                    *reinterpret_cast<float4 *>(part + (size_t)b * a.N + r) =
+                        make_float4(acc[mt][n][0] * inv, acc[mt][n][1] * inv, acc[mt][n][2] * inv, acc[mt][n][3] * inv);
+            }
+        }
+    }
+}
+
+// The same split-K projection for int8 weights, entirely on the int8 matrix cores: the weight codes are the A
+// operand as they are (16 bytes = 16 consecutive k of one row per lane and 64-element slab), the activations
+// arrive as two int8 digit planes with one scale per 128-element block (store_digits4) and are the B operand.
+// Each digit has its own exact i32 accumulator; at the end of every 128-element block (two slabs) the pair is
+// folded into the fp32 accumulator as scale/254 * (254*D1 + D2).  No per-element conversion of weights anywhere.
+// (128-element slabs, i.e. whole 128-byte lines per row and step, measured slower: 19.6 -> 25 us on the 70B-shaped
+// gate/up matrix at batch 8.)
+struct GemmI8Args {
+    const int8_t *W, *W2;          // rows >= split_row come from W2
+    const float *scale, *scale2;   // per-row weight scales
+    int split_row;
+    const uint8_t *xd;             // digit plane d1 [round_up(batch,16)][K]; d2 x_plane bytes later; then the block scales
+    size_t x_plane;
+    float *part;                   // [splits][batch][N]
+    int batch, N, K, n_slabs, slabs_per_block;
+    const float *ssq;              // see GemmSkArgs
+    float eps;
+};
+
+template <int NB>
+__global__ __launch_bounds__(256) void k_gemm_sk_i8(GemmI8Args a)
+{
+    constexpr int PF = 8;                          // slabs of weight codes in flight per wave (2 x 16 bytes each)
+    __shared__ uint4 xs[2][NB * 2][64];            // [buffer][batch tile * 2 + digit][lane]
+    __shared__ float bs[2][NB * 16];               // block scale of each batch row for the buffered slab
+    __shared__ float inv_s[NB * 16];
+    const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
+    const int row_base = blockIdx.x * 128 + w * 32;
+    const int s0 = blockIdx.y * a.slabs_per_block, s1 = min(s0 + a.slabs_per_block, a.n_slabs);
+    const int K = a.K;
+    const float *bscale = reinterpret_cast<const float *>(a.xd + 2 * a.x_plane);
+    const int nblk128 = K / 128;
+
+    const int8_t *wp[2];
+    bool wok[2];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const int r = row_base + mt * 16 + i;
+        wok[mt] = r < a.N;
+        const int rr = wok[mt] ? r : 0;
+        wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 16;
+    }
+    // Lane (i, g) owns bytes g*16 .. g*16+15 of row i of every 64-element slab: the A operand of one MFMA.
+    struct WFrag { uint4 c[2]; };
+    auto load_w = [&](int s, WFrag &f) {
+#pragma unroll
+        for (int mt = 0; mt < 2; ++mt)
+            f.c[mt] = wok[mt] ? *reinterpret_cast<const uint4 *>(wp[mt] + (size_t)s * 64) : zero16();
+    };
+    // activation slab: NB*128 16-byte units, unit u = ((tile*2 + digit)*16 + row)*4 + segment
+    constexpr int NU = (NB + 1) / 2;
+    struct SlabRegs { uint4 r[NU]; float sc; };
+    auto load_slab = [&](int s, SlabRegs &sr) {
+#pragma unroll
+        for (int j = 0; j < NU; ++j) {
+            const int u = tid + j * 256, n = u >> 7, dgt = (u >> 6) & 1, row = (u >> 2) & 15, seg = u & 3;
+            sr.r[j] = u < NB * 128 ? *reinterpret_cast<const uint4 *>(a.xd + (size_t)dgt * a.x_plane +
+                                                                       (size_t)(n * 16 + row) * K + (size_t)s * 64 + seg * 16)
+                                   : zero16();
+        }
+        sr.sc = tid < NB * 16 ? bscale[(size_t)tid * nblk128 + (s >> 1)] : 0.f;
+    };
+    auto store_slab = [&](int buf, const SlabRegs &sr) {
+#pragma unroll
+        for (int j = 0; j < NU; ++j) {
+            const int u = tid + j * 256, n = u >> 7, dgt = (u >> 6) & 1, row = (u >> 2) & 15, seg = u & 3;
+            if (u < NB * 128) xs[buf][n * 2 + dgt][seg * 16 + row] = sr.r[j];   // B operand: lane (row, segment)
+        }
+        if (tid < NB * 16) bs[buf][tid] = sr.sc;
+    };
+    f32x4 acc[2][NB];
+    i32x4 d1[2][NB], d2[2][NB];
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+            acc[mt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
+            d1[mt][n] = i32x4{0, 0, 0, 0};
+            d2[mt][n] = i32x4{0, 0, 0, 0};
+        }
+
+    WFrag wq[PF];
+#pragma unroll
+    for (int q = 0; q < PF; ++q)
+        if (s0 + q < s1) load_w(s0 + q, wq[q]);
+    SlabRegs xr[2];
+    if (s0 < s1) {
+        load_slab(s0, xr[0]);
+        if (s0 + 1 < s1) load_slab(s0 + 1, xr[1]);
+        store_slab(0, xr[0]);
+    }
+    if (tid < NB * 16) {   // 1/rms of every batch row (see k_gemm_sk)
+        float inv = 1.0f;
+        if (a.ssq) {
+            float tot = 0.f;
+            const int nblk = K / 512;
+            if (tid < a.batch) {
+                const float *p = a.ssq + (size_t)tid * nblk;
+                if ((nblk & 3) == 0) {
+                    float4 t[8];
+#pragma unroll
+                    for (int q = 0; q < 8; ++q)
+                        t[q] = 4 * q < nblk ? *reinterpret_cast<const float4 *>(p + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                    for (int q = 0; q < 8; ++q) tot = (((tot + t[q].x) + t[q].y) + t[q].z) + t[q].w;
+                } else {
+                    for (int q = 0; q < nblk; ++q) tot += p[q];
+                }
+            }
+            inv = 1.0f / sqrtf(tot / (float)K + a.eps);
+        }
+        inv_s[tid] = inv;
+    }
+    __syncthreads();
+
+    for (int sb = s0; sb < s1; sb += PF) {
+#pragma unroll
+        for (int q = 0; q < PF; ++q) {
+            const int s = sb + q;
+            if (s < s1) {                       // uniform over the workgroup
+                const int buf = q & 1;          // (s - s0) & 1, because PF is even
+                if (s + 2 < s1) load_slab(s + 2, xr[q & 1]);
+                const bool fold = (s & 1) || s + 1 == s1;   // end of a 128-element block, or of this workgroup's range
+#pragma unroll
+                for (int n = 0; n < NB; ++n) {
+                    const i32x4 x1 = __builtin_bit_cast(i32x4, xs[buf][n * 2 + 0][lane]);
+                    const i32x4 x2 = __builtin_bit_cast(i32x4, xs[buf][n * 2 + 1][lane]);
+#pragma unroll
+                    for (int mt = 0; mt < 2; ++mt) {
+                        const i32x4 wc = __builtin_bit_cast(i32x4, wq[q].c[mt]);
+                        d1[mt][n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wc, x1, d1[mt][n], 0, 0, 0);
+                        d2[mt][n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wc, x2, d2[mt][n], 0, 0, 0);
+                    }
+                    if (fold) {
+                        const float sc = bs[buf][n * 16 + i] * (1.0f / 254.0f);
+#pragma unroll
+                        for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+                            for (int j = 0; j < 4; ++j)
+                                acc[mt][n][j] = fmaf(sc, (float)(d1[mt][n][j] * 254 + d2[mt][n][j]), acc[mt][n][j]);
+                            d1[mt][n] = i32x4{0, 0, 0, 0};
+                            d2[mt][n] = i32x4{0, 0, 0, 0};
+                        }
+                    }
+                }
+                if (s + PF < s1) load_w(s + PF, wq[q]);
+                if (s + 1 < s1) store_slab(buf ^ 1, xr[(q + 1) & 1]);
+                __syncthreads();
+            }
+        }
+    }
+
+    // D fragment: lane holds rows 4g..4g+3 of batch column i
+    float *part = a.part + (size_t)blockIdx.y * a.batch * a.N;
+#pragma unroll
+    for (int mt = 0; mt < 2; ++mt) {
+        const int r = row_base + mt * 16 + 4 * g;
+        if (r < a.N) {
+            const float4 sc = r < a.split_row ? *reinterpret_cast<const float4 *>(a.scale + r)
+                                              : *reinterpret_cast<const float4 *>(a.scale2 + (r - a.split_row));
+#pragma unroll
+            for (int n = 0; n < NB; ++n) {
+                const int b = n * 16 + i;
+                const float inv = inv_s[b];
+                if (b < a.batch)
+                    *reinterpret_cast<float4 *>(part + (size_t)b * a.N + r) =
+                        make_float4(acc[mt][n][0] * sc.x * inv, acc[mt][n][1] * sc.y * inv, acc[mt][n][2] * sc.z * inv,
+                                    acc[mt][n][3] * sc.w * inv);
+            }
+        }
+    }
+}
+
+// Number of K splits, from a small cost model of the kernel: a workgroup needs ~0.6 us per slab it walks
+// (latency of one pipelined slab step), 512 workgroups are resident at a time, and weights plus partial
+// results (written once, read back once) stream at ~4 TB/s.  More splits shorten the walk and cost partial
+// traffic of batch * N * 8 bytes each; small matrices at batch 64 end up with 4-16 splits, wide ones at
+// small batch with as many as keep every CU busy.
+int gemm_sk_splits(int batch, int N, int K, bool w8)
+{
+    const int n_slabs = K / 64;
+    const double row_groups = (double)((N + 127) / 128);
+    const double w_bytes = (w8 ? 1.0 : 2.0) * N * K, part_bytes = 8.0 * batch * N;
+    int best = 1;
+    double best_cost = 1e30;
+    for (int ks = 1; ks <= kSkMaxSplits && ks * 2 <= n_slabs; ++ks) {
+        const int spb = (n_slabs + ks - 1) / ks;
+        const int real = (n_slabs + spb - 1) / spb;
+        if (real != ks) continue;
+        const double rounds = (double)(long long)((row_groups * ks + 511) / 512);
+        const double cost = rounds * spb * 0.6 + (w_bytes + ks * part_bytes) / 4.0e6;
+        if (cost < best_cost - 1e-9) { best_cost = cost; best = ks; }
+    }
+    return best;
+}
+
+bool gemm_sk_supported(int batch, int N, int K)
+{
+    return batch >= 1 && batch <= 64 && N % 16 == 0 && K % 64 == 0;
+}
+
+hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, const float *ssq, float eps, float *part,
+                          int batch, int N, int K, hipStream_t s)
+{
+    const int nb = (batch + 15) / 16;
+    if (W.scale) {   // int8 weights: xb holds digit planes (bytes), see k_gemm_sk_i8
+        GemmI8Args q{};
+        q.W = static_cast<const int8_t *>(W.w); q.W2 = static_cast<const int8_t *>(W2.w ? W2.w : W.w);
+        q.scale = W.scale; q.scale2 = W2.w ? W2.scale : W.scale; q.split_row = W2.w ? split_row : N;
+        q.xd = reinterpret_cast<const uint8_t *>(xb); q.x_plane = (size_t)nb * 16 * K;
+        q.part = part; q.batch = batch; q.N = N; q.K = K; q.n_slabs = K / 64; q.ssq = ssq; q.eps = eps;
+        const int splits = gemm_sk_splits(batch, N, K, true);
+        q.slabs_per_block = (q.n_slabs + splits - 1) / splits;
+        const dim3 grid((N + 127) / 128, splits);
+        switch (nb) {
+        case 1: PSV_LAUNCH(k_gemm_sk_i8<1>, grid, dim3(256), 0, s, q); break;
+        case 2: PSV_LAUNCH(k_gemm_sk_i8<2>, grid, dim3(256), 0, s, q); break;
+        case 3: PSV_LAUNCH(k_gemm_sk_i8<3>, grid, dim3(256), 0, s, q); break;
+        case 4: PSV_LAUNCH(k_gemm_sk_i8<4>, grid, dim3(256), 0, s, q); break;
+        default: return hipErrorInvalidValue;
+        }
+        return hipGetLastError();
+    }
+    GemmSkArgs a{};
+    a.ssq = ssq; a.eps = eps;
+    a.W = static_cast<const uint16_t *>(W.w); a.W2 = static_cast<const uint16_t *>(W2.w ? W2.w : W.w);
+    a.split_row = W2.w ? split_row : N; a.xb = xb; a.x_plane = (size_t)nb * 16 * K;
+    a.part = part; a.batch = batch; a.N = N; a.K = K; a.n_slabs = K / 64;
+    const int splits = gemm_sk_splits(batch, N, K, false);
+    a.slabs_per_block = (a.n_slabs + splits - 1) / splits;
+    const dim3 grid((N + 127) / 128, splits);
+    switch (nb) {
+    case 1: PSV_LAUNCH(k_gemm_sk<1>, grid, dim3(256), 0, s, a); break;
+    case 2: PSV_LAUNCH(k_gemm_sk<2>, grid, dim3(256), 0, s, a); break;
+    case 3: PSV_LAUNCH(k_gemm_sk<3>, grid, dim3(256), 0, s, a); break;
+    case 4: PSV_LAUNCH(k_gemm_sk<4>, grid, dim3(256), 0, s, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// out[b][n] = sum over splits (split order) of part[ks][b][n]; with SwiGLU the N columns are gate | up
+// halves and the result is silu(gate) * up, [batch][N/2], stored as fp32 and as hi/lo bf16 planes.
+template <bool SWIGLU>
+__global__ __launch_bounds__(256) void k_sk_reduce(const float *__restrict__ part, int splits, int batch, int N,
+                                                   float *__restrict__ out, uint16_t *__restrict__ out_bf16, size_t out_plane,
+                                                   int digits)
+{
+    const int NO = SWIGLU ? N / 2 : N;                 // output columns
+    const size_t total4 = (size_t)batch * NO / 4;
+    const size_t split_stride = (size_t)batch * N;
+    for (size_t q = (size_t)blockIdx.x * 256 + threadIdx.x; q < total4; q += (size_t)gridDim.x * 256) {
+        const size_t e = q * 4, b = e / NO, c = e % NO;
+        const float *p = part + b * N + c;
+        // all split loads first (their latencies overlap), then the sums in split order
+        float4 t[kSkMaxSplits], t2[SWIGLU ? kSkMaxSplits : 1];
+#pragma unroll
+        for (int ks = 0; ks < kSkMaxSplits; ++ks) {
+            t[ks] = ks < splits ? *reinterpret_cast<const float4 *>(p + ks * split_stride) : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (SWIGLU)
+                t2[ks] = ks < splits ? *reinterpret_cast<const float4 *>(p + ks * split_stride + NO)
+                                     : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        float4 v = t[0], u = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (SWIGLU) u = t2[0];
+#pragma unroll
+        for (int ks = 1; ks < kSkMaxSplits; ++ks) {
+            v.x += t[ks].x; v.y += t[ks].y; v.z += t[ks].z; v.w += t[ks].w;
+            if (SWIGLU) { u.x += t2[ks].x; u.y += t2[ks].y; u.z += t2[ks].z; u.w += t2[ks].w; }
+        }
+        if (SWIGLU) {
+            v.x = silu_mul(v.x, u.x); v.y = silu_mul(v.y, u.y); v.z = silu_mul(v.z, u.z); v.w = silu_mul(v.w, u.w);
+        }
+        *reinterpret_cast<float4 *>(out + b * NO + c) = v;
+        if (out_bf16 && digits) {   // whole waves take this branch together (NO is a multiple of 256)
+            store_digits4(reinterpret_cast<uint8_t *>(out_bf16), out_plane, NO, b, (int)c, v);
+        } else if (out_bf16) {
+            uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
+            split_bf16(v.x, h0, l0); split_bf16(v.y, h1, l1); split_bf16(v.z, h2, l2); split_bf16(v.w, h3, l3);
+            *reinterpret_cast<uint2 *>(out_bf16 + b * NO + c) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+            *reinterpret_cast<uint2 *>(out_bf16 + out_plane + b * NO + c) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+        }
+    }
+}
+
+hipError_t launch_sk_reduce(const float *part, int splits, int batch, int N, bool swiglu, float *out,
+                            uint16_t *out_bf16, bool digits, hipStream_t s)
+{
+    const int NO = swiglu ? N / 2 : N;
+    const size_t total4 = (size_t)batch * NO / 4;
+    unsigned blocks = (unsigned)((total4 + 255) / 256);
+    if (blocks > 2048) blocks = 2048;
+    if (blocks < 1) blocks = 1;
+    const size_t out_plane = (size_t)((batch + 15) / 16 * 16) * NO;
+    if (swiglu)
+        PSV_LAUNCH(k_sk_reduce<true>, dim3(blocks), dim3(256), 0, s, part, splits, batch, N, out, out_bf16, out_plane, digits ? 1 : 0);
+    else
+        PSV_LAUNCH(k_sk_reduce<false>, dim3(blocks), dim3(256), 0, s, part, splits, batch, N, out, out_bf16, out_plane, digits ? 1 : 0);
+    return hipGetLastError();
+}
+
+}  // namespace psv

@@ -1,0 +1,190 @@
+// gfx950 (MI355X, CDNA4) kernels of the PRESERVE decode step: the communication-window stand-in, the gate, the prefetch kernel and the calibration copy.
+//
+// Weights and the KV-cache are bf16 (or int8 codes with fp32 scales) in HBM; every accumulation is fp32.  The step
+// is bound by HBM bandwidth (Section 2, "LLM decoding is memory BW-limited"), so the kernels are built around
+// 16-byte-per-lane coalesced loads with many loads in flight per 64-lane wave; the matrix cores are used where a
+// vector-ALU formulation would bind on arithmetic (batch > 2 projections, grouped-query attention).
+#include "device.h"
+
+namespace psv {
+
+void set_launch_events(hipEvent_t start, hipEvent_t stop)
+{
+    g_ev_start = start;
+    g_ev_stop = stop;
+}
+
+// ------------------------------------------------------------------------------------ spin window
+
+// One workgroup of one wave busy-waits on the constant-rate wall clock; the iteration cap makes
+// sure the wave exits even if the clock misbehaves.  On entry it publishes the window's sequence
+// number: a gate kernel (k_gate) is already waiting for it on the side stream, ahead of the window's
+// prefetch launches (a device-side fork, no host event in between).
+// On exit it publishes the same number in *done (release order): a consumer kernel that was launched ahead of
+// time on the other stream and has already pulled its weights into registers waits for exactly that (k_gemv).
+__global__ __launch_bounds__(64) void k_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned *done, unsigned seq)
+{
+    const uint64_t t0 = wall_clock64();
+    if (flag && threadIdx.x == 0) __hip_atomic_store(flag, seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t it = 0;
+    while (wall_clock64() - t0 < ticks && it < max_iters) {
+        __builtin_amdgcn_s_sleep(2);
+        ++it;
+    }
+    if (done && threadIdx.x == 0) __hip_atomic_store(done, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+hipError_t launch_spin(uint64_t ticks, uint32_t max_iters, unsigned *flag, unsigned *done, unsigned seq, hipStream_t s)
+{
+    PSV_LAUNCH(k_spin, dim3(1), dim3(64), 0, s, ticks, max_iters, flag, done, seq);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------ prefetch
+
+// Reads memory with 16-byte loads and throws the data away: the loads allocate the lines in the
+// memory-side cache (Infinity Cache).  Nothing is written.  One launch serves a whole communication
+// window: up to kPrefetchRegions linear regions (projection weights) plus a range of KV blocks that
+// is walked through the page table.  The grid size is the CU budget of the policy; 16 x 16-byte loads are in flight per thread.
+__device__ __forceinline__ uint32_t fold(uint4 v) { return v.x ^ v.y ^ v.z ^ v.w; }
+
+__global__ __launch_bounds__(256) void k_prefetch(PrefetchJob j)
+{
+    constexpr int U = 16;
+    if (j.skip && *j.skip) return;   // the gate kernel ahead of this launch found the window already over
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    const uint64_t me = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    uint32_t sink = 0;
+    for (int r = 0; r < j.n_regions; ++r) {
+        const uint4 *p = reinterpret_cast<const uint4 *>(j.ptr[r]);
+        const uint64_t n16 = j.n16[r];
+        // batches of U independent loads per thread; the ragged end of a region is predicated rather than
+        // peeled into a one-load-at-a-time loop, so a region costs one round trip per batch, tail included
+        for (uint64_t base = me; base < n16; base += U * stride) {
+            uint4 v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const uint64_t idx = base + u * stride;
+                v[u] = idx < n16 ? p[idx] : zero16();
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) sink ^= fold(v[u]);
+        }
+    }
+    if (j.kv_count) {
+        // Work item = one (logical block, kv head): a K unit and a V unit (bf16: 4 KiB each; int8: 2112 bytes, codes
+        // + scales).  A wave takes up to NBW items per step and requests all of them before it looks at any
+        // result; with few items every wave takes one, so that a small cache is spread over many waves.
+        constexpr int NBW = 4;
+        const int lane = threadIdx.x & 63;
+        const uint64_t gw = (uint64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+        const uint64_t nw = (uint64_t)gridDim.x * 4;
+        const uint32_t unit16 = j.kv.int8 ? PSV_KV_UNIT_BYTES_INT8 / 16 : 256;   // 16-byte words per unit
+        const uint64_t items = j.kv_count * (uint64_t)j.nkv;
+        const int nbw = items >= nw * NBW ? NBW : 1;
+        for (uint64_t q0 = gw * nbw; q0 < items; q0 += nw * nbw) {
+            const uint4 *kp[NBW], *vp[NBW];
+#pragma unroll
+            for (int u = 0; u < NBW; ++u) {
+                kp[u] = vp[u] = nullptr;
+                const uint64_t q = q0 + u;
+                if (u < nbw && q < items) {
+                    const uint64_t lin = j.kv_first + q / j.nkv;
+                    const int kvh = (int)(q % j.nkv);
+                    const int b = (int)(lin / j.blocks_per_seq), lb = (int)(lin % j.blocks_per_seq);
+                    const int blk = lb < j.kv.max_blocks
+                                        ? kv_phys_block(j.kv.page_table, j.kv.max_blocks, j.kv.num_pool_blocks, b, lb) : -1;
+                    if (blk >= 0) {
+                        const size_t at = ((size_t)blk * j.nkv + kvh) * unit16;
+                        kp[u] = reinterpret_cast<const uint4 *>(j.kv.k_pool) + at;
+                        vp[u] = reinterpret_cast<const uint4 *>(j.kv.v_pool) + at;
+                    }
+                }
+            }
+            for (uint32_t o = lane; o < unit16; o += 192) {   // 3 words per pool: one step covers an int8 unit
+                const bool p1 = o + 64 < unit16, p2 = o + 128 < unit16;
+                uint4 v[NBW][6];
+#pragma unroll
+                for (int u = 0; u < NBW; ++u) {
+                    const bool ok = kp[u] != nullptr;
+                    v[u][0] = ok ? kp[u][o] : zero16();
+                    v[u][1] = ok && p1 ? kp[u][o + 64] : zero16();
+                    v[u][2] = ok && p2 ? kp[u][o + 128] : zero16();
+                    v[u][3] = ok ? vp[u][o] : zero16();
+                    v[u][4] = ok && p1 ? vp[u][o + 64] : zero16();
+                    v[u][5] = ok && p2 ? vp[u][o + 128] : zero16();
+                }
+#pragma unroll
+                for (int u = 0; u < NBW; ++u)
+                    sink ^= fold(v[u][0]) ^ fold(v[u][1]) ^ fold(v[u][2]) ^ fold(v[u][3]) ^ fold(v[u][4]) ^ fold(v[u][5]);
+            }
+        }
+    }
+    asm volatile("" ::"v"(sink));   // keeps the loads alive without a store
+}
+
+// Device-side fork.  One wave waits (bounded) until the main stream has entered the window whose
+// sequence number is `seq` (published by k_spin), then ends, which releases the prefetch launches queued
+// behind it on the side stream.  A single wave cannot keep any main-stream kernel off the CUs, whatever
+// that kernel's register or LDS footprint.  If a later window has already begun, the data would arrive
+// after its consumers ran: *skip = 1 tells the prefetch launches to do nothing.  Being early or late can
+// never change a result (prefetch only reads), so the bounds are just an exit guarantee.
+__global__ __launch_bounds__(64) void k_gate(const unsigned *flag, unsigned seq, uint32_t wait_iters, uint64_t wait_ticks,
+                                             unsigned *skip)
+{
+    if (threadIdx.x != 0) return;
+    const uint64_t t0 = wall_clock64();
+    unsigned v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    uint32_t it = 0;
+    while ((int)(v - seq) < 0 && it < wait_iters && wall_clock64() - t0 < wait_ticks) {
+        __builtin_amdgcn_s_sleep(2);
+        v = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ++it;
+    }
+    *skip = (int)(v - seq) > 0 ? 1u : 0u;
+}
+
+hipError_t launch_gate(const unsigned *flag, unsigned seq, uint32_t wait_iters, uint64_t wait_ticks, unsigned *skip,
+                       hipStream_t s)
+{
+    PSV_LAUNCH(k_gate, dim3(1), dim3(64), 0, s, flag, seq, wait_iters, wait_ticks, skip);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefetch_job(const PrefetchJob &j, uint32_t workgroups, hipStream_t s)
+{
+    if (workgroups == 0 || (j.n_regions == 0 && j.kv_count == 0)) return hipSuccess;
+    PSV_LAUNCH(k_prefetch, dim3(workgroups), dim3(256), 0, s, j);
+    return hipGetLastError();
+}
+
+hipError_t launch_prefetch(const void *ptr, uint64_t bytes, uint32_t workgroups, hipStream_t s)
+{
+    if (bytes < 16) return hipSuccess;
+    PrefetchJob j{};
+    j.n_regions = 1;
+    j.ptr[0] = ptr;
+    j.n16[0] = bytes / 16;
+    return launch_prefetch_job(j, workgroups, s);
+}
+
+// ------------------------------------------------------------------------------------ copy (counter calibration)
+
+__global__ __launch_bounds__(256) void k_copy(uint4 *__restrict__ dst, const uint4 *__restrict__ src, uint64_t n16)
+{
+    const uint64_t stride = (uint64_t)gridDim.x * 256;
+    for (uint64_t i = (uint64_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+hipError_t launch_copy(void *dst, const void *src, uint64_t bytes, hipStream_t s)
+{
+    if (bytes < 16) return hipSuccess;
+    uint64_t n16 = bytes / 16;
+    uint64_t blocks = (n16 + 255) / 256;
+    if (blocks > 4096) blocks = 4096;
+    PSV_LAUNCH(k_copy, dim3((unsigned)blocks), dim3(256), 0, s, reinterpret_cast<uint4 *>(dst),
+                       reinterpret_cast<const uint4 *>(src), n16);
+    return hipGetLastError();
+}
+
+}  // namespace psv
