@@ -1,0 +1,476 @@
+// Context, workspace and step executor of libpreserve_mi355x.
+//
+// Execution model (Section 3, "PRESERVE"): the decode step's operators run in order on the main
+// stream; beside each communication window an event forks the side stream, which runs the
+// prefetch kernels the plan assigned to that window while the main stream sits in the window
+// (here: a spin kernel standing in for the allreduce).  Prefetch kernels only read, so the main
+// stream never has to wait for them; the side stream itself serialises consecutive windows.
+#include <math.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <utility>
+#include <vector>
+
+#include "context.h"
+
+namespace psv {
+
+Workspace layout_workspace(const psv_model_desc &d)
+{
+    Workspace w;
+    const size_t B = d.max_batch, Bp = (B + 15) / 16 * 16, H = d.hidden, F = d.ffn;
+    const size_t QR = (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim, QD = (size_t)d.n_q_heads * d.head_dim;
+    const size_t G = d.n_q_heads / d.n_kv_heads;
+    // room for the finest attention split psv_tune_attention may choose, not only the default one
+    const size_t tile_unit = (size_t)(d.kv_format == PSV_FMT_INT8 ? kAttnTileTokensInt8 : kAttnTileTokens) * kAttnWaves;
+    AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq, d.kv_format == PSV_FMT_INT8);
+    {
+        size_t finest = (d.max_seq + tile_unit - 1) / tile_unit;
+        if (finest > (size_t)kAttnMaxChunks) finest = kAttnMaxChunks;
+        if ((size_t)sp.n_chunks < finest) sp.n_chunks = (int)finest;
+    }
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes); return o; };
+    w.x = take(B * H * 4);
+    w.y = take(B * H * 4);
+    w.h1_f32 = take(B * H * 4);
+    w.h1_bf16 = take(2 * Bp * H * 2);
+    w.h2_f32 = take(B * H * 4);
+    w.h2_bf16 = take(2 * Bp * H * 2);
+    w.qkv = take(B * QR * 4);
+    w.rope = take(B * 64 * 2 * 4);
+    w.part_ml = take(B * d.n_kv_heads * (size_t)sp.n_chunks * 16 * 2 * 4);
+    w.part_o = take(B * d.n_kv_heads * (size_t)sp.n_chunks * G * 128 * 4);
+    w.attn_f32 = take(B * QD * 4);
+    w.attn_bf16 = take(2 * Bp * QD * 2);
+    w.delta_a = take(B * H * 4);
+    w.delta_m = take(B * H * 4);
+    w.m_f32 = take(B * F * 4);
+    w.m_bf16 = take(2 * Bp * F * 2);
+    w.inv_freq = take(64 * sizeof(double));
+    w.flag = take(256);
+    w.ssq = take(B * (H / 512) * 4);
+    {   // split-K partials of the widest projection
+        size_t widest = QR > H ? QR : H;
+        if (2 * F > widest) widest = 2 * F;
+        w.part = take((size_t)kSkMaxSplits * B * widest * 4);
+    }
+    w.total = off;
+    return w;
+}
+
+void drop_graph(psv_ctx *c)
+{
+    if (c->graph_exec) {
+        (void)hipGraphExecDestroy(c->graph_exec);
+        c->graph_exec = nullptr;
+    }
+}
+
+void touch(psv_ctx *c)
+{
+    ++c->version;
+    drop_graph(c);
+}
+
+KvView kv_view(const psv_ctx *c, uint32_t layer)
+{
+    KvView v;
+    v.k_pool = static_cast<uint16_t *>(c->k_pools[layer]);
+    v.v_pool = static_cast<uint16_t *>(c->v_pools[layer]);
+    v.int8 = c->d.kv_format == PSV_FMT_INT8 ? 1 : 0;
+    v.page_table = c->kv.page_table;
+    v.max_blocks = (int)c->kv.max_blocks;
+    v.num_pool_blocks = (int)c->kv.num_pool_blocks;
+    v.seq_lens = c->kv.seq_lens;
+    return v;
+}
+
+// Attention split of this context: the default heuristic, or the chunk size chosen by psv_tune_attention.
+AttnSplit ctx_split(const psv_ctx *c)
+{
+    const psv_model_desc &d = c->d;
+    AttnSplit sp = attn_split(d.max_batch, d.n_kv_heads, d.max_seq, d.kv_format == PSV_FMT_INT8);
+    if (c->attn_chunk_tokens) {
+        sp.chunk_tokens = (int)c->attn_chunk_tokens;
+        sp.n_chunks = (int)((d.max_seq + c->attn_chunk_tokens - 1) / c->attn_chunk_tokens);
+    }
+    return sp;
+}
+
+uint64_t us_to_ticks(uint64_t clock_khz, float us) { return (uint64_t)llround((double)us * (double)clock_khz / 1000.0); }
+uint32_t spin_cap(float us) { return (uint32_t)(us * 4000.0f) + 100000u; }
+
+// Per-operator timing.  While profiling is on, every main-stream kernel carries an event bound to its own
+// dispatch (its end timestamp).  The duration of an operator's kernel is the distance between its event and
+// the event of the kernel launched just before it on the same stream, i.e. the kernel's execution time plus
+// the true dispatch gap -- no marker packets in between, which would add ~2 us each.
+psv_status prof_tag(psv_ctx *c, int32_t op)
+{
+    if (c->capturing || c->profile_op < 0) return PSV_OK;
+    if (c->prof_next == c->prof_events.size()) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreate(&e));
+        c->prof_events.push_back(e);
+    }
+    hipEvent_t ev = c->prof_events[c->prof_next++];
+    set_launch_events(nullptr, ev);
+    if (op == c->profile_op && c->prof_last) c->prof_pairs.push_back({c->prof_last, ev});
+    c->prof_last = ev;
+    return PSV_OK;
+}
+
+// Projection matrix `op` of a layer in the context's weight format.
+Mat mat_of(const psv_ctx *c, const psv_layer_weights &w, uint32_t op)
+{
+    const bool q8 = c->d.weight_format == PSV_FMT_INT8;
+    Mat m;
+    switch (op) {
+    case PSV_OP_QKV: m.w = w.w_qkv; m.scale = q8 ? w.s_qkv : nullptr; break;
+    case PSV_OP_O: m.w = w.w_o; m.scale = q8 ? w.s_o : nullptr; break;
+    case PSV_OP_GATE: m.w = w.w_gate; m.scale = q8 ? w.s_gate : nullptr; break;
+    case PSV_OP_UP: m.w = w.w_up; m.scale = q8 ? w.s_up : nullptr; break;
+    case PSV_OP_DOWN: m.w = w.w_down; m.scale = q8 ? w.s_down : nullptr; break;
+    default: break;
+    }
+    return m;
+}
+
+const void *weight_ptr(const psv_layer_weights &w, uint32_t op)
+{
+    switch (op) {
+    case PSV_OP_QKV: return w.w_qkv;
+    case PSV_OP_O: return w.w_o;
+    case PSV_OP_GATE: return w.w_gate;
+    case PSV_OP_UP: return w.w_up;
+    case PSV_OP_DOWN: return w.w_down;
+    default: return nullptr;
+    }
+}
+
+// Packs the plan entries of one window into prefetch launches: one launch per window, or several
+// when the policy caps the bytes per launch (chunk_bytes).
+struct JobBuilder {
+    psv_ctx *c;
+    uint64_t cap;        // bytes per launch (0 = unlimited)
+    const unsigned *skip;   // word written by the gate kernel of this window (null under graph capture)
+    hipStream_t stream;     // where the prefetch launches go
+    uint64_t used = 0;
+    PrefetchJob job{};
+    psv_status st = PSV_OK;
+
+    void flush()
+    {
+        if (st != PSV_OK) return;
+        if (job.n_regions || job.kv_count) {
+            const uint32_t wg = c->policy.cu_budget ? c->policy.cu_budget : 64u;
+            job.skip = skip;
+            if (launch_prefetch_job(job, wg, stream) != hipSuccess) st = PSV_ERR_HIP;
+            ++c->last_prefetch_launches;
+        }
+        job = PrefetchJob{};
+        used = 0;
+    }
+    void add_region(const char *p, uint64_t bytes)
+    {
+        bytes &= ~(uint64_t)15;
+        while (bytes && st == PSV_OK) {
+            uint64_t room = cap ? (cap > used ? cap - used : 0) : bytes;
+            room &= ~(uint64_t)15;
+            if (room == 0 || job.n_regions == kPrefetchRegions) { flush(); continue; }
+            const uint64_t n = bytes < room ? bytes : room;
+            job.ptr[job.n_regions] = p;
+            job.n16[job.n_regions] = n / 16;
+            ++job.n_regions;
+            used += n;
+            p += n;
+            bytes -= n;
+        }
+    }
+    void add_kv(const KvView &v, int nkv, uint32_t blocks_per_seq, uint64_t count, uint64_t bytes_per_block)
+    {
+        uint64_t first = 0;
+        while (count && st == PSV_OK) {
+            uint64_t room = cap ? (cap > used ? (cap - used) / bytes_per_block : 0) : count;
+            if (room == 0 && used == 0) room = 1;          // a launch always makes progress
+            if (room == 0 || job.kv_count) { flush(); continue; }
+            const uint64_t n = count < room ? count : room;
+            job.kv = v;
+            job.nkv = nkv;
+            job.blocks_per_seq = blocks_per_seq;
+            job.kv_first = first;
+            job.kv_count = n;
+            used += n * bytes_per_block;
+            first += n;
+            count -= n;
+        }
+    }
+};
+
+psv_status add_entry(psv_ctx *c, JobBuilder &jb, const psv_plan_entry &e, uint32_t batch)
+{
+    if (e.target_op == PSV_OP_ATTN) {
+        const uint32_t ro_tokens = c->plan_context > 0 ? c->plan_context - 1 : 0;
+        const uint32_t blocks_per_seq = (ro_tokens + PSV_BLOCK_TOKENS - 1) / PSV_BLOCK_TOKENS;
+        if (blocks_per_seq == 0) return PSV_OK;
+        const uint64_t unit = c->d.kv_format == PSV_FMT_INT8 ? PSV_KV_UNIT_BYTES_INT8 : PSV_KV_UNIT_BYTES_BF16;
+        const uint64_t bytes_per_block = (uint64_t)c->d.n_kv_heads * unit * 2;   // K and V
+        const uint64_t total = (uint64_t)batch * blocks_per_seq;
+        uint64_t count = (e.bytes + bytes_per_block - 1) / bytes_per_block;
+        if (count > total) count = total;
+        jb.add_kv(kv_view(c, e.target_layer), (int)c->d.n_kv_heads, blocks_per_seq, count, bytes_per_block);
+        return jb.st;
+    }
+    const char *p = static_cast<const char *>(weight_ptr(c->weights[e.target_layer], e.target_op));
+    if (!p) return PSV_ERR_BAD_STATE;
+    jb.add_region(p, e.bytes);
+    return jb.st;
+}
+
+// The two streams of a step.  Normally `cur` is the caller's main stream for the whole step; with the
+// `prelaunch` policy the operator chain hops to the other stream at every communication window.
+struct Lanes {
+    hipStream_t cur, other;
+};
+
+// The communication window after the attention block (window 0) or the MLP block (window 1).  The
+// stand-in for the collective is enqueued first, so that the stream never waits for the host; the window's
+// prefetch job goes to the other stream and starts when the window starts.
+//
+// prelaunch (policy extension, eager launches, vector path): the first consumer after the window -- gate/up
+// after window 0, the next layer's QKV after window 1 -- is the one operator whose weights are needed the moment
+// the window ends.  If Algorithm 1 planned a prefetch for it, that prefetch is done by the consumer itself: the
+// caller launches it on the other stream right behind the window's gate and its (remaining) prefetch job, with a
+// GemvWait on the window's end.  It pulls its first weights into registers while the window runs and finishes a
+// few microseconds after the window does.  The rest of the chain follows it on that stream, so the two streams
+// swap roles at every window and no host-side event is needed: every cross-stream dependency is one of the two
+// flags the window kernel publishes (start, end).  *wait_set tells the caller to launch the consumer that way.
+// Does the plan hand the whole weight matrix of the first consumer after (layer, window) to that window, so that
+// the consumer can be launched ahead of time (policy.prelaunch, eager launches, vector path)?
+bool can_prelaunch(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t layer_end, bool vec)
+{
+    if (c->capturing || !vec || c->policy.mode != 1 || !c->policy.prelaunch || !(c->window_us[window] > 0.f)) return false;
+    if (c->overlap != 1) return false;      // a waiting kernel may only be queued where it cannot block the window kernel
+    if (window == 1 && layer + 1 >= layer_end) return false;       // end of the graph: no consumer
+    const uint32_t first_op = window == 0 ? PSV_OP_GATE : PSV_OP_QKV;
+    for (const psv_plan_entry &e : c->plan)
+        if (e.layer == layer && e.window == window && e.target_op == first_op && e.bytes == e.mem_size) return true;
+    return false;
+}
+
+psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t batch, uint32_t layer_end, bool pre,
+                       Lanes *ln, GemvWait *wait, bool *wait_set, bool *side_used)
+{
+    *wait_set = false;
+    const float us = c->window_us[window];
+    if (!(us > 0.f)) return PSV_OK;
+    bool any = false;
+    if (c->policy.mode == 1)
+        for (const psv_plan_entry &e : c->plan)
+            if (e.layer == layer && e.window == window && e.target_layer < layer_end) { any = true; break; }
+    // Eager launches fork on the device: the window kernel publishes a sequence number that a one-wave gate
+    // kernel, queued on the other stream ahead of the prefetch launches, waits for.  Under graph capture the
+    // fork is an event edge.
+    unsigned *flag = c->capturing ? nullptr : c->at<unsigned>(c->ws.flag);
+    unsigned *done = flag ? flag + 32 : nullptr, *err = flag ? flag + 48 : nullptr;
+    const unsigned seq = ++c->window_seq;
+    const uint32_t first_op = window == 0 ? PSV_OP_GATE : PSV_OP_QKV;
+    hipEvent_t ev = c->ev_fork[layer * 2 + window];
+    if (any && !flag) HIP_TRY(hipEventRecord(ev, ln->cur));
+    ST_TRY(prof_tag(c, -2));
+    HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), flag, done, seq, ln->cur));
+    if (!any) return PSV_OK;
+    unsigned *skip = flag ? flag + 16 : nullptr;
+    if (flag)
+        // A gate that gives up only costs its window's prefetch -- unless a consumer is queued behind it: that
+        // one must not start (and then run out of patience itself) while the stream of the window is merely
+        // held up by earlier work of the caller, so its gate and its own wait are bounded by a second, not 20 ms.
+        HIP_TRY(launch_gate(flag, seq, pre ? 1u << 22 : 1u << 20, c->clock_khz * (pre ? 1000 : 20) /* 1 s : 20 ms */, skip,
+                            ln->other));
+    else
+        HIP_TRY(hipStreamWaitEvent(ln->other, ev, 0));
+    uint64_t cap = c->policy.chunk_bytes & ~(uint64_t)15;
+    if (c->policy.chunk_bytes && cap < 16) cap = 16;
+    JobBuilder jb{c, cap, skip, ln->other};
+    for (const psv_plan_entry &e : c->plan) {
+        if (e.layer != layer || e.window != window || e.target_layer >= layer_end) continue;
+        // what the pre-launched consumer reads itself needs no second copy in the memory-side cache
+        if (pre && (e.target_op == first_op || (window == 0 && e.target_op == PSV_OP_UP))) continue;
+        psv_status st = add_entry(c, jb, e, batch);
+        if (st != PSV_OK) return st;
+    }
+    jb.flush();
+    if (jb.st != PSV_OK) return jb.st;
+    *side_used = true;
+    if (pre) {
+        wait->done = done;
+        wait->seq = seq;
+        wait->iters = c->force_wait_timeout ? 0u : (1u << 22);
+        wait->ticks = c->force_wait_timeout ? 0ull : us_to_ticks(c->clock_khz, us) * 2 + c->clock_khz * 1000 /* + 1 s */;
+        wait->err = err;
+        *wait_set = true;
+        c->prelaunch_used = true;
+        std::swap(ln->cur, ln->other);     // the chain continues behind the consumer
+        return PSV_OK;
+    }
+    if (c->policy.join) {
+        HIP_TRY(hipEventRecord(c->ev_join[layer * 2 + window], ln->other));
+        HIP_TRY(hipStreamWaitEvent(ln->cur, c->ev_join[layer * 2 + window], 0));
+    }
+    return PSV_OK;
+}
+
+psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t batch, uint32_t lb, uint32_t le)
+{
+    const psv_model_desc &d = c->d;
+    const int B = (int)batch, H = (int)d.hidden, F = (int)d.ffn, nq = (int)d.n_q_heads, nkv = (int)d.n_kv_heads;
+    const int QR = (nq + 2 * nkv) * 128, QD = nq * 128;
+    const AttnSplit sp = ctx_split(c);
+    float *x = c->at<float>(c->ws.x), *y = c->at<float>(c->ws.y);
+    float *delta_a = c->at<float>(c->ws.delta_a), *delta_m = c->at<float>(c->ws.delta_m);
+    float *h1 = c->at<float>(c->ws.h1_f32), *h2 = c->at<float>(c->ws.h2_f32);
+    uint16_t *h1b = c->at<uint16_t>(c->ws.h1_bf16), *h2b = c->at<uint16_t>(c->ws.h2_bf16);
+    float *qkv = c->at<float>(c->ws.qkv), *attn = c->at<float>(c->ws.attn_f32), *m = c->at<float>(c->ws.m_f32);
+    uint16_t *attnb = c->at<uint16_t>(c->ws.attn_bf16), *mb = c->at<uint16_t>(c->ws.m_bf16);
+    float *pml = c->at<float>(c->ws.part_ml), *po = c->at<float>(c->ws.part_o);
+    float2 *rope = c->at<float2>(c->ws.rope);
+    const double *inv_freq = d.rope_theta > 0.f ? c->at<double>(c->ws.inv_freq) : nullptr;
+    Lanes ln{c->main, c->side};
+    hipStream_t &s = ln.cur;          // the stream the operator chain is on (changes at a pre-launching window)
+    GemvWait wait{};
+    bool wait_qkv = false, wait_gate = false;
+    bool side_used = false;
+    c->last_prefetch_launches = 0;
+    auto u16 = [](const void *p) { return static_cast<const uint16_t *>(p); };
+    const bool w8 = d.weight_format == PSV_FMT_INT8;
+    const size_t plane_h = (size_t)((B + 15) / 16 * 16) * H;   // hi -> lo plane distance of the bf16 activations
+
+    // Batch 1 (and batch 2 on 8B-sized matrices) runs every projection on the vector ALU with the normalisation
+    // fused into the prologue; larger batches use the matrix cores: split-K GEMMs whose partials are summed by the
+    // residual kernel (O, down) or a small reduction kernel (QKV; gate/up with SwiGLU), the RMSNorm factor being
+    // applied in the epilogue of the GEMM that follows the residual kernel.
+    // (Measured crossover: the vector path loses ~10 us per layer and extra batch row to register pressure.)
+    const bool vec = (B == 1 || (B == 2 && H <= 4096)) && gemv_supported(B, QR, H) && gemv_supported(B, H, QD) &&
+                     gemv_supported(B, F, H) && gemv_supported(B, H, F);
+    const bool sk = !vec;
+    c->last_step_vec = vec;
+    float *part = c->at<float>(c->ws.part), *ssq = c->at<float>(c->ws.ssq);
+
+    // The chain hops to the other stream at every pre-launching window and has to be back on the main stream when
+    // the step ends (the caller's own work on that stream follows it): with an odd number of such windows the last
+    // one runs without pre-launch.
+    int pre_left = 0;
+    for (uint32_t l = lb; l < le; ++l)
+        for (uint32_t wdw = 0; wdw < 2; ++wdw) pre_left += can_prelaunch(c, l, wdw, le, vec) ? 1 : 0;
+    if (pre_left & 1) --pre_left;
+    auto take_pre = [&](uint32_t l, uint32_t wdw) {
+        if (pre_left > 0 && can_prelaunch(c, l, wdw, le, vec)) { --pre_left; return true; }
+        return false;
+    };
+
+    ST_TRY(prof_tag(c, -2));
+    HIP_TRY(launch_rope_table(c->kv.seq_lens, inv_freq, (int)c->kv.max_blocks * 16, B, rope, s));
+    const float *res = x_in, *delta = nullptr;   // residual stream entering the layer = res + delta
+    int delta_splits = 1;                        // delta may be a stack of split-K partials
+    for (uint32_t l = lb; l < le; ++l) {
+        const psv_layer_weights &w = c->weights[l];
+        const KvView kv = kv_view(c, l);
+        const Mat Wqkv = mat_of(c, w, PSV_OP_QKV), Wo = mat_of(c, w, PSV_OP_O), Wg = mat_of(c, w, PSV_OP_GATE),
+                  Wu = mat_of(c, w, PSV_OP_UP), Wd = mat_of(c, w, PSV_OP_DOWN);
+
+        if (sk) {
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x, u16(w.g_attn), h1b, plane_h, w8, ssq, s));
+        }
+        ST_TRY(prof_tag(c, PSV_OP_QKV));
+        if (vec) {
+            HIP_TRY(launch_gemv_norm(Wqkv, Mat{}, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H,
+                                     wait_qkv ? &wait : nullptr, s));
+            wait_qkv = false;
+        } else {
+            if (!gemm_sk_supported(B, QR, H)) return PSV_ERR_UNSUPPORTED;
+            HIP_TRY(launch_gemm_sk(Wqkv, Mat{}, 0, h1b, ssq, d.rms_eps, part, B, QR, H, s));
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H, w8), B, QR, false, qkv, nullptr, false, s));
+        }
+
+        ST_TRY(prof_tag(c, PSV_OP_ATTN));
+        HIP_TRY(launch_attn(qkv, rope, kv, B, nq, nkv, sp, pml, po, s));
+        const bool fuse_merge = vec && gemv_merge_supported(B, nq, sp.n_chunks);
+        if (!fuse_merge) {
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_attn_merge(pml, po, B, nq, nkv, sp, attn, attnb, sk && w8, s));
+        }
+
+        ST_TRY(prof_tag(c, PSV_OP_O));
+        const float *attn_delta = delta_a;
+        int attn_splits = 1;
+        if (fuse_merge) {
+            HIP_TRY(launch_gemv_merge(Wo, pml, po, nq, nkv, sp.n_chunks, attn, delta_a, B, H, s));
+        } else if (vec) {
+            HIP_TRY(launch_gemv(Wo, Mat{}, attn, delta_a, B, H, QD, s));
+        } else {
+            if (!gemm_sk_supported(B, H, QD)) return PSV_ERR_UNSUPPORTED;
+            HIP_TRY(launch_gemm_sk(Wo, Mat{}, 0, attnb, nullptr, 0.f, part, B, H, QD, s));
+            attn_delta = part;
+            attn_splits = gemm_sk_splits(B, H, QD, w8);
+        }
+
+        ST_TRY(comm_window(c, l, 0, batch, le, take_pre(l, 0), &ln, &wait, &wait_gate, &side_used));
+
+        if (sk) {
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_resid_sum(x, attn_delta, attn_splits, B, H, y, u16(w.g_mlp), h2b, plane_h, w8, ssq, s));
+        }
+        ST_TRY(prof_tag(c, PSV_OP_GATE));
+        if (vec) {
+            HIP_TRY(launch_gemv_norm(Wg, Wu, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H,
+                                     wait_gate ? &wait : nullptr, s));
+            wait_gate = false;
+        } else {
+            if (!gemm_sk_supported(B, 2 * F, H)) return PSV_ERR_UNSUPPORTED;
+            HIP_TRY(launch_gemm_sk(Wg, Wu, F, h2b, ssq, d.rms_eps, part, B, 2 * F, H, s));
+            ST_TRY(prof_tag(c, -2));
+            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H, w8), B, 2 * F, true, m, mb, w8, s));
+        }
+
+        ST_TRY(prof_tag(c, PSV_OP_DOWN));
+        delta = delta_m;
+        delta_splits = 1;
+        if (vec) {
+            HIP_TRY(launch_gemv(Wd, Mat{}, m, delta_m, B, H, F, s));
+        } else {
+            if (!gemm_sk_supported(B, H, F)) return PSV_ERR_UNSUPPORTED;
+            HIP_TRY(launch_gemm_sk(Wd, Mat{}, 0, mb, nullptr, 0.f, part, B, H, F, s));
+            delta = part;
+            delta_splits = gemm_sk_splits(B, H, F, w8);
+        }
+
+        ST_TRY(comm_window(c, l, 1, batch, le, take_pre(l, 1), &ln, &wait, &wait_qkv, &side_used));
+        res = y;
+    }
+    ST_TRY(prof_tag(c, -2));
+    HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x_out, nullptr, nullptr, 0, false, nullptr, s));
+    if (ln.cur != c->main) {           // cannot happen with the pairing above; kept as a safety net
+        HIP_TRY(hipEventRecord(c->ev_end, ln.cur));
+        HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));
+    }
+    if (side_used && c->capturing) {   // a captured side branch has to rejoin the origin stream
+        HIP_TRY(hipEventRecord(c->ev_end, c->side));
+        HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));
+    }
+    return PSV_OK;
+}
+
+psv_status rebuild_plan(psv_ctx *c)
+{
+    c->plan.clear();
+    if (c->plan_batch == 0) return PSV_OK;
+    size_t n = plan_chain(c->d, c->plan_batch, c->plan_context, c->policy, nullptr, 0);
+    c->plan.resize(n);
+    if (n) plan_chain(c->d, c->plan_batch, c->plan_context, c->policy, c->plan.data(), n);
+    return PSV_OK;
+}
+
+}  // namespace psv

@@ -1,4 +1,4 @@
-// Internal interface between the host side of libpreserve_mi355x (api.cpp, planner.cpp) and
+// Internal interface between the host side of libpreserve_mi355x (api.cpp, executor.cpp, planner.cpp) and
 // its gfx950 kernels (gemv.hip, gemm_sk.hip, attention.hip, window.hip).  Launch wrappers take plain
 // pointers and sizes, validate nothing (the API layer has already done so) and return the hipError_t
 // of the launch.
