@@ -81,3 +81,26 @@ def test_prelaunch_takes_the_first_consumers_out_of_the_post_window_path():
     big = model.op_bytes(8192, 16, 2, 7168, 1, 4096)
     t_pre = model.layer_time(big, (20.0, 20.0), m, 256e6, prelaunch=True)
     assert t_pre > 40.0 + (big["gate"] + big["up"] - m.reg_bytes) / m.bw_hbm
+
+
+def test_default_policy_is_the_bench_configuration():
+    """bench.py, the full-size parity tests and smoke() share one default policy: C = min(192 MiB, window x 4.5 MiB/us),
+    256 prefetch workgroups, partial only for paged workloads, consumers launched into their windows."""
+    from paper_2501_08192_amd.harness import default_policy
+    c2, c4, c5 = synth.WORKLOADS["c2"], synth.WORKLOADS["c4"], synth.WORKLOADS["c5"]
+    p = default_policy(c2)
+    assert (p.mode, p.cu_budget, p.partial, p.prelaunch, p.join) == (1, 256, 0, 1, 0)
+    assert p.budget_bytes == int(67.5 * (1 << 20))
+    assert default_policy(c4).partial == 1 and default_policy(c4).budget_bytes == int(112.5 * (1 << 20))
+    assert default_policy(c5).budget_bytes == 90 << 20
+    assert default_policy(c2, prelaunch=0, budget_bytes=123).budget_bytes == 123
+    assert default_policy(c2.scaled(window_us=(100.0, 1.0))).budget_bytes == 192 << 20      # capped at the cache
+
+
+def test_sweep_driver_parses_its_command_line():
+    from paper_2501_08192_amd import sweeps
+    assert set(sweeps.SHAPES) == {"tp4", "tp8"}
+    with pytest.raises(SystemExit):
+        sweeps.main(["map", "tp16"])                      # unknown shape
+    with pytest.raises(SystemExit):
+        sweeps.main(["sweep", "c9"])                      # unknown workload
