@@ -102,7 +102,9 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
     const int s0 = blockIdx.y * a.slabs_per_block, s1 = min(s0 + a.slabs_per_block, a.n_slabs);
     const int K = a.K;
 
-    // Lane (i, g) owns elements g*16 .. g*16+15 of row i of every 64-element slab: 32 contiguous bytes = two fragments.
+    // Lane (i, g) owns elements g*8 .. g*8+7 of both 32-element halves of row i of every 64-element slab (the matrix
+    // cores' own operand order): each of its two load instructions covers 64 contiguous bytes of every row, whole
+    // 32-byte sectors, instead of 16 bytes out of every 32.
     const uint16_t *wp[2];
     bool wok[2];
 #pragma unroll
@@ -110,21 +112,21 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
         const int r = row_base + mt * 16 + i;
         wok[mt] = r < a.N;
         const int rr = wok[mt] ? r : 0;
-        wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 16;
+        wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 8;
     }
     struct WFrag { uint4 a0[2], a1[2]; };
     auto load_w = [&](int s, WFrag &f) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
             f.a0[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64) : zero16();
-            f.a1[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64 + 8) : zero16();
+            f.a1[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64 + 32) : zero16();
         }
     };
     auto load_w_all = [&](int s, WFrag &f) {   // unpredicated: a row past N reads row 0 (wp) and is never stored
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
             f.a0[mt] = ld16(wp[mt] + (size_t)s * 64);
-            f.a1[mt] = ld16(wp[mt] + (size_t)s * 64 + 8);
+            f.a1[mt] = ld16(wp[mt] + (size_t)s * 64 + 32);
         }
     };
     // activation slab: NB*256 16-byte units, unit u = ((tile*2 + plane)*16 + row)*8 + segment
@@ -139,7 +141,7 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
 #pragma unroll
         for (int j = 0; j < NB; ++j) {
             const int u = tid + j * 256, n = u >> 8, p = (u >> 7) & 1, row = (u >> 3) & 15, seg = u & 7;
-            xs[buf][(n * 2 + p) * 2 + (seg & 1)][(seg >> 1) * 16 + row] = r[j];   // fragment order: k = g*16 + half*8 + e
+            xs[buf][(n * 2 + p) * 2 + (seg >> 2)][(seg & 3) * 16 + row] = r[j];   // fragment order: k = half*32 + g*8 + e
         }
     };
 
