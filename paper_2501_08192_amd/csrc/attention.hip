@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     const KvView &kv = a.kv;
     const int qkv_rows = (nq + 2 * nkv) * 128;
     int T = kv.seq_lens[b];
-    if (T < 0 || T > kv.max_blocks * 16) T = 0;
+    if (T < 0 || T > kv.max_tokens) T = 0;      // a length outside the descriptor's range is treated as an empty sequence
     const int t_begin = c * a.chunk_tokens;
     const int t_end = min(T, t_begin + a.chunk_tokens);
     const float *qkv_b = a.qkv + (size_t)b * qkv_rows;
@@ -172,26 +172,29 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     if (early) load_blocks(blkA0, blkB0);
 
     // ---- Q fragments, rotated: lane (g = i, q4) holds channels ks*32 + q4*8 + e; channel f < 64
-    //      pairs with f + 64, i.e. fragment ks with fragment ks + 2 of the same lane.
-    bf16x8 qf[4];
+    //      pairs with f + 64, i.e. fragment ks with fragment ks + 2 of the same lane.  The rotated query is carried
+    //      as two bf16 fragments, q = hi + lo: a single bf16 query (2^-9 relative) puts a 2e-3 relative error on the
+    //      attention output, which wide models amplify past the tolerance in the MLP block that follows.
+    bf16x8 qf[4], qfl[4];
     {
         uint4 z = zero16();
         qf[0] = qf[1] = qf[2] = qf[3] = __builtin_bit_cast(bf16x8, z);
+        qfl[0] = qfl[1] = qfl[2] = qfl[3] = __builtin_bit_cast(bf16x8, z);
         if (i < G) {
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks) {
                 const float *lo = qlo[ks], *hi = qhi[ks];
-                float rl[8], rh[8];
+                uint32_t lh[4], ll[4], hh[4], hl[4];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    const float2 cs = qcs[ks][e];
-                    rl[e] = lo[e] * cs.x - hi[e] * cs.y;
-                    rh[e] = hi[e] * cs.x + lo[e] * cs.y;
+                for (int e = 0; e < 8; e += 2) {
+                    const float2 c0 = qcs[ks][e], c1 = qcs[ks][e + 1];
+                    pack_split(lo[e] * c0.x - hi[e] * c0.y, lo[e + 1] * c1.x - hi[e + 1] * c1.y, lh[e >> 1], ll[e >> 1]);
+                    pack_split(hi[e] * c0.x + lo[e] * c0.y, hi[e + 1] * c1.x + lo[e + 1] * c1.y, hh[e >> 1], hl[e >> 1]);
                 }
-                uint4 pl = make_uint4(pack_bf16(rl[0], rl[1]), pack_bf16(rl[2], rl[3]), pack_bf16(rl[4], rl[5]), pack_bf16(rl[6], rl[7]));
-                uint4 ph = make_uint4(pack_bf16(rh[0], rh[1]), pack_bf16(rh[2], rh[3]), pack_bf16(rh[4], rh[5]), pack_bf16(rh[6], rh[7]));
-                qf[ks] = __builtin_bit_cast(bf16x8, pl);
-                qf[ks + 2] = __builtin_bit_cast(bf16x8, ph);
+                qf[ks] = __builtin_bit_cast(bf16x8, make_uint4(lh[0], lh[1], lh[2], lh[3]));
+                qfl[ks] = __builtin_bit_cast(bf16x8, make_uint4(ll[0], ll[1], ll[2], ll[3]));
+                qf[ks + 2] = __builtin_bit_cast(bf16x8, make_uint4(hh[0], hh[1], hh[2], hh[3]));
+                qfl[ks + 2] = __builtin_bit_cast(bf16x8, make_uint4(hl[0], hl[1], hl[2], hl[3]));
             }
         }
     }
@@ -232,6 +235,8 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         f32x4 s1 = {0.f, 0.f, 0.f, 0.f}, s2 = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
+            s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[ks]), qfl[ks], s1, 0, 0, 0);
+            s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[ks]), qfl[ks], s2, 0, 0, 0);
             s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, ka[ks]), qf[ks], s1, 0, 0, 0);
             s2 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kb[ks]), qf[ks], s2, 0, 0, 0);
         }
@@ -261,7 +266,12 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 #pragma unroll
         for (int dg = 0; dg < 8; ++dg) acc[dg] *= alpha;
 
-        uint4 pk = make_uint4(pack_bf16(p[0], p[1]), pack_bf16(p[2], p[3]), pack_bf16(p[4], p[5]), pack_bf16(p[6], p[7]));
+        // probabilities as two bf16 fragments as well (p = hi + lo)
+        uint4 pk, pkl;
+        pack_split(p[0], p[1], pk.x, pkl.x);
+        pack_split(p[2], p[3], pk.y, pkl.y);
+        pack_split(p[4], p[5], pk.z, pkl.z);
+        pack_split(p[6], p[7], pk.w, pkl.w);
         if (t0 + kAttnTileTokens > t_end) {
             // ragged tail: cache slots past the span may hold anything (even NaN); blank them so
             // that 0 * garbage cannot reach the accumulators.
@@ -277,10 +287,12 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                 vf[dg].x &= mlo[0]; vf[dg].y &= mlo[1]; vf[dg].z &= mlo[2]; vf[dg].w &= mlo[3];
             }
         }
-        const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pk);
+        const bf16x8 pfrag = __builtin_bit_cast(bf16x8, pk), pfrag_lo = __builtin_bit_cast(bf16x8, pkl);
 #pragma unroll
-        for (int dg = 0; dg < 8; ++dg)
+        for (int dg = 0; dg < 8; ++dg) {
+            acc[dg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dg]), pfrag_lo, acc[dg], 0, 0, 0);
             acc[dg] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf[dg]), pfrag, acc[dg], 0, 0, 0);
+        }
     }
 
     // ---- merge the 4 waves (wave order)
@@ -343,7 +355,7 @@ __global__ __launch_bounds__(256) void k_attn_q8(AttnArgs a)
     const KvView &kv = a.kv;
     const int qkv_rows = (nq + 2 * nkv) * 128;
     int T = kv.seq_lens[b];
-    if (T < 0 || T > kv.max_blocks * 16) T = 0;
+    if (T < 0 || T > kv.max_tokens) T = 0;      // a length outside the descriptor's range is treated as an empty sequence
     const int t_begin = c * a.chunk_tokens;
     const int t_end = min(T, t_begin + a.chunk_tokens);
     const float *qkv_b = a.qkv + (size_t)b * qkv_rows;

@@ -82,6 +82,16 @@ __device__ __forceinline__ float wave_sum(float v)
     return (r0 + r1) + (r2 + r3);
 }
 
+// Two values as a pair of packed bf16 words: hi = their bf16 roundings, lo = the bf16 roundings of what is left.
+__device__ __forceinline__ void pack_split(float a, float b, uint32_t &hi, uint32_t &lo)
+{
+    uint32_t ah, al, bh, bl;
+    split_bf16(a, ah, al);
+    split_bf16(b, bh, bl);
+    hi = ah | (bh << 16);
+    lo = al | (bl << 16);
+}
+
 // low bytes of four floats that hold small integers in "magic number" form (x + 1.5 * 2^23)
 __device__ __forceinline__ uint32_t pack_magic_bytes(float a0, float a1, float a2, float a3)
 {

@@ -82,6 +82,10 @@ KvView kv_view(const psv_ctx *c, uint32_t layer)
     v.int8 = c->d.kv_format == PSV_FMT_INT8 ? 1 : 0;
     v.page_table = c->kv.page_table;
     v.max_blocks = (int)c->kv.max_blocks;
+    {
+        const uint64_t cap = (uint64_t)c->kv.max_blocks * PSV_BLOCK_TOKENS;
+        v.max_tokens = (int)(cap < c->d.max_seq ? cap : c->d.max_seq);
+    }
     v.num_pool_blocks = (int)c->kv.num_pool_blocks;
     v.seq_lens = c->kv.seq_lens;
     return v;
@@ -370,7 +374,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     };
 
     ST_TRY(prof_tag(c, -2));
-    HIP_TRY(launch_rope_table(c->kv.seq_lens, inv_freq, (int)c->kv.max_blocks * 16, B, rope, s));
+    HIP_TRY(launch_rope_table(c->kv.seq_lens, inv_freq, kv_view(c, lb).max_tokens, B, rope, s));
     const float *res = x_in, *delta = nullptr;   // residual stream entering the layer = res + delta
     int delta_splits = 1;                        // delta may be a stack of split-K partials
     for (uint32_t l = lb; l < le; ++l) {

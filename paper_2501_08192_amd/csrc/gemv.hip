@@ -183,10 +183,10 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
     // ---- launched ahead of its inputs: the weights above travel (and then sit in registers) while the
     //      communication window is still running; one wave of the workgroup polls for the window's end
     if (WAIT) {
-        __shared__ unsigned wait_ok;
         if (wave == 0) {
             const uint64_t t0 = wall_clock64();
-            // relaxed polls (an acquire per poll would invalidate caches every time); one acquire fence follows
+            // relaxed polls (an acquire per poll would invalidate caches every time); no fence follows either: what
+            // the kernel reads after the wait is fetched with device-coherent loads (ldc_issue)
             unsigned v = __hip_atomic_load(a.wait_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             uint32_t it = 0;
             while ((int)(v - a.wait_seq) < 0 && it < a.wait_iters && wall_clock64() - t0 < a.wait_ticks) {
@@ -194,10 +194,7 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
                 v = __hip_atomic_load(a.wait_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 ++it;
             }
-            if (lane == 0) {
-                wait_ok = (int)(v - a.wait_seq) >= 0 ? 1u : 0u;
-                if (!wait_ok) atomicOr(a.wait_err, 1u);
-            }
+            if (lane == 0 && (int)(v - a.wait_seq) < 0) atomicOr(a.wait_err, 1u);
         }
         __syncthreads();
         // The activations read below may have been written while this kernel was already running (by the

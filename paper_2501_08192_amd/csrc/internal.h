@@ -33,6 +33,8 @@ struct KvView {
     int int8;
     const int32_t *page_table;   // null => contiguous
     int max_blocks;
+    int max_tokens;              // longest valid sequence: min(max_blocks * 16, the descriptor's max_seq); the
+                                 //   attention grid and its partial buffers are sized for it
     int num_pool_blocks;
     const int32_t *seq_lens;
 };

@@ -22,7 +22,7 @@ class Session:
     layers: which layers to materialise (default all); others cannot be run.
     """
 
-    def __init__(self, w: synth.Workload, seed=2501, device="cuda:0", layers=None, pool_slack_blocks=0):
+    def __init__(self, w: synth.Workload, seed=2501, device="cuda:0", layers=None, pool_slack_blocks=0, max_seq=None):
         if not torch.cuda.is_available():
             raise RuntimeError("the PRESERVE decode path needs a GPU; there is no CPU fallback")
         self.w = w
@@ -30,7 +30,8 @@ class Session:
         self.device = torch.device(device)
         torch.cuda.set_device(self.device)
         self.layers = list(range(w.n_layers)) if layers is None else list(layers)
-        self.max_seq = (w.context + 15) // 16 * 16
+        # longest sequence the context is created for; the cache itself always has room for w.context tokens
+        self.max_seq = (w.context + 15) // 16 * 16 if max_seq is None else int(max_seq)
         self.desc = psv.model_desc(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch, self.max_seq,
                                    head_dim=w.head_dim, rms_eps=w.rms_eps, rope_theta=w.rope_theta,
                                    weight_format=w.weight_format, kv_format=w.kv_format)
@@ -71,7 +72,7 @@ class Session:
 
     def set_policy(self, policy):
         self.policy = policy
-        psv.psv_set_policy(self.ctx, policy, self.w.batch, self.w.context)
+        psv.psv_set_policy(self.ctx, policy, self.w.batch, min(self.w.context, self.max_seq))
 
     def set_windows(self, us0, us1):
         psv.psv_set_comm_windows(self.ctx, float(us0), float(us1))

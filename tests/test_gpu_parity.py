@@ -341,6 +341,26 @@ def test_prelaunched_consumers_outwait_earlier_work_on_the_main_stream():
         assert torch.equal(s.x_out, base)
 
 
+def test_length_beyond_the_descriptors_max_seq_is_an_empty_sequence():
+    """The cache has room for 208 tokens per sequence, the context was created for at most 64: a length in between
+    is outside what the attention grid covers and must be treated like any other invalid length (nothing appended,
+    empty attention span), not half-processed."""
+    w = W("gap", 1, 512, 4, 2, 256, 2, 200)
+    with Session(w, seed=23, max_seq=64) as s:
+        s.set_policy(psv.prefetch_policy(mode=0))
+        k0, v0 = s.k_pools[0].clone(), s.v_pools[0].clone()
+        s.seq_lens.copy_(torch.tensor([100, 0], dtype=torch.int32))
+        a = s.run().clone()
+        assert torch.isfinite(a).all()
+        assert torch.equal(s.k_pools[0], k0) and torch.equal(s.v_pools[0], v0)
+        s.seq_lens.copy_(torch.tensor([0, 0], dtype=torch.int32))
+        assert torch.equal(s.run(), a)
+        # lengths inside the range still work on the same context
+        s.seq_lens.copy_(torch.tensor([64, 33], dtype=torch.int32))
+        s.run()
+        assert not torch.equal(s.k_pools[0], k0)
+
+
 def test_layer_ranges_chain_like_the_whole_step():
     w = W("range", 3, 512, 4, 2, 256, 2, 90)
     with Session(w, seed=22) as s:
