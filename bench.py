@@ -39,8 +39,6 @@ def parse():
                     help="1 = the first operator after a window is launched at the window's start and holds its weights in "
                          "registers until the window ends (policy extension; batch 1-2 only)")
     ap.add_argument("--targets", type=int, default=3)
-    ap.add_argument("--graph", type=int, default=0,
-                    help="1 = replay the step as a HIP graph (the library refuses unless PSV_ENABLE_HIP_GRAPHS=1 is set)")
     ap.add_argument("--window-us", type=float, nargs=2, default=None)
     ap.add_argument("--tune", type=int, default=0,
                     help="1 = let the library time its candidate attention splits on layer 0 first (psv_tune_attention); "
@@ -76,7 +74,6 @@ def time_steps(sess, steps, warmup):
 def profile_op(sess, op, steps):
     """Average duration (us) of one operator's kernel, bracketed by HIP events on the main stream."""
     from paper_2501_08192_amd import binding as psv
-    psv.psv_set_graph_mode(sess.ctx, False)
     psv.psv_set_profile_op(sess.ctx, op)
     for _ in range(steps):
         sess.step()
@@ -157,7 +154,6 @@ def main():
     attn_chunk = sess.tune_attention() if a.tune else 0
 
     # prefetch off (vanilla execution) and on, same launch configuration otherwise
-    psv.psv_set_graph_mode(sess.ctx, bool(a.graph))
     sess.set_policy(off)
     x_off = sess.run().clone()
     ms_off = time_steps(sess, a.steps, a.warmup)
@@ -224,7 +220,7 @@ def main():
                                "windows %g/%g us" % (w.name, L, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch,
                                                       w.context, "paged" if w.paged else "contiguous", *w.window_us),
                    "prefetch_budget_mb": a.budget_mb, "cu_budget": a.cu_budget, "chunk_mb": a.chunk_mb,
-                   "partial": a.partial, "join": a.join, "prelaunch": a.prelaunch, "targets": a.targets, "hip_graph": bool(a.graph),
+                   "partial": a.partial, "join": a.join, "prelaunch": a.prelaunch, "targets": a.targets,
                    "streams_overlap": bool(sess.overlap),
                    "attn_tokens_per_workgroup": attn_chunk if a.tune else "default"},
         "us_per_layer_prefetch_off": round(us_off, 3),

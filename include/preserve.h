@@ -63,7 +63,9 @@ enum {
     PSV_ERR_BAD_STATE = -2,     /* e.g. decode step before weights / KV were set */
     PSV_ERR_UNSUPPORTED = -3,   /* shape outside what the kernels are built for */
     PSV_ERR_HIP = -4,           /* a HIP runtime call failed (also: no GPU present) */
-    PSV_ERR_NOMEM = -5          /* host or device allocation failed */
+    PSV_ERR_NOMEM = -5,         /* host or device allocation failed */
+    PSV_ERR_TIMEOUT = -6        /* a kernel launched ahead of its communication window (policy.prelaunch) gave up its
+                                   bounded wait for the window's end; reported once, by psv_sync */
 };
 
 typedef struct psv_ctx psv_ctx;   /* opaque */
@@ -131,8 +133,8 @@ typedef struct {
                                 operator chain continues on that stream, so the two streams swap roles at
                                 every window.  Takes effect for eager launches at batch 1 (and batch 2 up
                                 to H = 4096), and only on a context whose two streams run concurrently
-                                (psv_check_overlap; psv_set_policy runs that check itself if it has not
-                                been run): a kernel that waits on a flag must never sit in front of the
+                                -- i.e. after psv_check_overlap (preserve_aux.h) has been called on the
+                                context and answered 1: a kernel that waits on a flag must never sit in front of the
                                 kernel that sets it -- under a profiler that serialises kernels, or on two
                                 streams that share a hardware queue, it would wait until its time limit.
                                 Otherwise ignored.  Results are bit-identical either way. */
@@ -194,116 +196,60 @@ psv_status psv_plan_chain(const psv_model_desc *desc, uint32_t batch, uint32_t c
 
 /* ---- context ---------------------------------------------------------------------------- */
 
-/* Creates a context on the current HIP device.  stream_main / stream_side are hipStream_t
- * handles owned by the caller; they must differ and have default priority.  Allocates the
- * workspace.  *out is set only on success. */
+/* Creates a context on the current HIP device.  The two streams are Section 3's ("PRESERVE") execution
+ * model: the operators of the step run in order on stream_main, the prefetch operators that Algorithm 1
+ * inserted run on stream_side beside the communication operator they were attached to.  Both are hipStream_t
+ * handles owned by the caller; they must differ and have default priority.  Allocates the workspace
+ * (psv_workspace_bytes) with hipMalloc.  *out is set only on success. */
 psv_status psv_create(const psv_model_desc *desc, void *stream_main, void *stream_side,
                       psv_ctx **out);
+/* Frees the context and its workspace.  The caller synchronises first (psv_sync). */
 psv_status psv_destroy(psv_ctx *ctx);
 
+/* The operands of one layer's five MatMul nodes (Section 2, "LLM inference workloads": QKV, output, and the
+ * three MLP projections) and its two norm gains; they are also what a prefetch operator of class "weights"
+ * reads.  Borrowed until replaced or psv_destroy; pointers must be 16-byte aligned. */
 psv_status psv_set_layer_weights(psv_ctx *ctx, uint32_t layer, const psv_layer_weights *w);
+/* The KV-cache every SelfAttention node reads and appends to (Section 3, "Execution with the proposed method":
+ * all of it except the newest entry is known before the step and can be prefetched).  The host arrays of pool
+ * pointers are copied; pools, page table and seq_lens are borrowed.  max_blocks * 16 >= the descriptor's
+ * max_seq; without a page table num_pool_blocks >= max_batch * max_blocks. */
 psv_status psv_set_kv(psv_ctx *ctx, const psv_kv_desc *kv);
 
-/* Durations of the two communication windows of every layer, microseconds (>= 0).  A window
- * of 0 launches neither the spin kernel nor any prefetch. */
+/* Durations of the two communication operators of every layer (Section 2, "Multi-device inference": one
+ * allreduce after the attention block, one after the MLP block), microseconds (0 <= us <= 1e6); each is
+ * executed as a spin kernel of that length standing in for the collective.  A window of 0 launches neither
+ * the spin kernel nor any prefetch. */
 psv_status psv_set_comm_windows(psv_ctx *ctx, float us_after_attn, float us_after_mlp);
 
-/* Stores the policy and rebuilds the plan for (batch, context): Algorithm 1 needs the KV size,
- * which depends on them.  context is the attention span used for memSize(). */
+/* Stores the policy and runs Algorithm 1 (Section 3, "Operator insertion") for (batch, context): its inputs
+ * are the operator graph, fixed by the descriptor, the capacity C = policy->budget_bytes, and memSize() of
+ * every node, which for SelfAttention depends on batch and on context, the attention span.  Pure host work:
+ * nothing is launched. */
 psv_status psv_set_policy(psv_ctx *ctx, const psv_prefetch_policy *policy, uint32_t batch,
                           uint32_t context);
 
 /* Copies the current plan (see psv_plan_chain) to host memory. */
 psv_status psv_plan(psv_ctx *ctx, psv_plan_entry *out, size_t cap, size_t *n);
 
-/* 0 = launch kernels one by one on the two streams; 1 = capture the step into a HIP graph on
- * first use (keyed by the argument tuple of psv_decode_step) and replay it afterwards.
- * Graph mode is switched off by default: 1 is answered with PSV_ERR_UNSUPPORTED unless the environment
- * variable PSV_ENABLE_HIP_GRAPHS is "1".  Test runs that went through many capture / replay / destroy
- * cycles ended, rarely, in an abort inside the HIP runtime; until that is understood the eager path (which
- * is also the faster one on this runtime) is the only one enabled. */
-psv_status psv_set_graph_mode(psv_ctx *ctx, uint32_t use_graph);
-
 /*
  * One decode step over layers [layer_begin, layer_end): Section 3's execution with (policy
  * mode 1) or without (mode 0) prefetching.  x_in, x_out: dev fp32 [batch, H] (may alias).
  * Asynchronous: returns after enqueueing on stream_main / stream_side.  Mutates only x_out,
  * slot seq_lens[b]-1 of each layer's K and V pools, and the workspace.  The results are bit
- * identical for every policy, window and graph mode.
+ * identical for every policy and window.
  */
 psv_status psv_decode_step(psv_ctx *ctx, const float *x_in, float *x_out, uint32_t batch,
                            uint32_t layer_begin, uint32_t layer_end);
 
-/* Waits for both streams; returns PSV_ERR_HIP if any enqueued work failed (including a pre-launched kernel
- * whose bounded wait for its window expired). */
+/* Waits for both streams (the event synchronisation between the two streams of Section 3, "PRESERVE", seen
+ * from the host).  PSV_ERR_HIP if any enqueued work failed; PSV_ERR_TIMEOUT, once, if a kernel launched ahead
+ * of its window gave up waiting for the window's end (it still finished; the context stays usable). */
 psv_status psv_sync(psv_ctx *ctx);
 
+/* Algorithmic bytes of the step as Section 2 ("LLM decoding is memory BW-limited") counts them -- every weight
+ * once, K and V of the attended span once -- and what the current plan prefetches. */
 psv_status psv_get_stats(psv_ctx *ctx, psv_stats *out);
-
-/* Chooses how many tokens of a sequence one attention workgroup covers (the split of the span over
- * workgroups).  The default comes from a heuristic on (max_batch, kv heads, max_seq); which split is fastest
- * depends on the shape in ways a heuristic captures only roughly (measured spread over the candidates: 10 %;
- * the default lands within 1-2 % of the best on the shapes it was centred on), so this call times
- * psv_decode_step(ctx, x_in, x_out, batch, 0, 1) -- layer 0 only, prefetching off, no windows -- for a list of
- * candidate splits and keeps the fastest for all later steps of this context.  It has the side effects of that
- * decode step (x_out, slot seq_lens[b]-1 of layer 0's cache) and needs weights of layer 0 and the KV-cache set.
- * The split changes the summation order of the attention partials, i.e. results before and after tuning agree
- * to rounding, not bit for bit; within one split they stay bit-identical for every policy.  *chunk_tokens
- * (optional) receives the choice.  Synchronises both streams. */
-psv_status psv_tune_attention(psv_ctx *ctx, const float *x_in, float *x_out, uint32_t batch,
-                              uint32_t *chunk_tokens);
-
-/* Checks that work on stream_side really runs beside work on stream_main.  HIP multiplexes streams
- * onto a few hardware queues; two streams that land on the same queue execute one after the other,
- * and a prefetch can then never overlap its window.  The check runs a 1 ms window kernel on
- * stream_main and a gate on stream_side that waits for the window's start flag, and times on the
- * host how long stream_side takes to drain: *concurrent = 1 if the gate got through in under half
- * the window, 0 if it had to wait for the window's end (then create the context again with another
- * side stream).  The context remembers the answer: policy.prelaunch stays without effect unless it is 1.
- * Synchronises both streams. */
-psv_status psv_check_overlap(psv_ctx *ctx, int32_t *concurrent);
-
-/* ---- measurement and test aids ---------------------------------------------------------- */
-
-/* When op is a PSV_OP_* id (not PSV_OP_UP: gate and up share one kernel), every later eager-mode
- * decode step binds a HIP event to the dispatch of each main-stream kernel; the duration reported
- * for the operator is the time from the end of the kernel launched just before it on stream_main
- * to the end of the operator's kernel (for PSV_OP_ATTN: the split-K kernel, not the small merge
- * that follows).  op = -1 switches it off.  Synchronises. */
-psv_status psv_set_profile_op(psv_ctx *ctx, int32_t op);
-/* After psv_sync: total milliseconds and number of bracketed launches since the last call of
- * psv_set_profile_op; resets the accumulation. */
-psv_status psv_get_profile(psv_ctx *ctx, double *total_ms, uint64_t *launches);
-
-/* The prefetch kernel on its own: reads `bytes` at dev pointer `ptr` with `workgroups`
- * workgroups on `stream` (hipStream_t) and writes nothing. */
-psv_status psv_prefetch_region(const void *ptr, uint64_t bytes, uint32_t workgroups, void *stream);
-/* The communication stand-in on its own: one workgroup spinning for `us` microseconds. */
-psv_status psv_spin(float us, void *stream);
-/* A plain device-to-device copy kernel of `bytes` (multiple of 16) used to calibrate hardware
- * byte counters against a known size. */
-psv_status psv_copy_bytes(void *dst, const void *src, uint64_t bytes, void *stream);
-
-/* Test aid for the prelaunch policy: while on, a kernel launched ahead of its window's end gives up its
- * (always bounded) wait at once.  The kernel then still completes, sets an error word, and the next psv_sync
- * returns PSV_ERR_HIP once; the context stays usable. */
-psv_status psv_debug_force_wait_timeout(psv_ctx *ctx, uint32_t on);
-
-/* Intermediate buffers of the most recent layer executed, for debugging parity failures.  PSV_DBG_H1 and
- * PSV_DBG_H2 exist only when the step ran on the vector path (batch 1, or batch 2 with H <= 4096): the
- * matrix-core path never forms the normalised activations (it scales the projection's result instead), and
- * psv_debug_read returns PSV_ERR_BAD_STATE for them. */
-enum {
-    PSV_DBG_H1 = 0,     /* fp32 [batch, H]            normalised input of QKV */
-    PSV_DBG_QKV = 1,    /* fp32 [batch, (nq+2nkv)*128] projection output before rotation */
-    PSV_DBG_ATTN = 2,   /* fp32 [batch, nq*128]       attention output */
-    PSV_DBG_Y = 3,      /* fp32 [batch, H]            residual after the attention block */
-    PSV_DBG_H2 = 4,     /* fp32 [batch, H]            normalised input of gate/up */
-    PSV_DBG_M = 5,      /* fp32 [batch, F]            silu(gate) * up */
-    PSV_DBG_COUNT = 6
-};
-/* Synchronises, then copies min(bytes, buffer size) bytes of buffer `which` to host memory. */
-psv_status psv_debug_read(psv_ctx *ctx, uint32_t which, void *host_dst, size_t bytes);
 
 #ifdef __cplusplus
 }

@@ -1,4 +1,4 @@
-"""ctypes binding of libpreserve_mi355x.so: the same entry points as include/preserve.h.
+"""ctypes binding of libpreserve_mi355x.so: the same entry points as include/preserve.h and include/preserve_aux.h.
 
 Argument marshalling only -- every step of the decode path runs inside the library's HIP kernels.
 There is no fallback: if the built library is missing, loading raises.  Device buffers are torch
@@ -11,6 +11,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libpreserve_mi355x.so")
 
 PSV_OK, PSV_ERR_INVALID_ARG, PSV_ERR_BAD_STATE, PSV_ERR_UNSUPPORTED, PSV_ERR_HIP, PSV_ERR_NOMEM = 0, -1, -2, -3, -4, -5
+PSV_ERR_TIMEOUT = -6
 PSV_TARGET_WEIGHTS, PSV_TARGET_KV = 1, 2
 PSV_OP_QKV, PSV_OP_ATTN, PSV_OP_O, PSV_OP_GATE, PSV_OP_UP, PSV_OP_DOWN = range(6)
 OP_NAMES = ["qkv", "attn", "o", "gate", "up", "down"]

@@ -9,7 +9,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpreserve_mi355x.so")
 SOURCES = ["gemv.hip", "gemm_sk.hip", "attention.hip", "window.hip", "executor.cpp", "api.cpp", "planner.cpp"]
 HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "device.h"), os.path.join(CSRC, "context.h"),
-           os.path.join(HERE, "..", "include", "preserve.h")]
+           os.path.join(HERE, "..", "include", "preserve.h"), os.path.join(HERE, "..", "include", "preserve_aux.h")]
 
 # Packed-FP32 VALU instructions are switched off for all device code.
 HIP_FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-Wall", "-Wno-unused-result",

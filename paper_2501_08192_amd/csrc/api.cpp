@@ -1,5 +1,5 @@
-// C entry points of libpreserve_mi355x (include/preserve.h): argument checks, context life cycle, setters, the
-// decode step with its optional graph capture, synchronisation, statistics and the measurement aids.
+// C entry points of libpreserve_mi355x (include/preserve.h, include/preserve_aux.h): argument checks, context life
+// cycle, setters, the decode step, synchronisation, statistics and the measurement aids.
 #include <cstdlib>
 #include <math.h>
 #include <stdlib.h>
@@ -11,6 +11,7 @@
 #include <vector>
 
 #include "context.h"
+#include "../../include/preserve_aux.h"
 
 using namespace psv;
 
@@ -51,12 +52,9 @@ psv_status psv_create(const psv_model_desc *desc, void *stream_main, void *strea
     c->weights_set.assign(c->d.n_layers, 0);
     c->k_pools.assign(c->d.n_layers, nullptr);
     c->v_pools.assign(c->d.n_layers, nullptr);
-    c->ev_fork.assign((size_t)c->d.n_layers * 2, nullptr);
     c->ev_join.assign((size_t)c->d.n_layers * 2, nullptr);
-    for (size_t i = 0; i < c->ev_fork.size(); ++i) {
-        if (hipEventCreateWithFlags(&c->ev_fork[i], hipEventDisableTiming) != hipSuccess) return fail(PSV_ERR_HIP);
+    for (size_t i = 0; i < c->ev_join.size(); ++i)
         if (hipEventCreateWithFlags(&c->ev_join[i], hipEventDisableTiming) != hipSuccess) return fail(PSV_ERR_HIP);
-    }
     if (hipEventCreateWithFlags(&c->ev_end, hipEventDisableTiming) != hipSuccess) return fail(PSV_ERR_HIP);
     c->policy.mode = 0;
     c->policy.targets = PSV_TARGET_WEIGHTS | PSV_TARGET_KV;
@@ -67,8 +65,6 @@ psv_status psv_create(const psv_model_desc *desc, void *stream_main, void *strea
 psv_status psv_destroy(psv_ctx *c)
 {
     if (!c) return PSV_ERR_INVALID_ARG;
-    drop_graph(c);
-    for (hipEvent_t e : c->ev_fork) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->ev_join) if (e) (void)hipEventDestroy(e);
     for (hipEvent_t e : c->prof_events) if (e) (void)hipEventDestroy(e);
     if (c->ev_end) (void)hipEventDestroy(c->ev_end);
@@ -91,7 +87,6 @@ psv_status psv_set_layer_weights(psv_ctx *c, uint32_t layer, const psv_layer_wei
     }
     c->weights[layer] = *w;
     c->weights_set[layer] = 1;
-    touch(c);
     return PSV_OK;
 }
 
@@ -114,7 +109,6 @@ psv_status psv_set_kv(psv_ctx *c, const psv_kv_desc *kv)
     c->kv.k_pools = nullptr;   // the host arrays are copied, not borrowed
     c->kv.v_pools = nullptr;
     c->kv_set = true;
-    touch(c);
     return PSV_OK;
 }
 
@@ -123,7 +117,6 @@ psv_status psv_set_comm_windows(psv_ctx *c, float us_after_attn, float us_after_
     if (!c || !(us_after_attn >= 0.f) || !(us_after_mlp >= 0.f) || us_after_attn > 1.0e6f || us_after_mlp > 1.0e6f) return PSV_ERR_INVALID_ARG;
     c->window_us[0] = us_after_attn;
     c->window_us[1] = us_after_mlp;
-    touch(c);
     return PSV_OK;
 }
 
@@ -133,15 +126,9 @@ psv_status psv_set_policy(psv_ctx *c, const psv_prefetch_policy *p, uint32_t bat
     if (p->mode > 1 || (p->targets & ~3u) || p->partial > 1 || p->join > 1 || p->prelaunch > 1 || p->cu_budget > 65535)
         return PSV_ERR_INVALID_ARG;
     if (batch == 0 || batch > c->d.max_batch || context == 0 || context > c->d.max_seq) return PSV_ERR_INVALID_ARG;
-    if (p->mode == 1 && p->prelaunch && c->overlap < 0) {   // pre-launched kernels need streams that really overlap
-        int32_t concurrent = 0;
-        psv_status st = psv_check_overlap(c, &concurrent);
-        if (st != PSV_OK) return st;
-    }
     c->policy = *p;
     c->plan_batch = batch;
     c->plan_context = context;
-    touch(c);
     return rebuild_plan(c);
 }
 
@@ -156,15 +143,9 @@ psv_status psv_plan(psv_ctx *c, psv_plan_entry *out, size_t cap, size_t *n)
 psv_status psv_set_graph_mode(psv_ctx *c, uint32_t use_graph)
 {
     if (!c || use_graph > 1) return PSV_ERR_INVALID_ARG;
-    if (use_graph == 1) {
-        // Off unless asked for twice: runs that captured, replayed and destroyed step graphs ended twice (in ~20 runs
-        // of ~75 captures each) in an abort inside the HIP runtime, with no message and no cause found.
-        const char *on = std::getenv("PSV_ENABLE_HIP_GRAPHS");
-        if (!on || on[0] != '1' || on[1] != '\0') return PSV_ERR_UNSUPPORTED;
-    }
-    c->use_graph = use_graph == 1;
-    if (!c->use_graph) drop_graph(c);
-    return PSV_OK;
+    // Retired: runs that captured, replayed and destroyed step graphs ended twice (in ~20 runs of ~75 captures each)
+    // in an abort inside the HIP runtime, with no message and no cause found; eager launches were faster anyway.
+    return use_graph == 1 ? PSV_ERR_UNSUPPORTED : PSV_OK;
 }
 
 psv_status psv_decode_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t batch, uint32_t lb, uint32_t le)
@@ -177,31 +158,7 @@ psv_status psv_decode_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t
         if (!c->weights_set[l]) return PSV_ERR_BAD_STATE;
     if (c->policy.mode == 1 && c->plan_batch != batch) return PSV_ERR_BAD_STATE;   // the plan was sized for another batch
     ++c->steps;
-    if (!c->use_graph) return enqueue_step(c, x_in, x_out, batch, lb, le);
-
-    GraphKey key{x_in, x_out, batch, lb, le, c->version};
-    if (!c->graph_exec || !(key == c->graph_key)) {
-        drop_graph(c);
-        hipGraph_t graph = nullptr;
-        HIP_TRY(hipStreamBeginCapture(c->main, hipStreamCaptureModeThreadLocal));
-        c->capturing = true;
-        psv_status st = enqueue_step(c, x_in, x_out, batch, lb, le);
-        c->capturing = false;
-        hipError_t e = hipStreamEndCapture(c->main, &graph);
-        if (st != PSV_OK || e != hipSuccess) {
-            if (graph) (void)hipGraphDestroy(graph);
-            return st != PSV_OK ? st : PSV_ERR_HIP;
-        }
-        e = hipGraphInstantiate(&c->graph_exec, graph, nullptr, nullptr, 0);
-        (void)hipGraphDestroy(graph);
-        if (e != hipSuccess) {
-            c->graph_exec = nullptr;
-            return PSV_ERR_HIP;
-        }
-        c->graph_key = key;
-    }
-    HIP_TRY(hipGraphLaunch(c->graph_exec, c->main));
-    return PSV_OK;
+    return enqueue_step(c, x_in, x_out, batch, lb, le);
 }
 
 psv_status psv_sync(psv_ctx *c)
@@ -218,7 +175,7 @@ psv_status psv_sync(psv_ctx *c)
         c->prelaunch_used = false;
         if (v) {
             (void)hipMemset(err, 0, sizeof v);
-            return PSV_ERR_HIP;
+            return PSV_ERR_TIMEOUT;
         }
     }
     return PSV_OK;
@@ -228,7 +185,6 @@ psv_status psv_debug_force_wait_timeout(psv_ctx *c, uint32_t on)
 {
     if (!c || on > 1) return PSV_ERR_INVALID_ARG;
     c->force_wait_timeout = on == 1;
-    touch(c);
     return PSV_OK;
 }
 
@@ -269,7 +225,6 @@ psv_status psv_check_overlap(psv_ctx *c, int32_t *concurrent)
     const double waited_us = std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now() - t0).count();
     *concurrent = waited_us < 0.5 * us ? 1 : 0;
     c->overlap = *concurrent;
-    touch(c);
     return psv_sync(c);
 }
 
@@ -281,14 +236,11 @@ psv_status psv_tune_attention(psv_ctx *c, const float *x_in, float *x_out, uint3
     if (st != PSV_OK) return st;
     const psv_model_desc &d = c->d;
     const uint32_t unit = (d.kv_format == PSV_FMT_INT8 ? kAttnTileTokensInt8 : kAttnTileTokens) * kAttnWaves;
-    // measured with prefetching off, eager launches and no windows; everything is restored afterwards
+    // measured with prefetching off and no windows; everything is restored afterwards
     const psv_prefetch_policy saved_policy = c->policy;
     const float saved_win[2] = {c->window_us[0], c->window_us[1]};
-    const bool saved_graph = c->use_graph;
     c->policy.mode = 0;
     c->window_us[0] = c->window_us[1] = 0.f;
-    c->use_graph = false;
-    drop_graph(c);
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess) st = PSV_ERR_HIP;
     uint32_t best = 0;
@@ -317,9 +269,7 @@ psv_status psv_tune_attention(psv_ctx *c, const float *x_in, float *x_out, uint3
     c->policy = saved_policy;
     c->window_us[0] = saved_win[0];
     c->window_us[1] = saved_win[1];
-    c->use_graph = saved_graph;
     c->attn_chunk_tokens = (st == PSV_OK && best != (uint32_t)def.chunk_tokens) ? best : 0;
-    touch(c);
     if (st == PSV_OK && chunk_tokens) *chunk_tokens = best;
     const psv_status st2 = psv_sync(c);
     return st != PSV_OK ? st : st2;

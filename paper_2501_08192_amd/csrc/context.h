@@ -24,17 +24,6 @@ struct Workspace {
 
 Workspace layout_workspace(const psv_model_desc &d);
 
-struct GraphKey {
-    const float *x_in = nullptr;
-    float *x_out = nullptr;
-    uint32_t batch = 0, lb = 0, le = 0;
-    uint64_t version = 0;
-    bool operator==(const GraphKey &o) const
-    {
-        return x_in == o.x_in && x_out == o.x_out && batch == o.batch && lb == o.lb && le == o.le && version == o.version;
-    }
-};
-
 }  // namespace psv
 
 struct psv_ctx {
@@ -53,12 +42,8 @@ struct psv_ctx {
     psv_prefetch_policy policy{};
     uint32_t plan_batch = 0, plan_context = 0;
     std::vector<psv_plan_entry> plan;
-    std::vector<hipEvent_t> ev_fork, ev_join;   // [layer*2 + window]
+    std::vector<hipEvent_t> ev_join;             // [layer*2 + window], policy.join
     hipEvent_t ev_end = nullptr;
-    uint64_t version = 1;                        // bumped by every psv_set_*
-    bool use_graph = false;
-    hipGraphExec_t graph_exec = nullptr;
-    psv::GraphKey graph_key{};
     int32_t profile_op = -1;
     std::vector<hipEvent_t> prof_events;         // pool, one per profiled launch
     size_t prof_next = 0;
@@ -67,7 +52,6 @@ struct psv_ctx {
     uint32_t steps = 0;
     uint32_t last_prefetch_launches = 0;
     unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
-    bool capturing = false;
     uint32_t attn_chunk_tokens = 0;               // 0 = default split; else tokens per attention workgroup (psv_tune_attention)
     int overlap = -1;                            // psv_check_overlap's last answer (-1 = not run yet)
     bool prelaunch_used = false;                 // some consumer was launched ahead of its window's end: check the error word at sync
@@ -91,13 +75,11 @@ struct psv_ctx {
 
 namespace psv {
 
-void drop_graph(psv_ctx *c);                 // destroys the captured step, if any
-void touch(psv_ctx *c);                      // a setter changed the context: new version, captured step dropped
 AttnSplit ctx_split(const psv_ctx *c);       // attention split in force (default or tuned)
 uint64_t us_to_ticks(uint64_t clock_khz, float us);
 uint32_t spin_cap(float us);
 psv_status rebuild_plan(psv_ctx *c);
-// Enqueues one decode step over layers [lb, le) on the context's two streams (or into the capture in progress).
+// Enqueues one decode step over layers [lb, le) on the context's two streams.
 psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t batch, uint32_t lb, uint32_t le);
 
 }  // namespace psv

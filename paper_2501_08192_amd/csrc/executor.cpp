@@ -1,9 +1,9 @@
 // Context, workspace and step executor of libpreserve_mi355x.
 //
 // Execution model (Section 3, "PRESERVE"): the decode step's operators run in order on the main
-// stream; beside each communication window an event forks the side stream, which runs the
-// prefetch kernels the plan assigned to that window while the main stream sits in the window
-// (here: a spin kernel standing in for the allreduce).  Prefetch kernels only read, so the main
+// stream; beside each communication window the side stream runs the prefetch kernels the plan
+// assigned to that window while the main stream sits in the window (here: a spin kernel standing
+// in for the allreduce); the fork between the two streams is a flag on the device.  Prefetch kernels only read, so the main
 // stream never has to wait for them; the side stream itself serialises consecutive windows.
 #include <math.h>
 #include <stdlib.h>
@@ -60,20 +60,6 @@ Workspace layout_workspace(const psv_model_desc &d)
     return w;
 }
 
-void drop_graph(psv_ctx *c)
-{
-    if (c->graph_exec) {
-        (void)hipGraphExecDestroy(c->graph_exec);
-        c->graph_exec = nullptr;
-    }
-}
-
-void touch(psv_ctx *c)
-{
-    ++c->version;
-    drop_graph(c);
-}
-
 KvView kv_view(const psv_ctx *c, uint32_t layer)
 {
     KvView v;
@@ -112,7 +98,7 @@ uint32_t spin_cap(float us) { return (uint32_t)(us * 4000.0f) + 100000u; }
 // the true dispatch gap -- no marker packets in between, which would add ~2 us each.
 psv_status prof_tag(psv_ctx *c, int32_t op)
 {
-    if (c->capturing || c->profile_op < 0) return PSV_OK;
+    if (c->profile_op < 0) return PSV_OK;
     if (c->prof_next == c->prof_events.size()) {
         hipEvent_t e;
         HIP_TRY(hipEventCreate(&e));
@@ -158,7 +144,7 @@ const void *weight_ptr(const psv_layer_weights &w, uint32_t op)
 struct JobBuilder {
     psv_ctx *c;
     uint64_t cap;        // bytes per launch (0 = unlimited)
-    const unsigned *skip;   // word written by the gate kernel of this window (null under graph capture)
+    const unsigned *skip;   // word written by the gate kernel of this window
     hipStream_t stream;     // where the prefetch launches go
     uint64_t used = 0;
     PrefetchJob job{};
@@ -254,7 +240,7 @@ struct Lanes {
 // the consumer can be launched ahead of time (policy.prelaunch, eager launches, vector path)?
 bool can_prelaunch(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t layer_end, bool vec)
 {
-    if (c->capturing || !vec || c->policy.mode != 1 || !c->policy.prelaunch || !(c->window_us[window] > 0.f)) return false;
+    if (!vec || c->policy.mode != 1 || !c->policy.prelaunch || !(c->window_us[window] > 0.f)) return false;
     if (c->overlap != 1) return false;      // a waiting kernel may only be queued where it cannot block the window kernel
     if (window == 1 && layer + 1 >= layer_end) return false;       // end of the graph: no consumer
     const uint32_t first_op = window == 0 ? PSV_OP_GATE : PSV_OP_QKV;
@@ -273,27 +259,21 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
     if (c->policy.mode == 1)
         for (const psv_plan_entry &e : c->plan)
             if (e.layer == layer && e.window == window && e.target_layer < layer_end) { any = true; break; }
-    // Eager launches fork on the device: the window kernel publishes a sequence number that a one-wave gate
-    // kernel, queued on the other stream ahead of the prefetch launches, waits for.  Under graph capture the
-    // fork is an event edge.
-    unsigned *flag = c->capturing ? nullptr : c->at<unsigned>(c->ws.flag);
-    unsigned *done = flag ? flag + 32 : nullptr, *err = flag ? flag + 48 : nullptr;
+    // The fork is on the device: the window kernel publishes a sequence number that a one-wave gate kernel,
+    // queued on the other stream ahead of the prefetch launches, waits for.
+    unsigned *flag = c->at<unsigned>(c->ws.flag);
+    unsigned *done = flag + 32, *err = flag + 48;
     const unsigned seq = ++c->window_seq;
     const uint32_t first_op = window == 0 ? PSV_OP_GATE : PSV_OP_QKV;
-    hipEvent_t ev = c->ev_fork[layer * 2 + window];
-    if (any && !flag) HIP_TRY(hipEventRecord(ev, ln->cur));
     ST_TRY(prof_tag(c, -2));
     HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), flag, done, seq, ln->cur));
     if (!any) return PSV_OK;
-    unsigned *skip = flag ? flag + 16 : nullptr;
-    if (flag)
-        // A gate that gives up only costs its window's prefetch -- unless a consumer is queued behind it: that
-        // one must not start (and then run out of patience itself) while the stream of the window is merely
-        // held up by earlier work of the caller, so its gate and its own wait are bounded by a second, not 20 ms.
-        HIP_TRY(launch_gate(flag, seq, pre ? 1u << 22 : 1u << 20, c->clock_khz * (pre ? 1000 : 20) /* 1 s : 20 ms */, skip,
-                            ln->other));
-    else
-        HIP_TRY(hipStreamWaitEvent(ln->other, ev, 0));
+    unsigned *skip = flag + 16;
+    // A gate that gives up only costs its window's prefetch -- unless a consumer is queued behind it: that
+    // one must not start (and then run out of patience itself) while the stream of the window is merely
+    // held up by earlier work of the caller, so its gate and its own wait are bounded by a second, not 20 ms.
+    HIP_TRY(launch_gate(flag, seq, pre ? 1u << 22 : 1u << 20, c->clock_khz * (pre ? 1000 : 20) /* 1 s : 20 ms */, skip,
+                        ln->other));
     uint64_t cap = c->policy.chunk_bytes & ~(uint64_t)15;
     if (c->policy.chunk_bytes && cap < 16) cap = 16;
     JobBuilder jb{c, cap, skip, ln->other};
@@ -460,10 +440,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         HIP_TRY(hipEventRecord(c->ev_end, ln.cur));
         HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));
     }
-    if (side_used && c->capturing) {   // a captured side branch has to rejoin the origin stream
-        HIP_TRY(hipEventRecord(c->ev_end, c->side));
-        HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));
-    }
+    (void)side_used;
     return PSV_OK;
 }
 

@@ -101,6 +101,7 @@ const char *psv_strerror(psv_status s)
     case PSV_ERR_UNSUPPORTED: return "shape not supported by the kernels";
     case PSV_ERR_HIP: return "HIP runtime error";
     case PSV_ERR_NOMEM: return "out of memory";
+    case PSV_ERR_TIMEOUT: return "a kernel launched ahead of its communication window gave up waiting for the window's end";
     default: return "unknown status";
     }
 }

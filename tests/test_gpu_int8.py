@@ -157,10 +157,9 @@ def test_policies_are_bit_identical_int8():
     _policies_int8((False,))
 
 
-@pytest.mark.skip(reason="HIP graph mode is switched off (PSV_ENABLE_HIP_GRAPHS): test runs that captured, replayed and "
-                         "destroyed step graphs ended twice in an abort inside the HIP runtime, cause not found")
-def test_graph_mode_is_bit_identical_int8(monkeypatch):
-    monkeypatch.setenv("PSV_ENABLE_HIP_GRAPHS", "1")
+@pytest.mark.skip(reason="HIP graph mode is retired (psv_set_graph_mode(1) answers PSV_ERR_UNSUPPORTED): test runs that captured, "
+                         "replayed and destroyed step graphs ended twice in an abort inside the HIP runtime, cause not found")
+def test_graph_mode_is_bit_identical_int8():
     _policies_int8((True,))
 
 

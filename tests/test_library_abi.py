@@ -15,10 +15,13 @@ from paper_2501_08192_amd import synth
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def header_symbols():
-    text = open(os.path.join(ROOT, "include", "preserve.h")).read()
-    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(psv_[a-z_]+)\s*\(", text)))
+def header_symbols(names=("preserve.h", "preserve_aux.h")):
+    found = set()
+    for name in names:
+        text = open(os.path.join(ROOT, "include", name)).read()
+        text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+        found |= set(re.findall(r"\b(psv_[a-z_]+)\s*\(", text))
+    return sorted(found)
 
 
 def test_library_loads_and_exports_every_declared_symbol():
@@ -28,10 +31,13 @@ def test_library_loads_and_exports_every_declared_symbol():
     for n in names:
         assert hasattr(L, n), n
     assert sorted(psv.EXPORTS) == names
+    # the decode-step contract proper: create / set / plan / step / sync / stats and the pure host functions
+    core = header_symbols(("preserve.h",))
+    assert len(core) <= 16 and "psv_decode_step" in core and not [n for n in core if "debug" in n or "profile" in n]
 
 
 def test_strerror_is_total():
-    for s in (0, -1, -2, -3, -4, -5, -99, 7):
+    for s in (0, -1, -2, -3, -4, -5, -6, -99, 7):
         assert isinstance(psv.strerror(s), str) and psv.strerror(s)
 
 
