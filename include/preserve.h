@@ -251,6 +251,24 @@ psv_status psv_sync(psv_ctx *ctx);
  * once, K and V of the attended span once -- and what the current plan prefetches. */
 psv_status psv_get_stats(psv_ctx *ctx, psv_stats *out);
 
+/* ---- for callers that cannot allocate ------------------------------------------------------- */
+
+/* For callers that cannot call hipMalloc -- code under HIP graph capture, tight serving loops, harnesses that
+ * forbid it: psv_decode_step without a context.  One decode step over layers [layer_begin, layer_end) in vanilla
+ * execution (no communication stand-in, no prefetch), enqueued on `stream` (hipStream_t), with the workspace that
+ * psv_create would allocate held in a fixed device array of PSV_STATIC_SCRATCH_BYTES inside the library instead.
+ * The call allocates no device memory and creates no stream or event (its host-side bookkeeping is a few small
+ * heap vectors).  layers: host array [desc->n_layers] (only the entries of the range are read); kv, x_in, x_out,
+ * batch: as for psv_set_kv / psv_decode_step; the results are those of psv_decode_step with the policy off and both
+ * windows 0, bit for bit.  PSV_ERR_UNSUPPORTED if psv_workspace_bytes(desc) exceeds PSV_STATIC_SCRATCH_BYTES.
+ * Every call on a GPU shares that GPU's one array, which keeps the previous call's contents (nothing in it has to
+ * start at zero): calls that overlap on one GPU -- from two streams or two threads -- race; serialise them.  The
+ * array (one per GPU the library runs on) stays allocated until the process ends. */
+#define PSV_STATIC_SCRATCH_BYTES (16u << 20)
+psv_status psv_decode_step_static(const psv_model_desc *desc, const psv_layer_weights *layers,
+                                  const psv_kv_desc *kv, const float *x_in, float *x_out, uint32_t batch,
+                                  uint32_t layer_begin, uint32_t layer_end, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

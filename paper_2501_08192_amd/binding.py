@@ -18,6 +18,7 @@ OP_NAMES = ["qkv", "attn", "o", "gate", "up", "down"]
 PSV_FMT_BF16, PSV_FMT_INT8 = 0, 1
 FORMATS = {"bf16": PSV_FMT_BF16, "int8": PSV_FMT_INT8}
 PSV_KV_UNIT_BYTES_BF16, PSV_KV_UNIT_BYTES_INT8 = 4096, 2112
+PSV_STATIC_SCRATCH_BYTES = 16 << 20
 PSV_DBG_H1, PSV_DBG_QKV, PSV_DBG_ATTN, PSV_DBG_Y, PSV_DBG_H2, PSV_DBG_M = range(6)
 
 EXPORTS = [
@@ -26,7 +27,7 @@ EXPORTS = [
     "psv_set_graph_mode", "psv_decode_step", "psv_sync", "psv_get_stats", "psv_tune_attention", "psv_check_overlap",
     "psv_set_profile_op",
     "psv_get_profile", "psv_prefetch_region", "psv_spin", "psv_copy_bytes", "psv_debug_read",
-    "psv_debug_force_wait_timeout",
+    "psv_debug_force_wait_timeout", "psv_decode_step_static",
 ]
 
 
@@ -110,6 +111,8 @@ def lib():
             "psv_copy_bytes": (C.c_int32, [vp, vp, u64, vp]),
             "psv_debug_read": (C.c_int32, [vp, u32, vp, sz]),
             "psv_debug_force_wait_timeout": (C.c_int32, [vp, u32]),
+            "psv_decode_step_static": (C.c_int32, [C.POINTER(psv_model_desc), C.POINTER(psv_layer_weights),
+                                                   C.POINTER(psv_kv_desc), vp, vp, u32, u32, u32, vp]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -221,6 +224,22 @@ def psv_set_graph_mode(ctx, use_graph):
 
 def psv_decode_step(ctx, x_in, x_out, batch, layer_begin, layer_end):
     _check(lib().psv_decode_step(ctx, _dev_ptr(x_in), _dev_ptr(x_out), batch, layer_begin, layer_end), "psv_decode_step")
+
+
+def psv_decode_step_static(desc, layers, k_pools, v_pools, page_table, max_blocks, num_pool_blocks, seq_lens, x_in, x_out,
+                           batch, layer_begin, layer_end, stream):
+    """layers: list (one entry per layer of desc; None where a layer is outside the range) of weight dicts as for
+    psv_set_layer_weights; k_pools / v_pools: lists of device tensors, one per layer."""
+    n = len(layers)
+    arr = (psv_layer_weights * n)()
+    for i, w in enumerate(layers):
+        if w is not None:
+            arr[i] = psv_layer_weights(*[_dev_ptr(w.get(f)) for f, _ in psv_layer_weights._fields_])
+    ka = (C.c_void_p * n)(*[_dev_ptr(t) for t in k_pools])
+    va = (C.c_void_p * n)(*[_dev_ptr(t) for t in v_pools])
+    kv = psv_kv_desc(ka, va, _dev_ptr(page_table), max_blocks, num_pool_blocks, _dev_ptr(seq_lens))
+    _check(lib().psv_decode_step_static(C.byref(desc), arr, C.byref(kv), _dev_ptr(x_in), _dev_ptr(x_out), batch,
+                                        layer_begin, layer_end, _stream(stream)), "psv_decode_step_static")
 
 
 def psv_sync(ctx):
