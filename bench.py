@@ -52,6 +52,7 @@ def parse():
                          "measurement precision), w8 / kv8 (only the weights / only the cache in int8)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="also launch one plain copy kernel of this size (known bytes, to scale hardware counters)")
+    ap.add_argument("--fused", type=int, default=1, help="0 = one kernel per operator everywhere (psv_set_fused_kernels)")
     ap.add_argument("--skip-kernel-table", action="store_true", help="omit the per-operator event timing passes")
     return ap.parse_args()
 
@@ -151,6 +152,7 @@ def main():
                         prelaunch=a.prelaunch)
     off = psv.prefetch_policy(mode=0)
 
+    psv.psv_set_fused_kernels(sess.ctx, bool(a.fused))
     attn_chunk = sess.tune_attention() if a.tune else 0
 
     # prefetch off (vanilla execution) and on, same launch configuration otherwise
@@ -195,7 +197,7 @@ def main():
             us, n = profile_op(sess, op, n_prof)
             kernels.setdefault(name, {"bytes": op_bytes[name]})
             kernels[name]["us_" + mode_name] = round(us, 3)
-            kernels[name]["gbps_" + mode_name] = round(op_bytes[name] / us / 1e3, 1)
+            kernels[name]["gbps_" + mode_name] = round(op_bytes[name] / us / 1e3, 1) if us > 0 else None
             kernels[name]["launches"] = n
     gate_us, gate_n = kernels["gate_up"]["us_off"], kernels["gate_up"]["launches"]
     gate_us_on = kernels["gate_up"].get("us_on", float("nan"))

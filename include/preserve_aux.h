@@ -23,6 +23,14 @@ extern "C" {
  * HIP runtime whose cause was not found. */
 psv_status psv_set_graph_mode(psv_ctx *ctx, uint32_t use_graph);
 
+/* 0 (default) = one kernel per operator; 1 = at batch 1, where the shape allows it (bf16 cache, sequences up to 4096
+ * tokens), the operators between two communication windows run as one fused kernel each (QKV + attention + O;
+ * gate/up + down) whose phases hand their results over through tagged values in memory.  Faster by ~3 us per layer
+ * on an 8B-shaped shard when the kernels are launched into the windows (policy.prelaunch), slower otherwise.  The two
+ * settings agree to rounding, not bit for bit; within one setting every policy gives the same bits.  A hand-over that
+ * does not complete within its bound makes the next psv_sync return PSV_ERR_HIP. */
+psv_status psv_set_fused_kernels(psv_ctx *ctx, uint32_t on);
+
 /* ---- streams and tuning -------------------------------------------------------------------- */
 
 /* Chooses how many tokens of a sequence one attention workgroup covers (the split of the span over

@@ -27,7 +27,7 @@ EXPORTS = [
     "psv_set_graph_mode", "psv_decode_step", "psv_sync", "psv_get_stats", "psv_tune_attention", "psv_check_overlap",
     "psv_set_profile_op",
     "psv_get_profile", "psv_prefetch_region", "psv_spin", "psv_copy_bytes", "psv_debug_read",
-    "psv_debug_force_wait_timeout", "psv_decode_step_static",
+    "psv_debug_force_wait_timeout", "psv_decode_step_static", "psv_set_fused_kernels",
 ]
 
 
@@ -111,6 +111,7 @@ def lib():
             "psv_copy_bytes": (C.c_int32, [vp, vp, u64, vp]),
             "psv_debug_read": (C.c_int32, [vp, u32, vp, sz]),
             "psv_debug_force_wait_timeout": (C.c_int32, [vp, u32]),
+            "psv_set_fused_kernels": (C.c_int32, [vp, u32]),
             "psv_decode_step_static": (C.c_int32, [C.POINTER(psv_model_desc), C.POINTER(psv_layer_weights),
                                                    C.POINTER(psv_kv_desc), vp, vp, u32, u32, u32, vp]),
         }
@@ -290,6 +291,10 @@ def psv_debug_read(ctx, which, host_array):
     """host_array: a contiguous numpy array that receives the buffer."""
     _check(lib().psv_debug_read(ctx, which, host_array.ctypes.data_as(C.c_void_p), host_array.nbytes), "psv_debug_read")
     return host_array
+
+
+def psv_set_fused_kernels(ctx, on):
+    _check(lib().psv_set_fused_kernels(ctx, 1 if on else 0), "psv_set_fused_kernels")
 
 
 def psv_debug_force_wait_timeout(ctx, on):

@@ -37,6 +37,7 @@ psv_status psv_create(const psv_model_desc *desc, void *stream_main, void *strea
     if (hipGetDevice(&c->device) != hipSuccess) return fail(PSV_ERR_HIP);
     int khz = 0;
     if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, c->device) == hipSuccess && khz > 0) c->clock_khz = (uint64_t)khz;
+    if (hipDeviceGetAttribute(&c->cus, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess) c->cus = 0;
     c->ws = layout_workspace(c->d);
     if (hipMalloc(reinterpret_cast<void **>(&c->wsp), c->ws.total) != hipSuccess) {
         c->wsp = nullptr;
@@ -168,14 +169,16 @@ psv_status psv_sync(psv_ctx *c)
     hipError_t b = hipStreamSynchronize(c->side);
     hipError_t l = hipGetLastError();
     if (!(a == hipSuccess && b == hipSuccess && l == hipSuccess)) return PSV_ERR_HIP;
-    if (c->prelaunch_used) {   // did a consumer launched ahead of time give up waiting for its window's end?
+    if (c->check_err_word) {
+        // bit 0: a consumer launched ahead of time gave up waiting for its window's end (its results are still right);
+        // bit 1: a hand-over inside a fused kernel expired (results invalid)
         unsigned *err = c->at<unsigned>(c->ws.flag) + 48;
         unsigned v = 0;
         if (hipMemcpy(&v, err, sizeof v, hipMemcpyDeviceToHost) != hipSuccess) return PSV_ERR_HIP;
-        c->prelaunch_used = false;
+        c->check_err_word = false;
         if (v) {
             (void)hipMemset(err, 0, sizeof v);
-            return PSV_ERR_TIMEOUT;
+            return (v & 2u) ? PSV_ERR_HIP : PSV_ERR_TIMEOUT;
         }
     }
     return PSV_OK;
@@ -185,6 +188,13 @@ psv_status psv_debug_force_wait_timeout(psv_ctx *c, uint32_t on)
 {
     if (!c || on > 1) return PSV_ERR_INVALID_ARG;
     c->force_wait_timeout = on == 1;
+    return PSV_OK;
+}
+
+psv_status psv_set_fused_kernels(psv_ctx *c, uint32_t on)
+{
+    if (!c || on > 1) return PSV_ERR_INVALID_ARG;
+    c->fused = on == 1;
     return PSV_OK;
 }
 
@@ -355,6 +365,14 @@ psv_status psv_debug_read(psv_ctx *c, uint32_t which, void *host_dst, size_t byt
     default: return PSV_ERR_INVALID_ARG;
     }
     if (bytes < size) size = bytes;
+    if ((which == PSV_DBG_M && c->last_step_seg_mlp) || (which == PSV_DBG_QKV && c->last_step_seg_attn)) {
+        // the fused kernels keep m and qkv (one sequence) as {value, tag} pairs
+        if (which == PSV_DBG_QKV && size > QR * 4) size = QR * 4;
+        std::vector<uint32_t> pairs(size / 4 * 2);
+        HIP_TRY(hipMemcpy(pairs.data(), c->wsp + (which == PSV_DBG_M ? c->ws.m_ll : c->ws.qkv_ll), pairs.size() * 4, hipMemcpyDeviceToHost));
+        for (size_t i = 0; i < size / 4; ++i) static_cast<uint32_t *>(host_dst)[i] = pairs[2 * i];
+        return PSV_OK;
+    }
     HIP_TRY(hipMemcpy(host_dst, c->wsp + off, size, hipMemcpyDeviceToHost));
     return PSV_OK;
 }

@@ -19,7 +19,7 @@ struct Workspace {
     size_t total = 0;
     // offsets
     size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, rope, part_ml, part_o, attn_f32, attn_bf16,
-        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag, part, ssq;
+        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag, part, ssq, m_ll, qkv_ll, pml_ll, po_ll;
 };
 
 Workspace layout_workspace(const psv_model_desc &d);
@@ -54,9 +54,13 @@ struct psv_ctx {
     unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
     uint32_t attn_chunk_tokens = 0;               // 0 = default split; else tokens per attention workgroup (psv_tune_attention)
     int overlap = -1;                            // psv_check_overlap's last answer (-1 = not run yet)
-    bool prelaunch_used = false;                 // some consumer was launched ahead of its window's end: check the error word at sync
+    bool check_err_word = false;                 // a kernel that may set the error word (a pre-launched consumer, a fused kernel) was launched: read it at sync
+    bool fused = false;                          // fused kernels of the vector path switched on (psv_set_fused_kernels)
     bool force_wait_timeout = false;             // test aid: such consumers give up waiting at once (and report it)
     bool last_step_vec = false;                  // the last step formed h1 / h2 (vector path)
+    bool last_step_seg_attn = false;             // ... the attention block (qkv lives in the tagged buffer)
+    bool last_step_seg_mlp = false;              // ... and ran the MLP block as one fused kernel (m lives in the tagged buffer)
+    int cus = 0;                                 // compute units of the device = workgroups of a fused kernel (0: fused kernels off)
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(wsp + off); }
 };

@@ -37,17 +37,16 @@ typedef int i32x4 __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-__device__ __forceinline__ uint32_t f32_to_bf16(float f)   // round to nearest even
-{
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    u += 0x7fffu + ((u >> 16) & 1u);
-    return u >> 16;
-}
+// float -> bf16, round to nearest even: the hardware conversion of gfx950 (one instruction per pair of values; the
+// bit-twiddling version costs ~6 vector instructions per value, which showed in kernels that convert thousands).
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 {
-    return f32_to_bf16(lo) | (f32_to_bf16(hi) << 16);
+    const bf16x2_t v = __builtin_convertvector(f32x2_t{lo, hi}, bf16x2_t);
+    return __builtin_bit_cast(uint32_t, v);
 }
+__device__ __forceinline__ uint32_t f32_to_bf16(float f) { return pack_bf16(f, 0.f) & 0xffffu; }
 
 // Activations that feed the matrix cores are carried as two bf16 planes, x = hi + lo (+ a remainder below
 // 2^-17 |x|): one MFMA per plane restores fp32-grade accuracy at negligible cost, since the matrix cores
@@ -85,11 +84,8 @@ __device__ __forceinline__ float wave_sum(float v)
 // Two values as a pair of packed bf16 words: hi = their bf16 roundings, lo = the bf16 roundings of what is left.
 __device__ __forceinline__ void pack_split(float a, float b, uint32_t &hi, uint32_t &lo)
 {
-    uint32_t ah, al, bh, bl;
-    split_bf16(a, ah, al);
-    split_bf16(b, bh, bl);
-    hi = ah | (bh << 16);
-    lo = al | (bl << 16);
+    hi = pack_bf16(a, b);
+    lo = pack_bf16(a - bf16_lo(hi), b - bf16_hi(hi));
 }
 
 // low bytes of four floats that hold small integers in "magic number" form (x + 1.5 * 2^23)

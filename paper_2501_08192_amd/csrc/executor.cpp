@@ -51,6 +51,13 @@ Workspace layout_workspace(const psv_model_desc &d)
     w.inv_freq = take(64 * sizeof(double));
     w.flag = take(256);
     w.ssq = take(B * (H / 512) * 4);
+    w.m_ll = take(B * F * 8);               // tagged values of the fused MLP kernel
+    {                                       // ... and of the fused attention-block kernel (one sequence)
+        const size_t nc = (size_t)seg_attn_chunks(d.max_seq);
+        w.qkv_ll = take(QR * 8);
+        w.pml_ll = take(d.n_kv_heads * nc * 16 * 2 * 8);
+        w.po_ll = take(d.n_kv_heads * nc * G * 128 * 8);
+    }
     {   // split-K partials of the widest projection
         size_t widest = QR > H ? QR : H;
         if (2 * F > widest) widest = 2 * F;
@@ -249,8 +256,18 @@ bool can_prelaunch(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t l
     return false;
 }
 
+// Does the plan hand all of operator `op` of `target_layer` to window (layer, window)?
+bool plan_has_whole(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t target_layer, uint32_t op)
+{
+    for (const psv_plan_entry &e : c->plan)
+        if (e.layer == layer && e.window == window && e.target_layer == target_layer && e.target_op == op) return e.bytes == e.mem_size;
+    return false;
+}
+
+// held: bit mask (1 << PSV_OP_*) of the operators whose planned bytes the pre-launched consumer pulls into its own
+// registers during the window; their plan entries are not prefetched a second time.
 psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t batch, uint32_t layer_end, bool pre,
-                       Lanes *ln, GemvWait *wait, bool *wait_set, bool *side_used)
+                       uint32_t held, Lanes *ln, GemvWait *wait, bool *wait_set, bool *side_used)
 {
     *wait_set = false;
     const float us = c->window_us[window];
@@ -264,7 +281,6 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
     unsigned *flag = c->at<unsigned>(c->ws.flag);
     unsigned *done = flag + 32, *err = flag + 48;
     const unsigned seq = ++c->window_seq;
-    const uint32_t first_op = window == 0 ? PSV_OP_GATE : PSV_OP_QKV;
     ST_TRY(prof_tag(c, -2));
     HIP_TRY(launch_spin(us_to_ticks(c->clock_khz, us), spin_cap(us), flag, done, seq, ln->cur));
     if (!any) return PSV_OK;
@@ -280,7 +296,7 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
     for (const psv_plan_entry &e : c->plan) {
         if (e.layer != layer || e.window != window || e.target_layer >= layer_end) continue;
         // what the pre-launched consumer reads itself needs no second copy in the memory-side cache
-        if (pre && (e.target_op == first_op || (window == 0 && e.target_op == PSV_OP_UP))) continue;
+        if (pre && (held >> e.target_op & 1u)) continue;
         psv_status st = add_entry(c, jb, e, batch);
         if (st != PSV_OK) return st;
     }
@@ -294,7 +310,7 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
         wait->ticks = c->force_wait_timeout ? 0ull : us_to_ticks(c->clock_khz, us) * 2 + c->clock_khz * 1000 /* + 1 s */;
         wait->err = err;
         *wait_set = true;
-        c->prelaunch_used = true;
+        c->check_err_word = true;
         std::swap(ln->cur, ln->other);     // the chain continues behind the consumer
         return PSV_OK;
     }
@@ -339,6 +355,16 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
                      gemv_supported(B, F, H) && gemv_supported(B, H, F);
     const bool sk = !vec;
     c->last_step_vec = vec;
+    // The vector path runs the operators between two windows as one fused kernel where the shape allows it.  Which
+    // kernels run depends on the shape only, never on the policy, so every policy gives the same bits.
+    const int blocks = c->fused ? c->cus : 0;
+    const bool seg_mlp = vec && blocks >= 64 && seg_mlp_supported(B, H, F);
+    const bool seg_attn = vec && blocks >= 64 && seg_attn_supported(B, H, nq, nkv, d.max_seq, d.kv_format == PSV_FMT_INT8, blocks);
+    const int seg_nc = seg_attn_chunks(d.max_seq);
+    c->last_step_seg_mlp = seg_mlp;
+    c->last_step_seg_attn = seg_attn;
+    unsigned *errw = c->at<unsigned>(c->ws.flag) + 48;
+    if (seg_mlp || seg_attn) c->check_err_word = true;
     float *part = c->at<float>(c->ws.part), *ssq = c->at<float>(c->ws.ssq);
 
     // The chain hops to the other stream at every pre-launching window and has to be back on the main stream when
@@ -368,7 +394,15 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x, u16(w.g_attn), h1b, plane_h, w8, ssq, s));
         }
         ST_TRY(prof_tag(c, PSV_OP_QKV));
-        if (vec) {
+        if (seg_attn) {
+            // QKV + rotary embedding + KV append + attention + merge + O in one launch (profiled as the QKV operator)
+            const bool from_window = wait_qkv && l > lb;
+            HIP_TRY(launch_seg_attn(Wqkv, Wo, res, delta, u16(w.g_attn), d.rms_eps, x, h1, c->at<void>(c->ws.qkv_ll), rope, kv, nq, nkv,
+                                    seg_nc, c->at<void>(c->ws.pml_ll), c->at<void>(c->ws.po_ll), attn, delta_a, H, next_tag(), errw,
+                                    wait_qkv ? &wait : nullptr, from_window && plan_has_whole(c, l - 1, 1, l, PSV_OP_ATTN),
+                                    from_window && plan_has_whole(c, l - 1, 1, l, PSV_OP_O), blocks, s));
+            wait_qkv = false;
+        } else if (vec) {
             HIP_TRY(launch_gemv_norm(Wqkv, Mat{}, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H,
                                      wait_qkv ? &wait : nullptr, s));
             wait_qkv = false;
@@ -379,18 +413,21 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H, w8), B, QR, false, qkv, nullptr, false, s));
         }
 
-        ST_TRY(prof_tag(c, PSV_OP_ATTN));
-        HIP_TRY(launch_attn(qkv, rope, kv, B, nq, nkv, sp, pml, po, s));
+        if (!seg_attn) {
+            ST_TRY(prof_tag(c, PSV_OP_ATTN));
+            HIP_TRY(launch_attn(qkv, rope, kv, B, nq, nkv, sp, pml, po, s));
+        }
         const bool fuse_merge = vec && gemv_merge_supported(B, nq, sp.n_chunks);
-        if (!fuse_merge) {
+        if (!fuse_merge && !seg_attn) {
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_attn_merge(pml, po, B, nq, nkv, sp, attn, attnb, sk && w8, s));
         }
 
-        ST_TRY(prof_tag(c, PSV_OP_O));
+        if (!seg_attn) ST_TRY(prof_tag(c, PSV_OP_O));
         const float *attn_delta = delta_a;
         int attn_splits = 1;
-        if (fuse_merge) {
+        if (seg_attn) {
+        } else if (fuse_merge) {
             HIP_TRY(launch_gemv_merge(Wo, pml, po, nq, nkv, sp.n_chunks, attn, delta_a, B, H, s));
         } else if (vec) {
             HIP_TRY(launch_gemv(Wo, Mat{}, attn, delta_a, B, H, QD, s));
@@ -401,14 +438,23 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             attn_splits = gemm_sk_splits(B, H, QD, w8);
         }
 
-        ST_TRY(comm_window(c, l, 0, batch, le, take_pre(l, 0), &ln, &wait, &wait_gate, &side_used));
+        {
+            uint32_t held = 1u << PSV_OP_GATE | 1u << PSV_OP_UP;
+            if (seg_mlp && plan_has_whole(c, l, 0, l, PSV_OP_DOWN) && seg_mlp_holds_down(H, F, w8, blocks)) held |= 1u << PSV_OP_DOWN;
+            ST_TRY(comm_window(c, l, 0, batch, le, take_pre(l, 0), held, &ln, &wait, &wait_gate, &side_used));
+        }
 
         if (sk) {
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_resid_sum(x, attn_delta, attn_splits, B, H, y, u16(w.g_mlp), h2b, plane_h, w8, ssq, s));
         }
         ST_TRY(prof_tag(c, PSV_OP_GATE));
-        if (vec) {
+        if (seg_mlp) {
+            // gate/up + SwiGLU + down in one launch (profiled as the gate/up operator; down has no kernel of its own)
+            HIP_TRY(launch_seg_mlp(Wg, Wu, Wd, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, c->at<void>(c->ws.m_ll), delta_m, B, H, F,
+                                   next_tag(), errw, wait_gate ? &wait : nullptr, plan_has_whole(c, l, 0, l, PSV_OP_DOWN), blocks, s));
+            wait_gate = false;
+        } else if (vec) {
             HIP_TRY(launch_gemv_norm(Wg, Wu, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H,
                                      wait_gate ? &wait : nullptr, s));
             wait_gate = false;
@@ -419,10 +465,11 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H, w8), B, 2 * F, true, m, mb, w8, s));
         }
 
-        ST_TRY(prof_tag(c, PSV_OP_DOWN));
+        if (!seg_mlp) ST_TRY(prof_tag(c, PSV_OP_DOWN));
         delta = delta_m;
         delta_splits = 1;
-        if (vec) {
+        if (seg_mlp) {
+        } else if (vec) {
             HIP_TRY(launch_gemv(Wd, Mat{}, m, delta_m, B, H, F, s));
         } else {
             if (!gemm_sk_supported(B, H, F)) return PSV_ERR_UNSUPPORTED;
@@ -431,7 +478,14 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             delta_splits = gemm_sk_splits(B, H, F, w8);
         }
 
-        ST_TRY(comm_window(c, l, 1, batch, le, take_pre(l, 1), &ln, &wait, &wait_qkv, &side_used));
+        {
+            uint32_t held = 1u << PSV_OP_QKV;
+            if (seg_attn && l + 1 < le) {     // every K/V tile has a wave of its own; O if its first pass covers the matrix
+                if (plan_has_whole(c, l, 1, l + 1, PSV_OP_ATTN)) held |= 1u << PSV_OP_ATTN;
+                if (plan_has_whole(c, l, 1, l + 1, PSV_OP_O) && seg_attn_holds_o(H, nq, w8, blocks)) held |= 1u << PSV_OP_O;
+            }
+            ST_TRY(comm_window(c, l, 1, batch, le, take_pre(l, 1), held, &ln, &wait, &wait_qkv, &side_used));
+        }
         res = y;
     }
     ST_TRY(prof_tag(c, -2));

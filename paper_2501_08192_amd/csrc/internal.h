@@ -82,6 +82,33 @@ bool gemv_merge_supported(int batch, int nq, int n_chunks);
 hipError_t launch_gemv_merge(Mat W, const float *part_ml, const float *part_o, int nq, int nkv,
                              int n_chunks, float *out_attn, float *out, int batch, int N, hipStream_t s);
 
+// ---- fused kernels of the vector path (segment.hip): all operators between two communication windows in one launch
+// of `blocks` workgroups (one per CU, all resident).  Phases hand their results over through buffers of tagged values
+// ({value, tag} pairs, 8 bytes each); `tag` must be unique per launch (next_tag).  *err: bit 0 = the wait for the
+// window's end expired (wait != null), bit 1 = a hand-over poll expired (results invalid).
+unsigned next_tag();
+// MLP block: y = res + delta; h = rmsnorm(y) * gain; m = silu(Wg h) * (Wu h); out = Wd m.  m_ll: [batch][F] pairs.
+// wait != null: launched into the window ahead of its inputs, see GemvWait; hold_down = false makes that variant
+// request the down weights only after the window's end (the plan did not hand them to this window).
+bool seg_mlp_supported(int batch, int H, int F);
+// does the first pass of the down projection (the part requested at the start of the kernel) cover all of W_down?
+bool seg_mlp_holds_down(int H, int F, bool w8, int blocks);
+hipError_t launch_seg_mlp(Mat Wg, Mat Wu, Mat Wd, const float *res, const float *delta, const uint16_t *gain, float eps,
+                          float *out_res, float *out_h, void *m_ll, float *out, int batch, int H, int F, unsigned tag,
+                          unsigned *err, const GemvWait *wait, bool hold_down, int blocks, hipStream_t s);
+
+// Attention block of one sequence: x = res + delta; h = rmsnorm(x) * gain; qkv = Wq h; rotary embedding, KV append and
+// decode attention over 256-token chunks (workgroup kvh * n_chunks + c runs chunk c of kv head kvh); out = Wo attn.
+// qkv_ll: [QR] pairs; pml_ll: [nkv][n_chunks][16][2] pairs; po_ll: [nkv][n_chunks][G][128] pairs.  bf16 cache only.
+// hold_kv / hold_o: see hold_down.
+int seg_attn_chunks(uint32_t max_seq);
+bool seg_attn_supported(int batch, int H, int nq, int nkv, uint32_t max_seq, bool kv_int8, int blocks);
+bool seg_attn_holds_o(int H, int nq, bool w8, int blocks);      // the first pass of the O projection covers all of W_o
+hipError_t launch_seg_attn(Mat Wq, Mat Wo, const float *res, const float *delta, const uint16_t *gain, float eps,
+                           float *out_res, float *out_h, void *qkv_ll, const float2 *rope, KvView kv, int nq, int nkv,
+                           int n_chunks, void *pml_ll, void *po_ll, float *out_attn, float *out, int H, unsigned tag,
+                           unsigned *err, const GemvWait *wait, bool hold_kv, bool hold_o, int blocks, hipStream_t s);
+
 // Split-K skinny GEMM on the matrix cores with the activation slab shared through LDS:
 // part[split][b][r] = partial sums of W[r].x[b] (rows >= split_row come from W2), to be summed in split
 // order by launch_sk_reduce or launch_resid_sum.  x_bf16: see the operand formats above.

@@ -55,6 +55,7 @@ extern "C" psv_status psv_decode_step_static(const psv_model_desc *desc, const p
     c.main = static_cast<hipStream_t>(stream);
     c.side = nullptr;                       // never used: no windows, no prefetch
     c.device = dev;
+    if (hipDeviceGetAttribute(&c.cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) c.cus = 0;
     c.ws = ws;
     c.wsp = static_cast<char *>(g_scratch_ptr[dev]);
     c.weights.resize(desc->n_layers);

@@ -22,7 +22,8 @@ class Session:
     layers: which layers to materialise (default all); others cannot be run.
     """
 
-    def __init__(self, w: synth.Workload, seed=2501, device="cuda:0", layers=None, pool_slack_blocks=0, max_seq=None):
+    def __init__(self, w: synth.Workload, seed=2501, device="cuda:0", layers=None, pool_slack_blocks=0, max_seq=None,
+                 fused=False):
         if not torch.cuda.is_available():
             raise RuntimeError("the PRESERVE decode path needs a GPU; there is no CPU fallback")
         self.w = w
@@ -49,6 +50,8 @@ class Session:
             self._spare_streams.append(self.side)
         else:
             self.ctx = psv.psv_create(self.desc, self.main, self.side)
+        if fused:
+            psv.psv_set_fused_kernels(self.ctx, True)
         self.pool_blocks = w.pool_blocks + int(pool_slack_blocks)
         self.weights, self.k_pools, self.v_pools = {}, {}, {}
         for l in self.layers:
