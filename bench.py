@@ -1,10 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the PRESERVE decode step on one MI355X.
 
-A "step" is one pass of the whole hot path (all layers: norms, QKV, RoPE + KV append, decode
-attention, O, comm window #1 || prefetch, gate/up + SwiGLU, down, comm window #2 || prefetch) over one
-batch of synthetic input that is already resident in HBM.  The default workload is c2, one TP=8 shard
-of a Llama-3-8B-shaped model (the configuration the metric is quoted on).  Prints ONE JSON line.
+A "step" is one pass of the whole hot path (all layers: norms, QKV, RoPE + KV append, decode attention, O, comm
+window #1 || prefetch, gate/up + SwiGLU, down, comm window #2 || prefetch) over one batch of synthetic input that is
+already resident in HBM.  The default workload is c2, one TP=8 shard of a Llama-3-8B-shaped model (the configuration
+the metric is quoted on).  Prints ONE JSON line.
+
+Protocol (per mode: prefetch off, prefetch on into the memory-side cache only, prefetch on with the policy's
+`prelaunch` extension):
+  * W untimed steps, then exactly K steps between two full synchronisations -> mean us/layer (`value`,
+    `us_per_layer_prefetch_off`, `us_per_layer_cache_only`);
+  * K more steps, each bracketed by a pair of events on the caller's stream -> median, p10 and p90 per step;
+  * when a step moves less than the memory-side cache holds (the small workload), the same K event-timed steps again
+    with 1 GiB streamed through the GPU before each one, outside the timed region, so that the step starts from HBM
+    as a multi-GB model would ("cold"); the back-to-back numbers are then the "hot" ones.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2] [--budget-mb 64] ...
 """
@@ -19,6 +28,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0
+CACHE_BYTES = 256 << 20          # memory-side cache of the device
+FLUSH_BYTES = 1 << 30
 
 
 def parse():
@@ -43,6 +54,8 @@ def parse():
     ap.add_argument("--tune", type=int, default=0,
                     help="1 = let the library time its candidate attention splits on layer 0 first (psv_tune_attention); "
                          "the default split is within ~1 %% of the tuned one on the five workloads")
+    ap.add_argument("--fused", type=int, default=0,
+                    help="1 = fused kernels per inter-window segment at batch 1 (psv_set_fused_kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = auto)")
     ap.add_argument("--seed", type=int, default=2501)
@@ -52,8 +65,12 @@ def parse():
                          "measurement precision), w8 / kv8 (only the weights / only the cache in int8)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="also launch one plain copy kernel of this size (known bytes, to scale hardware counters)")
-    ap.add_argument("--fused", type=int, default=1, help="0 = one kernel per operator everywhere (psv_set_fused_kernels)")
     ap.add_argument("--skip-kernel-table", action="store_true", help="omit the per-operator event timing passes")
+    ap.add_argument("--skip-cold", action="store_true", help="omit the cold-cache pass of small workloads")
+    ap.add_argument("--also", default="c1,c3,c4,c5",
+                    help="other workloads measured by the same code on their first layers (real shapes; default policy) and "
+                         "reported under other_workloads; empty = none")
+    ap.add_argument("--also-layers", type=int, default=4)
     return ap.parse_args()
 
 
@@ -72,6 +89,31 @@ def time_steps(sess, steps, warmup):
     return (time.perf_counter() - t0) * 1e3 / steps
 
 
+def event_steps(sess, steps, flush=None):
+    """K steps, each between two events on the caller's (main) stream; `flush` (a device buffer) is streamed through the
+    GPU before each step, outside the timed region.  Returns the sorted step times in us."""
+    import torch
+    from paper_2501_08192_amd import binding as psv
+    pairs = []
+    for _ in range(steps):
+        if flush is not None:
+            psv.psv_prefetch_region(flush, flush.numel(), 1024, sess.main)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(sess.main)
+        sess.step()
+        e1.record(sess.main)
+        pairs.append((e0, e1))
+    sess.sync()
+    torch.cuda.synchronize()
+    return sorted(a.elapsed_time(b) * 1e3 for a, b in pairs)
+
+
+def spread(us_sorted, layers):
+    n = len(us_sorted)
+    pick = lambda q: us_sorted[min(n - 1, max(0, int(round(q * (n - 1)))))] / layers
+    return {"median": round(pick(0.5), 3), "p10": round(pick(0.1), 3), "p90": round(pick(0.9), 3)}
+
+
 def profile_op(sess, op, steps):
     """Average duration (us) of one operator's kernel, bracketed by HIP events on the main stream."""
     from paper_2501_08192_amd import binding as psv
@@ -80,7 +122,7 @@ def profile_op(sess, op, steps):
         sess.step()
     ms, n = psv.psv_get_profile(sess.ctx)
     psv.psv_set_profile_op(sess.ctx, -1)
-    return ms * 1e3 / max(1, n), n
+    return (ms * 1e3 / n if n else 0.0), n
 
 
 def cpu_baseline(sess, n_layers, target_s=10.0, max_reps=40):
@@ -105,15 +147,56 @@ def cpu_baseline(sess, n_layers, target_s=10.0, max_reps=40):
     return total * 1e6 / (reps * len(host)), len(host), reps, oracle.num_threads()
 
 
+def other_workload(name, n_layers, steps, warmup, seed):
+    """The same three modes on the first layers of another workload (its real shape; more layers would only repeat
+    them).  Each of these moves far more per step than the memory-side cache holds, except the small c1, which is
+    measured whole, hot and cold."""
+    import torch
+    from paper_2501_08192_amd import binding as psv
+    from paper_2501_08192_amd import synth
+    from paper_2501_08192_amd.harness import Session, default_policy
+    w = synth.WORKLOADS[name]
+    L = min(n_layers, w.n_layers)
+    with Session(w, seed=seed, layers=list(range(L))) as sess:
+        modes = {"off": psv.prefetch_policy(mode=0), "cache_only": default_policy(w, prelaunch=0), "on": default_policy(w)}
+        flush = None
+        if w.layer_bytes * L < CACHE_BYTES * 2:
+            flush = torch.empty(FLUSH_BYTES, dtype=torch.uint8, device="cuda").zero_()
+        res = {"layers_run": L, "layers_total": w.n_layers, "layer_bytes": w.layer_bytes, "us_per_layer": {}, "step_us_per_layer": {}}
+        outs = {}
+        for mode, pol in modes.items():
+            sess.set_policy(pol)
+            outs[mode] = sess.run().clone()
+            res["us_per_layer"][mode] = round(time_steps(sess, steps, warmup) * 1e3 / L, 3)
+            res["step_us_per_layer"][mode] = spread(event_steps(sess, steps), L)
+            if flush is not None:
+                res.setdefault("cold_step_us_per_layer", {})[mode] = spread(event_steps(sess, steps, flush), L)
+        u = res["us_per_layer"]
+        res["speedup_cache_only"] = round(u["off"] / u["cache_only"], 4)
+        res["speedup_prelaunch"] = round(u["off"] / u["on"], 4)
+        if flush is not None:
+            cs = res["cold_step_us_per_layer"]
+            res["cold_speedup_cache_only"] = round(cs["off"]["median"] / cs["cache_only"]["median"], 4)
+            res["cold_speedup_prelaunch"] = round(cs["off"]["median"] / cs["on"]["median"], 4)
+        win = sum(w.window_us)
+        res["hbm_frac_outside_windows"] = {m: round(w.layer_bytes / max(1e-9, u[m] - win) / 1e3 / HBM_PEAK_GBPS, 4) for m in ("off", "on")}
+        res["on_off_bit_identical"] = bool(torch.equal(outs["off"], outs["on"]) and torch.equal(outs["off"], outs["cache_only"]))
+    del flush
+    torch.cuda.empty_cache()
+    return res
+
+
 def stored_traffic(workload, kernel):
-    """HBM bytes per launch of a kernel from the committed rocprofv3 PMC summary (None if there is none)."""
+    """HBM bytes per launch of a kernel as recorded in the committed rocprofv3 counter summary of this workload:
+    (bytes, path of the summary) or (None, None).  A stored figure from an earlier profiler run, not a measurement
+    of this run -- hardware counters cannot be read from inside the benchmark."""
     import re
-    path = os.path.join(ROOT, "profiles", "%s_pmc_hbm_traffic.md" % workload)
+    rel = os.path.join("profiles", "%s_pmc_hbm_traffic.md" % workload)
     try:
-        m = re.search(r"traffic_bytes_per_launch\[%s,%s\]\s*=\s*(\d+)" % (workload, kernel), open(path).read())
-        return int(m.group(1)) if m else None
+        m = re.search(r"traffic_bytes_per_launch\[%s,%s\]\s*=\s*(\d+)" % (workload, kernel), open(os.path.join(ROOT, rel)).read())
+        return (int(m.group(1)), rel) if m else (None, None)
     except OSError:
-        return None
+        return None, None
 
 
 def main():
@@ -139,40 +222,46 @@ def main():
         w = w.scaled(weight_format="int8" if a.format in ("int8", "w8") else "bf16",
                      kv_format="int8" if a.format in ("int8", "kv8") else "bf16")
     layers = list(range(a.layers)) if a.layers else None
-    sess = Session(w, seed=a.seed, layers=layers)
+    sess = Session(w, seed=a.seed, layers=layers, fused=bool(a.fused))
     L = len(sess.layers)
     MB = 1 << 20
     if a.budget_mb <= 0:
         a.budget_mb = min(192.0, max(w.window_us) * 4.5)
     if a.partial < 0:
         a.partial = 1 if w.paged else 0
-    # with no flags this is harness.default_policy(w), the configuration the full-size parity tests run
-    on = default_policy(w, targets=a.targets, budget_bytes=int(a.budget_mb * MB),
-                        chunk_bytes=int(a.chunk_mb * MB), cu_budget=a.cu_budget, partial=a.partial, join=a.join,
-                        prelaunch=a.prelaunch)
-    off = psv.prefetch_policy(mode=0)
+    # with no flags `on` is harness.default_policy(w), the configuration the full-size parity tests run
+    kw = dict(targets=a.targets, budget_bytes=int(a.budget_mb * MB), chunk_bytes=int(a.chunk_mb * MB),
+              cu_budget=a.cu_budget, partial=a.partial, join=a.join)
+    modes = {"off": psv.prefetch_policy(mode=0),
+             "cache_only": default_policy(w, prelaunch=0, **kw),        # the paper's scheme: every prefetch goes to the cache
+             "on": default_policy(w, prelaunch=a.prelaunch, **kw)}
 
-    psv.psv_set_fused_kernels(sess.ctx, bool(a.fused))
     attn_chunk = sess.tune_attention() if a.tune else 0
+    step_bytes = w.layer_bytes * L
+    flush = None
+    if step_bytes < CACHE_BYTES * 2 and not a.skip_cold:      # the whole step (nearly) fits the memory-side cache
+        flush = torch.empty(FLUSH_BYTES, dtype=torch.uint8, device="cuda").zero_()
 
-    # prefetch off (vanilla execution) and on, same launch configuration otherwise
-    sess.set_policy(off)
-    x_off = sess.run().clone()
-    ms_off = time_steps(sess, a.steps, a.warmup)
-    sess.set_policy(on)
-    x_on = sess.run().clone()
-    ms_on = time_steps(sess, a.steps, a.warmup)
-    identical = bool(torch.equal(x_off, x_on))
+    ms, hot, cold, outputs = {}, {}, {}, {}
+    for name, pol in modes.items():
+        sess.set_policy(pol)
+        outputs[name] = sess.run().clone()
+        ms[name] = time_steps(sess, a.steps, a.warmup)
+        hot[name] = spread(event_steps(sess, a.steps), L)
+        if flush is not None:
+            cold[name] = spread(event_steps(sess, max(10, min(a.steps, 60)), flush), L)
+    identical = bool(torch.equal(outputs["off"], outputs["on"]) and torch.equal(outputs["off"], outputs["cache_only"]))
     stats = psv.psv_get_stats(sess.ctx)
+    prelaunch_active = bool(a.prelaunch) and bool(sess.overlap) and (w.batch == 1 or (w.batch == 2 and w.hidden <= 4096))
 
-    us_off, us_on = ms_off * 1e3 / L, ms_on * 1e3 / L
+    us = {k: v * 1e3 / L for k, v in ms.items()}
     win = sum(w.window_us)
     layer_bytes = stats["weight_bytes_per_layer"] + stats["kv_bytes_per_layer"]
-    eff_off = layer_bytes / max(1e-9, (us_off - win)) / 1e3          # GB/s outside the windows
-    eff_on = layer_bytes / max(1e-9, (us_on - win)) / 1e3
+    eff = {k: layer_bytes / max(1e-9, (v - win)) / 1e3 for k, v in us.items()}          # GB/s outside the windows
 
-    # per-operator kernel durations (events attached to the kernel dispatches), prefetch off and on; the
-    # dominant kernel -- gate/up projection + SwiGLU, HBM-bound -- carries the roofline entry
+    # per-operator kernel durations (events attached to the kernel dispatches: end of the previous kernel on the stream
+    # to the end of this one), prefetch off and on; the dominant kernel -- gate/up projection + SwiGLU, HBM-bound --
+    # carries the roofline entry
     qkv_rows = (w.n_q_heads + 2 * w.n_kv_heads) * w.head_dim
     wb = 1 if w.weight_format == "int8" else 2          # bytes per weight
     op_bytes = {"qkv": wb * qkv_rows * w.hidden, "attn": stats["kv_bytes_per_layer"],
@@ -189,29 +278,38 @@ def main():
         torch.cuda.synchronize()
         psv.psv_copy_bytes(dst, src, nb, sess.main)
         sess.sync()
-    for mode_name, pol in (("off", off), ("on", on)):
+    for mode_name in ("off", "on"):
         if a.skip_kernel_table and mode_name == "on":
             break
-        sess.set_policy(pol)
+        sess.set_policy(modes[mode_name])
         for name, op in op_ids.items():
-            us, n = profile_op(sess, op, n_prof)
-            kernels.setdefault(name, {"bytes": op_bytes[name]})
-            kernels[name]["us_" + mode_name] = round(us, 3)
-            kernels[name]["gbps_" + mode_name] = round(op_bytes[name] / us / 1e3, 1) if us > 0 else None
-            kernels[name]["launches"] = n
+            t, n = profile_op(sess, op, n_prof)
+            k = kernels.setdefault(name, {"bytes": op_bytes[name]})
+            k["launches"] = n
+            if n == 0:                      # fused into the kernel of the operator that opens its segment
+                k["us_" + mode_name] = None
+                continue
+            k["us_" + mode_name] = round(t, 3)
+            launched_into_window = mode_name == "on" and prelaunch_active and name in ("qkv", "gate_up")
+            if launched_into_window:
+                # its weights were requested while the window ran: the time left after the window is no bandwidth figure
+                k["us_after_window_on"] = round(t, 3)
+                del k["us_on"]
+            elif not a.fused:
+                k["gbps_" + mode_name] = round(op_bytes[name] / t / 1e3, 1)
     gate_us, gate_n = kernels["gate_up"]["us_off"], kernels["gate_up"]["launches"]
-    gate_us_on = kernels["gate_up"].get("us_on", float("nan"))
-    gate_bytes = op_bytes["gate_up"]
+    gate_bytes = op_bytes["gate_up"] + (op_bytes["down"] if a.fused and kernels["down"]["launches"] == 0 else 0)
     achieved = gate_bytes / gate_us / 1e3
+    traffic, traffic_src = stored_traffic(w.name, "gate_up") if (a.format == "bf16" and not a.fused) else (None, None)
 
     out = {
         "metric": "decode_step_latency_us_per_layer_prefetch_on",
-        "value": round(us_on, 3),
+        "value": round(us["on"], 3),
         "unit": "us/layer",
         "n_gpus": 1,
         "steps": a.steps,
         "warmup": a.warmup,
-        "ms_per_step": round(ms_on, 5),
+        "ms_per_step": round(ms["on"], 5),
         "higher_is_better": False,
         "scaling": "weak",
         "vs_baseline": None,
@@ -222,25 +320,37 @@ def main():
                                "windows %g/%g us" % (w.name, L, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch,
                                                       w.context, "paged" if w.paged else "contiguous", *w.window_us),
                    "prefetch_budget_mb": a.budget_mb, "cu_budget": a.cu_budget, "chunk_mb": a.chunk_mb,
-                   "partial": a.partial, "join": a.join, "prelaunch": a.prelaunch, "targets": a.targets,
-                   "streams_overlap": bool(sess.overlap),
+                   "partial": a.partial, "join": a.join, "prelaunch": a.prelaunch, "prelaunch_active": prelaunch_active,
+                   "targets": a.targets, "fused_kernels": bool(a.fused), "streams_overlap": bool(sess.overlap),
                    "attn_tokens_per_workgroup": attn_chunk if a.tune else "default"},
-        "us_per_layer_prefetch_off": round(us_off, 3),
-        "prefetch_speedup": round(us_off / us_on, 4),
+        "us_per_layer_prefetch_off": round(us["off"], 3),
+        "us_per_layer_cache_only": round(us["cache_only"], 3),
+        "prefetch_speedup": round(us["off"] / us["on"], 4),
+        "speedup_cache_only": round(us["off"] / us["cache_only"], 4),          # the paper's method alone
+        "speedup_prelaunch": round(us["off"] / us["on"], 4),                   # with the first consumer launched into the window
+        "step_us_per_layer": {k: hot[k] for k in ("off", "cache_only", "on")},    # per-step event pairs: median, p10, p90
         "on_off_bit_identical": identical,
         "layer_bytes": layer_bytes,
         "planned_prefetch_bytes_per_step": stats["planned_prefetch_bytes"],
-        "effective_hbm_gbps_outside_windows": {"prefetch_off": round(eff_off, 1), "prefetch_on": round(eff_on, 1),
+        "effective_hbm_gbps_outside_windows": {"prefetch_off": round(eff["off"], 1), "prefetch_on": round(eff["on"], 1),
                                                 "peak": HBM_PEAK_GBPS,
-                                                "frac_off": round(eff_off / HBM_PEAK_GBPS, 4),
-                                                "frac_on": round(eff_on / HBM_PEAK_GBPS, 4)},
-        "roofline": {"bound": "hbm", "kernel": "gate/up projection + SwiGLU (prefetch off)",
+                                                "frac_off": round(eff["off"] / HBM_PEAK_GBPS, 4),
+                                                "frac_on": round(eff["on"] / HBM_PEAK_GBPS, 4)},
+        "roofline": {"bound": "hbm", "kernel": ("gate/up + SwiGLU + down, fused (prefetch off)" if gate_bytes != op_bytes["gate_up"]
+                                                else "gate/up projection + SwiGLU (prefetch off)"),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": stored_traffic(w.name, "gate_up") if a.format == "bf16" else None,
-                     "bytes_per_launch": gate_bytes, "avg_us": round(gate_us, 3), "launches": gate_n,
-                     "avg_us_prefetch_on": round(gate_us_on, 3),
-                     "achieved_prefetch_on": round(gate_bytes / gate_us_on / 1e3, 1)},
+                     "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
+                     "traffic_source": ("stored: %s (rocprofv3 counters of an earlier run of this kernel; not measured by this run)"
+                                        % traffic_src) if traffic is not None else None,
+                     "bytes_per_launch": gate_bytes, "avg_us": round(gate_us, 3), "launches": gate_n},
     }
+    if cold:
+        out["cold_cache"] = {"rule": "%d MiB streamed through the GPU before every timed step, outside the timed region"
+                                     % (FLUSH_BYTES >> 20),
+                             "step_us_per_layer": cold,
+                             "speedup_cache_only": round(cold["off"]["median"] / cold["cache_only"]["median"], 4),
+                             "speedup_prelaunch": round(cold["off"]["median"] / cold["on"]["median"], 4)}
+        out["hot_cache_note"] = "back-to-back steps of this workload run from the memory-side cache: step_us_per_layer and value are hot numbers"
     out["kernels"] = kernels
     if not a.no_cpu_baseline:
         # whole step when a layer is cheap; otherwise the first layers whose oracle cost is ~10-30 s
@@ -251,6 +361,12 @@ def main():
                                "sample": "fp64 C oracle, first %d of %d layers of the same workload, %d repetitions"
                                          % (n_done, L, reps)}
     sess.close()
+    del sess, flush
+    torch.cuda.empty_cache()
+    others = [n for n in a.also.split(",") if n and n != a.workload]
+    if others and a.format == "bf16" and not a.fused and a.window_us is None:
+        out["other_workloads"] = {n: other_workload(n, a.also_layers, max(10, min(a.steps, 50)), min(a.warmup, 10), a.seed)
+                                  for n in others}
     print(json.dumps(out))
 
 
