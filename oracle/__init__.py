@@ -19,7 +19,7 @@ _lib = None
 class _Model(C.Structure):
     _fields_ = [("hidden", C.c_int32), ("n_q_heads", C.c_int32), ("n_kv_heads", C.c_int32),
                 ("head_dim", C.c_int32), ("ffn", C.c_int32), ("block_tokens", C.c_int32),
-                ("rms_eps", C.c_double), ("rope_theta", C.c_double)]
+                ("rms_eps", C.c_double), ("rope_theta", C.c_double), ("kv_token_major", C.c_int32)]
 
 
 class _LayerWeights(C.Structure):
@@ -107,9 +107,9 @@ def _ptr(a):
 
 
 def model(hidden, n_q_heads, n_kv_heads, head_dim, ffn, block_tokens=16, rms_eps=1e-5,
-          rope_theta=500000.0):
+          rope_theta=500000.0, kv_token_major=False):
     return _Model(int(hidden), int(n_q_heads), int(n_kv_heads), int(head_dim), int(ffn),
-                  int(block_tokens), float(rms_eps), float(rope_theta))
+                  int(block_tokens), float(rms_eps), float(rope_theta), 1 if kv_token_major else 0)
 
 
 # ---- elementary pieces -------------------------------------------------------------------

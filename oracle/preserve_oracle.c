@@ -98,14 +98,22 @@ static size_t kv_block_of(const orc_kv *kv, int b, int t, int bt)
     return kv->page_table ? (size_t)kv->page_table[logical] : logical;
 }
 
+static size_t tm_index(const orc_model *m, size_t block, int kvh, int row, int c)
+{
+    return ((block * (size_t)m->block_tokens + (size_t)row) * (size_t)m->n_kv_heads + (size_t)kvh)
+               * (size_t)m->head_dim + (size_t)c;
+}
+
 static size_t k_index(const orc_model *m, size_t block, int kvh, int row, int c)
 {
+    if (m->kv_token_major) return tm_index(m, block, kvh, row, c);
     return ((block * (size_t)m->n_kv_heads + (size_t)kvh) * (size_t)m->block_tokens + (size_t)row)
                * (size_t)m->head_dim + (size_t)c;
 }
 
 static size_t v_index(const orc_model *m, size_t block, int kvh, int row, int c)
 {
+    if (m->kv_token_major) return tm_index(m, block, kvh, row, c);
     return ((block * (size_t)m->n_kv_heads + (size_t)kvh) * (size_t)m->head_dim + (size_t)c)
                * (size_t)m->block_tokens + (size_t)row;
 }

@@ -16,9 +16,12 @@
  * one per MLP block).  With a single rank the allreduce is the identity, so the communication
  * window has no numeric effect and does not appear here.
  *
- * KV-cache layout (bt = tokens per block, d = head dim, nkv = local kv heads):
+ * KV-cache layout (bt = tokens per block, d = head dim, nkv = local kv heads), head-major (the default):
  *   K pool : [block][kv head][bt tokens][d]      (token-major inside a block)
  *   V pool : [block][kv head][d][bt tokens]      (channel-major inside a block)
+ * Token-major layout (orc_model.kv_token_major; bf16 cache only): both pools [block][bt tokens][kv head][d], the
+ * layout in which a shard with several local kv heads reads one head's keys and values strided (Section 4, the
+ * discussion of the tensor-parallel degree).  Same logical cache, same results.
  * The block that holds token t of sequence b is page_table[b*max_blocks + t/bt], or
  * b*max_blocks + t/bt when page_table is NULL ("contiguous" cache).
  */
@@ -41,6 +44,7 @@ typedef struct {
     int32_t block_tokens;  /* bt */
     double  rms_eps;
     double  rope_theta;    /* 0 => no positional rotation */
+    int32_t kv_token_major; /* 0 => head-major pools, 1 => token-major pools (see above) */
 } orc_model;
 
 typedef struct {

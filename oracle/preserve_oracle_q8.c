@@ -108,6 +108,7 @@ int orc_decode_layer_x(const orc_model *m, const orc_layer_weights_x *w, const o
     int H = m->hidden, nq = m->n_q_heads, nkv = m->n_kv_heads, d = m->head_dim, F = m->ffn;
     int bt = m->block_tokens;
     if (H <= 0 || nq <= 0 || nkv <= 0 || d <= 0 || (d & 1) || F <= 0 || bt <= 0 || nq % nkv) return -1;
+    if (m->kv_token_major && kv->kv_int8) return -1;      /* the token-major layout is defined for the bf16 cache only */
     int qkv_rows = (nq + 2 * nkv) * d;
 
     double *h   = (double *)malloc((size_t)H * sizeof(double));
@@ -142,9 +143,15 @@ int orc_decode_layer_x(const orc_model *m, const orc_layer_weights_x *w, const o
             } else {
                 uint16_t *kp = (uint16_t *)kv->k_pool, *vp = (uint16_t *)kv->v_pool;
                 size_t base = blk * (size_t)nkv + (size_t)kvh;
+                size_t tm = ((blk * (size_t)bt + (size_t)r) * (size_t)nkv + (size_t)kvh) * (size_t)d;   /* token-major row */
                 for (int c = 0; c < d; ++c) {
-                    kp[(base * (size_t)bt + (size_t)r) * (size_t)d + (size_t)c] = orc_f64_to_bf16(kn[c]);
-                    vp[(base * (size_t)d + (size_t)c) * (size_t)bt + (size_t)r] = orc_f64_to_bf16(vn[c]);
+                    if (m->kv_token_major) {
+                        kp[tm + (size_t)c] = orc_f64_to_bf16(kn[c]);
+                        vp[tm + (size_t)c] = orc_f64_to_bf16(vn[c]);
+                    } else {
+                        kp[(base * (size_t)bt + (size_t)r) * (size_t)d + (size_t)c] = orc_f64_to_bf16(kn[c]);
+                        vp[(base * (size_t)d + (size_t)c) * (size_t)bt + (size_t)r] = orc_f64_to_bf16(vn[c]);
+                    }
                 }
             }
         }

@@ -455,3 +455,62 @@ def test_bad_arguments_are_rejected():
         oracle.decode_layer(m, w, k, v, None, 3, [0, 5, 5], x)        # empty span
     with pytest.raises(ValueError):
         oracle.decode_layer(m, w, k, v, None, 3, [13, 5, 5], x)       # beyond the page-table row
+
+
+# ---- token-major cache layout: same logical cache, other addresses ------------------------------------------
+
+@pytest.mark.parametrize("theta", [0.0, 10000.0])
+@pytest.mark.parametrize("nq,nkv", [(4, 2), (6, 3), (4, 1)])
+def test_token_major_layout_matches_torch_composition_and_head_major_bitwise(theta, nq, nkv):
+    """Pools [block, token, kv head, channel] (the layout in which several local kv heads make one head's reads
+    strided) against the torch composition and, bit for bit, against the head-major run of the same logical cache;
+    the appended rows land at the token-major addresses (read back through the helper's own restatement of the
+    layout) and nothing else moves."""
+    rng = np.random.default_rng(40 + nq + nkv)
+    B, H, d, F_, T = 3, 24, 8, 20, 21
+    m_hm = oracle.model(H, nq, nkv, d, F_, block_tokens=BT, rope_theta=theta)
+    m_tm = oracle.model(H, nq, nkv, d, F_, block_tokens=BT, rope_theta=theta, kv_token_major=True)
+    w = random_layer(rng, H, nq, nkv, d, F_, std=0.3)
+    kd = rng.normal(0, 1, (B, nkv, T, d)); vd = rng.normal(0, 1, (B, nkv, T, d))
+    mb = (T + BT - 1) // BT
+    pool = B * mb + 3
+    pt = rng.permutation(pool)[: B * mb].astype(np.int32).reshape(B, mb)
+    x = rng.normal(0, 1, (B, H))
+    k0, v0 = fill_pools(kd, vd, BT, page_table=pt, n_blocks=pool)
+    k1, v1 = fill_pools(kd, vd, BT, page_table=pt, n_blocks=pool, token_major=True)
+    assert k1.shape == (pool, BT, nkv, d) and not np.array_equal(v0.reshape(-1), v1.reshape(-1))
+    assert np.array_equal(k0.reshape(-1), k1.reshape(-1)) == (nkv == 1)      # with one kv head the K pools coincide
+    kq, vq = dense_from_pools(k1, v1, B, T, page_table=pt, token_major=True)
+    a = oracle.decode_layer(m_hm, w, k0, v0, pt, mb, [T] * B, x)
+    b = oracle.decode_layer(m_tm, w, k1, v1, pt, mb, [T] * B, x)
+    assert np.array_equal(a, b)
+    want, kn, vn = _torch_layer(m_tm, w, kq, vq, T, x)
+    assert np.allclose(b, want, rtol=1e-11, atol=1e-12)
+    ka, va = dense_from_pools(k0, v0, B, T, page_table=pt)
+    kb, vb = dense_from_pools(k1, v1, B, T, page_table=pt, token_major=True)
+    assert np.array_equal(ka, kb) and np.array_equal(va, vb)
+    assert np.array_equal(kb[:, :, T - 1], kn) and np.array_equal(vb[:, :, T - 1], vn)
+    assert np.array_equal(kb[:, :, : T - 1], kq[:, :, : T - 1]) and np.array_equal(vb[:, :, : T - 1], vq[:, :, : T - 1])
+    # reading token-major pools as head-major must NOT give the same result (the switch does something)
+    if nkv > 1:
+        k2, v2 = fill_pools(kd, vd, BT, page_table=pt, n_blocks=pool, token_major=True)
+        c = oracle.decode_layer(m_hm, w, k2.reshape(pool, nkv, BT, d), v2.reshape(pool, nkv, d, BT), pt, mb, [T] * B, x)
+        assert not np.allclose(c, a)
+
+
+def test_token_major_layout_with_int8_weights_and_refusal_for_int8_cache():
+    rng = np.random.default_rng(47)
+    B, H, nq, nkv, d, F_, T = 2, 16, 4, 2, 8, 12, 9
+    m_hm = oracle.model(H, nq, nkv, d, F_, block_tokens=BT)
+    m_tm = oracle.model(H, nq, nkv, d, F_, block_tokens=BT, kv_token_major=True)
+    w = random_layer(rng, H, nq, nkv, d, F_, std=0.3)
+    kd = rng.normal(0, 1, (B, nkv, T, d)); vd = rng.normal(0, 1, (B, nkv, T, d))
+    mb = (T + BT - 1) // BT
+    x = rng.normal(0, 1, (B, H))
+    k0, v0 = fill_pools(kd, vd, BT)
+    k1, v1 = fill_pools(kd, vd, BT, token_major=True)
+    a = oracle.decode_layer_x(m_hm, w, k0, v0, None, mb, [T] * B, x)       # the general-format entry point, bf16 everywhere
+    b = oracle.decode_layer_x(m_tm, w, k1, v1, None, mb, [T] * B, x)
+    assert np.array_equal(a, b)
+    assert np.array_equal(dense_from_pools(k0, v0, B, T)[0], dense_from_pools(k1, v1, B, T, token_major=True)[0])
+    assert np.array_equal(dense_from_pools(k0, v0, B, T)[1], dense_from_pools(k1, v1, B, T, token_major=True)[1])
