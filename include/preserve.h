@@ -22,6 +22,11 @@
  *    [block][kv head][16 tokens][128 channels] and one V pool [block][kv head][128 channels]
  *    [16 tokens].  Token t of sequence b lives in block page_table[b*max_blocks + t/16], or in
  *    block b*max_blocks + t/16 when the page table is NULL ("contiguous" cache).
+ *    With kv_layout = PSV_KV_TOKEN_MAJOR (bf16 cache only) both pools are [block][16 tokens][kv head][128 channels]
+ *    instead: the layout in which a shard with several local kv heads reads one head's keys and values as
+ *    256-byte pieces at a stride of n_kv_heads * 256 bytes (Section 4, the discussion of the tensor-parallel
+ *    degree, attributes the larger gains at 2 local kv heads to such strided reads).  Same bytes per block, same
+ *    results to rounding; offered to measure that effect.
  *  - int8 formats (the precision the paper measures in, Section 4; it gives no quantisation scheme, this
  *    one is symmetric and per row).  Weights (weight_format = PSV_FMT_INT8): int8 codes row-major
  *    [out, in] plus one fp32 scale per output row, W[r][c] = scale[r] * code[r][c]; RMSNorm gains stay
@@ -55,6 +60,7 @@ extern "C" {
 #define PSV_KV_UNIT_BYTES_INT8 2112u   /* 2048 int8 codes + 16 fp32 scales */
 
 enum { PSV_FMT_BF16 = 0u, PSV_FMT_INT8 = 1u };
+enum { PSV_KV_HEAD_MAJOR = 0u, PSV_KV_TOKEN_MAJOR = 1u };
 
 typedef int32_t psv_status;
 enum {
@@ -85,6 +91,7 @@ typedef struct {
     uint32_t max_seq;       /* largest seq_lens[b] that will be used */
     uint32_t weight_format; /* PSV_FMT_BF16 or PSV_FMT_INT8: format of the five projection matrices */
     uint32_t kv_format;     /* PSV_FMT_BF16 or PSV_FMT_INT8: format of the K and V pools */
+    uint32_t kv_layout;     /* PSV_KV_HEAD_MAJOR (default) or PSV_KV_TOKEN_MAJOR (bf16 cache only): see the conventions */
 } psv_model_desc;
 
 /* dev pointers; projection matrices in the descriptor's weight_format, gains bf16 */

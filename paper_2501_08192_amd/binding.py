@@ -17,6 +17,8 @@ PSV_OP_QKV, PSV_OP_ATTN, PSV_OP_O, PSV_OP_GATE, PSV_OP_UP, PSV_OP_DOWN = range(6
 OP_NAMES = ["qkv", "attn", "o", "gate", "up", "down"]
 PSV_FMT_BF16, PSV_FMT_INT8 = 0, 1
 FORMATS = {"bf16": PSV_FMT_BF16, "int8": PSV_FMT_INT8}
+PSV_KV_HEAD_MAJOR, PSV_KV_TOKEN_MAJOR = 0, 1
+KV_LAYOUTS = {"head": PSV_KV_HEAD_MAJOR, "token": PSV_KV_TOKEN_MAJOR}
 PSV_KV_UNIT_BYTES_BF16, PSV_KV_UNIT_BYTES_INT8 = 4096, 2112
 PSV_STATIC_SCRATCH_BYTES = 16 << 20
 PSV_DBG_H1, PSV_DBG_QKV, PSV_DBG_ATTN, PSV_DBG_Y, PSV_DBG_H2, PSV_DBG_M = range(6)
@@ -35,7 +37,8 @@ class psv_model_desc(C.Structure):
     _fields_ = [("n_layers", C.c_uint32), ("hidden", C.c_uint32), ("n_q_heads", C.c_uint32),
                 ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32), ("ffn", C.c_uint32),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("max_batch", C.c_uint32),
-                ("max_seq", C.c_uint32), ("weight_format", C.c_uint32), ("kv_format", C.c_uint32)]
+                ("max_seq", C.c_uint32), ("weight_format", C.c_uint32), ("kv_format", C.c_uint32),
+                ("kv_layout", C.c_uint32)]
 
 
 class psv_layer_weights(C.Structure):
@@ -147,9 +150,9 @@ def strerror(status):
 
 
 def model_desc(n_layers, hidden, n_q_heads, n_kv_heads, ffn, max_batch, max_seq, head_dim=128, rms_eps=1e-5,
-               rope_theta=500000.0, weight_format="bf16", kv_format="bf16"):
+               rope_theta=500000.0, weight_format="bf16", kv_format="bf16", kv_layout="head"):
     return psv_model_desc(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, rms_eps, rope_theta, max_batch,
-                          max_seq, FORMATS[weight_format], FORMATS[kv_format])
+                          max_seq, FORMATS[weight_format], FORMATS[kv_format], KV_LAYOUTS[kv_layout])
 
 
 def prefetch_policy(mode=0, targets=PSV_TARGET_WEIGHTS | PSV_TARGET_KV, budget_bytes=0, chunk_bytes=0, cu_budget=0,

@@ -86,10 +86,18 @@ struct AttnArgs {
 //    exactly the B-fragment the O^T MFMA needs.  Probabilities never leave registers.
 //  * epilogue: the 4 waves merge through LDS and the workgroup stores one partial (max, sum, O);
 //    k_attn_merge then combines the partials of a (sequence, kv head) in chunk order.
+//
+// TM: token-major cache (both pools [block][16 tokens][kv head][128 channels]).  One head's key rows are then 256-byte
+// pieces at a stride of n_kv_heads * 256 bytes -- the strided read of a shard with several local kv heads -- and are
+// loaded exactly like the head-major rows.  The value tile arrives token-major as well, but the second contraction
+// needs, per lane, eight consecutive tokens of one channel: each wave passes its 32 x 128 tile through LDS (whole
+// 256-byte token rows in, 16-byte pieces XOR-swizzled by the token's group of eight so that the transposed 2-byte
+// reads of all 64 lanes fall into different banks) and picks its fragments up transposed.
+template <bool TM>
 __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 {
     __shared__ float ms[kAttnWaves][16], ls[kAttnWaves][16];
-    __shared__ f32x4 accs[kAttnWaves][8][64];
+    __shared__ f32x4 accs[kAttnWaves][8][64];      // TM: also the waves' value tiles (4 x 8 KiB) while the loop runs
 
     const int b = blockIdx.z, kvh = blockIdx.y, c = blockIdx.x;
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, q4 = lane >> 4;
@@ -118,16 +126,27 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
         {
             const int blk = (i < 8) ? blkA : blkB;
             if (blk >= 0) {
-                const uint16_t *base = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + (tau1 & 15)) * 128 + q4 * 8;
+                const uint16_t *base = TM ? kv.k_pool + (((size_t)blk * 16 + (tau1 & 15)) * nkv + kvh) * 128 + q4 * 8
+                                          : kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + (tau1 & 15)) * 128 + q4 * 8;
+                const size_t row4 = TM ? (size_t)4 * nkv * 128 : (size_t)4 * 128;      // four tokens further
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) {
                     ka[ks] = ld16(base + ks * 32);
-                    kb[ks] = ld16(base + 4 * 128 + ks * 32);
+                    kb[ks] = ld16(base + row4 + ks * 32);
                 }
             } else {
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) { ka[ks] = zero16(); kb[ks] = zero16(); }
             }
+        }
+        if constexpr (TM) {
+            // value tile, token-major: load j brings the whole rows of tokens 4j .. 4j+3 (lane = token q4, 16-byte piece i)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int blk = j < 4 ? blkA : blkB;
+                vf[j] = blk >= 0 ? ld16(kv.v_pool + (((size_t)blk * 16 + ((4 * j + q4) & 15)) * nkv + kvh) * 128 + i * 8) : zero16();
+            }
+            return;
         }
         // V^T fragments: row = channel dg*16 + i, k-slots of lane group q4 = tokens 8*q4 .. 8*q4+7
         {
@@ -210,12 +229,18 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                 const float *vrow = qkv_b + (size_t)(nq + nkv + kvh) * 128;
                 const float lo = krow[tid], hi = krow[tid + 64];
                 const int r = pos & 15;
-                uint16_t *kdst = kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + r) * 128;
+                const size_t tm_row = (((size_t)blk * 16 + r) * nkv + kvh) * 128;
+                uint16_t *kdst = TM ? kv.k_pool + tm_row : kv.k_pool + (((size_t)blk * nkv + kvh) * 16 + r) * 128;
                 kdst[tid] = (uint16_t)f32_to_bf16(lo * cs.x - hi * cs.y);
                 kdst[tid + 64] = (uint16_t)f32_to_bf16(hi * cs.x + lo * cs.y);
-                uint16_t *vdst = kv.v_pool + ((size_t)blk * nkv + kvh) * 128 * 16 + r;
-                vdst[(size_t)tid * 16] = (uint16_t)f32_to_bf16(vrow[tid]);
-                vdst[(size_t)(tid + 64) * 16] = (uint16_t)f32_to_bf16(vrow[tid + 64]);
+                if constexpr (TM) {
+                    kv.v_pool[tm_row + tid] = (uint16_t)f32_to_bf16(vrow[tid]);
+                    kv.v_pool[tm_row + tid + 64] = (uint16_t)f32_to_bf16(vrow[tid + 64]);
+                } else {
+                    uint16_t *vdst = kv.v_pool + ((size_t)blk * nkv + kvh) * 128 * 16 + r;
+                    vdst[(size_t)tid * 16] = (uint16_t)f32_to_bf16(vrow[tid]);
+                    vdst[(size_t)(tid + 64) * 16] = (uint16_t)f32_to_bf16(vrow[tid + 64]);
+                }
             }
             __threadfence();
         }
@@ -266,6 +291,29 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
 #pragma unroll
         for (int dg = 0; dg < 8; ++dg) acc[dg] *= alpha;
 
+        if constexpr (TM) {
+            // the wave's own 8 KiB of LDS: token rows in (piece index XOR 2 * (token / 8)), fragments out transposed
+            unsigned char *vt = reinterpret_cast<unsigned char *>(&accs[w][0][0]);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const int tok = 4 * j + q4;
+                *reinterpret_cast<uint4 *>(vt + tok * 256 + ((i ^ (2 * (tok >> 3))) << 4)) = vf[j];
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int dg = 0; dg < 8; ++dg) {
+                const int piece = (2 * dg + (i >> 3)) ^ (2 * q4);        // tokens 8 q4 .. 8 q4 + 7 all have token / 8 = q4
+                const unsigned char *src = vt + (8 * q4) * 256 + (piece << 4) + (i & 7) * 2;
+                uint32_t h[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) h[e] = *reinterpret_cast<const uint16_t *>(src + e * 256);
+                vf[dg] = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();      // the next tile's rows overwrite the buffer only after these reads
+        }
         // probabilities as two bf16 fragments as well (p = hi + lo)
         uint4 pk, pkl;
         pack_split(p[0], p[1], pk.x, pkl.x);
@@ -299,7 +347,7 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
     l_part += __shfl_xor(l_part, 16, 64);
     l_part += __shfl_xor(l_part, 32, 64);
     if (q4 == 0) ms[w][i] = m_run;
-    __syncthreads();
+    __syncthreads();      // (TM: every wave is also done with its value tile in accs)
     const float M = fmaxf(fmaxf(ms[0][i], ms[1][i]), fmaxf(ms[2][i], ms[3][i]));
     const float sc = exp2f(m_run - M);
     if (q4 == 0) ls[w][i] = l_part * sc;
@@ -714,8 +762,10 @@ hipError_t launch_attn(const float *qkv, const float2 *rope, KvView kv, int batc
     AttnArgs a = attn_args(qkv, rope, kv, batch, nq, nkv, sp, part_ml, part_o, nullptr, nullptr);
     if (kv.int8)
         PSV_LAUNCH(k_attn_q8, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
+    else if (kv.token_major)
+        PSV_LAUNCH(k_attn<true>, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
     else
-        PSV_LAUNCH(k_attn, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
+        PSV_LAUNCH(k_attn<false>, dim3(sp.n_chunks, nkv, batch), dim3(256), 0, s, a);
     return hipGetLastError();
 }
 

@@ -73,6 +73,7 @@ KvView kv_view(const psv_ctx *c, uint32_t layer)
     v.k_pool = static_cast<uint16_t *>(c->k_pools[layer]);
     v.v_pool = static_cast<uint16_t *>(c->v_pools[layer]);
     v.int8 = c->d.kv_format == PSV_FMT_INT8 ? 1 : 0;
+    v.token_major = c->d.kv_layout == PSV_KV_TOKEN_MAJOR ? 1 : 0;
     v.page_table = c->kv.page_table;
     v.max_blocks = (int)c->kv.max_blocks;
     {
@@ -359,7 +360,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     // kernels run depends on the shape only, never on the policy, so every policy gives the same bits.
     const int blocks = c->fused ? c->cus : 0;
     const bool seg_mlp = vec && blocks >= 64 && seg_mlp_supported(B, H, F);
-    const bool seg_attn = vec && blocks >= 64 && seg_attn_supported(B, H, nq, nkv, d.max_seq, d.kv_format == PSV_FMT_INT8, blocks);
+    const bool seg_attn = vec && blocks >= 64 && seg_attn_supported(B, H, nq, nkv, d.max_seq, d.kv_format == PSV_FMT_INT8 || d.kv_layout != PSV_KV_HEAD_MAJOR, blocks);
     const int seg_nc = seg_attn_chunks(d.max_seq);
     c->last_step_seg_mlp = seg_mlp;
     c->last_step_seg_attn = seg_attn;

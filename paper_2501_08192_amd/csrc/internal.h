@@ -31,6 +31,7 @@ struct KvView {
     uint16_t *k_pool;            // bf16 pool, or (int8 != 0) byte pool of PSV_KV_UNIT_BYTES_INT8 units
     uint16_t *v_pool;
     int int8;
+    int token_major;             // bf16 pools laid out [block][16 tokens][kv head][128] (both K and V)
     const int32_t *page_table;   // null => contiguous
     int max_blocks;
     int max_tokens;              // longest valid sequence: min(max_blocks * 16, the descriptor's max_seq); the

@@ -35,7 +35,7 @@ class Session:
         self.max_seq = (w.context + 15) // 16 * 16 if max_seq is None else int(max_seq)
         self.desc = psv.model_desc(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch, self.max_seq,
                                    head_dim=w.head_dim, rms_eps=w.rms_eps, rope_theta=w.rope_theta,
-                                   weight_format=w.weight_format, kv_format=w.kv_format)
+                                   weight_format=w.weight_format, kv_format=w.kv_format, kv_layout=w.kv_layout)
         # HIP maps streams onto a few hardware queues; take a side stream that really runs beside the main one
         self.main = torch.cuda.Stream(device=self.device)
         self.overlap = False

@@ -43,18 +43,18 @@ def timed(sess, n_layers, steps=20, warmup=5, reps=3):
     return sorted(ts)[len(ts) // 2]
 
 
-def speed_map(shape, batches, contexts, layers=3, window=20.0, out=print):
+def speed_map(shape, batches, contexts, layers=3, window=20.0, out=print, kv_layout="head"):
     """off / on us per layer and speedup for every (batch, context), beside the analytic model's prediction.
     The budget is the one the model picks; the rest of the policy is bench.py's default."""
     hidden, nq, nkv, ffn = SHAPES[shape]
     mach = model.Machine()
-    out("shape %s: hidden %d, %d q / %d kv heads, ffn %d, windows %g us, %d layers materialised"
-        % (shape, hidden, nq, nkv, ffn, window, layers))
+    out("shape %s: hidden %d, %d q / %d kv heads, ffn %d, windows %g us, %d layers materialised, %s-major KV"
+        % (shape, hidden, nq, nkv, ffn, window, layers, kv_layout))
     out("%5s %7s | %9s %9s %8s | %9s %9s %8s | budget" % ("batch", "context", "off", "on", "speedup", "m.off", "m.on", "m.spd"))
     rows = []
     for B in batches:
         for T in contexts:
-            w = synth.Workload("map", 80, hidden, nq, nkv, 128, ffn, B, T, False, (window, window))
+            w = synth.Workload("map", 80, hidden, nq, nkv, 128, ffn, B, T, False, (window, window), kv_layout=kv_layout)
             if w.kv_bytes_per_layer * layers > 60e9:
                 continue
             b = model.op_bytes(hidden, nq, nkv, ffn, B, T)
@@ -129,6 +129,9 @@ def main(argv=None):
     m.add_argument("--contexts", default="1024,4096,16384,65536")
     m.add_argument("--layers", type=int, default=3)
     m.add_argument("--window", type=float, default=20.0)
+    m.add_argument("--kv-layout", default="head", choices=["head", "token"],
+                   help="token: both pools [block, token, kv head, channel] -- one head's reads are strided when the shard has "
+                        "several local kv heads")
     sw = sub.add_parser("sweep")
     sw.add_argument("workload", choices=sorted(synth.WORKLOADS))
     sw.add_argument("--layers", type=int, default=4)
@@ -141,7 +144,7 @@ def main(argv=None):
 
     if a.cmd == "map":
         speed_map(a.shape, [int(x) for x in a.batches.split(",")], [int(x) for x in a.contexts.split(",")],
-                  a.layers, a.window, out)
+                  a.layers, a.window, out, kv_layout=a.kv_layout)
     else:
         policy_sweeps(a.workload, a.layers, a.steps, tuple(a.which.split(",")), out)
 

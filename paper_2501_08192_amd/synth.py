@@ -40,6 +40,8 @@ class Workload:
     rope_theta: float = 500000.0
     weight_format: str = "bf16"   # or "int8"
     kv_format: str = "bf16"       # or "int8"
+    kv_layout: str = "head"       # "head": K [block, kv head, token, channel], V [block, kv head, channel, token];
+                                  # "token" (bf16 only): both [block, token, kv head, channel]
 
     @property
     def qkv_rows(self):
@@ -150,7 +152,7 @@ def kv_pools(w: Workload, layer: int, seed: int = 2501, device="cpu", n_blocks=N
     """K and V pools of one layer, every slot ~ N(0,1): bf16, or the int8 byte layout."""
     nb = w.pool_blocks if n_blocks is None else int(n_blocks)
     if w.kv_format == "int8":
-        assert w.head_dim == 128
+        assert w.head_dim == 128 and w.kv_layout == "head"
         pools = []
         for name in ("k_pool", "v_pool"):
             pool = torch.empty((nb, w.n_kv_heads, KV_UNIT_INT8), dtype=torch.uint8, device=device)
@@ -160,6 +162,10 @@ def kv_pools(w: Workload, layer: int, seed: int = 2501, device="cpu", n_blocks=N
             pool[:, :, BLOCK_TOKENS * 128:] = sc.view(torch.uint8)
             pools.append(pool)
         return pools[0], pools[1]
+    if w.kv_layout == "token":
+        k = _normal((nb, BLOCK_TOKENS, w.n_kv_heads, w.head_dim), 1.0, 0.0, seed, "k_pool", layer, device)
+        v = _normal((nb, BLOCK_TOKENS, w.n_kv_heads, w.head_dim), 1.0, 0.0, seed, "v_pool", layer, device)
+        return k, v
     k = _normal((nb, w.n_kv_heads, BLOCK_TOKENS, w.head_dim), 1.0, 0.0, seed, "k_pool", layer, device)
     v = _normal((nb, w.n_kv_heads, w.head_dim, BLOCK_TOKENS), 1.0, 0.0, seed, "v_pool", layer, device)
     return k, v

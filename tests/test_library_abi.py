@@ -215,7 +215,7 @@ def test_storage_formats_in_the_descriptor_and_the_planner():
 
 def test_binding_structs_match_the_header_layout():
     # field order and sizes restated from include/preserve.h
-    assert C.sizeof(psv.psv_model_desc) == 12 * 4
+    assert C.sizeof(psv.psv_model_desc) == 13 * 4
     assert C.sizeof(psv.psv_layer_weights) == 12 * C.sizeof(C.c_void_p)
     assert C.sizeof(psv.psv_prefetch_policy) == 40
     assert C.sizeof(psv.psv_plan_entry) == 32
