@@ -1,27 +1,69 @@
 """Analytic latency model of one decode layer with and without prefetching, in the spirit of the paper's
 design-space model (Section 5, "Performance & cost model": memory time linear in bytes over the bandwidth of
-the level that serves them, communication as a fixed latency), re-parameterised with what was measured on
-MI355X.  Pure Python; used to predict the speedup map and to pick a prefetch budget.
+the level that serves them, communication as a fixed latency), re-parameterised for MI355X.  Pure Python; used to
+predict the speedup map and to pick a prefetch budget.
 
-Per kernel:  t = t_fixed + hit_bytes / bw_cache + miss_bytes / bw_hbm.
+Per kernel:  t = t_fixed + hit_bytes / bw_cache + miss_bytes / bw_hbm, with one (t_fixed, bw_hbm, bw_cache) triple
+per kernel class: the vector-ALU projections of batch 1-2, the matrix-core projections of larger batches, the decode
+attention, and the small kernels the matrix-core path adds (residual sums, split-K reductions, attention merge).
 Per window:  t = max(window, t_fork + prefetch_bytes / bw_prefetch)   (the prefetch may outlast the window),
 and whatever part of a prefetch is still running after the window competes with its consumer for HBM.
+
+The constants are not fitted to the workloads the model is used to predict: `sweeps.py calibrate` measures the
+per-operator kernel times of seven calibration shapes that are none of the benchmark workloads nor cells of the
+speedup map, fits the triples by least squares and writes machine_mi355x.json next to this file; Machine.load()
+reads it.  tests/test_model.py holds the model to the measured records in tests/golden/measured_mi355x.json
+(written by `sweeps.py record`) within a stated tolerance.
 """
-from dataclasses import dataclass
+import json
+import os
+from dataclasses import dataclass, fields, replace
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+MACHINE_FILE = os.path.join(HERE, "machine_mi355x.json")
 
 
 @dataclass(frozen=True)
 class Machine:
-    bw_hbm: float = 4.5e6        # bytes/us a consumer kernel streams from HBM (incremental rate measured on GEMV/GEMM)
-    bw_cache: float = 5.5e6      # bytes/us a consumer kernel streams prefetched (Infinity-Cache resident) data
-    bw_prefetch: float = 5.0e6   # bytes/us of the prefetch kernel with >= 128 workgroups
-    t_fixed: float = 3.5         # us per dependent kernel: dispatch, first byte, reduction, drain
+    # vector-ALU projections (batch 1; batch 2 up to hidden 4096)
+    t_fixed: float = 3.5         # us per dependent kernel: dispatch gap, first byte, reduction, drain
+    bw_hbm: float = 4.5e6        # bytes/us streamed from HBM
+    bw_cache: float = 5.5e6      # bytes/us streamed when the bytes were prefetched into the Infinity Cache
+    # matrix-core projections (split-K GEMM)
+    t_fixed_mm: float = 4.0
+    bw_mm: float = 4.2e6
+    bw_mm_cache: float = 5.0e6
+    # decode attention
+    t_fixed_attn: float = 4.5
+    bw_attn: float = 4.8e6
+    bw_attn_cache: float = 5.5e6
+    # small kernels of the matrix-core path (2 residual sums, 2 split-K reductions, attention merge)
+    t_small: float = 3.7
+    n_small: int = 5
+    # prefetch kernel
+    bw_prefetch: float = 5.0e6   # bytes/us with >= 128 workgroups
     t_fork: float = 2.5          # us from window start to the first prefetch load (gate kernel + dispatch)
+    t_window_extra: float = 0.8  # us a window costs beyond its length (the stand-in kernel's overrun and its dispatch gap)
     cache_bytes: float = 192e6   # usable part of the 256 MB Infinity Cache
-    small_kernels: float = 0.0   # extra us per layer for merge / reduce / norm launches (matrix-core path)
-    reg_bytes: float = 32e6      # weights the first pass of a GEMV launched into a window holds in registers
-    t_post: float = 3.0          # us such a kernel still needs after the window (poll, activations, reduce, drain)
-    bw_reg: float = 24e6         # bytes/us at which it works through the weights it holds (c2: QKV 3.3 us, gate/up 4.3 us)
+    # a projection launched into its window (policy.prelaunch, vector path)
+    reg_bytes: float = 32e6      # weights its first pass holds in registers
+    t_post: float = 3.0          # us it still needs after the window (poll, activations, reduce, drain)
+    bw_reg: float = 24e6         # bytes/us at which it works through the weights it holds
+
+    @classmethod
+    def load(cls, path=MACHINE_FILE):
+        """The calibrated constants if the calibration file exists, else the defaults above."""
+        try:
+            data = json.load(open(path))
+        except OSError:
+            return cls()
+        names = {f.name for f in fields(cls)}
+        return replace(cls(), **{k: v for k, v in data.get("machine", {}).items() if k in names})
+
+
+def path_of(batch, hidden):
+    """Which projections a step runs: "vec" (vector ALU) or "mm" (matrix cores) -- the library's own rule."""
+    return "vec" if batch == 1 or (batch == 2 and hidden <= 4096) else "mm"
 
 
 def op_bytes(hidden, n_q, n_kv, ffn, batch, context, head_dim=128, weight_format="bf16", kv_format="bf16"):
@@ -52,20 +94,29 @@ def plan_windows(b, budget):
 def prelaunched(b, windows, budget):
     """Which first consumers the `prelaunch` policy launches into their window: gate/up after window 1, the next
     layer's QKV after window 2, each only if the plan hands that window the whole operator (the gate matrix for
-    the pair).  Batch 1-2 only: the matrix-core path has no such launch."""
+    the pair).  Vector path only: the matrix-core path has no such launch."""
     planned = plan_windows(b, budget) if budget > 0 else {}
     return {"gate_up": windows[0] > 0 and planned.get("gate", 0.0) >= b["gate"],
             "qkv": windows[1] > 0 and planned.get("qkv", 0.0) >= b["qkv"]}
 
 
-def layer_time(b, windows, m: Machine, budget=0.0, prelaunch=False):
+def kernel_time(m: Machine, name, nbytes, hit, path="vec"):
+    """One kernel of class `name` ("attn", or a projection on `path`) moving nbytes, `hit` of them prefetched."""
+    if name == "attn":
+        return m.t_fixed_attn + hit / m.bw_attn_cache + (nbytes - hit) / m.bw_attn
+    if path == "mm":
+        return m.t_fixed_mm + hit / m.bw_mm_cache + (nbytes - hit) / m.bw_mm
+    return m.t_fixed + hit / m.bw_cache + (nbytes - hit) / m.bw_hbm
+
+
+def layer_time(b, windows, m: Machine, budget=0.0, prelaunch=False, path="vec"):
     """us per layer.  budget = 0: prefetch off.  A window of 0 us launches no prefetch; a window's plan larger
-    than the cache keeps only cache_bytes / planned of itself resident.  prelaunch: the first consumer of a window
-    that the plan covers whole is launched into the window; it is not prefetched a second time, holds up to
-    reg_bytes of its weights in registers when the window ends and streams the rest."""
+    than the cache keeps only cache_bytes / planned of itself resident.  prelaunch (vector path): the first consumer
+    of a window that the plan covers whole is launched into the window; it is not prefetched a second time, holds
+    up to reg_bytes of its weights in registers when the window ends and streams the rest."""
     groups = (("gate", "up", "down"), ("qkv", "attn", "o"))
     planned = plan_windows(b, budget) if budget > 0 else {}
-    pre = prelaunched(b, windows, budget) if prelaunch else {"gate_up": False, "qkv": False}
+    pre = prelaunched(b, windows, budget) if (prelaunch and path == "vec") else {"gate_up": False, "qkv": False}
     if pre["gate_up"]:
         planned["gate"] = planned["up"] = 0.0
     if pre["qkv"]:
@@ -78,26 +129,41 @@ def layer_time(b, windows, m: Machine, budget=0.0, prelaunch=False):
             hit[op] = planned.get(op, 0.0) * keep
     kernels = [("qkv", b["qkv"], hit["qkv"]), ("attn", b["attn"], hit["attn"]), ("o", b["o"], hit["o"]),
                ("gate_up", b["gate"] + b["up"], hit["gate"] + hit["up"]), ("down", b["down"], hit["down"])]
-    t = m.small_kernels
+    t = m.t_small * m.n_small if path == "mm" else 0.0
     for name, nbytes, h in kernels:
         if pre.get(name):
             t += m.t_post + min(nbytes, m.reg_bytes) / m.bw_reg + max(0.0, nbytes - m.reg_bytes) / m.bw_hbm
         else:
-            t += m.t_fixed + h / m.bw_cache + (nbytes - h) / m.bw_hbm
+            t += kernel_time(m, name, nbytes, h, path)
     for w, ops in zip(windows, groups):
         if w <= 0:
             continue
         pf = sum(planned.get(op, 0.0) for op in ops)
         t_pf = m.t_fork + pf / m.bw_prefetch if pf > 0 else 0.0
-        t += w
+        t += w + m.t_window_extra
         if t_pf > w:                       # the tail of the prefetch shares HBM with the consumer
             t += (t_pf - w) * 0.5
     return t
 
 
-def best_budget(b, windows, m: Machine, candidates=(8e6, 16e6, 32e6, 64e6, 96e6, 128e6, 192e6, 256e6)):
-    return min(candidates, key=lambda c: layer_time(b, windows, m, c))
+def best_budget(b, windows, m: Machine, candidates=(8e6, 16e6, 32e6, 64e6, 96e6, 128e6, 192e6, 256e6), path="vec"):
+    return min(candidates, key=lambda c: layer_time(b, windows, m, c, path=path))
 
 
-def speedup(b, windows, m: Machine, budget, prelaunch=False):
-    return layer_time(b, windows, m, 0.0) / layer_time(b, windows, m, budget, prelaunch)
+def speedup(b, windows, m: Machine, budget, prelaunch=False, path="vec"):
+    return layer_time(b, windows, m, 0.0, path=path) / layer_time(b, windows, m, budget, prelaunch, path=path)
+
+
+def fit_line(points):
+    """Least-squares (t_fixed, bytes_per_us) of t = t_fixed + bytes / bw over (bytes, us) points."""
+    n = len(points)
+    sx = sum(p[0] for p in points); sy = sum(p[1] for p in points)
+    sxx = sum(p[0] * p[0] for p in points); sxy = sum(p[0] * p[1] for p in points)
+    den = n * sxx - sx * sx
+    if n < 2 or den <= 0:
+        raise ValueError("need at least two distinct sizes")
+    slope = (n * sxy - sx * sy) / den
+    icpt = (sy - slope * sx) / n
+    if slope <= 0:
+        raise ValueError("times do not grow with bytes")
+    return icpt, 1.0 / slope

@@ -5,12 +5,16 @@ policies, run decode steps and time them; every step of the path runs in the lib
     python -m paper_2501_08192_amd.sweeps map tp4            # Section 4, "Impact of batch size and sequence length"
     python -m paper_2501_08192_amd.sweeps map tp8
     python -m paper_2501_08192_amd.sweeps sweep c5 --layers 4 --which window,budget,chunk,cu,targets
+    python -m paper_2501_08192_amd.sweeps calibrate          # fits the analytic model's constants -> machine_mi355x.json
+    python -m paper_2501_08192_amd.sweeps record             # measured rows the model is tested against -> tests/golden/
 
 The map stands in for the paper's sweep over batch size and sequence length (its Figure on the speedup across
 batch sizes and sequence lengths); the sweeps for its remark that the prefetch should take about as long as the
 allreduce it hides behind (appendix on the optimal cache size).
 """
 import argparse
+import json
+import os
 import time
 
 import torch
@@ -47,7 +51,7 @@ def speed_map(shape, batches, contexts, layers=3, window=20.0, out=print, kv_lay
     """off / on us per layer and speedup for every (batch, context), beside the analytic model's prediction.
     The budget is the one the model picks; the rest of the policy is bench.py's default."""
     hidden, nq, nkv, ffn = SHAPES[shape]
-    mach = model.Machine()
+    mach = model.Machine.load()
     out("shape %s: hidden %d, %d q / %d kv heads, ffn %d, windows %g us, %d layers materialised, %s-major KV"
         % (shape, hidden, nq, nkv, ffn, window, layers, kv_layout))
     out("%5s %7s | %9s %9s %8s | %9s %9s %8s | budget" % ("batch", "context", "off", "on", "speedup", "m.off", "m.on", "m.spd"))
@@ -58,7 +62,8 @@ def speed_map(shape, batches, contexts, layers=3, window=20.0, out=print, kv_lay
             if w.kv_bytes_per_layer * layers > 60e9:
                 continue
             b = model.op_bytes(hidden, nq, nkv, ffn, B, T)
-            budget = model.best_budget(b, (window, window), mach)
+            path = model.path_of(B, hidden)
+            budget = model.best_budget(b, (window, window), mach, path=path)
             with Session(w, layers=list(range(layers))) as s:
                 s.set_policy(psv.prefetch_policy(mode=0))
                 x_off = s.run().clone()
@@ -68,8 +73,8 @@ def speed_map(shape, batches, contexts, layers=3, window=20.0, out=print, kv_lay
                 on = timed(s, layers)
                 if not torch.equal(x_off, x_on):
                     raise AssertionError("prefetch on/off outputs differ at batch %d context %d" % (B, T))
-            m_off = model.layer_time(b, (window, window), mach, 0.0)
-            m_on = model.layer_time(b, (window, window), mach, budget)
+            m_off = model.layer_time(b, (window, window), mach, 0.0, path=path)
+            m_on = model.layer_time(b, (window, window), mach, budget, prelaunch=True, path=path)
             rows.append((B, T, off, on, m_off, m_on, budget))
             out("%5d %7d | %9.1f %9.1f %8.3f | %9.1f %9.1f %8.3f | %d MB"
                 % (B, T, off, on, off / on, m_off, m_on, m_off / m_on, budget / 1e6))
@@ -120,6 +125,153 @@ def policy_sweeps(name, layers=4, steps=30, which=("window", "budget", "chunk", 
             run(base_win, 192, join=1)
 
 
+# ---- calibration of the analytic model ---------------------------------------------------------------------
+
+# Shapes the constants are fitted on: none of them is a benchmark workload or a cell of the speedup map.
+CAL_SHAPES = {   # hidden, q heads, kv heads, ffn, batch, context
+    "v1": (2048, 16, 2, 5632, 1, 1024), "v2": (8192, 8, 1, 3584, 1, 512), "v3": (4096, 8, 2, 2816, 1, 3072),
+    "m1": (2048, 16, 2, 5632, 8, 2048), "m2": (8192, 8, 1, 3584, 12, 2048), "m3": (4096, 8, 2, 2816, 48, 4096),
+    "m4": (8192, 8, 1, 3584, 24, 12288),     # a KV-dominated layer (151 MB of cache): sets the attention's streaming rate
+}
+OPS = {"qkv": psv.PSV_OP_QKV, "attn": psv.PSV_OP_ATTN, "o": psv.PSV_OP_O, "gate_up": psv.PSV_OP_GATE, "down": psv.PSV_OP_DOWN}
+
+
+def op_times(sess, steps=8):
+    out = {}
+    for name, op in OPS.items():
+        psv.psv_set_profile_op(sess.ctx, op)
+        for _ in range(steps):
+            sess.step()
+        ms, n = psv.psv_get_profile(sess.ctx)
+        out[name] = ms * 1e3 / max(1, n)
+    psv.psv_set_profile_op(sess.ctx, -1)
+    return out
+
+
+def slope_through(points, icpt):
+    """bytes per us of t = icpt + bytes / bw with the intercept given (least squares)."""
+    num = sum(p[0] * p[0] for p in points)
+    den = sum(p[0] * (p[1] - icpt) for p in points)
+    return num / den
+
+
+def calibrate(path, window=50.0, layers=3, out=print):
+    pts = {"vec": [], "vec_hit": [], "mm": [], "mm_hit": [], "attn": [], "attn_hit": [], "pre": []}
+    raw, resid = {}, {}
+    big = 192 * MB
+    for name, (H, nq, nkv, F, B, T) in CAL_SHAPES.items():
+        w = synth.Workload(name, 80, H, nq, nkv, 128, F, B, T, False, (window, window))
+        b = model.op_bytes(H, nq, nkv, F, B, T)
+        nb = {"qkv": b["qkv"], "attn": b["attn"], "o": b["o"], "gate_up": b["gate"] + b["up"], "down": b["down"]}
+        cls = model.path_of(B, H)
+        with Session(w, layers=list(range(layers))) as s:
+            # windows long enough for the whole budget to arrive inside them; whole-layer timing first (it warms up)
+            s.set_policy(psv.prefetch_policy(mode=0))
+            off = timed(s, layers)
+            off_ops = op_times(s)
+            s.set_policy(default_policy(w, budget_bytes=big, prelaunch=0, partial=1))
+            hit = timed(s, layers)
+            hit_ops = op_times(s)
+            pre_ops = None
+            if cls == "vec":
+                s.set_policy(default_policy(w, budget_bytes=big, partial=1))
+                timed(s, layers, steps=5, reps=1)
+                pre_ops = op_times(s)
+        raw[name] = {"bytes": nb, "us_off": off_ops, "us_cache_only": hit_ops, "us_prelaunch": pre_ops, "layer_off": off, "layer_cache_only": hit}
+        for op in ("qkv", "o", "gate_up", "down"):
+            pts[cls].append((nb[op], off_ops[op]))
+            pts[cls + "_hit"].append((nb[op], hit_ops[op]))
+        pts["attn"].append((nb["attn"], off_ops["attn"]))
+        pts["attn_hit"].append((nb["attn"], hit_ops["attn"]))
+        if pre_ops:
+            pts["pre"] += [(nb["qkv"], pre_ops["qkv"]), (nb["gate_up"], pre_ops["gate_up"])]
+        resid[name] = off - sum(off_ops.values()) - 2 * window       # what the five operator kernels and the windows leave
+        out("%s: layer off %.1f cache-only %.1f; ops off %s" % (name, off, hit, {k: round(v, 2) for k, v in off_ops.items()}))
+        torch.cuda.empty_cache()
+    d = model.Machine()
+    t_fixed, bw_hbm = model.fit_line(pts["vec"])
+    t_fixed_mm, bw_mm = model.fit_line(pts["mm"])
+    t_fixed_attn, bw_attn = model.fit_line(pts["attn"])
+    w_extra = sum(resid[n] for n in ("v1", "v2", "v3")) / 3 / 2      # per window: its kernel overruns the request, plus its dispatch gap
+    mm_names = [n for n in CAL_SHAPES if n.startswith("m")]
+    t_small = sum(resid[n] - 2 * w_extra for n in mm_names) / len(mm_names) / d.n_small
+    # a projection launched into its window: what is left after the window against the bytes it holds
+    pre_pts = [(min(nb, d.reg_bytes), us - max(0.0, nb - d.reg_bytes) / bw_hbm) for nb, us in pts["pre"]]
+    t_post, bw_reg = model.fit_line(pre_pts)
+    # the prefetch kernel alone on cold regions of three sizes
+    pf = []
+    stream = torch.cuda.Stream()
+    for mb in (16, 64, 192):
+        buf = torch.empty(mb * MB, dtype=torch.uint8, device="cuda").random_()
+        flush = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        psv.psv_prefetch_region(buf, mb * MB, 256, stream)
+        e1.record(stream)
+        stream.synchronize()
+        pf.append((mb * MB, e0.elapsed_time(e1) * 1e3))
+        del buf, flush
+    _, bw_prefetch = model.fit_line(pf)
+    mach = {"t_fixed": t_fixed, "bw_hbm": bw_hbm, "bw_cache": slope_through(pts["vec_hit"], t_fixed),
+            "t_fixed_mm": t_fixed_mm, "bw_mm": bw_mm, "bw_mm_cache": slope_through(pts["mm_hit"], t_fixed_mm),
+            "t_fixed_attn": t_fixed_attn, "bw_attn": bw_attn, "bw_attn_cache": slope_through(pts["attn_hit"], t_fixed_attn),
+            "t_small": t_small, "t_window_extra": w_extra, "bw_prefetch": bw_prefetch, "t_post": t_post, "bw_reg": bw_reg}
+    mach = {k: round(float(v), 4) for k, v in mach.items()}
+    json.dump({"command": "python -m paper_2501_08192_amd.sweeps calibrate", "shapes": CAL_SHAPES, "window_us": window,
+               "machine": mach, "measured": raw, "prefetch_kernel": pf}, open(path, "w"), indent=1, sort_keys=True)
+    out("machine: %s" % mach)
+    return mach
+
+
+# ---- measured records the model is tested against ----------------------------------------------------------
+
+def record(path, layers=4, out=print):
+    """us per layer of the five benchmark workloads (their first layers) and of cells of the speedup map, prefetch off,
+    cache only and with the default policy, plus the c5 budget sweep at two windows: the rows tests/test_model.py holds
+    the analytic model to."""
+    rows = []
+
+    def measure(name, w, n_layers, budget=None):
+        with Session(w, layers=list(range(n_layers))) as s:
+            kw = {} if budget is None else {"budget_bytes": int(budget)}
+            s.set_policy(psv.prefetch_policy(mode=0))
+            off = timed(s, n_layers)
+            s.set_policy(default_policy(w, prelaunch=0, **kw))
+            cache = timed(s, n_layers)
+            pol = default_policy(w, **kw)
+            s.set_policy(pol)
+            pre = timed(s, n_layers)
+        rows.append({"name": name, "hidden": w.hidden, "n_q": w.n_q_heads, "n_kv": w.n_kv_heads, "ffn": w.ffn, "batch": w.batch,
+                     "context": w.context, "windows": list(w.window_us), "budget": int(pol.budget_bytes), "partial": int(pol.partial),
+                     "us_off": round(off, 2), "us_cache_only": round(cache, 2), "us_default": round(pre, 2)})
+        out(str(rows[-1]))
+        torch.cuda.empty_cache()
+
+    for name in ("c1", "c2", "c3", "c4", "c5"):
+        w = synth.WORKLOADS[name]
+        measure(name, w, min(layers, w.n_layers) if name != "c2" else 8)
+    for shape, cells in (("tp8", ((1, 1024), (1, 16384), (4, 4096), (16, 4096), (64, 4096), (16, 16384))),
+                         ("tp4", ((1, 4096), (16, 4096), (64, 16384)))):
+        H, nq, nkv, F = SHAPES[shape]
+        for B, T in cells:
+            measure("%s_b%d_t%d" % (shape, B, T), synth.Workload("map", 80, H, nq, nkv, 128, F, B, T, False, (20.0, 20.0)), 3, budget=96e6)
+    sweep = []
+    w = synth.WORKLOADS["c5"]
+    with Session(w, layers=list(range(layers))) as s:
+        for win in (20.0, 50.0):
+            s.set_windows(win, win)
+            s.set_policy(psv.prefetch_policy(mode=0))
+            off = timed(s, layers)
+            for mb in (16, 64, 128, 192, 256, 384, 600):
+                s.set_policy(psv.prefetch_policy(mode=1, budget_bytes=mb * MB, cu_budget=256, partial=1))
+                on = timed(s, layers)
+                sweep.append({"window": win, "budget_mb": mb, "us_off": round(off, 2), "us_on": round(on, 2)})
+                out(str(sweep[-1]))
+    json.dump({"command": "python -m paper_2501_08192_amd.sweeps record", "rows": rows, "c5_budget_sweep": sweep},
+              open(path, "w"), indent=1)
+
+
 def main(argv=None):
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
     sub = ap.add_subparsers(dest="cmd", required=True)
@@ -137,12 +289,21 @@ def main(argv=None):
     sw.add_argument("--layers", type=int, default=4)
     sw.add_argument("--steps", type=int, default=30)
     sw.add_argument("--which", default="window,budget,chunk,cu,targets")
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    ca = sub.add_parser("calibrate")
+    ca.add_argument("--out", default=model.MACHINE_FILE)
+    rc = sub.add_parser("record")
+    rc.add_argument("--out", default=os.path.join(root, "tests", "golden", "measured_mi355x.json"))
     a = ap.parse_args(argv)
 
     def out(line):
         print(line, flush=True)
 
-    if a.cmd == "map":
+    if a.cmd == "calibrate":
+        calibrate(a.out, out=out)
+    elif a.cmd == "record":
+        record(a.out, out=out)
+    elif a.cmd == "map":
         speed_map(a.shape, [int(x) for x in a.batches.split(",")], [int(x) for x in a.contexts.split(",")],
                   a.layers, a.window, out, kv_layout=a.kv_layout)
     else:

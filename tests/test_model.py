@@ -28,8 +28,105 @@ def test_model_plan_matches_library_planner(name, budget_mb):
 def test_prefetch_off_is_the_plain_sum():
     w = synth.WORKLOADS["c2"]
     b, m = _bytes(w), model.Machine()
-    want = 5 * m.t_fixed + sum(b.values()) / m.bw_hbm + sum(w.window_us)
+    proj = b["qkv"] + b["o"] + b["gate"] + b["up"] + b["down"]
+    want = (4 * m.t_fixed + proj / m.bw_hbm + m.t_fixed_attn + b["attn"] / m.bw_attn
+            + sum(w.window_us) + 2 * m.t_window_extra)
     assert model.layer_time(b, w.window_us, m, 0.0) == pytest.approx(want)
+    # the matrix-core path adds its five small kernels and uses its own projection constants
+    mm = (4 * m.t_fixed_mm + proj / m.bw_mm + m.t_fixed_attn + b["attn"] / m.bw_attn + m.n_small * m.t_small
+          + sum(w.window_us) + 2 * m.t_window_extra)
+    assert model.layer_time(b, w.window_us, m, 0.0, path="mm") == pytest.approx(mm)
+    assert model.path_of(1, 8192) == "vec" and model.path_of(2, 4096) == "vec" and model.path_of(2, 8192) == "mm" and model.path_of(8, 1024) == "mm"
+
+
+def test_fit_line_recovers_a_line_and_refuses_nonsense():
+    icpt, bw = model.fit_line([(1e6, 3.0 + 1e6 / 4e6), (8e6, 3.0 + 8e6 / 4e6), (30e6, 3.0 + 30e6 / 4e6)])
+    assert icpt == pytest.approx(3.0) and bw == pytest.approx(4e6)
+    with pytest.raises(ValueError):
+        model.fit_line([(1e6, 5.0), (2e6, 4.0)])
+    with pytest.raises(ValueError):
+        model.fit_line([(1e6, 5.0)])
+
+
+# ---- the calibrated model against measured records -----------------------------------------------------------
+#
+# machine_mi355x.json holds constants fitted (sweeps.py calibrate) on seven calibration shapes that are neither benchmark
+# workloads nor cells of the speedup map; tests/golden/measured_mi355x.json holds measured us/layer (sweeps.py record) of
+# the five workloads, nine map cells and the c5 budget sweep.  The model has to predict every row it was not fitted on.
+
+import json
+import os
+
+GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "measured_mi355x.json")
+TOL = 0.17      # relative error allowed per row and mode (worst measured: 15 %, the KV-dominated c5)
+
+
+def _golden():
+    return json.load(open(GOLDEN))
+
+
+def test_calibration_shapes_are_not_the_rows_being_predicted():
+    cal = json.load(open(model.MACHINE_FILE))
+    rows = {(r["hidden"], r["n_q"], r["n_kv"], r["ffn"], r["batch"], r["context"]) for r in _golden()["rows"]}
+    assert len(cal["shapes"]) >= 6 and not rows & {tuple(v) for v in cal["shapes"].values()}
+    assert set(cal["machine"]) >= {"t_fixed", "bw_hbm", "bw_cache", "t_fixed_mm", "bw_mm", "t_fixed_attn", "bw_attn", "t_small",
+                                   "t_window_extra", "bw_prefetch", "t_post", "bw_reg"}
+
+
+def test_calibrated_model_predicts_every_measured_row():
+    m = model.Machine.load()
+    assert m != model.Machine()                       # the calibration file is in place
+    worst = 0.0
+    for r in _golden()["rows"]:
+        b = model.op_bytes(r["hidden"], r["n_q"], r["n_kv"], r["ffn"], r["batch"], r["context"])
+        path, w = model.path_of(r["batch"], r["hidden"]), tuple(r["windows"])
+        pred = {"us_off": model.layer_time(b, w, m, 0.0, path=path),
+                "us_cache_only": model.layer_time(b, w, m, r["budget"], path=path),
+                "us_default": model.layer_time(b, w, m, r["budget"], prelaunch=True, path=path)}
+        for k, v in pred.items():
+            err = abs(v / r[k] - 1.0)
+            worst = max(worst, err)
+            assert err <= TOL, "%s %s: model %.1f measured %.1f" % (r["name"], k, v, r[k])
+    assert worst > 0.0
+
+
+def test_calibrated_model_ranks_the_modes_like_the_measurement_at_batch_one():
+    """Where the first consumers are launched into their windows (vector path) the measured gain over the cache-only
+    policy is 3-6 us per layer on the large shapes; the model has to see a gain of the same order."""
+    m = model.Machine.load()
+    for r in _golden()["rows"]:
+        if model.path_of(r["batch"], r["hidden"]) != "vec" or r["hidden"] < 4096:
+            continue
+        b = model.op_bytes(r["hidden"], r["n_q"], r["n_kv"], r["ffn"], r["batch"], r["context"])
+        w = tuple(r["windows"])
+        gain_model = model.layer_time(b, w, m, r["budget"]) - model.layer_time(b, w, m, r["budget"], prelaunch=True)
+        gain_meas = r["us_cache_only"] - r["us_default"]
+        assert gain_meas > 1.0 and 0.4 * gain_meas < gain_model < 2.5 * gain_meas, (r["name"], gain_meas, gain_model)
+
+
+def test_calibrated_model_finds_the_budget_knee_of_the_kv_dominated_workload():
+    """c5 budget sweep: the best budget grows with the window (64 MB at 20 us, 192 MB at 50 us: prefetch time about equal
+    to the window, the optimum the paper's appendix describes), budgets far beyond it lose; the model has to pick a
+    budget whose measured speedup is within 1.5 % of the best measured one, and to agree on which budgets lose."""
+    m = model.Machine.load()
+    g = _golden()
+    b = model.op_bytes(8192, 8, 1, 3584, 32, 32768)
+    for win in (20.0, 50.0):
+        pts = [s for s in g["c5_budget_sweep"] if s["window"] == win]
+        meas = {s["budget_mb"]: s["us_off"] / s["us_on"] for s in pts}
+        pred = {mb: model.speedup(b, (win, win), m, mb * 2 ** 20, path="mm") for mb in meas}
+        best_meas, best_pred = max(meas, key=meas.get), max(pred, key=pred.get)
+        assert meas[best_pred] >= meas[best_meas] - 0.015, (win, best_meas, best_pred)
+        for mb in meas:
+            if meas[mb] < 0.95:
+                assert pred[mb] < 1.0, (win, mb)
+            assert abs(pred[mb] - meas[mb]) < 0.06, (win, mb, pred[mb], meas[mb])      # worst: 0.054 (256 MB in a 20 us window)
+        # prefetch time of the model's pick ~ the window (within a factor of two: the budgets are a coarse grid)
+        t_pf = m.t_fork + best_pred * 2 ** 20 / m.bw_prefetch
+        assert 0.5 * win <= t_pf <= 2.0 * win, (win, best_pred, t_pf)
+    best20 = max((s for s in g["c5_budget_sweep"] if s["window"] == 20.0), key=lambda s: s["us_off"] / s["us_on"])["budget_mb"]
+    best50 = max((s for s in g["c5_budget_sweep"] if s["window"] == 50.0), key=lambda s: s["us_off"] / s["us_on"])["budget_mb"]
+    assert best20 < best50
 
 
 def test_speedup_has_a_knee_at_window_capacity_and_at_cache_capacity():
