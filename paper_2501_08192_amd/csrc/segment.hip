@@ -748,7 +748,6 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
         scales3(r3);
     }
     if (early && (!WAIT || a.hold_kv)) load_blocks(blkA0, blkB0);
-    if (att && tid < 64) rope_s[tid] = rope_v;          // read after the barriers of the normalisation below
 
     if (WAIT) {
         if (wave == 0) {
@@ -815,6 +814,7 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
         }
         ss = wave_sum(ss);
         if (lane == 0) ssq[wave] = ss;
+        if (att && tid < 64) rope_s[tid] = rope_v;      // stored here, not where it was requested: by now it has arrived
         __syncthreads();
         float tot = 0.f;
         for (int w = 0; w < wpg1; ++w) tot += ssq[gid1 * wpg1 + w];   // fixed order
