@@ -55,7 +55,7 @@ def parse():
                     help="1 = let the library time its candidate attention splits on layer 0 first (psv_tune_attention); "
                          "the default split is within ~1 %% of the tuned one on the five workloads")
     ap.add_argument("--fused", type=int, default=0,
-                    help="1 = fused kernels per inter-window segment at batch 1 (psv_set_fused_kernels)")
+                    help="1 = fused kernels per inter-window segment at batch 1, 2 = the whole step as one kernel (psv_set_fused_kernels)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = auto)")
     ap.add_argument("--seed", type=int, default=2501)
@@ -222,7 +222,7 @@ def main():
         w = w.scaled(weight_format="int8" if a.format in ("int8", "w8") else "bf16",
                      kv_format="int8" if a.format in ("int8", "kv8") else "bf16")
     layers = list(range(a.layers)) if a.layers else None
-    sess = Session(w, seed=a.seed, layers=layers, fused=bool(a.fused))
+    sess = Session(w, seed=a.seed, layers=layers, fused=a.fused)
     L = len(sess.layers)
     MB = 1 << 20
     if a.budget_mb <= 0:

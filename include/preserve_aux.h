@@ -28,7 +28,12 @@ psv_status psv_set_graph_mode(psv_ctx *ctx, uint32_t use_graph);
  * gate/up + down) whose phases hand their results over through tagged values in memory.  Faster by ~3 us per layer
  * on an 8B-shaped shard when the kernels are launched into the windows (policy.prelaunch), slower otherwise.  The two
  * settings agree to rounding, not bit for bit; within one setting every policy gives the same bits.  A hand-over that
- * does not complete within its bound makes the next psv_sync return PSV_ERR_HIP. */
+ * does not complete within its bound makes the next psv_sync return PSV_ERR_HIP.
+ * 2 = under the same conditions (and every projection at least as many rows as the device has thread groups) the whole
+ * step is ONE kernel: resident workgroups walk the layers, the residual stream stays in registers, the communication
+ * windows are timed inside the kernel, and what the plan hands to a window whole is requested into registers before the
+ * window's end (nothing runs on the side stream; an operator the plan covers only in part is not requested early).
+ * Shapes it does not take run as under 1.  Per-operator profiling sees one kernel (reported as the QKV operator). */
 psv_status psv_set_fused_kernels(psv_ctx *ctx, uint32_t on);
 
 /* ---- streams and tuning -------------------------------------------------------------------- */
@@ -82,6 +87,10 @@ psv_status psv_copy_bytes(void *dst, const void *src, uint64_t bytes, void *stre
  * (always bounded) wait at once.  The kernel then still completes, sets an error word, and the next psv_sync
  * returns PSV_ERR_TIMEOUT once; the context stays usable. */
 psv_status psv_debug_force_wait_timeout(psv_ctx *ctx, uint32_t on);
+
+/* Which kernels the most recent psv_decode_step ran: 0 = one per operator, 1 = at least one block as a fused kernel,
+ * 2 = the whole step as one kernel (psv_set_fused_kernels asks; the shape decides). */
+psv_status psv_debug_last_step_path(psv_ctx *ctx, uint32_t *path);
 
 /* Intermediate buffers of the most recent layer executed, for debugging parity failures.  PSV_DBG_H1 and
  * PSV_DBG_H2 exist only when the step ran on the vector path (batch 1, or batch 2 with H <= 4096): the

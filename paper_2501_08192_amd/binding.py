@@ -29,7 +29,7 @@ EXPORTS = [
     "psv_set_graph_mode", "psv_decode_step", "psv_sync", "psv_get_stats", "psv_tune_attention", "psv_check_overlap",
     "psv_set_profile_op",
     "psv_get_profile", "psv_prefetch_region", "psv_spin", "psv_copy_bytes", "psv_debug_read",
-    "psv_debug_force_wait_timeout", "psv_decode_step_static", "psv_set_fused_kernels",
+    "psv_debug_force_wait_timeout", "psv_decode_step_static", "psv_set_fused_kernels", "psv_debug_last_step_path",
 ]
 
 
@@ -114,6 +114,7 @@ def lib():
             "psv_copy_bytes": (C.c_int32, [vp, vp, u64, vp]),
             "psv_debug_read": (C.c_int32, [vp, u32, vp, sz]),
             "psv_debug_force_wait_timeout": (C.c_int32, [vp, u32]),
+            "psv_debug_last_step_path": (C.c_int32, [vp, C.POINTER(u32)]),
             "psv_set_fused_kernels": (C.c_int32, [vp, u32]),
             "psv_decode_step_static": (C.c_int32, [C.POINTER(psv_model_desc), C.POINTER(psv_layer_weights),
                                                    C.POINTER(psv_kv_desc), vp, vp, u32, u32, u32, vp]),
@@ -297,7 +298,14 @@ def psv_debug_read(ctx, which, host_array):
 
 
 def psv_set_fused_kernels(ctx, on):
-    _check(lib().psv_set_fused_kernels(ctx, 1 if on else 0), "psv_set_fused_kernels")
+    """on: 0 / False = one kernel per operator, 1 / True = one per block, 2 = the whole step as one kernel."""
+    _check(lib().psv_set_fused_kernels(ctx, int(on)), "psv_set_fused_kernels")
+
+
+def psv_debug_last_step_path(ctx):
+    out = C.c_uint32(0)
+    _check(lib().psv_debug_last_step_path(ctx, C.byref(out)), "psv_debug_last_step_path")
+    return int(out.value)
 
 
 def psv_debug_force_wait_timeout(ctx, on):

@@ -88,6 +88,7 @@ psv_status psv_set_layer_weights(psv_ctx *c, uint32_t layer, const psv_layer_wei
     }
     c->weights[layer] = *w;
     c->weights_set[layer] = 1;
+    c->step_tbl_dirty = true;
     return PSV_OK;
 }
 
@@ -110,6 +111,7 @@ psv_status psv_set_kv(psv_ctx *c, const psv_kv_desc *kv)
     c->kv.k_pools = nullptr;   // the host arrays are copied, not borrowed
     c->kv.v_pools = nullptr;
     c->kv_set = true;
+    c->step_tbl_dirty = true;
     return PSV_OK;
 }
 
@@ -191,10 +193,17 @@ psv_status psv_debug_force_wait_timeout(psv_ctx *c, uint32_t on)
     return PSV_OK;
 }
 
+psv_status psv_debug_last_step_path(psv_ctx *c, uint32_t *path)
+{
+    if (!c || !path) return PSV_ERR_INVALID_ARG;
+    *path = c->last_step_whole ? 2u : (c->last_step_seg_attn || c->last_step_seg_mlp) ? 1u : 0u;
+    return PSV_OK;
+}
+
 psv_status psv_set_fused_kernels(psv_ctx *c, uint32_t on)
 {
-    if (!c || on > 1) return PSV_ERR_INVALID_ARG;
-    c->fused = on == 1;
+    if (!c || on > 2) return PSV_ERR_INVALID_ARG;
+    c->fused = (int)on;
     return PSV_OK;
 }
 

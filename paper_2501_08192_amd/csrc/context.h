@@ -19,7 +19,7 @@ struct Workspace {
     size_t total = 0;
     // offsets
     size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, rope, part_ml, part_o, attn_f32, attn_bf16,
-        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag, part, ssq, m_ll, qkv_ll, pml_ll, po_ll;
+        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag, part, ssq, m_ll, qkv_ll, pml_ll, po_ll, step_tbl, step_ll;
 };
 
 Workspace layout_workspace(const psv_model_desc &d);
@@ -55,11 +55,14 @@ struct psv_ctx {
     uint32_t attn_chunk_tokens = 0;               // 0 = default split; else tokens per attention workgroup (psv_tune_attention)
     int overlap = -1;                            // psv_check_overlap's last answer (-1 = not run yet)
     bool check_err_word = false;                 // a kernel that may set the error word (a pre-launched consumer, a fused kernel) was launched: read it at sync
-    bool fused = false;                          // fused kernels of the vector path switched on (psv_set_fused_kernels)
+    int fused = 0;                               // psv_set_fused_kernels: 0 one kernel per operator, 1 one per block, 2 one per step
+    bool step_tbl_dirty = true;                  // the per-layer pointer table of the whole-step kernel has to be uploaded again
+    std::vector<unsigned char> step_tbl_host;    // ... its host copy (kept alive until the upload has run)
     bool force_wait_timeout = false;             // test aid: such consumers give up waiting at once (and report it)
     bool last_step_vec = false;                  // the last step formed h1 / h2 (vector path)
     bool last_step_seg_attn = false;             // ... the attention block (qkv lives in the tagged buffer)
     bool last_step_seg_mlp = false;              // ... and ran the MLP block as one fused kernel (m lives in the tagged buffer)
+    bool last_step_whole = false;                // ... or the whole step as one kernel
     int cus = 0;                                 // compute units of the device = workgroups of a fused kernel (0: fused kernels off)
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(wsp + off); }

@@ -58,6 +58,8 @@ Workspace layout_workspace(const psv_model_desc &d)
         w.pml_ll = take(d.n_kv_heads * nc * 16 * 2 * 8);
         w.po_ll = take(d.n_kv_heads * nc * G * 128 * 8);
     }
+    w.step_tbl = take((size_t)d.n_layers * kStepLayerBytes);   // per-layer pointers of the whole-step kernel
+    w.step_ll = take((2 * H + 2) * 8);                         // ... its tagged projection outputs and window-end words
     {   // split-K partials of the widest projection
         size_t widest = QR > H ? QR : H;
         if (2 * F > widest) widest = 2 * F;
@@ -322,6 +324,80 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
     return PSV_OK;
 }
 
+// The whole step of one sequence as one kernel (step.hip).  The communication windows are timed inside the kernel and
+// what Algorithm 1 hands to a window is requested into registers before the window's end (StepLaunch::hold); no
+// second stream, no prefetch kernel.  A part of an operator the plan hands over is treated as none of it.
+static psv_status enqueue_whole_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t lb, uint32_t le, int blocks)
+{
+    const psv_model_desc &d = c->d;
+    hipStream_t s = c->main;
+    if (c->step_tbl_dirty) {
+        const void **t;
+        c->step_tbl_host.assign((size_t)d.n_layers * kStepLayerBytes, 0);
+        for (uint32_t l = 0; l < d.n_layers; ++l) {
+            if (!c->weights_set[l]) continue;
+            const psv_layer_weights &w = c->weights[l];
+            t = reinterpret_cast<const void **>(c->step_tbl_host.data() + (size_t)l * kStepLayerBytes);
+            const bool q8 = d.weight_format == PSV_FMT_INT8;
+            t[0] = w.w_qkv; t[1] = w.w_o; t[2] = w.w_gate; t[3] = w.w_up; t[4] = w.w_down;
+            t[5] = q8 ? w.s_qkv : nullptr; t[6] = q8 ? w.s_o : nullptr; t[7] = q8 ? w.s_gate : nullptr;
+            t[8] = q8 ? w.s_up : nullptr; t[9] = q8 ? w.s_down : nullptr;
+            t[10] = w.g_attn; t[11] = w.g_mlp; t[12] = c->k_pools[l]; t[13] = c->v_pools[l];
+        }
+        // pageable source: the call returns once the bytes are staged, so the host copy may change afterwards
+        HIP_TRY(hipMemcpyAsync(c->wsp + c->ws.step_tbl, c->step_tbl_host.data(), c->step_tbl_host.size(), hipMemcpyHostToDevice, s));
+        c->step_tbl_dirty = false;
+    }
+    const KvView kv = kv_view(c, lb);
+    float2 *rope = c->at<float2>(c->ws.rope);
+    const double *inv_freq = d.rope_theta > 0.f ? c->at<double>(c->ws.inv_freq) : nullptr;
+    c->last_prefetch_launches = 0;
+    ST_TRY(prof_tag(c, -2));
+    HIP_TRY(launch_rope_table(c->kv.seq_lens, inv_freq, kv.max_tokens, 1, rope, s));
+    StepLaunch p{};
+    p.layer_table = c->wsp + c->ws.step_tbl;
+    p.lb = (int)lb; p.le = (int)le;
+    p.x_in = x_in; p.x_out = x_out;
+    p.H = (int)d.hidden; p.F = (int)d.ffn; p.nq = (int)d.n_q_heads; p.nkv = (int)d.n_kv_heads;
+    p.n_chunks = seg_attn_chunks(d.max_seq);
+    p.w8 = d.weight_format == PSV_FMT_INT8;
+    p.eps = d.rms_eps;
+    p.rope = rope;
+    p.kv = kv;
+    p.qkv_ll = c->at<void>(c->ws.qkv_ll); p.pml_ll = c->at<void>(c->ws.pml_ll); p.po_ll = c->at<void>(c->ws.po_ll);
+    p.m_ll = c->at<void>(c->ws.m_ll); p.ll_base = c->at<void>(c->ws.step_ll);
+    p.tag_base = next_tags(8u * (le - lb + 1));
+    p.err = c->at<unsigned>(c->ws.flag) + 48;
+    for (int w = 0; w < 2; ++w) {
+        const float us = c->window_us[w];
+        p.ticks[w] = us > 0.f ? us_to_ticks(c->clock_khz, us) : 0;
+        if (us > 0.f && p.ticks[w] == 0) p.ticks[w] = 1;
+        p.spin_iters[w] = spin_cap(us > 0.f ? us : 0.f);
+        p.hold[w] = 0;
+    }
+    if (c->policy.mode == 1) {
+        int h0 = 3, h1 = 7;
+        for (uint32_t l = lb; l < le; ++l) {
+            if (!plan_has_whole(c, l, 0, l, PSV_OP_GATE) || !plan_has_whole(c, l, 0, l, PSV_OP_UP)) h0 &= ~1;
+            if (!plan_has_whole(c, l, 0, l, PSV_OP_DOWN)) h0 &= ~2;
+            if (l + 1 < le) {
+                if (!plan_has_whole(c, l, 1, l + 1, PSV_OP_QKV)) h1 &= ~1;
+                if (!plan_has_whole(c, l, 1, l + 1, PSV_OP_ATTN)) h1 &= ~2;
+                if (!plan_has_whole(c, l, 1, l + 1, PSV_OP_O)) h1 &= ~4;
+            }
+        }
+        p.hold[0] = h0;
+        p.hold[1] = le - lb > 1 ? h1 : 0;
+    }
+    p.dbg_x = c->at<float>(c->ws.x); p.dbg_h1 = c->at<float>(c->ws.h1_f32); p.dbg_attn = c->at<float>(c->ws.attn_f32);
+    p.dbg_y = c->at<float>(c->ws.y); p.dbg_h2 = c->at<float>(c->ws.h2_f32);
+    c->last_step_whole = c->last_step_seg_attn = c->last_step_seg_mlp = true;
+    c->check_err_word = true;
+    ST_TRY(prof_tag(c, PSV_OP_QKV));
+    HIP_TRY(launch_step(p, blocks, s));
+    return PSV_OK;
+}
+
 psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t batch, uint32_t lb, uint32_t le)
 {
     const psv_model_desc &d = c->d;
@@ -359,6 +435,10 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     // The vector path runs the operators between two windows as one fused kernel where the shape allows it.  Which
     // kernels run depends on the shape only, never on the policy, so every policy gives the same bits.
     const int blocks = c->fused ? c->cus : 0;
+    c->last_step_whole = false;
+    if (c->fused == 2 && vec && blocks >= 64 &&
+        step_supported(B, H, F, nq, nkv, d.max_seq, d.kv_format == PSV_FMT_INT8 || d.kv_layout != PSV_KV_HEAD_MAJOR, w8, blocks))
+        return enqueue_whole_step(c, x_in, x_out, lb, le, blocks);
     const bool seg_mlp = vec && blocks >= 64 && seg_mlp_supported(B, H, F);
     const bool seg_attn = vec && blocks >= 64 && seg_attn_supported(B, H, nq, nkv, d.max_seq, d.kv_format == PSV_FMT_INT8 || d.kv_layout != PSV_KV_HEAD_MAJOR, blocks);
     const int seg_nc = seg_attn_chunks(d.max_seq);

@@ -110,6 +110,39 @@ hipError_t launch_seg_attn(Mat Wq, Mat Wo, const float *res, const float *delta,
                            int n_chunks, void *pml_ll, void *po_ll, float *out_attn, float *out, int H, unsigned tag,
                            unsigned *err, const GemvWait *wait, bool hold_kv, bool hold_o, int blocks, hipStream_t s);
 
+// ---- the whole step of one sequence as one kernel (step.hip): `blocks` resident workgroups walk layers [lb, le); the
+// residual stream stays in registers, every hand-over is a buffer of tagged values, and the communication windows
+// are timed inside the kernel (wave 0 of workgroup 0 spins `ticks` of the wall clock and publishes the window's end).
+// hold[w]: what is requested into registers before the end of window w (0: after the attention block, 1: after the
+// MLP block) instead of after it -- bit 0 the first projection of the next block, then [0] bit 1 down, [1] bit 1 the
+// K/V tiles and bit 2 O; a window of 0 ticks does not exist and everything is requested up front.
+// layer_table: device array of kStepLayerBytes per layer of the model (index = layer): pointers Wq, Wo, Wg, Wu, Wd,
+// their int8 row scales sq, so, sg, su, sd, the gains g_attn, g_mlp and the layer's K and V pools.
+// ll_base: (2 * H + 2) pairs for the two projection outputs and the two window-end words.  Tags tag_base ..
+// tag_base + 8 * (le - lb) - 1 must be unused by any other launch (next_tags).
+constexpr size_t kStepLayerBytes = 14 * sizeof(void *);
+unsigned next_tags(unsigned n);
+struct StepLaunch {
+    const void *layer_table;
+    int lb, le;
+    const float *x_in;
+    float *x_out;
+    int H, F, nq, nkv, n_chunks;
+    bool w8;
+    float eps;
+    const float2 *rope;
+    KvView kv;
+    void *qkv_ll, *pml_ll, *po_ll, *m_ll, *ll_base;
+    unsigned tag_base;
+    unsigned *err;
+    uint64_t ticks[2];
+    uint32_t spin_iters[2];
+    int hold[2];
+    float *dbg_x, *dbg_h1, *dbg_attn, *dbg_y, *dbg_h2;   // intermediates of the last layer (optional)
+};
+bool step_supported(int batch, int H, int F, int nq, int nkv, uint32_t max_seq, bool other_cache, bool w8, int blocks);
+hipError_t launch_step(const StepLaunch &p, int blocks, hipStream_t s);
+
 // Split-K skinny GEMM on the matrix cores with the activation slab shared through LDS:
 // part[split][b][r] = partial sums of W[r].x[b] (rows >= split_row come from W2), to be summed in split
 // order by launch_sk_reduce or launch_resid_sum.  x_bf16: see the operand formats above.

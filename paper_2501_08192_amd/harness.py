@@ -51,7 +51,7 @@ class Session:
         else:
             self.ctx = psv.psv_create(self.desc, self.main, self.side)
         if fused:
-            psv.psv_set_fused_kernels(self.ctx, True)
+            psv.psv_set_fused_kernels(self.ctx, int(fused))
         self.pool_blocks = w.pool_blocks + int(pool_slack_blocks)
         self.weights, self.k_pools, self.v_pools = {}, {}, {}
         for l in self.layers:

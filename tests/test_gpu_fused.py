@@ -1,5 +1,6 @@
-"""GPU parity of the fused kernels of the batch-1 path (psv_set_fused_kernels: QKV + attention + O in one launch,
-gate/up + down in one launch, phases handing over through tagged values) against the CPU oracle, through the C ABI:
+"""GPU parity of the fused kernels of the batch-1 path (psv_set_fused_kernels; 1: QKV + attention + O in one launch,
+gate/up + down in one launch; 2: the whole step in one launch with the windows timed inside the kernel; phases
+handing over through tagged values) against the CPU oracle, through the C ABI:
 same tolerance |gpu - ref| <= 2e-2 + 1e-2*|ref| and the same checks of the appended cache rows as the default
 path, every policy bit-identical to prefetch off, and agreement with the one-kernel-per-operator path to rounding."""
 import numpy as np
@@ -26,9 +27,13 @@ SHAPES = [
 ]
 
 
-def run_fused(w, seed, policies):
+# shapes the whole-step kernel takes (every thread group owns rows of every projection)
+WHOLE_STEP = {"c1_like", "c2_like", "tp8_70b", "tp4_70b", "odd"}
+
+
+def run_fused(w, seed, policies, mode=1):
     m = oracle.model(w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn, 16, w.rms_eps, w.rope_theta)
-    with Session(w, seed=seed, fused=True) as s:
+    with Session(w, seed=seed, fused=mode) as s:
         x = s.x_in.cpu().numpy().astype(np.float64)
         lens = s.seq_lens_host.numpy()
         pt = s.page_table_host.numpy() if w.paged else None
@@ -41,6 +46,7 @@ def run_fused(w, seed, policies):
         off = s.run().clone()
         pools = [s.k_pools[l].clone() for l in s.layers] + [s.v_pools[l].clone() for l in s.layers]
         bf.assert_close(off.cpu().numpy(), x, w.name + " fused")
+        assert psv.psv_debug_last_step_path(s.ctx) == (2 if mode == 2 and w.name in WHOLE_STEP else 1)
         for l in s.layers:       # appended rows: the only cache bytes that may differ from the oracle's, and only to rounding
             for got, ref in ((synth.bits(s.k_pools[l]), ref_pools[l][0]), (synth.bits(s.v_pools[l]), ref_pools[l][1])):
                 diff = got != ref
@@ -54,15 +60,16 @@ def run_fused(w, seed, policies):
             for a, b in zip(pools, [s.k_pools[l] for l in s.layers] + [s.v_pools[l] for l in s.layers]):
                 assert torch.equal(a, b)
         # the default path on the same inputs agrees to rounding
-        psv.psv_set_fused_kernels(s.ctx, False)
+        psv.psv_set_fused_kernels(s.ctx, 0)
         s.set_policy(psv.prefetch_policy(mode=0))
         plain = s.run().clone()
         assert torch.allclose(plain, off, rtol=1e-4, atol=1e-4)
         return off
 
 
+@pytest.mark.parametrize("mode", [1, 2], ids=["per_block", "whole_step"])
 @pytest.mark.parametrize("shape", SHAPES, ids=[s[0] for s in SHAPES])
-def test_fused_bf16_matches_oracle_and_policies_agree(shape):
+def test_fused_bf16_matches_oracle_and_policies_agree(shape, mode):
     name, L, H, nq, nkv, F, T, paged = shape
     w = bf.W(name, L, H, nq, nkv, F, 1, T, paged=paged, win=(6.0, 6.0))
     big = 1 << 40
@@ -70,14 +77,16 @@ def test_fused_bf16_matches_oracle_and_policies_agree(shape):
                       # a budget that hands only part of each window's operators to it: the consumer launched into the
                       # window must hold back the requests of what was not planned
                       default_policy(w, budget_bytes=max(1 << 16, w.weight_bytes_per_layer // 4)),
-                      psv.prefetch_policy(mode=1, targets=psv.PSV_TARGET_WEIGHTS, budget_bytes=big, prelaunch=1, cu_budget=32)])
+                      psv.prefetch_policy(mode=1, targets=psv.PSV_TARGET_WEIGHTS, budget_bytes=big, prelaunch=1, cu_budget=32)],
+              mode=mode)
 
 
+@pytest.mark.parametrize("mode", [1, 2], ids=["per_block", "whole_step"])
 @pytest.mark.parametrize("shape", SHAPES[:3], ids=[s[0] for s in SHAPES[:3]])
-def test_fused_int8_weights_match_oracle(shape):
+def test_fused_int8_weights_match_oracle(shape, mode):
     name, L, H, nq, nkv, F, T, paged = shape
     w = q8.W(name, L, H, nq, nkv, F, 1, T, ("int8", "bf16"), paged=paged, win=(6.0, 6.0))
-    run_fused(w, 62, [default_policy(w, budget_bytes=1 << 40)])
+    run_fused(w, 62, [default_policy(w, budget_bytes=1 << 40)], mode=mode)
 
 
 def test_fused_falls_back_where_the_shape_does_not_fit():
