@@ -278,8 +278,19 @@ def main():
         torch.cuda.synchronize()
         psv.psv_copy_bytes(dst, src, nb, sess.main)
         sess.sync()
+    whole_step = psv.psv_debug_last_step_path(sess.ctx) == 2      # the step is one kernel: no per-operator table
+    step_kernel = None
+    if whole_step:
+        # the kernel's own duration without windows, prefetch off: all the step's bytes over that time is its bandwidth
+        sess.set_policy(modes["off"])
+        sess.set_windows(0.0, 0.0)
+        sess.run()
+        t_k, n_k = profile_op(sess, psv.PSV_OP_QKV, n_prof)
+        sess.set_windows(*w.window_us)
+        step_kernel = {"us": round(t_k, 3), "launches": n_k, "bytes": int(layer_bytes * L),
+                       "gbps": round(layer_bytes * L / t_k / 1e3, 1), "us_per_layer": round(t_k / L, 3)}
     for mode_name in ("off", "on"):
-        if a.skip_kernel_table and mode_name == "on":
+        if whole_step or (a.skip_kernel_table and mode_name == "on"):
             break
         sess.set_policy(modes[mode_name])
         for name, op in op_ids.items():
@@ -297,8 +308,11 @@ def main():
                 del k["us_on"]
             elif not a.fused:
                 k["gbps_" + mode_name] = round(op_bytes[name] / t / 1e3, 1)
-    gate_us, gate_n = kernels["gate_up"]["us_off"], kernels["gate_up"]["launches"]
-    gate_bytes = op_bytes["gate_up"] + (op_bytes["down"] if a.fused and kernels["down"]["launches"] == 0 else 0)
+    if whole_step:
+        gate_us, gate_n, gate_bytes = step_kernel["us"], step_kernel["launches"], step_kernel["bytes"]
+    else:
+        gate_us, gate_n = kernels["gate_up"]["us_off"], kernels["gate_up"]["launches"]
+        gate_bytes = op_bytes["gate_up"] + (op_bytes["down"] if a.fused and kernels["down"]["launches"] == 0 else 0)
     achieved = gate_bytes / gate_us / 1e3
     traffic, traffic_src = stored_traffic(w.name, "gate_up") if (a.format == "bf16" and not a.fused) else (None, None)
 
@@ -321,7 +335,7 @@ def main():
                                                       w.context, "paged" if w.paged else "contiguous", *w.window_us),
                    "prefetch_budget_mb": a.budget_mb, "cu_budget": a.cu_budget, "chunk_mb": a.chunk_mb,
                    "partial": a.partial, "join": a.join, "prelaunch": a.prelaunch, "prelaunch_active": prelaunch_active,
-                   "targets": a.targets, "fused_kernels": bool(a.fused), "streams_overlap": bool(sess.overlap),
+                   "targets": a.targets, "fused_kernels": int(a.fused), "whole_step_kernel": whole_step, "streams_overlap": bool(sess.overlap),
                    "attn_tokens_per_workgroup": attn_chunk if a.tune else "default"},
         "us_per_layer_prefetch_off": round(us["off"], 3),
         "us_per_layer_cache_only": round(us["cache_only"], 3),
@@ -336,7 +350,8 @@ def main():
                                                 "peak": HBM_PEAK_GBPS,
                                                 "frac_off": round(eff["off"] / HBM_PEAK_GBPS, 4),
                                                 "frac_on": round(eff["on"] / HBM_PEAK_GBPS, 4)},
-        "roofline": {"bound": "hbm", "kernel": ("gate/up + SwiGLU + down, fused (prefetch off)" if gate_bytes != op_bytes["gate_up"]
+        "roofline": {"bound": "hbm", "kernel": ("the whole step as one kernel, windows of 0 us, prefetch off" if whole_step else
+                                                "gate/up + SwiGLU + down, fused (prefetch off)" if gate_bytes != op_bytes["gate_up"]
                                                 else "gate/up projection + SwiGLU (prefetch off)"),
                      "achieved": round(achieved, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": round(achieved / HBM_PEAK_GBPS, 4), "traffic": traffic,
@@ -352,6 +367,8 @@ def main():
                              "speedup_prelaunch": round(cold["off"]["median"] / cold["on"]["median"], 4)}
         out["hot_cache_note"] = "back-to-back steps of this workload run from the memory-side cache: step_us_per_layer and value are hot numbers"
     out["kernels"] = kernels
+    if step_kernel is not None:
+        out["step_kernel"] = step_kernel
     if not a.no_cpu_baseline:
         # whole step when a layer is cheap; otherwise the first layers whose oracle cost is ~10-30 s
         n_cpu = a.cpu_layers or max(1, min(L, int(6.0e10 / max(1, (stats["weight_bytes_per_layer"] +

@@ -112,7 +112,8 @@ hipError_t launch_seg_attn(Mat Wq, Mat Wo, const float *res, const float *delta,
 
 // ---- the whole step of one sequence as one kernel (step.hip): `blocks` resident workgroups walk layers [lb, le); the
 // residual stream stays in registers, every hand-over is a buffer of tagged values, and the communication windows
-// are timed inside the kernel (wave 0 of workgroup 0 spins `ticks` of the wall clock and publishes the window's end).
+// are timed inside the kernel (the last workgroup computes nothing: it waits for a block's whole output, spins `ticks`
+// of the wall clock and publishes the window's end).
 // hold[w]: what is requested into registers before the end of window w (0: after the attention block, 1: after the
 // MLP block) instead of after it -- bit 0 the first projection of the next block, then [0] bit 1 down, [1] bit 1 the
 // K/V tiles and bit 2 O; a window of 0 ticks does not exist and everything is requested up front.

@@ -7,11 +7,13 @@
 // registers, and adds the same tagged projection outputs to it.
 //
 // Communication window (Section 2, "Multi-device inference": one allreduce after the attention block, one after the MLP
-// block; here the timed stand-in): workgroup 0 stands in for the collective.  It reads the block's whole output (which
-// it needs anyway) until every value carries the layer's tag -- the collective cannot start before its input exists --,
-// then its wave 0, the time-keeper, spins for the window's length on the wall clock (one wave on one CU) and publishes
+// block; here the timed stand-in): the last workgroup of the grid stands in for the collective and does nothing else.
+// It reads the block's whole output until every value carries the layer's tag -- the collective cannot start before its
+// input exists --, then its wave 0 spins for the window's length on the wall clock (one wave on one CU) and publishes
 // the window's end as a tagged word.  No other workgroup reads the block's output before it has seen that word: the
-// output of a real in-kernel collective would not exist earlier.
+// output of a real in-kernel collective would not exist earlier.  (The time-keeper must not be a wave that also
+// requests weights: a wave cannot go on to its spin loop until the memory pipeline has accepted its loads, which under
+// the load of a whole chip requesting at once takes as long as the transfer -- measured: the window then starts 8 us late.)
 //
 // Prefetch (Section 3, "Execution with the proposed method"): what Algorithm 1 hands to a window -- the next block's
 // projection weights, and for the attention block its K/V tiles -- is requested into registers BEFORE the workgroup
@@ -99,6 +101,7 @@ __device__ __noinline__ void step_layer(StepState<ITH> &st, int l_any, uint64_t 
     __shared__ f32x4 accs[4][8][64];
     __shared__ float ms[8][16], ls[8][16];
     __shared__ float2 rope_s[64];
+    const int nwg = (int)gridDim.x - 1;      // the last workgroup keeps the windows' time
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, i = lane & 15, q4 = lane >> 4;
     const int H = a.H, F = a.F, QR = a.QR, QD = a.QD, nq = a.nq, nkv = a.nkv, G = nq / nkv, nc = a.n_chunks;
     auto ldw = [](const char *p) __attribute__((always_inline)) {
@@ -144,7 +147,6 @@ __device__ __noinline__ void step_layer(StepState<ITH> &st, int l_any, uint64_t 
     const bool early = att && t0 < a.max_blocks * 16;
     const int tau1 = 8 * (i >> 2) + (i & 3);
     const int blkA = st.blkA, blkB = st.blkB;
-    const bool keeper = blockIdx.x == 0 && wave == 0;
     if (att && tid < 64) rope_s[tid] = a.rope[tid];      // read after the barriers of the normalisation
     float res[ITH][8];
 #pragma unroll
@@ -164,7 +166,7 @@ __device__ __noinline__ void step_layer(StepState<ITH> &st, int l_any, uint64_t 
     const StepLayer L = a.layers[last ? a.lb : l];
     // waits (bounded) until the tagged word `slot` of done_ll carries `tag`; wave 0 polls, the others wait at the barrier
     auto wait_window = [&](int slot, unsigned tag) __attribute__((always_inline)) {
-        if (wave == 0 && !keeper) {
+        if (wave == 0) {
             uint2 v;
             bool ok = false;
             for (uint32_t spin = 0; !ok && spin < a.ll_iters; ++spin) {
@@ -176,18 +178,6 @@ __device__ __noinline__ void step_layer(StepState<ITH> &st, int l_any, uint64_t 
             if (!ok) lost = true;
         }
         __syncthreads();
-    };
-    // the time-keeper's side of a window: spin for its length, publish its end
-    auto keep_window = [&](int w, int slot, unsigned tag) __attribute__((always_inline)) {
-        if (keeper) {
-            const uint64_t ts = wall_clock64();
-            uint32_t it = 0;
-            while (wall_clock64() - ts < a.ticks[w] && it < a.spin_iters[w]) {
-                __builtin_amdgcn_s_sleep(2);
-                ++it;
-            }
-            if (lane == 0) ll_store(a.done_ll + slot, 0.f, tag);
-        }
     };
     // adds the tagged projection output `buf` (K = H values) to the residual registers
     auto add_delta = [&](const uint2 *buf, unsigned tag) __attribute__((always_inline)) {
@@ -322,17 +312,8 @@ __device__ __noinline__ void step_layer(StepState<ITH> &st, int l_any, uint64_t 
         if (hold & 1) load_q(rq);
         if (hold & 4) load_o(ro);
         if (early && (hold & 2)) load_tile();
-        bool got = false;
-        if (win) {
-            if (blockIdx.x == 0) {   // the stand-in for the collective starts its clock when the whole output exists
-                add_delta(a.dm_ll, tag0 - TAGS_PER_LAYER + TAG_DM);
-                got = true;
-                __syncthreads();
-            }
-            keep_window(1, 1, tag0 - TAGS_PER_LAYER + TAG_WIN1);
-            wait_window(1, tag0 - TAGS_PER_LAYER + TAG_WIN1);
-        }
-        if (!first && !got) add_delta(a.dm_ll, tag0 - TAGS_PER_LAYER + TAG_DM);
+        if (win) wait_window(1, tag0 - TAGS_PER_LAYER + TAG_WIN1);
+        if (!first) add_delta(a.dm_ll, tag0 - TAGS_PER_LAYER + TAG_DM);
         if (last) {                  // the step's output
             if (blockIdx.x == 0 && gq.gid == 0)
 #pragma unroll
@@ -710,19 +691,10 @@ __device__ __noinline__ void step_layer(StepState<ITH> &st, int l_any, uint64_t 
         int r1 = g1.rb, r2 = g2.rb;
         if (hold & 1) load1(r1);
         if (hold & 2) load2(r2);
-        bool got = false;
-        if (win) {
-            if (blockIdx.x == 0) {   // see the window before the attention block
-                add_delta(a.da_ll, tag0 + TAG_DA);
-                got = true;
-                __syncthreads();
-            }
-            keep_window(0, 0, tag0 + TAG_WIN0);
-            wait_window(0, tag0 + TAG_WIN0);
-        }
+        if (win) wait_window(0, tag0 + TAG_WIN0);
         if (!(hold & 1)) load1(r1);
         if (!(hold & 2)) load2(r2);
-        if (!got) add_delta(a.da_ll, tag0 + TAG_DA);
+        add_delta(a.da_ll, tag0 + TAG_DA);
         float xv[ITH][8];
         normalise(L.g_mlp, xv, a.dbg_y, a.dbg_h2);
 
@@ -781,16 +753,16 @@ __device__ __noinline__ void step_layer(StepState<ITH> &st, int l_any, uint64_t 
         float mv[IT2][8];
         {
             if (wave == 0) {
-                const int slots1 = gridDim.x * g1.groups;
+                const int slots1 = nwg * g1.groups;
                 bool ready = false;
                 for (uint32_t spin = 0; !ready && spin < a.ll_iters; ++spin) {
                     bool mine = true;
-                    for (int p0 = 0; p0 < (int)gridDim.x; p0 += 256) {
+                    for (int p0 = 0; p0 < nwg; p0 += 256) {
                         uint2 v[4];
                         int pe[4];
 #pragma unroll
                         for (int u = 0; u < 4; ++u) {
-                            const int wg = min(p0 + lane + 64 * u, (int)gridDim.x - 1);
+                            const int wg = min(p0 + lane + 64 * u, nwg - 1);
                             pe[u] = (int)((long long)(wg + 1) * g1.groups * F / slots1);
                             ll_issue1(v[u], a.m_ll + max(pe[u] - 1, 0));
                         }
@@ -872,15 +844,54 @@ __device__ __noinline__ void step_layer(StepState<ITH> &st, int l_any, uint64_t 
 template <int ITH, int IT2, bool W8>
 __global__ __launch_bounds__(512) void k_step(StepArgs a)
 {
-    StepState<ITH> st;
     const int tid = threadIdx.x, wave = tid >> 6;
+    const int nwg = (int)gridDim.x - 1;
+    if ((int)blockIdx.x == nwg) {
+        // ---- the stand-in for the collectives
+        bool lost = false;
+        auto window = [&](const uint2 *buf, unsigned tag, int w, unsigned tag_done) __attribute__((always_inline)) {
+            bool all = false;           // the window starts when the block's whole output exists
+            for (uint32_t spin = 0; !all && spin < a.ll_iters; ++spin) {
+                bool mine = true;
+                u32x4 q[8];             // H <= 8192: at most 8 pairs of values per thread, requested together
+#pragma unroll
+                for (int k = 0; k < 8; ++k) ll_issue(q[k], buf + 2 * min(tid + 512 * k, a.H / 2 - 1));
+                ll_wait_all();
+#pragma unroll
+                for (int k = 0; k < 8; ++k) {
+                    asm volatile("" : "+v"(q[k]));
+                    if (q[k].y != tag || q[k].w != tag) mine = false;
+                }
+                all = __syncthreads_and(mine ? 1 : 0) != 0;
+                if (!all) __builtin_amdgcn_s_sleep(4);
+            }
+            if (!all) lost = true;
+            if (wave == 0) {
+                const uint64_t ts = wall_clock64();
+                uint32_t it = 0;
+                while (wall_clock64() - ts < a.ticks[w] && it < a.spin_iters[w]) {
+                    __builtin_amdgcn_s_sleep(2);
+                    ++it;
+                }
+                if (tid == 0) ll_store(a.done_ll + w, 0.f, tag_done);
+            }
+        };
+        for (int l = a.lb; l < a.le; ++l) {
+            const unsigned tag0 = a.tag_base + (unsigned)(l - a.lb) * TAGS_PER_LAYER;
+            if (a.ticks[0] > 0) window(a.da_ll, tag0 + TAG_DA, 0, tag0 + TAG_WIN0);
+            if (a.ticks[1] > 0) window(a.dm_ll, tag0 + TAG_DM, 1, tag0 + TAG_WIN1);
+        }
+        if (__any(lost) && (tid & 63) == 0) atomicOr(a.err, 2u);
+        return;
+    }
+    StepState<ITH> st;
     {
         const SegGeom gs[4] = {a.gq, a.go, a.g1, a.g2};
         const int Ns[4] = {a.QR, a.H, a.F, a.H};
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
             const int groups = 512 >> gs[p].gs_log2, gid = tid >> gs[p].gs_log2;
-            const int slots = gridDim.x * groups, slot = blockIdx.x * groups + gid;
+            const int slots = nwg * groups, slot = blockIdx.x * groups + gid;
             st.rb[p] = (int)((long long)slot * Ns[p] / slots);
             st.re[p] = (int)((long long)(slot + 1) * Ns[p] / slots);
         }
@@ -922,9 +933,11 @@ bool step_supported(int batch, int H, int F, int nq, int nkv, uint32_t max_seq, 
 {
     if (!seg_attn_supported(batch, H, nq, nkv, max_seq, other_cache, blocks) || !seg_mlp_supported(batch, H, F)) return false;
     const int QR = (nq + 2 * nkv) * 128, QD = nq * 128, ith = H > 4096 ? 2 : 1, it2 = F > 4096 ? 2 : 1;
-    const SegGeom gq = seg_geom(QR, H, ith, w8 ? 8 : 4, blocks), go = seg_geom(H, QD, 1, w8 ? 16 : 8, blocks);
-    const SegGeom g1 = seg_geom(F, H, ith, 8, blocks), g2 = seg_geom(H, F, it2, w8 ? 16 : 8, blocks);
-    auto slots = [&](SegGeom g) __attribute__((always_inline)) { return (long long)blocks * (512 >> g.gs_log2); };
+    const int nwg = blocks - 1;                    // one workgroup keeps the windows' time
+    if (nwg < 1 || nkv * seg_attn_chunks(max_seq) > nwg) return false;
+    const SegGeom gq = seg_geom(QR, H, ith, w8 ? 8 : 4, nwg), go = seg_geom(H, QD, 1, w8 ? 16 : 8, nwg);
+    const SegGeom g1 = seg_geom(F, H, ith, 8, nwg), g2 = seg_geom(H, F, it2, w8 ? 16 : 8, nwg);
+    auto slots = [&](SegGeom g) { return (long long)nwg * (512 >> g.gs_log2); };
     return QR >= slots(gq) && H >= slots(go) && F >= slots(g1) && H >= slots(g2);
 }
 
@@ -932,10 +945,10 @@ template <int ITH, int IT2, bool W8>
 static hipError_t step_go(StepArgs a, int blocks, hipStream_t s)
 {
     constexpr int RBQ = W8 ? 8 : 4, RBO = W8 ? 16 : 8, RB1 = (ITH == 1 ? 8 : 4) * (W8 ? 2 : 1), RB2 = W8 ? 16 : 8;
-    a.gq = seg_geom(a.QR, a.H, ITH, RBQ, blocks);
-    a.go = seg_geom(a.H, a.QD, 1, RBO, blocks);
-    a.g1 = seg_geom(a.F, a.H, ITH, RB1, blocks);
-    a.g2 = seg_geom(a.H, a.F, IT2, RB2, blocks);
+    a.gq = seg_geom(a.QR, a.H, ITH, RBQ, blocks - 1);      // the last workgroup computes nothing
+    a.go = seg_geom(a.H, a.QD, 1, RBO, blocks - 1);
+    a.g1 = seg_geom(a.F, a.H, ITH, RB1, blocks - 1);
+    a.g2 = seg_geom(a.H, a.F, IT2, RB2, blocks - 1);
     PSV_LAUNCH((k_step<ITH, IT2, W8>), dim3(blocks), dim3(512), 0, s, a);
     return hipGetLastError();
 }
