@@ -54,8 +54,9 @@ def parse():
     ap.add_argument("--tune", type=int, default=0,
                     help="1 = let the library time its candidate attention splits on layer 0 first (psv_tune_attention); "
                          "the default split is within ~1 %% of the tuned one on the five workloads")
-    ap.add_argument("--fused", type=int, default=0,
-                    help="1 = fused kernels per inter-window segment at batch 1, 2 = the whole step as one kernel (psv_set_fused_kernels)")
+    ap.add_argument("--fused", type=int, default=-1,
+                    help="kernels of the batch-1 path (psv_set_fused_kernels): 0 = one per operator, 1 = one per inter-window "
+                         "segment, 2 = the whole step as one kernel, -1 (default) = the library chooses by shape")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-layers", type=int, default=0, help="layers the oracle is timed on (0 = auto)")
     ap.add_argument("--seed", type=int, default=2501)
@@ -186,6 +187,27 @@ def other_workload(name, n_layers, steps, warmup, seed):
     return res
 
 
+def per_operator_leg(w, layers, steps, warmup, seed, policies, gate_bytes):
+    """The same workload with one kernel per operator (psv_set_fused_kernels 0), for a record whose timed path runs the
+    per-segment kernels: the three modes and the gate/up kernel's own bandwidth with prefetching off."""
+    from paper_2501_08192_amd import binding as psv
+    from paper_2501_08192_amd.harness import Session
+    with Session(w, seed=seed, layers=layers, fused=0) as sess:
+        L = len(sess.layers)
+        res = {"us_per_layer": {}}
+        for mode, pol in policies.items():
+            sess.set_policy(pol)
+            sess.run()
+            res["us_per_layer"][mode] = round(time_steps(sess, steps, warmup) * 1e3 / L, 3)
+        sess.set_policy(policies["off"])
+        t, n = profile_op(sess, psv.PSV_OP_GATE, max(3, min(steps, 10)))
+        res["roofline_gate_up"] = {"kernel": "gate/up projection + SwiGLU (prefetch off), not in the timed path of this record",
+                                   "bytes_per_launch": gate_bytes, "avg_us": round(t, 3), "launches": n,
+                                   "achieved": round(gate_bytes / t / 1e3, 1), "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                   "frac": round(gate_bytes / t / 1e3 / HBM_PEAK_GBPS, 4)}
+    return res
+
+
 def stored_traffic(workload, kernel):
     """HBM bytes per launch of a kernel as recorded in the committed rocprofv3 counter summary of this workload:
     (bytes, path of the summary) or (None, None).  A stored figure from an earlier profiler run, not a measurement
@@ -222,7 +244,7 @@ def main():
         w = w.scaled(weight_format="int8" if a.format in ("int8", "w8") else "bf16",
                      kv_format="int8" if a.format in ("int8", "kv8") else "bf16")
     layers = list(range(a.layers)) if a.layers else None
-    sess = Session(w, seed=a.seed, layers=layers, fused=a.fused)
+    sess = Session(w, seed=a.seed, layers=layers, fused=None if a.fused < 0 else a.fused)
     L = len(sess.layers)
     MB = 1 << 20
     if a.budget_mb <= 0:
@@ -278,7 +300,9 @@ def main():
         torch.cuda.synchronize()
         psv.psv_copy_bytes(dst, src, nb, sess.main)
         sess.sync()
-    whole_step = psv.psv_debug_last_step_path(sess.ctx) == 2      # the step is one kernel: no per-operator table
+    path = psv.psv_debug_last_step_path(sess.ctx)   # 0 one kernel per operator, 1 one per segment, 2 one per step
+    fused_on = path >= 1
+    whole_step = path == 2                          # the step is one kernel: no per-operator table
     step_kernel = None
     if whole_step:
         # the kernel's own duration without windows, prefetch off: all the step's bytes over that time is its bandwidth
@@ -306,15 +330,16 @@ def main():
                 # its weights were requested while the window ran: the time left after the window is no bandwidth figure
                 k["us_after_window_on"] = round(t, 3)
                 del k["us_on"]
-            elif not a.fused:
+            elif not fused_on:
                 k["gbps_" + mode_name] = round(op_bytes[name] / t / 1e3, 1)
     if whole_step:
         gate_us, gate_n, gate_bytes = step_kernel["us"], step_kernel["launches"], step_kernel["bytes"]
     else:
         gate_us, gate_n = kernels["gate_up"]["us_off"], kernels["gate_up"]["launches"]
-        gate_bytes = op_bytes["gate_up"] + (op_bytes["down"] if a.fused and kernels["down"]["launches"] == 0 else 0)
+        gate_bytes = op_bytes["gate_up"] + (op_bytes["down"] if fused_on and kernels["down"]["launches"] == 0 else 0)
     achieved = gate_bytes / gate_us / 1e3
-    traffic, traffic_src = stored_traffic(w.name, "gate_up") if (a.format == "bf16" and not a.fused) else (None, None)
+    traffic, traffic_src = (stored_traffic(w.name, "mlp_fused" if fused_on else "gate_up")
+                            if (a.format == "bf16" and not whole_step) else (None, None))
 
     out = {
         "metric": "decode_step_latency_us_per_layer_prefetch_on",
@@ -335,7 +360,7 @@ def main():
                                                       w.context, "paged" if w.paged else "contiguous", *w.window_us),
                    "prefetch_budget_mb": a.budget_mb, "cu_budget": a.cu_budget, "chunk_mb": a.chunk_mb,
                    "partial": a.partial, "join": a.join, "prelaunch": a.prelaunch, "prelaunch_active": prelaunch_active,
-                   "targets": a.targets, "fused_kernels": int(a.fused), "whole_step_kernel": whole_step, "streams_overlap": bool(sess.overlap),
+                   "targets": a.targets, "fused_kernels": "by shape" if a.fused < 0 else int(a.fused), "kernel_path": path, "streams_overlap": bool(sess.overlap),
                    "attn_tokens_per_workgroup": attn_chunk if a.tune else "default"},
         "us_per_layer_prefetch_off": round(us["off"], 3),
         "us_per_layer_cache_only": round(us["cache_only"], 3),
@@ -380,8 +405,14 @@ def main():
     sess.close()
     del sess, flush
     torch.cuda.empty_cache()
+    if path == 1 and a.fused < 0:
+        # the library chose the per-segment kernels for this shape: the record also carries the per-operator kernels
+        out["per_operator_kernels"] = per_operator_leg(w, layers, max(10, min(a.steps, 50)), min(a.warmup, 10), a.seed, modes,
+                                                       op_bytes["gate_up"])
+        best_off = min(out["us_per_layer_prefetch_off"], out["per_operator_kernels"]["us_per_layer"]["off"])
+        out["speedup_vs_fastest_off"] = round(best_off / out["value"], 4)
     others = [n for n in a.also.split(",") if n and n != a.workload]
-    if others and a.format == "bf16" and not a.fused and a.window_us is None:
+    if others and a.format == "bf16" and a.fused < 0 and a.window_us is None:
         out["other_workloads"] = {n: other_workload(n, a.also_layers, max(10, min(a.steps, 50)), min(a.warmup, 10), a.seed)
                                   for n in others}
     print(json.dumps(out))

@@ -23,7 +23,7 @@ extern "C" {
  * HIP runtime whose cause was not found. */
 psv_status psv_set_graph_mode(psv_ctx *ctx, uint32_t use_graph);
 
-/* 0 (default) = one kernel per operator; 1 = at batch 1, where the shape allows it (bf16 cache, sequences up to 4096
+/* 0 = one kernel per operator; 1 = at batch 1, where the shape allows it (bf16 cache, sequences up to 4096
  * tokens), the operators between two communication windows run as one fused kernel each (QKV + attention + O;
  * gate/up + down) whose phases hand their results over through tagged values in memory.  Faster by ~3 us per layer
  * on an 8B-shaped shard when the kernels are launched into the windows (policy.prelaunch), slower otherwise.  The two
@@ -33,7 +33,10 @@ psv_status psv_set_graph_mode(psv_ctx *ctx, uint32_t use_graph);
  * step is ONE kernel: resident workgroups walk the layers, the residual stream stays in registers, the communication
  * windows are timed inside the kernel, and what the plan hands to a window whole is requested into registers before the
  * window's end (nothing runs on the side stream; an operator the plan covers only in part is not requested early).
- * Shapes it does not take run as under 1.  Per-operator profiling sees one kernel (reported as the QKV operator). */
+ * Shapes it does not take run as under 1.  Per-operator profiling sees one kernel (reported as the QKV operator).
+ * 3 (default) = the library chooses by shape between 0 and 1: 1 where rows have at least 4096 elements and all
+ * weights of a block fit the registers of one pass (an 8B-shaped TP=8 shard does), 0 elsewhere.
+ * psv_decode_step_static always runs as under 0. */
 psv_status psv_set_fused_kernels(psv_ctx *ctx, uint32_t on);
 
 /* ---- streams and tuning -------------------------------------------------------------------- */

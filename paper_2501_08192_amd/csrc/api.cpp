@@ -202,7 +202,7 @@ psv_status psv_debug_last_step_path(psv_ctx *c, uint32_t *path)
 
 psv_status psv_set_fused_kernels(psv_ctx *c, uint32_t on)
 {
-    if (!c || on > 2) return PSV_ERR_INVALID_ARG;
+    if (!c || on > 3) return PSV_ERR_INVALID_ARG;
     c->fused = (int)on;
     return PSV_OK;
 }

@@ -55,7 +55,7 @@ struct psv_ctx {
     uint32_t attn_chunk_tokens = 0;               // 0 = default split; else tokens per attention workgroup (psv_tune_attention)
     int overlap = -1;                            // psv_check_overlap's last answer (-1 = not run yet)
     bool check_err_word = false;                 // a kernel that may set the error word (a pre-launched consumer, a fused kernel) was launched: read it at sync
-    int fused = 0;                               // psv_set_fused_kernels: 0 one kernel per operator, 1 one per block, 2 one per step
+    int fused = 3;                               // psv_set_fused_kernels: 0 one kernel per operator, 1 one per block, 2 one per step, 3 by shape
     bool step_tbl_dirty = true;                  // the per-layer pointer table of the whole-step kernel has to be uploaded again
     std::vector<unsigned char> step_tbl_host;    // ... its host copy (kept alive until the upload has run)
     bool force_wait_timeout = false;             // test aid: such consumers give up waiting at once (and report it)

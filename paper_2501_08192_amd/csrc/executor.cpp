@@ -432,11 +432,22 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
                      gemv_supported(B, F, H) && gemv_supported(B, H, F);
     const bool sk = !vec;
     c->last_step_vec = vec;
-    // The vector path runs the operators between two windows as one fused kernel where the shape allows it.  Which
-    // kernels run depends on the shape only, never on the policy, so every policy gives the same bits.
-    const int blocks = c->fused ? c->cus : 0;
+    // Which kernels run depends on the shape and the caller's setting only, never on the policy, so every policy gives
+    // the same bits.  Left to the library (3), the per-block kernels are used where they are the faster way to run with
+    // prefetching on: rows of at least 4096 elements and blocks whose weights all fit the registers of one pass, so that
+    // a kernel launched into its window holds its whole block when the window ends (measured on such a shard: 3.5 us per
+    // layer faster with prefetching on, equal with prefetching off; on smaller or multi-pass shapes 3-9 us slower).
+    int fused = c->fused;
+    if (fused == 3) {
+        const bool other_cache = d.kv_format == PSV_FMT_INT8 || d.kv_layout != PSV_KV_HEAD_MAJOR;
+        fused = vec && c->cus >= 64 && H >= 4096 && seg_mlp_supported(B, H, F) && seg_attn_supported(B, H, nq, nkv, d.max_seq, other_cache, c->cus) &&
+                        seg_mlp_holds_gate_up(H, F, w8, c->cus) && seg_mlp_holds_down(H, F, w8, c->cus) &&
+                        seg_attn_holds_qkv(H, QR, w8, c->cus) && seg_attn_holds_o(H, nq, w8, c->cus)
+                    ? 1 : 0;
+    }
+    const int blocks = fused ? c->cus : 0;
     c->last_step_whole = false;
-    if (c->fused == 2 && vec && blocks >= 64 &&
+    if (fused == 2 && vec && blocks >= 64 &&
         step_supported(B, H, F, nq, nkv, d.max_seq, d.kv_format == PSV_FMT_INT8 || d.kv_layout != PSV_KV_HEAD_MAJOR, w8, blocks))
         return enqueue_whole_step(c, x_in, x_out, lb, le, blocks);
     const bool seg_mlp = vec && blocks >= 64 && seg_mlp_supported(B, H, F);

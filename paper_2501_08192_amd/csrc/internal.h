@@ -92,7 +92,9 @@ unsigned next_tag();
 // wait != null: launched into the window ahead of its inputs, see GemvWait; hold_down = false makes that variant
 // request the down weights only after the window's end (the plan did not hand them to this window).
 bool seg_mlp_supported(int batch, int H, int F);
-// does the first pass of the down projection (the part requested at the start of the kernel) cover all of W_down?
+// do the first passes of the gate/up and of the down projection (what the kernel requests at its start) cover all of
+// W_gate and W_up / all of W_down?
+bool seg_mlp_holds_gate_up(int H, int F, bool w8, int blocks);
 bool seg_mlp_holds_down(int H, int F, bool w8, int blocks);
 hipError_t launch_seg_mlp(Mat Wg, Mat Wu, Mat Wd, const float *res, const float *delta, const uint16_t *gain, float eps,
                           float *out_res, float *out_h, void *m_ll, float *out, int batch, int H, int F, unsigned tag,
@@ -105,6 +107,7 @@ hipError_t launch_seg_mlp(Mat Wg, Mat Wu, Mat Wd, const float *res, const float 
 int seg_attn_chunks(uint32_t max_seq);
 bool seg_attn_supported(int batch, int H, int nq, int nkv, uint32_t max_seq, bool kv_int8, int blocks);
 bool seg_attn_holds_o(int H, int nq, bool w8, int blocks);      // the first pass of the O projection covers all of W_o
+bool seg_attn_holds_qkv(int H, int QR, bool w8, int blocks);    // ... of the QKV projection all of W_qkv
 hipError_t launch_seg_attn(Mat Wq, Mat Wo, const float *res, const float *delta, const uint16_t *gain, float eps,
                            float *out_res, float *out_h, void *qkv_ll, const float2 *rope, KvView kv, int nq, int nkv,
                            int n_chunks, void *pml_ll, void *po_ll, float *out_attn, float *out, int H, unsigned tag,

@@ -460,6 +460,13 @@ bool seg_mlp_supported(int batch, int H, int F)
     return batch == 1 && H % 8 == 0 && F % 8 == 0 && H >= 64 && F >= 64 && H <= 8192 && F <= 8192;
 }
 
+bool seg_mlp_holds_gate_up(int H, int F, bool w8, int blocks)
+{
+    const int r1 = w8 ? 8 : 4;
+    if (H > 4096) return seg_geom(F, H, 2, r1, blocks).passes == 1;
+    return seg_geom(F, H, 1, r1, blocks).passes <= (F > 4096 ? 1 : 2);     // see seg_mlp_pick: two passes' worth fit when rows are long
+}
+
 bool seg_mlp_holds_down(int H, int F, bool w8, int blocks)
 {
     return seg_geom(H, F, F > 4096 ? 2 : 1, w8 ? 16 : 8, blocks).passes == 1;

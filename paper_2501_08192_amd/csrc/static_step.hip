@@ -63,6 +63,7 @@ extern "C" psv_status psv_decode_step_static(const psv_model_desc *desc, const p
     c.k_pools.assign(desc->n_layers, nullptr);
     c.v_pools.assign(desc->n_layers, nullptr);
     c.policy.mode = 0;
+    c.fused = 0;                            // one kernel per operator: nothing here reads the error word of a fused kernel
     for (uint32_t l = layer_begin; l < layer_end; ++l) ST_TRY(psv_set_layer_weights(&c, l, &layers[l]));
     {
         // layers outside the range are not run; psv_set_kv wants a pool pointer for every layer

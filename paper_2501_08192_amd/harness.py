@@ -23,7 +23,7 @@ class Session:
     """
 
     def __init__(self, w: synth.Workload, seed=2501, device="cuda:0", layers=None, pool_slack_blocks=0, max_seq=None,
-                 fused=False):
+                 fused=None):
         if not torch.cuda.is_available():
             raise RuntimeError("the PRESERVE decode path needs a GPU; there is no CPU fallback")
         self.w = w
@@ -50,7 +50,7 @@ class Session:
             self._spare_streams.append(self.side)
         else:
             self.ctx = psv.psv_create(self.desc, self.main, self.side)
-        if fused:
+        if fused is not None:      # None: the library chooses by shape
             psv.psv_set_fused_kernels(self.ctx, int(fused))
         self.pool_blocks = w.pool_blocks + int(pool_slack_blocks)
         self.weights, self.k_pools, self.v_pools = {}, {}, {}
