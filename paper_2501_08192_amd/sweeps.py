@@ -242,9 +242,10 @@ def record(path, layers=4, out=print):
             pol = default_policy(w, **kw)
             s.set_policy(pol)
             pre = timed(s, n_layers)
+            kernel_path = psv.psv_debug_last_step_path(s.ctx)      # 0: one kernel per operator, 1: one per segment
         rows.append({"name": name, "hidden": w.hidden, "n_q": w.n_q_heads, "n_kv": w.n_kv_heads, "ffn": w.ffn, "batch": w.batch,
                      "context": w.context, "windows": list(w.window_us), "budget": int(pol.budget_bytes), "partial": int(pol.partial),
-                     "us_off": round(off, 2), "us_cache_only": round(cache, 2), "us_default": round(pre, 2)})
+                     "us_off": round(off, 2), "us_cache_only": round(cache, 2), "us_default": round(pre, 2), "kernel_path": kernel_path})
         out(str(rows[-1]))
         torch.cuda.empty_cache()
 

@@ -92,16 +92,21 @@ def test_calibrated_model_predicts_every_measured_row():
 
 def test_calibrated_model_ranks_the_modes_like_the_measurement_at_batch_one():
     """Where the first consumers are launched into their windows (vector path) the measured gain over the cache-only
-    policy is 3-6 us per layer on the large shapes; the model has to see a gain of the same order."""
+    policy is 3-6 us per layer on the large shapes; the model has to see a gain of the same order.  Rows that the library
+    runs with one kernel per inter-window segment (kernel_path 1: the 8B-shaped TP=8 shard) are left out: the model has
+    no class for those kernels, whose gain from being launched into the window is about twice as large."""
     m = model.Machine.load()
+    seen = 0
     for r in _golden()["rows"]:
-        if model.path_of(r["batch"], r["hidden"]) != "vec" or r["hidden"] < 4096:
+        if model.path_of(r["batch"], r["hidden"]) != "vec" or r["hidden"] < 4096 or r.get("kernel_path", 0) != 0:
             continue
+        seen += 1
         b = model.op_bytes(r["hidden"], r["n_q"], r["n_kv"], r["ffn"], r["batch"], r["context"])
         w = tuple(r["windows"])
         gain_model = model.layer_time(b, w, m, r["budget"]) - model.layer_time(b, w, m, r["budget"], prelaunch=True)
         gain_meas = r["us_cache_only"] - r["us_default"]
         assert gain_meas > 1.0 and 0.4 * gain_meas < gain_model < 2.5 * gain_meas, (r["name"], gain_meas, gain_model)
+    assert seen >= 3
 
 
 def test_calibrated_model_finds_the_budget_knee_of_the_kv_dominated_workload():
