@@ -142,10 +142,12 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
     uint4 gv[ITERS];                             // NORM: gains
     float2 mt[MB];                               // MERGE: (max, sum) and two 16-byte pieces of the partial of MB chunks
     float4 mo0[MB], mo1[MB];
+    if (MODE == GEMV_NORM)
+#pragma unroll
+        for (int it = 0; it < ITERS; ++it) gv[it] = kok[it] ? ld16(a.gain + kk[it]) : zero16();   // constants: never after a wait
     if (ahead) {
 #pragma unroll
         for (int it = 0; it < ITERS; ++it) {
-            gv[it] = kok[it] ? ld16(a.gain + kk[it]) : zero16();
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -205,9 +207,6 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
     // ---- activations into registers
     float xv[ITERS][NB][8];
     if (MODE == GEMV_NORM) {
-        if (WAIT)
-#pragma unroll
-            for (int it = 0; it < ITERS; ++it) gv[it] = kok[it] ? ld16(a.gain + kk[it]) : zero16();
         float ss[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {

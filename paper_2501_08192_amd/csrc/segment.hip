@@ -171,10 +171,11 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
     //      requests the weights of both phases, waits for the window's end and only then reads the residual.
     float4 xr[IT1][NB][2], xd[IT1][NB][2];
     uint4 gv[IT1];
+#pragma unroll
+    for (int it = 0; it < IT1; ++it) gv[it] = ok1[it] ? ld16(a.gain + k1[it]) : zero16();   // constants: never after the wait
     if (!WAIT) {
 #pragma unroll
         for (int it = 0; it < IT1; ++it) {
-            gv[it] = ok1[it] ? ld16(a.gain + k1[it]) : zero16();
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
@@ -220,9 +221,6 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
     // ---- rmsnorm(res + delta) * gain into registers
     float xv[IT1][NB][8];
     {
-        if (WAIT)
-#pragma unroll
-            for (int it = 0; it < IT1; ++it) gv[it] = ok1[it] ? ld16(a.gain + k1[it]) : zero16();
         float ss[NB];
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
@@ -677,10 +675,11 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
     if (early) lookup(blkA0, blkB0);
     float4 xr[ITQ][2], xd[ITQ][2];
     uint4 gv[ITQ];
+#pragma unroll
+    for (int it = 0; it < ITQ; ++it) gv[it] = ok1[it] ? ld16(a.gain + k1[it]) : zero16();   // constants: never after the wait
     if (!WAIT) {
 #pragma unroll
         for (int it = 0; it < ITQ; ++it) {
-            gv[it] = ok1[it] ? ld16(a.gain + k1[it]) : zero16();
             const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
             xr[it][0] = xr[it][1] = xd[it][0] = xd[it][1] = z;
             if (ok1[it]) {
@@ -725,9 +724,6 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
     // ---- rmsnorm(res + delta) * gain into registers
     float xv[ITQ][8];
     {
-        if (WAIT)
-#pragma unroll
-            for (int it = 0; it < ITQ; ++it) gv[it] = ok1[it] ? ld16(a.gain + k1[it]) : zero16();
         float ss = 0.f;
 #pragma unroll
         for (int it = 0; it < ITQ; ++it) {
