@@ -64,6 +64,9 @@ def parse():
     ap.add_argument("--format", default="bf16", choices=["bf16", "int8", "w8", "kv8"],
                     help="storage format of weights and KV-cache: bf16 (the benchmark's), int8 (both, the paper's "
                          "measurement precision), w8 / kv8 (only the weights / only the cache in int8)")
+    ap.add_argument("--weight-layout", default="", choices=["", "row", "tiled"],
+                    help="storage order of the projection matrices: row-major, or the tiled order of the matrix-core "
+                         "projections (default: the workload's own)")
     ap.add_argument("--calibrate-copy-mb", type=int, default=0,
                     help="also launch one plain copy kernel of this size (known bytes, to scale hardware counters)")
     ap.add_argument("--skip-kernel-table", action="store_true", help="omit the per-operator event timing passes")
@@ -243,6 +246,8 @@ def main():
     if a.format != "bf16":
         w = w.scaled(weight_format="int8" if a.format in ("int8", "w8") else "bf16",
                      kv_format="int8" if a.format in ("int8", "kv8") else "bf16")
+    if a.weight_layout:
+        w = w.scaled(weight_layout=a.weight_layout)
     layers = list(range(a.layers)) if a.layers else None
     sess = Session(w, seed=a.seed, layers=layers, fused=None if a.fused < 0 else a.fused)
     L = len(sess.layers)
@@ -356,8 +361,9 @@ def main():
             a.format, w.weight_format, w.kv_format),
         "data": "synthetic",
         "config": {"workload": "%s: %d layers, hidden %d, %d q / %d kv heads x 128, ffn %d, batch %d, context %d, %s KV, "
-                               "windows %g/%g us" % (w.name, L, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch,
-                                                      w.context, "paged" if w.paged else "contiguous", *w.window_us),
+                               "%s weights, windows %g/%g us" % (w.name, L, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch,
+                                                      w.context, "paged" if w.paged else "contiguous",
+                                                      "tiled" if w.weight_layout == "tiled" else "row-major", *w.window_us),
                    "prefetch_budget_mb": a.budget_mb, "cu_budget": a.cu_budget, "chunk_mb": a.chunk_mb,
                    "partial": a.partial, "join": a.join, "prelaunch": a.prelaunch, "prelaunch_active": prelaunch_active,
                    "targets": a.targets, "fused_kernels": "by shape" if a.fused < 0 else int(a.fused), "kernel_path": path, "streams_overlap": bool(sess.overlap),

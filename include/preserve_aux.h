@@ -86,6 +86,12 @@ psv_status psv_spin(float us, void *stream);
  * byte counters against a known size. */
 psv_status psv_copy_bytes(void *dst, const void *src, uint64_t bytes, void *stream);
 
+/* Rewrites a row-major projection matrix [rows][cols] (dev, bf16 or int8 codes per `weight_format`) into the tiled
+ * layout of PSV_W_TILED (preserve.h) at dst (dev, same size, must not overlap src); rows % 128 == 0, cols % 64 == 0,
+ * both pointers 16-byte aligned.  Row scales of an int8 matrix are not touched (they stay one per row).  Asynchronous
+ * on `stream`. */
+psv_status psv_tile_weights(void *dst, const void *src, uint32_t rows, uint32_t cols, uint32_t weight_format, void *stream);
+
 /* Test aid for the prelaunch policy: while on, a kernel launched ahead of its window's end gives up its
  * (always bounded) wait at once.  The kernel then still completes, sets an error word, and the next psv_sync
  * returns PSV_ERR_TIMEOUT once; the context stays usable. */

@@ -19,6 +19,8 @@ PSV_FMT_BF16, PSV_FMT_INT8 = 0, 1
 FORMATS = {"bf16": PSV_FMT_BF16, "int8": PSV_FMT_INT8}
 PSV_KV_HEAD_MAJOR, PSV_KV_TOKEN_MAJOR = 0, 1
 KV_LAYOUTS = {"head": PSV_KV_HEAD_MAJOR, "token": PSV_KV_TOKEN_MAJOR}
+PSV_W_ROW_MAJOR, PSV_W_TILED = 0, 1
+WEIGHT_LAYOUTS = {"row": PSV_W_ROW_MAJOR, "tiled": PSV_W_TILED}
 PSV_KV_UNIT_BYTES_BF16, PSV_KV_UNIT_BYTES_INT8 = 4096, 2112
 PSV_STATIC_SCRATCH_BYTES = 16 << 20
 PSV_DBG_H1, PSV_DBG_QKV, PSV_DBG_ATTN, PSV_DBG_Y, PSV_DBG_H2, PSV_DBG_M = range(6)
@@ -29,7 +31,7 @@ EXPORTS = [
     "psv_set_graph_mode", "psv_decode_step", "psv_sync", "psv_get_stats", "psv_tune_attention", "psv_check_overlap",
     "psv_set_profile_op",
     "psv_get_profile", "psv_prefetch_region", "psv_spin", "psv_copy_bytes", "psv_debug_read",
-    "psv_debug_force_wait_timeout", "psv_decode_step_static", "psv_set_fused_kernels", "psv_debug_last_step_path",
+    "psv_debug_force_wait_timeout", "psv_decode_step_static", "psv_set_fused_kernels", "psv_debug_last_step_path", "psv_tile_weights",
 ]
 
 
@@ -38,7 +40,7 @@ class psv_model_desc(C.Structure):
                 ("n_kv_heads", C.c_uint32), ("head_dim", C.c_uint32), ("ffn", C.c_uint32),
                 ("rms_eps", C.c_float), ("rope_theta", C.c_float), ("max_batch", C.c_uint32),
                 ("max_seq", C.c_uint32), ("weight_format", C.c_uint32), ("kv_format", C.c_uint32),
-                ("kv_layout", C.c_uint32)]
+                ("kv_layout", C.c_uint32), ("weight_layout", C.c_uint32)]
 
 
 class psv_layer_weights(C.Structure):
@@ -115,6 +117,7 @@ def lib():
             "psv_debug_read": (C.c_int32, [vp, u32, vp, sz]),
             "psv_debug_force_wait_timeout": (C.c_int32, [vp, u32]),
             "psv_debug_last_step_path": (C.c_int32, [vp, C.POINTER(u32)]),
+            "psv_tile_weights": (C.c_int32, [vp, vp, u32, u32, u32, vp]),
             "psv_set_fused_kernels": (C.c_int32, [vp, u32]),
             "psv_decode_step_static": (C.c_int32, [C.POINTER(psv_model_desc), C.POINTER(psv_layer_weights),
                                                    C.POINTER(psv_kv_desc), vp, vp, u32, u32, u32, vp]),
@@ -151,9 +154,9 @@ def strerror(status):
 
 
 def model_desc(n_layers, hidden, n_q_heads, n_kv_heads, ffn, max_batch, max_seq, head_dim=128, rms_eps=1e-5,
-               rope_theta=500000.0, weight_format="bf16", kv_format="bf16", kv_layout="head"):
+               rope_theta=500000.0, weight_format="bf16", kv_format="bf16", kv_layout="head", weight_layout="row"):
     return psv_model_desc(n_layers, hidden, n_q_heads, n_kv_heads, head_dim, ffn, rms_eps, rope_theta, max_batch,
-                          max_seq, FORMATS[weight_format], FORMATS[kv_format], KV_LAYOUTS[kv_layout])
+                          max_seq, FORMATS[weight_format], FORMATS[kv_format], KV_LAYOUTS[kv_layout], WEIGHT_LAYOUTS[weight_layout])
 
 
 def prefetch_policy(mode=0, targets=PSV_TARGET_WEIGHTS | PSV_TARGET_KV, budget_bytes=0, chunk_bytes=0, cu_budget=0,
@@ -300,6 +303,12 @@ def psv_debug_read(ctx, which, host_array):
 def psv_set_fused_kernels(ctx, on):
     """on: 0 / False = one kernel per operator, 1 / True = one per block, 2 = the whole step as one kernel."""
     _check(lib().psv_set_fused_kernels(ctx, int(on)), "psv_set_fused_kernels")
+
+
+def psv_tile_weights(dst, src, rows, cols, weight_format, stream):
+    """dst, src: device tensors of rows * cols elements; weight_format "bf16" or "int8"."""
+    _check(lib().psv_tile_weights(_dev_ptr(dst), _dev_ptr(src), int(rows), int(cols), FORMATS[weight_format], _stream(stream)),
+           "psv_tile_weights")
 
 
 def psv_debug_last_step_path(ctx):

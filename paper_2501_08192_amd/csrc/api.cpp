@@ -220,7 +220,7 @@ psv_status psv_get_stats(psv_ctx *c, psv_stats *out)
     out->kv_bytes_per_layer = op_mem_size(c->d, PSV_OP_ATTN, batch, context + 1);   // the whole span, new token included
     for (const psv_plan_entry &e : c->plan) out->planned_prefetch_bytes += e.bytes;
     out->workspace_bytes = c->ws.total;
-    const bool vec = (batch == 1 || (batch == 2 && c->d.hidden <= 4096)) && c->d.hidden <= 8192 && c->d.ffn <= 8192;
+    const bool vec = c->d.weight_layout == PSV_W_ROW_MAJOR && (batch == 1 || (batch == 2 && c->d.hidden <= 4096)) && c->d.hidden <= 8192 && c->d.ffn <= 8192;
     out->kernels_per_layer = (vec ? 5 : 7) + (c->window_us[0] > 0.f ? 1 : 0) + (c->window_us[1] > 0.f ? 1 : 0);
     out->prefetch_launches = c->last_prefetch_launches;
     out->steps = c->steps;
@@ -345,6 +345,20 @@ psv_status psv_spin(float us, void *stream)
     if (!(us >= 0.f) || us > 1.0e6f) return PSV_ERR_INVALID_ARG;
     if (us == 0.f) return PSV_OK;
     HIP_TRY(launch_spin(us_to_ticks(current_clock_khz(), us), spin_cap(us), nullptr, nullptr, 0, static_cast<hipStream_t>(stream)));
+    return PSV_OK;
+}
+
+psv_status psv_tile_weights(void *dst, const void *src, uint32_t rows, uint32_t cols, uint32_t weight_format, void *stream)
+{
+    if (!dst || !src || dst == src || weight_format > PSV_FMT_INT8) return PSV_ERR_INVALID_ARG;
+    if (rows == 0 || cols == 0 || rows % 128 || cols % 64 || rows > (1u << 20) || cols > (1u << 20)) return PSV_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(dst) % 16 || reinterpret_cast<uintptr_t>(src) % 16) return PSV_ERR_INVALID_ARG;
+    {
+        const size_t bytes = (size_t)rows * cols * (weight_format == PSV_FMT_INT8 ? 1 : 2);
+        const char *a = static_cast<const char *>(src), *b = static_cast<const char *>(dst);
+        if ((a < b ? b - a : a - b) < (ptrdiff_t)bytes) return PSV_ERR_INVALID_ARG;      // the two regions overlap
+    }
+    HIP_TRY(launch_tile_weights(dst, src, (int)rows, (int)cols, weight_format == PSV_FMT_INT8 ? 1 : 2, static_cast<hipStream_t>(stream)));
     return PSV_OK;
 }
 

@@ -134,6 +134,7 @@ Mat mat_of(const psv_ctx *c, const psv_layer_weights &w, uint32_t op)
     case PSV_OP_DOWN: m.w = w.w_down; m.scale = q8 ? w.s_down : nullptr; break;
     default: break;
     }
+    m.tiled = c->d.weight_layout == PSV_W_TILED;
     return m;
 }
 
@@ -428,7 +429,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     // residual kernel (O, down) or a small reduction kernel (QKV; gate/up with SwiGLU), the RMSNorm factor being
     // applied in the epilogue of the GEMM that follows the residual kernel.
     // (Measured crossover: the vector path loses ~10 us per layer and extra batch row to register pressure.)
-    const bool vec = (B == 1 || (B == 2 && H <= 4096)) && gemv_supported(B, QR, H) && gemv_supported(B, H, QD) &&
+    const bool vec = d.weight_layout == PSV_W_ROW_MAJOR && (B == 1 || (B == 2 && H <= 4096)) && gemv_supported(B, QR, H) && gemv_supported(B, H, QD) &&
                      gemv_supported(B, F, H) && gemv_supported(B, H, F);
     const bool sk = !vec;
     c->last_step_vec = vec;

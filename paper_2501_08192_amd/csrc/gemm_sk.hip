@@ -90,6 +90,7 @@ struct GemmSkArgs {
     // holds partial sums of squares of x (k_resid_sum) and the epilogue multiplies column b by 1/rms(b)
     const float *ssq;
     float eps;
+    int tiled;                // weights in the tiled layout: a workgroup's 128 rows x 64 elements per slab are contiguous
 };
 
 template <int NB>
@@ -105,28 +106,38 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
     // Lane (i, g) owns elements g*8 .. g*8+7 of both 32-element halves of row i of every 64-element slab (the matrix
     // cores' own operand order): each of its two load instructions covers 64 contiguous bytes of every row, whole
     // 32-byte sectors, instead of 16 bytes out of every 32.
+    // Tiled storage: the unit of (row tile, slab) is 16 KiB in exactly this order -- [wave][row group][k half][lane] --
+    // so every load instruction of a wave covers 1 KiB of contiguous memory and the workgroup walks one contiguous run.
     const uint16_t *wp[2];
     bool wok[2];
+    const size_t wstep = a.tiled ? 8192 : 64;       // elements from one slab to the next
+    const int whalf = a.tiled ? 512 : 32;           // ... from the first 32 elements of a slab to the second
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
         const int r = row_base + mt * 16 + i;
         wok[mt] = r < a.N;
         const int rr = wok[mt] ? r : 0;
-        wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 8;
+        if (a.tiled) {
+            const int tile = blockIdx.x, tsplit = a.split_row >> 7;
+            const uint16_t *t = tile < tsplit ? a.W + (size_t)tile * 128 * K : a.W2 + (size_t)(tile - tsplit) * 128 * K;
+            wp[mt] = t + ((w * 2 + mt) * 2 * 64 + lane) * 8;
+        } else {
+            wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 8;
+        }
     }
     struct WFrag { uint4 a0[2], a1[2]; };
     auto load_w = [&](int s, WFrag &f) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
-            f.a0[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64) : zero16();
-            f.a1[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * 64 + 32) : zero16();
+            f.a0[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * wstep) : zero16();
+            f.a1[mt] = wok[mt] ? ld16(wp[mt] + (size_t)s * wstep + whalf) : zero16();
         }
     };
     auto load_w_all = [&](int s, WFrag &f) {   // unpredicated: a row past N reads row 0 (wp) and is never stored
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt) {
-            f.a0[mt] = ld16(wp[mt] + (size_t)s * 64);
-            f.a1[mt] = ld16(wp[mt] + (size_t)s * 64 + 32);
+            f.a0[mt] = ld16(wp[mt] + (size_t)s * wstep);
+            f.a1[mt] = ld16(wp[mt] + (size_t)s * wstep + whalf);
         }
     };
     // activation slab: NB*256 16-byte units, unit u = ((tile*2 + plane)*16 + row)*8 + segment
@@ -272,6 +283,7 @@ struct GemmI8Args {
     int batch, N, K, n_slabs, slabs_per_block;
     const float *ssq;              // see GemmSkArgs
     float eps;
+    int tiled;                     // see GemmSkArgs; the unit of (row tile, slab) is 8 KiB: [wave][row group][lane][16 codes]
 };
 
 template <int NB>
@@ -290,19 +302,26 @@ __global__ __launch_bounds__(256) void k_gemm_sk_i8(GemmI8Args a)
 
     const int8_t *wp[2];
     bool wok[2];
+    const size_t wstep = a.tiled ? 8192 : 64;       // bytes from one slab to the next
 #pragma unroll
     for (int mt = 0; mt < 2; ++mt) {
         const int r = row_base + mt * 16 + i;
         wok[mt] = r < a.N;
         const int rr = wok[mt] ? r : 0;
-        wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 16;
+        if (a.tiled) {
+            const int tile = blockIdx.x, tsplit = a.split_row >> 7;
+            const int8_t *t = tile < tsplit ? a.W + (size_t)tile * 128 * K : a.W2 + (size_t)(tile - tsplit) * 128 * K;
+            wp[mt] = t + ((w * 2 + mt) * 64 + lane) * 16;
+        } else {
+            wp[mt] = (rr < a.split_row ? a.W + (size_t)rr * K : a.W2 + (size_t)(rr - a.split_row) * K) + g * 16;
+        }
     }
     // Lane (i, g) owns bytes g*16 .. g*16+15 of row i of every 64-element slab: the A operand of one MFMA.
     struct WFrag { uint4 c[2]; };
     auto load_w = [&](int s, WFrag &f) {
 #pragma unroll
         for (int mt = 0; mt < 2; ++mt)
-            f.c[mt] = wok[mt] ? *reinterpret_cast<const uint4 *>(wp[mt] + (size_t)s * 64) : zero16();
+            f.c[mt] = wok[mt] ? *reinterpret_cast<const uint4 *>(wp[mt] + (size_t)s * wstep) : zero16();
     };
     // activation slab: NB*128 16-byte units, unit u = ((tile*2 + digit)*16 + row)*4 + segment
     constexpr int NU = (NB + 1) / 2;
@@ -466,6 +485,7 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
         q.scale = W.scale; q.scale2 = W2.w ? W2.scale : W.scale; q.split_row = W2.w ? split_row : N;
         q.xd = reinterpret_cast<const uint8_t *>(xb); q.x_plane = (size_t)nb * 16 * K;
         q.part = part; q.batch = batch; q.N = N; q.K = K; q.n_slabs = K / 64; q.ssq = ssq; q.eps = eps;
+        q.tiled = W.tiled ? 1 : 0;
         const int splits = gemm_sk_splits(batch, N, K, true);
         q.slabs_per_block = (q.n_slabs + splits - 1) / splits;
         const dim3 grid((N + 127) / 128, splits);
@@ -483,6 +503,7 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
     a.W = static_cast<const uint16_t *>(W.w); a.W2 = static_cast<const uint16_t *>(W2.w ? W2.w : W.w);
     a.split_row = W2.w ? split_row : N; a.xb = xb; a.x_plane = (size_t)nb * 16 * K;
     a.part = part; a.batch = batch; a.N = N; a.K = K; a.n_slabs = K / 64;
+    a.tiled = W.tiled ? 1 : 0;
     const int splits = gemm_sk_splits(batch, N, K, false);
     a.slabs_per_block = (a.n_slabs + splits - 1) / splits;
     const dim3 grid((N + 127) / 128, splits);
@@ -553,6 +574,40 @@ hipError_t launch_sk_reduce(const float *part, int splits, int batch, int N, boo
         PSV_LAUNCH(k_sk_reduce<true>, dim3(blocks), dim3(256), 0, s, part, splits, batch, N, out, out_bf16, out_plane, digits ? 1 : 0);
     else
         PSV_LAUNCH(k_sk_reduce<false>, dim3(blocks), dim3(256), 0, s, part, splits, batch, N, out, out_bf16, out_plane, digits ? 1 : 0);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------ tiled weight layout
+
+// One thread per 16-byte piece of the destination: row-major [rows][cols] -> [row tile][slab][unit] (see GemmSkArgs /
+// GemmI8Args for the order inside a unit).
+template <int EB>
+__global__ __launch_bounds__(256) void k_tile_weights(const char *__restrict__ src, char *__restrict__ dst, int rows, int cols)
+{
+    const size_t n_slabs = cols / 64, unit16 = EB == 2 ? 1024 : 512;       // 16-byte pieces per unit
+    const size_t total = (size_t)(rows / 128) * n_slabs * unit16;
+    for (size_t u = (size_t)blockIdx.x * 256 + threadIdx.x; u < total; u += (size_t)gridDim.x * 256) {
+        const size_t unit = u / unit16, tile = unit / n_slabs, slab = unit % n_slabs;
+        const int in = (int)(u % unit16);
+        int w, mt, half, lane;
+        if (EB == 2) { w = in >> 8; mt = (in >> 7) & 1; half = (in >> 6) & 1; lane = in & 63; }
+        else { w = in >> 7; mt = (in >> 6) & 1; half = 0; lane = in & 63; }
+        const size_t row = tile * 128 + w * 32 + mt * 16 + (lane & 15);
+        const size_t col = slab * 64 + (EB == 2 ? half * 32 + (lane >> 4) * 8 : (lane >> 4) * 16);
+        *reinterpret_cast<uint4 *>(dst + u * 16) = *reinterpret_cast<const uint4 *>(src + (row * cols + col) * EB);
+    }
+}
+
+hipError_t launch_tile_weights(void *dst, const void *src, int rows, int cols, int elem_bytes, hipStream_t s)
+{
+    const size_t total = (size_t)rows * cols * elem_bytes / 16;
+    unsigned blocks = (unsigned)((total + 255) / 256);
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    if (elem_bytes == 2)
+        hipLaunchKernelGGL(k_tile_weights<2>, dim3(blocks), dim3(256), 0, s, static_cast<const char *>(src), static_cast<char *>(dst), rows, cols);
+    else
+        hipLaunchKernelGGL(k_tile_weights<1>, dim3(blocks), dim3(256), 0, s, static_cast<const char *>(src), static_cast<char *>(dst), rows, cols);
     return hipGetLastError();
 }
 

@@ -50,6 +50,7 @@ struct KvView {
 struct Mat {
     const void *w = nullptr;
     const float *scale = nullptr;
+    bool tiled = false;          // PSV_W_TILED storage (matrix-core projections only)
 };
 
 // ---- kernel launchers ---------------------------------------------------------------------
@@ -204,6 +205,8 @@ hipError_t launch_prefetch_job(const PrefetchJob &j, uint32_t workgroups, hipStr
 hipError_t launch_prefetch(const void *ptr, uint64_t bytes, uint32_t workgroups, hipStream_t s);
 
 hipError_t launch_copy(void *dst, const void *src, uint64_t bytes, hipStream_t s);
+// row-major [rows][cols] -> the tiled layout of PSV_W_TILED; elem_bytes = 2 (bf16) or 1 (int8 codes)
+hipError_t launch_tile_weights(void *dst, const void *src, int rows, int cols, int elem_bytes, hipStream_t s);
 
 // ---- planner (pure host) ---------------------------------------------------------------------
 uint64_t op_mem_size(const psv_model_desc &d, uint32_t op, uint32_t batch, uint32_t context);

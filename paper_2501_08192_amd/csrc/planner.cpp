@@ -18,6 +18,7 @@ static bool desc_ok(const psv_model_desc &d)
     if (d.max_seq == 0 || d.max_seq % PSV_BLOCK_TOKENS != 0 || d.max_seq > (1u << 20)) return false;
     if (d.weight_format > PSV_FMT_INT8 || d.kv_format > PSV_FMT_INT8) return false;
     if (d.kv_layout > PSV_KV_TOKEN_MAJOR || (d.kv_layout == PSV_KV_TOKEN_MAJOR && d.kv_format != PSV_FMT_BF16)) return false;
+    if (d.weight_layout > PSV_W_TILED) return false;
     return true;
 }
 

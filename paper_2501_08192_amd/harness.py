@@ -35,7 +35,8 @@ class Session:
         self.max_seq = (w.context + 15) // 16 * 16 if max_seq is None else int(max_seq)
         self.desc = psv.model_desc(w.n_layers, w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch, self.max_seq,
                                    head_dim=w.head_dim, rms_eps=w.rms_eps, rope_theta=w.rope_theta,
-                                   weight_format=w.weight_format, kv_format=w.kv_format, kv_layout=w.kv_layout)
+                                   weight_format=w.weight_format, kv_format=w.kv_format, kv_layout=w.kv_layout,
+                                   weight_layout=w.weight_layout)
         # HIP maps streams onto a few hardware queues; take a side stream that really runs beside the main one
         self.main = torch.cuda.Stream(device=self.device)
         self.overlap = False
@@ -56,6 +57,14 @@ class Session:
         self.weights, self.k_pools, self.v_pools = {}, {}, {}
         for l in self.layers:
             self.weights[l] = synth.layer_weights(w, l, seed, self.device)
+            if w.weight_layout == "tiled":      # the library gets the tiled copy; the row-major original is dropped
+                cur = torch.cuda.current_stream(self.device)     # the stream the generators ran on
+                for n in ("w_qkv", "w_o", "w_gate", "w_up", "w_down"):
+                    src = self.weights[l][n]
+                    dst = torch.empty_like(src)
+                    psv.psv_tile_weights(dst, src, src.shape[0], src.shape[1], w.weight_format, cur)
+                    self.weights[l][n] = dst
+                cur.synchronize()
             self.k_pools[l], self.v_pools[l] = synth.kv_pools(w, l, seed, self.device, n_blocks=self.pool_blocks)
             psv.psv_set_layer_weights(self.ctx, l, self.weights[l])
         self.page_table_host = synth.page_table(w, seed, n_blocks=self.pool_blocks) if w.paged else None
@@ -114,7 +123,9 @@ class Session:
 
     # ---- host copies for the oracle (tests / cpu baseline only) ----
     def host_layer(self, l):
-        return {n: synth.bits(t) for n, t in self.weights[l].items()}
+        """Row-major host copy of a layer's weights (what the oracle reads), whatever layout the library was given."""
+        src = synth.layer_weights(self.w, l, self.seed, self.device) if self.w.weight_layout == "tiled" else self.weights[l]
+        return {n: synth.bits(t) for n, t in src.items()}
 
     def host_pools(self, l):
         return synth.bits(self.k_pools[l]), synth.bits(self.v_pools[l])

@@ -84,6 +84,19 @@ def test_null_and_range_arguments_are_rejected_without_a_gpu():
     assert L.psv_prefetch_region(None, 64, 1, None) == psv.PSV_ERR_INVALID_ARG
     assert L.psv_spin(-1.0, None) == psv.PSV_ERR_INVALID_ARG
     assert L.psv_copy_bytes(None, None, 16, None) == psv.PSV_ERR_INVALID_ARG
+    # tiled weight layout: null, unaligned, overlapping or mis-sized arguments never reach the GPU
+    assert L.psv_tile_weights(None, 4096, 128, 64, 0, None) == psv.PSV_ERR_INVALID_ARG
+    assert L.psv_tile_weights(1 << 20, 1 << 20, 128, 64, 0, None) == psv.PSV_ERR_INVALID_ARG           # dst == src
+    assert L.psv_tile_weights(1 << 20, (1 << 20) + 4096, 128, 64, 0, None) == psv.PSV_ERR_INVALID_ARG  # overlap (16 KiB matrix)
+    assert L.psv_tile_weights(1 << 20, 1 << 24, 100, 64, 0, None) == psv.PSV_ERR_INVALID_ARG           # rows % 128
+    assert L.psv_tile_weights(1 << 20, 1 << 24, 128, 48, 0, None) == psv.PSV_ERR_INVALID_ARG           # cols % 64
+    assert L.psv_tile_weights((1 << 20) + 8, 1 << 24, 128, 64, 0, None) == psv.PSV_ERR_INVALID_ARG     # alignment
+    assert L.psv_tile_weights(1 << 20, 1 << 24, 128, 64, 7, None) == psv.PSV_ERR_INVALID_ARG           # format
+    w2 = synth.WORKLOADS["c1"]
+    assert psv.psv_validate_desc(_desc(w2, weight_layout="tiled")) == psv.PSV_OK
+    bad_layout = _desc(w2)
+    bad_layout.weight_layout = 2
+    assert psv.psv_validate_desc(bad_layout) == psv.PSV_ERR_INVALID_ARG
 
 
 def test_create_fails_cleanly_without_a_gpu():
@@ -215,7 +228,7 @@ def test_storage_formats_in_the_descriptor_and_the_planner():
 
 def test_binding_structs_match_the_header_layout():
     # field order and sizes restated from include/preserve.h
-    assert C.sizeof(psv.psv_model_desc) == 13 * 4
+    assert C.sizeof(psv.psv_model_desc) == 14 * 4
     assert C.sizeof(psv.psv_layer_weights) == 12 * C.sizeof(C.c_void_p)
     assert C.sizeof(psv.psv_prefetch_policy) == 40
     assert C.sizeof(psv.psv_plan_entry) == 32
