@@ -1,6 +1,6 @@
 """GPU parity on seeded random shapes: hidden and FFN widths, head groupings, batches on both projection paths,
-ragged and mixed context lengths, contiguous and paged caches, every storage format and a mix of prefetch
-policies -- each case run through the C ABI and compared with the CPU oracle exactly as the hand-picked cases
+ragged and mixed context lengths, contiguous and paged caches, every storage format, both weight layouts and a mix of
+prefetch policies -- each case run through the C ABI and compared with the CPU oracle exactly as the hand-picked cases
 of test_gpu_parity / test_gpu_int8 are (same tolerance, same checks of the appended cache rows)."""
 import random
 
@@ -30,17 +30,22 @@ def draw(case):
     lens = [rng.randint(1, context) for _ in range(batch)] if (batch > 1 and rng.random() < 0.4) else None
     policy = rng.choice(["off", "default", "default", "cache only", "small partial"])
     slack = rng.choice([0, 5]) if paged else 0
-    return hidden, nkv * group, nkv, ffn, batch, context, layers, paged, fmt, win, lens, policy, slack
+    # drawn last: the other choices of a case do not depend on it; mostly on the batches whose projections are on the
+    # matrix cores anyway, so that the vector-ALU path keeps its share of the cases
+    tiled = rng.random() < 0.4 and (batch >= 3 or rng.random() < 0.3)
+    return hidden, nkv * group, nkv, ffn, batch, context, layers, paged, fmt, win, lens, policy, slack, tiled
 
 
 @pytest.mark.parametrize("case", range(32))
 def test_random_shape(case):
-    hidden, nq, nkv, ffn, batch, context, layers, paged, fmt, win, lens, policy, slack = draw(case)
+    hidden, nq, nkv, ffn, batch, context, layers, paged, fmt, win, lens, policy, slack, tiled = draw(case)
     name = "rnd%d" % case
     if fmt is None:
         mod, w = bf, bf.W(name, layers, hidden, nq, nkv, ffn, batch, context, paged=paged, win=win)
     else:
         mod, w = q8, q8.W(name, layers, hidden, nq, nkv, ffn, batch, context, fmt, paged=paged, win=win)
+    if tiled:                            # projection matrices in the tiled order (matrix-core projections at every batch)
+        w = w.scaled(weight_layout="tiled")
     pol = {"off": None,
            "default": default_policy(w, budget_bytes=1 << 40),
            "cache only": default_policy(w, budget_bytes=1 << 40, prelaunch=0),
