@@ -36,7 +36,11 @@ psv_status psv_set_graph_mode(psv_ctx *ctx, uint32_t use_graph);
  * Shapes it does not take run as under 1.  Per-operator profiling sees one kernel (reported as the QKV operator).
  * 3 (default) = the library chooses by shape between 0 and 1: 1 where rows have at least 4096 elements and all
  * weights of a block fit the registers of one pass (an 8B-shaped TP=8 shard does), 0 elsewhere.
- * psv_decode_step_static always runs as under 0. */
+ * psv_decode_step_static always runs as under 0.
+ * Kernels of settings 1 and 2 need every one of their workgroups resident at once (one per compute unit): while such a
+ * step runs, nothing else that holds compute units for long may run on the device -- in particular not a step of
+ * another context -- or their hand-overs run out of patience and psv_sync reports PSV_ERR_HIP.  The library's own
+ * window and prefetch kernels are short or single-workgroup and are accounted for. */
 psv_status psv_set_fused_kernels(psv_ctx *ctx, uint32_t on);
 
 /* ---- streams and tuning -------------------------------------------------------------------- */
