@@ -100,3 +100,35 @@ def test_fused_falls_back_where_the_shape_does_not_fit():
                 assert torch.equal(xa, xb)
             else:
                 assert torch.allclose(xa, xb, rtol=1e-4, atol=1e-4)
+
+
+@pytest.mark.parametrize("mode", [1, 2], ids=["per_block", "whole_step"])
+@pytest.mark.parametrize("win", [(0.0, 6.0), (12.0, 0.0), (0.0, 0.0)], ids=["only_after_mlp", "only_after_attention", "none"])
+def test_fused_with_a_missing_window(win, mode):
+    """A window of 0 us does not exist: nothing is launched (or timed) for it and whatever follows it requests its weights
+    at once; results and policy-independence as with both windows."""
+    w = bf.W("c2_like", 3, 4096, 4, 1, 1792, 1, 300, win=win)
+    run_fused(w, 64, [default_policy(w, budget_bytes=1 << 40), default_policy(w, budget_bytes=1 << 40, prelaunch=0)], mode=mode)
+
+
+@pytest.mark.parametrize("mode", [1, 2], ids=["per_block", "whole_step"])
+def test_fused_layer_ranges_compose(mode):
+    """Running layers [0, 2) and then [2, 3) on the first run's output equals one run over [0, 3), bit for bit: every
+    kernel of the fused paths takes its layer's weights and cache by the layer's own index."""
+    w = bf.W("c2_like", 3, 4096, 4, 1, 1792, 1, 300, win=(5.0, 5.0))
+    with Session(w, seed=65, fused=mode) as s:
+        s.set_policy(default_policy(w, budget_bytes=1 << 40))
+        pools0 = [s.k_pools[l].clone() for l in s.layers] + [s.v_pools[l].clone() for l in s.layers]
+        whole = s.run().clone()
+        pools1 = [s.k_pools[l].clone() for l in s.layers] + [s.v_pools[l].clone() for l in s.layers]
+        for t, src in zip([s.k_pools[l] for l in s.layers] + [s.v_pools[l] for l in s.layers], pools0):
+            t.copy_(src)                                   # the cache as it was before the step
+        mid = torch.empty_like(s.x_in)
+        s.step(x_out=mid, layer_begin=0, layer_end=2)
+        s.sync()
+        out = torch.empty_like(s.x_in)
+        s.step(x_in=mid, x_out=out, layer_begin=2, layer_end=3)
+        s.sync()
+        assert torch.equal(out, whole)
+        for a, b in zip(pools1, [s.k_pools[l] for l in s.layers] + [s.v_pools[l] for l in s.layers]):
+            assert torch.equal(a, b)
