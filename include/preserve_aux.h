@@ -96,9 +96,11 @@ psv_status psv_copy_bytes(void *dst, const void *src, uint64_t bytes, void *stre
  * on `stream`. */
 psv_status psv_tile_weights(void *dst, const void *src, uint32_t rows, uint32_t cols, uint32_t weight_format, void *stream);
 
-/* Test aid for the prelaunch policy: while on, a kernel launched ahead of its window's end gives up its
- * (always bounded) wait at once.  The kernel then still completes, sets an error word, and the next psv_sync
- * returns PSV_ERR_TIMEOUT once; the context stays usable. */
+/* Test aid for the bounded waits: while on, a kernel launched ahead of its window's end gives up its (always bounded)
+ * wait at once -- it still completes with the right result, sets an error word, and the next psv_sync returns
+ * PSV_ERR_TIMEOUT once -- and every hand-over inside a fused kernel (psv_set_fused_kernels) expires at once: those
+ * kernels run to their end on whatever their buffers held, the step's output and the cache rows it appends are
+ * invalid, and the next psv_sync returns PSV_ERR_HIP once.  The context stays usable either way. */
 psv_status psv_debug_force_wait_timeout(psv_ctx *ctx, uint32_t on);
 
 /* Which kernels the most recent psv_decode_step ran: 0 = one per operator, 1 = at least one block as a fused kernel,

@@ -367,6 +367,7 @@ static psv_status enqueue_whole_step(psv_ctx *c, const float *x_in, float *x_out
     p.kv = kv;
     p.qkv_ll = c->at<void>(c->ws.qkv_ll); p.pml_ll = c->at<void>(c->ws.pml_ll); p.po_ll = c->at<void>(c->ws.po_ll);
     p.m_ll = c->at<void>(c->ws.m_ll); p.ll_base = c->at<void>(c->ws.step_ll);
+    p.poll_iters = c->force_wait_timeout ? 0u : kSegPollIters / 4;
     p.tag_base = next_tags(8u * (le - lb + 1));
     p.err = c->at<unsigned>(c->ws.flag) + 48;
     for (int w = 0; w < 2; ++w) {
@@ -447,6 +448,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
                     ? 1 : 0;
     }
     const int blocks = fused ? c->cus : 0;
+    const uint32_t poll_iters = c->force_wait_timeout ? 0u : kSegPollIters;     // hand-overs inside the fused kernels
     c->last_step_whole = false;
     if (fused == 2 && vec && blocks >= 64 &&
         step_supported(B, H, F, nq, nkv, d.max_seq, d.kv_format == PSV_FMT_INT8 || d.kv_layout != PSV_KV_HEAD_MAJOR, w8, blocks))
@@ -493,7 +495,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_seg_attn(Wqkv, Wo, res, delta, u16(w.g_attn), d.rms_eps, x, h1, c->at<void>(c->ws.qkv_ll), rope, kv, nq, nkv,
                                     seg_nc, c->at<void>(c->ws.pml_ll), c->at<void>(c->ws.po_ll), attn, delta_a, H, next_tag(), errw,
                                     wait_qkv ? &wait : nullptr, from_window && plan_has_whole(c, l - 1, 1, l, PSV_OP_ATTN),
-                                    from_window && plan_has_whole(c, l - 1, 1, l, PSV_OP_O), blocks, s));
+                                    from_window && plan_has_whole(c, l - 1, 1, l, PSV_OP_O), poll_iters, blocks, s));
             wait_qkv = false;
         } else if (vec) {
             HIP_TRY(launch_gemv_norm(Wqkv, Mat{}, res, delta, u16(w.g_attn), d.rms_eps, x, h1, qkv, B, QR, H,
@@ -545,7 +547,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         if (seg_mlp) {
             // gate/up + SwiGLU + down in one launch (profiled as the gate/up operator; down has no kernel of its own)
             HIP_TRY(launch_seg_mlp(Wg, Wu, Wd, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, c->at<void>(c->ws.m_ll), delta_m, B, H, F,
-                                   next_tag(), errw, wait_gate ? &wait : nullptr, plan_has_whole(c, l, 0, l, PSV_OP_DOWN), blocks, s));
+                                   next_tag(), errw, wait_gate ? &wait : nullptr, plan_has_whole(c, l, 0, l, PSV_OP_DOWN), poll_iters, blocks, s));
             wait_gate = false;
         } else if (vec) {
             HIP_TRY(launch_gemv_norm(Wg, Wu, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, m, B, F, H,

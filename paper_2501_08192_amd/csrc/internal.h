@@ -88,10 +88,12 @@ hipError_t launch_gemv_merge(Mat W, const float *part_ml, const float *part_o, i
 // of `blocks` workgroups (one per CU, all resident).  Phases hand their results over through buffers of tagged values
 // ({value, tag} pairs, 8 bytes each); `tag` must be unique per launch (next_tag).  *err: bit 0 = the wait for the
 // window's end expired (wait != null), bit 1 = a hand-over poll expired (results invalid).
+constexpr uint32_t kSegPollIters = 1u << 16;
 unsigned next_tag();
 // MLP block: y = res + delta; h = rmsnorm(y) * gain; m = silu(Wg h) * (Wu h); out = Wd m.  m_ll: [batch][F] pairs.
 // wait != null: launched into the window ahead of its inputs, see GemvWait; hold_down = false makes that variant
 // request the down weights only after the window's end (the plan did not hand them to this window).
+// poll_iters: bound of every hand-over poll (kSegPollIters; 0 makes every hand-over expire at once -- a test aid).
 bool seg_mlp_supported(int batch, int H, int F);
 // do the first passes of the gate/up and of the down projection (what the kernel requests at its start) cover all of
 // W_gate and W_up / all of W_down?
@@ -99,7 +101,7 @@ bool seg_mlp_holds_gate_up(int H, int F, bool w8, int blocks);
 bool seg_mlp_holds_down(int H, int F, bool w8, int blocks);
 hipError_t launch_seg_mlp(Mat Wg, Mat Wu, Mat Wd, const float *res, const float *delta, const uint16_t *gain, float eps,
                           float *out_res, float *out_h, void *m_ll, float *out, int batch, int H, int F, unsigned tag,
-                          unsigned *err, const GemvWait *wait, bool hold_down, int blocks, hipStream_t s);
+                          unsigned *err, const GemvWait *wait, bool hold_down, uint32_t poll_iters, int blocks, hipStream_t s);
 
 // Attention block of one sequence: x = res + delta; h = rmsnorm(x) * gain; qkv = Wq h; rotary embedding, KV append and
 // decode attention over 256-token chunks (workgroup kvh * n_chunks + c runs chunk c of kv head kvh); out = Wo attn.
@@ -112,7 +114,7 @@ bool seg_attn_holds_qkv(int H, int QR, bool w8, int blocks);    // ... of the QK
 hipError_t launch_seg_attn(Mat Wq, Mat Wo, const float *res, const float *delta, const uint16_t *gain, float eps,
                            float *out_res, float *out_h, void *qkv_ll, const float2 *rope, KvView kv, int nq, int nkv,
                            int n_chunks, void *pml_ll, void *po_ll, float *out_attn, float *out, int H, unsigned tag,
-                           unsigned *err, const GemvWait *wait, bool hold_kv, bool hold_o, int blocks, hipStream_t s);
+                           unsigned *err, const GemvWait *wait, bool hold_kv, bool hold_o, uint32_t poll_iters, int blocks, hipStream_t s);
 
 // ---- the whole step of one sequence as one kernel (step.hip): `blocks` resident workgroups walk layers [lb, le); the
 // residual stream stays in registers, every hand-over is a buffer of tagged values, and the communication windows
@@ -142,6 +144,7 @@ struct StepLaunch {
     unsigned *err;
     uint64_t ticks[2];
     uint32_t spin_iters[2];
+    uint32_t poll_iters;      // bound of every hand-over poll (kSegPollIters / 4; 0: a test aid, see launch_seg_mlp)
     int hold[2];
     float *dbg_x, *dbg_h1, *dbg_attn, *dbg_y, *dbg_h2;   // intermediates of the last layer (optional)
 };

@@ -497,12 +497,12 @@ static hipError_t seg_mlp_pick(const SegMlpArgs &a, bool wait, int blocks, hipSt
 
 hipError_t launch_seg_mlp(Mat Wg, Mat Wu, Mat Wd, const float *res, const float *delta, const uint16_t *gain, float eps,
                           float *out_res, float *out_h, void *m_ll, float *out, int batch, int H, int F, unsigned tag,
-                          unsigned *err, const GemvWait *wait, bool hold_down, int blocks, hipStream_t s)
+                          unsigned *err, const GemvWait *wait, bool hold_down, uint32_t poll_iters, int blocks, hipStream_t s)
 {
     SegMlpArgs a{};
     a.Wg = Wg.w; a.Wu = Wu.w; a.Wd = Wd.w; a.sg = Wg.scale; a.su = Wu.scale; a.sd = Wd.scale;
     a.res = res; a.delta = delta; a.gain = gain; a.eps = eps; a.out_res = out_res; a.out_h = out_h;
-    a.m_ll = static_cast<uint2 *>(m_ll); a.out = out; a.F = F; a.H = H; a.tag = tag; a.ll_iters = 1u << 16; a.err = err;
+    a.m_ll = static_cast<uint2 *>(m_ll); a.out = out; a.F = F; a.H = H; a.tag = tag; a.ll_iters = poll_iters; a.err = err;
     if (wait) a.wait = SegWait{wait->done, wait->seq, wait->iters, wait->ticks};
     a.hold_down = hold_down ? 1 : 0;
     if (batch != 1) return hipErrorInvalidValue;
@@ -1189,14 +1189,14 @@ static hipError_t seg_attn_pick(const SegAttnArgs &a, bool wait, int blocks, hip
 hipError_t launch_seg_attn(Mat Wq, Mat Wo, const float *res, const float *delta, const uint16_t *gain, float eps,
                            float *out_res, float *out_h, void *qkv_ll, const float2 *rope, KvView kv, int nq, int nkv,
                            int n_chunks, void *pml_ll, void *po_ll, float *out_attn, float *out, int H, unsigned tag,
-                           unsigned *err, const GemvWait *wait, bool hold_kv, bool hold_o, int blocks, hipStream_t s)
+                           unsigned *err, const GemvWait *wait, bool hold_kv, bool hold_o, uint32_t poll_iters, int blocks, hipStream_t s)
 {
     SegAttnArgs a{};
     a.Wq = Wq.w; a.Wo = Wo.w; a.sq = Wq.scale; a.so = Wo.scale;
     a.res = res; a.delta = delta; a.gain = gain; a.eps = eps; a.out_res = out_res; a.out_h = out_h;
     a.qkv_ll = static_cast<uint2 *>(qkv_ll); a.rope = rope; a.kv = kv; a.nq = nq; a.nkv = nkv; a.n_chunks = n_chunks;
     a.pml_ll = static_cast<uint2 *>(pml_ll); a.po_ll = static_cast<uint2 *>(po_ll); a.out_attn = out_attn; a.out = out;
-    a.H = H; a.QR = (nq + 2 * nkv) * 128; a.QD = nq * 128; a.tag = tag; a.ll_iters = 1u << 16; a.err = err;
+    a.H = H; a.QR = (nq + 2 * nkv) * 128; a.QD = nq * 128; a.tag = tag; a.ll_iters = poll_iters; a.err = err;
     if (wait) a.wait = SegWait{wait->done, wait->seq, wait->iters, wait->ticks};
     a.hold_kv = hold_kv ? 1 : 0;
     a.hold_o = hold_o ? 1 : 0;

@@ -966,7 +966,7 @@ hipError_t launch_step(const StepLaunch &p, int blocks, hipStream_t s)
     a.qkv_ll = static_cast<uint2 *>(p.qkv_ll); a.pml_ll = static_cast<uint2 *>(p.pml_ll); a.po_ll = static_cast<uint2 *>(p.po_ll);
     a.m_ll = static_cast<uint2 *>(p.m_ll);
     a.da_ll = ll; a.dm_ll = ll + p.H; a.done_ll = ll + 2 * (size_t)p.H;
-    a.tag_base = p.tag_base; a.ll_iters = 1u << 14; a.err = p.err;
+    a.tag_base = p.tag_base; a.ll_iters = p.poll_iters; a.err = p.err;
     a.ticks[0] = p.ticks[0]; a.ticks[1] = p.ticks[1]; a.spin_iters[0] = p.spin_iters[0]; a.spin_iters[1] = p.spin_iters[1];
     a.hold[0] = p.hold[0]; a.hold[1] = p.hold[1];
     a.dbg_x = p.dbg_x; a.dbg_h1 = p.dbg_h1; a.dbg_attn = p.dbg_attn; a.dbg_y = p.dbg_y; a.dbg_h2 = p.dbg_h2;

@@ -132,3 +132,21 @@ def test_fused_layer_ranges_compose(mode):
         assert torch.equal(out, whole)
         for a, b in zip(pools1, [s.k_pools[l] for l in s.layers] + [s.v_pools[l] for l in s.layers]):
             assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("mode", [1, 2], ids=["per_block", "whole_step"])
+def test_fused_hand_over_that_expires_is_reported_and_the_context_survives(mode):
+    """With every hand-over poll forced to expire at once the fused kernels still run to their end (no hang, no fault), the
+    next sync reports the step as failed, once, and the context computes the right result again afterwards."""
+    w = bf.W("c2_like", 2, 4096, 4, 1, 1792, 1, 300, win=(5.0, 5.0))
+    with Session(w, seed=66, fused=mode) as s:
+        s.set_policy(default_policy(w, budget_bytes=1 << 40))
+        good = s.run().clone()
+        psv.psv_debug_force_wait_timeout(s.ctx, True)
+        s.step()
+        with pytest.raises(psv.PsvError) as e:
+            s.sync()
+        assert e.value.status == psv.PSV_ERR_HIP
+        psv.psv_debug_force_wait_timeout(s.ctx, False)
+        assert torch.equal(s.run(), good)                 # the failed step's cache rows are rewritten by this one
+        s.sync()
