@@ -47,22 +47,23 @@ def timed(sess, n_layers, steps=20, warmup=5, reps=3):
     return sorted(ts)[len(ts) // 2]
 
 
-def speed_map(shape, batches, contexts, layers=3, window=20.0, out=print, kv_layout="head"):
+def speed_map(shape, batches, contexts, layers=3, window=20.0, out=print, kv_layout="head", weight_layout="row"):
     """off / on us per layer and speedup for every (batch, context), beside the analytic model's prediction.
     The budget is the one the model picks; the rest of the policy is bench.py's default."""
     hidden, nq, nkv, ffn = SHAPES[shape]
     mach = model.Machine.load()
-    out("shape %s: hidden %d, %d q / %d kv heads, ffn %d, windows %g us, %d layers materialised, %s-major KV"
-        % (shape, hidden, nq, nkv, ffn, window, layers, kv_layout))
+    out("shape %s: hidden %d, %d q / %d kv heads, ffn %d, windows %g us, %d layers materialised, %s-major KV, %s weights"
+        % (shape, hidden, nq, nkv, ffn, window, layers, kv_layout, "tiled" if weight_layout == "tiled" else "row-major"))
     out("%5s %7s | %9s %9s %8s | %9s %9s %8s | budget" % ("batch", "context", "off", "on", "speedup", "m.off", "m.on", "m.spd"))
     rows = []
     for B in batches:
         for T in contexts:
-            w = synth.Workload("map", 80, hidden, nq, nkv, 128, ffn, B, T, False, (window, window), kv_layout=kv_layout)
+            w = synth.Workload("map", 80, hidden, nq, nkv, 128, ffn, B, T, False, (window, window), kv_layout=kv_layout,
+                               weight_layout=weight_layout)
             if w.kv_bytes_per_layer * layers > 60e9:
                 continue
             b = model.op_bytes(hidden, nq, nkv, ffn, B, T)
-            path = model.path_of(B, hidden)
+            path = model.path_of(B, hidden) if weight_layout == "row" else "mm"     # tiled weights: matrix cores at every batch
             budget = model.best_budget(b, (window, window), mach, path=path)
             with Session(w, layers=list(range(layers))) as s:
                 s.set_policy(psv.prefetch_policy(mode=0))
@@ -285,6 +286,8 @@ def main(argv=None):
     m.add_argument("--kv-layout", default="head", choices=["head", "token"],
                    help="token: both pools [block, token, kv head, channel] -- one head's reads are strided when the shard has "
                         "several local kv heads")
+    m.add_argument("--weight-layout", default="row", choices=["row", "tiled"],
+                   help="tiled: projection matrices in the order of the matrix-core projections (which then run at every batch)")
     sw = sub.add_parser("sweep")
     sw.add_argument("workload", choices=sorted(synth.WORKLOADS))
     sw.add_argument("--layers", type=int, default=4)
@@ -306,7 +309,7 @@ def main(argv=None):
         record(a.out, out=out)
     elif a.cmd == "map":
         speed_map(a.shape, [int(x) for x in a.batches.split(",")], [int(x) for x in a.contexts.split(",")],
-                  a.layers, a.window, out, kv_layout=a.kv_layout)
+                  a.layers, a.window, out, kv_layout=a.kv_layout, weight_layout=a.weight_layout)
     else:
         policy_sweeps(a.workload, a.layers, a.steps, tuple(a.which.split(",")), out)
 
