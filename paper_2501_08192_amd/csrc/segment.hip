@@ -20,12 +20,14 @@
 //    it costs 3-3.5 us: a device-coherent round trip is ~1.1 us there, the slowest producer's store takes about as
 //    long to become visible, and a reader that just missed it needs a second round trip.
 //
-// Measured (8B-shaped shard, batch 1, context 2048): these kernels are an option, not the default.  With the first
-// kernel after each window launched into the window they save 2.9 us per layer (attention block 15.5 -> 13.1 us,
-// MLP block 9.4 -> 8.4 us after the window); launched the ordinary way they are 1-1.5 us per layer slower than one
-// kernel per operator (18.2 vs 17.5 us, 15.2 vs 14.5 us): a hand-over costs as much as the kernel boundary it
-// replaces, and what the later phases gain from having their weights requested early, the first phase loses to
-// sharing the memory system with them.  On the small 2-layer shape (hidden 1024) they lose in both modes.
+// Measured (8B-shaped shard, batch 1, context 2048).  With the first kernel after each window launched into the window
+// they save 3.5 us per layer (12.7 us remain of the attention block after its window, 8.4 us of the MLP block, against
+// 3.2 + 6.7 + 5.7 and 4.4 + 5.1 us for one kernel per operator, of which only the first can be launched ahead); launched
+// the ordinary way they are about as fast as one kernel per operator (17.9 vs 17.6 us, 15.2 vs 14.3 us): a hand-over costs
+// as much as the kernel boundary it replaces, and what the later phases gain from having their weights requested early,
+// the first phase loses to sharing the memory system with them.  On shapes whose blocks need several passes, and on short
+// rows (hidden 1024-2048), they lose 3-9 us per layer; the executor uses them by default only where rows have at least
+// 4096 elements and every block's weights fit one pass.
 //
 // Tags are unique per launch (a process-wide counter), so a buffer never has to be cleared and stale contents of any
 // earlier launch can never be taken for data.  Every poll is bounded; a poll that expires sets bit 1 of the error
