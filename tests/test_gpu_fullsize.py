@@ -1,5 +1,6 @@
 """GPU parity at the full sizes of the five benchmark workloads, in the launch configuration bench.py times
-(eager launches, bench.py's default prefetch policy from harness.default_policy).  c1 and c2 are checked over the whole
+(eager launches, bench.py's default prefetch policy from harness.default_policy, the workloads' own kernel and weight-layout
+defaults, plus the alternatives).  c1 and c2 are checked over the whole
 step; c3-c5 hold 18-60 GB of weights and cache, so for them single layers are materialised at their real
 shape, run through the same entry point with a layer range, and compared output by output with the oracle.
 Tolerance: |gpu - ref| <= 2e-2 + 1e-2*|ref|; prefetch on/off must agree bit for bit."""
@@ -21,9 +22,9 @@ def bench_policy(w):
     return default_policy(w)
 
 
-def check_layers(w, layers, seed=2501):
+def check_layers(w, layers, seed=2501, fused=None):
     m = oracle.model(w.hidden, w.n_q_heads, w.n_kv_heads, w.head_dim, w.ffn, 16, w.rms_eps, w.rope_theta)
-    with Session(w, seed=seed, layers=layers) as s:
+    with Session(w, seed=seed, layers=layers, fused=fused) as s:
         lens = s.seq_lens_host.numpy()
         pt = s.page_table_host.numpy() if w.paged else None
         x = s.x_in.cpu().numpy().astype(np.float64)
@@ -88,3 +89,18 @@ def test_c5_one_layer_paged_context_32k():
     w = synth.WORKLOADS["c5"]
     check_layers(w, [0])
     check_layers(w, [w.n_layers - 1])
+
+
+def test_c2_whole_step_with_one_kernel_per_operator():
+    """c2's shape is one the library runs with per-segment kernels by default; the per-operator kernels stay reachable
+    (psv_set_fused_kernels 0, the second leg of bench.py) and are held to the same bar at full size."""
+    w = synth.WORKLOADS["c2"]
+    check_layers(w, list(range(w.n_layers)), fused=0)
+
+
+def test_c3_and_c5_on_row_major_weights():
+    """c3-c5 store their weights tiled by default; the same layers on row-major weights."""
+    w = synth.WORKLOADS["c3"].scaled(weight_layout="row")
+    check_layers(w, [0, 1])
+    w = synth.WORKLOADS["c5"].scaled(weight_layout="row")
+    check_layers(w, [0])
