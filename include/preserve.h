@@ -180,7 +180,8 @@ typedef struct {
     uint64_t kv_bytes_per_layer;       /* algorithmic bytes: K and V of the attended span once */
     uint64_t planned_prefetch_bytes;   /* sum of plan entry bytes over the whole step */
     uint64_t workspace_bytes;
-    uint32_t kernels_per_layer;        /* main-stream launches per layer */
+    uint32_t kernels_per_layer;        /* launches of the operator chain per layer, windows included: counted on the last
+                                          step, before the first one an estimate from the shape */
     uint32_t prefetch_launches;        /* side-stream launches per step */
     uint32_t steps;                    /* decode steps issued since creation */
     uint32_t reserved;

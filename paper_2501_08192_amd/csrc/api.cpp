@@ -221,7 +221,14 @@ psv_status psv_get_stats(psv_ctx *c, psv_stats *out)
     for (const psv_plan_entry &e : c->plan) out->planned_prefetch_bytes += e.bytes;
     out->workspace_bytes = c->ws.total;
     const bool vec = c->d.weight_layout == PSV_W_ROW_MAJOR && (batch == 1 || (batch == 2 && c->d.hidden <= 4096)) && c->d.hidden <= 8192 && c->d.ffn <= 8192;
-    out->kernels_per_layer = (vec ? 5 : 7) + (c->window_us[0] > 0.f ? 1 : 0) + (c->window_us[1] > 0.f ? 1 : 0);
+    // counted on the last step where there was one (its rotary-table and final-residual launches are once per step);
+    // before the first step: the per-operator kernels of the path the shape selects
+    if (c->last_step_whole)
+        out->kernels_per_layer = 1;          // one kernel for the whole step
+    else if (c->step_layers && c->step_launches > 2)
+        out->kernels_per_layer = (c->step_launches - 2 + c->step_layers - 1) / c->step_layers;
+    else
+        out->kernels_per_layer = (vec ? 5 : 10) + (c->window_us[0] > 0.f ? 1 : 0) + (c->window_us[1] > 0.f ? 1 : 0);
     out->prefetch_launches = c->last_prefetch_launches;
     out->steps = c->steps;
     return PSV_OK;

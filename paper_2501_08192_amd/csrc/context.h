@@ -51,6 +51,7 @@ struct psv_ctx {
     std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_pairs;
     uint32_t steps = 0;
     uint32_t last_prefetch_launches = 0;
+    uint32_t step_launches = 0, step_layers = 0; // launches of the operator chain in the last step (windows included), and its layers
     unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
     uint32_t attn_chunk_tokens = 0;               // 0 = default split; else tokens per attention workgroup (psv_tune_attention)
     int overlap = -1;                            // psv_check_overlap's last answer (-1 = not run yet)

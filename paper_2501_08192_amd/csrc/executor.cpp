@@ -108,6 +108,7 @@ uint32_t spin_cap(float us) { return (uint32_t)(us * 4000.0f) + 100000u; }
 // the true dispatch gap -- no marker packets in between, which would add ~2 us each.
 psv_status prof_tag(psv_ctx *c, int32_t op)
 {
+    ++c->step_launches;                      // called once before every launch of the operator chain
     if (c->profile_op < 0) return PSV_OK;
     if (c->prof_next == c->prof_events.size()) {
         hipEvent_t e;
@@ -353,6 +354,8 @@ static psv_status enqueue_whole_step(psv_ctx *c, const float *x_in, float *x_out
     float2 *rope = c->at<float2>(c->ws.rope);
     const double *inv_freq = d.rope_theta > 0.f ? c->at<double>(c->ws.inv_freq) : nullptr;
     c->last_prefetch_launches = 0;
+    c->step_launches = 0;
+    c->step_layers = le - lb;
     ST_TRY(prof_tag(c, -2));
     HIP_TRY(launch_rope_table(c->kv.seq_lens, inv_freq, kv.max_tokens, 1, rope, s));
     StepLaunch p{};
@@ -421,6 +424,8 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     bool wait_qkv = false, wait_gate = false;
     bool side_used = false;
     c->last_prefetch_launches = 0;
+    c->step_launches = 0;
+    c->step_layers = le - lb;
     auto u16 = [](const void *p) { return static_cast<const uint16_t *>(p); };
     const bool w8 = d.weight_format == PSV_FMT_INT8;
     const size_t plane_h = (size_t)((B + 15) / 16 * 16) * H;   // hi -> lo plane distance of the bf16 activations

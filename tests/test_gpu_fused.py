@@ -150,3 +150,15 @@ def test_fused_hand_over_that_expires_is_reported_and_the_context_survives(mode)
         psv.psv_debug_force_wait_timeout(s.ctx, False)
         assert torch.equal(s.run(), good)                 # the failed step's cache rows are rewritten by this one
         s.sync()
+
+
+def test_stats_count_the_launches_of_the_path_that_ran():
+    w = bf.W("c2_like", 2, 4096, 4, 1, 1792, 1, 300, win=(5.0, 5.0))
+    for mode, want in ((None, 4), (1, 4), (0, 7), (2, 1)):       # by shape: per-segment kernels here; windows count as launches
+        with Session(w, seed=67, fused=mode) as s:
+            s.run()
+            assert psv.psv_get_stats(s.ctx)["kernels_per_layer"] == want, mode
+    wb = bf.W("b4", 2, 1024, 8, 2, 768, 4, 100, win=(5.0, 0.0))   # matrix-core path: ten kernels and one window
+    with Session(wb, seed=67) as s:
+        s.run()
+        assert psv.psv_get_stats(s.ctx)["kernels_per_layer"] == 11
