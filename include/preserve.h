@@ -105,7 +105,8 @@ typedef struct {
     uint32_t weight_layout; /* PSV_W_ROW_MAJOR (default) or PSV_W_TILED: see the conventions */
 } psv_model_desc;
 
-/* dev pointers; projection matrices in the descriptor's weight_format, gains bf16 */
+/* dev pointers; projection matrices in the descriptor's weight_format and weight_layout (shapes below: rows x columns),
+ * gains bf16 */
 typedef struct {
     const void *w_qkv;      /* [(nq+2nkv)*128, H]  rows: q heads, then k heads, then v heads */
     const void *w_o;        /* [H, nq*128] */
@@ -262,8 +263,10 @@ psv_status psv_decode_step(psv_ctx *ctx, const float *x_in, float *x_out, uint32
                            uint32_t layer_begin, uint32_t layer_end);
 
 /* Waits for both streams (the event synchronisation between the two streams of Section 3, "PRESERVE", seen
- * from the host).  PSV_ERR_HIP if any enqueued work failed; PSV_ERR_TIMEOUT, once, if a kernel launched ahead
- * of its window gave up waiting for the window's end (it still finished; the context stays usable). */
+ * from the host).  PSV_ERR_HIP if any enqueued work failed -- also, once, if a hand-over inside a fused kernel
+ * (psv_set_fused_kernels, preserve_aux.h) ran out of its bound: that step's results are invalid, the context stays
+ * usable; PSV_ERR_TIMEOUT, once, if a kernel launched ahead of its window gave up waiting for the window's end (it
+ * still finished with the right result; the context stays usable). */
 psv_status psv_sync(psv_ctx *ctx);
 
 /* Algorithmic bytes of the step as Section 2 ("LLM decoding is memory BW-limited") counts them -- every weight
@@ -278,8 +281,8 @@ psv_status psv_get_stats(psv_ctx *ctx, psv_stats *out);
  * psv_create would allocate held in a fixed device array of PSV_STATIC_SCRATCH_BYTES inside the library instead.
  * The call allocates no device memory and creates no stream or event (its host-side bookkeeping is a few small
  * heap vectors).  layers: host array [desc->n_layers] (only the entries of the range are read); kv, x_in, x_out,
- * batch: as for psv_set_kv / psv_decode_step; the results are those of psv_decode_step with the policy off and both
- * windows 0, bit for bit.  PSV_ERR_UNSUPPORTED if psv_workspace_bytes(desc) exceeds PSV_STATIC_SCRATCH_BYTES.
+ * batch: as for psv_set_kv / psv_decode_step; the results are those of psv_decode_step with the policy off, both
+ * windows 0 and one kernel per operator (psv_set_fused_kernels 0, preserve_aux.h), bit for bit.  PSV_ERR_UNSUPPORTED if psv_workspace_bytes(desc) exceeds PSV_STATIC_SCRATCH_BYTES.
  * Every call on a GPU shares that GPU's one array, which keeps the previous call's contents (nothing in it has to
  * start at zero): calls that overlap on one GPU -- from two streams or two threads -- race; serialise them.  The
  * array (one per GPU the library runs on) stays allocated until the process ends. */
