@@ -106,6 +106,9 @@ psv_status psv_debug_force_wait_timeout(psv_ctx *ctx, uint32_t on);
 /* Which kernels the most recent psv_decode_step ran: 0 = one per operator, 1 = at least one block as a fused kernel,
  * 2 = the whole step as one kernel (psv_set_fused_kernels asks; the shape decides). */
 psv_status psv_debug_last_step_path(psv_ctx *ctx, uint32_t *path);
+/* How many first consumers the most recent psv_decode_step launched into their communication windows (policy.prelaunch;
+ * per-operator and per-block kernels -- the whole-step kernel has its windows inside and reports 0). */
+psv_status psv_debug_last_step_prelaunches(psv_ctx *ctx, uint32_t *count);
 
 /* Intermediate buffers of the most recent layer executed, for debugging parity failures.  PSV_DBG_H1 and
  * PSV_DBG_H2 exist only when the step ran on the vector path (batch 1, or batch 2 with H <= 4096): the

@@ -31,7 +31,7 @@ EXPORTS = [
     "psv_set_graph_mode", "psv_decode_step", "psv_sync", "psv_get_stats", "psv_tune_attention", "psv_check_overlap",
     "psv_set_profile_op",
     "psv_get_profile", "psv_prefetch_region", "psv_spin", "psv_copy_bytes", "psv_debug_read",
-    "psv_debug_force_wait_timeout", "psv_decode_step_static", "psv_set_fused_kernels", "psv_debug_last_step_path", "psv_tile_weights",
+    "psv_debug_force_wait_timeout", "psv_decode_step_static", "psv_set_fused_kernels", "psv_debug_last_step_path", "psv_debug_last_step_prelaunches", "psv_tile_weights",
 ]
 
 
@@ -117,6 +117,7 @@ def lib():
             "psv_debug_read": (C.c_int32, [vp, u32, vp, sz]),
             "psv_debug_force_wait_timeout": (C.c_int32, [vp, u32]),
             "psv_debug_last_step_path": (C.c_int32, [vp, C.POINTER(u32)]),
+            "psv_debug_last_step_prelaunches": (C.c_int32, [vp, C.POINTER(u32)]),
             "psv_tile_weights": (C.c_int32, [vp, vp, u32, u32, u32, vp]),
             "psv_set_fused_kernels": (C.c_int32, [vp, u32]),
             "psv_decode_step_static": (C.c_int32, [C.POINTER(psv_model_desc), C.POINTER(psv_layer_weights),
@@ -314,6 +315,12 @@ def psv_tile_weights(dst, src, rows, cols, weight_format, stream):
 def psv_debug_last_step_path(ctx):
     out = C.c_uint32(0)
     _check(lib().psv_debug_last_step_path(ctx, C.byref(out)), "psv_debug_last_step_path")
+    return int(out.value)
+
+
+def psv_debug_last_step_prelaunches(ctx):
+    out = C.c_uint32(0)
+    _check(lib().psv_debug_last_step_prelaunches(ctx, C.byref(out)), "psv_debug_last_step_prelaunches")
     return int(out.value)
 
 

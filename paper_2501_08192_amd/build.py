@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpreserve_mi355x.so")
 SOURCES = ["gemv.hip", "gemm_sk.hip", "attention.hip", "window.hip", "segment.hip", "step.hip", "static_step.hip", "executor.cpp", "api.cpp", "planner.cpp"]
-HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "device.h"), os.path.join(CSRC, "context.h"), os.path.join(CSRC, "tagged.h"),
+HEADERS = [os.path.join(CSRC, "internal.h"), os.path.join(CSRC, "device.h"), os.path.join(CSRC, "context.h"), os.path.join(CSRC, "tagged.h"), os.path.join(CSRC, "prefetch.h"),
            os.path.join(HERE, "..", "include", "preserve.h"), os.path.join(HERE, "..", "include", "preserve_aux.h")]
 
 # Packed-FP32 VALU instructions are switched off for all device code.

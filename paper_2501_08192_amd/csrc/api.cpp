@@ -200,6 +200,13 @@ psv_status psv_debug_last_step_path(psv_ctx *c, uint32_t *path)
     return PSV_OK;
 }
 
+psv_status psv_debug_last_step_prelaunches(psv_ctx *c, uint32_t *count)
+{
+    if (!c || !count) return PSV_ERR_INVALID_ARG;
+    *count = c->last_step_prelaunches;
+    return PSV_OK;
+}
+
 psv_status psv_set_fused_kernels(psv_ctx *c, uint32_t on)
 {
     if (!c || on > 3) return PSV_ERR_INVALID_ARG;

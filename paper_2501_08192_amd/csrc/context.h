@@ -19,7 +19,7 @@ struct Workspace {
     size_t total = 0;
     // offsets
     size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, rope, part_ml, part_o, attn_f32, attn_bf16,
-        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag, part, ssq, m_ll, qkv_ll, pml_ll, po_ll, step_tbl, step_ll;
+        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag, part, ssq, ssq_ll, m_ll, qkv_ll, pml_ll, po_ll, step_tbl, step_ll;
 };
 
 Workspace layout_workspace(const psv_model_desc &d);
@@ -52,6 +52,7 @@ struct psv_ctx {
     uint32_t steps = 0;
     uint32_t last_prefetch_launches = 0;
     uint32_t step_launches = 0, step_layers = 0; // launches of the operator chain in the last step (windows included), and its layers
+    uint32_t last_step_prelaunches = 0;          // consumers the last step launched into their windows
     unsigned window_seq = 0;                     // sequence number of the last communication window enqueued
     uint32_t attn_chunk_tokens = 0;               // 0 = default split; else tokens per attention workgroup (psv_tune_attention)
     int overlap = -1;                            // psv_check_overlap's last answer (-1 = not run yet)

@@ -51,6 +51,7 @@ Workspace layout_workspace(const psv_model_desc &d)
     w.inv_freq = take(64 * sizeof(double));
     w.flag = take(256);
     w.ssq = take(B * (H / 512) * 4);
+    w.ssq_ll = take((B * (H / 512) + 511) / 512 * 512 * 8);     // the same as tagged values, for a projection launched ahead of them
     w.m_ll = take(B * F * 8);               // tagged values of the fused MLP kernel
     {                                       // ... and of the fused attention-block kernel (one sequence)
         const size_t nc = (size_t)seg_attn_chunks(d.max_seq);
@@ -250,14 +251,27 @@ struct Lanes {
 // flags the window kernel publishes (start, end).  *wait_set tells the caller to launch the consumer that way.
 // Does the plan hand the whole weight matrix of the first consumer after (layer, window) to that window, so that
 // the consumer can be launched ahead of time (policy.prelaunch, eager launches, vector path)?
-bool can_prelaunch(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t layer_end, bool vec)
+// Matrix-core path (bf16 weights, batch <= 16, gate/up only): the consumer is a split-K GEMM that keeps only its first
+// slabs on chip, so any planned share of its weights qualifies, and its waiting workgroups must leave room for the kernel
+// they wait for.
+bool can_prelaunch(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t layer_end, bool vec, int batch)
 {
-    if (!vec || c->policy.mode != 1 || !c->policy.prelaunch || !(c->window_us[window] > 0.f)) return false;
+    if (c->policy.mode != 1 || !c->policy.prelaunch || !(c->window_us[window] > 0.f)) return false;
     if (c->overlap != 1) return false;      // a waiting kernel may only be queued where it cannot block the window kernel
     if (window == 1 && layer + 1 >= layer_end) return false;       // end of the graph: no consumer
     const uint32_t first_op = window == 0 ? PSV_OP_GATE : PSV_OP_QKV;
+    if (!vec) {
+        // Only the gate/up projection: the next layer's QKV projection launched that way measured 1-2 us per layer
+        // slower than left behind its window (a matrix of 20-40 MB: the latencies after the wait -- poll, activations,
+        // epilogue -- add up to the whole ordinary kernel).
+        if (window != 0) return false;
+        const psv_model_desc &d = c->d;
+        const int H = (int)d.hidden, N = window == 0 ? 2 * (int)d.ffn : (int)(d.n_q_heads + 2 * d.n_kv_heads) * 128;
+        if (!gemm_sk_can_wait(batch, N, H, d.weight_format == PSV_FMT_INT8, c->cus)) return false;
+    }
     for (const psv_plan_entry &e : c->plan)
-        if (e.layer == layer && e.window == window && e.target_op == first_op && e.bytes == e.mem_size) return true;
+        if (e.layer == layer && e.window == window && e.target_op == first_op && (vec ? e.bytes == e.mem_size : e.bytes > 0))
+            return true;
     return false;
 }
 
@@ -271,10 +285,13 @@ bool plan_has_whole(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t 
 
 // held: bit mask (1 << PSV_OP_*) of the operators whose planned bytes the pre-launched consumer pulls into its own
 // registers during the window; their plan entries are not prefetched a second time.
+// defer (matrix-core path): the pre-launched consumer walks the window's (last) prefetch job itself while it waits --
+// behind a prefetch launch on its own stream it would only start when that launch has finished.
 psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t batch, uint32_t layer_end, bool pre,
-                       uint32_t held, Lanes *ln, GemvWait *wait, bool *wait_set, bool *side_used)
+                       uint32_t held, Lanes *ln, GemvWait *wait, bool *wait_set, bool *side_used, PrefetchJob *defer)
 {
     *wait_set = false;
+    if (defer) *defer = PrefetchJob{};
     const float us = c->window_us[window];
     if (!(us > 0.f)) return PSV_OK;
     bool any = false;
@@ -305,7 +322,13 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
         psv_status st = add_entry(c, jb, e, batch);
         if (st != PSV_OK) return st;
     }
-    jb.flush();
+    if (pre && defer) {
+        *defer = jb.job;
+        defer->skip = skip;
+        if (jb.st == PSV_OK && (jb.job.n_regions || jb.job.kv_count)) ++c->last_prefetch_launches;
+    } else {
+        jb.flush();
+    }
     if (jb.st != PSV_OK) return jb.st;
     *side_used = true;
     if (pre) {
@@ -315,6 +338,7 @@ psv_status comm_window(psv_ctx *c, uint32_t layer, uint32_t window, uint32_t bat
         wait->ticks = c->force_wait_timeout ? 0ull : us_to_ticks(c->clock_khz, us) * 2 + c->clock_khz * 1000 /* + 1 s */;
         wait->err = err;
         *wait_set = true;
+        ++c->last_step_prelaunches;
         c->check_err_word = true;
         std::swap(ln->cur, ln->other);     // the chain continues behind the consumer
         return PSV_OK;
@@ -354,6 +378,7 @@ static psv_status enqueue_whole_step(psv_ctx *c, const float *x_in, float *x_out
     float2 *rope = c->at<float2>(c->ws.rope);
     const double *inv_freq = d.rope_theta > 0.f ? c->at<double>(c->ws.inv_freq) : nullptr;
     c->last_prefetch_launches = 0;
+    c->last_step_prelaunches = 0;
     c->step_launches = 0;
     c->step_layers = le - lb;
     ST_TRY(prof_tag(c, -2));
@@ -424,6 +449,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     bool wait_qkv = false, wait_gate = false;
     bool side_used = false;
     c->last_prefetch_launches = 0;
+    c->last_step_prelaunches = 0;
     c->step_launches = 0;
     c->step_layers = le - lb;
     auto u16 = [](const void *p) { return static_cast<const uint16_t *>(p); };
@@ -472,11 +498,35 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     // one runs without pre-launch.
     int pre_left = 0;
     for (uint32_t l = lb; l < le; ++l)
-        for (uint32_t wdw = 0; wdw < 2; ++wdw) pre_left += can_prelaunch(c, l, wdw, le, vec) ? 1 : 0;
+        for (uint32_t wdw = 0; wdw < 2; ++wdw) pre_left += can_prelaunch(c, l, wdw, le, vec, B) ? 1 : 0;
     if (pre_left & 1) --pre_left;
     auto take_pre = [&](uint32_t l, uint32_t wdw) {
-        if (pre_left > 0 && can_prelaunch(c, l, wdw, le, vec)) { --pre_left; return true; }
+        if (pre_left > 0 && can_prelaunch(c, l, wdw, le, vec, B)) { --pre_left; return true; }
         return false;
+    };
+
+    // Matrix-core path, consumer launched into its window: it waits for the k_resid_sum that follows the window on the
+    // other stream, which publishes its sums of squares as tagged values.
+    SkWait skw{};
+    PrefetchJob sk_job{};
+    auto planned_share = [&](uint32_t layer, uint32_t window, uint32_t target_layer, uint32_t op) {
+        for (const psv_plan_entry &e : c->plan)
+            if (e.layer == layer && e.window == window && e.target_layer == target_layer && e.target_op == op)
+                return e.mem_size ? (double)e.bytes / (double)e.mem_size : 0.0;
+        return 0.0;
+    };
+    auto sk_wait = [&](uint32_t layer, uint32_t window) {      // the window that was just enqueued
+        skw.ssq_ll = c->at<void>(c->ws.ssq_ll);
+        skw.tag = next_tag();
+        skw.iters = wait.iters; skw.ticks = wait.ticks; skw.err = wait.err;
+        skw.win_done = wait.done; skw.win_seq = wait.seq;
+        skw.job = &sk_job;
+        if (window == 0) {
+            skw.share_w = planned_share(layer, 0, layer, PSV_OP_GATE);
+            skw.share_w2 = planned_share(layer, 0, layer, PSV_OP_UP);
+        } else {
+            skw.share_w = skw.share_w2 = planned_share(layer, 1, layer + 1, PSV_OP_QKV);
+        }
     };
 
     ST_TRY(prof_tag(c, -2));
@@ -491,7 +541,12 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
 
         if (sk) {
             ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x, u16(w.g_attn), h1b, plane_h, w8, ssq, s));
+            if (wait_qkv) {             // the QKV projection is launched into the window: this kernel stays behind the window's
+                sk_wait(l - 1, 1);      // kernel on the other stream and signals the projection
+                HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x, u16(w.g_attn), h1b, plane_h, w8, ssq, &skw, ln.other));
+            } else {
+                HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x, u16(w.g_attn), h1b, plane_h, w8, ssq, nullptr, s));
+            }
         }
         ST_TRY(prof_tag(c, PSV_OP_QKV));
         if (seg_attn) {
@@ -508,7 +563,8 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             wait_qkv = false;
         } else {
             if (!gemm_sk_supported(B, QR, H)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(Wqkv, Mat{}, 0, h1b, ssq, d.rms_eps, part, B, QR, H, s));
+            HIP_TRY(launch_gemm_sk(Wqkv, Mat{}, 0, h1b, ssq, d.rms_eps, part, B, QR, H, wait_qkv ? &skw : nullptr, s));
+            wait_qkv = false;
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H, w8), B, QR, false, qkv, nullptr, false, s));
         }
@@ -533,20 +589,25 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_gemv(Wo, Mat{}, attn, delta_a, B, H, QD, s));
         } else {
             if (!gemm_sk_supported(B, H, QD)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(Wo, Mat{}, 0, attnb, nullptr, 0.f, part, B, H, QD, s));
+            HIP_TRY(launch_gemm_sk(Wo, Mat{}, 0, attnb, nullptr, 0.f, part, B, H, QD, nullptr, s));
             attn_delta = part;
             attn_splits = gemm_sk_splits(B, H, QD, w8);
         }
 
         {
-            uint32_t held = 1u << PSV_OP_GATE | 1u << PSV_OP_UP;
+            uint32_t held = 1u << PSV_OP_GATE | 1u << PSV_OP_UP;     // (a pre-launched GEMM prefetches the rest of its share itself)
             if (seg_mlp && plan_has_whole(c, l, 0, l, PSV_OP_DOWN) && seg_mlp_holds_down(H, F, w8, blocks)) held |= 1u << PSV_OP_DOWN;
-            ST_TRY(comm_window(c, l, 0, batch, le, take_pre(l, 0), held, &ln, &wait, &wait_gate, &side_used));
+            ST_TRY(comm_window(c, l, 0, batch, le, take_pre(l, 0), held, &ln, &wait, &wait_gate, &side_used, sk ? &sk_job : nullptr));
         }
 
         if (sk) {
             ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_resid_sum(x, attn_delta, attn_splits, B, H, y, u16(w.g_mlp), h2b, plane_h, w8, ssq, s));
+            if (wait_gate) {
+                sk_wait(l, 0);
+                HIP_TRY(launch_resid_sum(x, attn_delta, attn_splits, B, H, y, u16(w.g_mlp), h2b, plane_h, w8, ssq, &skw, ln.other));
+            } else {
+                HIP_TRY(launch_resid_sum(x, attn_delta, attn_splits, B, H, y, u16(w.g_mlp), h2b, plane_h, w8, ssq, nullptr, s));
+            }
         }
         ST_TRY(prof_tag(c, PSV_OP_GATE));
         if (seg_mlp) {
@@ -560,7 +621,8 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             wait_gate = false;
         } else {
             if (!gemm_sk_supported(B, 2 * F, H)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(Wg, Wu, F, h2b, ssq, d.rms_eps, part, B, 2 * F, H, s));
+            HIP_TRY(launch_gemm_sk(Wg, Wu, F, h2b, ssq, d.rms_eps, part, B, 2 * F, H, wait_gate ? &skw : nullptr, s));
+            wait_gate = false;
             ST_TRY(prof_tag(c, -2));
             HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H, w8), B, 2 * F, true, m, mb, w8, s));
         }
@@ -573,7 +635,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_gemv(Wd, Mat{}, m, delta_m, B, H, F, s));
         } else {
             if (!gemm_sk_supported(B, H, F)) return PSV_ERR_UNSUPPORTED;
-            HIP_TRY(launch_gemm_sk(Wd, Mat{}, 0, mb, nullptr, 0.f, part, B, H, F, s));
+            HIP_TRY(launch_gemm_sk(Wd, Mat{}, 0, mb, nullptr, 0.f, part, B, H, F, nullptr, s));
             delta = part;
             delta_splits = gemm_sk_splits(B, H, F, w8);
         }
@@ -584,12 +646,12 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
                 if (plan_has_whole(c, l, 1, l + 1, PSV_OP_ATTN)) held |= 1u << PSV_OP_ATTN;
                 if (plan_has_whole(c, l, 1, l + 1, PSV_OP_O) && seg_attn_holds_o(H, nq, w8, blocks)) held |= 1u << PSV_OP_O;
             }
-            ST_TRY(comm_window(c, l, 1, batch, le, take_pre(l, 1), held, &ln, &wait, &wait_qkv, &side_used));
+            ST_TRY(comm_window(c, l, 1, batch, le, take_pre(l, 1), held, &ln, &wait, &wait_qkv, &side_used, sk ? &sk_job : nullptr));
         }
         res = y;
     }
     ST_TRY(prof_tag(c, -2));
-    HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x_out, nullptr, nullptr, 0, false, nullptr, s));
+    HIP_TRY(launch_resid_sum(res, delta, delta_splits, B, H, x_out, nullptr, nullptr, 0, false, nullptr, nullptr, s));
     if (ln.cur != c->main) {           // cannot happen with the pairing above; kept as a safety net
         HIP_TRY(hipEventRecord(c->ev_end, ln.cur));
         HIP_TRY(hipStreamWaitEvent(c->main, c->ev_end, 0));

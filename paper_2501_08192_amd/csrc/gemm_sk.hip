@@ -5,6 +5,8 @@
 // 16-byte-per-lane coalesced loads with many loads in flight per 64-lane wave; the matrix cores are used where a
 // vector-ALU formulation would bind on arithmetic (batch > 2 projections, grouped-query attention).
 #include "device.h"
+#include "tagged.h"
+#include "prefetch.h"
 
 namespace psv {
 
@@ -16,11 +18,30 @@ namespace psv {
 // a whole row: it stores out_res * gain as hi/lo bf16 planes and the sum of squares of its 512 outputs in
 // ssq[batch][H / 512].  RMSNorm is linear in its 1/rms factor, so that projection runs on the unnormalised planes
 // and multiplies its result by 1/rms of the batch row, which it forms from ssq (k_gemm_sk).
+// SIGNAL: a projection launched ahead of this kernel is waiting for its outputs (k_gemm_sk<NB, true>).  Every output is
+// stored written through to the memory side; once a workgroup's stores are acknowledged, its sum of squares goes out as a
+// tagged value {sum, tag} (ssq_ll, same index as ssq), and the waiting kernel proceeds when every entry carries the tag of
+// this launch.  No fence and no counter: a release fence makes every wave write back its XCD's L2 and a device-scope
+// counter serialises at the memory side -- measured 25-55 ns per workgroup either way, 7 us per layer at batch 8 and
+// 25 us at batch 32.
+__device__ __forceinline__ void st_wt16(void *p, float4 v)
+{
+    const f32x4 w = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(w) : "memory");
+}
+__device__ __forceinline__ void st_wt8(void *p, uint2 v)
+{
+    typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+    const u32x2_t w = {v.x, v.y};
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" ::"v"(p), "v"(w) : "memory");
+}
+
+template <bool SIGNAL>
 __global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res, const float *__restrict__ delta,
                                                    int delta_splits, size_t delta_stride, int H,
                                                    float *__restrict__ out_res, const uint16_t *__restrict__ gain,
                                                    uint16_t *__restrict__ xg_bf16, size_t plane_stride,
-                                                   int digits, float *__restrict__ ssq)
+                                                   int digits, float *__restrict__ ssq, uint2 *ssq_ll, unsigned tag)
 {
     __shared__ float red[2];
     const int b = blockIdx.y, tid = threadIdx.x;
@@ -41,7 +62,8 @@ __global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res
         for (int ks = 1; ks < kSkMaxSplits; ++ks) { e.x += t[ks].x; e.y += t[ks].y; e.z += t[ks].z; e.w += t[ks].w; }
         v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w;
     }
-    *reinterpret_cast<float4 *>(out_res + at) = v;
+    if (SIGNAL) st_wt16(out_res + at, v);
+    else *reinterpret_cast<float4 *>(out_res + at) = v;
     if (!gain) return;
     const float4 xg = make_float4(v.x * bf16_lo(g.x), v.y * bf16_hi(g.x), v.z * bf16_lo(g.y), v.w * bf16_hi(g.y));
     if (digits) {   // operand of an int8 projection
@@ -49,23 +71,40 @@ __global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res
     } else {
         uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
         split_bf16(xg.x, h0, l0); split_bf16(xg.y, h1, l1); split_bf16(xg.z, h2, l2); split_bf16(xg.w, h3, l3);
-        *reinterpret_cast<uint2 *>(xg_bf16 + at) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
-        *reinterpret_cast<uint2 *>(xg_bf16 + plane_stride + at) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+        if (SIGNAL) {
+            st_wt8(xg_bf16 + at, make_uint2(h0 | (h1 << 16), h2 | (h3 << 16)));
+            st_wt8(xg_bf16 + plane_stride + at, make_uint2(l0 | (l1 << 16), l2 | (l3 << 16)));
+        } else {
+            *reinterpret_cast<uint2 *>(xg_bf16 + at) = make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
+            *reinterpret_cast<uint2 *>(xg_bf16 + plane_stride + at) = make_uint2(l0 | (l1 << 16), l2 | (l3 << 16));
+        }
     }
     const float ss = wave_sum(v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w);
     if ((tid & 63) == 0) red[tid >> 6] = ss;
     __syncthreads();
-    if (tid == 0) ssq[(size_t)b * gridDim.x + blockIdx.x] = red[0] + red[1];
+    if (!SIGNAL) {
+        if (tid == 0) ssq[(size_t)b * gridDim.x + blockIdx.x] = red[0] + red[1];
+        return;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // every wave: its stores are acknowledged by the memory side
+    __syncthreads();
+    if (tid == 0) ll_store(ssq_ll + (size_t)b * gridDim.x + blockIdx.x, red[0] + red[1], tag);
 }
 
 hipError_t launch_resid_sum(const float *res, const float *delta, int delta_splits, int batch, int H, float *out_res,
                             const uint16_t *gain, uint16_t *xg_bf16, size_t plane_stride, bool digits, float *ssq,
-                            hipStream_t s)
+                            const SkWait *signal, hipStream_t s)
 {
-    PSV_LAUNCH(k_resid_sum, dim3(H / 512, batch), dim3(128), 0, s, res, delta, delta_splits, (size_t)batch * H, H,
-               out_res, gain, xg_bf16, plane_stride, digits ? 1 : 0, ssq);
+    if (signal && (!gain || digits || !signal->ssq_ll)) return hipErrorInvalidValue;   // only the form that prepares a bf16 operand signals
+    if (signal)
+        PSV_LAUNCH(k_resid_sum<true>, dim3(H / 512, batch), dim3(128), 0, s, res, delta, delta_splits, (size_t)batch * H, H,
+                   out_res, gain, xg_bf16, plane_stride, 0, ssq, static_cast<uint2 *>(signal->ssq_ll), signal->tag);
+    else
+        PSV_LAUNCH(k_resid_sum<false>, dim3(H / 512, batch), dim3(128), 0, s, res, delta, delta_splits, (size_t)batch * H, H,
+                   out_res, gain, xg_bf16, plane_stride, digits ? 1 : 0, ssq, static_cast<uint2 *>(nullptr), 0u);
     return hipGetLastError();
 }
+
 
 // ------------------------------------------------------------------------------------ split-K skinny GEMM
 
@@ -91,11 +130,35 @@ struct GemmSkArgs {
     const float *ssq;
     float eps;
     int tiled;                // weights in the tiled layout: a workgroup's 128 rows x 64 elements per slab are contiguous
+    // Launched ahead of its activations (k_gemm_sk<NB, true>): after requesting its first PF weight slabs every workgroup
+    // waits until all batch * K / 512 tagged sums of squares of k_resid_sum<true> carry wait_tag -- each is stored after
+    // its workgroup's share of xb has reached the memory side -- before it touches xb.  Bounds as in GemvArgs: a wait that
+    // runs into them sets *wait_err and the kernel goes on.
+    // While it waits it also does the window's prefetch of its own weights: every workgroup reads touch_w (rows of W) or
+    // touch_w2 (rows of W2) further slabs of its range and drops them, which leaves them in the memory-side cache.
+    const unsigned *win_done;   // the window's end word and sequence number: polled first (one word; the tagged values are
+    unsigned win_seq;           //   4-8 KiB per poll and workgroup, too much to hammer on for a whole window)
+    const uint2 *wait_ll;
+    unsigned wait_tag;
+    int touch_w, touch_w2;
+    uint32_t wait_iters;
+    uint64_t wait_ticks;
+    unsigned *wait_err;
 };
 
-template <int NB>
-__global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
+// WAIT: the variant launched into a communication window, on another stream than the kernel that produces its
+// activations; a kernel of its own, so that the ordinary one carries none of that code.  The activation planes are read
+// with ordinary loads: the kernel has not touched them before the wait, so neither its XCD's L2 nor its CU's cache can
+// hold an older copy (both were invalidated when the kernel started), and the producer's stores have reached the memory
+// side before it signals.  The sums of squares are what the wait polls, with device-coherent loads.
+__device__ __forceinline__ uint32_t xor4(uint4 v) { return v.x ^ v.y ^ v.z ^ v.w; }
+
+// pj (WAIT only): what else the window's plan prefetches -- other operators' weights, KV blocks.  The waiting kernel
+// is the window's prefetch kernel as well: it walks the job after its own slabs, before it starts polling.
+template <int NB, bool WAIT>
+__global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
 {
+    static_assert(!WAIT || NB == 1, "the waiting variant is built for one batch tile");
     constexpr int PF = 4;   // slabs of weight fragments in flight per wave (8 measured slower: fewer straight-line rounds, more registers)
     __shared__ uint4 xs[2][NB * 4][64];   // [buffer][(batch tile*2 + plane)*2 + k half][lane]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
@@ -163,12 +226,106 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
         for (int n = 0; n < NB; ++n) acc[mt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
     __shared__ float inv_s[NB * 16];
 
+    // WAIT: the first PF slabs of the range wait in the register ring as always and the next LH are parked in LDS (each
+    // thread keeps its own fragments there: 16 KiB per slab and workgroup).  LH is even (the activation double buffer
+    // alternates per slab); four slabs (78 KiB with the rest, two workgroups per compute unit) measured slower than two.
+    constexpr int LH = !WAIT ? 0 : 2;
+    constexpr int HS = PF + LH;             // slabs held on chip when the wait ends
+    __shared__ uint4 wl[LH ? LH * 4 * 256 : 1];
+    const bool held = WAIT && s1 - s0 >= HS;
+    if (held) {
+        // First the window's prefetch, while no register holds anything yet: the other operators' job, then the slabs of
+        // this workgroup's own range beyond the ones kept on chip -- four slabs (16 loads per lane) in flight, results dropped.
+        if (pj.n_regions || pj.kv_count) prefetch_walk(pj, blockIdx.y * gridDim.x + blockIdx.x, (uint64_t)gridDim.x * gridDim.y);
+        {
+            const int t_end = min(s1, s0 + (row_base < a.split_row ? a.touch_w : a.touch_w2));
+            uint32_t sink = 0;
+            for (int s = s0 + HS; s < t_end; s += 4) {
+                WFrag t[4];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if (s + q < t_end) load_w(s + q, t[q]);
+                    else t[q].a0[0] = t[q].a0[1] = t[q].a1[0] = t[q].a1[1] = zero16();
+                }
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    sink ^= xor4(t[q].a0[0]) ^ xor4(t[q].a0[1]) ^ xor4(t[q].a1[0]) ^ xor4(t[q].a1[1]);
+            }
+            asm volatile("" ::"v"(sink));   // keeps the loads alive without a store
+        }
+#pragma unroll
+        for (int e = 0; e < LH; e += 2) {
+            WFrag t[2];
+            load_w(s0 + PF + e, t[0]);
+            load_w(s0 + PF + e + 1, t[1]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                uint4 *d = wl + ((e + j) * 4) * 256 + tid;
+                d[0] = t[j].a0[0]; d[256] = t[j].a0[1]; d[512] = t[j].a1[0]; d[768] = t[j].a1[1];
+            }
+        }
+    } else if (WAIT) {      // a range too short for that: the job still has to be walked
+        if (pj.n_regions || pj.kv_count) prefetch_walk(pj, blockIdx.y * gridDim.x + blockIdx.x, (uint64_t)gridDim.x * gridDim.y);
+    }
     WFrag wq[PF];
 #pragma unroll
     for (int q = 0; q < PF; ++q)
         if (s0 + q < s1) load_w(s0 + q, wq[q]);
+    __shared__ float ssq_s[WAIT ? kSkWaitEntries : 1];
+    if (WAIT) {     // the weights above travel, then sit on chip, while the window runs
+        if (w == 0) {           // one wave polls
+            const int n_ent = a.batch * (K / 512);          // <= kSkWaitEntries; the buffer is padded to a multiple of 512 entries
+            const uint64_t t0 = wall_clock64();
+            uint32_t it = 0;
+            {
+                unsigned v = __hip_atomic_load(a.win_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                while ((int)(v - a.win_seq) < 0 && it < a.wait_iters && wall_clock64() - t0 < a.wait_ticks) {
+                    __builtin_amdgcn_s_sleep(8);
+                    v = __hip_atomic_load(a.win_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ++it;
+                }
+            }
+            bool ok;
+            for (;;) {
+                ok = true;
+                for (int e0 = 0; e0 < n_ent; e0 += 512) {   // 8 entries per lane and round: four 16-byte loads in flight
+                    const int e = e0 + lane * 8;
+                    u32x4 q0, q1, q2, q3;
+                    ll_issue(q0, a.wait_ll + e);
+                    ll_issue(q1, a.wait_ll + e + 2);
+                    ll_issue(q2, a.wait_ll + e + 4);
+                    ll_issue(q3, a.wait_ll + e + 6);
+                    ll_wait4(q0, q1, q2, q3);
+                    const unsigned t = a.wait_tag;
+                    ok = ok && (e + 0 >= n_ent || q0.y == t) && (e + 1 >= n_ent || q0.w == t) && (e + 2 >= n_ent || q1.y == t) &&
+                         (e + 3 >= n_ent || q1.w == t) && (e + 4 >= n_ent || q2.y == t) && (e + 5 >= n_ent || q2.w == t) &&
+                         (e + 6 >= n_ent || q3.y == t) && (e + 7 >= n_ent || q3.w == t);
+                    ssq_s[e + 0] = __uint_as_float(q0.x); ssq_s[e + 1] = __uint_as_float(q0.z);
+                    ssq_s[e + 2] = __uint_as_float(q1.x); ssq_s[e + 3] = __uint_as_float(q1.z);
+                    ssq_s[e + 4] = __uint_as_float(q2.x); ssq_s[e + 5] = __uint_as_float(q2.z);
+                    ssq_s[e + 6] = __uint_as_float(q3.x); ssq_s[e + 7] = __uint_as_float(q3.z);
+                }
+                ok = __all(ok);
+                if (ok || it >= a.wait_iters || wall_clock64() - t0 >= a.wait_ticks) break;
+                __builtin_amdgcn_s_sleep(16);
+                ++it;
+            }
+            if (lane == 0 && !ok) atomicOr(a.wait_err, 2u);     // the activations may not be there: results invalid
+        }
+        __syncthreads();
+    }
+    // Activations.  Ordinary start: the first two slabs are requested, the first one goes to LDS.  After a wait the
+    // weights of the first HS slabs are on chip, so those steps would each cost one load latency of the activation
+    // pipeline (a slab is requested one step before it is stored): all their activation slabs are requested at once,
+    // together with the two that the main loop starts from.
     uint4 xr[2][NB];
-    if (s0 < s1) {
+    uint4 xa[WAIT ? HS : 1][NB];
+    if (held) {
+#pragma unroll
+        for (int h = 0; h < HS; ++h) load_slab(s0 + h, xa[h]);
+        if (s0 + HS < s1) load_slab(s0 + HS, xr[0]);
+        if (s0 + HS + 1 < s1) load_slab(s0 + HS + 1, xr[1]);
+    } else if (s0 < s1) {
         load_slab(s0, xr[0]);
         if (s0 + 1 < s1) load_slab(s0 + 1, xr[1]);
         store_slab(0, xr[0]);
@@ -182,7 +339,9 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
             const int nblk = K / 512;                       // <= 32
             if (tid < a.batch) {
                 const float *p = a.ssq + (size_t)tid * nblk;
-                if ((nblk & 3) == 0) {                      // all loads at once, then the sum in block order
+                if (WAIT) {                                 // what the wait has read, in block order
+                    for (int q = 0; q < nblk; ++q) tot += ssq_s[tid * nblk + q];
+                } else if ((nblk & 3) == 0) {               // all loads at once, then the sum in block order
                     float4 t[8];
 #pragma unroll
                     for (int q = 0; q < 8; ++q)
@@ -222,10 +381,33 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a)
     // one it needs and wait with the exact vmcnt; behind predicated loads it waits for everything outstanding at the
     // top of every round, which exposes a full memory latency per PF slabs.
     int sb = s0;
+    if (held) {
+        // The slabs held on chip, in the order of the range (the sum of a split has one order, launched ahead or not):
+        // the ring's PF, each slot refilled with the slab PF + LH further on (the ring then holds what the main loop
+        // expects), then the LH from LDS.  Straight-line; a refill past the range re-reads its last slab and is never used.
+#pragma unroll
+        for (int h = 0; h < HS; ++h) {
+            const int buf = h & 1;
+            store_slab(buf, xa[h]);
+            __syncthreads();
+            if (h < PF) {
+                mfma_slab(buf, wq[h]);
+                load_w_all(min(s0 + h + HS, s1 - 1), wq[h]);
+            } else {
+                WFrag f;
+                const uint4 *d = wl + ((h - PF) * 4) * 256 + tid;
+                f.a0[0] = d[0]; f.a0[1] = d[256]; f.a1[0] = d[512]; f.a1[1] = d[768];
+                mfma_slab(buf, f);
+            }
+        }
+        sb = s0 + HS;
+        if (sb < s1) store_slab(0, xr[0]);      // HS is even: the main loop's first slab goes to buffer 0
+        __syncthreads();
+    }
     for (; sb + 2 * PF <= s1; sb += PF) {
 #pragma unroll
         for (int q = 0; q < PF; ++q) {
-            const int s = sb + q, buf = q & 1;      // (s - s0) & 1, because PF is even
+            const int s = sb + q, buf = q & 1;      // (s - s0) & 1, because PF and the number of slabs parked in LDS are even
             load_slab(s + 2, xr[q & 1]);
             mfma_slab(buf, wq[q]);
             load_w_all(s + PF, wq[q]);
@@ -475,10 +657,30 @@ bool gemm_sk_supported(int batch, int N, int K)
     return batch >= 1 && batch <= 64 && N % 16 == 0 && K % 64 == 0;
 }
 
+// Can this projection be launched ahead of its activations (launch_gemm_sk with a wait)?  Its workgroups then sit on
+// the compute units until k_resid_sum has run, so they must leave room for that kernel: at least a quarter of the
+// compute units keep a free workgroup slot of this kernel's size.  bf16 weights only.
+bool gemm_sk_can_wait(int batch, int N, int K, bool w8, int cus)
+{
+    if (w8 || !gemm_sk_supported(batch, N, K) || K % 512 || (long long)batch * (K / 512) > kSkWaitEntries) return false;
+    if (batch > kSkWaitMaxBatch) return false;         // one batch tile: the only instantiation of the waiting kernel
+    static int occ = 0;                    // resident workgroups per compute unit of k_gemm_sk<1, true>
+    if (!occ) {
+        int n = 0;
+        const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_gemm_sk<1, true>, 256, 0);
+        occ = e == hipSuccess && n > 0 ? n : -1;
+    }
+    if (occ < 1) return false;
+    const long long grid = (long long)((N + 127) / 128) * gemm_sk_splits(batch, N, K, false);
+    // ... and it is the window's prefetch kernel as well, which needs at least 128 workgroups to reach its rate
+    return grid >= 128 && grid + cus / 4 <= (long long)occ * cus;
+}
+
 hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, const float *ssq, float eps, float *part,
-                          int batch, int N, int K, hipStream_t s)
+                          int batch, int N, int K, const SkWait *wait, hipStream_t s)
 {
     const int nb = (batch + 15) / 16;
+    if (wait && (W.scale || !ssq || !wait->ssq_ll || !wait->win_done || batch > kSkWaitMaxBatch || K % 512 || (long long)batch * (K / 512) > kSkWaitEntries)) return hipErrorInvalidValue;
     if (W.scale) {   // int8 weights: xb holds digit planes (bytes), see k_gemm_sk_i8
         GemmI8Args q{};
         q.W = static_cast<const int8_t *>(W.w); q.W2 = static_cast<const int8_t *>(W2.w ? W2.w : W.w);
@@ -507,11 +709,24 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
     const int splits = gemm_sk_splits(batch, N, K, false);
     a.slabs_per_block = (a.n_slabs + splits - 1) / splits;
     const dim3 grid((N + 127) / 128, splits);
+    if (wait) {
+        a.win_done = wait->win_done; a.win_seq = wait->win_seq;
+        a.wait_ll = static_cast<const uint2 *>(wait->ssq_ll); a.wait_tag = wait->tag; a.wait_iters = wait->iters;
+        a.wait_ticks = wait->ticks; a.wait_err = wait->err;
+        // planned share of each matrix, spread evenly over its workgroups: slabs of a workgroup's range that are either kept
+        // on chip or read and dropped
+        auto touch = [&](double share) { return (int)(share * a.slabs_per_block + 0.5); };
+        a.touch_w = touch(wait->share_w);
+        a.touch_w2 = touch(wait->share_w2);
+        const PrefetchJob pj = wait->job ? *wait->job : PrefetchJob{};
+        PSV_LAUNCH((k_gemm_sk<1, true>), grid, dim3(256), 0, s, a, pj);
+        return hipGetLastError();
+    }
     switch (nb) {
-    case 1: PSV_LAUNCH(k_gemm_sk<1>, grid, dim3(256), 0, s, a); break;
-    case 2: PSV_LAUNCH(k_gemm_sk<2>, grid, dim3(256), 0, s, a); break;
-    case 3: PSV_LAUNCH(k_gemm_sk<3>, grid, dim3(256), 0, s, a); break;
-    case 4: PSV_LAUNCH(k_gemm_sk<4>, grid, dim3(256), 0, s, a); break;
+    case 1: PSV_LAUNCH((k_gemm_sk<1, false>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
+    case 2: PSV_LAUNCH((k_gemm_sk<2, false>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
+    case 3: PSV_LAUNCH((k_gemm_sk<3, false>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
+    case 4: PSV_LAUNCH((k_gemm_sk<4, false>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

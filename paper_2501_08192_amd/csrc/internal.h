@@ -159,14 +159,35 @@ int gemm_sk_splits(int batch, int N, int K, bool w8);
 bool gemm_sk_supported(int batch, int N, int K);
 // ssq != null (K % 512 == 0): x_bf16 holds x * gain without the 1/rms factor of its RMSNorm and ssq the partial
 // sums of squares [batch][K / 512] written by launch_resid_sum; the result is multiplied by 1/rms of its batch row.
+// wait != null (bf16 weights, ssq != null): launched into a communication window ahead of its activations, on another
+// stream than the launch_resid_sum that produces them, which is given the same SkWait as its signal.
+constexpr int kSkWaitMaxBatch = 16;      // measured: at batch 32 and 64 the producer's write-through stores and the reload of the
+                                         // activations cost what the held weights save
+constexpr int kSkWaitEntries = 1024;     // batch * K / 512 of a projection launched that way
+struct SkWait {
+    void *ssq_ll;            // tagged sums of squares, [batch][K / 512] x 8 bytes, padded to a multiple of 512 entries
+    unsigned tag;            // of this launch pair (next_tag)
+    const unsigned *win_done;   // launch_gemm_sk: end word of the window and the value it takes then (GemvWait::done, seq)
+    unsigned win_seq;
+    uint32_t iters;          // bounds of the wait, as in GemvWait
+    uint64_t ticks;
+    unsigned *err;
+    double share_w, share_w2;   // launch_gemm_sk: planned fraction (0..1) of W and of W2 that the kernel prefetches for itself
+    const struct PrefetchJob *job;   // launch_gemm_sk: what else it prefetches while it waits (may be null)
+};
 hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *x_bf16, const float *ssq, float eps,
-                          float *part, int batch, int N, int K, hipStream_t s);
+                          float *part, int batch, int N, int K, const SkWait *wait, hipStream_t s);
+// May that projection be launched with a wait on a device of `cus` compute units (its waiting workgroups leave room
+// for the kernel they wait for)?
+bool gemm_sk_can_wait(int batch, int N, int K, bool w8, int cus);
 // out_res = res + delta (delta: null, or `delta_splits` split-K partials summed in split order), one float4 per
 // thread over grid (H / 512, batch).  gain != null: also out_res * gain as hi/lo bf16 planes (xg_bf16, lo plane
 // plane_stride elements after the hi plane) and the sums of squares per workgroup, ssq[batch][H / 512].
 hipError_t launch_resid_sum(const float *res, const float *delta, int delta_splits, int batch, int H, float *out_res,
                             const uint16_t *gain, uint16_t *xg_bf16, size_t plane_stride, bool digits, float *ssq,
-                            hipStream_t s);
+                            const SkWait *signal, hipStream_t s);
+// signal != null (gain != null, bf16 planes): every output is written through to the memory side and each workgroup's
+// sum of squares is published as a tagged value in signal->ssq_ll once its other stores are acknowledged.
 // out = sum of the splits; swiglu: N = gate | up columns, out = silu(gate) * up of width N/2.  out_bf16
 // (optional) receives hi/lo planes.
 hipError_t launch_sk_reduce(const float *part, int splits, int batch, int N, bool swiglu, float *out,
