@@ -44,11 +44,14 @@ def parse():
                          "(window us x 4.5 MB/us), capped at 192 MB of the 256 MB Infinity Cache")
     ap.add_argument("--chunk-mb", type=float, default=0.0)
     ap.add_argument("--cu-budget", type=int, default=256)
-    ap.add_argument("--partial", type=int, default=-1, help="-1 = on for paged workloads (KV per layer exceeds any budget)")
+    ap.add_argument("--partial", type=int, default=1,
+                    help="1 = an operator that does not fit the rest of the budget is prefetched in part (policy extension; a KV "
+                         "cache or a wide projection can exceed any budget); 0 = whole operators only, as in Algorithm 1")
     ap.add_argument("--join", type=int, default=0)
     ap.add_argument("--prelaunch", type=int, default=1,
                     help="1 = the first operator after a window is launched at the window's start and holds its weights in "
-                         "registers until the window ends (policy extension; batch 1-2 only)")
+                         "registers until the window ends (policy extension; at batch 3-16 the gate/up projection only, "
+                         "above that none)")
     ap.add_argument("--targets", type=int, default=3)
     ap.add_argument("--window-us", type=float, nargs=2, default=None)
     ap.add_argument("--tune", type=int, default=0,
@@ -254,8 +257,6 @@ def main():
     MB = 1 << 20
     if a.budget_mb <= 0:
         a.budget_mb = min(192.0, max(w.window_us) * 4.5)
-    if a.partial < 0:
-        a.partial = 1 if w.paged else 0
     # with no flags `on` is harness.default_policy(w), the configuration the full-size parity tests run
     kw = dict(targets=a.targets, budget_bytes=int(a.budget_mb * MB), chunk_bytes=int(a.chunk_mb * MB),
               cu_budget=a.cu_budget, partial=a.partial, join=a.join)
@@ -279,7 +280,12 @@ def main():
             cold[name] = spread(event_steps(sess, max(10, min(a.steps, 60)), flush), L)
     identical = bool(torch.equal(outputs["off"], outputs["on"]) and torch.equal(outputs["off"], outputs["cache_only"]))
     stats = psv.psv_get_stats(sess.ctx)
-    prelaunch_active = bool(a.prelaunch) and bool(sess.overlap) and (w.batch == 1 or (w.batch == 2 and w.hidden <= 4096))
+    sess.set_policy(modes["on"])
+    sess.run()
+    n_prelaunched = psv.psv_debug_last_step_prelaunches(sess.ctx)     # consumers the `on` step launched into their windows
+    prelaunch_active = n_prelaunched > 0
+    vector_path = w.weight_layout != "tiled" and (w.batch == 1 or (w.batch == 2 and w.hidden <= 4096))
+    prelaunched_ops = ("qkv", "gate_up") if vector_path else ("gate_up",)      # matrix-core path: the gate/up GEMM only
 
     us = {k: v * 1e3 / L for k, v in ms.items()}
     win = sum(w.window_us)
@@ -330,7 +336,7 @@ def main():
                 k["us_" + mode_name] = None
                 continue
             k["us_" + mode_name] = round(t, 3)
-            launched_into_window = mode_name == "on" and prelaunch_active and name in ("qkv", "gate_up")
+            launched_into_window = mode_name == "on" and prelaunch_active and name in prelaunched_ops
             if launched_into_window:
                 # its weights were requested while the window ran: the time left after the window is no bandwidth figure
                 k["us_after_window_on"] = round(t, 3)
@@ -365,7 +371,7 @@ def main():
                                                       w.context, "paged" if w.paged else "contiguous",
                                                       "tiled" if w.weight_layout == "tiled" else "row-major", *w.window_us),
                    "prefetch_budget_mb": a.budget_mb, "cu_budget": a.cu_budget, "chunk_mb": a.chunk_mb,
-                   "partial": a.partial, "join": a.join, "prelaunch": a.prelaunch, "prelaunch_active": prelaunch_active,
+                   "partial": a.partial, "join": a.join, "prelaunch": a.prelaunch, "prelaunch_active": prelaunch_active, "prelaunched_per_step": n_prelaunched,
                    "targets": a.targets, "fused_kernels": "by shape" if a.fused < 0 else int(a.fused), "kernel_path": path, "streams_overlap": bool(sess.overlap),
                    "attn_tokens_per_workgroup": attn_chunk if a.tune else "default"},
         "us_per_layer_prefetch_off": round(us["off"], 3),

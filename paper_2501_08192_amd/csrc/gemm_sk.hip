@@ -18,7 +18,7 @@ namespace psv {
 // a whole row: it stores out_res * gain as hi/lo bf16 planes and the sum of squares of its 512 outputs in
 // ssq[batch][H / 512].  RMSNorm is linear in its 1/rms factor, so that projection runs on the unnormalised planes
 // and multiplies its result by 1/rms of the batch row, which it forms from ssq (k_gemm_sk).
-// SIGNAL: a projection launched ahead of this kernel is waiting for its outputs (k_gemm_sk<NB, true>).  Every output is
+// SIGNAL: a projection launched ahead of this kernel is waiting for its outputs (k_gemm_sk<1, HOLD>, HOLD > 0).  Every output is
 // stored written through to the memory side; once a workgroup's stores are acknowledged, its sum of squares goes out as a
 // tagged value {sum, tag} (ssq_ll, same index as ssq), and the waiting kernel proceeds when every entry carries the tag of
 // this launch.  No fence and no counter: a release fence makes every wave write back its XCD's L2 and a device-scope
@@ -52,14 +52,22 @@ __global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res
     if (gain) g = *reinterpret_cast<const uint2 *>(gain + i);
     if (delta) {
         const float *d = delta + at;
-        float4 t[kSkMaxSplits];   // all loads first (their latencies overlap), then the sum in split order
+        // all loads of a group first (their latencies overlap), then the sum in split order.  The signalling variant runs
+        // beside a full house of waiting workgroups and has to fit the registers they leave: groups of 8 instead of 16.
+        constexpr int GR = SIGNAL ? 8 : kSkMaxSplits;
+        float4 e = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int ks = 0; ks < kSkMaxSplits; ++ks)
-            t[ks] = ks < delta_splits ? *reinterpret_cast<const float4 *>(d + ks * delta_stride)
-                                      : make_float4(0.f, 0.f, 0.f, 0.f);
-        float4 e = t[0];
+        for (int k0 = 0; k0 < kSkMaxSplits; k0 += GR) {
+            if (k0 && k0 >= delta_splits) break;
+            float4 t[GR];
 #pragma unroll
-        for (int ks = 1; ks < kSkMaxSplits; ++ks) { e.x += t[ks].x; e.y += t[ks].y; e.z += t[ks].z; e.w += t[ks].w; }
+            for (int ks = 0; ks < GR; ++ks)
+                t[ks] = k0 + ks < delta_splits ? *reinterpret_cast<const float4 *>(d + (k0 + ks) * delta_stride)
+                                               : make_float4(0.f, 0.f, 0.f, 0.f);
+            if (k0 == 0) e = t[0];
+#pragma unroll
+            for (int ks = k0 ? 0 : 1; ks < GR; ++ks) { e.x += t[ks].x; e.y += t[ks].y; e.z += t[ks].z; e.w += t[ks].w; }
+        }
         v.x += e.x; v.y += e.y; v.z += e.z; v.w += e.w;
     }
     if (SIGNAL) st_wt16(out_res + at, v);
@@ -130,7 +138,7 @@ struct GemmSkArgs {
     const float *ssq;
     float eps;
     int tiled;                // weights in the tiled layout: a workgroup's 128 rows x 64 elements per slab are contiguous
-    // Launched ahead of its activations (k_gemm_sk<NB, true>): after requesting its first PF weight slabs every workgroup
+    // Launched ahead of its activations (k_gemm_sk<1, HOLD>, HOLD > 0): after requesting its first PF weight slabs every workgroup
     // waits until all batch * K / 512 tagged sums of squares of k_resid_sum<true> carry wait_tag -- each is stored after
     // its workgroup's share of xb has reached the memory side -- before it touches xb.  Bounds as in GemvArgs: a wait that
     // runs into them sets *wait_err and the kernel goes on.
@@ -155,9 +163,12 @@ __device__ __forceinline__ uint32_t xor4(uint4 v) { return v.x ^ v.y ^ v.z ^ v.w
 
 // pj (WAIT only): what else the window's plan prefetches -- other operators' weights, KV blocks.  The waiting kernel
 // is the window's prefetch kernel as well: it walks the job after its own slabs, before it starts polling.
-template <int NB, bool WAIT>
+// HOLD: 0 = the ordinary kernel; 1, 2 = the waiting variant keeping 6 or 12 slabs of its range on chip (the launcher takes
+// the larger one that the range has).
+template <int NB, int HOLD>
 __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
 {
+    constexpr bool WAIT = HOLD > 0;
     static_assert(!WAIT || NB == 1, "the waiting variant is built for one batch tile");
     constexpr int PF = 4;   // slabs of weight fragments in flight per wave (8 measured slower: fewer straight-line rounds, more registers)
     __shared__ uint4 xs[2][NB * 4][64];   // [buffer][(batch tile*2 + plane)*2 + k half][lane]
@@ -226,11 +237,12 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
         for (int n = 0; n < NB; ++n) acc[mt][n] = f32x4{0.f, 0.f, 0.f, 0.f};
     __shared__ float inv_s[NB * 16];
 
-    // WAIT: the first PF slabs of the range wait in the register ring as always and the next LH are parked in LDS (each
-    // thread keeps its own fragments there: 16 KiB per slab and workgroup).  LH is even (the activation double buffer
-    // alternates per slab); four slabs (78 KiB with the rest, two workgroups per compute unit) measured slower than two.
-    constexpr int LH = !WAIT ? 0 : 2;
-    constexpr int HS = PF + LH;             // slabs held on chip when the wait ends
+    // WAIT: the first PF slabs of the range wait in the register ring as always, the next RH in registers of their own
+    // (used once) and the LH after those are parked in LDS (each thread keeps its own fragments there: 16 KiB per slab and
+    // workgroup).  HS is even (the activation double buffer alternates per slab).
+    constexpr int RH = HOLD == 2 ? 4 : 0;
+    constexpr int LH = HOLD == 2 ? 4 : HOLD == 1 ? 2 : 0;
+    constexpr int HS = PF + RH + LH;        // slabs held on chip when the wait ends
     __shared__ uint4 wl[LH ? LH * 4 * 256 : 1];
     const bool held = WAIT && s1 - s0 >= HS;
     if (held) {
@@ -256,8 +268,8 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
 #pragma unroll
         for (int e = 0; e < LH; e += 2) {
             WFrag t[2];
-            load_w(s0 + PF + e, t[0]);
-            load_w(s0 + PF + e + 1, t[1]);
+            load_w(s0 + PF + RH + e, t[0]);
+            load_w(s0 + PF + RH + e + 1, t[1]);
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
                 uint4 *d = wl + ((e + j) * 4) * 256 + tid;
@@ -266,6 +278,11 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
         }
     } else if (WAIT) {      // a range too short for that: the job still has to be walked
         if (pj.n_regions || pj.kv_count) prefetch_walk(pj, blockIdx.y * gridDim.x + blockIdx.x, (uint64_t)gridDim.x * gridDim.y);
+    }
+    WFrag hq[RH ? RH : 1];
+    if (RH && held) {
+#pragma unroll
+        for (int q = 0; q < RH; ++q) load_w(s0 + PF + q, hq[q]);
     }
     WFrag wq[PF];
 #pragma unroll
@@ -316,13 +333,14 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
     }
     // Activations.  Ordinary start: the first two slabs are requested, the first one goes to LDS.  After a wait the
     // weights of the first HS slabs are on chip, so those steps would each cost one load latency of the activation
-    // pipeline (a slab is requested one step before it is stored): all their activation slabs are requested at once,
-    // together with the two that the main loop starts from.
+    // pipeline (a slab is requested one step before it is stored): their activation slabs are requested XG steps ahead --
+    // the first XG at once, together with the two that the main loop starts from.
     uint4 xr[2][NB];
-    uint4 xa[WAIT ? HS : 1][NB];
+    constexpr int XG = WAIT ? 6 : 1;
+    uint4 xa[XG][NB];
     if (held) {
 #pragma unroll
-        for (int h = 0; h < HS; ++h) load_slab(s0 + h, xa[h]);
+        for (int h = 0; h < XG; ++h) load_slab(s0 + h, xa[h]);
         if (s0 + HS < s1) load_slab(s0 + HS, xr[0]);
         if (s0 + HS + 1 < s1) load_slab(s0 + HS + 1, xr[1]);
     } else if (s0 < s1) {
@@ -383,19 +401,23 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
     int sb = s0;
     if (held) {
         // The slabs held on chip, in the order of the range (the sum of a split has one order, launched ahead or not):
-        // the ring's PF, each slot refilled with the slab PF + LH further on (the ring then holds what the main loop
-        // expects), then the LH from LDS.  Straight-line; a refill past the range re-reads its last slab and is never used.
+        // the ring's PF, each slot refilled with the slab HS further on (the ring then holds what the main loop expects),
+        // the RH of the extra registers, the LH from LDS.  Straight-line; a refill past the range re-reads its last slab
+        // and is never used.
 #pragma unroll
         for (int h = 0; h < HS; ++h) {
             const int buf = h & 1;
-            store_slab(buf, xa[h]);
+            store_slab(buf, xa[h % XG]);
+            if (h + XG < HS) load_slab(s0 + h + XG, xa[h % XG]);
             __syncthreads();
             if (h < PF) {
                 mfma_slab(buf, wq[h]);
                 load_w_all(min(s0 + h + HS, s1 - 1), wq[h]);
+            } else if (h < PF + RH) {
+                mfma_slab(buf, hq[RH ? h - PF : 0]);
             } else {
                 WFrag f;
-                const uint4 *d = wl + ((h - PF) * 4) * 256 + tid;
+                const uint4 *d = wl + ((h - PF - RH) * 4) * 256 + tid;
                 f.a0[0] = d[0]; f.a0[1] = d[256]; f.a1[0] = d[512]; f.a1[1] = d[768];
                 mfma_slab(buf, f);
             }
@@ -657,23 +679,61 @@ bool gemm_sk_supported(int batch, int N, int K)
     return batch >= 1 && batch <= 64 && N % 16 == 0 && K % 64 == 0;
 }
 
+// Which waiting variant a range of `slabs_per_block` slabs takes: the one that keeps 12 slabs on chip if the range has them.
+static int sk_hold_level(int slabs_per_block) { return slabs_per_block >= 12 ? 2 : 1; }
+
+// Resources of the waiting variants and of the kernel they wait for, asked from the runtime once.
+struct SkWaitRes {
+    int occ[2];          // resident workgroups per compute unit of k_gemm_sk<1, 1> and <1, 2>
+    int regs[2];         // registers per lane (vector + accumulation), rounded up to the allocation unit
+    int lds[2];          // static LDS bytes per workgroup
+    int regs_signal;     // k_resid_sum<true>
+    bool ok;
+};
+static const SkWaitRes &sk_wait_res()
+{
+    static SkWaitRes r = [] {
+        SkWaitRes q{};
+        const void *fn[2] = {reinterpret_cast<const void *>(k_gemm_sk<1, 1>), reinterpret_cast<const void *>(k_gemm_sk<1, 2>)};
+        q.ok = true;
+        for (int i = 0; i < 2; ++i) {
+            hipFuncAttributes at{};
+            int n = 0;
+            const hipError_t e1 = i == 0 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_gemm_sk<1, 1>, 256, 0)
+                                         : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_gemm_sk<1, 2>, 256, 0);
+            const hipError_t e2 = hipFuncGetAttributes(&at, fn[i]);
+            q.ok = q.ok && e1 == hipSuccess && e2 == hipSuccess && n > 0;
+            q.occ[i] = n;
+            q.regs[i] = (at.numRegs + 7) / 8 * 8;
+            q.lds[i] = (int)at.sharedSizeBytes;
+        }
+        hipFuncAttributes at{};
+        q.ok = q.ok && hipFuncGetAttributes(&at, reinterpret_cast<const void *>(k_resid_sum<true>)) == hipSuccess;
+        q.regs_signal = (at.numRegs + 7) / 8 * 8;
+        return q;
+    }();
+    return r;
+}
+
 // Can this projection be launched ahead of its activations (launch_gemm_sk with a wait)?  Its workgroups then sit on
-// the compute units until k_resid_sum has run, so they must leave room for that kernel: at least a quarter of the
-// compute units keep a free workgroup slot of this kernel's size.  bf16 weights only.
+// the compute units until k_resid_sum has run, so all of them must be resident at once and leave room for that kernel:
+// either a quarter of the compute units keep a free workgroup slot of this kernel's size, or a wave of k_resid_sum fits
+// beside a full house (512 registers per lane and SIMD, with 16 to spare; 160 KiB of LDS, with 4 KiB to spare).
+// bf16 weights only.
 bool gemm_sk_can_wait(int batch, int N, int K, bool w8, int cus)
 {
     if (w8 || !gemm_sk_supported(batch, N, K) || K % 512 || (long long)batch * (K / 512) > kSkWaitEntries) return false;
-    if (batch > kSkWaitMaxBatch) return false;         // one batch tile: the only instantiation of the waiting kernel
-    static int occ = 0;                    // resident workgroups per compute unit of k_gemm_sk<1, true>
-    if (!occ) {
-        int n = 0;
-        const hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_gemm_sk<1, true>, 256, 0);
-        occ = e == hipSuccess && n > 0 ? n : -1;
-    }
-    if (occ < 1) return false;
-    const long long grid = (long long)((N + 127) / 128) * gemm_sk_splits(batch, N, K, false);
+    if (batch > kSkWaitMaxBatch) return false;         // one batch tile: the only instantiations of the waiting kernel
+    const SkWaitRes &r = sk_wait_res();
+    if (!r.ok) return false;
+    const int splits = gemm_sk_splits(batch, N, K, false);
+    const int lv = sk_hold_level((K / 64 + splits - 1) / splits) - 1;
+    const long long grid = (long long)((N + 127) / 128) * splits;
     // ... and it is the window's prefetch kernel as well, which needs at least 128 workgroups to reach its rate
-    return grid >= 128 && grid + cus / 4 <= (long long)occ * cus;
+    if (grid < 128 || grid > (long long)r.occ[lv] * cus) return false;
+    const bool free_slots = grid + cus / 4 <= (long long)r.occ[lv] * cus;
+    const bool beside = 512 - r.occ[lv] * r.regs[lv] >= r.regs_signal + 16 && 163840 - r.occ[lv] * r.lds[lv] >= 4096;
+    return free_slots || beside;
 }
 
 hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, const float *ssq, float eps, float *part,
@@ -719,14 +779,15 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
         a.touch_w = touch(wait->share_w);
         a.touch_w2 = touch(wait->share_w2);
         const PrefetchJob pj = wait->job ? *wait->job : PrefetchJob{};
-        PSV_LAUNCH((k_gemm_sk<1, true>), grid, dim3(256), 0, s, a, pj);
+        if (sk_hold_level(a.slabs_per_block) == 2) PSV_LAUNCH((k_gemm_sk<1, 2>), grid, dim3(256), 0, s, a, pj);
+        else PSV_LAUNCH((k_gemm_sk<1, 1>), grid, dim3(256), 0, s, a, pj);
         return hipGetLastError();
     }
     switch (nb) {
-    case 1: PSV_LAUNCH((k_gemm_sk<1, false>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
-    case 2: PSV_LAUNCH((k_gemm_sk<2, false>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
-    case 3: PSV_LAUNCH((k_gemm_sk<3, false>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
-    case 4: PSV_LAUNCH((k_gemm_sk<4, false>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
+    case 1: PSV_LAUNCH((k_gemm_sk<1, 0>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
+    case 2: PSV_LAUNCH((k_gemm_sk<2, 0>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
+    case 3: PSV_LAUNCH((k_gemm_sk<3, 0>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
+    case 4: PSV_LAUNCH((k_gemm_sk<4, 0>), grid, dim3(256), 0, s, a, PrefetchJob{}); break;
     default: return hipErrorInvalidValue;
     }
     return hipGetLastError();

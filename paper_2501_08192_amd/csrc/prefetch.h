@@ -1,5 +1,5 @@
 // The walk of the prefetch kernel as a device function: k_prefetch runs it with its own grid, and a projection that is
-// launched into a communication window (k_gemm_sk<NB, true>) runs it while it waits, with the window's job as an argument.
+// launched into a communication window (the waiting variant of k_gemm_sk) runs it while it waits, with the window's job as an argument.
 #ifndef PSV_PREFETCH_H
 #define PSV_PREFETCH_H
 

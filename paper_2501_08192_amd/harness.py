@@ -8,10 +8,11 @@ from . import synth
 
 def default_policy(w: synth.Workload, **overrides):
     """The prefetch-on policy that bench.py times by default: budget C = min(192 MiB, longest window x 4.5 MiB/us)
-    (what the prefetch kernel can pull inside the window), 256 prefetch workgroups, whole operators except for
-    paged workloads (whose KV per layer exceeds any budget), first consumer of a window launched into the window."""
+    (what the prefetch kernel can pull inside the window), 256 prefetch workgroups, an operator that does not fit the rest
+    of the budget prefetched in part (a KV cache or a wide projection can exceed any budget), first consumer of a window
+    launched into the window."""
     kw = dict(mode=1, budget_bytes=int(min(192.0, max(w.window_us) * 4.5) * (1 << 20)), cu_budget=256,
-              partial=1 if w.paged else 0, prelaunch=1)
+              partial=1, prelaunch=1)
     kw.update(overrides)
     return psv.prefetch_policy(**kw)
 
