@@ -4,13 +4,14 @@ the level that serves them, communication as a fixed latency), re-parameterised 
 predict the speedup map and to pick a prefetch budget.
 
 Per kernel:  t = t_fixed + hit_bytes / bw_cache + miss_bytes / bw_hbm, with one (t_fixed, bw_hbm, bw_cache) triple
-per kernel class: the vector-ALU projections of batch 1-2, the matrix-core projections of larger batches, the decode
-attention, and the small kernels the matrix-core path adds (residual sums, split-K reductions, attention merge).
+per kernel class: the vector-ALU projections of batch 1-2, the matrix-core projections of larger batches (on row-major
+and on tiled weights), the decode attention, and the small kernels the matrix-core path adds (residual sums, split-K
+reductions, attention merge).
 Per window:  t = max(window, t_fork + prefetch_bytes / bw_prefetch)   (the prefetch may outlast the window),
 and whatever part of a prefetch is still running after the window competes with its consumer for HBM.
 
 The constants are not fitted to the workloads the model is used to predict: `sweeps.py calibrate` measures the
-per-operator kernel times of seven calibration shapes that are none of the benchmark workloads nor cells of the
+per-operator kernel times of a dozen calibration shapes that are none of the benchmark workloads nor cells of the
 speedup map, fits the triples by least squares and writes machine_mi355x.json next to this file; Machine.load()
 reads it.  tests/test_model.py holds the model to the measured records in tests/golden/measured_mi355x.json
 (written by `sweeps.py record`) within a stated tolerance.
@@ -33,6 +34,10 @@ class Machine:
     t_fixed_mm: float = 4.0
     bw_mm: float = 4.2e6
     bw_mm_cache: float = 5.0e6
+    # ... on tiled weights
+    t_fixed_mmt: float = 4.0
+    bw_mmt: float = 4.9e6
+    bw_mmt_cache: float = 5.6e6
     # decode attention
     t_fixed_attn: float = 4.5
     bw_attn: float = 4.8e6
@@ -49,6 +54,9 @@ class Machine:
     reg_bytes: float = 32e6      # weights its first pass holds in registers
     t_post: float = 3.0          # us it still needs after the window (poll, activations, reduce, drain)
     bw_reg: float = 24e6         # bytes/us at which it works through the weights it holds
+    # the gate/up GEMM launched into its window (policy.prelaunch, matrix-core path, batch <= 16)
+    t_post_mm: float = 6.0       # us after the window until it has worked through what it holds, the residual kernel it
+                                 #   waits for included
 
     @classmethod
     def load(cls, path=MACHINE_FILE):
@@ -61,9 +69,48 @@ class Machine:
         return replace(cls(), **{k: v for k, v in data.get("machine", {}).items() if k in names})
 
 
-def path_of(batch, hidden):
-    """Which projections a step runs: "vec" (vector ALU) or "mm" (matrix cores) -- the library's own rule."""
+def path_of(batch, hidden, weight_layout="row"):
+    """Which projections a step runs: "vec" (vector ALU), "mm" (matrix cores) or "mmt" (matrix cores on tiled weights,
+    at every batch) -- the library's own rule."""
+    if weight_layout == "tiled":
+        return "mmt"
     return "vec" if batch == 1 or (batch == 2 and hidden <= 4096) else "mm"
+
+
+def sk_splits(batch, n_rows, k, weight_bytes=2.0):
+    """K splits of the split-K GEMM: the library's cost model (0.6 us per slab step, 512 resident workgroups, weights and
+    partials at 4 TB/s)."""
+    n_slabs = k // 64
+    row_groups = (n_rows + 127) // 128
+    w_bytes, part_bytes = weight_bytes * n_rows * k, 8.0 * batch * n_rows
+    best, best_cost = 1, 1e30
+    ks = 1
+    while ks <= 16 and ks * 2 <= n_slabs:
+        spb = (n_slabs + ks - 1) // ks
+        if (n_slabs + spb - 1) // spb == ks:
+            rounds = (row_groups * ks + 511) // 512
+            cost = rounds * spb * 0.6 + (w_bytes + ks * part_bytes) / 4.0e6
+            if cost < best_cost - 1e-9:
+                best, best_cost = ks, cost
+        ks += 1
+    return best
+
+
+def mm_hold(batch, hidden, ffn, weight_format="bf16", cus=256):
+    """Fraction of the gate/up weights that the GEMM launched into its window keeps on chip (12 slabs of each workgroup's
+    range if it has that many, else 6), or 0.0 where the library does not launch it that way: batch above 16, int8
+    weights, fewer than 128 workgroups or more than stay resident beside the kernel it waits for."""
+    if weight_format != "bf16" or not (1 <= batch <= 16) or hidden % 512 or batch * (hidden // 512) > 1024:
+        return 0.0
+    n_rows = 2 * ffn
+    splits = sk_splits(batch, n_rows, hidden)
+    spb = (hidden // 64 + splits - 1) // splits
+    grid = (n_rows + 127) // 128 * splits
+    if spb >= 12:
+        ok, held = 128 <= grid <= 2 * cus, 12
+    else:
+        ok, held = grid >= 128 and grid + cus // 4 <= 3 * cus, 6
+    return min(1.0, held / spb) if ok else 0.0
 
 
 def op_bytes(hidden, n_q, n_kv, ffn, batch, context, head_dim=128, weight_format="bf16", kv_format="bf16"):
@@ -94,7 +141,7 @@ def plan_windows(b, budget):
 def prelaunched(b, windows, budget):
     """Which first consumers the `prelaunch` policy launches into their window: gate/up after window 1, the next
     layer's QKV after window 2, each only if the plan hands that window the whole operator (the gate matrix for
-    the pair).  Vector path only: the matrix-core path has no such launch."""
+    the pair).  Vector path; for the matrix-core paths see mm_hold and layer_time."""
     planned = plan_windows(b, budget) if budget > 0 else {}
     return {"gate_up": windows[0] > 0 and planned.get("gate", 0.0) >= b["gate"],
             "qkv": windows[1] > 0 and planned.get("qkv", 0.0) >= b["qkv"]}
@@ -106,14 +153,18 @@ def kernel_time(m: Machine, name, nbytes, hit, path="vec"):
         return m.t_fixed_attn + hit / m.bw_attn_cache + (nbytes - hit) / m.bw_attn
     if path == "mm":
         return m.t_fixed_mm + hit / m.bw_mm_cache + (nbytes - hit) / m.bw_mm
+    if path == "mmt":
+        return m.t_fixed_mmt + hit / m.bw_mmt_cache + (nbytes - hit) / m.bw_mmt
     return m.t_fixed + hit / m.bw_cache + (nbytes - hit) / m.bw_hbm
 
 
-def layer_time(b, windows, m: Machine, budget=0.0, prelaunch=False, path="vec"):
+def layer_time(b, windows, m: Machine, budget=0.0, prelaunch=False, path="vec", hold_mm=0.0):
     """us per layer.  budget = 0: prefetch off.  A window of 0 us launches no prefetch; a window's plan larger
     than the cache keeps only cache_bytes / planned of itself resident.  prelaunch (vector path): the first consumer
     of a window that the plan covers whole is launched into the window; it is not prefetched a second time, holds
-    up to reg_bytes of its weights in registers when the window ends and streams the rest."""
+    up to reg_bytes of its weights in registers when the window ends and streams the rest.  prelaunch (matrix-core
+    paths, hold_mm = mm_hold(...) > 0): the gate/up GEMM is launched into window 1 if the plan gives it anything, keeps
+    hold_mm of its weights on chip and streams the rest; the residual kernel ahead of it is part of t_post_mm."""
     groups = (("gate", "up", "down"), ("qkv", "attn", "o"))
     planned = plan_windows(b, budget) if budget > 0 else {}
     pre = prelaunched(b, windows, budget) if (prelaunch and path == "vec") else {"gate_up": False, "qkv": False}
@@ -129,9 +180,15 @@ def layer_time(b, windows, m: Machine, budget=0.0, prelaunch=False, path="vec"):
             hit[op] = planned.get(op, 0.0) * keep
     kernels = [("qkv", b["qkv"], hit["qkv"]), ("attn", b["attn"], hit["attn"]), ("o", b["o"], hit["o"]),
                ("gate_up", b["gate"] + b["up"], hit["gate"] + hit["up"]), ("down", b["down"], hit["down"])]
-    t = m.t_small * m.n_small if path == "mm" else 0.0
+    mm = path in ("mm", "mmt")
+    pre_mm = mm and prelaunch and hold_mm > 0 and windows[0] > 0 and planned.get("gate", 0.0) > 0
+    t = m.t_small * (m.n_small - (1 if pre_mm else 0)) if mm else 0.0
     for name, nbytes, h in kernels:
-        if pre.get(name):
+        if pre_mm and name == "gate_up":
+            rest, hit_rest = (1.0 - hold_mm) * nbytes, (1.0 - hold_mm) * h
+            bw, bwc = (m.bw_mmt, m.bw_mmt_cache) if path == "mmt" else (m.bw_mm, m.bw_mm_cache)
+            t += m.t_post_mm + hit_rest / bwc + (rest - hit_rest) / bw
+        elif pre.get(name):
             t += m.t_post + min(nbytes, m.reg_bytes) / m.bw_reg + max(0.0, nbytes - m.reg_bytes) / m.bw_hbm
         else:
             t += kernel_time(m, name, nbytes, h, path)
@@ -150,8 +207,8 @@ def best_budget(b, windows, m: Machine, candidates=(8e6, 16e6, 32e6, 64e6, 96e6,
     return min(candidates, key=lambda c: layer_time(b, windows, m, c, path=path))
 
 
-def speedup(b, windows, m: Machine, budget, prelaunch=False, path="vec"):
-    return layer_time(b, windows, m, 0.0, path=path) / layer_time(b, windows, m, budget, prelaunch, path=path)
+def speedup(b, windows, m: Machine, budget, prelaunch=False, path="vec", hold_mm=0.0):
+    return layer_time(b, windows, m, 0.0, path=path) / layer_time(b, windows, m, budget, prelaunch, path=path, hold_mm=hold_mm)
 
 
 def fit_line(points):

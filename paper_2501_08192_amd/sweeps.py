@@ -63,7 +63,8 @@ def speed_map(shape, batches, contexts, layers=3, window=20.0, out=print, kv_lay
             if w.kv_bytes_per_layer * layers > 60e9:
                 continue
             b = model.op_bytes(hidden, nq, nkv, ffn, B, T)
-            path = model.path_of(B, hidden) if weight_layout == "row" else "mm"     # tiled weights: matrix cores at every batch
+            path = model.path_of(B, hidden, weight_layout)
+            hold = model.mm_hold(B, hidden, ffn) if path != "vec" else 0.0
             budget = model.best_budget(b, (window, window), mach, path=path)
             with Session(w, layers=list(range(layers))) as s:
                 s.set_policy(psv.prefetch_policy(mode=0))
@@ -75,7 +76,7 @@ def speed_map(shape, batches, contexts, layers=3, window=20.0, out=print, kv_lay
                 if not torch.equal(x_off, x_on):
                     raise AssertionError("prefetch on/off outputs differ at batch %d context %d" % (B, T))
             m_off = model.layer_time(b, (window, window), mach, 0.0, path=path)
-            m_on = model.layer_time(b, (window, window), mach, budget, prelaunch=True, path=path)
+            m_on = model.layer_time(b, (window, window), mach, budget, prelaunch=True, path=path, hold_mm=hold)
             rows.append((B, T, off, on, m_off, m_on, budget))
             out("%5d %7d | %9.1f %9.1f %8.3f | %9.1f %9.1f %8.3f | %d MB"
                 % (B, T, off, on, off / on, m_off, m_on, m_off / m_on, budget / 1e6))
@@ -129,10 +130,13 @@ def policy_sweeps(name, layers=4, steps=30, which=("window", "budget", "chunk", 
 # ---- calibration of the analytic model ---------------------------------------------------------------------
 
 # Shapes the constants are fitted on: none of them is a benchmark workload or a cell of the speedup map.
-CAL_SHAPES = {   # hidden, q heads, kv heads, ffn, batch, context
-    "v1": (2048, 16, 2, 5632, 1, 1024), "v2": (8192, 8, 1, 3584, 1, 512), "v3": (4096, 8, 2, 2816, 1, 3072),
-    "m1": (2048, 16, 2, 5632, 8, 2048), "m2": (8192, 8, 1, 3584, 12, 2048), "m3": (4096, 8, 2, 2816, 48, 4096),
-    "m4": (8192, 8, 1, 3584, 24, 12288),     # a KV-dominated layer (151 MB of cache): sets the attention's streaming rate
+CAL_SHAPES = {   # hidden, q heads, kv heads, ffn, batch, context, weight layout
+    "v1": (2048, 16, 2, 5632, 1, 1024, "row"), "v2": (8192, 8, 1, 3584, 1, 512, "row"), "v3": (4096, 8, 2, 2816, 1, 3072, "row"),
+    "m1": (2048, 16, 2, 5632, 8, 2048, "row"), "m2": (8192, 8, 1, 3584, 12, 2048, "row"), "m3": (4096, 8, 2, 2816, 48, 4096, "row"),
+    "m4": (8192, 8, 1, 3584, 24, 12288, "row"),     # a KV-dominated layer (151 MB of cache): sets the attention's streaming rate
+    "m5": (4096, 8, 2, 2816, 6, 2048, "row"),
+    "t1": (2048, 16, 2, 5632, 8, 2048, "tiled"), "t2": (8192, 8, 1, 3584, 12, 2048, "tiled"), "t3": (4096, 8, 2, 2816, 48, 4096, "tiled"),
+    "t4": (8192, 8, 1, 3584, 24, 12288, "tiled"), "t5": (4096, 8, 2, 2816, 6, 2048, "tiled"),
 }
 OPS = {"qkv": psv.PSV_OP_QKV, "attn": psv.PSV_OP_ATTN, "o": psv.PSV_OP_O, "gate_up": psv.PSV_OP_GATE, "down": psv.PSV_OP_DOWN}
 
@@ -157,14 +161,15 @@ def slope_through(points, icpt):
 
 
 def calibrate(path, window=50.0, layers=3, out=print):
-    pts = {"vec": [], "vec_hit": [], "mm": [], "mm_hit": [], "attn": [], "attn_hit": [], "pre": []}
+    pts = {"vec": [], "vec_hit": [], "mm": [], "mm_hit": [], "mmt": [], "mmt_hit": [], "attn": [], "attn_hit": [], "pre": [], "pre_mm": []}
     raw, resid = {}, {}
     big = 192 * MB
-    for name, (H, nq, nkv, F, B, T) in CAL_SHAPES.items():
-        w = synth.Workload(name, 80, H, nq, nkv, 128, F, B, T, False, (window, window))
+    for name, (H, nq, nkv, F, B, T, layout) in CAL_SHAPES.items():
+        w = synth.Workload(name, 80, H, nq, nkv, 128, F, B, T, False, (window, window), weight_layout=layout)
         b = model.op_bytes(H, nq, nkv, F, B, T)
         nb = {"qkv": b["qkv"], "attn": b["attn"], "o": b["o"], "gate_up": b["gate"] + b["up"], "down": b["down"]}
-        cls = model.path_of(B, H)
+        cls = model.path_of(B, H, layout)
+        hold = model.mm_hold(B, H, F) if cls != "vec" else 0.0
         with Session(w, layers=list(range(layers))) as s:
             # windows long enough for the whole budget to arrive inside them; whole-layer timing first (it warms up)
             s.set_policy(psv.prefetch_policy(mode=0))
@@ -174,9 +179,11 @@ def calibrate(path, window=50.0, layers=3, out=print):
             hit = timed(s, layers)
             hit_ops = op_times(s)
             pre_ops = None
-            if cls == "vec":
+            if cls == "vec" or hold > 0:
                 s.set_policy(default_policy(w, budget_bytes=big, partial=1))
                 timed(s, layers, steps=5, reps=1)
+                if (psv.psv_debug_last_step_prelaunches(s.ctx) > 0) != (cls == "vec" or hold > 0):
+                    raise AssertionError("%s: the model's rule for launching into windows is not the library's" % name)
                 pre_ops = op_times(s)
         raw[name] = {"bytes": nb, "us_off": off_ops, "us_cache_only": hit_ops, "us_prelaunch": pre_ops, "layer_off": off, "layer_cache_only": hit}
         for op in ("qkv", "o", "gate_up", "down"):
@@ -184,21 +191,28 @@ def calibrate(path, window=50.0, layers=3, out=print):
             pts[cls + "_hit"].append((nb[op], hit_ops[op]))
         pts["attn"].append((nb["attn"], off_ops["attn"]))
         pts["attn_hit"].append((nb["attn"], hit_ops["attn"]))
-        if pre_ops:
+        if pre_ops and cls == "vec":
             pts["pre"] += [(nb["qkv"], pre_ops["qkv"]), (nb["gate_up"], pre_ops["gate_up"])]
+        elif pre_ops:       # (class, bytes it does not hold, us after the window) of the gate/up GEMM launched into its window
+            pts["pre_mm"].append((cls, (1.0 - hold) * nb["gate_up"], pre_ops["gate_up"]))
         resid[name] = off - sum(off_ops.values()) - 2 * window       # what the five operator kernels and the windows leave
         out("%s: layer off %.1f cache-only %.1f; ops off %s" % (name, off, hit, {k: round(v, 2) for k, v in off_ops.items()}))
         torch.cuda.empty_cache()
     d = model.Machine()
     t_fixed, bw_hbm = model.fit_line(pts["vec"])
     t_fixed_mm, bw_mm = model.fit_line(pts["mm"])
+    t_fixed_mmt, bw_mmt = model.fit_line(pts["mmt"])
+    bw_mm_cache, bw_mmt_cache = slope_through(pts["mm_hit"], t_fixed_mm), slope_through(pts["mmt_hit"], t_fixed_mmt)
     t_fixed_attn, bw_attn = model.fit_line(pts["attn"])
     w_extra = sum(resid[n] for n in ("v1", "v2", "v3")) / 3 / 2      # per window: its kernel overruns the request, plus its dispatch gap
-    mm_names = [n for n in CAL_SHAPES if n.startswith("m")]
+    mm_names = [n for n in CAL_SHAPES if n[0] in "mt"]
     t_small = sum(resid[n] - 2 * w_extra for n in mm_names) / len(mm_names) / d.n_small
     # a projection launched into its window: what is left after the window against the bytes it holds
     pre_pts = [(min(nb, d.reg_bytes), us - max(0.0, nb - d.reg_bytes) / bw_hbm) for nb, us in pts["pre"]]
     t_post, bw_reg = model.fit_line(pre_pts)
+    # the gate/up GEMM launched into its window: what is left after the window beyond streaming the part it does not hold
+    # (from the cache: the calibration budget covers the whole matrix)
+    t_post_mm = sum(us - rest / (bw_mmt_cache if cls == "mmt" else bw_mm_cache) for cls, rest, us in pts["pre_mm"]) / len(pts["pre_mm"])
     # the prefetch kernel alone on cold regions of three sizes
     pf = []
     stream = torch.cuda.Stream()
@@ -215,7 +229,8 @@ def calibrate(path, window=50.0, layers=3, out=print):
         del buf, flush
     _, bw_prefetch = model.fit_line(pf)
     mach = {"t_fixed": t_fixed, "bw_hbm": bw_hbm, "bw_cache": slope_through(pts["vec_hit"], t_fixed),
-            "t_fixed_mm": t_fixed_mm, "bw_mm": bw_mm, "bw_mm_cache": slope_through(pts["mm_hit"], t_fixed_mm),
+            "t_fixed_mm": t_fixed_mm, "bw_mm": bw_mm, "bw_mm_cache": bw_mm_cache,
+            "t_fixed_mmt": t_fixed_mmt, "bw_mmt": bw_mmt, "bw_mmt_cache": bw_mmt_cache, "t_post_mm": t_post_mm,
             "t_fixed_attn": t_fixed_attn, "bw_attn": bw_attn, "bw_attn_cache": slope_through(pts["attn_hit"], t_fixed_attn),
             "t_small": t_small, "t_window_extra": w_extra, "bw_prefetch": bw_prefetch, "t_post": t_post, "bw_reg": bw_reg}
     mach = {k: round(float(v), 4) for k, v in mach.items()}
@@ -244,7 +259,8 @@ def record(path, layers=4, out=print):
             s.set_policy(pol)
             pre = timed(s, n_layers)
             kernel_path = psv.psv_debug_last_step_path(s.ctx)      # 0: one kernel per operator, 1: one per segment
-        rows.append({"name": name, "hidden": w.hidden, "n_q": w.n_q_heads, "n_kv": w.n_kv_heads, "ffn": w.ffn, "batch": w.batch,
+            prelaunched = psv.psv_debug_last_step_prelaunches(s.ctx)
+        rows.append({"name": name, "weight_layout": w.weight_layout, "prelaunched": prelaunched, "hidden": w.hidden, "n_q": w.n_q_heads, "n_kv": w.n_kv_heads, "ffn": w.ffn, "batch": w.batch,
                      "context": w.context, "windows": list(w.window_us), "budget": int(pol.budget_bytes), "partial": int(pol.partial),
                      "us_off": round(off, 2), "us_cache_only": round(cache, 2), "us_default": round(pre, 2), "kernel_path": kernel_path})
         out(str(rows[-1]))
@@ -253,11 +269,13 @@ def record(path, layers=4, out=print):
     for name in ("c1", "c2", "c3", "c4", "c5"):
         w = synth.WORKLOADS[name]
         measure(name, w, min(layers, w.n_layers) if name != "c2" else 8)
-    for shape, cells in (("tp8", ((1, 1024), (1, 16384), (4, 4096), (16, 4096), (64, 4096), (16, 16384))),
-                         ("tp4", ((1, 4096), (16, 4096), (64, 16384)))):
+    for shape, layout, cells in (("tp8", "row", ((1, 1024), (1, 16384), (4, 4096), (16, 4096), (64, 4096), (16, 16384))),
+                                 ("tp4", "row", ((1, 4096), (16, 4096), (64, 16384))),
+                                 ("tp8", "tiled", ((4, 4096), (8, 16384), (16, 4096))), ("tp4", "tiled", ((8, 4096),))):
         H, nq, nkv, F = SHAPES[shape]
         for B, T in cells:
-            measure("%s_b%d_t%d" % (shape, B, T), synth.Workload("map", 80, H, nq, nkv, 128, F, B, T, False, (20.0, 20.0)), 3, budget=96e6)
+            measure("%s_b%d_t%d%s" % (shape, B, T, "_tiled" if layout == "tiled" else ""),
+                    synth.Workload("map", 80, H, nq, nkv, 128, F, B, T, False, (20.0, 20.0), weight_layout=layout), 3, budget=96e6)
     sweep = []
     w = synth.WORKLOADS["c5"]
     with Session(w, layers=list(range(layers))) as s:
