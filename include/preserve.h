@@ -81,7 +81,9 @@ enum {
     PSV_ERR_HIP = -4,           /* a HIP runtime call failed (also: no GPU present) */
     PSV_ERR_NOMEM = -5,         /* host or device allocation failed */
     PSV_ERR_TIMEOUT = -6        /* a kernel launched ahead of its communication window (policy.prelaunch) gave up its
-                                   bounded wait for the window's end; reported once, by psv_sync */
+                                   bounded wait for the window's end; reported once, by psv_sync.  (A matrix-core
+                                   projection launched that way waits for its activations as well: giving up
+                                   invalidates the step and is reported as PSV_ERR_HIP.) */
 };
 
 typedef struct psv_ctx psv_ctx;   /* opaque */
@@ -150,8 +152,14 @@ typedef struct {
                                 other stream, loads its first weights into registers while the window runs,
                                 waits for the window's end on a device flag and finishes from registers; the
                                 operator chain continues on that stream, so the two streams swap roles at
-                                every window.  Takes effect for eager launches at batch 1 (and batch 2 up
-                                to H = 4096), and only on a context whose two streams run concurrently
+                                every window.  Takes effect at batch 1 (and batch 2 up to H = 4096) for both
+                                windows when the plan hands them the operator whole; with the matrix-core
+                                projections (larger batches, or tiled weights) at batch <= 16 and bf16 weights
+                                for the gate/up projection when the plan hands its window any of it and all
+                                its workgroups fit the device at once -- that kernel also walks the window's
+                                prefetch job, keeps its first weight slabs in registers and LDS, and waits
+                                for the residual kernel that follows the window; and only on a context whose
+                                two streams run concurrently
                                 -- i.e. after psv_check_overlap (preserve_aux.h) has been called on the
                                 context and answered 1: a kernel that waits on a flag must never sit in front of the
                                 kernel that sets it -- under a profiler that serialises kernels, or on two

@@ -98,7 +98,8 @@ psv_status psv_tile_weights(void *dst, const void *src, uint32_t rows, uint32_t 
 
 /* Test aid for the bounded waits: while on, a kernel launched ahead of its window's end gives up its (always bounded)
  * wait at once -- it still completes with the right result, sets an error word, and the next psv_sync returns
- * PSV_ERR_TIMEOUT once -- and every hand-over inside a fused kernel (psv_set_fused_kernels) expires at once: those
+ * PSV_ERR_TIMEOUT once; a matrix-core projection launched that way reads activations that are not there yet, the step's
+ * output is invalid and the next psv_sync returns PSV_ERR_HIP once -- and every hand-over inside a fused kernel (psv_set_fused_kernels) expires at once: those
  * kernels run to their end on whatever their buffers held, the step's output and the cache rows it appends are
  * invalid, and the next psv_sync returns PSV_ERR_HIP once.  The context stays usable either way. */
 psv_status psv_debug_force_wait_timeout(psv_ctx *ctx, uint32_t on);

@@ -47,7 +47,7 @@ def timed(sess, n_layers, steps=20, warmup=5, reps=3):
     return sorted(ts)[len(ts) // 2]
 
 
-def speed_map(shape, batches, contexts, layers=3, window=20.0, out=print, kv_layout="head", weight_layout="row"):
+def speed_map(shape, batches, contexts, layers=4, window=20.0, out=print, kv_layout="head", weight_layout="row"):
     """off / on us per layer and speedup for every (batch, context), beside the analytic model's prediction.
     The budget is the one the model picks; the rest of the policy is bench.py's default."""
     hidden, nq, nkv, ffn = SHAPES[shape]
@@ -160,7 +160,7 @@ def slope_through(points, icpt):
     return num / den
 
 
-def calibrate(path, window=50.0, layers=3, out=print):
+def calibrate(path, window=50.0, layers=4, out=print):
     pts = {"vec": [], "vec_hit": [], "mm": [], "mm_hit": [], "mmt": [], "mmt_hit": [], "attn": [], "attn_hit": [], "pre": [], "pre_mm": []}
     raw, resid = {}, {}
     big = 192 * MB
@@ -275,7 +275,7 @@ def record(path, layers=4, out=print):
         H, nq, nkv, F = SHAPES[shape]
         for B, T in cells:
             measure("%s_b%d_t%d%s" % (shape, B, T, "_tiled" if layout == "tiled" else ""),
-                    synth.Workload("map", 80, H, nq, nkv, 128, F, B, T, False, (20.0, 20.0), weight_layout=layout), 3, budget=96e6)
+                    synth.Workload("map", 80, H, nq, nkv, 128, F, B, T, False, (20.0, 20.0), weight_layout=layout), 4, budget=96e6)
     sweep = []
     w = synth.WORKLOADS["c5"]
     with Session(w, layers=list(range(layers))) as s:
@@ -299,7 +299,8 @@ def main(argv=None):
     m.add_argument("shape", choices=sorted(SHAPES))
     m.add_argument("--batches", default="1,4,16,64")
     m.add_argument("--contexts", default="1024,4096,16384,65536")
-    m.add_argument("--layers", type=int, default=3)
+    m.add_argument("--layers", type=int, default=4,
+                   help="layers materialised; an even count, so that every window that can be launched into is (the chain has to end on the main stream)")
     m.add_argument("--window", type=float, default=20.0)
     m.add_argument("--kv-layout", default="head", choices=["head", "token"],
                    help="token: both pools [block, token, kv head, channel] -- one head's reads are strided when the shard has "
