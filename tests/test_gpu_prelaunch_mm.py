@@ -38,6 +38,8 @@ CASES = [
     ("wide_b8_row", 2, 8192, 8, 1, 3584, 8, 300, False, "row", (8.0, 8.0), 2),
     ("wide_b16_paged", 3, 8192, 8, 1, 3584, 16, 150, True, "tiled", (8.0, 8.0), 2),   # odd count: the last one stays behind
     ("wide_b3", 4, 4096, 4, 1, 7168, 3, 90, False, "row", (8.0, 0.0), 4),             # no window after the MLP block
+    ("short_range", 2, 1024, 8, 2, 8192, 8, 70, False, "row", (8.0, 8.0), 2),         # 4 slabs per workgroup: all in the ring
+    ("short_range5", 2, 1536, 12, 4, 6144, 4, 40, True, "tiled", (8.0, 8.0), 2),       # 5 slabs: one more than the ring holds
     ("no_window", 2, 8192, 8, 1, 3584, 8, 64, False, "tiled", (0.0, 8.0), 0),         # nothing to launch into
     ("b32", 2, 8192, 8, 1, 3584, 32, 64, False, "tiled", (8.0, 8.0), 0),              # above the batch limit of that route
     ("small", 2, 1024, 8, 2, 768, 5, 129, False, "row", (8.0, 8.0), 0),               # too few workgroups to carry the job
