@@ -138,14 +138,14 @@ struct GemmSkArgs {
     const float *ssq;
     float eps;
     int tiled;                // weights in the tiled layout: a workgroup's 128 rows x 64 elements per slab are contiguous
-    // Launched ahead of its activations (k_gemm_sk<1, HOLD>, HOLD > 0): after requesting its first PF weight slabs every workgroup
-    // waits until all batch * K / 512 tagged sums of squares of k_resid_sum<true> carry wait_tag -- each is stored after
-    // its workgroup's share of xb has reached the memory side -- before it touches xb.  Bounds as in GemvArgs: a wait that
-    // runs into them sets *wait_err and the kernel goes on.
-    // While it waits it also does the window's prefetch of its own weights: every workgroup reads touch_w (rows of W) or
-    // touch_w2 (rows of W2) further slabs of its range and drops them, which leaves them in the memory-side cache.
+    // Launched ahead of its activations (k_gemm_sk<1, HOLD>, HOLD > 0).  While the window runs every workgroup walks the
+    // window's prefetch job, reads and drops the slabs of its own range up to touch_w (rows of W) or touch_w2 (rows of
+    // W2) -- which leaves them in the memory-side cache -- and requests the slabs it keeps on chip.  Then it waits: for the
+    // window's end word first, then until all batch * K / 512 tagged sums of squares of k_resid_sum<true> carry wait_tag
+    // (each is stored after its workgroup's share of xb has reached the memory side); only then does it touch xb.
+    // Bounds as in GemvArgs: a wait that runs into them sets bit 1 of *wait_err and the kernel goes on.
     const unsigned *win_done;   // the window's end word and sequence number: polled first (one word; the tagged values are
-    unsigned win_seq;           //   4-8 KiB per poll and workgroup, too much to hammer on for a whole window)
+    unsigned win_seq;           //   up to 8 KiB per poll and workgroup, too much to hammer on for a whole window)
     const uint2 *wait_ll;
     unsigned wait_tag;
     int touch_w, touch_w2;
@@ -154,17 +154,16 @@ struct GemmSkArgs {
     unsigned *wait_err;
 };
 
-// WAIT: the variant launched into a communication window, on another stream than the kernel that produces its
-// activations; a kernel of its own, so that the ordinary one carries none of that code.  The activation planes are read
+// HOLD: 0 = the ordinary kernel; 1, 2 = the variant launched into a communication window, on another stream than the kernel
+// that produces its activations, keeping 6 or 12 slabs of its range on chip (the launcher takes the larger one that the
+// range has); kernels of their own, so that the ordinary one carries none of that code.  The activation planes are read
 // with ordinary loads: the kernel has not touched them before the wait, so neither its XCD's L2 nor its CU's cache can
 // hold an older copy (both were invalidated when the kernel started), and the producer's stores have reached the memory
 // side before it signals.  The sums of squares are what the wait polls, with device-coherent loads.
+// pj (HOLD > 0): what else the window's plan prefetches -- other operators' weights, KV blocks.  The waiting kernel is the
+// window's prefetch kernel as well: it walks the job first, before anything of its own sits in registers.
 __device__ __forceinline__ uint32_t xor4(uint4 v) { return v.x ^ v.y ^ v.z ^ v.w; }
 
-// pj (WAIT only): what else the window's plan prefetches -- other operators' weights, KV blocks.  The waiting kernel
-// is the window's prefetch kernel as well: it walks the job after its own slabs, before it starts polling.
-// HOLD: 0 = the ordinary kernel; 1, 2 = the waiting variant keeping 6 or 12 slabs of its range on chip (the launcher takes
-// the larger one that the range has).
 template <int NB, int HOLD>
 __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
 {

@@ -135,6 +135,7 @@ CAL_SHAPES = {   # hidden, q heads, kv heads, ffn, batch, context, weight layout
     "m1": (2048, 16, 2, 5632, 8, 2048, "row"), "m2": (8192, 8, 1, 3584, 12, 2048, "row"), "m3": (4096, 8, 2, 2816, 48, 4096, "row"),
     "m4": (8192, 8, 1, 3584, 24, 12288, "row"),     # a KV-dominated layer (151 MB of cache): sets the attention's streaming rate
     "m5": (4096, 8, 2, 2816, 6, 2048, "row"),
+    "m6": (8192, 8, 1, 3584, 20, 40960, "row"),      # 419 MB of cache per layer: the attention at its streaming rate
     "t1": (2048, 16, 2, 5632, 8, 2048, "tiled"), "t2": (8192, 8, 1, 3584, 12, 2048, "tiled"), "t3": (4096, 8, 2, 2816, 48, 4096, "tiled"),
     "t4": (8192, 8, 1, 3584, 24, 12288, "tiled"), "t5": (4096, 8, 2, 2816, 6, 2048, "tiled"),
 }

@@ -50,7 +50,7 @@ def test_fit_line_recovers_a_line_and_refuses_nonsense():
 
 # ---- the calibrated model against measured records -----------------------------------------------------------
 #
-# machine_mi355x.json holds constants fitted (sweeps.py calibrate) on thirteen calibration shapes that are neither benchmark
+# machine_mi355x.json holds constants fitted (sweeps.py calibrate) on fourteen calibration shapes that are neither benchmark
 # workloads nor cells of the speedup map; tests/golden/measured_mi355x.json holds measured us/layer (sweeps.py record) of
 # the five workloads, thirteen map cells and the c5 budget sweep.  The model has to predict every row it was not fitted on.
 
@@ -58,7 +58,7 @@ import json
 import os
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "measured_mi355x.json")
-TOL = 0.17      # relative error allowed per row and mode (worst measured: 15 %, the KV-dominated c5)
+TOL = 0.15      # relative error allowed per row and mode (worst: 14 %, batch 64 at a short context)
 
 
 def _golden():
