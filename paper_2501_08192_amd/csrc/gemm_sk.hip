@@ -290,7 +290,6 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
     __shared__ float ssq_s[WAIT ? kSkWaitEntries : 1];
     if (WAIT) {     // the weights above travel, then sit on chip, while the window runs
         if (w == 0) {           // one wave polls
-            const int n_ent = a.batch * (K / 512);          // <= kSkWaitEntries; the buffer is padded to a multiple of 512 entries
             const uint64_t t0 = wall_clock64();
             uint32_t it = 0;
             {
@@ -301,29 +300,22 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
                     ++it;
                 }
             }
+            // Then the tags of the producer workgroups that write this workgroup's K range (all batch rows): a few dozen
+            // entries, different lines for different splits.  (Every workgroup polling every entry made one 1-4 KiB
+            // region a hot spot: the flag was seen 4-5 us after the last producer had signalled.)
+            const int nblk = K / 512, blk0 = s0 >> 3, nbr = (((s1 << 6) - 1) >> 9) - blk0 + 1, cnt = a.batch * nbr;
             bool ok;
             for (;;) {
                 ok = true;
-                for (int e0 = 0; e0 < n_ent; e0 += 512) {   // 8 entries per lane and round: four 16-byte loads in flight
-                    const int e = e0 + lane * 8;
-                    u32x4 q0, q1, q2, q3;
-                    ll_issue(q0, a.wait_ll + e);
-                    ll_issue(q1, a.wait_ll + e + 2);
-                    ll_issue(q2, a.wait_ll + e + 4);
-                    ll_issue(q3, a.wait_ll + e + 6);
-                    ll_wait4(q0, q1, q2, q3);
-                    const unsigned t = a.wait_tag;
-                    ok = ok && (e + 0 >= n_ent || q0.y == t) && (e + 1 >= n_ent || q0.w == t) && (e + 2 >= n_ent || q1.y == t) &&
-                         (e + 3 >= n_ent || q1.w == t) && (e + 4 >= n_ent || q2.y == t) && (e + 5 >= n_ent || q2.w == t) &&
-                         (e + 6 >= n_ent || q3.y == t) && (e + 7 >= n_ent || q3.w == t);
-                    ssq_s[e + 0] = __uint_as_float(q0.x); ssq_s[e + 1] = __uint_as_float(q0.z);
-                    ssq_s[e + 2] = __uint_as_float(q1.x); ssq_s[e + 3] = __uint_as_float(q1.z);
-                    ssq_s[e + 4] = __uint_as_float(q2.x); ssq_s[e + 5] = __uint_as_float(q2.z);
-                    ssq_s[e + 6] = __uint_as_float(q3.x); ssq_s[e + 7] = __uint_as_float(q3.z);
+                for (int idx = lane; idx < cnt; idx += 64) {
+                    uint2 v;
+                    ll_issue1(v, a.wait_ll + (idx / nbr) * nblk + blk0 + idx % nbr);
+                    asm volatile("s_waitcnt vmcnt(0)" : "+v"(v) : : "memory");
+                    ok = ok && v.y == a.wait_tag;
                 }
                 ok = __all(ok);
                 if (ok || it >= a.wait_iters || wall_clock64() - t0 >= a.wait_ticks) break;
-                __builtin_amdgcn_s_sleep(16);
+                __builtin_amdgcn_s_sleep(8);
                 ++it;
             }
             if (lane == 0 && !ok) atomicOr(a.wait_err, 2u);     // the activations may not be there: results invalid
@@ -347,32 +339,35 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
         if (s0 + 1 < s1) load_slab(s0 + 1, xr[1]);
         store_slab(0, xr[0]);
     }
-    // 1/rms of every batch row from the partial sums of squares (block order); read in the epilogue only, the
-    // barriers of the main loop make it visible
-    if (tid < NB * 16) {
-        float inv = 1.0f;
-        if (a.ssq) {
-            float tot = 0.f;
-            const int nblk = K / 512;                       // <= 32
-            if (tid < a.batch) {
-                const float *p = a.ssq + (size_t)tid * nblk;
-                if (WAIT) {                                 // what the wait has read, in block order
-                    for (int q = 0; q < nblk; ++q) tot += ssq_s[tid * nblk + q];
-                } else if ((nblk & 3) == 0) {               // all loads at once, then the sum in block order
-                    float4 t[8];
+    // 1/rms of every batch row from the partial sums of squares (block order); read in the epilogue only.  The waiting
+    // variant forms it after the main loop, from the tagged values of all producer workgroups (by then long complete).
+    auto inv_rms = [&]() {
+        if (tid < NB * 16) {
+            float inv = 1.0f;
+            if (a.ssq) {
+                float tot = 0.f;
+                const int nblk = K / 512;                       // <= 32
+                if (tid < a.batch) {
+                    const float *p = a.ssq + (size_t)tid * nblk;
+                    if (WAIT) {                                 // what the wait has read, in block order
+                        for (int q = 0; q < nblk; ++q) tot += ssq_s[tid * nblk + q];
+                    } else if ((nblk & 3) == 0) {               // all loads at once, then the sum in block order
+                        float4 t[8];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q)
-                        t[q] = 4 * q < nblk ? *reinterpret_cast<const float4 *>(p + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+                        for (int q = 0; q < 8; ++q)
+                            t[q] = 4 * q < nblk ? *reinterpret_cast<const float4 *>(p + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) tot = (((tot + t[q].x) + t[q].y) + t[q].z) + t[q].w;
-                } else {
-                    for (int q = 0; q < nblk; ++q) tot += p[q];
+                        for (int q = 0; q < 8; ++q) tot = (((tot + t[q].x) + t[q].y) + t[q].z) + t[q].w;
+                    } else {
+                        for (int q = 0; q < nblk; ++q) tot += p[q];
+                    }
                 }
+                inv = 1.0f / sqrtf(tot / (float)K + a.eps);
             }
-            inv = 1.0f / sqrtf(tot / (float)K + a.eps);
+            inv_s[tid] = inv;
         }
-        inv_s[tid] = inv;
-    }
+    };
+    if (!WAIT) inv_rms();
     __syncthreads();
 
     auto mfma_slab = [&](int buf, const WFrag &f) {
@@ -451,6 +446,44 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
         }
     }
 
+    if (WAIT) {
+        if (w == 0) {       // all tagged sums of squares (eight per lane and round; the buffer is padded to 512 entries)
+            const int n_ent = a.batch * (K / 512);          // <= kSkWaitEntries
+            const uint64_t t0 = wall_clock64();
+            uint32_t it = 0;
+            bool ok;
+            for (;;) {
+                ok = true;
+                for (int e0 = 0; e0 < n_ent; e0 += 512) {
+                    const int e = e0 + lane * 8;
+                    if (e < n_ent) {
+                        u32x4 q0, q1, q2, q3;
+                        ll_issue(q0, a.wait_ll + e);
+                        ll_issue(q1, a.wait_ll + e + 2);
+                        ll_issue(q2, a.wait_ll + e + 4);
+                        ll_issue(q3, a.wait_ll + e + 6);
+                        ll_wait4(q0, q1, q2, q3);
+                        const unsigned t = a.wait_tag;
+                        ok = ok && (e + 0 >= n_ent || q0.y == t) && (e + 1 >= n_ent || q0.w == t) && (e + 2 >= n_ent || q1.y == t) &&
+                             (e + 3 >= n_ent || q1.w == t) && (e + 4 >= n_ent || q2.y == t) && (e + 5 >= n_ent || q2.w == t) &&
+                             (e + 6 >= n_ent || q3.y == t) && (e + 7 >= n_ent || q3.w == t);
+                        ssq_s[e + 0] = __uint_as_float(q0.x); ssq_s[e + 1] = __uint_as_float(q0.z);
+                        ssq_s[e + 2] = __uint_as_float(q1.x); ssq_s[e + 3] = __uint_as_float(q1.z);
+                        ssq_s[e + 4] = __uint_as_float(q2.x); ssq_s[e + 5] = __uint_as_float(q2.z);
+                        ssq_s[e + 6] = __uint_as_float(q3.x); ssq_s[e + 7] = __uint_as_float(q3.z);
+                    }
+                }
+                ok = __all(ok);
+                if (ok || it >= a.wait_iters || wall_clock64() - t0 >= a.wait_ticks) break;
+                __builtin_amdgcn_s_sleep(8);
+                ++it;
+            }
+            if (lane == 0 && !ok) atomicOr(a.wait_err, 2u);
+        }
+        __syncthreads();
+        inv_rms();
+        __syncthreads();
+    }
     // D fragment: lane holds rows 4g..4g+3 of batch column i
     float *part = a.part + (size_t)blockIdx.y * a.batch * a.N;
 #pragma unroll
