@@ -116,6 +116,93 @@ hipError_t launch_resid_sum(const float *res, const float *delta, int delta_spli
 
 // ------------------------------------------------------------------------------------ split-K skinny GEMM
 
+// What a projection that is launched into its communication window (k_gemm_sk<1, HOLD>, k_gemm_sk_i8<1, HOLD>, HOLD > 0)
+// is told besides its ordinary arguments.  While the window runs every workgroup walks the window's prefetch job, reads
+// and drops the slabs of its own range up to touch_w (rows of W) or touch_w2 (rows of W2) -- which leaves them in the
+// memory-side cache -- and requests the slabs it keeps on chip.  Then it waits: for the window's end word first (one word;
+// the tagged values would be too much to hammer on for a whole window), then until the tagged sums of squares of the
+// k_resid_sum<true> workgroups that write its K range carry `tag` (each is stored after its workgroup's share of the
+// operand has reached the memory side); only then does it touch the operand.  The waits are bounded: one that runs into
+// its bounds sets bit 1 of *err and the kernel goes on.
+struct SkWaitArgs {
+    const unsigned *win_done;
+    unsigned win_seq;
+    const uint2 *ll;          // tagged sums of squares [batch][K / 512], padded to a multiple of 512 entries
+    unsigned tag;
+    int touch_w, touch_w2;
+    uint32_t iters;
+    uint64_t ticks;
+    unsigned *err;
+};
+
+// The wait itself, run by one wave of the workgroup whose K range is slabs [s0, s1).
+__device__ __forceinline__ void sk_wait_for_operand(const SkWaitArgs &wt, int batch, int K, int s0, int s1, int lane)
+{
+    const uint64_t t0 = wall_clock64();
+    uint32_t it = 0;
+    {
+        unsigned v = __hip_atomic_load(wt.win_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        while ((int)(v - wt.win_seq) < 0 && it < wt.iters && wall_clock64() - t0 < wt.ticks) {
+            __builtin_amdgcn_s_sleep(8);
+            v = __hip_atomic_load(wt.win_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            ++it;
+        }
+    }
+    // The tags of the producer workgroups that write this K range (all batch rows): a few dozen entries, different lines
+    // for different splits.  (Every workgroup polling every entry made one 1-4 KiB region a hot spot.)
+    const int nblk = K / 512, blk0 = s0 >> 3, nbr = (((s1 << 6) - 1) >> 9) - blk0 + 1, cnt = batch * nbr;
+    bool ok;
+    for (;;) {
+        ok = true;
+        for (int idx = lane; idx < cnt; idx += 64) {
+            uint2 v;
+            ll_issue1(v, wt.ll + (idx / nbr) * nblk + blk0 + idx % nbr);
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(v) : : "memory");
+            ok = ok && v.y == wt.tag;
+        }
+        ok = __all(ok);
+        if (ok || it >= wt.iters || wall_clock64() - t0 >= wt.ticks) break;
+        __builtin_amdgcn_s_sleep(8);
+        ++it;
+    }
+    if (lane == 0 && !ok) atomicOr(wt.err, 2u);     // the operand may not be there: results invalid
+}
+
+// All tagged sums of squares into LDS (one wave; eight entries per lane and round), for the 1/rms factors of the epilogue.
+__device__ __forceinline__ void sk_read_sums(const SkWaitArgs &wt, int n_ent, int lane, float *ssq_s)
+{
+    const uint64_t t0 = wall_clock64();
+    uint32_t it = 0;
+    bool ok;
+    for (;;) {
+        ok = true;
+        for (int e0 = 0; e0 < n_ent; e0 += 512) {
+            const int e = e0 + lane * 8;
+            if (e < n_ent) {
+                u32x4 q0, q1, q2, q3;
+                ll_issue(q0, wt.ll + e);
+                ll_issue(q1, wt.ll + e + 2);
+                ll_issue(q2, wt.ll + e + 4);
+                ll_issue(q3, wt.ll + e + 6);
+                ll_wait4(q0, q1, q2, q3);
+                const unsigned t = wt.tag;
+                ok = ok && (e + 0 >= n_ent || q0.y == t) && (e + 1 >= n_ent || q0.w == t) && (e + 2 >= n_ent || q1.y == t) &&
+                     (e + 3 >= n_ent || q1.w == t) && (e + 4 >= n_ent || q2.y == t) && (e + 5 >= n_ent || q2.w == t) &&
+                     (e + 6 >= n_ent || q3.y == t) && (e + 7 >= n_ent || q3.w == t);
+                ssq_s[e + 0] = __uint_as_float(q0.x); ssq_s[e + 1] = __uint_as_float(q0.z);
+                ssq_s[e + 2] = __uint_as_float(q1.x); ssq_s[e + 3] = __uint_as_float(q1.z);
+                ssq_s[e + 4] = __uint_as_float(q2.x); ssq_s[e + 5] = __uint_as_float(q2.z);
+                ssq_s[e + 6] = __uint_as_float(q3.x); ssq_s[e + 7] = __uint_as_float(q3.z);
+            }
+        }
+        ok = __all(ok);
+        if (ok || it >= wt.iters || wall_clock64() - t0 >= wt.ticks) break;
+        __builtin_amdgcn_s_sleep(8);
+        ++it;
+    }
+    if (lane == 0 && !ok) atomicOr(wt.err, 2u);
+}
+
 // part[ks][b][r] = sum over the K-range of split ks of W[r][k] x[b][k], for batches of 17..64 (and any
 // smaller batch).  A workgroup of 4 waves owns 128 weight rows (2 MFMA row tiles per wave) and a range of
 // 64-element K slabs.  Per slab the activations of all batch entries (hi and lo bf16 planes) are brought
@@ -138,20 +225,7 @@ struct GemmSkArgs {
     const float *ssq;
     float eps;
     int tiled;                // weights in the tiled layout: a workgroup's 128 rows x 64 elements per slab are contiguous
-    // Launched ahead of its activations (k_gemm_sk<1, HOLD>, HOLD > 0).  While the window runs every workgroup walks the
-    // window's prefetch job, reads and drops the slabs of its own range up to touch_w (rows of W) or touch_w2 (rows of
-    // W2) -- which leaves them in the memory-side cache -- and requests the slabs it keeps on chip.  Then it waits: for the
-    // window's end word first, then until all batch * K / 512 tagged sums of squares of k_resid_sum<true> carry wait_tag
-    // (each is stored after its workgroup's share of xb has reached the memory side); only then does it touch xb.
-    // Bounds as in GemvArgs: a wait that runs into them sets bit 1 of *wait_err and the kernel goes on.
-    const unsigned *win_done;   // the window's end word and sequence number: polled first (one word; the tagged values are
-    unsigned win_seq;           //   up to 8 KiB per poll and workgroup, too much to hammer on for a whole window)
-    const uint2 *wait_ll;
-    unsigned wait_tag;
-    int touch_w, touch_w2;
-    uint32_t wait_iters;
-    uint64_t wait_ticks;
-    unsigned *wait_err;
+    SkWaitArgs wt;            // k_gemm_sk<1, HOLD>, HOLD > 0
 };
 
 // HOLD: 0 = the ordinary kernel; 1, 2 = the variant launched into a communication window, on another stream than the kernel
@@ -249,7 +323,7 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
         // this workgroup's own range beyond the ones kept on chip -- four slabs (16 loads per lane) in flight, results dropped.
         if (pj.n_regions || pj.kv_count) prefetch_walk(pj, blockIdx.y * gridDim.x + blockIdx.x, (uint64_t)gridDim.x * gridDim.y);
         {
-            const int t_end = min(s1, s0 + (row_base < a.split_row ? a.touch_w : a.touch_w2));
+            const int t_end = min(s1, s0 + (row_base < a.split_row ? a.wt.touch_w : a.wt.touch_w2));
             uint32_t sink = 0;
             for (int s = s0 + HS; s < t_end; s += 4) {
                 WFrag t[4];
@@ -289,37 +363,7 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
         if (s0 + q < s1) load_w(s0 + q, wq[q]);
     __shared__ float ssq_s[WAIT ? kSkWaitEntries : 1];
     if (WAIT) {     // the weights above travel, then sit on chip, while the window runs
-        if (w == 0) {           // one wave polls
-            const uint64_t t0 = wall_clock64();
-            uint32_t it = 0;
-            {
-                unsigned v = __hip_atomic_load(a.win_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                while ((int)(v - a.win_seq) < 0 && it < a.wait_iters && wall_clock64() - t0 < a.wait_ticks) {
-                    __builtin_amdgcn_s_sleep(8);
-                    v = __hip_atomic_load(a.win_done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    ++it;
-                }
-            }
-            // Then the tags of the producer workgroups that write this workgroup's K range (all batch rows): a few dozen
-            // entries, different lines for different splits.  (Every workgroup polling every entry made one 1-4 KiB
-            // region a hot spot: the flag was seen 4-5 us after the last producer had signalled.)
-            const int nblk = K / 512, blk0 = s0 >> 3, nbr = (((s1 << 6) - 1) >> 9) - blk0 + 1, cnt = a.batch * nbr;
-            bool ok;
-            for (;;) {
-                ok = true;
-                for (int idx = lane; idx < cnt; idx += 64) {
-                    uint2 v;
-                    ll_issue1(v, a.wait_ll + (idx / nbr) * nblk + blk0 + idx % nbr);
-                    asm volatile("s_waitcnt vmcnt(0)" : "+v"(v) : : "memory");
-                    ok = ok && v.y == a.wait_tag;
-                }
-                ok = __all(ok);
-                if (ok || it >= a.wait_iters || wall_clock64() - t0 >= a.wait_ticks) break;
-                __builtin_amdgcn_s_sleep(8);
-                ++it;
-            }
-            if (lane == 0 && !ok) atomicOr(a.wait_err, 2u);     // the activations may not be there: results invalid
-        }
+        if (w == 0) sk_wait_for_operand(a.wt, a.batch, K, s0, s1, lane);     // one wave polls
         __syncthreads();
     }
     // Activations.  Ordinary start: the first two slabs are requested, the first one goes to LDS.  After a wait the
@@ -447,39 +491,7 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
     }
 
     if (WAIT) {
-        if (w == 0) {       // all tagged sums of squares (eight per lane and round; the buffer is padded to 512 entries)
-            const int n_ent = a.batch * (K / 512);          // <= kSkWaitEntries
-            const uint64_t t0 = wall_clock64();
-            uint32_t it = 0;
-            bool ok;
-            for (;;) {
-                ok = true;
-                for (int e0 = 0; e0 < n_ent; e0 += 512) {
-                    const int e = e0 + lane * 8;
-                    if (e < n_ent) {
-                        u32x4 q0, q1, q2, q3;
-                        ll_issue(q0, a.wait_ll + e);
-                        ll_issue(q1, a.wait_ll + e + 2);
-                        ll_issue(q2, a.wait_ll + e + 4);
-                        ll_issue(q3, a.wait_ll + e + 6);
-                        ll_wait4(q0, q1, q2, q3);
-                        const unsigned t = a.wait_tag;
-                        ok = ok && (e + 0 >= n_ent || q0.y == t) && (e + 1 >= n_ent || q0.w == t) && (e + 2 >= n_ent || q1.y == t) &&
-                             (e + 3 >= n_ent || q1.w == t) && (e + 4 >= n_ent || q2.y == t) && (e + 5 >= n_ent || q2.w == t) &&
-                             (e + 6 >= n_ent || q3.y == t) && (e + 7 >= n_ent || q3.w == t);
-                        ssq_s[e + 0] = __uint_as_float(q0.x); ssq_s[e + 1] = __uint_as_float(q0.z);
-                        ssq_s[e + 2] = __uint_as_float(q1.x); ssq_s[e + 3] = __uint_as_float(q1.z);
-                        ssq_s[e + 4] = __uint_as_float(q2.x); ssq_s[e + 5] = __uint_as_float(q2.z);
-                        ssq_s[e + 6] = __uint_as_float(q3.x); ssq_s[e + 7] = __uint_as_float(q3.z);
-                    }
-                }
-                ok = __all(ok);
-                if (ok || it >= a.wait_iters || wall_clock64() - t0 >= a.wait_ticks) break;
-                __builtin_amdgcn_s_sleep(8);
-                ++it;
-            }
-            if (lane == 0 && !ok) atomicOr(a.wait_err, 2u);
-        }
+        if (w == 0) sk_read_sums(a.wt, a.batch * (K / 512), lane, ssq_s);       // <= kSkWaitEntries
         __syncthreads();
         inv_rms();
         __syncthreads();
@@ -802,14 +814,14 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
     a.slabs_per_block = (a.n_slabs + splits - 1) / splits;
     const dim3 grid((N + 127) / 128, splits);
     if (wait) {
-        a.win_done = wait->win_done; a.win_seq = wait->win_seq;
-        a.wait_ll = static_cast<const uint2 *>(wait->ssq_ll); a.wait_tag = wait->tag; a.wait_iters = wait->iters;
-        a.wait_ticks = wait->ticks; a.wait_err = wait->err;
+        a.wt.win_done = wait->win_done; a.wt.win_seq = wait->win_seq;
+        a.wt.ll = static_cast<const uint2 *>(wait->ssq_ll); a.wt.tag = wait->tag; a.wt.iters = wait->iters;
+        a.wt.ticks = wait->ticks; a.wt.err = wait->err;
         // planned share of each matrix, spread evenly over its workgroups: slabs of a workgroup's range that are either kept
         // on chip or read and dropped
         auto touch = [&](double share) { return (int)(share * a.slabs_per_block + 0.5); };
-        a.touch_w = touch(wait->share_w);
-        a.touch_w2 = touch(wait->share_w2);
+        a.wt.touch_w = touch(wait->share_w);
+        a.wt.touch_w2 = touch(wait->share_w2);
         const PrefetchJob pj = wait->job ? *wait->job : PrefetchJob{};
         if (sk_hold_level(a.slabs_per_block) == 2) PSV_LAUNCH((k_gemm_sk<1, 2>), grid, dim3(256), 0, s, a, pj);
         else PSV_LAUNCH((k_gemm_sk<1, 1>), grid, dim3(256), 0, s, a, pj);
