@@ -126,6 +126,12 @@ __device__ __forceinline__ float max32(float v)
 // magnitude of the block) / 127, which keeps 15-16 bits of the block's largest element.  Plane d1 is [rows][K]
 // bytes at `base`, plane d2 follows `plane` bytes later, the block scales [rows][K / 128] fp32 after both.
 // Called by the 32 consecutive lanes that hold one block, four elements each (k0 = first of the lane's four).
+// WT: every store written through to the memory side (sc0 sc1), for a producer whose consumer is already running.
+__device__ __forceinline__ void st_wt4(void *p, uint32_t v)
+{
+    asm volatile("global_store_dword %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
+}
+template <bool WT = false>
 __device__ __forceinline__ void store_digits4(uint8_t *base, size_t plane, int K, size_t row, int k0, float4 v)
 {
     const float amax = max32(fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
@@ -136,10 +142,16 @@ __device__ __forceinline__ void store_digits4(uint8_t *base, size_t plane, int K
     two_digits(v.z * inv, a1[2], a2[2]);
     two_digits(v.w * inv, a1[3], a2[3]);
     uint8_t *p = base + row * K + k0;
-    *reinterpret_cast<uint32_t *>(p) = pack_magic_bytes(a1[0], a1[1], a1[2], a1[3]);
-    *reinterpret_cast<uint32_t *>(p + plane) = pack_magic_bytes(a2[0], a2[1], a2[2], a2[3]);
-    if ((threadIdx.x & 31) == 0)
-        reinterpret_cast<float *>(base + 2 * plane)[row * (K / 128) + k0 / 128] = amax / 127.0f;
+    float *sc = reinterpret_cast<float *>(base + 2 * plane) + row * (K / 128) + k0 / 128;
+    if (WT) {
+        st_wt4(p, pack_magic_bytes(a1[0], a1[1], a1[2], a1[3]));
+        st_wt4(p + plane, pack_magic_bytes(a2[0], a2[1], a2[2], a2[3]));
+        if ((threadIdx.x & 31) == 0) st_wt4(sc, __float_as_uint(amax / 127.0f));
+    } else {
+        *reinterpret_cast<uint32_t *>(p) = pack_magic_bytes(a1[0], a1[1], a1[2], a1[3]);
+        *reinterpret_cast<uint32_t *>(p + plane) = pack_magic_bytes(a2[0], a2[1], a2[2], a2[3]);
+        if ((threadIdx.x & 31) == 0) *sc = amax / 127.0f;
+    }
 }
 
 // Maximum over the 64 lanes of a wave, returned in every lane (all lanes must be active).

@@ -18,8 +18,8 @@ namespace psv {
 // a whole row: it stores out_res * gain as hi/lo bf16 planes and the sum of squares of its 512 outputs in
 // ssq[batch][H / 512].  RMSNorm is linear in its 1/rms factor, so that projection runs on the unnormalised planes
 // and multiplies its result by 1/rms of the batch row, which it forms from ssq (k_gemm_sk).
-// SIGNAL: a projection launched ahead of this kernel is waiting for its outputs (k_gemm_sk<1, HOLD>, HOLD > 0).  Every output is
-// stored written through to the memory side; once a workgroup's stores are acknowledged, its sum of squares goes out as a
+// SIGNAL: a projection launched ahead of this kernel is waiting for its outputs (k_gemm_sk<1, HOLD> or k_gemm_sk_i8<1, HOLD>, HOLD > 0).  Every
+// output is stored written through to the memory side; once a workgroup's stores are acknowledged, its sum of squares goes out as a
 // tagged value {sum, tag} (ssq_ll, same index as ssq), and the waiting kernel proceeds when every entry carries the tag of
 // this launch.  No fence and no counter: a release fence makes every wave write back its XCD's L2 and a device-scope
 // counter serialises at the memory side -- measured 25-55 ns per workgroup either way, 7 us per layer at batch 8 and
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res
     if (!gain) return;
     const float4 xg = make_float4(v.x * bf16_lo(g.x), v.y * bf16_hi(g.x), v.z * bf16_lo(g.y), v.w * bf16_hi(g.y));
     if (digits) {   // operand of an int8 projection
-        store_digits4(reinterpret_cast<uint8_t *>(xg_bf16), plane_stride, H, (size_t)b, i, xg);
+        store_digits4<SIGNAL>(reinterpret_cast<uint8_t *>(xg_bf16), plane_stride, H, (size_t)b, i, xg);
     } else {
         uint32_t h0, h1, h2, h3, l0, l1, l2, l3;
         split_bf16(xg.x, h0, l0); split_bf16(xg.y, h1, l1); split_bf16(xg.z, h2, l2); split_bf16(xg.w, h3, l3);
@@ -103,10 +103,10 @@ hipError_t launch_resid_sum(const float *res, const float *delta, int delta_spli
                             const uint16_t *gain, uint16_t *xg_bf16, size_t plane_stride, bool digits, float *ssq,
                             const SkWait *signal, hipStream_t s)
 {
-    if (signal && (!gain || digits || !signal->ssq_ll)) return hipErrorInvalidValue;   // only the form that prepares a bf16 operand signals
+    if (signal && (!gain || !signal->ssq_ll)) return hipErrorInvalidValue;   // only the form that prepares an operand signals
     if (signal)
         PSV_LAUNCH(k_resid_sum<true>, dim3(H / 512, batch), dim3(128), 0, s, res, delta, delta_splits, (size_t)batch * H, H,
-                   out_res, gain, xg_bf16, plane_stride, 0, ssq, static_cast<uint2 *>(signal->ssq_ll), signal->tag);
+                   out_res, gain, xg_bf16, plane_stride, digits ? 1 : 0, ssq, static_cast<uint2 *>(signal->ssq_ll), signal->tag);
     else
         PSV_LAUNCH(k_resid_sum<false>, dim3(H / 512, batch), dim3(128), 0, s, res, delta, delta_splits, (size_t)batch * H, H,
                    out_res, gain, xg_bf16, plane_stride, digits ? 1 : 0, ssq, static_cast<uint2 *>(nullptr), 0u);
@@ -532,15 +532,25 @@ struct GemmI8Args {
     const float *ssq;              // see GemmSkArgs
     float eps;
     int tiled;                     // see GemmSkArgs; the unit of (row tile, slab) is 8 KiB: [wave][row group][lane][16 codes]
+    SkWaitArgs wt;                 // k_gemm_sk_i8<1, HOLD>, HOLD > 0
 };
 
-template <int NB>
-__global__ __launch_bounds__(256) void k_gemm_sk_i8(GemmI8Args a)
+constexpr int kSkI8Blocks = 66;    // 128-element blocks a workgroup's K range can touch (ranges of up to 128 slabs)
+
+// HOLD, pj: as for k_gemm_sk.  The waiting variant keeps the 8 slabs of its register ring, or those and 4 more in LDS
+// (8 KiB each), on chip.  The operand's block scales share cache lines between producer workgroups of different XCDs,
+// so the waiting variant reads those of its K range with device-coherent loads, once, after the wait.
+template <int NB, int HOLD>
+__global__ __launch_bounds__(256) void k_gemm_sk_i8(GemmI8Args a, PrefetchJob pj)
 {
+    constexpr bool WAIT = HOLD > 0;
+    static_assert(!WAIT || NB == 1, "the waiting variant is built for one batch tile");
     constexpr int PF = 8;                          // slabs of weight codes in flight per wave (2 x 16 bytes each)
     __shared__ uint4 xs[2][NB * 2][64];            // [buffer][batch tile * 2 + digit][lane]
     __shared__ float bs[2][NB * 16];               // block scale of each batch row for the buffered slab
     __shared__ float inv_s[NB * 16];
+    __shared__ float bsl[WAIT ? 16 * kSkI8Blocks : 1];     // waiting variant: block scales of this K range, [batch row][block]
+    __shared__ float ssq_s[WAIT ? kSkWaitEntries : 1];
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
     const int row_base = blockIdx.x * 128 + w * 32;
     const int s0 = blockIdx.y * a.slabs_per_block, s1 = min(s0 + a.slabs_per_block, a.n_slabs);
@@ -582,7 +592,8 @@ __global__ __launch_bounds__(256) void k_gemm_sk_i8(GemmI8Args a)
                                                                        (size_t)(n * 16 + row) * K + (size_t)s * 64 + seg * 16)
                                    : zero16();
         }
-        sr.sc = tid < NB * 16 ? bscale[(size_t)tid * nblk128 + (s >> 1)] : 0.f;
+        if (WAIT) sr.sc = tid < a.batch ? bsl[tid * kSkI8Blocks + (s >> 1) - (s0 >> 1)] : 0.f;
+        else sr.sc = tid < NB * 16 ? bscale[(size_t)tid * nblk128 + (s >> 1)] : 0.f;
     };
     auto store_slab = [&](int buf, const SlabRegs &sr) {
 #pragma unroll
@@ -603,75 +614,168 @@ __global__ __launch_bounds__(256) void k_gemm_sk_i8(GemmI8Args a)
             d2[mt][n] = i32x4{0, 0, 0, 0};
         }
 
+    // Waiting variant: see k_gemm_sk.  The ring's PF slabs and the LH after them stay on chip.
+    constexpr int LH = HOLD == 2 ? 4 : 0;
+    constexpr int HS = PF + LH;
+    __shared__ uint4 wl[LH ? LH * 2 * 256 : 1];
+    const bool held = WAIT && s1 - s0 >= HS;
+    if (WAIT && (pj.n_regions || pj.kv_count))
+        prefetch_walk(pj, blockIdx.y * gridDim.x + blockIdx.x, (uint64_t)gridDim.x * gridDim.y);
+    if (held) {
+        {   // this workgroup's own slabs beyond the ones kept on chip: eight slabs (16 loads per lane) in flight, dropped
+            const int t_end = min(s1, s0 + (row_base < a.split_row ? a.wt.touch_w : a.wt.touch_w2));
+            uint32_t sink = 0;
+            for (int s = s0 + HS; s < t_end; s += 8) {
+                WFrag t[8];
+#pragma unroll
+                for (int q = 0; q < 8; ++q) {
+                    if (s + q < t_end) load_w(s + q, t[q]);
+                    else t[q].c[0] = t[q].c[1] = zero16();
+                }
+#pragma unroll
+                for (int q = 0; q < 8; ++q) sink ^= xor4(t[q].c[0]) ^ xor4(t[q].c[1]);
+            }
+            asm volatile("" ::"v"(sink));
+        }
+#pragma unroll
+        for (int e = 0; e < LH; e += 2) {
+            WFrag t[2];
+            load_w(s0 + PF + e, t[0]);
+            load_w(s0 + PF + e + 1, t[1]);
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                uint4 *d = wl + ((e + j) * 2) * 256 + tid;
+                d[0] = t[j].c[0]; d[256] = t[j].c[1];
+            }
+        }
+    }
     WFrag wq[PF];
 #pragma unroll
     for (int q = 0; q < PF; ++q)
         if (s0 + q < s1) load_w(s0 + q, wq[q]);
+    if (WAIT) {
+        if (w == 0) sk_wait_for_operand(a.wt, a.batch, K, s0, s1, lane);     // one wave polls
+        __syncthreads();
+        const int b0 = s0 >> 1, nbk = ((s1 - 1) >> 1) - b0 + 1;             // <= kSkI8Blocks
+        for (int idx = tid; idx < a.batch * nbk; idx += 256) {
+            float v;
+            asm volatile("global_load_dword %0, %1, off sc0 sc1" : "=v"(v) : "v"(bscale + (size_t)(idx / nbk) * nblk128 + b0 + idx % nbk) : "memory");
+            asm volatile("s_waitcnt vmcnt(0)" : "+v"(v) : : "memory");
+            bsl[(idx / nbk) * kSkI8Blocks + idx % nbk] = v;
+        }
+        __syncthreads();
+    }
     SlabRegs xr[2];
-    if (s0 < s1) {
+    constexpr int XG = WAIT ? 6 : 1;        // activation slabs requested ahead in the held part (see k_gemm_sk)
+    SlabRegs xa[XG];
+    if (held) {
+#pragma unroll
+        for (int h = 0; h < XG; ++h) load_slab(s0 + h, xa[h]);
+        if (s0 + HS < s1) load_slab(s0 + HS, xr[0]);
+        if (s0 + HS + 1 < s1) load_slab(s0 + HS + 1, xr[1]);
+    } else if (s0 < s1) {
         load_slab(s0, xr[0]);
         if (s0 + 1 < s1) load_slab(s0 + 1, xr[1]);
         store_slab(0, xr[0]);
     }
-    if (tid < NB * 16) {   // 1/rms of every batch row (see k_gemm_sk)
-        float inv = 1.0f;
-        if (a.ssq) {
-            float tot = 0.f;
-            const int nblk = K / 512;
-            if (tid < a.batch) {
-                const float *p = a.ssq + (size_t)tid * nblk;
-                if ((nblk & 3) == 0) {
-                    float4 t[8];
+    auto inv_rms = [&]() {      // 1/rms of every batch row (see k_gemm_sk)
+        if (tid < NB * 16) {
+            float inv = 1.0f;
+            if (a.ssq) {
+                float tot = 0.f;
+                const int nblk = K / 512;
+                if (tid < a.batch) {
+                    const float *p = a.ssq + (size_t)tid * nblk;
+                    if (WAIT) {
+                        for (int q = 0; q < nblk; ++q) tot += ssq_s[tid * nblk + q];
+                    } else if ((nblk & 3) == 0) {
+                        float4 t[8];
 #pragma unroll
-                    for (int q = 0; q < 8; ++q)
-                        t[q] = 4 * q < nblk ? *reinterpret_cast<const float4 *>(p + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
+                        for (int q = 0; q < 8; ++q)
+                            t[q] = 4 * q < nblk ? *reinterpret_cast<const float4 *>(p + 4 * q) : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-                    for (int q = 0; q < 8; ++q) tot = (((tot + t[q].x) + t[q].y) + t[q].z) + t[q].w;
-                } else {
-                    for (int q = 0; q < nblk; ++q) tot += p[q];
+                        for (int q = 0; q < 8; ++q) tot = (((tot + t[q].x) + t[q].y) + t[q].z) + t[q].w;
+                    } else {
+                        for (int q = 0; q < nblk; ++q) tot += p[q];
+                    }
                 }
+                inv = 1.0f / sqrtf(tot / (float)K + a.eps);
             }
-            inv = 1.0f / sqrtf(tot / (float)K + a.eps);
+            inv_s[tid] = inv;
         }
-        inv_s[tid] = inv;
-    }
+    };
+    if (!WAIT) inv_rms();
     __syncthreads();
 
-    for (int sb = s0; sb < s1; sb += PF) {
+    // one slab: both digit planes against the weight codes; at the end of a 128-element block (or of the range) the pair
+    // of exact sums is folded into the fp32 accumulator
+    auto mfma_slab = [&](int s, int buf, const WFrag &f) {
+        const bool fold = (s & 1) || s + 1 == s1;
+#pragma unroll
+        for (int n = 0; n < NB; ++n) {
+            const i32x4 x1 = __builtin_bit_cast(i32x4, xs[buf][n * 2 + 0][lane]);
+            const i32x4 x2 = __builtin_bit_cast(i32x4, xs[buf][n * 2 + 1][lane]);
+#pragma unroll
+            for (int mt = 0; mt < 2; ++mt) {
+                const i32x4 wc = __builtin_bit_cast(i32x4, f.c[mt]);
+                d1[mt][n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wc, x1, d1[mt][n], 0, 0, 0);
+                d2[mt][n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wc, x2, d2[mt][n], 0, 0, 0);
+            }
+            if (fold) {
+                const float sc = bs[buf][n * 16 + i] * (1.0f / 254.0f);
+#pragma unroll
+                for (int mt = 0; mt < 2; ++mt) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        acc[mt][n][j] = fmaf(sc, (float)(d1[mt][n][j] * 254 + d2[mt][n][j]), acc[mt][n][j]);
+                    d1[mt][n] = i32x4{0, 0, 0, 0};
+                    d2[mt][n] = i32x4{0, 0, 0, 0};
+                }
+            }
+        }
+    };
+
+    int sb0 = s0;
+    if (held) {     // the slabs held on chip, in the order of the range; ring slots are refilled with the slab HS further on
+#pragma unroll
+        for (int h = 0; h < HS; ++h) {
+            const int buf = h & 1;
+            store_slab(buf, xa[h % XG]);
+            if (h + XG < HS) load_slab(s0 + h + XG, xa[h % XG]);
+            __syncthreads();
+            if (h < PF) {
+                mfma_slab(s0 + h, buf, wq[h]);
+                load_w(min(s0 + h + HS, s1 - 1), wq[h]);
+            } else {
+                WFrag f;
+                const uint4 *d = wl + ((h - PF) * 2) * 256 + tid;
+                f.c[0] = d[0]; f.c[1] = d[256];
+                mfma_slab(s0 + h, buf, f);
+            }
+        }
+        sb0 = s0 + HS;
+        if (sb0 < s1) store_slab(0, xr[0]);     // HS is even: the main loop's first slab goes to buffer 0
+        __syncthreads();
+    }
+    for (int sb = sb0; sb < s1; sb += PF) {
 #pragma unroll
         for (int q = 0; q < PF; ++q) {
             const int s = sb + q;
             if (s < s1) {                       // uniform over the workgroup
-                const int buf = q & 1;          // (s - s0) & 1, because PF is even
+                const int buf = q & 1;          // (s - s0) & 1, because PF and the number of slabs held are even
                 if (s + 2 < s1) load_slab(s + 2, xr[q & 1]);
-                const bool fold = (s & 1) || s + 1 == s1;   // end of a 128-element block, or of this workgroup's range
-#pragma unroll
-                for (int n = 0; n < NB; ++n) {
-                    const i32x4 x1 = __builtin_bit_cast(i32x4, xs[buf][n * 2 + 0][lane]);
-                    const i32x4 x2 = __builtin_bit_cast(i32x4, xs[buf][n * 2 + 1][lane]);
-#pragma unroll
-                    for (int mt = 0; mt < 2; ++mt) {
-                        const i32x4 wc = __builtin_bit_cast(i32x4, wq[q].c[mt]);
-                        d1[mt][n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wc, x1, d1[mt][n], 0, 0, 0);
-                        d2[mt][n] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wc, x2, d2[mt][n], 0, 0, 0);
-                    }
-                    if (fold) {
-                        const float sc = bs[buf][n * 16 + i] * (1.0f / 254.0f);
-#pragma unroll
-                        for (int mt = 0; mt < 2; ++mt) {
-#pragma unroll
-                            for (int j = 0; j < 4; ++j)
-                                acc[mt][n][j] = fmaf(sc, (float)(d1[mt][n][j] * 254 + d2[mt][n][j]), acc[mt][n][j]);
-                            d1[mt][n] = i32x4{0, 0, 0, 0};
-                            d2[mt][n] = i32x4{0, 0, 0, 0};
-                        }
-                    }
-                }
+                mfma_slab(s, buf, wq[q]);
                 if (s + PF < s1) load_w(s + PF, wq[q]);
                 if (s + 1 < s1) store_slab(buf ^ 1, xr[(q + 1) & 1]);
                 __syncthreads();
             }
         }
+    }
+    if (WAIT) {
+        if (w == 0) sk_read_sums(a.wt, a.batch * (K / 512), lane, ssq_s);       // <= kSkWaitEntries
+        __syncthreads();
+        inv_rms();
+        __syncthreads();
     }
 
     // D fragment: lane holds rows 4g..4g+3 of batch column i
@@ -726,11 +830,12 @@ bool gemm_sk_supported(int batch, int N, int K)
 // Which waiting variant a range of `slabs_per_block` slabs takes: the one that keeps 12 slabs on chip if the range has them.
 static int sk_hold_level(int slabs_per_block) { return slabs_per_block >= 12 ? 2 : 1; }
 
-// Resources of the waiting variants and of the kernel they wait for, asked from the runtime once.
+// Resources of the waiting variants ([bf16 | int8 weights][hold level - 1]) and of the kernel they wait for, asked from
+// the runtime once.
 struct SkWaitRes {
-    int occ[2];          // resident workgroups per compute unit of k_gemm_sk<1, 1> and <1, 2>
-    int regs[2];         // registers per lane (vector + accumulation), rounded up to the allocation unit
-    int lds[2];          // static LDS bytes per workgroup
+    int occ[2][2];       // resident workgroups per compute unit
+    int regs[2][2];      // registers per lane (vector + accumulation), rounded up to the allocation unit
+    int lds[2][2];       // static LDS bytes per workgroup
     int regs_signal;     // k_resid_sum<true>
     bool ok;
 };
@@ -738,19 +843,21 @@ static const SkWaitRes &sk_wait_res()
 {
     static SkWaitRes r = [] {
         SkWaitRes q{};
-        const void *fn[2] = {reinterpret_cast<const void *>(k_gemm_sk<1, 1>), reinterpret_cast<const void *>(k_gemm_sk<1, 2>)};
         q.ok = true;
-        for (int i = 0; i < 2; ++i) {
+        auto ask = [&](int kind, int lv, auto kernel) {
             hipFuncAttributes at{};
             int n = 0;
-            const hipError_t e1 = i == 0 ? hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_gemm_sk<1, 1>, 256, 0)
-                                         : hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_gemm_sk<1, 2>, 256, 0);
-            const hipError_t e2 = hipFuncGetAttributes(&at, fn[i]);
+            const hipError_t e1 = hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, kernel, 256, 0);
+            const hipError_t e2 = hipFuncGetAttributes(&at, reinterpret_cast<const void *>(kernel));
             q.ok = q.ok && e1 == hipSuccess && e2 == hipSuccess && n > 0;
-            q.occ[i] = n;
-            q.regs[i] = (at.numRegs + 7) / 8 * 8;
-            q.lds[i] = (int)at.sharedSizeBytes;
-        }
+            q.occ[kind][lv] = n;
+            q.regs[kind][lv] = (at.numRegs + 7) / 8 * 8;
+            q.lds[kind][lv] = (int)at.sharedSizeBytes;
+        };
+        ask(0, 0, k_gemm_sk<1, 1>);
+        ask(0, 1, k_gemm_sk<1, 2>);
+        ask(1, 0, k_gemm_sk_i8<1, 1>);
+        ask(1, 1, k_gemm_sk_i8<1, 2>);
         hipFuncAttributes at{};
         q.ok = q.ok && hipFuncGetAttributes(&at, reinterpret_cast<const void *>(k_resid_sum<true>)) == hipSuccess;
         q.regs_signal = (at.numRegs + 7) / 8 * 8;
@@ -763,20 +870,20 @@ static const SkWaitRes &sk_wait_res()
 // the compute units until k_resid_sum has run, so all of them must be resident at once and leave room for that kernel:
 // either a quarter of the compute units keep a free workgroup slot of this kernel's size, or a wave of k_resid_sum fits
 // beside a full house (512 registers per lane and SIMD, with 16 to spare; 160 KiB of LDS, with 4 KiB to spare).
-// bf16 weights only.
 bool gemm_sk_can_wait(int batch, int N, int K, bool w8, int cus)
 {
-    if (w8 || !gemm_sk_supported(batch, N, K) || K % 512 || (long long)batch * (K / 512) > kSkWaitEntries) return false;
-    if (batch > kSkWaitMaxBatch) return false;         // one batch tile: the only instantiations of the waiting kernel
+    if (!gemm_sk_supported(batch, N, K) || K % 512 || (long long)batch * (K / 512) > kSkWaitEntries) return false;
+    if (batch > kSkWaitMaxBatch) return false;         // one batch tile: the only instantiations of the waiting kernels
     const SkWaitRes &r = sk_wait_res();
     if (!r.ok) return false;
-    const int splits = gemm_sk_splits(batch, N, K, false);
-    const int lv = sk_hold_level((K / 64 + splits - 1) / splits) - 1;
+    const int splits = gemm_sk_splits(batch, N, K, w8);
+    const int kind = w8 ? 1 : 0, lv = sk_hold_level((K / 64 + splits - 1) / splits) - 1;
     const long long grid = (long long)((N + 127) / 128) * splits;
     // ... and it is the window's prefetch kernel as well, which needs at least 128 workgroups to reach its rate
-    if (grid < 128 || grid > (long long)r.occ[lv] * cus) return false;
-    const bool free_slots = grid + cus / 4 <= (long long)r.occ[lv] * cus;
-    const bool beside = 512 - r.occ[lv] * r.regs[lv] >= r.regs_signal + 16 && 163840 - r.occ[lv] * r.lds[lv] >= 4096;
+    if (grid < 128 || grid > (long long)r.occ[kind][lv] * cus) return false;
+    const bool free_slots = grid + cus / 4 <= (long long)r.occ[kind][lv] * cus;
+    const bool beside = 512 - r.occ[kind][lv] * r.regs[kind][lv] >= r.regs_signal + 16 &&
+                        163840 - r.occ[kind][lv] * r.lds[kind][lv] >= 4096;
     return free_slots || beside;
 }
 
@@ -784,7 +891,16 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
                           int batch, int N, int K, const SkWait *wait, hipStream_t s)
 {
     const int nb = (batch + 15) / 16;
-    if (wait && (W.scale || !ssq || !wait->ssq_ll || !wait->win_done || batch > kSkWaitMaxBatch || K % 512 || (long long)batch * (K / 512) > kSkWaitEntries)) return hipErrorInvalidValue;
+    // planned share of each matrix, spread evenly over its workgroups: slabs of a workgroup's range that are either kept
+    // on chip or read and dropped
+    auto fill_wait = [&](SkWaitArgs &wt, int slabs_per_block) {
+        wt.win_done = wait->win_done; wt.win_seq = wait->win_seq;
+        wt.ll = static_cast<const uint2 *>(wait->ssq_ll); wt.tag = wait->tag; wt.iters = wait->iters;
+        wt.ticks = wait->ticks; wt.err = wait->err;
+        wt.touch_w = (int)(wait->share_w * slabs_per_block + 0.5);
+        wt.touch_w2 = (int)(wait->share_w2 * slabs_per_block + 0.5);
+    };
+    if (wait && (!ssq || !wait->ssq_ll || !wait->win_done || batch > kSkWaitMaxBatch || K % 512 || (long long)batch * (K / 512) > kSkWaitEntries)) return hipErrorInvalidValue;
     if (W.scale) {   // int8 weights: xb holds digit planes (bytes), see k_gemm_sk_i8
         GemmI8Args q{};
         q.W = static_cast<const int8_t *>(W.w); q.W2 = static_cast<const int8_t *>(W2.w ? W2.w : W.w);
@@ -795,11 +911,18 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
         const int splits = gemm_sk_splits(batch, N, K, true);
         q.slabs_per_block = (q.n_slabs + splits - 1) / splits;
         const dim3 grid((N + 127) / 128, splits);
+        if (wait) {
+            fill_wait(q.wt, q.slabs_per_block);
+            const PrefetchJob pj = wait->job ? *wait->job : PrefetchJob{};
+            if (sk_hold_level(q.slabs_per_block) == 2) PSV_LAUNCH((k_gemm_sk_i8<1, 2>), grid, dim3(256), 0, s, q, pj);
+            else PSV_LAUNCH((k_gemm_sk_i8<1, 1>), grid, dim3(256), 0, s, q, pj);
+            return hipGetLastError();
+        }
         switch (nb) {
-        case 1: PSV_LAUNCH(k_gemm_sk_i8<1>, grid, dim3(256), 0, s, q); break;
-        case 2: PSV_LAUNCH(k_gemm_sk_i8<2>, grid, dim3(256), 0, s, q); break;
-        case 3: PSV_LAUNCH(k_gemm_sk_i8<3>, grid, dim3(256), 0, s, q); break;
-        case 4: PSV_LAUNCH(k_gemm_sk_i8<4>, grid, dim3(256), 0, s, q); break;
+        case 1: PSV_LAUNCH((k_gemm_sk_i8<1, 0>), grid, dim3(256), 0, s, q, PrefetchJob{}); break;
+        case 2: PSV_LAUNCH((k_gemm_sk_i8<2, 0>), grid, dim3(256), 0, s, q, PrefetchJob{}); break;
+        case 3: PSV_LAUNCH((k_gemm_sk_i8<3, 0>), grid, dim3(256), 0, s, q, PrefetchJob{}); break;
+        case 4: PSV_LAUNCH((k_gemm_sk_i8<4, 0>), grid, dim3(256), 0, s, q, PrefetchJob{}); break;
         default: return hipErrorInvalidValue;
         }
         return hipGetLastError();
@@ -814,14 +937,7 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
     a.slabs_per_block = (a.n_slabs + splits - 1) / splits;
     const dim3 grid((N + 127) / 128, splits);
     if (wait) {
-        a.wt.win_done = wait->win_done; a.wt.win_seq = wait->win_seq;
-        a.wt.ll = static_cast<const uint2 *>(wait->ssq_ll); a.wt.tag = wait->tag; a.wt.iters = wait->iters;
-        a.wt.ticks = wait->ticks; a.wt.err = wait->err;
-        // planned share of each matrix, spread evenly over its workgroups: slabs of a workgroup's range that are either kept
-        // on chip or read and dropped
-        auto touch = [&](double share) { return (int)(share * a.slabs_per_block + 0.5); };
-        a.wt.touch_w = touch(wait->share_w);
-        a.wt.touch_w2 = touch(wait->share_w2);
+        fill_wait(a.wt, a.slabs_per_block);
         const PrefetchJob pj = wait->job ? *wait->job : PrefetchJob{};
         if (sk_hold_level(a.slabs_per_block) == 2) PSV_LAUNCH((k_gemm_sk<1, 2>), grid, dim3(256), 0, s, a, pj);
         else PSV_LAUNCH((k_gemm_sk<1, 1>), grid, dim3(256), 0, s, a, pj);

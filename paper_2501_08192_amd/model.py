@@ -98,18 +98,19 @@ def sk_splits(batch, n_rows, k, weight_bytes=2.0):
 
 def mm_hold(batch, hidden, ffn, weight_format="bf16", cus=256):
     """Fraction of the gate/up weights that the GEMM launched into its window keeps on chip (12 slabs of each workgroup's
-    range if it has that many, else 6), or 0.0 where the library does not launch it that way: batch above 16, int8
-    weights, fewer than 128 workgroups or more than stay resident beside the kernel it waits for."""
-    if weight_format != "bf16" or not (1 <= batch <= 16) or hidden % 512 or batch * (hidden // 512) > 1024:
+    range if it has that many, else 6 -- 8 with int8 weights), or 0.0 where the library does not launch it that way:
+    batch above 16, fewer than 128 workgroups or more than stay resident beside the kernel it waits for."""
+    if not (1 <= batch <= 16) or hidden % 512 or batch * (hidden // 512) > 1024:
         return 0.0
+    w8 = weight_format == "int8"
     n_rows = 2 * ffn
-    splits = sk_splits(batch, n_rows, hidden)
+    splits = sk_splits(batch, n_rows, hidden, 1.0 if w8 else 2.0)
     spb = (hidden // 64 + splits - 1) // splits
     grid = (n_rows + 127) // 128 * splits
     if spb >= 12:
-        ok, held = 128 <= grid <= 2 * cus, 12
+        ok, held = 128 <= grid <= (3 if w8 else 2) * cus, 12
     else:
-        ok, held = grid >= 128 and grid + cus // 4 <= 3 * cus, 6
+        ok, held = grid >= 128 and grid + cus // 4 <= 3 * cus, 8 if w8 else 6
     return min(1.0, held / spb) if ok else 0.0
 
 

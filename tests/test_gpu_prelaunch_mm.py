@@ -1,4 +1,4 @@
-"""GPU tests of the pre-launched gate/up projection on the matrix-core path (policy.prelaunch at batch 3..16, bf16 weights):
+"""GPU tests of the pre-launched gate/up projection on the matrix-core path (policy.prelaunch at batch 3..16):
 the split-K GEMM is launched into the window after the attention block, keeps its first weight slabs on chip, walks the
 window's prefetch job and waits for the tagged sums of squares of the residual kernel that follows the window on the other
 stream.  Through the C ABI against the CPU oracle (|gpu - ref| <= 2e-2 + 1e-2*|ref|), bit-identical to prefetch off under
@@ -70,13 +70,32 @@ def test_prelaunched_gate_up_gemm_matches_oracle_and_prefetch_off(case):
                 assert torch.equal(a, b)
 
 
-def test_int8_weights_are_never_launched_that_way():
-    w = W("w8", 2, 8192, 8, 1, 3584, 8, 64, layout="tiled", fmts=("int8", "bf16"))
-    with Session(w, seed=98) as s:
+# int8 weights: the operand is a pair of digit planes with block scales; the waiting int8 GEMM keeps 8 or 12 slabs on chip
+I8_CASES = [
+    ("w8_wide_b8", 2, 8192, 8, 1, 3584, 8, 200, False, "tiled", ("int8", "bf16"), 2),
+    ("w8_wide_b16_row", 2, 8192, 8, 1, 3584, 16, 90, True, "row", ("int8", "bf16"), 2),
+    ("w8_b3_odd", 3, 4096, 4, 1, 7168, 3, 60, False, "row", ("int8", "bf16"), 2),
+    ("w8_short_range", 2, 1024, 8, 2, 8192, 8, 70, False, "tiled", ("int8", "int8"), 2),
+]
+
+
+@pytest.mark.parametrize("case", I8_CASES, ids=[c[0] for c in I8_CASES])
+def test_prelaunched_int8_gate_up_gemm_matches_oracle_and_prefetch_off(case):
+    name, L, H, nq, nkv, F, B, T, paged, layout, fmts, want_pre = case
+    w = W(name, L, H, nq, nkv, F, B, T, paged=paged, layout=layout, fmts=fmts)
+    with Session(w, seed=101) as s:
+        ref = oracle_out(s, w)
         off = s.run().clone()
-        s.set_policy(default_policy(w, budget_bytes=1 << 40))
-        assert torch.equal(s.run(), off)
-        assert psv.psv_debug_last_step_prelaunches(s.ctx) == 0
+        bf.assert_close(off.cpu().numpy(), ref, name)
+        for pol, pre in ((default_policy(w, budget_bytes=1 << 40), want_pre),
+                         (default_policy(w, budget_bytes=max(1 << 20, w.weight_bytes_per_layer // 4)), want_pre),
+                         (default_policy(w, budget_bytes=1 << 40, prelaunch=0), 0)):
+            s.set_policy(pol)
+            for rep in range(3):
+                s.step()
+            s.sync()
+            assert torch.equal(s.x_out, off), "%s: a policy changes the result" % name
+            assert psv.psv_debug_last_step_prelaunches(s.ctx) == pre, name
 
 
 def test_gemm_that_gives_up_waiting_is_reported_and_the_context_survives():
