@@ -159,7 +159,7 @@ int gemm_sk_splits(int batch, int N, int K, bool w8);
 bool gemm_sk_supported(int batch, int N, int K);
 // ssq != null (K % 512 == 0): x_bf16 holds x * gain without the 1/rms factor of its RMSNorm and ssq the partial
 // sums of squares [batch][K / 512] written by launch_resid_sum; the result is multiplied by 1/rms of its batch row.
-// wait != null (bf16 weights, ssq != null): launched into a communication window ahead of its activations, on another
+// wait != null (ssq != null, one batch tile): launched into a communication window ahead of its activations, on another
 // stream than the launch_resid_sum that produces them, which is given the same SkWait as its signal.
 constexpr int kSkWaitMaxBatch = 16;      // measured: at batch 32 and 64 the producer's write-through stores and the reload of the
                                          // activations cost what the held weights save
@@ -186,7 +186,7 @@ bool gemm_sk_can_wait(int batch, int N, int K, bool w8, int cus);
 hipError_t launch_resid_sum(const float *res, const float *delta, int delta_splits, int batch, int H, float *out_res,
                             const uint16_t *gain, uint16_t *xg_bf16, size_t plane_stride, bool digits, float *ssq,
                             const SkWait *signal, hipStream_t s);
-// signal != null (gain != null, bf16 planes): every output is written through to the memory side and each workgroup's
+// signal != null (gain != null): every output is written through to the memory side and each workgroup's
 // sum of squares is published as a tagged value in signal->ssq_ll once its other stores are acknowledged.
 // out = sum of the splits; swiglu: N = gate | up columns, out = silu(gate) * up of width N/2.  out_bf16
 // (optional) receives hi/lo planes.
