@@ -267,7 +267,7 @@ bool can_prelaunch(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t l
         if (window != 0) return false;
         const psv_model_desc &d = c->d;
         const int H = (int)d.hidden, N = window == 0 ? 2 * (int)d.ffn : (int)(d.n_q_heads + 2 * d.n_kv_heads) * 128;
-        if (!gemm_sk_can_wait(batch, N, H, d.weight_format == PSV_FMT_INT8, c->cus)) return false;
+        if (!gemm_sk_can_wait(batch, N, H, d.weight_format == PSV_FMT_INT8, d.weight_layout == PSV_W_TILED, c->cus)) return false;
     }
     for (const psv_plan_entry &e : c->plan)
         if (e.layer == layer && e.window == window && e.target_op == first_op && (vec ? e.bytes == e.mem_size : e.bytes > 0))
@@ -453,7 +453,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
     c->step_launches = 0;
     c->step_layers = le - lb;
     auto u16 = [](const void *p) { return static_cast<const uint16_t *>(p); };
-    const bool w8 = d.weight_format == PSV_FMT_INT8;
+    const bool w8 = d.weight_format == PSV_FMT_INT8, tiled = d.weight_layout == PSV_W_TILED;
     const size_t plane_h = (size_t)((B + 15) / 16 * 16) * H;   // hi -> lo plane distance of the bf16 activations
 
     // Batch 1 (and batch 2 on 8B-sized matrices) runs every projection on the vector ALU with the normalisation
@@ -566,7 +566,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_gemm_sk(Wqkv, Mat{}, 0, h1b, ssq, d.rms_eps, part, B, QR, H, wait_qkv ? &skw : nullptr, s));
             wait_qkv = false;
             ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H, w8), B, QR, false, qkv, nullptr, false, s));
+            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, QR, H, w8, tiled), B, QR, false, qkv, nullptr, false, s));
         }
 
         if (!seg_attn) {
@@ -591,7 +591,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             if (!gemm_sk_supported(B, H, QD)) return PSV_ERR_UNSUPPORTED;
             HIP_TRY(launch_gemm_sk(Wo, Mat{}, 0, attnb, nullptr, 0.f, part, B, H, QD, nullptr, s));
             attn_delta = part;
-            attn_splits = gemm_sk_splits(B, H, QD, w8);
+            attn_splits = gemm_sk_splits(B, H, QD, w8, tiled);
         }
 
         {
@@ -624,7 +624,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             HIP_TRY(launch_gemm_sk(Wg, Wu, F, h2b, ssq, d.rms_eps, part, B, 2 * F, H, wait_gate ? &skw : nullptr, s));
             wait_gate = false;
             ST_TRY(prof_tag(c, -2));
-            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H, w8), B, 2 * F, true, m, mb, w8, s));
+            HIP_TRY(launch_sk_reduce(part, gemm_sk_splits(B, 2 * F, H, w8, tiled), B, 2 * F, true, m, mb, w8, s));
         }
 
         if (!seg_mlp) ST_TRY(prof_tag(c, PSV_OP_DOWN));
@@ -637,7 +637,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             if (!gemm_sk_supported(B, H, F)) return PSV_ERR_UNSUPPORTED;
             HIP_TRY(launch_gemm_sk(Wd, Mat{}, 0, mb, nullptr, 0.f, part, B, H, F, nullptr, s));
             delta = part;
-            delta_splits = gemm_sk_splits(B, H, F, w8);
+            delta_splits = gemm_sk_splits(B, H, F, w8, tiled);
         }
 
         {

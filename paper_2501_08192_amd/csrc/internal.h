@@ -155,7 +155,7 @@ hipError_t launch_step(const StepLaunch &p, int blocks, hipStream_t s);
 // part[split][b][r] = partial sums of W[r].x[b] (rows >= split_row come from W2), to be summed in split
 // order by launch_sk_reduce or launch_resid_sum.  x_bf16: see the operand formats above.
 constexpr int kSkMaxSplits = 16;
-int gemm_sk_splits(int batch, int N, int K, bool w8);
+int gemm_sk_splits(int batch, int N, int K, bool w8, bool tiled);
 bool gemm_sk_supported(int batch, int N, int K);
 // ssq != null (K % 512 == 0): x_bf16 holds x * gain without the 1/rms factor of its RMSNorm and ssq the partial
 // sums of squares [batch][K / 512] written by launch_resid_sum; the result is multiplied by 1/rms of its batch row.
@@ -179,7 +179,7 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *x_bf16, 
                           float *part, int batch, int N, int K, const SkWait *wait, hipStream_t s);
 // May that projection be launched with a wait on a device of `cus` compute units (its waiting workgroups leave room
 // for the kernel they wait for)?
-bool gemm_sk_can_wait(int batch, int N, int K, bool w8, int cus);
+bool gemm_sk_can_wait(int batch, int N, int K, bool w8, bool tiled, int cus);
 // out_res = res + delta (delta: null, or `delta_splits` split-K partials summed in split order), one float4 per
 // thread over grid (H / 512, batch).  gain != null: also out_res * gain as hi/lo bf16 planes (xg_bf16, lo plane
 // plane_stride elements after the hi plane) and the sums of squares per workgroup, ssq[batch][H / 512].

@@ -77,13 +77,13 @@ def path_of(batch, hidden, weight_layout="row"):
     return "vec" if batch == 1 or (batch == 2 and hidden <= 4096) else "mm"
 
 
-def sk_splits(batch, n_rows, k, weight_bytes=2.0):
+def sk_splits(batch, n_rows, k, weight_bytes=2.0, tiled=False):
     """K splits of the split-K GEMM: the library's cost model (0.6 us per slab step, 512 resident workgroups, weights and
     partials at 4 TB/s)."""
     n_slabs = k // 64
     row_groups = (n_rows + 127) // 128
     w_bytes, part_bytes = weight_bytes * n_rows * k, 8.0 * batch * n_rows
-    best, best_cost = 1, 1e30
+    best, best_cost, best1, best1_cost = 1, 1e30, 0, 1e30
     ks = 1
     while ks <= 16 and ks * 2 <= n_slabs:
         spb = (n_slabs + ks - 1) // ks
@@ -92,11 +92,15 @@ def sk_splits(batch, n_rows, k, weight_bytes=2.0):
             cost = rounds * spb * 0.6 + (w_bytes + ks * part_bytes) / 4.0e6
             if cost < best_cost - 1e-9:
                 best, best_cost = ks, cost
+            if rounds == 1 and cost < best1_cost - 1e-9:
+                best1, best1_cost = ks, cost
         ks += 1
+    if tiled and best1 and best1_cost <= 1.02 * best_cost:      # tiled weights: within 2 %, one round of workgroups wins
+        best = best1
     return best
 
 
-def mm_hold(batch, hidden, ffn, weight_format="bf16", cus=256):
+def mm_hold(batch, hidden, ffn, weight_format="bf16", cus=256, weight_layout="row"):
     """Fraction of the gate/up weights that the GEMM launched into its window keeps on chip (12 slabs of each workgroup's
     range if it has that many, else 6 -- 8 with int8 weights), or 0.0 where the library does not launch it that way:
     batch above 16, fewer than 128 workgroups or more than stay resident beside the kernel it waits for."""
@@ -104,7 +108,7 @@ def mm_hold(batch, hidden, ffn, weight_format="bf16", cus=256):
         return 0.0
     w8 = weight_format == "int8"
     n_rows = 2 * ffn
-    splits = sk_splits(batch, n_rows, hidden, 1.0 if w8 else 2.0)
+    splits = sk_splits(batch, n_rows, hidden, 1.0 if w8 else 2.0, weight_layout == "tiled")
     spb = (hidden // 64 + splits - 1) // splits
     grid = (n_rows + 127) // 128 * splits
     if spb >= 12:

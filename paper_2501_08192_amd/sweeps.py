@@ -64,7 +64,7 @@ def speed_map(shape, batches, contexts, layers=4, window=20.0, out=print, kv_lay
                 continue
             b = model.op_bytes(hidden, nq, nkv, ffn, B, T)
             path = model.path_of(B, hidden, weight_layout)
-            hold = model.mm_hold(B, hidden, ffn) if path != "vec" else 0.0
+            hold = model.mm_hold(B, hidden, ffn, weight_layout=weight_layout) if path != "vec" else 0.0
             budget = model.best_budget(b, (window, window), mach, path=path)
             with Session(w, layers=list(range(layers))) as s:
                 s.set_policy(psv.prefetch_policy(mode=0))
@@ -170,7 +170,7 @@ def calibrate(path, window=50.0, layers=4, out=print):
         b = model.op_bytes(H, nq, nkv, F, B, T)
         nb = {"qkv": b["qkv"], "attn": b["attn"], "o": b["o"], "gate_up": b["gate"] + b["up"], "down": b["down"]}
         cls = model.path_of(B, H, layout)
-        hold = model.mm_hold(B, H, F) if cls != "vec" else 0.0
+        hold = model.mm_hold(B, H, F, weight_layout=layout) if cls != "vec" else 0.0
         with Session(w, layers=list(range(layers))) as s:
             # windows long enough for the whole budget to arrive inside them; whole-layer timing first (it warms up)
             s.set_policy(psv.prefetch_policy(mode=0))

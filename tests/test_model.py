@@ -80,7 +80,7 @@ def test_calibrated_model_predicts_every_measured_row():
     for r in _golden()["rows"]:
         b = model.op_bytes(r["hidden"], r["n_q"], r["n_kv"], r["ffn"], r["batch"], r["context"])
         path, w = model.path_of(r["batch"], r["hidden"], r["weight_layout"]), tuple(r["windows"])
-        hold = model.mm_hold(r["batch"], r["hidden"], r["ffn"]) if path != "vec" else 0.0
+        hold = model.mm_hold(r["batch"], r["hidden"], r["ffn"], weight_layout=r["weight_layout"]) if path != "vec" else 0.0
         # the model's copy of the library's rule for launching the gate/up GEMM into its window agrees with what ran
         if path != "vec":
             assert (hold > 0) == (r["prelaunched"] > 0), r["name"]
