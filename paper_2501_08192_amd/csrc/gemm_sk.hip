@@ -242,7 +242,7 @@ template <int NB, int HOLD>
 __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
 {
     constexpr bool WAIT = HOLD > 0;
-    static_assert(!WAIT || NB == 1, "the waiting variant is built for one batch tile");
+    static_assert(!WAIT || NB <= 2, "the waiting variant is built for one or two batch tiles");
     constexpr int PF = 4;   // slabs of weight fragments in flight per wave (8 measured slower: fewer straight-line rounds, more registers)
     __shared__ uint4 xs[2][NB * 4][64];   // [buffer][(batch tile*2 + plane)*2 + k half][lane]
     const int tid = threadIdx.x, w = tid >> 6, lane = tid & 63, i = lane & 15, g = lane >> 4;
@@ -313,8 +313,8 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
     // WAIT: the first PF slabs of the range wait in the register ring as always, the next RH in registers of their own
     // (used once) and the LH after those are parked in LDS (each thread keeps its own fragments there: 16 KiB per slab and
     // workgroup).  HS is even (the activation double buffer alternates per slab).
-    constexpr int RH = HOLD == 2 ? 4 : 0;
-    constexpr int LH = HOLD == 2 ? 4 : HOLD == 1 ? 2 : 0;
+    constexpr int RH = HOLD == 2 ? (NB == 1 ? 4 : 2) : 0;          // two batch tiles: 6 or 8 slabs (registers, LDS)
+    constexpr int LH = HOLD == 2 ? (NB == 1 ? 4 : 2) : HOLD == 1 ? 2 : 0;
     constexpr int HS = PF + RH + LH;        // slabs held on chip when the wait ends
     __shared__ uint4 wl[LH ? LH * 4 * 256 : 1];
     const bool held = WAIT && s1 - s0 >= HS;
@@ -834,14 +834,14 @@ bool gemm_sk_supported(int batch, int N, int K)
 }
 
 // Which waiting variant a range of `slabs_per_block` slabs takes: the one that keeps 12 slabs on chip if the range has them.
-static int sk_hold_level(int slabs_per_block) { return slabs_per_block >= 12 ? 2 : 1; }
+static int sk_hold_level(int slabs_per_block, int nb = 1) { return slabs_per_block >= (nb == 1 ? 12 : 8) ? 2 : 1; }
 
-// Resources of the waiting variants ([bf16 | int8 weights][hold level - 1]) and of the kernel they wait for, asked from
+// Resources of the waiting variants ([bf16 | int8 | bf16 with two batch tiles][hold level - 1]) and of the kernel they wait for, asked from
 // the runtime once.
 struct SkWaitRes {
-    int occ[2][2];       // resident workgroups per compute unit
-    int regs[2][2];      // registers per lane (vector + accumulation), rounded up to the allocation unit
-    int lds[2][2];       // static LDS bytes per workgroup
+    int occ[3][2];       // resident workgroups per compute unit
+    int regs[3][2];      // registers per lane (vector + accumulation), rounded up to the allocation unit
+    int lds[3][2];       // static LDS bytes per workgroup
     int regs_signal;     // k_resid_sum<true>
     bool ok;
 };
@@ -864,6 +864,8 @@ static const SkWaitRes &sk_wait_res()
         ask(0, 1, k_gemm_sk<1, 2>);
         ask(1, 0, k_gemm_sk_i8<1, 1>);
         ask(1, 1, k_gemm_sk_i8<1, 2>);
+        ask(2, 0, k_gemm_sk<2, 1>);
+        ask(2, 1, k_gemm_sk<2, 2>);
         hipFuncAttributes at{};
         q.ok = q.ok && hipFuncGetAttributes(&at, reinterpret_cast<const void *>(k_resid_sum<true>)) == hipSuccess;
         q.regs_signal = (at.numRegs + 7) / 8 * 8;
@@ -879,12 +881,20 @@ static const SkWaitRes &sk_wait_res()
 bool gemm_sk_can_wait(int batch, int N, int K, bool w8, bool tiled, int cus)
 {
     if (!gemm_sk_supported(batch, N, K) || K % 512 || (long long)batch * (K / 512) > kSkWaitEntries) return false;
-    if (batch > kSkWaitMaxBatch) return false;         // one batch tile: the only instantiations of the waiting kernels
+    if (batch > (w8 ? 16 : kSkWaitMaxBatch)) return false;         // the instantiations of the waiting kernels
     const SkWaitRes &r = sk_wait_res();
     if (!r.ok) return false;
     const int splits = gemm_sk_splits(batch, N, K, w8, tiled);
-    const int kind = w8 ? 1 : 0, lv = sk_hold_level((K / 64 + splits - 1) / splits) - 1;
+    const int nb = (batch + 15) / 16;
+    const int kind = w8 ? 1 : nb == 2 ? 2 : 0, lv = sk_hold_level((K / 64 + splits - 1) / splits, nb) - 1;
     const long long grid = (long long)((N + 127) / 128) * splits;
+    // Worth it only if a good part of a workgroup's range stays on chip: with less than a third (two batch tiles on the
+    // 235 MB gate/up matrix of a TP=4 70B-shaped shard: 8 slabs of 32) the wait's latencies cost more than the slabs save.
+    {
+        const int spb = (K / 64 + splits - 1) / splits;
+        const int hs = w8 ? (lv ? 12 : 8) : nb == 2 ? (lv ? 8 : 6) : (lv ? 12 : 6);
+        if (hs * 3 < spb) return false;
+    }
     // ... and it is the window's prefetch kernel as well, which needs at least 128 workgroups to reach its rate
     if (grid < 128 || grid > (long long)r.occ[kind][lv] * cus) return false;
     const bool free_slots = grid + cus / 4 <= (long long)r.occ[kind][lv] * cus;
@@ -906,7 +916,7 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
         wt.touch_w = (int)(wait->share_w * slabs_per_block + 0.5);
         wt.touch_w2 = (int)(wait->share_w2 * slabs_per_block + 0.5);
     };
-    if (wait && (!ssq || !wait->ssq_ll || !wait->win_done || batch > kSkWaitMaxBatch || K % 512 || (long long)batch * (K / 512) > kSkWaitEntries)) return hipErrorInvalidValue;
+    if (wait && (!ssq || !wait->ssq_ll || !wait->win_done || batch > (W.scale ? 16 : kSkWaitMaxBatch) || K % 512 || (long long)batch * (K / 512) > kSkWaitEntries)) return hipErrorInvalidValue;
     if (W.scale) {   // int8 weights: xb holds digit planes (bytes), see k_gemm_sk_i8
         GemmI8Args q{};
         q.W = static_cast<const int8_t *>(W.w); q.W2 = static_cast<const int8_t *>(W2.w ? W2.w : W.w);
@@ -945,8 +955,11 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
     if (wait) {
         fill_wait(a.wt, a.slabs_per_block);
         const PrefetchJob pj = wait->job ? *wait->job : PrefetchJob{};
-        if (sk_hold_level(a.slabs_per_block) == 2) PSV_LAUNCH((k_gemm_sk<1, 2>), grid, dim3(256), 0, s, a, pj);
-        else PSV_LAUNCH((k_gemm_sk<1, 1>), grid, dim3(256), 0, s, a, pj);
+        const int lv = sk_hold_level(a.slabs_per_block, nb);
+        if (nb == 1 && lv == 2) PSV_LAUNCH((k_gemm_sk<1, 2>), grid, dim3(256), 0, s, a, pj);
+        else if (nb == 1) PSV_LAUNCH((k_gemm_sk<1, 1>), grid, dim3(256), 0, s, a, pj);
+        else if (lv == 2) PSV_LAUNCH((k_gemm_sk<2, 2>), grid, dim3(256), 0, s, a, pj);
+        else PSV_LAUNCH((k_gemm_sk<2, 1>), grid, dim3(256), 0, s, a, pj);
         return hipGetLastError();
     }
     switch (nb) {

@@ -101,20 +101,27 @@ def sk_splits(batch, n_rows, k, weight_bytes=2.0, tiled=False):
 
 
 def mm_hold(batch, hidden, ffn, weight_format="bf16", cus=256, weight_layout="row"):
-    """Fraction of the gate/up weights that the GEMM launched into its window keeps on chip (12 slabs of each workgroup's
-    range if it has that many, else 6 -- 8 with int8 weights), or 0.0 where the library does not launch it that way:
-    batch above 16, fewer than 128 workgroups or more than stay resident beside the kernel it waits for."""
-    if not (1 <= batch <= 16) or hidden % 512 or batch * (hidden // 512) > 1024:
-        return 0.0
+    """Fraction of the gate/up weights that the GEMM launched into its window keeps on chip, or 0.0 where the library does
+    not launch it that way: its own copy of the library's rule.  Slabs kept per workgroup: bf16 weights 12 (6 if the range
+    is shorter) at batch <= 16 and 8 (6) at batch 17-32; int8 weights 12 (8) at batch <= 16.  Not launched if that is
+    less than a third of the range, with fewer than 128 workgroups, or with more than stay resident beside the kernel it
+    waits for."""
     w8 = weight_format == "int8"
+    if not (1 <= batch <= (16 if w8 else 32)) or hidden % 512 or batch * (hidden // 512) > 1024:
+        return 0.0
+    nb = (batch + 15) // 16
     n_rows = 2 * ffn
     splits = sk_splits(batch, n_rows, hidden, 1.0 if w8 else 2.0, weight_layout == "tiled")
     spb = (hidden // 64 + splits - 1) // splits
     grid = (n_rows + 127) // 128 * splits
-    if spb >= 12:
-        ok, held = 128 <= grid <= (3 if w8 else 2) * cus, 12
-    else:
-        ok, held = grid >= 128 and grid + cus // 4 <= 3 * cus, 8 if w8 else 6
+    big = spb >= (12 if nb == 1 else 8)
+    held = (12 if big else 8) if w8 else ((8 if big else 6) if nb == 2 else (12 if big else 6))
+    if held * 3 < spb or grid < 128:
+        return 0.0
+    if w8 or (nb == 1 and not big):        # three resident workgroups per compute unit, a quarter of the slots kept free
+        ok = grid + cus // 4 <= 3 * cus
+    else:                                  # two per compute unit, the producer's waves fit beside them
+        ok = grid <= 2 * cus
     return min(1.0, held / spb) if ok else 0.0
 
 

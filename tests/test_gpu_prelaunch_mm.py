@@ -1,4 +1,4 @@
-"""GPU tests of the pre-launched gate/up projection on the matrix-core path (policy.prelaunch at batch 3..16):
+"""GPU tests of the pre-launched gate/up projection on the matrix-core path (policy.prelaunch at batch 3..32):
 the split-K GEMM is launched into the window after the attention block, keeps its first weight slabs on chip, walks the
 window's prefetch job and waits for the tagged sums of squares of the residual kernel that follows the window on the other
 stream.  Through the C ABI against the CPU oracle (|gpu - ref| <= 2e-2 + 1e-2*|ref|), bit-identical to prefetch off under
@@ -47,7 +47,11 @@ CASES = [
     ("short_range", 2, 1024, 8, 2, 8192, 8, 70, False, "row", (8.0, 8.0), 2),         # 4 slabs per workgroup: all in the ring
     ("short_range5", 2, 1536, 12, 4, 6144, 4, 40, True, "tiled", (8.0, 8.0), 2),       # 5 slabs: one more than the ring holds
     ("no_window", 2, 8192, 8, 1, 3584, 8, 64, False, "tiled", (0.0, 8.0), 0),         # nothing to launch into
-    ("b32", 2, 8192, 8, 1, 3584, 32, 64, False, "tiled", (8.0, 8.0), 0),              # above the batch limit of that route
+    ("b32", 2, 8192, 8, 1, 3584, 32, 64, False, "tiled", (8.0, 8.0), 2),              # two batch tiles: 8 slabs kept
+    ("b17_paged_row", 2, 8192, 8, 1, 3584, 17, 100, True, "row", (8.0, 8.0), 2),
+    ("b24_short", 2, 2048, 16, 2, 5632, 24, 40, False, "tiled", (8.0, 8.0), 2),       # two batch tiles, ranges of 6 slabs
+    ("b48", 2, 8192, 8, 1, 3584, 48, 40, False, "tiled", (8.0, 8.0), 0),              # above the batch limit of that route
+    ("b32_tp4", 2, 8192, 16, 2, 7168, 32, 40, False, "tiled", (8.0, 8.0), 0),         # less than a third of a range would stay
     ("small", 2, 1024, 8, 2, 768, 5, 129, False, "row", (8.0, 8.0), 0),               # too few workgroups to carry the job
 ]
 
