@@ -50,7 +50,7 @@ def parse():
     ap.add_argument("--join", type=int, default=0)
     ap.add_argument("--prelaunch", type=int, default=1,
                     help="1 = the first operator after a window is launched at the window's start and holds its weights in "
-                         "registers until the window ends (policy extension; at batch 3-16 the gate/up projection only, "
+                         "registers until the window ends (policy extension; at batch 3-32 the gate/up projection only, "
                          "above that none)")
     ap.add_argument("--targets", type=int, default=3)
     ap.add_argument("--window-us", type=float, nargs=2, default=None)

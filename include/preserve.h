@@ -154,7 +154,7 @@ typedef struct {
                                 operator chain continues on that stream, so the two streams swap roles at
                                 every window.  Takes effect at batch 1 (and batch 2 up to H = 4096) for both
                                 windows when the plan hands them the operator whole; with the matrix-core
-                                projections (larger batches, or tiled weights) at batch <= 16
+                                projections (larger batches, or tiled weights) at batch <= 32 (int8 weights: 16)
                                 for the gate/up projection when the plan hands its window any of it and all
                                 its workgroups fit the device at once -- that kernel also walks the window's
                                 prefetch job, keeps its first weight slabs in registers and LDS, and waits

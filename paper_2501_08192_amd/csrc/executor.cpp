@@ -251,7 +251,7 @@ struct Lanes {
 // flags the window kernel publishes (start, end).  *wait_set tells the caller to launch the consumer that way.
 // Does the plan hand the whole weight matrix of the first consumer after (layer, window) to that window, so that
 // the consumer can be launched ahead of time (policy.prelaunch, eager launches, vector path)?
-// Matrix-core path (batch <= 16, gate/up only): the consumer is a split-K GEMM that keeps only its first
+// Matrix-core path (batch <= 32, int8 weights 16; gate/up only): the consumer is a split-K GEMM that keeps only its first
 // slabs on chip, so any planned share of its weights qualifies, and its waiting workgroups must leave room for the kernel
 // they wait for.
 bool can_prelaunch(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t layer_end, bool vec, int batch)

@@ -161,8 +161,7 @@ bool gemm_sk_supported(int batch, int N, int K);
 // sums of squares [batch][K / 512] written by launch_resid_sum; the result is multiplied by 1/rms of its batch row.
 // wait != null (ssq != null, one batch tile): launched into a communication window ahead of its activations, on another
 // stream than the launch_resid_sum that produces them, which is given the same SkWait as its signal.
-constexpr int kSkWaitMaxBatch = 32;      // measured: at batch 32 and 64 the producer's write-through stores and the reload of the
-                                         // activations cost what the held weights save
+constexpr int kSkWaitMaxBatch = 32;      // one or two batch tiles (bf16 weights; int8: one)
 constexpr int kSkWaitEntries = 1024;     // batch * K / 512 of a projection launched that way
 struct SkWait {
     void *ssq_ll;            // tagged sums of squares, [batch][K / 512] x 8 bytes, padded to a multiple of 512 entries

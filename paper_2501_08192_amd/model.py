@@ -54,7 +54,7 @@ class Machine:
     reg_bytes: float = 32e6      # weights its first pass holds in registers
     t_post: float = 3.0          # us it still needs after the window (poll, activations, reduce, drain)
     bw_reg: float = 24e6         # bytes/us at which it works through the weights it holds
-    # the gate/up GEMM launched into its window (policy.prelaunch, matrix-core path, batch <= 16)
+    # the gate/up GEMM launched into its window (policy.prelaunch, matrix-core path, batch <= 32)
     t_post_mm: float = 6.0       # us after the window until it has worked through what it holds, the residual kernel it
                                  #   waits for included
 
