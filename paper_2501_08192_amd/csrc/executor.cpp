@@ -237,23 +237,11 @@ struct Lanes {
     hipStream_t cur, other;
 };
 
-// The communication window after the attention block (window 0) or the MLP block (window 1).  The
-// stand-in for the collective is enqueued first, so that the stream never waits for the host; the window's
-// prefetch job goes to the other stream and starts when the window starts.
-//
-// prelaunch (policy extension, eager launches, vector path): the first consumer after the window -- gate/up
-// after window 0, the next layer's QKV after window 1 -- is the one operator whose weights are needed the moment
-// the window ends.  If Algorithm 1 planned a prefetch for it, that prefetch is done by the consumer itself: the
-// caller launches it on the other stream right behind the window's gate and its (remaining) prefetch job, with a
-// GemvWait on the window's end.  It pulls its first weights into registers while the window runs and finishes a
-// few microseconds after the window does.  The rest of the chain follows it on that stream, so the two streams
-// swap roles at every window and no host-side event is needed: every cross-stream dependency is one of the two
-// flags the window kernel publishes (start, end).  *wait_set tells the caller to launch the consumer that way.
-// Does the plan hand the whole weight matrix of the first consumer after (layer, window) to that window, so that
-// the consumer can be launched ahead of time (policy.prelaunch, eager launches, vector path)?
-// Matrix-core path (batch <= 32, int8 weights 16; gate/up only): the consumer is a split-K GEMM that keeps only its first
-// slabs on chip, so any planned share of its weights qualifies, and its waiting workgroups must leave room for the kernel
-// they wait for.
+// Can the first consumer after (layer, window) be launched into that window (policy.prelaunch)?
+// Vector path: gate/up after window 0, the next layer's QKV after window 1, if the plan hands the window the whole
+// weight matrix.  Matrix-core path (batch <= 32, int8 weights 16): the gate/up GEMM only; it keeps just its first slabs on
+// chip, so any planned share of its weights qualifies, and its waiting workgroups must leave room for the kernel they
+// wait for (gemm_sk_can_wait).
 bool can_prelaunch(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t layer_end, bool vec, int batch)
 {
     if (c->policy.mode != 1 || !c->policy.prelaunch || !(c->window_us[window] > 0.f)) return false;
@@ -266,8 +254,7 @@ bool can_prelaunch(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t l
         // epilogue -- add up to the whole ordinary kernel).
         if (window != 0) return false;
         const psv_model_desc &d = c->d;
-        const int H = (int)d.hidden, N = window == 0 ? 2 * (int)d.ffn : (int)(d.n_q_heads + 2 * d.n_kv_heads) * 128;
-        if (!gemm_sk_can_wait(batch, N, H, d.weight_format == PSV_FMT_INT8, d.weight_layout == PSV_W_TILED, c->cus)) return false;
+        if (!gemm_sk_can_wait(batch, 2 * (int)d.ffn, (int)d.hidden, d.weight_format == PSV_FMT_INT8, d.weight_layout == PSV_W_TILED, c->cus)) return false;
     }
     for (const psv_plan_entry &e : c->plan)
         if (e.layer == layer && e.window == window && e.target_op == first_op && (vec ? e.bytes == e.mem_size : e.bytes > 0))
@@ -283,6 +270,20 @@ bool plan_has_whole(const psv_ctx *c, uint32_t layer, uint32_t window, uint32_t 
     return false;
 }
 
+// The communication window after the attention block (window 0) or the MLP block (window 1).  The
+// stand-in for the collective is enqueued first, so that the stream never waits for the host; the window's
+// prefetch job goes to the other stream and starts when the window starts.
+//
+// prelaunch (policy extension): the first consumer after the window -- gate/up
+// after window 0, the next layer's QKV after window 1 -- is the one operator whose weights are needed the moment
+// the window ends.  If Algorithm 1 planned a prefetch for it, that prefetch is done by the consumer itself: the
+// caller launches it on the other stream right behind the window's gate and its (remaining) prefetch job, with a
+// GemvWait on the window's end.  It pulls its first weights into registers while the window runs and finishes a
+// few microseconds after the window does.  The rest of the chain follows it on that stream, so the two streams
+// swap roles at every window and no host-side event is needed: every cross-stream dependency is one of the two
+// flags the window kernel publishes (start, end).  *wait_set tells the caller to launch the consumer that way.  (On the
+// matrix-core path the consumer is the gate/up GEMM, which waits for the residual kernel that follows the window on the
+// window's own stream; see defer below and launch_gemm_sk.)
 // held: bit mask (1 << PSV_OP_*) of the operators whose planned bytes the pre-launched consumer pulls into its own
 // registers during the window; their plan entries are not prefetched a second time.
 // defer (matrix-core path): the pre-launched consumer walks the window's (last) prefetch job itself while it waits --
