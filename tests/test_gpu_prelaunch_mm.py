@@ -140,3 +140,33 @@ def test_waiting_gemm_outwaits_earlier_work_on_the_main_stream():
         s.sync()
         assert torch.equal(s.x_out, base)
         assert psv.psv_debug_last_step_prelaunches(s.ctx) == 2
+
+
+def test_windows_of_any_length_layer_ranges_and_policy_changes_between_steps():
+    """The waiting GEMM under windows much shorter than its own loads (it starts its wait after the window has ended) and
+    much longer, over layer sub-ranges, with the policy and the windows changed between back-to-back steps."""
+    w = W("mmwin", 4, 8192, 8, 1, 3584, 8, 80, layout="tiled")
+    with Session(w, seed=102) as s:
+        need_overlap(s)
+        off = s.run().clone()
+        sub = {(lb, le): s.run(layer_begin=lb, layer_end=le).clone() for lb, le in ((1, 3), (0, 1), (2, 4))}
+        on = default_policy(w, budget_bytes=1 << 40)
+        for win in ((0.5, 0.5), (150.0, 3.0), (2.0, 60.0)):
+            s.set_windows(*win)
+            s.set_policy(on)
+            assert torch.equal(s.run(), off), win
+            assert psv.psv_debug_last_step_prelaunches(s.ctx) == 4
+            for (lb, le), ref in sub.items():
+                assert torch.equal(s.run(layer_begin=lb, layer_end=le), ref), (win, lb, le)
+            assert psv.psv_debug_last_step_prelaunches(s.ctx) == 2             # layers 2..3
+        # policies alternate between steps without a host synchronisation in between
+        s.set_windows(5.0, 5.0)
+        for rep in range(3):
+            s.set_policy(on)
+            s.step()
+            s.set_policy(default_policy(w, budget_bytes=16 << 20, prelaunch=0))
+            s.step()
+            s.set_policy(psv.prefetch_policy(mode=0))
+            s.step()
+        s.sync()
+        assert torch.equal(s.x_out, off)
