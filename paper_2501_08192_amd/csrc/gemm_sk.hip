@@ -231,9 +231,12 @@ struct GemmSkArgs {
 // HOLD: 0 = the ordinary kernel; 1, 2 = the variant launched into a communication window, on another stream than the kernel
 // that produces its activations, keeping 6 or 12 slabs of its range on chip (the launcher takes the larger one that the
 // range has); kernels of their own, so that the ordinary one carries none of that code.  The activation planes are read
-// with ordinary loads: the kernel has not touched them before the wait, so neither its XCD's L2 nor its CU's cache can
-// hold an older copy (both were invalidated when the kernel started), and the producer's stores have reached the memory
-// side before it signals.  The sums of squares are what the wait polls, with device-coherent loads.
+// with ordinary loads.  Nothing on the device reads them between this kernel's start and the producer's stores (not this
+// kernel before its wait, no other kernel of the step), so its CU's vector cache, emptied when the kernel started, holds
+// nothing of them; the XCDs' L2s are kept coherent for device memory by the hardware (a copy left from the previous
+// layer's operand does not outlive the producer's stores -- the same property every kernel that reads a reused buffer
+// written on another XCD relies on), and those stores have reached the memory side before the producer signals.  The
+// sums of squares are what the wait polls, with device-coherent loads.
 // pj (HOLD > 0): what else the window's plan prefetches -- other operators' weights, KV blocks.  The waiting kernel is the
 // window's prefetch kernel as well: it walks the job first, before anything of its own sits in registers.
 __device__ __forceinline__ uint32_t xor4(uint4 v) { return v.x ^ v.y ^ v.z ^ v.w; }
