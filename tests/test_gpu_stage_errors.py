@@ -48,6 +48,9 @@ CASES = [
     ("w8_tp4_b32_tiled", 8192, 16, 2, 7168, 32, 40, False, "tiled", "int8"),
     ("w8_tp8_b16", 8192, 8, 1, 3584, 16, 70, True, "tiled", "int8"),
     ("w8_ragged_b5", 1536, 12, 4, 6144, 5, 33, False, "row", "int8"),
+    ("b40_three_tiles", 4096, 8, 2, 3584, 40, 33, True, "tiled", "bf16"),
+    ("w8_b40_three_tiles", 4096, 8, 2, 3584, 40, 33, True, "tiled", "int8"),
+    ("w8_b64_row", 2048, 16, 4, 5632, 64, 20, False, "row", "int8"),
 ]
 
 
