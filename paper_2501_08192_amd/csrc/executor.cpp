@@ -51,8 +51,8 @@ Workspace layout_workspace(const psv_model_desc &d)
     w.inv_freq = take(64 * sizeof(double));
     w.flag = take(256);
     w.ssq = take(B * (H / 512) * 4);
-    w.ssq_ll = take((B * (H / 512) + 511) / 512 * 512 * 8);     // the same as tagged values, for a projection launched ahead of them
-    w.m_ll = take(B * F * 8);               // tagged values of the fused MLP kernel
+    w.ssq_ll = take(kSkTagCopies * sk_tag_stride((int)B, (int)H) * 8);     // the same as tagged values (in copies), for a projection launched ahead of them
+    w.m_ll = take(B * F * 8 + (size_t)kSegIndCopies * kSegIndStride * 8);   // tagged values of the fused MLP kernel + its indicator entries
     {                                       // ... and of the fused attention-block kernel (one sequence)
         const size_t nc = (size_t)seg_attn_chunks(d.max_seq);
         w.qkv_ll = take(QR * 8);

@@ -20,8 +20,8 @@ namespace psv {
 // and multiplies its result by 1/rms of the batch row, which it forms from ssq (k_gemm_sk).
 // SIGNAL: a projection launched ahead of this kernel is waiting for its outputs (k_gemm_sk<1, HOLD> or k_gemm_sk_i8<1, HOLD>, HOLD > 0).  Every
 // output is stored written through to the memory side; once a workgroup's stores are acknowledged, its sum of squares goes out as a
-// tagged value {sum, tag} (ssq_ll, same index as ssq), and the waiting kernel proceeds when every entry carries the tag of
-// this launch.  No fence and no counter: a release fence makes every wave write back its XCD's L2 and a device-scope
+// tagged value {sum, tag} (ssq_ll: kSkTagCopies copies of [H / 512][batch], stored by as many lanes at once), and the waiting
+// kernel proceeds when every entry it polls carries the tag of this launch.  No fence and no counter: a release fence makes every wave write back its XCD's L2 and a device-scope
 // counter serialises at the memory side -- measured 25-55 ns per workgroup either way, 7 us per layer at batch 8 and
 // 25 us at batch 32.
 __device__ __forceinline__ void st_wt16(void *p, float4 v)
@@ -41,7 +41,8 @@ __global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res
                                                    int delta_splits, size_t delta_stride, int H,
                                                    float *__restrict__ out_res, const uint16_t *__restrict__ gain,
                                                    uint16_t *__restrict__ xg_bf16, size_t plane_stride,
-                                                   int digits, float *__restrict__ ssq, uint2 *ssq_ll, unsigned tag)
+                                                   int digits, float *__restrict__ ssq, uint2 *ssq_ll, unsigned ll_stride,
+                                                   unsigned tag)
 {
     __shared__ float red[2];
     const int b = blockIdx.y, tid = threadIdx.x;
@@ -96,7 +97,8 @@ __global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res
     }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");      // every wave: its stores are acknowledged by the memory side
     __syncthreads();
-    if (tid == 0) ll_store(ssq_ll + (size_t)b * gridDim.x + blockIdx.x, red[0] + red[1], tag);
+    if (tid < kSkTagCopies)     // [copy][H / 512][batch]: every waiting workgroup polls one copy, a few dozen of them each
+        ll_store(ssq_ll + (size_t)tid * ll_stride + (size_t)blockIdx.x * gridDim.y + b, red[0] + red[1], tag);
 }
 
 hipError_t launch_resid_sum(const float *res, const float *delta, int delta_splits, int batch, int H, float *out_res,
@@ -106,10 +108,11 @@ hipError_t launch_resid_sum(const float *res, const float *delta, int delta_spli
     if (signal && (!gain || !signal->ssq_ll)) return hipErrorInvalidValue;   // only the form that prepares an operand signals
     if (signal)
         PSV_LAUNCH(k_resid_sum<true>, dim3(H / 512, batch), dim3(128), 0, s, res, delta, delta_splits, (size_t)batch * H, H,
-                   out_res, gain, xg_bf16, plane_stride, digits ? 1 : 0, ssq, static_cast<uint2 *>(signal->ssq_ll), signal->tag);
+                   out_res, gain, xg_bf16, plane_stride, digits ? 1 : 0, ssq, static_cast<uint2 *>(signal->ssq_ll),
+                   (unsigned)sk_tag_stride(batch, H), signal->tag);
     else
         PSV_LAUNCH(k_resid_sum<false>, dim3(H / 512, batch), dim3(128), 0, s, res, delta, delta_splits, (size_t)batch * H, H,
-                   out_res, gain, xg_bf16, plane_stride, digits ? 1 : 0, ssq, static_cast<uint2 *>(nullptr), 0u);
+                   out_res, gain, xg_bf16, plane_stride, digits ? 1 : 0, ssq, static_cast<uint2 *>(nullptr), 0u, 0u);
     return hipGetLastError();
 }
 
@@ -127,7 +130,8 @@ hipError_t launch_resid_sum(const float *res, const float *delta, int delta_spli
 struct SkWaitArgs {
     const unsigned *win_done;
     unsigned win_seq;
-    const uint2 *ll;          // tagged sums of squares [batch][K / 512], padded to a multiple of 512 entries
+    const uint2 *ll;          // tagged sums of squares: kSkTagCopies copies of [K / 512][batch], ll_stride entries apart
+    unsigned ll_stride;
     unsigned tag;
     int touch_w, touch_w2;
     uint32_t iters;
@@ -138,6 +142,7 @@ struct SkWaitArgs {
 // The wait itself, run by one wave of the workgroup whose K range is slabs [s0, s1).
 __device__ __forceinline__ void sk_wait_for_operand(const SkWaitArgs &wt, int batch, int K, int s0, int s1, int lane)
 {
+    const uint2 *ll = wt.ll + (size_t)(blockIdx.x % kSkTagCopies) * wt.ll_stride;     // this workgroup's copy
     const uint64_t t0 = wall_clock64();
     uint32_t it = 0;
     {
@@ -148,15 +153,18 @@ __device__ __forceinline__ void sk_wait_for_operand(const SkWaitArgs &wt, int ba
             ++it;
         }
     }
-    // The tags of the producer workgroups that write this K range (all batch rows): a few dozen entries, different lines
-    // for different splits.  (Every workgroup polling every entry made one 1-4 KiB region a hot spot.)
-    const int nblk = K / 512, blk0 = s0 >> 3, nbr = (((s1 << 6) - 1) >> 9) - blk0 + 1, cnt = batch * nbr;
+    // The tags of the producer workgroups that write this K range (all batch rows): a few dozen contiguous entries, other
+    // lines for other splits, and one copy of kSkTagCopies per workgroup.  Who polls what matters: every workgroup polling
+    // every entry made one 1-4 KiB region a hot spot, and with the entries of a range spread over one line per batch row,
+    // shared by all workgroups, the tags were seen 1.5 us later than with a line per range and copy (70B-shaped TP=8 shard,
+    // batch 8: 109.2 -> 107.3 us/layer).
+    const int blk0 = s0 >> 3, nbr = (((s1 << 6) - 1) >> 9) - blk0 + 1, cnt = batch * nbr;
     bool ok;
     for (;;) {
         ok = true;
         for (int idx = lane; idx < cnt; idx += 64) {
             uint2 v;
-            ll_issue1(v, wt.ll + (idx / nbr) * nblk + blk0 + idx % nbr);
+            ll_issue1(v, ll + blk0 * batch + idx);             // [K / 512][batch]: a range's entries are contiguous
             asm volatile("s_waitcnt vmcnt(0)" : "+v"(v) : : "memory");
             ok = ok && v.y == wt.tag;
         }
@@ -171,6 +179,7 @@ __device__ __forceinline__ void sk_wait_for_operand(const SkWaitArgs &wt, int ba
 // All tagged sums of squares into LDS (one wave; eight entries per lane and round), for the 1/rms factors of the epilogue.
 __device__ __forceinline__ void sk_read_sums(const SkWaitArgs &wt, int n_ent, int lane, float *ssq_s)
 {
+    const uint2 *ll = wt.ll + (size_t)(blockIdx.x % kSkTagCopies) * wt.ll_stride;
     const uint64_t t0 = wall_clock64();
     uint32_t it = 0;
     bool ok;
@@ -180,10 +189,10 @@ __device__ __forceinline__ void sk_read_sums(const SkWaitArgs &wt, int n_ent, in
             const int e = e0 + lane * 8;
             if (e < n_ent) {
                 u32x4 q0, q1, q2, q3;
-                ll_issue(q0, wt.ll + e);
-                ll_issue(q1, wt.ll + e + 2);
-                ll_issue(q2, wt.ll + e + 4);
-                ll_issue(q3, wt.ll + e + 6);
+                ll_issue(q0, ll + e);
+                ll_issue(q1, ll + e + 2);
+                ll_issue(q2, ll + e + 4);
+                ll_issue(q3, ll + e + 6);
                 ll_wait4(q0, q1, q2, q3);
                 const unsigned t = wt.tag;
                 ok = ok && (e + 0 >= n_ent || q0.y == t) && (e + 1 >= n_ent || q0.w == t) && (e + 2 >= n_ent || q1.y == t) &&
@@ -397,7 +406,7 @@ __global__ __launch_bounds__(256) void k_gemm_sk(GemmSkArgs a, PrefetchJob pj)
                 if (tid < a.batch) {
                     const float *p = a.ssq + (size_t)tid * nblk;
                     if (WAIT) {                                 // what the wait has read, in block order
-                        for (int q = 0; q < nblk; ++q) tot += ssq_s[tid * nblk + q];
+                        for (int q = 0; q < nblk; ++q) tot += ssq_s[q * a.batch + tid];
                     } else if ((nblk & 3) == 0) {               // all loads at once, then the sum in block order
                         float4 t[8];
 #pragma unroll
@@ -690,7 +699,7 @@ __global__ __launch_bounds__(256) void k_gemm_sk_i8(GemmI8Args a, PrefetchJob pj
                 if (tid < a.batch) {
                     const float *p = a.ssq + (size_t)tid * nblk;
                     if (WAIT) {
-                        for (int q = 0; q < nblk; ++q) tot += ssq_s[tid * nblk + q];
+                        for (int q = 0; q < nblk; ++q) tot += ssq_s[q * a.batch + tid];
                     } else if ((nblk & 3) == 0) {
                         float4 t[8];
 #pragma unroll
@@ -914,7 +923,8 @@ hipError_t launch_gemm_sk(Mat W, Mat W2, int split_row, const uint16_t *xb, cons
     // on chip or read and dropped
     auto fill_wait = [&](SkWaitArgs &wt, int slabs_per_block) {
         wt.win_done = wait->win_done; wt.win_seq = wait->win_seq;
-        wt.ll = static_cast<const uint2 *>(wait->ssq_ll); wt.tag = wait->tag; wt.iters = wait->iters;
+        wt.ll = static_cast<const uint2 *>(wait->ssq_ll); wt.ll_stride = (unsigned)sk_tag_stride(batch, K);
+        wt.tag = wait->tag; wt.iters = wait->iters;
         wt.ticks = wait->ticks; wt.err = wait->err;
         wt.touch_w = (int)(wait->share_w * slabs_per_block + 0.5);
         wt.touch_w2 = (int)(wait->share_w2 * slabs_per_block + 0.5);

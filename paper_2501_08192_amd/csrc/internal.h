@@ -90,6 +90,7 @@ hipError_t launch_gemv_merge(Mat W, const float *part_ml, const float *part_o, i
 // window's end expired (wait != null), bit 1 = a hand-over poll expired (results invalid).
 constexpr uint32_t kSegPollIters = 1u << 16;
 unsigned next_tag();
+constexpr int kSegIndCopies = 8, kSegIndStride = 512;    // indicator entries behind m_ll: copies x workgroups (launch_seg_mlp)
 // MLP block: y = res + delta; h = rmsnorm(y) * gain; m = silu(Wg h) * (Wu h); out = Wd m.  m_ll: [batch][F] pairs.
 // wait != null: launched into the window ahead of its inputs, see GemvWait; hold_down = false makes that variant
 // request the down weights only after the window's end (the plan did not hand them to this window).
@@ -163,8 +164,10 @@ bool gemm_sk_supported(int batch, int N, int K);
 // stream than the launch_resid_sum that produces them, which is given the same SkWait as its signal.
 constexpr int kSkWaitMaxBatch = 32;      // one or two batch tiles (bf16 weights; int8: one)
 constexpr int kSkWaitEntries = 1024;     // batch * K / 512 of a projection launched that way
+constexpr int kSkTagCopies = 8;         // the tagged sums of squares are published in that many copies; a waiting workgroup polls one
+inline size_t sk_tag_stride(int batch, int K) { return ((size_t)batch * (K / 512) + 511) / 512 * 512; }   // entries from copy to copy
 struct SkWait {
-    void *ssq_ll;            // tagged sums of squares, [batch][K / 512] x 8 bytes, padded to a multiple of 512 entries
+    void *ssq_ll;            // tagged sums of squares: kSkTagCopies copies of [K / 512][batch] x 8 bytes, sk_tag_stride entries apart
     unsigned tag;            // of this launch pair (next_tag)
     const unsigned *win_done;   // launch_gemm_sk: end word of the window and the value it takes then (GemvWait::done, seq)
     unsigned win_seq;

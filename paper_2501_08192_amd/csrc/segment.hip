@@ -355,6 +355,10 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
         }
     }
 
+    // this workgroup has issued all its stores of m: say so in the indicator array behind m ([copy][workgroup], kSegIndCopies
+    // copies written by as many lanes at once, so that the watchers below do not all poll the same lines)
+    if (tid < kSegIndCopies) ll_store(a.m_ll + (size_t)NB * F + tid * kSegIndStride + blockIdx.x, 0.f, a.tag);
+
     // ---- hand-over: every thread polls its slice of m until all of it carries this launch's tag
     float mv[IT2][NB][8];
     {
@@ -365,19 +369,16 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
             bool ready = false;
             for (uint32_t spin = 0; !ready && spin < a.ll_iters; ++spin) {
                 bool mine = true;
+                const uint2 *ind = a.m_ll + (size_t)NB * F + (blockIdx.x % kSegIndCopies) * kSegIndStride;
                 for (int p0 = 0; p0 < (int)gridDim.x; p0 += 256) {
                     uint2 v[4];
-                    int pe[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) {      // last row of workgroup p0 + lane + 64 u (clamped: a repeat is harmless)
-                        const int wg = min(p0 + lane + 64 * u, (int)gridDim.x - 1);
-                        pe[u] = (int)((long long)(wg + 1) * groups1 * F / slots1);
-                        ll_issue1(v[u], a.m_ll + (size_t)(NB - 1) * F + max(pe[u] - 1, 0));
-                    }
+                    for (int u = 0; u < 4; ++u)        // workgroup p0 + lane + 64 u (clamped: a repeat is harmless)
+                        ll_issue1(v[u], ind + min(p0 + lane + 64 * u, (int)gridDim.x - 1));
                     asm volatile("s_waitcnt vmcnt(0)" : "+v"(v[0]), "+v"(v[1]), "+v"(v[2]), "+v"(v[3]) : : "memory");
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
-                        if (pe[u] > 0 && v[u].y != a.tag) mine = false;
+                        if (v[u].y != a.tag) mine = false;
                 }
                 ready = __all(mine);
                 if (!ready) __builtin_amdgcn_s_sleep(8);
@@ -507,7 +508,7 @@ hipError_t launch_seg_mlp(Mat Wg, Mat Wu, Mat Wd, const float *res, const float 
     a.m_ll = static_cast<uint2 *>(m_ll); a.out = out; a.F = F; a.H = H; a.tag = tag; a.ll_iters = poll_iters; a.err = err;
     if (wait) a.wait = SegWait{wait->done, wait->seq, wait->iters, wait->ticks};
     a.hold_down = hold_down ? 1 : 0;
-    if (batch != 1) return hipErrorInvalidValue;
+    if (batch != 1 || blocks > kSegIndStride) return hipErrorInvalidValue;
     return Wg.scale ? seg_mlp_pick<1, true>(a, wait != nullptr, blocks, s) : seg_mlp_pick<1, false>(a, wait != nullptr, blocks, s);
 }
 
