@@ -91,7 +91,8 @@ hipError_t launch_gemv_merge(Mat W, const float *part_ml, const float *part_o, i
 constexpr uint32_t kSegPollIters = 1u << 16;
 unsigned next_tag();
 constexpr int kSegIndCopies = 8, kSegIndStride = 512;    // indicator entries behind m_ll: copies x workgroups (launch_seg_mlp)
-// MLP block: y = res + delta; h = rmsnorm(y) * gain; m = silu(Wg h) * (Wu h); out = Wd m.  m_ll: [batch][F] pairs.
+// MLP block: y = res + delta; h = rmsnorm(y) * gain; m = silu(Wg h) * (Wu h); out = Wd m.  m_ll: [batch][F] pairs,
+// followed by kSegIndCopies x kSegIndStride indicator pairs (blocks <= kSegIndStride).
 // wait != null: launched into the window ahead of its inputs, see GemvWait; hold_down = false makes that variant
 // request the down weights only after the window's end (the plan did not hand them to this window).
 // poll_iters: bound of every hand-over poll (kSegPollIters; 0 makes every hand-over expire at once -- a test aid).

@@ -68,7 +68,7 @@ struct SegMlpArgs {
     const uint16_t *gain;               // [H]
     float eps;
     float *out_res, *out_h;             // res + delta and the normalised activations, stored by workgroup 0
-    uint2 *m_ll;                        // [NB][F] tagged silu(gate) * up
+    uint2 *m_ll;                        // [NB][F] tagged silu(gate) * up, then kSegIndCopies x kSegIndStride indicator entries
     float *out;                         // [NB][H] down projection
     int F, H;
     SegGeom g1, g2;
@@ -362,7 +362,7 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
     // ---- hand-over: every thread polls its slice of m until all of it carries this launch's tag
     float mv[IT2][NB][8];
     {
-        // one wave per workgroup first watches the last row of every producer group, sleeping between looks, while
+        // one wave per workgroup first watches the producers' indicator entries (its copy of them), sleeping between looks, while
         // the others wait at the barrier: 130 000 threads polling from the moment they are done would slow the
         // stores they are waiting for
         if (wave == 0) {
