@@ -532,6 +532,7 @@ struct SegAttnArgs {
     int nq, nkv, n_chunks;
     uint2 *pml_ll;                      // [nkv][n_chunks][16] x {(max, tag), (sum, tag)}
     uint2 *po_ll;                       // [nkv][n_chunks][G][128] tagged partial outputs
+    uint2 *ind_ll;                      // [kSegIndCopies][kSegIndStride] one entry per partial: that workgroup has stored it
     float *out_attn;                    // [QD] merged attention output, stored by workgroup 0
     float *out;                         // [H] O projection
     int H, QR, QD;
@@ -1022,14 +1023,18 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
             for (int j = 0; j < 4; ++j) ll_store(dst + j, v[j], a.tag);
         }
         if (lost && lane == 0) atomicOr(a.err, 2u);
+        // all waves have issued their stores of this partial: say so in every copy of the indicator array, so that the
+        // watchers below do not all poll the same lines
+        __syncthreads();
+        if (tid < kSegIndCopies) ll_store(a.ind_ll + tid * kSegIndStride + kvh * nc + c, 0.f, a.tag);
     }
 
     // ---- phase 3: merge of the chunk partials (once per workgroup, into LDS), then the O rows
     {
         constexpr int MB = 8;
         bool lost = false;
-        // While the attention runs, one wave per workgroup watches the last value of every partial, sleeping between
-        // looks; the others wait at the barrier.  (All threads polling their own values from the start kept the memory
+        // While the attention runs, one wave per workgroup watches the indicator entry of every partial (in its copy of
+        // them), sleeping between looks; the others wait at the barrier.  (All threads polling their own values from the start kept the memory
         // side so busy that the attention workgroups' tagged stores took 15 us to get through.)
         if (wave == 0) {
             const int n_part = nkv * nc;
@@ -1038,7 +1043,7 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
                 bool mine = true;
                 for (int pi = lane; pi < n_part; pi += 64) {
                     uint2 v;
-                    ll_issue1(v, a.po_ll + ((size_t)pi * G + (G - 1)) * 128 + 127);
+                    ll_issue1(v, a.ind_ll + (blockIdx.x % kSegIndCopies) * kSegIndStride + pi);
                     asm volatile("s_waitcnt vmcnt(0)" : "+v"(v) : : "memory");
                     if (v.y != a.tag) mine = false;
                 }
@@ -1191,18 +1196,20 @@ static hipError_t seg_attn_pick(const SegAttnArgs &a, bool wait, int blocks, hip
 
 hipError_t launch_seg_attn(Mat Wq, Mat Wo, const float *res, const float *delta, const uint16_t *gain, float eps,
                            float *out_res, float *out_h, void *qkv_ll, const float2 *rope, KvView kv, int nq, int nkv,
-                           int n_chunks, void *pml_ll, void *po_ll, float *out_attn, float *out, int H, unsigned tag,
+                           int n_chunks, void *pml_ll, void *po_ll, void *ind_ll, float *out_attn, float *out, int H, unsigned tag,
                            unsigned *err, const GemvWait *wait, bool hold_kv, bool hold_o, uint32_t poll_iters, int blocks, hipStream_t s)
 {
     SegAttnArgs a{};
     a.Wq = Wq.w; a.Wo = Wo.w; a.sq = Wq.scale; a.so = Wo.scale;
     a.res = res; a.delta = delta; a.gain = gain; a.eps = eps; a.out_res = out_res; a.out_h = out_h;
     a.qkv_ll = static_cast<uint2 *>(qkv_ll); a.rope = rope; a.kv = kv; a.nq = nq; a.nkv = nkv; a.n_chunks = n_chunks;
-    a.pml_ll = static_cast<uint2 *>(pml_ll); a.po_ll = static_cast<uint2 *>(po_ll); a.out_attn = out_attn; a.out = out;
+    a.pml_ll = static_cast<uint2 *>(pml_ll); a.po_ll = static_cast<uint2 *>(po_ll); a.ind_ll = static_cast<uint2 *>(ind_ll);
+    a.out_attn = out_attn; a.out = out;
     a.H = H; a.QR = (nq + 2 * nkv) * 128; a.QD = nq * 128; a.tag = tag; a.ll_iters = poll_iters; a.err = err;
     if (wait) a.wait = SegWait{wait->done, wait->seq, wait->iters, wait->ticks};
     a.hold_kv = hold_kv ? 1 : 0;
     a.hold_o = hold_o ? 1 : 0;
+    if (nkv * n_chunks > kSegIndStride) return hipErrorInvalidValue;
     return Wq.scale ? seg_attn_pick<true>(a, wait != nullptr, blocks, s) : seg_attn_pick<false>(a, wait != nullptr, blocks, s);
 }
 
