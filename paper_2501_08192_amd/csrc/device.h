@@ -81,6 +81,72 @@ __device__ __forceinline__ float wave_sum(float v)
     return (r0 + r1) + (r2 + r3);
 }
 
+// Sums over the 64 lanes of a wave of N values per lane at once (N = 2, 4, 8 or 16), scattered: lane l < N returns the
+// total of v[scatter_index(l)].  Every step halves what a lane carries: it keeps the values of one class and adds its
+// partner's partial sums of them, so the whole reduction costs ~4N + 10 vector instructions and two LDS-pipe shuffles
+// instead of N times the eleven of wave_sum (measured on 16 values, beside the 16 dot products that produce them: 0.25 us
+// instead of 1.0 us per workgroup of 8 waves).  The partners are those of wave_sum -- quad swaps, half-row and row
+// mirrors, then the rows -- and the classes are chosen so that a partner always holds the class a lane keeps (the
+// mirrors flip the low lane bits as well: class bit 0 = l0 ^ l2, bit 1 = l1 ^ l2, bit 2 = l2 ^ l3, bit 3 = l3).  Every
+// total is summed in the same tree as wave_sum's, so the two give the same bits.  All lanes active.
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float v)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xf, 0xf, true));
+}
+template <int K>
+__device__ __forceinline__ float lane_partner(float v, int lane)
+{
+    if constexpr (K == 0) return dpp_get<0xB1>(v);          // quad_perm [1,0,3,2]
+    else if constexpr (K == 1) return dpp_get<0x4E>(v);     // quad_perm [2,3,0,1]
+    else if constexpr (K == 2) return dpp_get<0x141>(v);    // row_half_mirror
+    else if constexpr (K == 3) return dpp_get<0x140>(v);    // row_mirror
+    else if constexpr (K == 4) return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), 0x401F));   // lane ^ 16
+    else return __int_as_float(__builtin_amdgcn_ds_bpermute((lane ^ 32) << 2, __float_as_int(v)));
+}
+template <int N, int K>
+__device__ __forceinline__ float wave_sum_scatter_step(const float (&cur)[N], int lane)
+{
+    if constexpr (N > 1) {
+        float nxt[N / 2];
+        const bool up = K == 0 ? ((lane ^ (lane >> 2)) & 1) : K == 1 ? (((lane >> 1) ^ (lane >> 2)) & 1)
+                      : K == 2 ? (((lane >> 2) ^ (lane >> 3)) & 1) : ((lane >> 3) & 1);
+#pragma unroll
+        for (int m = 0; m < N / 2; ++m) {
+            const float keep = up ? cur[2 * m + 1] : cur[2 * m], send = up ? cur[2 * m] : cur[2 * m + 1];
+            nxt[m] = keep + lane_partner<K>(send, lane);
+        }
+        return wave_sum_scatter_step<N / 2, K + 1>(nxt, lane);
+    } else {
+        float v = cur[0];
+        if constexpr (K <= 0) v += lane_partner<0>(v, lane);
+        if constexpr (K <= 1) v += lane_partner<1>(v, lane);
+        if constexpr (K <= 2) v += lane_partner<2>(v, lane);
+        if constexpr (K <= 3) v += lane_partner<3>(v, lane);
+        if constexpr (K <= 4) v += lane_partner<4>(v, lane);
+        v += lane_partner<5>(v, lane);
+        return v;
+    }
+}
+template <int N>
+__device__ __forceinline__ float wave_sum_scatter(const float (&v)[N], int lane)
+{
+    static_assert(N == 1 || N == 2 || N == 4 || N == 8 || N == 16, "one value per lane of a 16-lane row at most");
+    return wave_sum_scatter_step<N, 0>(v, lane);
+}
+// Which of the N values lane l (any lane; lanes l < N are one holder of each) holds after wave_sum_scatter<N>.
+template <int N>
+__device__ __forceinline__ int scatter_index(int l)
+{
+    return (((l ^ (l >> 2)) & 1) | ((((l >> 1) ^ (l >> 2)) & 1) << 1) | ((((l >> 2) ^ (l >> 3)) & 1) << 2) | (((l >> 3) & 1) << 3)) & (N - 1);
+}
+// ... and the lane below N that holds value j.
+__device__ __forceinline__ int scatter_holder(int j)
+{
+    const int l3 = (j >> 3) & 1, l2 = ((j >> 2) & 1) ^ l3, l1 = ((j >> 1) & 1) ^ l2, l0 = (j & 1) ^ l2;
+    return l0 | (l1 << 1) | (l2 << 2) | (l3 << 3);
+}
+
 // Two values as a pair of packed bf16 words: hi = their bf16 roundings, lo = the bf16 roundings of what is left.
 __device__ __forceinline__ void pack_split(float a, float b, uint32_t &hi, uint32_t &lo)
 {

@@ -304,8 +304,14 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
                     float s = 0.f;
 #pragma unroll
                     for (int it = 0; it < IT1; ++it) s = dot8(w1[it][q][r], xv[it][b], s);
-                    acc[q][r][b] = wave_sum(s);
+                    acc[q][r][b] = s;
                 }
+        // the 2 * RB1 * NB sums over the wave at once: lane l < N1 holds the one of index l = (q * RB1 + r) * NB + b
+        constexpr int N1 = 2 * RB1 * NB, CS1 = N1 < 16 ? N1 : 16, NC1 = N1 / CS1;     // in chunks of 16: lane l < CS1, chunk c: index c * CS1 + l
+        float tot1[NC1];
+#pragma unroll
+        for (int c = 0; c < NC1; ++c)
+            tot1[c] = wave_sum_scatter<CS1>(reinterpret_cast<const float (&)[CS1]>((&acc[0][0][0])[c * CS1]), lane);
         const int rows_here = r1;
         r1 += RB1;
         const float sg_now = sc1[0], su_now = sc1[1];
@@ -314,27 +320,31 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
             scales1(r1);
         }
         if (wpg1 == 1) {
-            if (lane == 0)
-#pragma unroll
-                for (int r = 0; r < RB1; ++r)
-                    if (rows_here + r < re1)
-#pragma unroll
-                        for (int b = 0; b < NB; ++b) {
-                            float v = acc[0][r][b], u = acc[1][r][b];
-                            if (W8) {
-                                v *= a.sg[rows_here + r];
-                                u *= a.su[rows_here + r];
-                            }
-                            ll_store(a.m_ll + (size_t)b * F + rows_here + r, silu_mul(v, u), a.tag);
-                        }
+            // the gate sum of index i = r * NB + b (chunk i / CS1) and the up sum, RB1 * NB further on, into one lane
+            constexpr int HALF1 = RB1 * NB;
+            const int i1 = scatter_index<CS1>(lane);
+            float gate1 = tot1[0], up1;
+            if constexpr (NC1 == 1) {
+                up1 = __int_as_float(__builtin_amdgcn_ds_bpermute(scatter_holder((i1 + HALF1) & (CS1 - 1)) << 2, __float_as_int(tot1[0])));
+            } else {
+                static_assert(NC1 == 1 || (NC1 == 2 && HALF1 == 16), "gate sums in the first chunk, up sums in the second");
+                up1 = tot1[NC1 - 1];
+            }
+            if (lane < CS1 && i1 < HALF1) {
+                const int r = i1 / NB, b = i1 % NB;
+                if (rows_here + r < re1) {
+                    float v = gate1, u = up1;
+                    if (W8) {
+                        v *= a.sg[rows_here + r];
+                        u *= a.su[rows_here + r];
+                    }
+                    ll_store(a.m_ll + (size_t)b * F + rows_here + r, silu_mul(v, u), a.tag);
+                }
+            }
         } else {
-            if (lane == 0)
+            if (lane < CS1)
 #pragma unroll
-                for (int q = 0; q < 2; ++q)
-#pragma unroll
-                    for (int r = 0; r < RB1; ++r)
-#pragma unroll
-                        for (int b = 0; b < NB; ++b) red[wave][(q * RB1 + r) * NB + b] = acc[q][r][b];
+                for (int c = 0; c < NC1; ++c) red[wave][c * CS1 + scatter_index<CS1>(lane)] = tot1[c];
             __syncthreads();
             if (lg1 < RB1 * NB) {
                 const int r = lg1 / NB, b = lg1 % NB;
@@ -413,8 +423,11 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
                 float s = 0.f;
 #pragma unroll
                 for (int it = 0; it < IT2; ++it) s = dot8(w2[it][r], mv[it][b], s);
-                acc[r][b] = wave_sum(s);
+                acc[r][b] = s;
             }
+        constexpr int N2 = RB2 * NB;        // lane l < N2 holds the sum of index l = r * NB + b
+        static_assert(N2 <= 16, "one scatter sum");
+        const float tot2 = wave_sum_scatter<N2>(reinterpret_cast<const float (&)[N2]>(acc), lane);
         const int rows_here = r2;
         r2 += RB2;
         const float sd_now = sc2;
@@ -423,22 +436,16 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
             scales2(r2);
         }
         if (wpg2 == 1) {
-            if (lane == 0)
-#pragma unroll
-                for (int r = 0; r < RB2; ++r)
-                    if (rows_here + r < re2)
-#pragma unroll
-                        for (int b = 0; b < NB; ++b) {
-                            float v = acc[r][b];
-                            if (W8) v *= a.sd[rows_here + r];
-                            a.out[(size_t)b * H + rows_here + r] = v;
-                        }
+            if (lane < N2) {
+                const int i2 = scatter_index<N2>(lane), r = i2 / NB, b = i2 % NB;
+                if (rows_here + r < re2) {
+                    float v = tot2;
+                    if (W8) v *= a.sd[rows_here + r];
+                    a.out[(size_t)b * H + rows_here + r] = v;
+                }
+            }
         } else {
-            if (lane == 0)
-#pragma unroll
-                for (int r = 0; r < RB2; ++r)
-#pragma unroll
-                    for (int b = 0; b < NB; ++b) red[wave][r * NB + b] = acc[r][b];
+            if (lane < N2) red[wave][scatter_index<N2>(lane)] = tot2;
             __syncthreads();
             if (lg2 < RB2 * NB) {
                 const int r = lg2 / NB, b = lg2 % NB;
