@@ -344,8 +344,15 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
                     float s = 0.f;
 #pragma unroll
                     for (int it = 0; it < ITERS; ++it) s = dot8(wv[it][q][r], xv[it][b], s);
-                    acc[q][r][b] = wave_sum(s);
+                    acc[q][r][b] = s;
                 }
+        // all sums of the pass over the wave at once, in chunks of up to 16 values: lane l < CS holds, of chunk c, the
+        // value of index c * CS + scatter_index<CS>(l), index = (q * RB + r) * NB + b
+        constexpr int NT = NW * RB * NB, CS = NT < 16 ? NT : 16, NC = NT / CS, HALF = RB * NB;
+        float tot[NC];
+#pragma unroll
+        for (int c = 0; c < NC; ++c) tot[c] = wave_sum_scatter<CS>(reinterpret_cast<const float (&)[CS]>((&acc[0][0][0])[c * CS]), lane);
+        const int li = scatter_index<CS>(lane);
         const int rows_here = r0;
         r0 += RB;
         float sc_now[NW];
@@ -357,28 +364,28 @@ __global__ __launch_bounds__(512) void k_gemv(GemvArgs a)
         }
 
         if (wpg == 1) {
-            if (lane == 0)
 #pragma unroll
-                for (int r = 0; r < RB; ++r)
-                    if (rows_here + r < row_end)
-#pragma unroll
-                        for (int b = 0; b < NB; ++b) {
-                            float v = acc[0][r][b], u = SWIGLU ? acc[NW - 1][r][b] : 0.f;
-                            if (W8) {   // one wave per row group: a rare shape, the scale is fetched late
-                                v *= a.scale[rows_here + r];
-                                if (SWIGLU) u *= a.scale2[rows_here + r];
-                            }
-                            if (SWIGLU) v = silu_mul(v, u);
-                            a.out[(size_t)b * N + rows_here + r] = v;
-                        }
+            for (int c = 0; c < NC; ++c) {
+                if (c * CS >= HALF) continue;               // the chunks of the first (or only) matrix
+                const int i = c * CS + li, r = i / NB, b = i % NB;
+                float v = tot[c], u = 0.f;
+                if constexpr (SWIGLU) {                    // the second matrix's sum of the same row: HALF indices further on
+                    if constexpr (HALF >= CS) u = tot[c + HALF / CS];
+                    else u = __int_as_float(__builtin_amdgcn_ds_bpermute(scatter_holder((li + HALF) & (CS - 1)) << 2, __float_as_int(tot[c])));
+                }
+                if (lane < CS && i < HALF && rows_here + r < row_end) {
+                    if (W8) {   // one wave per row group: a rare shape, the scale is fetched late
+                        v *= a.scale[rows_here + r];
+                        if (SWIGLU) u *= a.scale2[rows_here + r];
+                    }
+                    if (SWIGLU) v = silu_mul(v, u);
+                    a.out[(size_t)b * N + rows_here + r] = v;
+                }
+            }
         } else {
-            if (lane == 0)
+            if (lane < CS)
 #pragma unroll
-                for (int q = 0; q < NW; ++q)
-#pragma unroll
-                    for (int r = 0; r < RB; ++r)
-#pragma unroll
-                        for (int b = 0; b < NB; ++b) red[wave][(q * RB + r) * NB + b] = acc[q][r][b];
+                for (int c = 0; c < NC; ++c) red[wave][c * CS + li] = tot[c];
             __syncthreads();
             if (lg < RB * NB) {
                 const int r = lg / NB, b = lg % NB;

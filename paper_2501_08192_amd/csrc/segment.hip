@@ -804,8 +804,9 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
             float s = 0.f;
 #pragma unroll
             for (int it = 0; it < ITQ; ++it) s = dot8(w1[it][r], xv[it], s);
-            acc[r] = wave_sum(s);
+            acc[r] = s;
         }
+        const float tot1 = wave_sum_scatter<RBQ>(acc, lane);      // lane l < RBQ: the sum of row scatter_index<RBQ>(l)
         const int rows_here = r1;
         r1 += RBQ;
         const float sc_now = sc1;
@@ -814,18 +815,14 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
             scales1(r1);
         }
         if (wpg1 == 1) {
-            if (lane == 0)
-#pragma unroll
-                for (int r = 0; r < RBQ; ++r)
-                    if (rows_here + r < re1) {
-                        float v = acc[r];
-                        if (W8) v *= a.sq[rows_here + r];
-                        ll_store(a.qkv_ll + rows_here + r, v, a.tag);
-                    }
+            const int r = scatter_index<RBQ>(lane);
+            if (lane < RBQ && rows_here + r < re1) {
+                float v = tot1;
+                if (W8) v *= a.sq[rows_here + r];
+                ll_store(a.qkv_ll + rows_here + r, v, a.tag);
+            }
         } else {
-            if (lane == 0)
-#pragma unroll
-                for (int r = 0; r < RBQ; ++r) red[wave][r] = acc[r];
+            if (lane < RBQ) red[wave][scatter_index<RBQ>(lane)] = tot1;
             __syncthreads();
             if (lg1 < RBQ && rows_here + lg1 < re1) {
                 float v = 0.f;
@@ -1115,7 +1112,8 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
         for (int pass = 0; pass < a.go.passes; ++pass) {
             float acc[RBO];
 #pragma unroll
-            for (int r = 0; r < RBO; ++r) acc[r] = wave_sum(dot8(w3[r], xo, 0.f));
+            for (int r = 0; r < RBO; ++r) acc[r] = dot8(w3[r], xo, 0.f);
+            const float tot3 = wave_sum_scatter<RBO>(acc, lane);
             const int rows_here = r3;
             r3 += RBO;
             const float sc_now = sc3;
@@ -1124,18 +1122,14 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
                 scales3(r3);
             }
             if (wpg3 == 1) {
-                if (lane == 0)
-#pragma unroll
-                    for (int r = 0; r < RBO; ++r)
-                        if (rows_here + r < re3) {
-                            float v = acc[r];
-                            if (W8) v *= a.so[rows_here + r];
-                            a.out[rows_here + r] = v;
-                        }
+                const int r = scatter_index<RBO>(lane);
+                if (lane < RBO && rows_here + r < re3) {
+                    float v = tot3;
+                    if (W8) v *= a.so[rows_here + r];
+                    a.out[rows_here + r] = v;
+                }
             } else {
-                if (lane == 0)
-#pragma unroll
-                    for (int r = 0; r < RBO; ++r) red[wave][r] = acc[r];
+                if (lane < RBO) red[wave][scatter_index<RBO>(lane)] = tot3;
                 __syncthreads();
                 if (lg3 < RBO && rows_here + lg3 < re3) {
                     float v = 0.f;
