@@ -58,7 +58,7 @@ import json
 import os
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "measured_mi355x.json")
-TOL = 0.15      # relative error allowed per row and mode (worst: 14.7 %, batch 64 at a short context)
+TOL = 0.15      # relative error allowed per row and mode (worst: 14.6 %, batch 64 at a short context)
 
 
 def _golden():
