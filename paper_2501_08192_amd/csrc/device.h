@@ -197,6 +197,17 @@ __device__ __forceinline__ void st_wt4(void *p, uint32_t v)
 {
     asm volatile("global_store_dword %0, %1, off sc0 sc1" ::"v"(p), "v"(v) : "memory");
 }
+__device__ __forceinline__ void st_wt8(void *p, uint2 v)
+{
+    typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+    const u32x2_t w = {v.x, v.y};
+    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" ::"v"(p), "v"(w) : "memory");
+}
+__device__ __forceinline__ void st_wt16(void *p, float4 v)
+{
+    const f32x4 w = {v.x, v.y, v.z, v.w};
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(w) : "memory");
+}
 template <bool WT = false>
 __device__ __forceinline__ void store_digits4(uint8_t *base, size_t plane, int K, size_t row, int k0, float4 v)
 {

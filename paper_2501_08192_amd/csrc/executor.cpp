@@ -59,6 +59,8 @@ Workspace layout_workspace(const psv_model_desc &d)
         w.pml_ll = take(d.n_kv_heads * nc * 16 * 2 * 8);
         w.po_ll = take(d.n_kv_heads * nc * G * 128 * 8);
         w.seg_ind = take((size_t)kSegIndCopies * kSegIndStride * 8);     // its indicator entries: copies x partials
+        w.seg_pml = take(d.n_kv_heads * nc * 16 * 8);                    // ... its partials as plain data: (max, sum) pairs
+        w.seg_po = take(d.n_kv_heads * nc * G * 128 * 4);                 // ... and outputs
     }
     w.step_tbl = take((size_t)d.n_layers * kStepLayerBytes);   // per-layer pointers of the whole-step kernel
     w.step_ll = take((2 * H + 2) * 8);                         // ... its tagged projection outputs and window-end words
@@ -555,7 +557,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
             // QKV + rotary embedding + KV append + attention + merge + O in one launch (profiled as the QKV operator)
             const bool from_window = wait_qkv && l > lb;
             HIP_TRY(launch_seg_attn(Wqkv, Wo, res, delta, u16(w.g_attn), d.rms_eps, x, h1, c->at<void>(c->ws.qkv_ll), rope, kv, nq, nkv,
-                                    seg_nc, c->at<void>(c->ws.pml_ll), c->at<void>(c->ws.po_ll), c->at<void>(c->ws.seg_ind), attn, delta_a, H,
+                                    seg_nc, c->at<void>(c->ws.seg_pml), c->at<void>(c->ws.seg_po), c->at<void>(c->ws.seg_ind), attn, delta_a, H,
                                     next_tag(), errw,
                                     wait_qkv ? &wait : nullptr, from_window && plan_has_whole(c, l - 1, 1, l, PSV_OP_ATTN),
                                     from_window && plan_has_whole(c, l - 1, 1, l, PSV_OP_O), poll_iters, blocks, s));

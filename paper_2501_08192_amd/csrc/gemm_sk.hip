@@ -24,17 +24,6 @@ namespace psv {
 // kernel proceeds when every entry it polls carries the tag of this launch.  No fence and no counter: a release fence makes every wave write back its XCD's L2 and a device-scope
 // counter serialises at the memory side -- measured 25-55 ns per workgroup either way, 7 us per layer at batch 8 and
 // 25 us at batch 32.
-__device__ __forceinline__ void st_wt16(void *p, float4 v)
-{
-    const f32x4 w = {v.x, v.y, v.z, v.w};
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1" ::"v"(p), "v"(w) : "memory");
-}
-__device__ __forceinline__ void st_wt8(void *p, uint2 v)
-{
-    typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
-    const u32x2_t w = {v.x, v.y};
-    asm volatile("global_store_dwordx2 %0, %1, off sc0 sc1" ::"v"(p), "v"(w) : "memory");
-}
 
 template <bool SIGNAL>
 __global__ __launch_bounds__(128) void k_resid_sum(const float *__restrict__ res, const float *__restrict__ delta,

@@ -107,8 +107,8 @@ hipError_t launch_seg_mlp(Mat Wg, Mat Wu, Mat Wd, const float *res, const float 
 
 // Attention block of one sequence: x = res + delta; h = rmsnorm(x) * gain; qkv = Wq h; rotary embedding, KV append and
 // decode attention over 256-token chunks (workgroup kvh * n_chunks + c runs chunk c of kv head kvh); out = Wo attn.
-// qkv_ll: [QR] pairs; pml_ll: [nkv][n_chunks][16][2] pairs; po_ll: [nkv][n_chunks][G][128] pairs;
-// ind_ll: kSegIndCopies x kSegIndStride indicator pairs (one entry per partial in every copy).  bf16 cache only.
+// qkv_ll: [QR] pairs; pml: [nkv][n_chunks][16] (max, sum) float pairs and po: [nkv][n_chunks][G][128] floats
+// (plain data, the kernel's own); ind_ll: kSegIndCopies x kSegIndStride indicator pairs (one entry per partial in every copy).  bf16 cache only.
 // hold_kv / hold_o: see hold_down.
 int seg_attn_chunks(uint32_t max_seq);
 bool seg_attn_supported(int batch, int H, int nq, int nkv, uint32_t max_seq, bool kv_int8, int blocks);
@@ -116,7 +116,7 @@ bool seg_attn_holds_o(int H, int nq, bool w8, int blocks);      // the first pas
 bool seg_attn_holds_qkv(int H, int QR, bool w8, int blocks);    // ... of the QKV projection all of W_qkv
 hipError_t launch_seg_attn(Mat Wq, Mat Wo, const float *res, const float *delta, const uint16_t *gain, float eps,
                            float *out_res, float *out_h, void *qkv_ll, const float2 *rope, KvView kv, int nq, int nkv,
-                           int n_chunks, void *pml_ll, void *po_ll, void *ind_ll, float *out_attn, float *out, int H, unsigned tag,
+                           int n_chunks, void *pml, void *po, void *ind_ll, float *out_attn, float *out, int H, unsigned tag,
                            unsigned *err, const GemvWait *wait, bool hold_kv, bool hold_o, uint32_t poll_iters, int blocks, hipStream_t s);
 
 // ---- the whole step of one sequence as one kernel (step.hip): `blocks` resident workgroups walk layers [lb, le); the

@@ -537,8 +537,8 @@ struct SegAttnArgs {
     const float2 *rope;                 // [64] (cos, sin) at position T-1
     KvView kv;
     int nq, nkv, n_chunks;
-    uint2 *pml_ll;                      // [nkv][n_chunks][16] x {(max, tag), (sum, tag)}
-    uint2 *po_ll;                       // [nkv][n_chunks][G][128] tagged partial outputs
+    float2 *pml;                        // [nkv][n_chunks][16] (max, sum) of every partial and head
+    float *po;                          // [nkv][n_chunks][G][128] partial outputs
     uint2 *ind_ll;                      // [kSegIndCopies][kSegIndStride] one entry per partial: that workgroup has stored it
     float *out_attn;                    // [QD] merged attention output, stored by workgroup 0
     float *out;                         // [H] O projection
@@ -1017,18 +1017,18 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
                 float L = ls[0][i];
 #pragma unroll
                 for (int w = 1; w < 8; ++w) L += ls[w][i];
-                ll_store(a.pml_ll + (slot * 16 + i) * 2, M, a.tag);
-                ll_store(a.pml_ll + (slot * 16 + i) * 2 + 1, L, a.tag);
+                st_wt8(a.pml + slot * 16 + i, make_uint2(__float_as_uint(M), __float_as_uint(L)));
             }
             // wave w finishes and stores channel group w: ((0+4) + (1+5)) + ((2+6) + (3+7))
             const f32x4 v = (accs[0][wave][lane] + accs[1][wave][lane]) + (accs[2][wave][lane] + accs[3][wave][lane]);
-            uint2 *dst = a.po_ll + (slot * G + i) * 128 + wave * 16 + 4 * q4;
-#pragma unroll
-            for (int j = 0; j < 4; ++j) ll_store(dst + j, v[j], a.tag);
+            st_wt16(a.po + (slot * G + i) * 128 + wave * 16 + 4 * q4, make_float4(v[0], v[1], v[2], v[3]));
         }
         if (lost && lane == 0) atomicOr(a.err, 2u);
-        // all waves have issued their stores of this partial: say so in every copy of the indicator array, so that the
-        // watchers below do not all poll the same lines
+        // The partial itself is plain data, written through to the memory side; once every wave's stores are
+        // acknowledged the workgroup says so with a tagged entry in every copy of the indicator array (copies, so that the
+        // watchers below do not all poll the same lines).  The readers then use ordinary loads, which their XCD's L2 serves
+        // after the first: with tagged values and device-coherent loads 256 workgroups reading all 32 KB took 2.4 us.
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
         if (tid < kSegIndCopies) ll_store(a.ind_ll + tid * kSegIndStride + kvh * nc + c, 0.f, a.tag);
     }
@@ -1054,39 +1054,28 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
                 all = __all(mine);
                 if (!all) __builtin_amdgcn_s_sleep(16);
             }
+            if (!all) lost = true;          // a partial may be missing: results invalid
         }
         __syncthreads();
+        // every partial is complete at the memory side; nothing on this CU has read these addresses since the kernel started
         for (int ch = tid; ch < QD; ch += 512) {
             const int j = ch >> 7, c7 = ch & 127, hk = j / G, g = j % G;
-            const uint2 *mlp = a.pml_ll + (((size_t)hk * nc) * 16 + g) * 2;
-            const uint2 *op = a.po_ll + (((size_t)hk * nc) * G + g) * 128 + c7;
+            const float2 *mlp = a.pml + ((size_t)hk * nc) * 16 + g;
+            const float *op = a.po + (((size_t)hk * nc) * G + g) * 128 + c7;
             float Mx = -1.0e30f, den = 0.f, num = 0.f;
             for (int sp0 = 0; sp0 < nc; sp0 += MB) {
-                u32x4 ml[MB];
-                uint2 ov[MB];
-                bool all = false;
-                for (uint32_t spin = 0; !all && spin < a.ll_iters; ++spin) {
+                float2 ml[MB];
+                float ov[MB];
 #pragma unroll
-                    for (int u = 0; u < MB; ++u) {
-                        const int sp = min(sp0 + u, nc - 1);
-                        ll_issue(ml[u], mlp + (size_t)sp * 32);
-                        ll_issue1(ov[u], op + (size_t)sp * G * 128);
-                    }
-                    ll_wait_all();
-                    bool mine = true;
-#pragma unroll
-                    for (int u = 0; u < MB; ++u) {
-                        asm volatile("" : "+v"(ml[u]), "+v"(ov[u]));
-                        if (ml[u].y != a.tag || ml[u].w != a.tag || ov[u].y != a.tag) mine = false;
-                    }
-                    all = __all(mine);
-                    if (!all) __builtin_amdgcn_s_sleep(4);
+                for (int u = 0; u < MB; ++u) {
+                    const int sp = min(sp0 + u, nc - 1);
+                    ml[u] = mlp[(size_t)sp * 16];
+                    ov[u] = op[(size_t)sp * G * 128];
                 }
-                if (!all) lost = true;
                 float bm = Mx;
 #pragma unroll
                 for (int u = 0; u < MB; ++u)
-                    if (sp0 + u < nc) bm = fmaxf(bm, __uint_as_float(ml[u].x));
+                    if (sp0 + u < nc) bm = fmaxf(bm, ml[u].x);
                 const float rs = exp2f(Mx - bm);
                 Mx = bm;
                 den *= rs;
@@ -1094,10 +1083,10 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
 #pragma unroll
                 for (int u = 0; u < MB; ++u)
                     if (sp0 + u < nc) {
-                        const float lsum = __uint_as_float(ml[u].z);
-                        const float wgt = lsum > 0.f ? exp2f(__uint_as_float(ml[u].x) - Mx) : 0.f;
+                        const float lsum = ml[u].y;
+                        const float wgt = lsum > 0.f ? exp2f(ml[u].x - Mx) : 0.f;
                         den += wgt * lsum;
-                        num = fmaf(wgt, __uint_as_float(ov[u].x), num);
+                        num = fmaf(wgt, ov[u], num);
                     }
             }
             const float r = den > 0.f ? num / den : 0.f;
@@ -1197,14 +1186,14 @@ static hipError_t seg_attn_pick(const SegAttnArgs &a, bool wait, int blocks, hip
 
 hipError_t launch_seg_attn(Mat Wq, Mat Wo, const float *res, const float *delta, const uint16_t *gain, float eps,
                            float *out_res, float *out_h, void *qkv_ll, const float2 *rope, KvView kv, int nq, int nkv,
-                           int n_chunks, void *pml_ll, void *po_ll, void *ind_ll, float *out_attn, float *out, int H, unsigned tag,
+                           int n_chunks, void *pml, void *po, void *ind_ll, float *out_attn, float *out, int H, unsigned tag,
                            unsigned *err, const GemvWait *wait, bool hold_kv, bool hold_o, uint32_t poll_iters, int blocks, hipStream_t s)
 {
     SegAttnArgs a{};
     a.Wq = Wq.w; a.Wo = Wo.w; a.sq = Wq.scale; a.so = Wo.scale;
     a.res = res; a.delta = delta; a.gain = gain; a.eps = eps; a.out_res = out_res; a.out_h = out_h;
     a.qkv_ll = static_cast<uint2 *>(qkv_ll); a.rope = rope; a.kv = kv; a.nq = nq; a.nkv = nkv; a.n_chunks = n_chunks;
-    a.pml_ll = static_cast<uint2 *>(pml_ll); a.po_ll = static_cast<uint2 *>(po_ll); a.ind_ll = static_cast<uint2 *>(ind_ll);
+    a.pml = static_cast<float2 *>(pml); a.po = static_cast<float *>(po); a.ind_ll = static_cast<uint2 *>(ind_ll);
     a.out_attn = out_attn; a.out = out;
     a.H = H; a.QR = (nq + 2 * nkv) * 128; a.QD = nq * 128; a.tag = tag; a.ll_iters = poll_iters; a.err = err;
     if (wait) a.wait = SegWait{wait->done, wait->seq, wait->iters, wait->ticks};
