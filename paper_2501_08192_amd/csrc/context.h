@@ -19,7 +19,7 @@ struct Workspace {
     size_t total = 0;
     // offsets
     size_t x, y, h1_f32, h1_bf16, h2_f32, h2_bf16, qkv, rope, part_ml, part_o, attn_f32, attn_bf16,
-        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag, part, ssq, ssq_ll, m_ll, qkv_ll, pml_ll, po_ll, step_tbl, step_ll, seg_ind, seg_pml, seg_po;
+        delta_a, delta_m, m_f32, m_bf16, inv_freq, flag, part, ssq, ssq_ll, m_ll, qkv_ll, pml_ll, po_ll, step_tbl, step_ll, seg_ind, seg_pml, seg_po, seg_m;
 };
 
 Workspace layout_workspace(const psv_model_desc &d);

@@ -53,6 +53,7 @@ Workspace layout_workspace(const psv_model_desc &d)
     w.ssq = take(B * (H / 512) * 4);
     w.ssq_ll = take(kSkTagCopies * sk_tag_stride((int)B, (int)H) * 8);     // the same as tagged values (in copies), for a projection launched ahead of them
     w.m_ll = take(B * F * 8 + (size_t)kSegIndCopies * kSegIndStride * 8);   // tagged values of the fused MLP kernel + its indicator entries
+    w.seg_m = take(B * F * 4);              // silu(gate) * up of the fused MLP kernel as plain data
     {                                       // ... and of the fused attention-block kernel (one sequence)
         const size_t nc = (size_t)seg_attn_chunks(d.max_seq);
         w.qkv_ll = take(QR * 8);
@@ -617,7 +618,7 @@ psv_status enqueue_step(psv_ctx *c, const float *x_in, float *x_out, uint32_t ba
         ST_TRY(prof_tag(c, PSV_OP_GATE));
         if (seg_mlp) {
             // gate/up + SwiGLU + down in one launch (profiled as the gate/up operator; down has no kernel of its own)
-            HIP_TRY(launch_seg_mlp(Wg, Wu, Wd, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, c->at<void>(c->ws.m_ll), delta_m, B, H, F,
+            HIP_TRY(launch_seg_mlp(Wg, Wu, Wd, x, delta_a, u16(w.g_mlp), d.rms_eps, y, h2, c->at<float>(c->ws.seg_m), c->at<void>(c->ws.m_ll), delta_m, B, H, F,
                                    next_tag(), errw, wait_gate ? &wait : nullptr, plan_has_whole(c, l, 0, l, PSV_OP_DOWN), poll_iters, blocks, s));
             wait_gate = false;
         } else if (vec) {

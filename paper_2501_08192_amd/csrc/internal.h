@@ -91,8 +91,8 @@ hipError_t launch_gemv_merge(Mat W, const float *part_ml, const float *part_o, i
 constexpr uint32_t kSegPollIters = 1u << 16;
 unsigned next_tag();
 constexpr int kSegIndCopies = 8, kSegIndStride = 512;    // indicator entries behind m_ll: copies x workgroups (launch_seg_mlp)
-// MLP block: y = res + delta; h = rmsnorm(y) * gain; m = silu(Wg h) * (Wu h); out = Wd m.  m_ll: [batch][F] pairs,
-// followed by kSegIndCopies x kSegIndStride indicator pairs (blocks <= kSegIndStride).
+// MLP block: y = res + delta; h = rmsnorm(y) * gain; m = silu(Wg h) * (Wu h); out = Wd m.  m: [batch][F] floats (the kernel's
+// own hand-over buffer); m_ll: [batch][F] pairs (unused here) followed by kSegIndCopies x kSegIndStride indicator pairs (blocks <= kSegIndStride).
 // wait != null: launched into the window ahead of its inputs, see GemvWait; hold_down = false makes that variant
 // request the down weights only after the window's end (the plan did not hand them to this window).
 // poll_iters: bound of every hand-over poll (kSegPollIters; 0 makes every hand-over expire at once -- a test aid).
@@ -102,7 +102,7 @@ bool seg_mlp_supported(int batch, int H, int F);
 bool seg_mlp_holds_gate_up(int H, int F, bool w8, int blocks);
 bool seg_mlp_holds_down(int H, int F, bool w8, int blocks);
 hipError_t launch_seg_mlp(Mat Wg, Mat Wu, Mat Wd, const float *res, const float *delta, const uint16_t *gain, float eps,
-                          float *out_res, float *out_h, void *m_ll, float *out, int batch, int H, int F, unsigned tag,
+                          float *out_res, float *out_h, float *m, void *m_ll, float *out, int batch, int H, int F, unsigned tag,
                           unsigned *err, const GemvWait *wait, bool hold_down, uint32_t poll_iters, int blocks, hipStream_t s);
 
 // Attention block of one sequence: x = res + delta; h = rmsnorm(x) * gain; qkv = Wq h; rotary embedding, KV append and

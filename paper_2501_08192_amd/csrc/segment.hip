@@ -68,7 +68,8 @@ struct SegMlpArgs {
     const uint16_t *gain;               // [H]
     float eps;
     float *out_res, *out_h;             // res + delta and the normalised activations, stored by workgroup 0
-    uint2 *m_ll;                        // [NB][F] tagged silu(gate) * up, then kSegIndCopies x kSegIndStride indicator entries
+    float *m;                           // [NB][F] silu(gate) * up: plain data, written through, complete when the indicators say so
+    uint2 *m_ll;                        // behind [NB][F] unused pairs: kSegIndCopies x kSegIndStride tagged indicator entries
     float *out;                         // [NB][H] down projection
     int F, H;
     SegGeom g1, g2;
@@ -338,7 +339,7 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
                         v *= a.sg[rows_here + r];
                         u *= a.su[rows_here + r];
                     }
-                    ll_store(a.m_ll + (size_t)b * F + rows_here + r, silu_mul(v, u), a.tag);
+                    st_wt4(a.m + (size_t)b * F + rows_here + r, __float_as_uint(silu_mul(v, u)));
                 }
             }
         } else {
@@ -358,15 +359,18 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
                         v *= sg_now;
                         u *= su_now;
                     }
-                    ll_store(a.m_ll + (size_t)b * F + rows_here + r, silu_mul(v, u), a.tag);
+                    st_wt4(a.m + (size_t)b * F + rows_here + r, __float_as_uint(silu_mul(v, u)));
                 }
             }
             __syncthreads();
         }
     }
 
-    // this workgroup has issued all its stores of m: say so in the indicator array behind m ([copy][workgroup], kSegIndCopies
-    // copies written by as many lanes at once, so that the watchers below do not all poll the same lines)
+    // this workgroup's part of m is at the memory side once its stores are acknowledged: it says so in the indicator array
+    // ([copy][workgroup], kSegIndCopies copies written by as many lanes at once, so that the watchers below do not all
+    // poll the same lines)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
     if (tid < kSegIndCopies) ll_store(a.m_ll + (size_t)NB * F + tid * kSegIndStride + blockIdx.x, 0.f, a.tag);
 
     // ---- hand-over: every thread polls its slice of m until all of it carries this launch's tag
@@ -393,24 +397,23 @@ __global__ __launch_bounds__(512) void k_seg_mlp(SegMlpArgs a)
                 ready = __all(mine);
                 if (!ready) __builtin_amdgcn_s_sleep(8);
             }
+            if (!ready && lane == 0) atomicOr(a.err, 2u);       // part of m may be missing: results invalid
         }
         __syncthreads();
-        bool all = false;
-        for (uint32_t spin = 0; !all && spin < a.ll_iters; ++spin) {
-            all = true;
+        // all of m is complete at the memory side and nothing on this CU has read it since the kernel started: ordinary
+        // loads, served by the XCD's L2 after the first workgroup's
 #pragma unroll
-            for (int it = 0; it < IT2; ++it)
+        for (int it = 0; it < IT2; ++it)
 #pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    if (ok2[it]) {
-                        if (!ll_read8(a.m_ll + (size_t)b * F + k2[it], a.tag, mv[it][b])) all = false;
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) mv[it][b][e] = 0.f;
-                    }
+            for (int b = 0; b < NB; ++b) {
+                float4 m0 = make_float4(0.f, 0.f, 0.f, 0.f), m1 = m0;
+                if (ok2[it]) {
+                    m0 = *reinterpret_cast<const float4 *>(a.m + (size_t)b * F + k2[it]);
+                    m1 = *reinterpret_cast<const float4 *>(a.m + (size_t)b * F + k2[it] + 4);
                 }
-        }
-        if (!all) atomicOr(a.err, 2u);
+                mv[it][b][0] = m0.x; mv[it][b][1] = m0.y; mv[it][b][2] = m0.z; mv[it][b][3] = m0.w;
+                mv[it][b][4] = m1.x; mv[it][b][5] = m1.y; mv[it][b][6] = m1.z; mv[it][b][7] = m1.w;
+            }
     }
 
     // ---- phase 2: down rows
@@ -506,13 +509,13 @@ static hipError_t seg_mlp_pick(const SegMlpArgs &a, bool wait, int blocks, hipSt
 }
 
 hipError_t launch_seg_mlp(Mat Wg, Mat Wu, Mat Wd, const float *res, const float *delta, const uint16_t *gain, float eps,
-                          float *out_res, float *out_h, void *m_ll, float *out, int batch, int H, int F, unsigned tag,
+                          float *out_res, float *out_h, float *m, void *m_ll, float *out, int batch, int H, int F, unsigned tag,
                           unsigned *err, const GemvWait *wait, bool hold_down, uint32_t poll_iters, int blocks, hipStream_t s)
 {
     SegMlpArgs a{};
     a.Wg = Wg.w; a.Wu = Wu.w; a.Wd = Wd.w; a.sg = Wg.scale; a.su = Wu.scale; a.sd = Wd.scale;
     a.res = res; a.delta = delta; a.gain = gain; a.eps = eps; a.out_res = out_res; a.out_h = out_h;
-    a.m_ll = static_cast<uint2 *>(m_ll); a.out = out; a.F = F; a.H = H; a.tag = tag; a.ll_iters = poll_iters; a.err = err;
+    a.m = m; a.m_ll = static_cast<uint2 *>(m_ll); a.out = out; a.F = F; a.H = H; a.tag = tag; a.ll_iters = poll_iters; a.err = err;
     if (wait) a.wait = SegWait{wait->done, wait->seq, wait->iters, wait->ticks};
     a.hold_down = hold_down ? 1 : 0;
     if (batch != 1 || blocks > kSegIndStride) return hipErrorInvalidValue;
