@@ -12,21 +12,24 @@
 //    communication window (policy.prelaunch), sits in registers before the window ends: the register file is the
 //    large on-chip memory of this machine (Section 3, "Execution with the proposed method", with the registers in
 //    the role of the paper's L2);
-//  * the hand-over between two phases is an all-gather through memory in which every value travels with a tag
-//    (8-byte stores of {value, tag}, written through to the memory side; readers poll the values themselves with
-//    device-coherent loads until every tag is this launch's).  There is no separate flag, hence no store that has to
-//    be acknowledged before a flag may follow it.  In isolation such a hand-over costs 1-2 us (1.0 us for 512 values,
-//    2.1 us for 4096, all 256 workgroups reading all of them; a flag-based grid barrier: ~4 us).  Inside these kernels
-//    it costs 3-3.5 us: a device-coherent round trip is ~1.1 us there, the slowest producer's store takes about as
-//    long to become visible, and a reader that just missed it needs a second round trip.
+//  * the hand-over between two phases is an all-gather through memory, in one of two forms.  Few readers (the QKV rows,
+//    read by the attention workgroups): every value travels with a tag (8-byte stores of {value, tag}, written through
+//    to the memory side) and the readers poll the values themselves with device-coherent loads until every tag is this
+//    launch's; no separate flag, hence no store that has to be acknowledged before a flag may follow it.  Everybody reads
+//    everything (the attention partials, the SwiGLU vector): the data is plain and written through; once its stores are
+//    acknowledged a producer workgroup publishes a tagged indicator entry (in copies, so that 256 watchers do not poll the
+//    same lines), one wave per workgroup watches the indicators, and when all are there every thread reads the data with
+//    ordinary loads, which the XCD's L2 serves after the first.  Read as tagged values with device-coherent loads these
+//    hand-overs were bound by the bandwidth of such loads (256 workgroups x 32 KB of attention partials: 2.4 us), not by
+//    latency.
 //
 // Measured (8B-shaped shard, batch 1, context 2048).  With the first kernel after each window launched into the window
-// they save 3.5 us per layer (12.7 us remain of the attention block after its window, 8.4 us of the MLP block, against
-// 3.2 + 6.7 + 5.7 and 4.4 + 5.1 us for one kernel per operator, of which only the first can be launched ahead); launched
-// the ordinary way they are about as fast as one kernel per operator (17.9 vs 17.6 us, 15.2 vs 14.3 us): a hand-over costs
-// as much as the kernel boundary it replaces, and what the later phases gain from having their weights requested early,
-// the first phase loses to sharing the memory system with them.  On shapes whose blocks need several passes, and on short
-// rows (hidden 1024-2048), they lose 3-9 us per layer; the executor uses them by default only where rows have at least
+// they save 5 us per layer (11.6 us remain of the attention block after its window, 6.8 us of the MLP block, against
+// 3.0 + 6.8 + 5.8 and 3.9 + 4.7 us for one kernel per operator, of which only the first can be launched ahead); launched
+// the ordinary way they are somewhat faster than one kernel per operator (16.2 vs 17.6 us, 13.0 vs 13.8 us): a hand-over
+// costs about what the kernel boundary it replaces does, and what the later phases gain from having their weights requested
+// early, the first phase loses to sharing the memory system with them.  On shapes whose blocks need several passes, and on
+// short rows (hidden 1024-2048), they lose 3-9 us per layer; the executor uses them by default only where rows have at least
 // 4096 elements and every block's weights fit one pass.
 //
 // Tags are unique per launch (a process-wide counter), so a buffer never has to be cleared and stale contents of any
