@@ -242,8 +242,9 @@ __global__ __launch_bounds__(256) void k_attn(AttnArgs a)
                     vdst[(size_t)(tid + 64) * 16] = (uint16_t)f32_to_bf16(vrow[tid + 64]);
                 }
             }
-            __threadfence();
         }
+        // the new rows are read back within this workgroup only, through the CU's cache: the barrier's workgroup-scope
+        // ordering suffices (later kernels see them after this one has ended)
         __syncthreads();   // uniform: the condition depends on the workgroup only
         if (early && T - 1 >= t_first && T - 1 < t_first + kAttnTileTokens) load_tile(t_first);   // now with the new entry
     }
@@ -552,8 +553,9 @@ __global__ __launch_bounds__(256) void k_attn_q8(AttnArgs a)
                     reinterpret_cast<float *>(vdst + 2048)[r] = vsc1;
                 }
             }
-            __threadfence();
         }
+        // the new rows are read back within this workgroup only, through the CU's cache: the barrier's workgroup-scope
+        // ordering suffices (later kernels see them after this one has ended)
         __syncthreads();   // uniform: the condition depends on the workgroup only
         if (early && T - 1 >= t_first && T - 1 < t_first + TT) load_tile(t_first);   // now with the new entry
     }

@@ -927,8 +927,10 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
                     vdst[(size_t)lane * 16] = (uint16_t)f32_to_bf16(vsrc[lane]);
                     vdst[(size_t)(lane + 64) * 16] = (uint16_t)f32_to_bf16(vsrc[lane + 64]);
                 }
-                __threadfence();
             }
+            // the new rows are read back by this workgroup only (its own tile), through the CU's cache: the barrier's
+            // workgroup-scope ordering is all that needs (a device-scope fence here cost the one workgroup that appends,
+            // and so the whole hand-over, a write-back of its XCD's L2)
             __syncthreads();   // uniform: the condition depends on the workgroup only
             if (early && T - 1 >= t0 && T - 1 < t0 + kAttnTileTokens) load_tile();   // now with the new entry
         }
