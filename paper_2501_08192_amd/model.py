@@ -125,14 +125,21 @@ def mm_hold(batch, hidden, ffn, weight_format="bf16", cus=256, weight_layout="ro
     return min(1.0, held / spb) if ok else 0.0
 
 
-def op_bytes(hidden, n_q, n_kv, ffn, batch, context, head_dim=128, weight_format="bf16", kv_format="bf16"):
+def op_bytes(hidden, n_q, n_kv, ffn, batch, context, head_dim=128, weight_format="bf16", kv_format="bf16",
+             weight_layout="row"):
     """Algorithmic bytes of the operators of one layer: bf16, or the int8 formats (1 byte per weight; per cached
-    token and kv head 128 code bytes + a 4-byte scale, for K and for V)."""
+    token and kv head 128 code bytes + a 4-byte scale, for K and for V).  Under "p_qkv", "p_o", "p_gate_up", "p_down": the
+    split-K partial results a matrix-core projection writes and its reducing kernel reads back, 8 * splits * batch * rows
+    bytes (zero on the vector path) -- never prefetched, but a third of the traffic of a small projection at batch 64."""
     wb = 1 if weight_format == "int8" else 2
     kv_token = 2 * (head_dim + 4) if kv_format == "int8" else 2 * 2 * head_dim
-    qkv = (n_q + 2 * n_kv) * head_dim * hidden * wb
-    return {"qkv": qkv, "attn": batch * context * n_kv * kv_token, "o": hidden * n_q * head_dim * wb,
-            "gate": ffn * hidden * wb, "up": ffn * hidden * wb, "down": hidden * ffn * wb}
+    qkv_rows = (n_q + 2 * n_kv) * head_dim
+    out = {"qkv": qkv_rows * hidden * wb, "attn": batch * context * n_kv * kv_token, "o": hidden * n_q * head_dim * wb,
+           "gate": ffn * hidden * wb, "up": ffn * hidden * wb, "down": hidden * ffn * wb}
+    mm = path_of(batch, hidden, weight_layout) != "vec"
+    for name, rows, k in (("qkv", qkv_rows, hidden), ("o", hidden, n_q * head_dim), ("gate_up", 2 * ffn, hidden), ("down", hidden, ffn)):
+        out["p_" + name] = 8.0 * sk_splits(batch, rows, k, float(wb), weight_layout == "tiled") * batch * rows if mm else 0.0
+    return out
 
 
 def plan_windows(b, budget):
@@ -159,14 +166,15 @@ def prelaunched(b, windows, budget):
             "qkv": windows[1] > 0 and planned.get("qkv", 0.0) >= b["qkv"]}
 
 
-def kernel_time(m: Machine, name, nbytes, hit, path="vec"):
-    """One kernel of class `name` ("attn", or a projection on `path`) moving nbytes, `hit` of them prefetched."""
+def kernel_time(m: Machine, name, nbytes, hit, path="vec", extra=0.0):
+    """One kernel of class `name` ("attn", or a projection on `path`) moving nbytes, `hit` of them prefetched, and
+    `extra` bytes of split-K partial results (matrix-core paths)."""
     if name == "attn":
         return m.t_fixed_attn + hit / m.bw_attn_cache + (nbytes - hit) / m.bw_attn
     if path == "mm":
-        return m.t_fixed_mm + hit / m.bw_mm_cache + (nbytes - hit) / m.bw_mm
+        return m.t_fixed_mm + hit / m.bw_mm_cache + (nbytes - hit + extra) / m.bw_mm
     if path == "mmt":
-        return m.t_fixed_mmt + hit / m.bw_mmt_cache + (nbytes - hit) / m.bw_mmt
+        return m.t_fixed_mmt + hit / m.bw_mmt_cache + (nbytes - hit + extra) / m.bw_mmt
     return m.t_fixed + hit / m.bw_cache + (nbytes - hit) / m.bw_hbm
 
 
@@ -199,11 +207,11 @@ def layer_time(b, windows, m: Machine, budget=0.0, prelaunch=False, path="vec", 
         if pre_mm and name == "gate_up":
             rest, hit_rest = (1.0 - hold_mm) * nbytes, (1.0 - hold_mm) * h
             bw, bwc = (m.bw_mmt, m.bw_mmt_cache) if path == "mmt" else (m.bw_mm, m.bw_mm_cache)
-            t += m.t_post_mm + hit_rest / bwc + (rest - hit_rest) / bw
+            t += m.t_post_mm + hit_rest / bwc + (rest - hit_rest + b.get("p_gate_up", 0.0)) / bw
         elif pre.get(name):
             t += m.t_post + min(nbytes, m.reg_bytes) / m.bw_reg + max(0.0, nbytes - m.reg_bytes) / m.bw_hbm
         else:
-            t += kernel_time(m, name, nbytes, h, path)
+            t += kernel_time(m, name, nbytes, h, path, b.get("p_" + name, 0.0) if mm else 0.0)
     for w, ops in zip(windows, groups):
         if w <= 0:
             continue

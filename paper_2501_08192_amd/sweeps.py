@@ -62,7 +62,7 @@ def speed_map(shape, batches, contexts, layers=4, window=20.0, out=print, kv_lay
                                weight_layout=weight_layout)
             if w.kv_bytes_per_layer * layers > 60e9:
                 continue
-            b = model.op_bytes(hidden, nq, nkv, ffn, B, T)
+            b = model.op_bytes(hidden, nq, nkv, ffn, B, T, weight_layout=weight_layout)
             path = model.path_of(B, hidden, weight_layout)
             hold = model.mm_hold(B, hidden, ffn, weight_layout=weight_layout) if path != "vec" else 0.0
             budget = model.best_budget(b, (window, window), mach, path=path)
@@ -167,8 +167,9 @@ def calibrate(path, window=50.0, layers=4, out=print):
     big = 192 * MB
     for name, (H, nq, nkv, F, B, T, layout) in CAL_SHAPES.items():
         w = synth.Workload(name, 80, H, nq, nkv, 128, F, B, T, False, (window, window), weight_layout=layout)
-        b = model.op_bytes(H, nq, nkv, F, B, T)
+        b = model.op_bytes(H, nq, nkv, F, B, T, weight_layout=layout)
         nb = {"qkv": b["qkv"], "attn": b["attn"], "o": b["o"], "gate_up": b["gate"] + b["up"], "down": b["down"]}
+        part = {op: b["p_" + op] for op in ("qkv", "o", "gate_up", "down")}      # split-K partials: traffic of the projection too
         cls = model.path_of(B, H, layout)
         hold = model.mm_hold(B, H, F, weight_layout=layout) if cls != "vec" else 0.0
         with Session(w, layers=list(range(layers))) as s:
@@ -188,14 +189,14 @@ def calibrate(path, window=50.0, layers=4, out=print):
                 pre_ops = op_times(s)
         raw[name] = {"bytes": nb, "us_off": off_ops, "us_cache_only": hit_ops, "us_prelaunch": pre_ops, "layer_off": off, "layer_cache_only": hit}
         for op in ("qkv", "o", "gate_up", "down"):
-            pts[cls].append((nb[op], off_ops[op]))
-            pts[cls + "_hit"].append((nb[op], hit_ops[op]))
+            pts[cls].append((nb[op] + part[op], off_ops[op]))
+            pts[cls + "_hit"].append((nb[op] + part[op], hit_ops[op]))
         pts["attn"].append((nb["attn"], off_ops["attn"]))
         pts["attn_hit"].append((nb["attn"], hit_ops["attn"]))
         if pre_ops and cls == "vec":
             pts["pre"] += [(nb["qkv"], pre_ops["qkv"]), (nb["gate_up"], pre_ops["gate_up"])]
         elif pre_ops:       # (class, bytes it does not hold, us after the window) of the gate/up GEMM launched into its window
-            pts["pre_mm"].append((cls, (1.0 - hold) * nb["gate_up"], pre_ops["gate_up"]))
+            pts["pre_mm"].append((cls, (1.0 - hold) * nb["gate_up"] + part["gate_up"], pre_ops["gate_up"]))
         resid[name] = off - sum(off_ops.values()) - 2 * window       # what the five operator kernels and the windows leave
         out("%s: layer off %.1f cache-only %.1f; ops off %s" % (name, off, hit, {k: round(v, 2) for k, v in off_ops.items()}))
         torch.cuda.empty_cache()

@@ -7,7 +7,7 @@ from paper_2501_08192_amd import model, synth
 
 
 def _bytes(w):
-    return model.op_bytes(w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch, w.context)
+    return model.op_bytes(w.hidden, w.n_q_heads, w.n_kv_heads, w.ffn, w.batch, w.context, weight_layout=w.weight_layout)
 
 
 @pytest.mark.parametrize("name", ["c2", "c3", "c4", "c5"])
@@ -58,7 +58,7 @@ import json
 import os
 
 GOLDEN = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "measured_mi355x.json")
-TOL = 0.15      # relative error allowed per row and mode (worst: 14.6 %, batch 64 at a short context)
+TOL = 0.15      # relative error allowed per row and mode (worst: 11.6 %, c1 cache-only; batch 64 at 4k tokens: 9.4 %)
 
 
 def _golden():
@@ -78,7 +78,7 @@ def test_calibrated_model_predicts_every_measured_row():
     assert m != model.Machine()                       # the calibration file is in place
     worst = 0.0
     for r in _golden()["rows"]:
-        b = model.op_bytes(r["hidden"], r["n_q"], r["n_kv"], r["ffn"], r["batch"], r["context"])
+        b = model.op_bytes(r["hidden"], r["n_q"], r["n_kv"], r["ffn"], r["batch"], r["context"], weight_layout=r["weight_layout"])
         path, w = model.path_of(r["batch"], r["hidden"], r["weight_layout"]), tuple(r["windows"])
         hold = model.mm_hold(r["batch"], r["hidden"], r["ffn"], weight_layout=r["weight_layout"]) if path != "vec" else 0.0
         # the model's copy of the library's rule for launching the gate/up GEMM into its window agrees with what ran
@@ -119,7 +119,7 @@ def test_calibrated_model_finds_the_budget_knee_of_the_kv_dominated_workload():
     budget whose measured speedup is within 1.5 % of the best measured one, and to agree on which budgets lose."""
     m = model.Machine.load()
     g = _golden()
-    b = model.op_bytes(8192, 8, 1, 3584, 32, 32768)
+    b = model.op_bytes(8192, 8, 1, 3584, 32, 32768, weight_layout="tiled")
     for win in (20.0, 50.0):
         pts = [s for s in g["c5_budget_sweep"] if s["window"] == win]
         meas = {s["budget_mb"]: s["us_off"] / s["us_on"] for s in pts}
