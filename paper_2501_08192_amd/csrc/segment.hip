@@ -570,7 +570,7 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
     __shared__ float red[8][RED];
     __shared__ float ssq[8];
     __shared__ float xs[4096];
-    __shared__ f32x4 accs[4][8][64];
+    __shared__ f32x4 accs[8][8][64];
     __shared__ float ms[8][16], ls[8][16];
     __shared__ float2 rope_s[64];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, i = lane & 15, q4 = lane >> 4;
@@ -1007,17 +1007,9 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
         if (q4 == 0) ls[wave][i] = l_part * scl;
 #pragma unroll
         for (int dg = 0; dg < 8; ++dg) acc[dg] *= scl;
-        if (wave >= 4)
+        // every wave leaves its scaled accumulators in LDS; one barrier, then wave w sums channel group w over the eight
 #pragma unroll
-            for (int dg = 0; dg < 8; ++dg) accs[wave - 4][dg][lane] = acc[dg];
-        __syncthreads();
-        if (wave < 4)
-#pragma unroll
-            for (int dg = 0; dg < 8; ++dg) acc[dg] += accs[wave][dg][lane];
-        __syncthreads();
-        if (wave < 4)
-#pragma unroll
-            for (int dg = 0; dg < 8; ++dg) accs[wave][dg][lane] = acc[dg];
+        for (int dg = 0; dg < 8; ++dg) accs[wave][dg][lane] = acc[dg];
         __syncthreads();
         if (i < G) {
             const size_t slot = (size_t)kvh * nc + c;
@@ -1028,7 +1020,8 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
                 st_wt8(a.pml + slot * 16 + i, make_uint2(__float_as_uint(M), __float_as_uint(L)));
             }
             // wave w finishes and stores channel group w: ((0+4) + (1+5)) + ((2+6) + (3+7))
-            const f32x4 v = (accs[0][wave][lane] + accs[1][wave][lane]) + (accs[2][wave][lane] + accs[3][wave][lane]);
+            const f32x4 v = ((accs[0][wave][lane] + accs[4][wave][lane]) + (accs[1][wave][lane] + accs[5][wave][lane])) +
+                            ((accs[2][wave][lane] + accs[6][wave][lane]) + (accs[3][wave][lane] + accs[7][wave][lane]));
             st_wt16(a.po + (slot * G + i) * 128 + wave * 16 + 4 * q4, make_float4(v[0], v[1], v[2], v[3]));
         }
         if (lost && lane == 0) atomicOr(a.err, 2u);
