@@ -882,32 +882,40 @@ __global__ __launch_bounds__(512) void k_seg_attn(SegAttnArgs a)
                     if (!all) __builtin_amdgcn_s_sleep(2);
                 }
             }
-            float qlo[2][8], qhi[2][8];
-            if (i < G)
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks)
+            if (!all) lost = true;
+            // The rotated query as hi + lo fragments: four pieces -- (k half ks, the rotation's first or second output) -- of
+            // which waves 0..3 form one each and leave it in LDS for all eight (every wave forming all four cost 0.85 us,
+            // three quarters of it redundant).  accs is free until the merge.
+            uint4 *qfs = reinterpret_cast<uint4 *>(&accs[0][0][0]);      // [8][64]: qf[0..3], qfl[0..3]
+            if (wave < 4) {
+                const int ks = wave & 1, second = wave >> 1;
+                uint4 fh = zero16(), fl = zero16();
+                if (i < G) {
+                    float qlo[8], qhi[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        qlo[ks][e] = qs[i * 128 + ks * 32 + q4 * 8 + e];
-                        qhi[ks][e] = qs[i * 128 + ks * 32 + q4 * 8 + e + 64];
+                        qlo[e] = qs[i * 128 + ks * 32 + q4 * 8 + e];
+                        qhi[e] = qs[i * 128 + ks * 32 + q4 * 8 + e + 64];
                     }
-            if (!all) lost = true;
-            if (i < G) {
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
                     const int f0 = ks * 32 + q4 * 8;
-                    uint32_t lh[4], ll[4], hh[4], hl[4];
+                    uint32_t h[4], l[4];
 #pragma unroll
                     for (int e = 0; e < 8; e += 2) {
                         const float2 c0 = rope_s[f0 + e], c1 = rope_s[f0 + e + 1];
-                        pack_split(qlo[ks][e] * c0.x - qhi[ks][e] * c0.y, qlo[ks][e + 1] * c1.x - qhi[ks][e + 1] * c1.y, lh[e >> 1], ll[e >> 1]);
-                        pack_split(qhi[ks][e] * c0.x + qlo[ks][e] * c0.y, qhi[ks][e + 1] * c1.x + qlo[ks][e + 1] * c1.y, hh[e >> 1], hl[e >> 1]);
+                        if (!second) pack_split(qlo[e] * c0.x - qhi[e] * c0.y, qlo[e + 1] * c1.x - qhi[e + 1] * c1.y, h[e >> 1], l[e >> 1]);
+                        else pack_split(qhi[e] * c0.x + qlo[e] * c0.y, qhi[e + 1] * c1.x + qlo[e + 1] * c1.y, h[e >> 1], l[e >> 1]);
                     }
-                    qf[ks] = __builtin_bit_cast(bf16x8, make_uint4(lh[0], lh[1], lh[2], lh[3]));
-                    qfl[ks] = __builtin_bit_cast(bf16x8, make_uint4(ll[0], ll[1], ll[2], ll[3]));
-                    qf[ks + 2] = __builtin_bit_cast(bf16x8, make_uint4(hh[0], hh[1], hh[2], hh[3]));
-                    qfl[ks + 2] = __builtin_bit_cast(bf16x8, make_uint4(hl[0], hl[1], hl[2], hl[3]));
+                    fh = make_uint4(h[0], h[1], h[2], h[3]);
+                    fl = make_uint4(l[0], l[1], l[2], l[3]);
                 }
+                qfs[(ks + 2 * second) * 64 + lane] = fh;
+                qfs[(4 + ks + 2 * second) * 64 + lane] = fl;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int f = 0; f < 4; ++f) {
+                qf[f] = __builtin_bit_cast(bf16x8, qfs[f * 64 + lane]);
+                qfl[f] = __builtin_bit_cast(bf16x8, qfs[(4 + f) * 64 + lane]);
             }
         }
         // append the new token's K and V (the workgroup whose chunk holds token T-1)
